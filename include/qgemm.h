@@ -1,0 +1,152 @@
+/*
+ * qgemm -- quantized matrix multiply  C_u8 = requant(A_u8 * B_s8)  for AMD MI355X
+ * (gfx950), with the pre- and post-processing of the FBGEMM paper
+ * (arXiv 2101.05615) fused in.  C ABI, plain pointers and sizes.
+ *
+ * Conventions taken from the paper's statement of the problem (Sec. 2.1,
+ * Eq. (1)-(2), and the interface of Appendix A):
+ *   - C = A B with A: M x K (uint8 activations), B: K x N (int8 weights),
+ *     C: M x N (uint8), all row-major with leading dimensions in elements.
+ *   - every matrix is affinely quantized, X = alpha_X (X^q - theta_X)   (Eq. 1);
+ *     theta_A and theta_C are per tensor, theta_B and the combined multiplier
+ *     alpha_A alpha_B / alpha_C are per tensor or per output channel (column of B).
+ *   - B is the constant matrix: it is packed ONCE, ahead of time, never at run
+ *     time (Sec. 2.2; Appendix A "packB.pack is never called").
+ *   - the library creates no streams, allocates no device memory and never
+ *     synchronises: device buffers, including scratch, are caller-allocated
+ *     (Appendix A: preallocated C_buffer, no threads created internally).
+ *
+ * "dev" pointers are device (HBM) addresses valid on the current HIP device;
+ * "host" pointers are ordinary host memory.  `stream` is a hipStream_t passed
+ * as void* (NULL = the default stream).  Every call that launches work is
+ * asynchronous: a 0 return means "enqueued on `stream`".
+ *
+ * Errors: every function returns 0 on success or one of the negative QG_E*
+ * codes; nothing is printed, nothing aborts.  On error no output is written.
+ */
+#ifndef QGEMM_H
+#define QGEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QG_OK 0
+#define QG_ENULL (-1)      /* a required pointer is NULL                               */
+#define QG_EINVAL (-2)     /* a size, leading dimension, zero point or count is invalid */
+#define QG_EALIGN (-3)     /* a device pointer violates a documented alignment          */
+#define QG_EWORKSPACE (-4) /* workspace needed but NULL                                 */
+#define QG_ELAUNCH (-5)    /* the HIP runtime refused a launch or copy                  */
+#define QG_ENOMEM (-6)     /* host allocation of the descriptor failed                  */
+#define QG_EUNSUPPORTED (-7) /* valid request outside what this build implements        */
+
+/* Largest K accepted: with |A| <= 255 and |B - theta_B| <= 255 the int32
+ * accumulator and every correction term stay below 2^31 (Eq. (2) never
+ * discusses overflow; this bound makes it impossible). */
+#define QG_MAX_K 32768
+
+/* Opaque HOST-side descriptor of a packed weight matrix.  It owns no device
+ * memory: it records K, N, the padded extents, the layout version and the
+ * caller's two device buffers, which must outlive it and all enqueued work. */
+typedef struct qg_packed_b qg_packed_b;
+
+/* Run-time parameters of the output pipeline (Sec. 2.1 requantization remark;
+ * Sec. 2.2 "bias addition, nonlinearities, requantization"):
+ *   x      = acc - theta_A*colsum_B[j] - theta_B[j]*rowsum_A[i] + K*theta_A*theta_B[j] + bias[j]
+ *   C[i,j] = clamp(rne((float)x * scale[j]), lo - theta_C, 255 - theta_C) + theta_C
+ * with lo = theta_C when relu != 0, else 0; rne = round to nearest even; the
+ * product is ONE IEEE fp32 multiply.  scales must be finite and > 0. */
+typedef struct {
+  int32_t a_zp;          /* theta_A, 0..255                                   */
+  const int32_t* bias;   /* dev, N entries in accumulator units, or NULL      */
+  const float* scales;   /* dev, n_scales entries                             */
+  int32_t n_scales;      /* 1 (per tensor) or N (per output channel)          */
+  int32_t c_zp;          /* theta_C, 0..255                                   */
+  int32_t relu;          /* 0 or 1                                            */
+} qg_requant_params;
+
+/* ---- offline: weight packing with column-offset precompute --------------- */
+
+/* Bytes the caller must allocate for qg_pack_b: `packed_bytes` for the
+ * reordered, zero-padded int8 weights and `col_offsets_bytes` for the int32
+ * side buffer.  Both buffers must be 256-byte aligned. */
+int qg_pack_b_sizes(int K, int N, size_t* packed_bytes, size_t* col_offsets_bytes);
+
+/* Pack B (Sec. 2.2: prepack the constant matrix once) and compute the column
+ * offsets with the constant term of Eq. (2) folded in (Sec. 2.1, second remark):
+ *     col_offsets[j] = sum_k B[k][j] - K * theta_B[j],   j = 0..N-1
+ * which occupy the first N int32 of col_offsets_dev; the rest of that buffer
+ * is private to the library (a per-channel copy of theta_B).
+ *   B_dev      dev, int8, row-major K x N, leading dimension ldb >= N
+ *   b_zp_host  HOST, n_b_zp entries (1 = per tensor, N = per channel), each -128..127
+ *   packed_dev, col_offsets_dev  dev, caller-allocated, sizes from qg_pack_b_sizes
+ *   out        receives the descriptor; release with qg_packed_b_destroy
+ * 1 <= K <= QG_MAX_K, N >= 1. */
+int qg_pack_b(const int8_t* B_dev, int K, int N, int ldb, const int32_t* b_zp_host, int n_b_zp,
+              void* packed_dev, int32_t* col_offsets_dev, void* stream, qg_packed_b** out);
+
+/* Frees the host descriptor only.  NULL is allowed. */
+void qg_packed_b_destroy(qg_packed_b* p);
+
+/* K, N of a descriptor (0 on NULL). */
+int qg_packed_b_k(const qg_packed_b* p);
+int qg_packed_b_n(const qg_packed_b* p);
+
+/* ---- run time ------------------------------------------------------------ */
+
+/* Scratch bytes qg_gemm_* needs for this M (the role of the paper's C_buffer,
+ * Appendix A).  May be 0, in which case workspace_dev may be NULL. */
+size_t qg_gemm_workspace_bytes(int M, const qg_packed_b* Bp);
+
+/* The fused hot path (Sec. 2.1 Eq. (2) + requantization; Sec. 2.2 fusion of
+ * row-offset computation into the A staging pass and of the output pipeline
+ * into the GEMM): one launch reads A once, computes row offsets from the
+ * staged tile, accumulates in int32 and writes uint8 C from the accumulators.
+ *   A_dev  dev, uint8, row-major M x K (K from Bp), lda >= K
+ *   C_dev  dev, uint8, row-major M x N, ldc >= N; must not alias A
+ * No alignment is required; 16-byte aligned A_dev/C_dev with lda, ldc multiples
+ * of 16 take the vectorised load/store path.  Identical inputs give identical
+ * bytes on every run. */
+int qg_gemm_u8s8_requant(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp,
+                         const qg_requant_params* p, uint8_t* C_dev, int ldc, void* workspace_dev,
+                         void* stream);
+
+/* Test hook for the first term of Eq. (2): C32[i][j] = sum_k A_u8[i][k]*B_s8[k][j]
+ * (the accumulator in the uint8 domain, exactly), through the same main loop as
+ * the fused call.  rowsum_dev (optional, M int32) receives sum_k A_u8[i][k]. */
+int qg_gemm_u8s8_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp, int32_t* C32_dev,
+                       int ldc, int32_t* rowsum_dev, void* workspace_dev, void* stream);
+
+/* ---- group-wise convolution with fused im2col ----------------------------- */
+
+/* The paper names convolution without describing it; the definition used is the
+ * real-domain one implied by Eq. (1): NHWC uint8 input with zero point theta_A,
+ * zero padding in the real domain (= theta_A in the quantized domain), G groups,
+ * each an independent GEMM with rows = output pixels, K = R*S*(C/G) ordered
+ * (kh, kw, c_in), N = Cout/G.  The im2col matrix is never materialised.
+ *   W_dev      dev, int8, [G][R][S][C/G][Cout/G]
+ *   b_zp_host  HOST, 1 or Cout entries
+ * This build implements C/G == 4 and Cout/G == 4 with R*S in {1, 9}; anything
+ * else returns QG_EUNSUPPORTED. */
+int qg_pack_conv_w_sizes(int G, int R, int S, int Cg, int Og, size_t* packed_bytes,
+                         size_t* col_offsets_bytes);
+int qg_pack_conv_w(const int8_t* W_dev, int G, int R, int S, int Cg, int Og, const int32_t* b_zp_host,
+                   int n_b_zp, void* packed_dev, int32_t* col_offsets_dev, void* stream,
+                   qg_packed_b** out);
+
+/* in_nhwc: dev uint8 [Nb][H][W][C]; out_nhwc: dev uint8 [Nb][Ho][Wo][Cout],
+ * Ho = (H + 2*pad - R)/stride + 1 (same for Wo); both 4-byte aligned.
+ * p->n_scales is 1 or Cout, p->bias has Cout entries or is NULL. */
+int qg_conv_groupwise_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int C, int pad,
+                                   int stride, const qg_packed_b* Wp, const qg_requant_params* p,
+                                   uint8_t* out_nhwc, void* stream);
+
+const char* qg_status_string(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QGEMM_H */

@@ -1,0 +1,285 @@
+// Host side of the C ABI declared in qgemm.h: argument checks, descriptor
+// bookkeeping and kernel selection by shape.  No device allocation, no stream
+// creation, no synchronisation happens here (paper Appendix A: the library works
+// on caller-provided buffers and leaves parallelism to the caller).
+#include <new>
+#include <vector>
+
+#include "qg_internal.h"
+
+namespace {
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int check_requant(const qg_requant_params* p, int N) {
+  if (!p) return QG_ENULL;
+  if (!p->scales) return QG_ENULL;
+  if (p->a_zp < 0 || p->a_zp > 255 || p->c_zp < 0 || p->c_zp > 255) return QG_EINVAL;
+  if (p->n_scales != 1 && p->n_scales != N) return QG_EINVAL;
+  if (p->relu != 0 && p->relu != 1) return QG_EINVAL;
+  return QG_OK;
+}
+
+// Builds the padded per-column theta_B array on the host and enqueues its upload
+// into the second half of the caller's col_offsets buffer.
+int upload_bzp(const int32_t* b_zp_host, int n_b_zp, int N, int N_pad, int32_t* dst_dev, hipStream_t s,
+               int* has_bzp) {
+  std::vector<int32_t> tmp;
+  try {
+    tmp.assign((size_t)N_pad, 0);
+  } catch (const std::bad_alloc&) {
+    return QG_ENOMEM;
+  }
+  int any = 0;
+  for (int j = 0; j < N; ++j) {
+    const int32_t z = b_zp_host[n_b_zp == 1 ? 0 : j];
+    if (z < -128 || z > 127) return QG_EINVAL;
+    tmp[j] = z;
+    any |= (z != 0);
+  }
+  *has_bzp = any;
+  // pageable source: the runtime stages it before returning, so tmp may die here
+  if (hipMemcpyAsync(dst_dev, tmp.data(), sizeof(int32_t) * (size_t)N_pad, hipMemcpyHostToDevice, s) !=
+      hipSuccess)
+    return QG_ELAUNCH;
+  if (hipStreamSynchronize(s) != hipSuccess) return QG_ELAUNCH;  // offline path; keeps tmp's lifetime trivially safe
+  return QG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* qg_status_string(int code) {
+  switch (code) {
+    case QG_OK: return "ok";
+    case QG_ENULL: return "required pointer is NULL";
+    case QG_EINVAL: return "invalid size, leading dimension, zero point or count";
+    case QG_EALIGN: return "device pointer alignment violated";
+    case QG_EWORKSPACE: return "workspace required but not provided";
+    case QG_ELAUNCH: return "HIP runtime refused the launch or copy";
+    case QG_ENOMEM: return "host allocation failed";
+    case QG_EUNSUPPORTED: return "configuration not implemented in this build";
+    default: return "unknown status";
+  }
+}
+
+int qg_pack_b_sizes(int K, int N, size_t* packed_bytes, size_t* col_offsets_bytes) {
+  if (!packed_bytes || !col_offsets_bytes) return QG_ENULL;
+  if (K <= 0 || N <= 0 || K > QG_MAX_K) return QG_EINVAL;
+  const size_t K_pad = (size_t)qg_round_up(K, QG_KPAD), N_pad = (size_t)qg_round_up(N, QG_NPAD);
+  *packed_bytes = K_pad * N_pad;
+  *col_offsets_bytes = 2 * N_pad * sizeof(int32_t);
+  return QG_OK;
+}
+
+int qg_pack_b(const int8_t* B_dev, int K, int N, int ldb, const int32_t* b_zp_host, int n_b_zp,
+              void* packed_dev, int32_t* col_offsets_dev, void* stream, qg_packed_b** out) {
+  if (!B_dev || !b_zp_host || !packed_dev || !col_offsets_dev || !out) return QG_ENULL;
+  if (K <= 0 || N <= 0 || K > QG_MAX_K || ldb < N) return QG_EINVAL;
+  if (n_b_zp != 1 && n_b_zp != N) return QG_EINVAL;
+  if (!aligned(packed_dev, 256) || !aligned(col_offsets_dev, 256)) return QG_EALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int K_pad = qg_round_up(K, QG_KPAD), N_pad = qg_round_up(N, QG_NPAD);
+
+  qg_packed_b* h = new (std::nothrow) qg_packed_b();
+  if (!h) return QG_ENOMEM;
+  h->kind = QG_KIND_GEMM;
+  h->version = QG_LAYOUT_VERSION;
+  h->K = K;
+  h->N = N;
+  h->K_pad = K_pad;
+  h->N_pad = N_pad;
+  h->n_b_zp = n_b_zp;
+  h->packed = static_cast<const int8_t*>(packed_dev);
+  h->col_off = col_offsets_dev;
+  h->bzp = col_offsets_dev + N_pad;
+  h->G = h->R = h->S = h->Cg = h->Og = 0;
+
+  int rc = upload_bzp(b_zp_host, n_b_zp, N, N_pad, col_offsets_dev + N_pad, s, &h->has_bzp);
+  if (rc != QG_OK) {
+    delete h;
+    return rc;
+  }
+  if (qg_launch_pack_b(B_dev, K, N, ldb, K_pad, N_pad, static_cast<int8_t*>(packed_dev), col_offsets_dev,
+                       col_offsets_dev + N_pad, s) != hipSuccess) {
+    delete h;
+    return QG_ELAUNCH;
+  }
+  *out = h;
+  return QG_OK;
+}
+
+void qg_packed_b_destroy(qg_packed_b* p) { delete p; }
+
+int qg_packed_b_k(const qg_packed_b* p) { return p ? p->K : 0; }
+int qg_packed_b_n(const qg_packed_b* p) { return p ? p->N : 0; }
+
+size_t qg_gemm_workspace_bytes(int M, const qg_packed_b* Bp) {
+  (void)M;
+  (void)Bp;
+  return 0;  // K is split only inside a workgroup; partial sums live in LDS
+}
+
+static int gemm_common(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp, qg_gemm_args* a) {
+  if (!A_dev || !Bp) return QG_ENULL;
+  if (Bp->kind != QG_KIND_GEMM || Bp->version != QG_LAYOUT_VERSION) return QG_EINVAL;
+  if (M <= 0 || lda < Bp->K) return QG_EINVAL;
+  a->A = A_dev;
+  a->Bp = Bp->packed;
+  a->col_off = Bp->col_off;
+  a->bzp = Bp->bzp;
+  a->M = M;
+  a->N = Bp->N;
+  a->K = Bp->K;
+  a->kb64 = Bp->K_pad / QG_FRAG_K;
+  a->lda = lda;
+  a->a_vec = aligned(A_dev, 16) && (lda % 16 == 0);
+  return QG_OK;
+}
+
+int qg_gemm_u8s8_requant(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp,
+                         const qg_requant_params* p, uint8_t* C_dev, int ldc, void* workspace_dev,
+                         void* stream) {
+  (void)workspace_dev;
+  qg_gemm_args a = {};
+  int rc = gemm_common(A_dev, M, lda, Bp, &a);
+  if (rc != QG_OK) return rc;
+  if (!C_dev) return QG_ENULL;
+  rc = check_requant(p, Bp->N);
+  if (rc != QG_OK) return rc;
+  if (ldc < Bp->N) return QG_EINVAL;
+  a.bias = p->bias;
+  a.scales = p->scales;
+  a.scale_stride = p->n_scales == 1 ? 0 : 1;
+  a.a_zp_m128 = p->a_zp - 128;
+  a.c_zp = p->c_zp;
+  const int lo = p->relu ? p->c_zp : 0;
+  a.clamp_lo = (float)(lo - p->c_zp);
+  a.clamp_hi = (float)(255 - p->c_zp);
+  a.C = C_dev;
+  a.ldc = ldc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e;
+  if (M <= QG_SKINNY_MAX_M) {
+    a.c_vec = aligned(C_dev, 4) && (ldc % 4 == 0);
+    e = qg_launch_gemm_skinny(a, QG_MODE_REQUANT, s);
+  } else {
+    a.c_vec = aligned(C_dev, 16) && (ldc % 16 == 0);
+    e = qg_launch_gemm_tile(a, QG_MODE_REQUANT, s);
+  }
+  return e == hipSuccess ? QG_OK : QG_ELAUNCH;
+}
+
+int qg_gemm_u8s8_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp, int32_t* C32_dev,
+                       int ldc, int32_t* rowsum_dev, void* workspace_dev, void* stream) {
+  (void)workspace_dev;
+  qg_gemm_args a = {};
+  int rc = gemm_common(A_dev, M, lda, Bp, &a);
+  if (rc != QG_OK) return rc;
+  if (!C32_dev) return QG_ENULL;
+  if (ldc < Bp->N) return QG_EINVAL;
+  a.C32 = C32_dev;
+  a.rowsum_out = rowsum_dev;
+  a.ldc = ldc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = (M <= QG_SKINNY_MAX_M) ? qg_launch_gemm_skinny(a, QG_MODE_ACC32, s)
+                                        : qg_launch_gemm_tile(a, QG_MODE_ACC32, s);
+  return e == hipSuccess ? QG_OK : QG_ELAUNCH;
+}
+
+int qg_pack_conv_w_sizes(int G, int R, int S, int Cg, int Og, size_t* packed_bytes,
+                         size_t* col_offsets_bytes) {
+  if (!packed_bytes || !col_offsets_bytes) return QG_ENULL;
+  if (G <= 0 || R <= 0 || S <= 0 || Cg <= 0 || Og <= 0) return QG_EINVAL;
+  if (Cg != 4 || Og != 4 || !((R == 1 && S == 1) || (R == 3 && S == 3)) || G > 256) return QG_EUNSUPPORTED;
+  *packed_bytes = (size_t)qg_round_up(G * R * S * Cg * Og, 256);
+  *col_offsets_bytes = (size_t)qg_round_up(2 * G * Og * (int)sizeof(int32_t), 256);
+  return QG_OK;
+}
+
+int qg_pack_conv_w(const int8_t* W_dev, int G, int R, int S, int Cg, int Og, const int32_t* b_zp_host,
+                   int n_b_zp, void* packed_dev, int32_t* col_offsets_dev, void* stream,
+                   qg_packed_b** out) {
+  if (!W_dev || !b_zp_host || !packed_dev || !col_offsets_dev || !out) return QG_ENULL;
+  size_t pb, cb;
+  int rc = qg_pack_conv_w_sizes(G, R, S, Cg, Og, &pb, &cb);
+  if (rc != QG_OK) return rc;
+  const int Cout = G * Og;
+  if (n_b_zp != 1 && n_b_zp != Cout) return QG_EINVAL;
+  if (!aligned(packed_dev, 256) || !aligned(col_offsets_dev, 256)) return QG_EALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  qg_packed_b* h = new (std::nothrow) qg_packed_b();
+  if (!h) return QG_ENOMEM;
+  h->kind = QG_KIND_CONV;
+  h->version = QG_LAYOUT_VERSION;
+  h->K = R * S * Cg;
+  h->N = Cout;
+  h->K_pad = h->K;
+  h->N_pad = Cout;
+  h->n_b_zp = n_b_zp;
+  h->packed = static_cast<const int8_t*>(packed_dev);
+  h->col_off = col_offsets_dev;
+  h->bzp = col_offsets_dev + Cout;
+  h->G = G;
+  h->R = R;
+  h->S = S;
+  h->Cg = Cg;
+  h->Og = Og;
+  rc = upload_bzp(b_zp_host, n_b_zp, Cout, Cout, col_offsets_dev + Cout, s, &h->has_bzp);
+  if (rc != QG_OK) {
+    delete h;
+    return rc;
+  }
+  if (qg_launch_pack_conv_w(W_dev, G, R * S, static_cast<int8_t*>(packed_dev), col_offsets_dev,
+                            col_offsets_dev + Cout, s) != hipSuccess) {
+    delete h;
+    return QG_ELAUNCH;
+  }
+  *out = h;
+  return QG_OK;
+}
+
+int qg_conv_groupwise_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int C, int pad,
+                                   int stride, const qg_packed_b* Wp, const qg_requant_params* p,
+                                   uint8_t* out_nhwc, void* stream) {
+  if (!in_nhwc || !Wp || !out_nhwc) return QG_ENULL;
+  if (Wp->kind != QG_KIND_CONV || Wp->version != QG_LAYOUT_VERSION) return QG_EINVAL;
+  if (Nb <= 0 || H <= 0 || W <= 0 || C <= 0 || pad < 0 || stride <= 0) return QG_EINVAL;
+  if (C != Wp->G * Wp->Cg) return QG_EINVAL;
+  int rc = check_requant(p, Wp->N);
+  if (rc != QG_OK) return rc;
+  const int Ho = (H + 2 * pad - Wp->R) / stride + 1;
+  const int Wo = (W + 2 * pad - Wp->S) / stride + 1;
+  if (H + 2 * pad < Wp->R || W + 2 * pad < Wp->S || Ho <= 0 || Wo <= 0) return QG_EINVAL;
+  if (!aligned(in_nhwc, 4) || !aligned(out_nhwc, 4)) return QG_EALIGN;
+  qg_conv_args a = {};
+  a.in = in_nhwc;
+  a.Wp = Wp->packed;
+  a.col_off = Wp->col_off;
+  a.bzp = Wp->bzp;
+  a.bias = p->bias;
+  a.scales = p->scales;
+  a.out = out_nhwc;
+  a.Nb = Nb;
+  a.H = H;
+  a.W = W;
+  a.C = C;
+  a.Ho = Ho;
+  a.Wo = Wo;
+  a.Cout = Wp->N;
+  a.G = Wp->G;
+  a.pad = pad;
+  a.stride = stride;
+  a.scale_stride = p->n_scales == 1 ? 0 : 1;
+  a.a_zp = p->a_zp;
+  a.c_zp = p->c_zp;
+  const int lo = p->relu ? p->c_zp : 0;
+  a.clamp_lo = (float)(lo - p->c_zp);
+  a.clamp_hi = (float)(255 - p->c_zp);
+  a.has_bzp = Wp->has_bzp;
+  hipError_t e = qg_launch_conv_group(a, Wp->R * Wp->S, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? QG_OK : QG_ELAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,93 @@
+// Offline weight packing (paper Sec. 2.2: the constant matrix is packed once and
+// reused) fused with the column-offset computation (Sec. 2.1: column offsets, with
+// the constant K*theta_A*theta_B folded into the offsets of the constant matrix).
+// Packing only moves data, so the column sums ride along for free.
+#include "qg_internal.h"
+
+namespace {
+
+__global__ void qg_fill_i32(int32_t* p, int n, int32_t v) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// One thread produces one 16-byte chunk of the packed buffer: 16 consecutive k of
+// one column.  Threads are ordered with the column fastest so that the 16 row
+// reads are coalesced across the wave.
+__global__ __launch_bounds__(256) void qg_pack_b_kernel(const int8_t* __restrict__ B, int K, int N,
+                                                        int ldb, int K_pad, int N_pad,
+                                                        int8_t* __restrict__ packed,
+                                                        int32_t* __restrict__ colsum) {
+  const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long total = (long long)N_pad * (K_pad / 16);
+  if (gid >= total) return;
+  const int n = (int)(gid % N_pad);
+  const int kc16 = (int)(gid / N_pad);
+  const int k0 = kc16 * 16;
+
+  union {
+    int4 v;
+    int8_t b[16];
+  } u;
+  int sum = 0;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    int8_t x = 0;
+    if (n < N && k0 + i < K) x = B[(size_t)(k0 + i) * ldb + n];
+    u.b[i] = x;
+    sum += x;
+  }
+  const int sb = n >> 5, c = n & 31;
+  const int slot = qg_col_to_slot(c);
+  const int nb16 = sb * 2 + (slot >> 4), nl = slot & 15;
+  const int kb = kc16 >> 2, g = kc16 & 3;
+  const size_t dst = ((size_t)nb16 * (K_pad / QG_FRAG_K) + kb) * QG_FRAG_BYTES + (g * 16 + nl) * 16;
+  *reinterpret_cast<int4*>(packed + dst) = u.v;
+  if (n < N && sum != 0) atomicAdd(&colsum[n], sum);
+}
+
+// col_offsets[j] = colsum[j] - K * theta_B[j]
+__global__ void qg_fold_offsets(int32_t* col_off, const int32_t* __restrict__ bzp, int n, int K) {
+  int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j < n) col_off[j] = col_off[j] - K * bzp[j];
+}
+
+// Conv weights [G][RS][4 ci][4 co] -> [G][RS][4 co][4 ci]: one dword per (tap, co)
+// holding the group's 4 input channels, the operand shape of v_dot4_i32_i8.
+// One thread per output channel; it also forms that channel's folded offset.
+__global__ void qg_pack_conv_w_kernel(const int8_t* __restrict__ W, int G, int RS,
+                                      int8_t* __restrict__ packed, int32_t* __restrict__ col_off,
+                                      const int32_t* __restrict__ bzp) {
+  const int oc = blockIdx.x * blockDim.x + threadIdx.x;
+  if (oc >= G * 4) return;
+  const int g = oc >> 2, co = oc & 3;
+  int sum = 0;
+  for (int tap = 0; tap < RS; ++tap)
+    for (int ci = 0; ci < 4; ++ci) {
+      const int8_t w = W[(((size_t)g * RS + tap) * 4 + ci) * 4 + co];
+      packed[(((size_t)g * RS + tap) * 4 + co) * 4 + ci] = w;
+      sum += w;
+    }
+  col_off[oc] = sum - RS * 4 * bzp[oc];
+}
+
+}  // namespace
+
+hipError_t qg_launch_pack_b(const int8_t* B, int K, int N, int ldb, int K_pad, int N_pad,
+                            int8_t* packed, int32_t* col_off, const int32_t* bzp_dev,
+                            hipStream_t s) {
+  hipLaunchKernelGGL(qg_fill_i32, dim3((N_pad + 255) / 256), dim3(256), 0, s, col_off, N_pad, 0);
+  const long long total = (long long)N_pad * (K_pad / 16);
+  hipLaunchKernelGGL(qg_pack_b_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, B, K,
+                     N, ldb, K_pad, N_pad, packed, col_off);
+  hipLaunchKernelGGL(qg_fold_offsets, dim3((N_pad + 255) / 256), dim3(256), 0, s, col_off, bzp_dev,
+                     N_pad, K);
+  return hipGetLastError();
+}
+
+hipError_t qg_launch_pack_conv_w(const int8_t* W, int G, int RS, int8_t* packed, int32_t* col_off,
+                                 const int32_t* bzp_dev, hipStream_t s) {
+  hipLaunchKernelGGL(qg_pack_conv_w_kernel, dim3((G * 4 + 63) / 64), dim3(64), 0, s, W, G, RS, packed,
+                     col_off, bzp_dev);
+  return hipGetLastError();
+}

@@ -1,0 +1,114 @@
+// Internal declarations shared by the HIP translation units of libqgemm.
+// Not part of the public interface.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "qgemm.h"
+
+// ---------------------------------------------------------------------------
+// Packed-B layout ("fragment-linear", version 1)
+//
+// B (K x N, int8) is zero-padded to K_pad x N_pad (multiples of 128 and 256) and
+// cut into fragments of 16 columns x 64 k = 1 KiB.  A fragment is stored in the
+// exact order in which one 64-lane wave feeds it to v_mfma_i32_16x16x64_i8:
+// lane (nl + 16 g), nl = 0..15, g = 0..3, owns the 16 consecutive bytes
+//     B[kb*64 + g*16 + 0..15][column(nl)]
+// at byte offset (g*16 + nl)*16, so a wave loads a fragment with ONE fully
+// coalesced 16-byte-per-lane load and no shuffling.  Two vertically adjacent
+// half-fragments (g pair) of two fragments of one 32-column super-block are
+// what v_mfma_i32_32x32x32_i8 wants, so the same bytes serve both MFMA shapes.
+//
+// Fragments are ordered [nb16][kb64]: all of K for 16 columns is contiguous.
+//
+// Columns are permuted inside each 32-column super-block so that the 32x32
+// MFMA leaves every lane holding 16 CONSECUTIVE output columns (one 16-byte
+// store).  Column c = 16h + 4q + t (h<2, q<4, t<4) sits in slot i = 8q + 4h + t;
+// slot i lives in fragment 2*sb + (i >> 4) at nl = i & 15.
+// ---------------------------------------------------------------------------
+#define QG_FRAG_COLS 16
+#define QG_FRAG_K 64
+#define QG_FRAG_BYTES 1024
+#define QG_KPAD 128
+#define QG_NPAD 256
+#define QG_LAYOUT_VERSION 1
+
+static inline __host__ __device__ int qg_round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+// column within a super-block -> slot (MFMA row index of the 32x32 shape)
+static inline __host__ __device__ int qg_col_to_slot(int c) {
+  return ((c >> 2) & 3) * 8 + (c >> 4) * 4 + (c & 3);
+}
+static inline __host__ __device__ int qg_slot_to_col(int i) {
+  return ((i >> 2) & 1) * 16 + (i >> 3) * 4 + (i & 3);
+}
+
+enum qg_kind { QG_KIND_GEMM = 1, QG_KIND_CONV = 2 };
+
+struct qg_packed_b {
+  int kind;
+  int version;
+  int K, N;          // logical extents (conv: K = R*S*Cg, N = Cout)
+  int K_pad, N_pad;  // padded extents of the packed buffer (gemm only)
+  int has_bzp;       // any theta_B != 0
+  int n_b_zp;
+  const int8_t* packed;   // device
+  const int32_t* col_off; // device: [0, N) col_offsets
+  const int32_t* bzp;     // device: per-column theta_B (inside the col_offsets buffer)
+  // conv only
+  int G, R, S, Cg, Og;
+};
+
+// Arguments of the GEMM kernels (by value).
+struct qg_gemm_args {
+  const uint8_t* A;
+  const int8_t* Bp;
+  const int32_t* col_off;
+  const int32_t* bzp;
+  const int32_t* bias;   // may be null
+  const float* scales;
+  uint8_t* C;            // requant output
+  int32_t* C32;          // acc32 output
+  int32_t* rowsum_out;   // acc32 mode, may be null
+  int M, N, K;
+  int kb64;              // K_pad / 64
+  int lda, ldc;
+  int scale_stride;      // 0 per tensor, 1 per channel
+  int a_zp_m128;         // theta_A - 128
+  int c_zp;
+  float clamp_lo, clamp_hi;  // lo - theta_C, 255 - theta_C
+  int a_vec;             // A base and lda are multiples of 16
+  int c_vec;             // C base and ldc are multiples of 16 (4 for the skinny kernel)
+};
+
+struct qg_conv_args {
+  const uint8_t* in;
+  const int8_t* Wp;
+  const int32_t* col_off;
+  const int32_t* bzp;
+  const int32_t* bias;
+  const float* scales;
+  uint8_t* out;
+  int Nb, H, W, C, Ho, Wo, Cout, G;
+  int pad, stride;
+  int scale_stride;
+  int a_zp;       // theta_A
+  int c_zp;
+  float clamp_lo, clamp_hi;
+  int has_bzp;
+};
+
+// launchers (each returns a hipError_t from hipGetLastError after the launch)
+hipError_t qg_launch_pack_b(const int8_t* B, int K, int N, int ldb, int K_pad, int N_pad,
+                            int8_t* packed, int32_t* col_off, const int32_t* bzp_dev, hipStream_t s);
+hipError_t qg_launch_pack_conv_w(const int8_t* W, int G, int RS, int8_t* packed, int32_t* col_off,
+                                 const int32_t* bzp_dev, hipStream_t s);
+hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, hipStream_t s);
+hipError_t qg_launch_gemm_skinny(const qg_gemm_args& a, int mode, hipStream_t s);
+hipError_t qg_launch_conv_group(const qg_conv_args& a, int RS, hipStream_t s);
+
+#define QG_MODE_REQUANT 0
+#define QG_MODE_ACC32 1
+#define QG_SKINNY_MAX_M 64

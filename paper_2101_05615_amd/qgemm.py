@@ -1,0 +1,197 @@
+"""Thin ctypes binding of libqgemm.so (the C ABI in include/qgemm.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.
+PyTorch supplies device memory (`tensor.data_ptr()`) and the stream.  There is
+no CPU fallback: if the library is not built, importing this module raises.
+"""
+import ctypes
+import os
+
+import torch  # noqa: F401  (imported first so that libqgemm binds to the HIP runtime torch loaded)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqgemm.so")
+
+OK, ENULL, EINVAL, EALIGN, EWORKSPACE, ELAUNCH, ENOMEM, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6, -7
+MAX_K = 32768
+
+EXPORTS = [
+    "qg_pack_b_sizes", "qg_pack_b", "qg_packed_b_destroy", "qg_packed_b_k", "qg_packed_b_n",
+    "qg_gemm_workspace_bytes", "qg_gemm_u8s8_requant", "qg_gemm_u8s8_acc32",
+    "qg_pack_conv_w_sizes", "qg_pack_conv_w", "qg_conv_groupwise_u8s8_requant", "qg_status_string",
+]
+
+
+class RequantParams(ctypes.Structure):
+    _fields_ = [("a_zp", ctypes.c_int32), ("bias", ctypes.c_void_p), ("scales", ctypes.c_void_p),
+                ("n_scales", ctypes.c_int32), ("c_zp", ctypes.c_int32), ("relu", ctypes.c_int32)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "or `python paper_2101_05615_amd/build.py` (there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.qg_pack_b_sizes.argtypes = [i, i, ctypes.POINTER(sz), ctypes.POINTER(sz)]
+    lib.qg_pack_b.argtypes = [vp, i, i, i, vp, i, vp, vp, vp, ctypes.POINTER(vp)]
+    lib.qg_packed_b_destroy.argtypes = [vp]
+    lib.qg_packed_b_destroy.restype = None
+    lib.qg_packed_b_k.argtypes = [vp]
+    lib.qg_packed_b_n.argtypes = [vp]
+    lib.qg_gemm_workspace_bytes.argtypes = [i, vp]
+    lib.qg_gemm_workspace_bytes.restype = sz
+    lib.qg_gemm_u8s8_requant.argtypes = [vp, i, i, vp, ctypes.POINTER(RequantParams), vp, i, vp, vp]
+    lib.qg_gemm_u8s8_acc32.argtypes = [vp, i, i, vp, vp, i, vp, vp, vp]
+    lib.qg_pack_conv_w_sizes.argtypes = [i, i, i, i, i, ctypes.POINTER(sz), ctypes.POINTER(sz)]
+    lib.qg_pack_conv_w.argtypes = [vp, i, i, i, i, i, vp, i, vp, vp, vp, ctypes.POINTER(vp)]
+    lib.qg_conv_groupwise_u8s8_requant.argtypes = [vp, i, i, i, i, i, i, vp, ctypes.POINTER(RequantParams),
+                                                   vp, vp]
+    lib.qg_status_string.argtypes = [i]
+    lib.qg_status_string.restype = ctypes.c_char_p
+    return lib
+
+
+lib = _load()
+
+
+class QGemmError(RuntimeError):
+    def __init__(self, code, where):
+        super().__init__(f"{where}: {lib.qg_status_string(code).decode()} ({code})")
+        self.code = code
+
+
+def _check(rc, where):
+    if rc != OK:
+        raise QGemmError(rc, where)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _host_i32(z):
+    import numpy as np
+    a = np.ascontiguousarray(np.atleast_1d(np.asarray(z)).astype(np.int32))
+    return a, a.ctypes.data_as(ctypes.c_void_p)
+
+
+class PackedB:
+    """Owner of the two device buffers and of the host descriptor of a packed weight matrix."""
+
+    def __init__(self, handle, packed, aux, n):
+        self.handle, self.packed, self.aux, self._n = handle, packed, aux, n
+
+    @property
+    def col_offsets(self):
+        return self.aux[: self._n]
+
+    @property
+    def K(self):
+        return lib.qg_packed_b_k(self.handle)
+
+    @property
+    def N(self):
+        return lib.qg_packed_b_n(self.handle)
+
+    def close(self):
+        if self.handle:
+            lib.qg_packed_b_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def pack_b_sizes(K, N):
+    pb, cb = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib.qg_pack_b_sizes(K, N, ctypes.byref(pb), ctypes.byref(cb)), "qg_pack_b_sizes")
+    return pb.value, cb.value
+
+
+def pack_b(B, b_zp):
+    """B: int8 cuda tensor [K, N] (row stride arbitrary, unit column stride); b_zp: 1 or N ints (host)."""
+    assert B.is_cuda and B.dtype == torch.int8 and B.dim() == 2 and B.stride(1) == 1
+    K, N = B.shape
+    pb, cb = pack_b_sizes(K, N)
+    packed = torch.empty(pb, dtype=torch.int8, device=B.device)
+    aux = torch.empty(cb // 4, dtype=torch.int32, device=B.device)
+    z, zp = _host_i32(b_zp)
+    h = ctypes.c_void_p()
+    _check(lib.qg_pack_b(B.data_ptr(), K, N, B.stride(0), zp, z.size, packed.data_ptr(), aux.data_ptr(),
+                         _stream(), ctypes.byref(h)), "qg_pack_b")
+    return PackedB(h, packed, aux, N)
+
+
+def _params(a_zp, bias, scales, c_zp, relu):
+    assert scales.is_cuda and scales.dtype == torch.float32 and scales.is_contiguous()
+    if bias is not None:
+        assert bias.is_cuda and bias.dtype == torch.int32 and bias.is_contiguous()
+    return RequantParams(int(a_zp), bias.data_ptr() if bias is not None else None, scales.data_ptr(),
+                         scales.numel(), int(c_zp), int(bool(relu)))
+
+
+def gemm_workspace_bytes(M, Bp):
+    return lib.qg_gemm_workspace_bytes(M, Bp.handle)
+
+
+def gemm_u8s8_requant(A, a_zp, Bp, bias, scales, c_zp, relu, out=None, workspace=None):
+    """C_u8 = requant(A_u8 . B_s8): A uint8 cuda [M, K]; returns / fills uint8 [M, N]."""
+    assert A.is_cuda and A.dtype == torch.uint8 and A.dim() == 2 and A.stride(1) == 1
+    M = A.shape[0]
+    assert A.shape[1] == Bp.K
+    if out is None:
+        out = torch.empty((M, Bp.N), dtype=torch.uint8, device=A.device)
+    assert out.is_cuda and out.dtype == torch.uint8 and out.stride(1) == 1 and out.shape == (M, Bp.N)
+    p = _params(a_zp, bias, scales, c_zp, relu)
+    ws = workspace.data_ptr() if workspace is not None else None
+    _check(lib.qg_gemm_u8s8_requant(A.data_ptr(), M, A.stride(0), Bp.handle, ctypes.byref(p), out.data_ptr(),
+                                    out.stride(0), ws, _stream()), "qg_gemm_u8s8_requant")
+    return out
+
+
+def gemm_u8s8_acc32(A, Bp, want_rowsum=False):
+    assert A.is_cuda and A.dtype == torch.uint8 and A.dim() == 2 and A.stride(1) == 1
+    M = A.shape[0]
+    out = torch.empty((M, Bp.N), dtype=torch.int32, device=A.device)
+    rs = torch.empty(M, dtype=torch.int32, device=A.device) if want_rowsum else None
+    _check(lib.qg_gemm_u8s8_acc32(A.data_ptr(), M, A.stride(0), Bp.handle, out.data_ptr(), out.stride(0),
+                                  rs.data_ptr() if rs is not None else None, None, _stream()),
+           "qg_gemm_u8s8_acc32")
+    return (out, rs) if want_rowsum else out
+
+
+def pack_conv_w(Wt, b_zp):
+    """Wt: int8 cuda [G][R][S][C/G][Cout/G], contiguous."""
+    assert Wt.is_cuda and Wt.dtype == torch.int8 and Wt.dim() == 5 and Wt.is_contiguous()
+    G, R, S, Cg, Og = Wt.shape
+    pb, cb = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib.qg_pack_conv_w_sizes(G, R, S, Cg, Og, ctypes.byref(pb), ctypes.byref(cb)), "qg_pack_conv_w_sizes")
+    packed = torch.empty(pb.value, dtype=torch.int8, device=Wt.device)
+    aux = torch.empty(cb.value // 4, dtype=torch.int32, device=Wt.device)
+    z, zp = _host_i32(b_zp)
+    h = ctypes.c_void_p()
+    _check(lib.qg_pack_conv_w(Wt.data_ptr(), G, R, S, Cg, Og, zp, z.size, packed.data_ptr(), aux.data_ptr(),
+                              _stream(), ctypes.byref(h)), "qg_pack_conv_w")
+    pk = PackedB(h, packed, aux, G * Og)
+    pk.R, pk.S = R, S
+    return pk
+
+
+def conv_groupwise_u8s8_requant(inp, Wp, a_zp, bias, scales, c_zp, relu, pad=1, stride=1, out=None):
+    """inp: uint8 cuda NHWC contiguous; returns uint8 NHWC."""
+    assert inp.is_cuda and inp.dtype == torch.uint8 and inp.dim() == 4 and inp.is_contiguous()
+    Nb, H, W, C = inp.shape
+    Ho = (H + 2 * pad - Wp.R) // stride + 1
+    Wo = (W + 2 * pad - Wp.S) // stride + 1
+    if out is None:
+        out = torch.empty((Nb, Ho, Wo, Wp.N), dtype=torch.uint8, device=inp.device)
+    assert out.is_contiguous() and out.shape == (Nb, Ho, Wo, Wp.N)
+    p = _params(a_zp, bias, scales, c_zp, relu)
+    _check(lib.qg_conv_groupwise_u8s8_requant(inp.data_ptr(), Nb, H, W, C, pad, stride, Wp.handle,
+                                              ctypes.byref(p), out.data_ptr(), _stream()),
+           "qg_conv_groupwise_u8s8_requant")
+    return out

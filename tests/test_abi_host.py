@@ -1,0 +1,111 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol the header declares,
+and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "qgemm.h")
+LIB = os.path.join(ROOT, "paper_2101_05615_amd", "libqgemm.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        import __graft_entry__ as g
+        g.build()
+    from paper_2101_05615_amd import qgemm
+    return qgemm.lib
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qg_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    syms = declared_symbols()
+    for must in ["qg_pack_b", "qg_pack_b_sizes", "qg_gemm_u8s8_requant", "qg_gemm_u8s8_acc32",
+                 "qg_conv_groupwise_u8s8_requant", "qg_packed_b_destroy", "qg_status_string"]:
+        assert must in syms
+
+
+def test_library_exports_every_declared_symbol(lib):
+    raw = ctypes.CDLL(LIB)
+    for s in declared_symbols():
+        assert hasattr(raw, s), f"{s} declared in qgemm.h but not exported"
+    from paper_2101_05615_amd import qgemm
+    assert sorted(qgemm.EXPORTS) == declared_symbols()
+
+
+def test_no_torch_types_in_the_boundary():
+    text = open(HEADER).read()
+    assert "torch" not in text.lower() and "at::" not in text and "#include <hip" not in text
+
+
+def test_pack_sizes_and_padding(lib):
+    pb, cb = ctypes.c_size_t(), ctypes.c_size_t()
+    assert lib.qg_pack_b_sizes(4096, 4096, ctypes.byref(pb), ctypes.byref(cb)) == 0
+    assert pb.value == 4096 * 4096 and cb.value == 2 * 4096 * 4
+    assert lib.qg_pack_b_sizes(36, 4, ctypes.byref(pb), ctypes.byref(cb)) == 0
+    assert pb.value == 128 * 256 and cb.value == 2 * 256 * 4
+    assert lib.qg_pack_b_sizes(1, 257, ctypes.byref(pb), ctypes.byref(cb)) == 0
+    assert pb.value == 128 * 512
+
+
+def test_size_query_rejects_bad_arguments(lib):
+    from paper_2101_05615_amd import qgemm as q
+    pb, cb = ctypes.c_size_t(), ctypes.c_size_t()
+    assert lib.qg_pack_b_sizes(0, 4, ctypes.byref(pb), ctypes.byref(cb)) == q.EINVAL
+    assert lib.qg_pack_b_sizes(4, -1, ctypes.byref(pb), ctypes.byref(cb)) == q.EINVAL
+    assert lib.qg_pack_b_sizes(q.MAX_K + 1, 4, ctypes.byref(pb), ctypes.byref(cb)) == q.EINVAL
+    assert lib.qg_pack_b_sizes(q.MAX_K, 4, ctypes.byref(pb), ctypes.byref(cb)) == q.OK
+    assert lib.qg_pack_b_sizes(4, 4, None, ctypes.byref(cb)) == q.ENULL
+    assert lib.qg_pack_conv_w_sizes(32, 3, 3, 4, 4, ctypes.byref(pb), ctypes.byref(cb)) == q.OK
+    assert pb.value >= 32 * 36 * 4
+    assert lib.qg_pack_conv_w_sizes(32, 3, 3, 8, 4, ctypes.byref(pb), ctypes.byref(cb)) == q.EUNSUPPORTED
+    assert lib.qg_pack_conv_w_sizes(32, 5, 5, 4, 4, ctypes.byref(pb), ctypes.byref(cb)) == q.EUNSUPPORTED
+    assert lib.qg_pack_conv_w_sizes(0, 3, 3, 4, 4, ctypes.byref(pb), ctypes.byref(cb)) == q.EINVAL
+
+
+def test_null_and_range_checks_happen_before_any_device_work(lib):
+    from paper_2101_05615_amd import qgemm as q
+    h = ctypes.c_void_p()
+    fake = ctypes.c_void_p(256)  # never dereferenced: the checks below fail first
+    assert lib.qg_pack_b(None, 4, 4, 4, fake, 1, fake, fake, None, ctypes.byref(h)) == q.ENULL
+    assert lib.qg_pack_b(fake, 4, 4, 4, None, 1, fake, fake, None, ctypes.byref(h)) == q.ENULL
+    assert lib.qg_pack_b(fake, 4, 4, 3, fake, 1, fake, fake, None, ctypes.byref(h)) == q.EINVAL   # ldb < N
+    assert lib.qg_pack_b(fake, 4, 4, 4, fake, 2, fake, fake, None, ctypes.byref(h)) == q.EINVAL   # n_b_zp
+    assert lib.qg_pack_b(fake, q.MAX_K + 1, 4, 4, fake, 1, fake, fake, None, ctypes.byref(h)) == q.EINVAL
+    assert lib.qg_pack_b(fake, 4, 4, 4, fake, 1, ctypes.c_void_p(260), fake, None, ctypes.byref(h)) == q.EALIGN
+    p = q.RequantParams(0, None, 256, 1, 0, 0)
+    assert lib.qg_gemm_u8s8_requant(fake, 4, 4, None, ctypes.byref(p), fake, 4, None, None) == q.ENULL
+    assert lib.qg_gemm_u8s8_acc32(None, 4, 4, None, fake, 4, None, None, None) == q.ENULL
+    assert lib.qg_conv_groupwise_u8s8_requant(fake, 1, 4, 4, 4, 1, 1, None, ctypes.byref(p), fake, None) == q.ENULL
+    lib.qg_packed_b_destroy(None)
+    assert lib.qg_packed_b_k(None) == 0 and lib.qg_gemm_workspace_bytes(16, None) == 0
+
+
+def test_status_strings(lib):
+    for code in range(0, -8, -1):
+        s = lib.qg_status_string(code)
+        assert s and (code == 0) == (s == b"ok")
+    assert lib.qg_status_string(-99) == b"unknown status"
+
+
+def test_column_permutation_is_a_bijection_with_16_contiguous_columns_per_lane():
+    # host model of the packed layout rule stated in the header of the packing code:
+    # column c = 16h + 4q + t of a 32-column super-block sits in slot 8q + 4h + t
+    slot = lambda c: ((c >> 2) & 3) * 8 + (c >> 4) * 4 + (c & 3)
+    assert sorted(slot(c) for c in range(32)) == list(range(32))
+    # the 32x32 MFMA gives lane-half h, register r = 4q + t the row 8q + 4h + t:
+    for h in range(2):
+        cols = []
+        for r in range(16):
+            q, t = r >> 2, r & 3
+            i = 8 * q + 4 * h + t
+            cols.append([c for c in range(32) if slot(c) == i][0])
+        assert cols == list(range(16 * h, 16 * h + 16))

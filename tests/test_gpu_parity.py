@@ -1,0 +1,303 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, bit for bit.
+
+Integer results (column offsets, row sums, int32 accumulators) and requantized uint8 outputs must be
+identical: every step is integer arithmetic or a fixed sequence of correctly rounded fp32 operations, so
+exactly one result is right and the tolerance is zero.
+"""
+import numpy as np
+import pytest
+
+from paper_2101_05615_amd import workloads as wl
+from gpu_util import assert_same, dev_case, oracle_gemm, run_gemm, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2101_05615_amd import qgemm as q
+    import oracle
+    oracle.build()
+    return q, torch, torch.device("cuda:0"), oracle
+
+
+# ---------------------------------------------------------------- sub-results
+@pytest.mark.parametrize("K,N,per_channel", [(128, 64, False), (36, 4, True), (100, 100, True), (4097, 257, True),
+                                             (1, 1, False), (4096, 512, True)])
+def test_col_offsets_match_oracle(env, K, N, per_channel):
+    q, torch, dev, oracle = env
+    say(f"col_offsets K={K} N={N}")
+    c = wl.random_gemm(K + N, 2, N, K, per_channel=per_channel, wide_zp=True)
+    Bp = q.pack_b(torch.from_numpy(c.B).to(dev), c.b_zp)
+    torch.cuda.synchronize()
+    assert_same(Bp.col_offsets.cpu().numpy(), oracle.col_offsets(c.B, c.b_zp), "col_offsets")
+
+
+def test_pack_b_accepts_strided_b(env):
+    q, torch, dev, oracle = env
+    c = wl.random_gemm(77, 20, 50, 90, wide_zp=True)
+    big = torch.zeros((90, 64), dtype=torch.int8, device=dev)
+    big[:, :50] = torch.from_numpy(c.B).to(dev)
+    Bp = q.pack_b(big[:, :50], c.b_zp)
+    acc = q.gemm_u8s8_acc32(torch.from_numpy(c.A).to(dev), Bp)
+    torch.cuda.synchronize()
+    assert_same(Bp.col_offsets.cpu().numpy(), oracle.col_offsets(c.B, c.b_zp), "col_offsets strided")
+    assert_same(acc.cpu().numpy(), oracle.acc32(c.A, c.B), "acc32 strided B")
+
+
+ACC_SHAPES = [  # (M, N, K): both kernels (M <= 64 skinny, above: large tile), ragged in every dimension
+    (1, 1, 1), (1, 16, 64), (16, 16, 64), (16, 32, 128), (16, 100, 300), (17, 40, 36), (33, 257, 4097),
+    (64, 64, 128), (5, 4, 36), (48, 512, 1024),
+    (65, 64, 128), (255, 100, 100), (256, 256, 128), (257, 300, 129), (300, 4, 36), (512, 512, 512),
+    (700, 520, 4097), (1024, 256, 2048),
+]
+
+
+@pytest.mark.parametrize("M,N,K", ACC_SHAPES)
+def test_int32_accumulators_and_row_sums_bit_exact(env, M, N, K):
+    q, torch, dev, oracle = env
+    say(f"acc32 M={M} N={N} K={K}")
+    c = wl.random_gemm(M * 7 + N * 3 + K, M, N, K, wide_zp=True)
+    Bp = q.pack_b(torch.from_numpy(c.B).to(dev), c.b_zp)
+    acc, rs = q.gemm_u8s8_acc32(torch.from_numpy(c.A).to(dev), Bp, want_rowsum=True)
+    torch.cuda.synchronize()
+    assert_same(acc.cpu().numpy(), oracle.acc32(c.A, c.B), "acc32")
+    assert_same(rs.cpu().numpy(), oracle.rowsum(c.A), "rowsum")
+
+
+def test_accumulator_extremes_do_not_saturate(env):
+    # all-255 activations against all -128 / +127 weights at the largest K: |acc| ~ 1.07e9, still exact int32
+    q, torch, dev, oracle = env
+    K = q.MAX_K
+    for M in (16, 80):
+        for b in (-128, 127):
+            say(f"extremes M={M} b={b}")
+            A = np.full((M, K), 255, np.uint8)
+            B = np.full((K, 20), b, np.int8)
+            Bp = q.pack_b(torch.from_numpy(B).to(dev), np.zeros(1, np.int32))
+            acc, rs = q.gemm_u8s8_acc32(torch.from_numpy(A).to(dev), Bp, want_rowsum=True)
+            torch.cuda.synchronize()
+            assert np.all(acc.cpu().numpy() == 255 * b * K)
+            assert np.all(rs.cpu().numpy() == 255 * K)
+
+
+# ------------------------------------------------------------ requantized C
+REQ_SHAPES = [
+    (1, 1, 1), (1, 4, 36), (16, 64, 128), (16, 100, 100), (17, 100, 100), (31, 33, 65), (64, 257, 4097),
+    (65, 64, 128), (100, 4, 36), (255, 100, 100), (256, 256, 256), (257, 255, 127), (300, 300, 300),
+    (513, 264, 1000),
+]
+
+
+@pytest.mark.parametrize("M,N,K", REQ_SHAPES)
+@pytest.mark.parametrize("per_channel,relu,with_bias", [(True, False, True), (False, True, False)])
+def test_requant_bit_exact_on_ragged_shapes(env, M, N, K, per_channel, relu, with_bias):
+    q, torch, dev, oracle = env
+    say(f"requant M={M} N={N} K={K} pc={per_channel} relu={relu} bias={with_bias}")
+    c = wl.random_gemm(M + 2 * N + 3 * K, M, N, K, per_channel=per_channel, with_bias=with_bias, relu=relu)
+    got, _, _ = run_gemm(c, q, torch, dev)
+    want = oracle_gemm(c, oracle)
+    assert_same(got, want, c.name)
+    if M * N >= 4096:
+        inside = np.mean((want > 0) & (want < 255))
+        assert inside > 0.3, f"parity case is mostly saturated ({inside:.2f} unsaturated)"
+
+
+@pytest.mark.parametrize("M,N,K", [(16, 100, 100), (40, 260, 300), (200, 100, 100), (300, 260, 300)])
+def test_unaligned_pointers_and_padded_leading_dimensions(env, M, N, K):
+    # lda/ldc not multiples of 16 and odd base addresses: the byte-wise load/store paths; and the guard bytes
+    # around C must stay untouched
+    q, torch, dev, oracle = env
+    c = wl.random_gemm(M + N + K, M, N, K)
+    want = oracle_gemm(c, oracle)
+    for (lp, cp, ao, co) in [(3, 5, 1, 3), (16, 16, 0, 0), (0, 0, 16, 16), (12, 4, 4, 8)]:
+        say(f"unaligned M={M} N={N} K={K} lda+{lp} ldc+{cp} a_off={ao} c_off={co}")
+        got, store, _ = run_gemm(c, q, torch, dev, lda_pad=lp, ldc_pad=cp, a_off=ao, c_off=co)
+        assert_same(got, want, f"{c.name} lda+{lp} ldc+{cp}")
+        guard = store.copy()
+        view = guard[co:co + M * (N + cp)].reshape(M, N + cp)
+        view[:, :N] = 0xEE
+        assert np.all(guard == 0xEE), "bytes outside C were written"
+
+
+@pytest.mark.parametrize("a_zp,b_zp,c_zp", [(0, -128, 0), (255, 127, 255), (0, 127, 128), (255, -128, 1), (128, 0, 0)])
+@pytest.mark.parametrize("M", [16, 130])
+def test_extreme_zero_points(env, a_zp, b_zp, c_zp, M):
+    q, torch, dev, oracle = env
+    say(f"zp extremes M={M} a_zp={a_zp} b_zp={b_zp} c_zp={c_zp}")
+    c = wl.random_gemm(a_zp + c_zp + M, M, 72, 500, per_channel=False, a_zp=a_zp, c_zp=c_zp, unsat=False)
+    c.b_zp = np.array([b_zp], np.int32)
+    c.scales = np.array([2.0 ** -12], np.float32)
+    got, _, _ = run_gemm(c, q, torch, dev)
+    assert_same(got, oracle_gemm(c, oracle), c.name)
+
+
+def test_hand_worked_rounding_cases_through_the_gpu(env):
+    # x is injected through the bias with an all-zero accumulator (A = theta_A everywhere); expected values
+    # are the hand-worked ones in tests/golden/requant_hand_cases.txt
+    import os
+    q, torch, dev, oracle = env
+    rows = []
+    with open(os.path.join(os.path.dirname(__file__), "golden", "requant_hand_cases.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if line:
+                x, s, z, r, e = line.split()
+                rows.append((int(x), float(s), int(z), int(r), int(e)))
+    for M in (3, 70):  # both kernels
+        for x, s, z, r, e in rows:
+            A = np.full((M, 8), 7, np.uint8)
+            B = np.ones((8, 2), np.int8)
+            c = wl.GemmCase("hand", A, 7, B, np.zeros(1, np.int32), np.array([x, x], np.int32),
+                            np.array([s], np.float32), z, bool(r))
+            got, _, _ = run_gemm(c, q, torch, dev)
+            assert np.all(got == e), (M, x, s, z, r, e, got[0])
+
+
+# ---------------------------------------------------- the five stated configs
+def test_config1_tiny(env):
+    q, torch, dev, oracle = env
+    c = wl.config1_tiny()
+    got, _, _ = run_gemm(c, q, torch, dev)
+    assert_same(got, oracle_gemm(c, oracle), c.name)
+    u = wl.unsaturated(c)
+    got, _, _ = run_gemm(u, q, torch, dev)
+    assert_same(got, oracle_gemm(u, oracle), u.name)
+
+
+@pytest.mark.parametrize("with_bias", [False, True])
+def test_config2_small_batch_fc_full(env, with_bias):
+    q, torch, dev, oracle = env
+    c = wl.config2_small_batch_fc(with_bias=with_bias)
+    say(c.name)
+    got, _, _ = run_gemm(c, q, torch, dev)
+    assert_same(got, oracle_gemm(c, oracle), c.name)
+    u = wl.unsaturated(c)
+    got, _, _ = run_gemm(u, q, torch, dev)
+    want = oracle_gemm(u, oracle)
+    assert_same(got, want, u.name)
+    assert np.mean((want > 0) & (want < 255)) > 0.5
+
+
+def _sampled_rows(M, tile, rng, extra):
+    rows = [t * tile + int(rng.integers(0, min(tile, M - t * tile))) for t in range((M + tile - 1) // tile)]
+    rows += [0, M - 1] + [int(v) for v in rng.integers(0, M, extra)]
+    return np.array(sorted(set(rows)))
+
+
+def test_config3_square_full_size_sampled_rows(env):
+    # the launch configuration bench.py times; the oracle recomputes complete rows (all 8192 columns), at
+    # least one in every 256-row tile, so every workgroup tile of the grid is checked
+    q, torch, dev, oracle = env
+    c = wl.config3_square()
+    say(c.name)
+    rows = _sampled_rows(c.M, 256, np.random.default_rng(0), 16)
+    for case in (c, wl.unsaturated(c)):
+        got, _, Bp = run_gemm(case, q, torch, dev)
+        assert_same(got[rows], oracle_gemm(case, oracle, rows), case.name + " sampled rows")
+        assert_same(Bp.col_offsets.cpu().numpy(), oracle.col_offsets(case.B, case.b_zp), "col_offsets")
+    # properties that hold at any size: determinism, and ReLU lower bound = theta_C
+    got2, _, _ = run_gemm(c, q, torch, dev)
+    got1, _, _ = run_gemm(c, q, torch, dev)
+    assert np.array_equal(got1, got2)
+    assert got1.min() >= c.c_zp
+
+
+def test_config4_recsys_mlp_full_size_sampled_rows(env):
+    q, torch, dev, oracle = env
+    c = wl.config4_recsys_mlp()
+    say(c.name)
+    rows = _sampled_rows(c.M, 256, np.random.default_rng(1), 64)
+    for case in (c, wl.unsaturated(c)):
+        got, _, _ = run_gemm(case, q, torch, dev)
+        assert_same(got[rows], oracle_gemm(case, oracle, rows), case.name + " sampled rows")
+
+
+def test_determinism_and_independence_of_m_padding(env):
+    # the same rows give the same bytes whether they are computed alone (small-batch kernel) or as part
+    # of a larger batch (large-tile kernel): any K split or tile order must produce identical integers
+    q, torch, dev, oracle = env
+    c = wl.random_gemm(99, 300, 200, 700)
+    full, _, _ = run_gemm(c, q, torch, dev)
+    sub = wl.GemmCase("sub", np.ascontiguousarray(c.A[:16]), c.a_zp, c.B, c.b_zp, c.bias, c.scales, c.c_zp, c.relu)
+    part, _, _ = run_gemm(sub, q, torch, dev)
+    assert_same(part, full[:16], "skinny vs tile kernel")
+
+
+# ------------------------------------------------------------------ group conv
+def _run_conv(c, q, torch, dev):
+    Wp = q.pack_conv_w(torch.from_numpy(c.wgt).to(dev), c.b_zp)
+    bias = None if c.bias is None else torch.from_numpy(c.bias).to(dev)
+    out = q.conv_groupwise_u8s8_requant(torch.from_numpy(c.inp).to(dev), Wp, c.a_zp, bias,
+                                        torch.from_numpy(c.scales).to(dev), c.c_zp, c.relu, c.pad, c.stride)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), Wp
+
+
+def _oracle_conv(c, oracle):
+    return oracle.conv_groupwise_direct(c.inp, c.G, c.wgt, c.a_zp, c.b_zp, c.bias, c.scales, c.c_zp, c.relu,
+                                        c.pad, c.stride)
+
+
+@pytest.mark.parametrize("cfg", [
+    dict(Nb=1, H=3, W=3, C=4, G=1), dict(Nb=2, H=5, W=7, C=16, G=4), dict(Nb=1, H=9, W=6, C=128, G=32),
+    dict(Nb=3, H=8, W=8, C=32, G=8, stride=2), dict(Nb=1, H=6, W=6, C=8, G=2, pad=0),
+    dict(Nb=1, H=5, W=5, C=12, G=3, pad=2), dict(Nb=2, H=4, W=4, C=16, G=4, R=1, S=1, pad=0),
+    dict(Nb=1, H=1, W=1, C=4, G=1),
+])
+@pytest.mark.parametrize("per_channel,with_bias,relu", [(True, True, False), (False, False, True)])
+def test_group_conv_bit_exact_small(env, cfg, per_channel, with_bias, relu):
+    q, torch, dev, oracle = env
+    say(f"conv {cfg}")
+    c = wl.random_conv(5, per_channel=per_channel, with_bias=with_bias, relu=relu, **cfg)
+    got, Wp = _run_conv(c, q, torch, dev)
+    assert_same(got, _oracle_conv(c, oracle), c.name)
+
+
+def test_config5_group_conv_full(env):
+    q, torch, dev, oracle = env
+    c = wl.config5_group_conv()
+    say(c.name)
+    got, _ = _run_conv(c, q, torch, dev)
+    want = _oracle_conv(c, oracle)
+    assert_same(got, want, c.name)
+    # parity-sensitive variant: scales sized so most outputs are unsaturated
+    c.scales = (c.scales * 0 + 40.0 / (6.0 * 74.0 * 74.0)).astype(np.float32)
+    got, _ = _run_conv(c, q, torch, dev)
+    want = _oracle_conv(c, oracle)
+    assert_same(got, want, c.name + "_unsat")
+    assert np.mean((want > 0) & (want < 255)) > 0.5
+
+
+# ------------------------------------------------------------- error handling
+def test_runtime_argument_errors(env):
+    import ctypes
+    q, torch, dev, oracle = env
+    c = wl.config1_tiny()
+    A, B, bias, scales, C, _ = dev_case(c, torch, dev)
+    Bp = q.pack_b(B, c.b_zp)
+    bad = [dict(a_zp=256), dict(a_zp=-1), dict(c_zp=256), dict(n_scales=2), dict(relu=2)]
+    for kw in bad:
+        p = q.RequantParams(128, None, scales.data_ptr(), 1, 0, 0)
+        for k, v in kw.items():
+            setattr(p, k, v)
+        rc = q.lib.qg_gemm_u8s8_requant(A.data_ptr(), 64, 128, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None)
+        assert rc == q.EINVAL, kw
+    p = q.RequantParams(128, None, scales.data_ptr(), 1, 0, 0)
+    assert q.lib.qg_gemm_u8s8_requant(A.data_ptr(), 64, 127, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None) == q.EINVAL
+    assert q.lib.qg_gemm_u8s8_requant(A.data_ptr(), 64, 128, Bp.handle, ctypes.byref(p), C.data_ptr(), 63, None, None) == q.EINVAL
+    assert q.lib.qg_gemm_u8s8_requant(A.data_ptr(), 0, 128, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None) == q.EINVAL
+    assert q.lib.qg_gemm_u8s8_requant(A.data_ptr(), 64, 128, Bp.handle, ctypes.byref(p), None, 64, None, None) == q.ENULL
+    p.scales = None
+    assert q.lib.qg_gemm_u8s8_requant(A.data_ptr(), 64, 128, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None) == q.ENULL
+    with pytest.raises(q.QGemmError) as ei:
+        q.pack_b(B, np.array([200], np.int32))  # theta_B outside int8
+    assert ei.value.code == q.EINVAL
+    # a conv descriptor is not a GEMM descriptor
+    cc = wl.random_conv(1, Nb=1, H=4, W=4, C=8, G=2)
+    Wp = q.pack_conv_w(torch.from_numpy(cc.wgt).to(dev), cc.b_zp)
+    p = q.RequantParams(128, None, scales.data_ptr(), 1, 0, 0)
+    assert q.lib.qg_gemm_u8s8_requant(A.data_ptr(), 64, 128, Wp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None) == q.EINVAL
+    torch.cuda.synchronize()
