@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized-GEMM hot path on one MI355X.
+
+A "step" is one pass of the run-time hot path, qg_gemm_u8s8_requant, over one batch of synthetic input
+already resident in HBM: A staging with uint8->int8 shift and fused row offsets, the int8 MFMA main loop,
+and the requantization output pipeline.  Weight packing (qg_pack_b) is the paper's offline step (done
+once per weight matrix, Sec. 2.2); it is timed separately and reported as `pack_b_ms`, never included
+in `value`.
+
+Prints ONE JSON line.  `value` is int8 GEMM+requant TOPS (2*M*N*K / time) at M=N=K=8192; the other
+stated configs (HBM GB/s at M=16, N=K=4096 first of all) are reported under `configs`.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 MFMA, published
+PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, published
+
+
+def gemm_bytes(M, N, K, bias):
+    # algorithmic bytes of one call: A and B read once, C written once, column offsets (+ bias)
+    return M * K + K * N + M * N + 4 * N + (4 * N if bias else 0)
+
+
+def time_calls(torch, fn, steps, warmup):
+    """Wall-clock and device-event timing of `steps` back-to-back calls on torch's current stream."""
+    for _ in range(warmup):
+        fn(0)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(steps):
+        fn(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    dev_ms = ev0.elapsed_time(ev1) / steps
+    return wall_ms, dev_ms
+
+
+def traffic_from_profiles(kernel_key):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), if a summary is committed."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 2 and parts[0] == kernel_key:
+            try:
+                return float(parts[1])
+            except ValueError:
+                return None
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", default="", help="comma list of c1..c5 to restrict the side configs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards over M or N with no collective; "
+              "see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2101_05615_amd import qgemm as q
+    from paper_2101_05615_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    only = set(args.only.split(",")) if args.only else None
+    side = []
+
+    def up(x):
+        return None if x is None else torch.from_numpy(x).to(dev)
+
+    def gemm_setup(case):
+        A, B = up(case.A), up(case.B)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        Bp = q.pack_b(B, case.b_zp)
+        torch.cuda.synchronize()
+        pack_ms = (time.perf_counter() - t0) * 1e3
+        bias, scales = up(case.bias), up(case.scales)
+        C = torch.empty((case.M, case.N), dtype=torch.uint8, device=dev)
+        return A, Bp, bias, scales, C, pack_ms
+
+    # ------------------------------------------------------------------ headline: config 3
+    c3 = wl.config3_square()
+    A, Bp, bias, scales, C, pack_ms = gemm_setup(c3)
+
+    def step3(_):
+        q.gemm_u8s8_requant(A, c3.a_zp, Bp, bias, scales, c3.c_zp, c3.relu, out=C)
+
+    wall_ms, dev_ms = time_calls(torch, step3, args.steps, args.warmup)
+    ops = 2.0 * c3.M * c3.N * c3.K
+    tops = ops / (wall_ms * 1e-3) / 1e12
+    kern_tops = ops / (dev_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "qg_gemm_tile_kernel", "achieved": round(kern_tops, 2),
+                "peak": PEAK_INT8_TOPS, "unit": "TOP/s", "frac": round(kern_tops / PEAK_INT8_TOPS, 4),
+                "avg_launch_ms": round(dev_ms, 5), "traffic": traffic_from_profiles("qg_gemm_tile_kernel_c3")}
+    # spot check of the timed output against the sampled property used in the tests: ReLU floor
+    assert int(C.min().item()) >= c3.c_zp
+
+    # ------------------------------------------------------------------ cpu baseline (oracle, bounded sample)
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        rows = 4
+        t_used, total_rows = 0.0, 0
+        while True:
+            sub = np.ascontiguousarray(c3.A[:rows])
+            t0 = time.perf_counter()
+            want = oracle.gemm_u8s8_requant(sub, c3.a_zp, c3.B, c3.b_zp, c3.bias, c3.scales, c3.c_zp, c3.relu)
+            dt = time.perf_counter() - t0
+            if rows >= 4 and (dt >= 8.0 or rows >= c3.M):
+                t_used, total_rows = dt, rows
+                break
+            rows = min(c3.M, max(rows * 2, int(rows * 12.0 / max(dt, 1e-3))))
+        got = C[:total_rows].cpu().numpy()
+        if not np.array_equal(got, want):
+            print("bench.py: GPU output differs from the oracle on the cpu_baseline sample", file=sys.stderr)
+            sys.exit(3)
+        cpu = {"value": round(2.0 * total_rows * c3.N * c3.K / t_used / 1e12, 5), "unit": "TOPS",
+               "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"first {total_rows} rows of the 8192x8192x8192 workload (all N, all K), "
+                         f"{t_used:.1f} s, output compared bit-exact with the GPU result"}
+    del A, Bp, bias, scales, C
+
+    # ------------------------------------------------------------------ config 2: HBM-bound small batch
+    if only is None or "c2" in only:
+        c2 = wl.config2_small_batch_fc()
+        A2, Bp2, bias2, scales2, C2, pack2_ms = gemm_setup(c2)
+        nbytes = gemm_bytes(c2.M, c2.N, c2.K, False)
+        # warm: same buffers every call (working set 17 MB stays in the 256 MB Infinity Cache)
+        _, warm_ms = time_calls(torch, lambda i: q.gemm_u8s8_requant(A2, c2.a_zp, Bp2, None, scales2, c2.c_zp,
+                                                                      c2.relu, out=C2), 200, 20)
+        # cold: rotate over distinct packed weights, > 1 GB before any reuse
+        nsets = 72
+        B2 = up(c2.B)
+        sets = []
+        for _ in range(nsets):
+            sets.append((q.pack_b(B2, c2.b_zp), A2.clone(), torch.empty_like(C2)))
+        torch.cuda.synchronize()
+        _, cold_ms = time_calls(torch, lambda i: q.gemm_u8s8_requant(sets[i % nsets][1], c2.a_zp, sets[i % nsets][0],
+                                                                      None, scales2, c2.c_zp, c2.relu,
+                                                                      out=sets[i % nsets][2]), 2 * nsets, nsets)
+        side.append({"workload": c2.name, "bound": "hbm", "bytes": nbytes,
+                     "cold_us": round(cold_ms * 1e3, 2), "warm_us": round(warm_ms * 1e3, 2),
+                     "cold_GBps": round(nbytes / (cold_ms * 1e-3) / 1e9, 1),
+                     "warm_GBps": round(nbytes / (warm_ms * 1e-3) / 1e9, 1),
+                     "frac_hbm_peak_cold": round(nbytes / (cold_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                     "pack_b_ms": round(pack2_ms, 3)})
+        del sets, A2, Bp2, C2, B2
+
+    # ------------------------------------------------------------------ config 1 and 4
+    for key, make in (("c1", wl.config1_tiny), ("c4", wl.config4_recsys_mlp)):
+        if only is not None and key not in only:
+            continue
+        c = make()
+        Ax, Bpx, biasx, scalesx, Cx, packx_ms = gemm_setup(c)
+        _, ms = time_calls(torch, lambda i: q.gemm_u8s8_requant(Ax, c.a_zp, Bpx, biasx, scalesx, c.c_zp, c.relu,
+                                                                out=Cx), 50, 5)
+        nb = gemm_bytes(c.M, c.N, c.K, c.bias is not None)
+        o = 2.0 * c.M * c.N * c.K
+        side.append({"workload": c.name, "us": round(ms * 1e3, 2), "TOPS": round(o / (ms * 1e-3) / 1e12, 2),
+                     "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
+                     "frac_int8_peak": round(o / (ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 4),
+                     "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "pack_b_ms": round(packx_ms, 3)})
+        del Ax, Bpx, Cx
+
+    # ------------------------------------------------------------------ config 5: group conv
+    if only is None or "c5" in only:
+        c5 = wl.config5_group_conv()
+        inp, wgt = up(c5.inp), up(c5.wgt)
+        Wp = q.pack_conv_w(wgt, c5.b_zp)
+        sc5 = up(c5.scales)
+        nsets = 48  # 48 x 25.7 MB > 1 GB
+        ins = [inp.clone() for _ in range(nsets)]
+        outs = [torch.empty_like(inp) for _ in range(nsets)]
+        _, warm_ms = time_calls(torch, lambda i: q.conv_groupwise_u8s8_requant(ins[0], Wp, c5.a_zp, None, sc5, c5.c_zp,
+                                                                                c5.relu, 1, 1, out=outs[0]), 100, 10)
+        _, cold_ms = time_calls(torch, lambda i: q.conv_groupwise_u8s8_requant(ins[i % nsets], Wp, c5.a_zp, None, sc5,
+                                                                                c5.c_zp, c5.relu, 1, 1,
+                                                                                out=outs[i % nsets]), 2 * nsets, nsets)
+        nb = 2 * inp.numel() + wgt.numel()
+        o = 2.0 * inp.shape[0] * 56 * 56 * 128 * 36
+        side.append({"workload": c5.name, "bound": "hbm", "bytes": nb, "cold_us": round(cold_ms * 1e3, 2),
+                     "warm_us": round(warm_ms * 1e3, 2), "cold_GBps": round(nb / (cold_ms * 1e-3) / 1e9, 1),
+                     "warm_GBps": round(nb / (warm_ms * 1e-3) / 1e9, 1),
+                     "frac_hbm_peak_cold": round(nb / (cold_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                     "TOPS_cold": round(o / (cold_ms * 1e-3) / 1e12, 2)})
+
+    out = {
+        "metric": "int8 GEMM+requant TOPS at M=N=K=8192", "value": round(tops, 2), "unit": "TOPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "config3: square GEMM M=N=K=8192, uint8 x int8 -> uint8, per-channel B_zp and "
+                               "scales, int32 bias, ReLU (seed 2)", "M": c3.M, "N": c3.N, "K": c3.K,
+                   "step": "qg_gemm_u8s8_requant (pack_b offline, reported separately)"},
+        "pack_b_ms": round(pack_ms, 3),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "configs": side,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
