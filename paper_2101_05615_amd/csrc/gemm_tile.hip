@@ -1,10 +1,12 @@
 // Large-tile quantized GEMM for compute-bound shapes.
 //
 // One launch does everything the paper fuses around the GEMM (Sec. 2.1-2.2):
-//   - A is read once; while a tile is staged on its way to LDS it is shifted from
-//     uint8 to int8 (xor 0x80 == subtract 128, the int8 MFMA is signed x signed)
-//     and its row offsets are accumulated with v_dot4 ("row offsets are computed
-//     for the block being packed", Appendix B);
+//   - A is read once from HBM, straight into LDS (global_load_lds, no register
+//     staging); when a fragment is fetched from LDS for the matrix cores it is
+//     shifted from uint8 to int8 (xor 0x80 == subtract 128: the int8 MFMA is
+//     signed x signed) and its row offsets are accumulated with v_dot4 -- the row
+//     offsets are a by-product of the staged block, never a second pass over A
+//     (Appendix B, "PackingWithRowOffset");
 //   - int32 accumulation on v_mfma_i32_32x32x32_i8, LDS double-buffered;
 //   - the output pipeline (zero-point corrections of Eq. (2), bias, fp32 scale,
 //     round-to-nearest-even, clamp/ReLU) runs on the accumulators in registers and
@@ -15,29 +17,29 @@
 //   x = acc_s - (theta_A - 128) * (colsum - K theta_B) - theta_B * rowsum_s + bias,
 // i.e. "replace theta_A by theta_A - 128" with the folded column offsets.
 //
-// Workgroup: 512 threads = 8 waves as 4 (M) x 2 (N); tile 256 x 256 x 128;
-// each wave owns 64 x 128 = 2 x 4 MFMA blocks of 32 x 32 (128 accumulator VGPRs).
-// The MFMA is issued transposed (first operand = B fragment, second = A fragment)
-// so that a lane ends up with 16 consecutive columns of one row.
+// Tile 256 x 256 x 64, four LDS stages.  The MFMA is issued transposed (first operand = B
+// fragment, second = A fragment) so that a lane ends up with 16 consecutive
+// columns of one row (one 16-byte store); the packed-B column permutation makes
+// those columns consecutive.
 #include "qg_internal.h"
+#include "tile_loop_asm.inc"
 
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 256, BN = 256, BK = 128;
-constexpr int NTHREADS = 512;
-constexpr int A_STAGE_BYTES = BM * BK;                 // 32 KiB
-constexpr int B_STAGE_BYTES = BN * BK;                 // 32 KiB
-constexpr int STAGE_BYTES = A_STAGE_BYTES + B_STAGE_BYTES;
-constexpr int ROWSUM_OFF = 2 * STAGE_BYTES;            // 256 int32 after the two stages
-constexpr int SMEM_BYTES = ROWSUM_OFF + BM * 4;
-// epilogue constants live in stage 0 once the main loop is over
-constexpr int EP_CJ_OFF = 0, EP_BZ_OFF = 1024, EP_SC_OFF = 2048;
+constexpr int BK = 64;      // k extent of one LDS stage = one packed fragment deep
+constexpr int NSTAGE = 4;   // LDS stages: three tiles in flight behind the one being consumed
 
-// swizzled byte offset of 16-byte chunk kc (0..7) of row r in an A stage
-__device__ __forceinline__ int a_lds_off(int r, int kc) { return r * BK + ((kc ^ ((r >> 1) & 7)) << 4); }
+// waves in M, waves in N, 32-row blocks per wave, 32-column blocks per wave
+#ifndef QG_TILE_CFG
+#define QG_TILE_CFG 2, 2, 4, 4
+#endif
+
+// swizzled byte offset of 16-byte chunk kc (0..3) of row r in an A stage (rows are 64 B; the xor
+// spreads the 8 rows a quarter-wave reads at once over all 32 LDS banks)
+__device__ __forceinline__ int a_lds_off(int r, int kc) { return r * BK + ((kc ^ ((r >> 1) & 3)) << 4); }
 
 __device__ __forceinline__ v4i load_a_chunk_slow(const uint8_t* p, int kvalid) {
   // byte-wise, bounds-checked; bytes past K read as 0x80 (int8 zero after the shift)
@@ -58,14 +60,34 @@ __device__ __forceinline__ int requant_one(int x, float sc, float lo, float hi, 
   return (int)r + czp;
 }
 
-template <int MODE>
-__global__ __launch_bounds__(NTHREADS) void qg_gemm_tile_kernel(const qg_gemm_args p, int tiles_m,
-                                                               int tiles_n) {
+// 16 bytes per lane from global memory into LDS at lds_base + lane*16 (lds_base wave-uniform)
+__device__ __forceinline__ void dma16(const void* gptr, unsigned char* lds_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
+                                   (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
+}
+
+// NWM x NWN waves, each TM x TN blocks of 32 x 32.
+// FAST: A is 16-byte aligned with lda % 16 == 0, K % 64 == 0 and K >= 256, so every tile is requested with
+// global_load_lds and the loop is software-pipelined four tiles deep.  Otherwise a plain,
+// single-stage loop stages A byte-wise with bounds checks (correct for any pointer, lda and K).
+template <int MODE, bool FAST, int NWM, int NWN, int TM, int TN>
+__global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_gemm_args p, int tiles_m,
+                                                                      int tiles_n) {
+  constexpr int NW = NWM * NWN, NT = NW * 64;
+  constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
+  constexpr int A_STAGE = BM * BK, B_STAGE = BN * BK, STAGE = A_STAGE + B_STAGE;
+  constexpr int A_DMA = A_STAGE / 1024 / NW;  // 1 KiB wave-loads per wave per tile
+  constexpr int B_DMA = B_STAGE / 1024 / NW;
+  constexpr int N_DMA = A_DMA + B_DMA;
+  static_assert(A_STAGE % (1024 * NW) == 0 && B_STAGE % (1024 * NW) == 0, "tile/wave mismatch");
+  static_assert(2 * N_DMA <= 63, "vmcnt is a 6-bit counter");
   extern __shared__ __align__(16) unsigned char smem[];
+
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int wave_m = wave & 3, wave_n = wave >> 2;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in an SGPR
+  const int wave_m = wave % NWM, wave_n = wave / NWM;
+  const int l32 = lane & 31, lg = lane >> 5;
 
   // ---- workgroup -> tile.  Consecutive workgroup ids go to different XCDs
   // (8 of them, each with its own L2), so give every XCD one contiguous chunk of
@@ -84,152 +106,201 @@ __global__ __launch_bounds__(NTHREADS) void qg_gemm_tile_kernel(const qg_gemm_ar
   const int tn = in_band / rows_in_band;
   const int m0 = tm * BM, n0 = tn * BN;
 
-  // ---- staging assignment: thread -> (row, 16-byte chunk) of the A tile, 4 passes
-  const int a_row = tid >> 3;  // + 64 * pass
-  const int a_kc = tid & 7;
-  const uint8_t* a_src[4];
-  int a_dst[4];
+  // ---- staging.  A: one wave-load fills 1 KiB of LDS = 16 rows x 64 B; lane l lands at row l/4,
+  // physical chunk l%4, so it fetches the logical chunk that the swizzle maps there.  B: the tile is
+  // BN/16 fragments of 1 KiB, each contiguous in the packed buffer.  Addresses are a wave-uniform
+  // base (advanced per tile on the scalar unit) plus a fixed 32-bit per-lane offset.
+  unsigned a_voff[A_DMA], b_voff[B_DMA];
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int r = a_row + 64 * q;
+  for (int q = 0; q < A_DMA; ++q) {
+    const int r = (wave * A_DMA + q) * 16 + (lane >> 2);
+    const int kc = (lane & 3) ^ ((r >> 1) & 3);
     const int rg = min(m0 + r, p.M - 1);  // rows past M re-read the last row; never stored
-    a_src[q] = p.A + (size_t)rg * p.lda + a_kc * 16;
-    a_dst[q] = a_lds_off(r, a_kc);
+    a_voff[q] = (unsigned)rg * (unsigned)p.lda + kc * 16;
   }
-  // B tile: 16 fragments-pairs of 2 KiB, a straight copy
-  const int8_t* b_src[4];
-  int b_dst[4];
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int c = q * NTHREADS + tid;  // 16-byte chunk 0..2047
-    const int nbl = c >> 7, within = c & 127;
-    b_src[q] = p.Bp + ((size_t)(n0 / QG_FRAG_COLS + nbl) * p.kb64) * QG_FRAG_BYTES + within * 16;
-    b_dst[q] = A_STAGE_BYTES + c * 16;
-  }
+  for (int q = 0; q < B_DMA; ++q)
+    b_voff[q] = (unsigned)(wave * B_DMA + q) * (unsigned)p.kb64 * QG_FRAG_BYTES + lane * 16;
+  const int8_t* b_tile0 = p.Bp + (size_t)(n0 / QG_FRAG_COLS) * p.kb64 * QG_FRAG_BYTES;
 
-  v4i a_reg[4], b_reg[4];
-  int rs[4] = {0, 0, 0, 0};
-
-  auto load_global = [&](int kt) {
-    const int k0 = kt * BK;
-    if (p.a_vec && k0 + BK <= p.K) {
+  auto request_tile = [&](int kt, int stage) {
+    unsigned char* base = smem + stage * STAGE;
+    const uint8_t* a_base = p.A + kt * BK;
+    const int8_t* b_base = b_tile0 + (size_t)kt * QG_FRAG_BYTES;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) a_reg[q] = *reinterpret_cast<const v4i*>(a_src[q] + k0);
-    } else {
-      const int kvalid = p.K - (k0 + a_kc * 16);
+    for (int q = 0; q < A_DMA; ++q) dma16(a_base + a_voff[q], base + (wave * A_DMA + q) * 1024);
 #pragma unroll
-      for (int q = 0; q < 4; ++q) a_reg[q] = load_a_chunk_slow(a_src[q] + k0, kvalid);
-    }
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-      b_reg[q] = *reinterpret_cast<const v4i*>(b_src[q] + (size_t)kt * (2 * QG_FRAG_BYTES));
+    for (int q = 0; q < B_DMA; ++q) dma16(b_base + b_voff[q], base + A_STAGE + (wave * B_DMA + q) * 1024);
   };
 
-  auto store_lds = [&](int stage) {
-    unsigned char* base = smem + stage * STAGE_BYTES;
+  // ---- fragment fetch (LDS -> registers): per-lane base offsets, everything else is an immediate
+  int a_rd[2];  // k-step 0 / 1 of block mb = 0; block mb is 32 rows = 2 KiB further
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      v4i v = a_reg[q] ^ (int)0x80808080;  // uint8 -> int8 (minus 128)
-      rs[q] = __builtin_amdgcn_sdot4(v.x, 0x01010101, rs[q], false);
-      rs[q] = __builtin_amdgcn_sdot4(v.y, 0x01010101, rs[q], false);
-      rs[q] = __builtin_amdgcn_sdot4(v.z, 0x01010101, rs[q], false);
-      rs[q] = __builtin_amdgcn_sdot4(v.w, 0x01010101, rs[q], false);
-      *reinterpret_cast<v4i*>(base + a_dst[q]) = v;
-    }
+  for (int ks = 0; ks < 2; ++ks) a_rd[ks] = a_lds_off(wave_m * TM * 32 + l32, ks * 2 + lg);
+  // slot i = l32 -> fragment (i >> 4) of the super-block, nl = i & 15; k-half lg is 256 B further
+  const int b_rd = A_STAGE + ((wave_n * TN) * 2 + (l32 >> 4)) * QG_FRAG_BYTES + (l32 & 15) * 16 + lg * 256;
+  auto fetch = [&](int stage, int ks, v4i (&af)[TM], v4i (&bf)[TN]) {
+    const unsigned char* base = smem + stage * STAGE;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) *reinterpret_cast<v4i*>(base + b_dst[q]) = b_reg[q];
+    for (int mb = 0; mb < TM; ++mb)
+      af[mb] = *reinterpret_cast<const v4i*>(base + a_rd[ks] + mb * (32 * BK));
+#pragma unroll
+    for (int nb = 0; nb < TN; ++nb)
+      bf[nb] = *reinterpret_cast<const v4i*>(base + b_rd + nb * (2 * QG_FRAG_BYTES) + ks * 512);
   };
 
-  v16i acc[2][4];
+  v16i acc[TM][TN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+  unsigned rs[TM];  // sums of raw uint8 bytes, K padding (stored as 0x80) included
+#pragma unroll
+  for (int i = 0; i < TM; ++i) rs[i] = 0;
 
-  // fragment read offsets (constant over the k loop)
-  const int l32 = lane & 31, lg = lane >> 5;
-  int a_frag_row[2];
+  // Row-offset partial sums on the raw uint8 bytes (v_sad_u8 against 0 adds the four bytes of a
+  // dword in one plain VALU op; v_dot4 would contend with the MFMAs for the dot-product pipeline),
+  // then uint8 -> int8 in place (xor 0x80 == minus 128).
+  auto prep = [&](v4i (&af)[TM]) {
 #pragma unroll
-  for (int mb = 0; mb < 2; ++mb) a_frag_row[mb] = wave_m * 64 + mb * 32 + l32;
-  // B fragment: slot i = l32 -> fragment (i >> 4) of the super-block, nl = i & 15
-  int b_frag_base[4];
-#pragma unroll
-  for (int nb = 0; nb < 4; ++nb) {
-    const int nbl = (wave_n * 4 + nb) * 2 + (l32 >> 4);
-    b_frag_base[nb] = A_STAGE_BYTES + nbl * (2 * QG_FRAG_BYTES) + (l32 & 15) * 16;
-  }
-
-  const int KT = p.kb64 >> 1;
-  load_global(0);
-  store_lds(0);
-  __syncthreads();
-
-  for (int kt = 0; kt < KT; ++kt) {
-    const bool more = kt + 1 < KT;
-    if (more) load_global(kt + 1);
-    const unsigned char* base = smem + (kt & 1) * STAGE_BYTES;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      v4i af[2], bf[4];
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-        af[mb] = *reinterpret_cast<const v4i*>(base + a_lds_off(a_frag_row[mb], ks * 2 + lg));
-#pragma unroll
-      for (int nb = 0; nb < 4; ++nb)
-        bf[nb] = *reinterpret_cast<const v4i*>(base + b_frag_base[nb] + (ks >> 1) * QG_FRAG_BYTES +
-                                               (((ks & 1) * 2 + lg) * 16) * 16);
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
-          acc[mb][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf[nb], af[mb], acc[mb][nb], 0, 0, 0);
+    for (int mb = 0; mb < TM; ++mb) {
+      rs[mb] = __builtin_amdgcn_sad_u8(af[mb].x, 0u, rs[mb]);
+      rs[mb] = __builtin_amdgcn_sad_u8(af[mb].y, 0u, rs[mb]);
+      rs[mb] = __builtin_amdgcn_sad_u8(af[mb].z, 0u, rs[mb]);
+      rs[mb] = __builtin_amdgcn_sad_u8(af[mb].w, 0u, rs[mb]);
+      af[mb] = af[mb] ^ (int)0x80808080;
     }
-    if (more) store_lds((kt + 1) & 1);
-    __syncthreads();
+  };
+  auto mma = [&](const v4i (&af)[TM], const v4i (&bf)[TN]) {
+#pragma unroll
+    for (int mb = 0; mb < TM; ++mb)
+#pragma unroll
+      for (int nb = 0; nb < TN; ++nb)
+        acc[mb][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf[nb], af[mb], acc[mb][nb], 0, 0, 0);
+  };
+  // One k-step of 32: request the fragments of the next step, run this step's MFMAs, then row-sum and
+  // shift the fragments that arrived meanwhile.  With one wave per SIMD nothing else hides the LDS
+  // latency, so the instruction stream itself is interleaved: an LDS read behind each of the first
+  // MFMAs, the VALU work (and the tile requests, in the step that issues them) behind the rest.
+  auto interleave = [&](int n_vmem) {
+    constexpr int REST = TM * TN - (TM + TN);
+#pragma unroll
+    for (int i = 0; i < TM + TN; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+    }
+#pragma unroll
+    for (int i = 0; i < REST; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (i < n_vmem) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // tile request
+      __builtin_amdgcn_sched_group_barrier(0x002, (8 * TM + REST - 1) / REST, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  const int KT = (p.K + BK - 1) / BK;  // tiles that hold real data
+  v4i a0[TM], b0[TN], a1[TM], b1[TN];
+  if (FAST) {
+    // Tile kt lives in stage kt % 4.  In iteration kt: the first k-step runs while the fragments of
+    // the second are fetched; then every wave waits until ITS requests for tile kt+1 have landed
+    // (two younger tiles may still be in flight) and until its own reads of tile kt are done, the
+    // workgroup meets at one barrier, stage kt % 4 is handed to the request for tile kt+4, and the
+    // second k-step runs while the first fragments of tile kt+1 are fetched.  The loop is one
+    // hand-scheduled asm statement (gen_tile_loop.py): behind every MFMA sit at most seven other
+    // instructions, so LDS reads, row sums, shifts and tile requests issue in the MFMA's shadow.
+    static_assert(NWM == 2 && NWN == 2 && TM == 4 && TN == 4 && BK == 64 && NSTAGE == 4,
+                  "the scheduled loop is written for this configuration");
+    const unsigned long long av01 = a_voff[0] | ((unsigned long long)a_voff[1] << 32);
+    const unsigned long long av23 = a_voff[2] | ((unsigned long long)a_voff[3] << 32);
+    const unsigned long long bv01 = b_voff[0] | ((unsigned long long)b_voff[1] << 32);
+    const unsigned long long bv23 = b_voff[2] | ((unsigned long long)b_voff[3] << 32);
+    const unsigned long long ard = (unsigned)a_rd[0] | ((unsigned long long)(unsigned)a_rd[1] << 32);
+    const unsigned long long brd = (unsigned)b_rd;
+    const unsigned lds_base = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem);
+    const unsigned lds_dma = lds_base + wave * (A_DMA * 1024);
+    unsigned long long rs01, rs23;
+    asm volatile(QG_TILE_LOOP_ASM
+                 : [c0] "+a"(acc[0][0]), [c1] "+a"(acc[0][1]), [c2] "+a"(acc[0][2]), [c3] "+a"(acc[0][3]),
+                   [c4] "+a"(acc[1][0]), [c5] "+a"(acc[1][1]), [c6] "+a"(acc[1][2]), [c7] "+a"(acc[1][3]),
+                   [c8] "+a"(acc[2][0]), [c9] "+a"(acc[2][1]), [c10] "+a"(acc[2][2]), [c11] "+a"(acc[2][3]),
+                   [c12] "+a"(acc[3][0]), [c13] "+a"(acc[3][1]), [c14] "+a"(acc[3][2]), [c15] "+a"(acc[3][3]),
+                   [rs01] "=v"(rs01), [rs23] "=v"(rs23)
+                 : [av01] "v"(av01), [av23] "v"(av23), [bv01] "v"(bv01), [bv23] "v"(bv23), [ard] "v"(ard),
+                   [brd] "v"(brd), [aptr] "s"(p.A), [bptr] "s"(b_tile0), [kt] "s"(KT), [ldsdma] "s"(lds_dma),
+                   [lds] "s"(lds_base)
+                 : QG_TILE_LOOP_CLOBBERS);
+    rs[0] = (unsigned)rs01;
+    rs[1] = (unsigned)(rs01 >> 32);
+    rs[2] = (unsigned)rs23;
+    rs[3] = (unsigned)(rs23 >> 32);
+  } else {
+    // General path: one stage, no overlap.  A goes through registers byte by byte with bounds checks;
+    // bytes past K are stored as 0x80 (int8 zero after the shift), rows past M repeat the last row.
+    for (int kt = 0; kt < KT; ++kt) {
+      const int k0 = kt * BK;
+      __syncthreads();
+#pragma unroll 1
+      for (int q = 0; q < A_DMA; ++q) {
+        const int r = (wave * A_DMA + q) * 16 + (lane >> 2);
+        const int kc = (lane & 3) ^ ((r >> 1) & 3);
+        const uint8_t* src = p.A + (size_t)min(m0 + r, p.M - 1) * p.lda + kc * 16 + k0;
+        *reinterpret_cast<v4i*>(smem + (wave * A_DMA + q) * 1024 + lane * 16) =
+            load_a_chunk_slow(src, p.K - (k0 + kc * 16));
+      }
+      const int8_t* b_base = b_tile0 + (size_t)kt * QG_FRAG_BYTES;
+#pragma unroll
+      for (int q = 0; q < B_DMA; ++q)
+        *reinterpret_cast<v4i*>(smem + A_STAGE + (wave * B_DMA + q) * 1024 + lane * 16) =
+            *reinterpret_cast<const v4i*>(b_base + b_voff[q]);
+      __syncthreads();
+      fetch(0, 0, a0, b0);
+      fetch(0, 1, a1, b1);
+      prep(a0);
+      prep(a1);
+      mma(a0, b0);
+      mma(a1, b1);
+    }
   }
 
-  // ---- row offsets: the 8 threads that staged one row hold its partial sums
-  int* rowsum_s = reinterpret_cast<int*>(smem + ROWSUM_OFF);
+  // ---- row offsets: lane (m, k-half) holds half of row m's byte sum; every one of the KT*64 bytes
+  // summed (padding reads as 0x80) is 128 above its int8 value
+  int rsum_s[TM];
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    int v = rs[q];
-    v += __shfl_xor(v, 1);
-    v += __shfl_xor(v, 2);
-    v += __shfl_xor(v, 4);
-    if (a_kc == 0) rowsum_s[a_row + 64 * q] = v;
-  }
+  for (int mb = 0; mb < TM; ++mb)
+    rsum_s[mb] = (int)(rs[mb] + (unsigned)__shfl_xor((int)rs[mb], 32)) - 128 * (KT * BK);
+
   // ---- per-column constants of the output pipeline, staged once per workgroup
-  int* cj_s = reinterpret_cast<int*>(smem + EP_CJ_OFF);
-  int* bz_s = reinterpret_cast<int*>(smem + EP_BZ_OFF);
-  float* sc_s = reinterpret_cast<float*>(smem + EP_SC_OFF);
-  if (tid < BN) {
-    const int col = n0 + tid;  // col_off / bzp are padded to N_pad, bias / scales are not
+  __syncthreads();
+  int* cj_s = reinterpret_cast<int*>(smem);
+  int* bz_s = cj_s + BN;
+  float* sc_s = reinterpret_cast<float*>(bz_s + BN);
+  for (int t = tid; t < BN; t += NT) {
+    const int col = n0 + t;  // col_off / bzp are padded to N_pad, bias / scales are not
     const int co = p.col_off[col], bz = p.bzp[col];
     if (MODE == QG_MODE_REQUANT) {
       const int b = (p.bias != nullptr && col < p.N) ? p.bias[col] : 0;
-      cj_s[tid] = b - p.a_zp_m128 * co;
-      sc_s[tid] = (col < p.N) ? p.scales[(size_t)col * p.scale_stride] : 1.0f;
+      cj_s[t] = b - p.a_zp_m128 * co;
+      sc_s[t] = (col < p.N) ? p.scales[(size_t)col * p.scale_stride] : 1.0f;
     } else {
-      cj_s[tid] = 128 * (co + p.K * bz);  // acc_u = acc_s + 128 * colsum
+      cj_s[t] = 128 * (co + p.K * bz);  // acc_u = acc_s + 128 * colsum
     }
-    bz_s[tid] = bz;
+    bz_s[t] = bz;
   }
   __syncthreads();
 
   // ---- epilogue straight from the accumulators
 #pragma unroll
-  for (int mb = 0; mb < 2; ++mb) {
-    const int row_l = wave_m * 64 + mb * 32 + l32;
-    const int row = m0 + row_l;
-    const int rsum = rowsum_s[row_l];
+  for (int mb = 0; mb < TM; ++mb) {
+    const int row = m0 + (wave_m * TM + mb) * 32 + l32;
+    const int rsum = rsum_s[mb];
     if (MODE == QG_MODE_ACC32 && p.rowsum_out != nullptr && tn == 0 && wave_n == 0 && lg == 0 &&
         row < p.M)
       p.rowsum_out[row] = rsum + 128 * p.K;
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb) {
-      const int col_l = wave_n * 128 + nb * 32 + lg * 16;
+    for (int nb = 0; nb < TN; ++nb) {
+      const int col_l = (wave_n * TN + nb) * 32 + lg * 16;
       const int col = n0 + col_l;
       if (row >= p.M || col >= p.N) continue;
       if (MODE == QG_MODE_REQUANT) {
@@ -267,21 +338,26 @@ __global__ __launch_bounds__(NTHREADS) void qg_gemm_tile_kernel(const qg_gemm_ar
   }
 }
 
+template <int MODE, bool FAST, int NWM, int NWN, int TM, int TN>
+hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
+  constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
+  constexpr int SMEM = (FAST ? NSTAGE : 1) * (BM + BN) * BK;
+  const int tiles_m = (a.M + BM - 1) / BM;
+  const int tiles_n = (a.N + BN - 1) / BN;
+  auto fn = qg_gemm_tile_kernel<MODE, FAST, NWM, NWN, TM, TN>;
+  hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(fn, dim3((unsigned)(tiles_m * tiles_n)), dim3(NWM * NWN * 64), SMEM, s, a, tiles_m,
+                     tiles_n);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, hipStream_t s) {
-  const int tiles_m = (a.M + BM - 1) / BM;
-  const int tiles_n = (a.N + BN - 1) / BN;
-  const void* fn = mode == QG_MODE_REQUANT ? (const void*)qg_gemm_tile_kernel<QG_MODE_REQUANT>
-                                           : (const void*)qg_gemm_tile_kernel<QG_MODE_ACC32>;
-  hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
-  if (e != hipSuccess) return e;
-  const dim3 grid((unsigned)(tiles_m * tiles_n)), block(NTHREADS);
+  // a.a_vec: A base and lda are multiples of 16 and every byte offset into A fits 32 bits
+  const bool fast = a.a_vec && (a.K % BK == 0) && (a.K >= NSTAGE * BK);
   if (mode == QG_MODE_REQUANT)
-    hipLaunchKernelGGL(qg_gemm_tile_kernel<QG_MODE_REQUANT>, grid, block, SMEM_BYTES, s, a, tiles_m,
-                       tiles_n);
-  else
-    hipLaunchKernelGGL(qg_gemm_tile_kernel<QG_MODE_ACC32>, grid, block, SMEM_BYTES, s, a, tiles_m,
-                       tiles_n);
-  return hipGetLastError();
+    return fast ? launch<QG_MODE_REQUANT, true, QG_TILE_CFG>(a, s) : launch<QG_MODE_REQUANT, false, QG_TILE_CFG>(a, s);
+  return fast ? launch<QG_MODE_ACC32, true, QG_TILE_CFG>(a, s) : launch<QG_MODE_ACC32, false, QG_TILE_CFG>(a, s);
 }
