@@ -17,14 +17,6 @@
 
 namespace {
 
-__device__ __forceinline__ int requant_one(int x, float sc, float lo, float hi, int czp) {
-  float f = (float)x;
-  float p = f * sc;
-  float r = __builtin_rintf(p);
-  r = __builtin_fminf(__builtin_fmaxf(r, lo), hi);
-  return (int)r + czp;
-}
-
 template <int R, int S>
 __global__ __launch_bounds__(256) void qg_conv_group_kernel(const qg_conv_args p, int ppb) {
   constexpr int RS = R * S;
@@ -79,7 +71,7 @@ __global__ __launch_bounds__(256) void qg_conv_group_kernel(const qg_conv_args p
 #pragma unroll
     for (int co = 0; co < 4; ++co) {
       const int x = acc[co] + cj[co] - bz[co] * rsum;
-      out |= (unsigned)requant_one(x, sc[co], p.clamp_lo, p.clamp_hi, p.c_zp) << (8 * co);
+      out |= (unsigned)qg_requant_one(x, sc[co], p.clamp_lo, p.clamp_hi, p.c_zp) << (8 * co);
     }
     *reinterpret_cast<unsigned*>(p.out + (size_t)px * p.Cout + 4 * g) = out;
   }

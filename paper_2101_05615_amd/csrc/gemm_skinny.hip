@@ -29,14 +29,6 @@ __device__ __forceinline__ v4i load_a_chunk_slow(const uint8_t* p, int kvalid) {
   return u.v;
 }
 
-__device__ __forceinline__ int requant_one(int x, float sc, float lo, float hi, int czp) {
-  float f = (float)x;
-  float p = f * sc;
-  float r = __builtin_rintf(p);
-  r = __builtin_fminf(__builtin_fmaxf(r, lo), hi);
-  return (int)r + czp;
-}
-
 template <int MODE, int MB>
 __global__ __launch_bounds__(NTHREADS) void qg_gemm_skinny_kernel(const qg_gemm_args p) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -132,7 +124,7 @@ __global__ __launch_bounds__(NTHREADS) void qg_gemm_skinny_kernel(const qg_gemm_
       const int b = (p.bias != nullptr && col < p.N) ? p.bias[col] : 0;
       const float sc = (col < p.N) ? p.scales[(size_t)col * p.scale_stride] : 1.0f;
       const int x = sum[r] + b - p.a_zp_m128 * co - bz * rsum;
-      out |= (unsigned)requant_one(x, sc, p.clamp_lo, p.clamp_hi, p.c_zp) << (8 * r);
+      out |= (unsigned)qg_requant_one(x, sc, p.clamp_lo, p.clamp_hi, p.c_zp) << (8 * r);
     }
     uint8_t* dst = p.C + (size_t)row * p.ldc + c0;
     if (p.c_vec && c0 + 4 <= p.N) {

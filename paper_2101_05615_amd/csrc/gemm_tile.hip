@@ -52,14 +52,6 @@ __device__ __forceinline__ v4i load_a_chunk_slow(const uint8_t* p, int kvalid) {
   return u.v;
 }
 
-__device__ __forceinline__ int requant_one(int x, float sc, float lo, float hi, int czp) {
-  float f = (float)x;                 // v_cvt_f32_i32, round to nearest even
-  float p = f * sc;                   // one fp32 multiply
-  float r = __builtin_rintf(p);       // v_rndne_f32
-  r = __builtin_fminf(__builtin_fmaxf(r, lo), hi);
-  return (int)r + czp;
-}
-
 // 16 bytes per lane from global memory into LDS at lds_base + lane*16 (lds_base wave-uniform)
 __device__ __forceinline__ void dma16(const void* gptr, unsigned char* lds_base) {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
@@ -286,49 +278,66 @@ __global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_g
     } else {
       cj_s[t] = 128 * (co + p.K * bz);  // acc_u = acc_s + 128 * colsum
     }
-    bz_s[t] = bz;
+    bz_s[t] = -bz;  // negated: x = acc + cj + (-theta_B) * rowsum
   }
   __syncthreads();
 
-  // ---- epilogue straight from the accumulators
-#pragma unroll
-  for (int mb = 0; mb < TM; ++mb) {
-    const int row = m0 + (wave_m * TM + mb) * 32 + l32;
-    const int rsum = rsum_s[mb];
-    if (MODE == QG_MODE_ACC32 && p.rowsum_out != nullptr && tn == 0 && wave_n == 0 && lg == 0 &&
-        row < p.M)
-      p.rowsum_out[row] = rsum + 128 * p.K;
+  // ---- epilogue straight from the accumulators.  Lane (l32, lg) of block (mb, nb) holds row
+  // 32*mb + l32 and the 16 consecutive columns 32*nb + 16*lg .. +15; the per-column constants of a
+  // column block are fetched once and reused for the wave's TM row blocks.
+  if (MODE == QG_MODE_REQUANT) {
+    const bool full_cols = p.c_vec && (n0 + BN <= p.N);  // uniform: every 16-byte store is in range
 #pragma unroll
     for (int nb = 0; nb < TN; ++nb) {
       const int col_l = (wave_n * TN + nb) * 32 + lg * 16;
       const int col = n0 + col_l;
-      if (row >= p.M || col >= p.N) continue;
-      if (MODE == QG_MODE_REQUANT) {
+      int cj[16], nbz[16];
+      float sc[16];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        *reinterpret_cast<v4i*>(&cj[4 * q]) = *reinterpret_cast<const v4i*>(&cj_s[col_l + 4 * q]);
+        *reinterpret_cast<v4i*>(&nbz[4 * q]) = *reinterpret_cast<const v4i*>(&bz_s[col_l + 4 * q]);
+        *reinterpret_cast<float4*>(&sc[4 * q]) = *reinterpret_cast<const float4*>(&sc_s[col_l + 4 * q]);
+      }
+#pragma unroll
+      for (int mb = 0; mb < TM; ++mb) {
+        const int row = m0 + (wave_m * TM + mb) * 32 + l32;
+        const int rsum = rsum_s[mb];
         unsigned out[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const v4i cj = *reinterpret_cast<const v4i*>(&cj_s[col_l + 4 * q]);
-          const v4i bz = *reinterpret_cast<const v4i*>(&bz_s[col_l + 4 * q]);
-          const float4 sc = *reinterpret_cast<const float4*>(&sc_s[col_l + 4 * q]);
-          const int x0 = acc[mb][nb][4 * q + 0] + cj.x - bz.x * rsum;
-          const int x1 = acc[mb][nb][4 * q + 1] + cj.y - bz.y * rsum;
-          const int x2 = acc[mb][nb][4 * q + 2] + cj.z - bz.z * rsum;
-          const int x3 = acc[mb][nb][4 * q + 3] + cj.w - bz.w * rsum;
-          const unsigned q0 = (unsigned)requant_one(x0, sc.x, p.clamp_lo, p.clamp_hi, p.c_zp);
-          const unsigned q1 = (unsigned)requant_one(x1, sc.y, p.clamp_lo, p.clamp_hi, p.c_zp);
-          const unsigned q2 = (unsigned)requant_one(x2, sc.z, p.clamp_lo, p.clamp_hi, p.c_zp);
-          const unsigned q3 = (unsigned)requant_one(x3, sc.w, p.clamp_lo, p.clamp_hi, p.c_zp);
-          out[q] = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
-        }
-        uint8_t* dst = p.C + (size_t)row * p.ldc + col;
-        if (p.c_vec && col + 16 <= p.N) {
-          *reinterpret_cast<uint4*>(dst) = make_uint4(out[0], out[1], out[2], out[3]);
-        } else {
+          unsigned w = 0;
 #pragma unroll
-          for (int i = 0; i < 16; ++i)
-            if (col + i < p.N) dst[i] = (uint8_t)(out[i >> 2] >> ((i & 3) * 8));
+          for (int t = 0; t < 4; ++t) {
+            const int i = 4 * q + t;
+            const int x = acc[mb][nb][i] + cj[i] + __mul24(nbz[i], rsum);
+            w |= (unsigned)qg_requant_one(x, sc[i], p.clamp_lo, p.clamp_hi, p.c_zp) << (8 * t);
+          }
+          out[q] = w;
         }
-      } else {
+        if (row < p.M) {
+          uint8_t* dst = p.C + (size_t)row * p.ldc + col;
+          if (full_cols) {
+            *reinterpret_cast<uint4*>(dst) = make_uint4(out[0], out[1], out[2], out[3]);
+          } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+              if (col + i < p.N) dst[i] = (uint8_t)(out[i >> 2] >> ((i & 3) * 8));
+          }
+        }
+      }
+    }
+  } else {
+#pragma unroll
+    for (int mb = 0; mb < TM; ++mb) {
+      const int row = m0 + (wave_m * TM + mb) * 32 + l32;
+      if (row >= p.M) continue;
+      if (p.rowsum_out != nullptr && tn == 0 && wave_n == 0 && lg == 0)
+        p.rowsum_out[row] = rsum_s[mb] + 128 * p.K;
+#pragma unroll
+      for (int nb = 0; nb < TN; ++nb) {
+        const int col_l = (wave_n * TN + nb) * 32 + lg * 16;
+        const int col = n0 + col_l;
         int32_t* dst = p.C32 + (size_t)row * p.ldc + col;
 #pragma unroll
         for (int i = 0; i < 16; ++i)

@@ -23,6 +23,8 @@ av01 av23 bv01 bv23 ard brd, SGPR inputs aptr bptr kt ldsdma lds, 64-bit VGPR ou
 """
 import os
 
+ABL = set(filter(None, os.environ.get("QG_GEN_ABL", "").split(",")))
+
 A = [160, 192]
 B = [176, 208]
 RS, AV, BV, ARD0, ARD1, BRD, VA, VB = 224, 228, 232, 236, 237, 238, 240, 241
@@ -48,6 +50,8 @@ class Emit:
 
 def dma(e, q):
     """one tile request: q = 0..3 A, 4..7 B; m0 = request stage base + slot"""
+    if "nodma" in ABL:
+        return
     if q < 4:
         e(f"s_add_u32 m0, s96, {q * 1024}")
         e("s_nop 0")
@@ -67,12 +71,16 @@ def advance_request_pointers(e):
 
 def mfma(e, i, use):
     mb, nb = i // 4, i % 4
+    if "nomfma" in ABL:
+        return
     e(f"v_mfma_i32_32x32x32_i8 %[c{i}], {vr(B[use] + 4 * nb)}, {vr(A[use] + 4 * mb)}, %[c{i}]")
 
 
 def reads(e, slot, ld, ks):
     """the two LDS reads of slot 0..3: A fragments first (they are needed first), then B"""
     for j in (2 * slot, 2 * slot + 1):
+        if "nolds" in ABL:
+            continue
         if j < 4:
             e(f"ds_read_b128 {vr(A[ld] + 4 * j)}, v{VA} offset:{j * 2048}")
         else:
@@ -83,6 +91,8 @@ def reads(e, slot, ld, ks):
 def prep(e, slot, ld):
     """slots 8..15: fragment f = (slot-8)//2; even slot: byte sums, odd slot: xor"""
     f, odd = (slot - 8) // 2, (slot - 8) % 2
+    if "novalu" in ABL:
+        return
     base = A[ld] + 4 * f
     if not odd:
         e(f"s_waitcnt lgkmcnt({7 - f})")
@@ -133,7 +143,8 @@ def tile(e, wait_vm, request, last=False):
         return
     # every wave: its requests for tile t+1 have landed, its reads of tile t are done
     e(f"s_waitcnt vmcnt({wait_vm}) lgkmcnt(0)")
-    e("s_barrier")
+    if "nobar" not in ABL:
+        e("s_barrier")
     if request:
         e("s_lshl_b32 s94, s93, 15")
         e("s_add_u32 s96, s91, s94")
@@ -218,6 +229,6 @@ def generate():
 
 if __name__ == "__main__":
     here = os.path.dirname(os.path.abspath(__file__))
-    with open(os.path.join(here, "tile_loop_asm.inc"), "w") as f:
+    with open(os.environ.get("QG_GEN_OUT", os.path.join(here, "tile_loop_asm.inc")), "w") as f:
         f.write(generate())
     print("wrote tile_loop_asm.inc")

@@ -100,6 +100,19 @@ struct qg_conv_args {
   int has_bzp;
 };
 
+#ifdef __HIPCC__
+// Requantization of one corrected int32 accumulator, the fixed fp32 sequence of the output pipeline
+// (paper Sec. 2.1, requantization remark): int32 -> fp32 (round to nearest even), ONE fp32 multiply,
+// round to nearest even, clamp in float (so the conversion back can never be out of range), add theta_C.
+__device__ __forceinline__ int qg_requant_one(int x, float sc, float lo, float hi, int czp) {
+  const float f = (float)x;                          // v_cvt_f32_i32
+  const float p = f * sc;                            // v_mul_f32
+  const float r = __builtin_rintf(p);                // v_rndne_f32
+  const float c = __builtin_amdgcn_fmed3f(r, lo, hi);  // lo <= hi, r is never NaN for finite scales
+  return (int)c + czp;
+}
+#endif
+
 // launchers (each returns a hipError_t from hipGetLastError after the launch)
 hipError_t qg_launch_pack_b(const int8_t* B, int K, int N, int ldb, int K_pad, int N_pad,
                             int8_t* packed, int32_t* col_off, const int32_t* bzp_dev, hipStream_t s);
