@@ -61,6 +61,43 @@ def traffic_from_profiles(kernel_key):
     return None
 
 
+def pmc_target(which, torch, q, wl, dev):
+    """A handful of launches of one kernel, nothing else on the device: counter runs stay short."""
+    n = 3
+    if which == "copy":
+        src = torch.full((256 << 20,), 7, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(n):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_target": "copy", "bytes_read": src.numel(), "bytes_written": dst.numel(), "launches": n}))
+        return
+    if which == "c5":
+        c = wl.config5_group_conv()
+        inp, wgt = torch.from_numpy(c.inp).to(dev), torch.from_numpy(c.wgt).to(dev)
+        Wp = q.pack_conv_w(wgt, c.b_zp)
+        sc = torch.from_numpy(c.scales).to(dev)
+        out = torch.empty_like(inp)
+        torch.cuda.synchronize()
+        for _ in range(n):
+            q.conv_groupwise_u8s8_requant(inp, Wp, c.a_zp, None, sc, c.c_zp, c.relu, 1, 1, out=out)
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_target": which, "workload": c.name, "launches": n}))
+        return
+    c = {"c2": wl.config2_small_batch_fc, "c3": wl.config3_square, "c4": wl.config4_recsys_mlp}[which]()
+    A, B = torch.from_numpy(c.A).to(dev), torch.from_numpy(c.B).to(dev)
+    Bp = q.pack_b(B, c.b_zp)
+    bias = None if c.bias is None else torch.from_numpy(c.bias).to(dev)
+    sc = torch.from_numpy(c.scales).to(dev)
+    C = torch.empty((c.M, c.N), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    for _ in range(n):
+        q.gemm_u8s8_requant(A, c.a_zp, Bp, bias, sc, c.c_zp, c.relu, out=C)
+    torch.cuda.synchronize()
+    print(json.dumps({"pmc_target": which, "workload": c.name, "launches": n}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -68,6 +105,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", default="", help="comma list of c1..c5 to restrict the side configs")
+    ap.add_argument("--pmc-target", default="", choices=["", "c2", "c3", "c4", "c5", "copy"],
+                    help="run ONLY a few launches of one workload (or of a plain 256 MiB device copy, the "
+                         "calibration kernel for FETCH_SIZE / WRITE_SIZE) and exit: for rocprofv3 --pmc runs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path shards over M or N with no collective; "
@@ -86,6 +126,8 @@ def main():
     torch.cuda.set_device(dev)
     only = set(args.only.split(",")) if args.only else None
     side = []
+    if args.pmc_target:
+        return pmc_target(args.pmc_target, torch, q, wl, dev)
 
     def up(x):
         return None if x is None else torch.from_numpy(x).to(dev)
