@@ -95,6 +95,7 @@ int qg_pack_b(const int8_t* B_dev, int K, int N, int ldb, const int32_t* b_zp_ho
   h->col_off = col_offsets_dev;
   h->bzp = col_offsets_dev + N_pad;
   h->G = h->R = h->S = h->Cg = h->Og = 0;
+  h->conv_frags = nullptr;
 
   int rc = upload_bzp(b_zp_host, n_b_zp, N, N_pad, col_offsets_dev + N_pad, s, &h->has_bzp);
   if (rc != QG_OK) {
@@ -194,7 +195,9 @@ int qg_pack_conv_w_sizes(int G, int R, int S, int Cg, int Og, size_t* packed_byt
   if (!packed_bytes || !col_offsets_bytes) return QG_ENULL;
   if (G <= 0 || R <= 0 || S <= 0 || Cg <= 0 || Og <= 0) return QG_EINVAL;
   if (Cg != 4 || Og != 4 || !((R == 1 && S == 1) || (R == 3 && S == 3)) || G > 256) return QG_EUNSUPPORTED;
-  *packed_bytes = (size_t)qg_round_up(G * R * S * Cg * Og, 256);
+  // dot4 layout, then (when C = 4 G is a multiple of 32) the matrix-core fragments
+  *packed_bytes = (size_t)qg_round_up(G * R * S * Cg * Og, 256) +
+                  ((G % 8 == 0) ? (size_t)(G / 8) * R * S * QG_FRAG_BYTES : 0);
   *col_offsets_bytes = (size_t)qg_round_up(2 * G * Og * (int)sizeof(int32_t), 256);
   return QG_OK;
 }
@@ -227,13 +230,15 @@ int qg_pack_conv_w(const int8_t* W_dev, int G, int R, int S, int Cg, int Og, con
   h->S = S;
   h->Cg = Cg;
   h->Og = Og;
+  int8_t* frags = (G % 8 == 0) ? static_cast<int8_t*>(packed_dev) + qg_round_up(G * R * S * Cg * Og, 256) : nullptr;
+  h->conv_frags = frags;
   rc = upload_bzp(b_zp_host, n_b_zp, Cout, Cout, col_offsets_dev + Cout, s, &h->has_bzp);
   if (rc != QG_OK) {
     delete h;
     return rc;
   }
   if (qg_launch_pack_conv_w(W_dev, G, R * S, static_cast<int8_t*>(packed_dev), col_offsets_dev,
-                            col_offsets_dev + Cout, s) != hipSuccess) {
+                            col_offsets_dev + Cout, frags, s) != hipSuccess) {
     delete h;
     return QG_ELAUNCH;
   }
@@ -254,9 +259,11 @@ int qg_conv_groupwise_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W,
   const int Wo = (W + 2 * pad - Wp->S) / stride + 1;
   if (H + 2 * pad < Wp->R || W + 2 * pad < Wp->S || Ho <= 0 || Wo <= 0) return QG_EINVAL;
   if (!aligned(in_nhwc, 4) || !aligned(out_nhwc, 4)) return QG_EALIGN;
+  if ((uint64_t)Nb * H * W * C >= (1ull << 31) || (uint64_t)Nb * Ho * Wo * Wp->N >= (1ull << 31)) return QG_EUNSUPPORTED;
   qg_conv_args a = {};
   a.in = in_nhwc;
   a.Wp = Wp->packed;
+  a.Wfrag = Wp->conv_frags;
   a.col_off = Wp->col_off;
   a.bzp = Wp->bzp;
   a.bias = p->bias;

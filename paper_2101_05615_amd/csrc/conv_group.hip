@@ -5,17 +5,273 @@
 // arithmetic is the same Eq. (2) + requantization pipeline as the GEMM, with
 // out-of-image taps carrying theta_A (real zero).
 //
-// With 4 channels per group one tap of one group is exactly one dword, i.e. one
-// v_dot4_i32_i8 operand, and a 36 x 4 weight block fits in 36 registers.  The
-// shape is HBM-bound (36 op/byte), so the matrix cores are not needed to reach
-// the memory roofline; the work per pixel is 36 dot4 + the output pipeline.
-//
-// Thread = (pixel, group): the 32 groups of a pixel are 32 adjacent lanes reading
-// one contiguous 128-byte pixel; every thread keeps its group's weights and
-// per-channel constants in registers and walks over pixels grid-stride.
+// Two kernels:
+//  * matrix-core kernel (C a multiple of 32).  For one tap, 32 adjacent channels (8 groups) of 32 pixels
+//    against the 32 matching output channels is a 32 x 32 x 32 product whose weight matrix is block
+//    diagonal (8 blocks of 4 x 4): one v_mfma_i32_32x32x32_i8 per tap, 9 per 3x3 filter.  7/8 of the MACs
+//    multiply zeros, but the shape is HBM-bound (36 op/byte) and the MFMA time stays far below the
+//    memory time, while the VALU is left to the output pipeline.  The activation operand is simply the 16
+//    contiguous channel bytes of a pixel per lane -- NHWC needs no gather -- and the column permutation
+//    of the packed weights leaves each lane with 16 consecutive output channels (one 16-byte store).
+//  * dot4 kernel (any C = 4 G): thread = (pixel, group), one tap of one group is one dword = one
+//    v_dot4_i32_i8 operand, the 36 x 4 weight block lives in 36 registers.
 #include "qg_internal.h"
 
 namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+// NCB 32-channel blocks per wave pass; the workgroup (4 waves) shares their weights in LDS and each wave
+// walks over blocks of 32 consecutive output pixels.
+template <int R, int S, int NCB, bool HAS_BZP>
+__global__ __launch_bounds__(256, HAS_BZP ? 2 : 4) void qg_conv_group_mfma_kernel(const qg_conv_args p) {
+  constexpr int RS = R * S;
+  constexpr int NCH = NCB * 32;
+  extern __shared__ __align__(16) unsigned char smem[];  // [cb][tap] 1 KiB fragments, then constants
+  int* cj_s = reinterpret_cast<int*>(smem + NCB * RS * QG_FRAG_BYTES);
+  int* nbz_s = cj_s + NCH;
+  float* sc_s = reinterpret_cast<float*>(nbz_s + NCH);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ch0 = blockIdx.y * NCH;  // first channel (input and output) of this workgroup
+
+  // ---- weights of this channel group and per-channel constants into LDS, once per workgroup
+  {
+    const int8_t* src = p.Wfrag + (size_t)blockIdx.y * NCB * RS * QG_FRAG_BYTES;
+    for (int c = tid; c < NCB * RS * 64; c += 256)
+      *reinterpret_cast<v4i*>(smem + c * 16) = *reinterpret_cast<const v4i*>(src + (size_t)c * 16);
+    for (int c = tid; c < NCH; c += 256) {
+      const int oc = ch0 + c;
+      cj_s[c] = (p.bias ? p.bias[oc] : 0) - (p.a_zp - 128) * p.col_off[oc];
+      nbz_s[c] = -p.bzp[oc];
+      sc_s[c] = p.scales[(size_t)oc * p.scale_stride];
+    }
+  }
+  __syncthreads();
+
+  const int pl = lane & 31, g = lane >> 5;  // pixel inside the block, channel half (k half of the MFMA)
+  const int npix = p.Nb * p.Ho * p.Wo;
+  const int nblk = (npix + 31) / 32;
+  const unsigned azp_word = (unsigned)p.a_zp * 0x01010101u;
+
+  for (int blk = blockIdx.x * 4 + wave; blk < nblk; blk += gridDim.x * 4) {
+    const int px = blk * 32 + pl;
+    const int pxc = min(px, npix - 1);  // lanes past the end recompute the last pixel; never stored
+    const int wo = pxc % p.Wo;
+    const int t1 = pxc / p.Wo;
+    const int ho = t1 % p.Ho;
+    const int n = t1 / p.Ho;
+
+    v16i acc[NCB];
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[cb][r] = 0;
+    unsigned rs[NCB][4];  // byte sums per (block, group inside this lane's 16 channels)
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) rs[cb][j] = 0;
+
+    // taps one at a time, the next tap's 16-byte loads in flight while this tap's MFMAs run; the
+    // scheduling barriers stop the compiler from hoisting all R*S*NCB loads (and their registers) up front
+    v4i xn[NCB];
+    unsigned keep_n, flip_n;
+    auto issue = [&](int tap) {
+      const int kh = tap / S, kw = tap % S;
+      const int hi = ho * p.stride + kh - p.pad, wi = wo * p.stride + kw - p.pad;
+      const bool ok = hi >= 0 && hi < p.H && wi >= 0 && wi < p.W;
+      const int hc = min(max(hi, 0), p.H - 1), wc = min(max(wi, 0), p.W - 1);
+      const uint8_t* src = p.in + ((size_t)(n * p.H + hc) * p.W + wc) * p.C + ch0 + 16 * g;
+      keep_n = ok ? 0xFFFFFFFFu : 0u;
+      // in-image: x ^ 0x80 (uint8 -> int8); out of image: theta_A - 128 in every byte
+      flip_n = ok ? 0x80808080u : (azp_word ^ 0x80808080u);
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) xn[cb] = *reinterpret_cast<const v4i*>(src + cb * 32);
+    };
+    issue(0);
+#pragma unroll
+    for (int tap = 0; tap < RS; ++tap) {
+      v4i x[NCB];
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) x[cb] = xn[cb];
+      const unsigned keep = keep_n, flip = flip_n;
+      __builtin_amdgcn_sched_barrier(0);
+      if (tap + 1 < RS) issue(tap + 1);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) {
+        if (HAS_BZP) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const unsigned y = ((unsigned)x[cb][j] & keep) | (azp_word & ~keep);  // uint8 value of the tap
+            rs[cb][j] = __builtin_amdgcn_sad_u8(y, 0u, rs[cb][j]);
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) x[cb][j] = (int)(((unsigned)x[cb][j] & keep) ^ flip);
+        const v4i wf = *reinterpret_cast<const v4i*>(smem + (cb * RS + tap) * QG_FRAG_BYTES + lane * 16);
+        acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, x[cb], acc[cb], 0, 0, 0);
+      }
+    }
+
+    // ---- output pipeline: lane (pixel pl, half g) holds channels 32 cb + 16 g .. + 15 of its pixel
+    if (px < npix) {
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) {
+        const int c_l = cb * 32 + 16 * g;
+        unsigned out[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const v4i cj = *reinterpret_cast<const v4i*>(&cj_s[c_l + 4 * q]);
+          const v4i nbz = *reinterpret_cast<const v4i*>(&nbz_s[c_l + 4 * q]);
+          const float4 sc = *reinterpret_cast<const float4*>(&sc_s[c_l + 4 * q]);
+          // row offset of group q of this half, in the int8 domain: every one of the RS*4 bytes is 128 high
+          const int rsum = HAS_BZP ? (int)rs[cb][q] - 128 * RS * 4 : 0;
+          const int x0 = acc[cb][4 * q + 0] + cj.x + (HAS_BZP ? __mul24(nbz.x, rsum) : 0);
+          const int x1 = acc[cb][4 * q + 1] + cj.y + (HAS_BZP ? __mul24(nbz.y, rsum) : 0);
+          const int x2 = acc[cb][4 * q + 2] + cj.z + (HAS_BZP ? __mul24(nbz.z, rsum) : 0);
+          const int x3 = acc[cb][4 * q + 3] + cj.w + (HAS_BZP ? __mul24(nbz.w, rsum) : 0);
+          out[q] = (unsigned)qg_requant_one(x0, sc.x, p.clamp_lo, p.clamp_hi, p.c_zp) |
+                   ((unsigned)qg_requant_one(x1, sc.y, p.clamp_lo, p.clamp_hi, p.c_zp) << 8) |
+                   ((unsigned)qg_requant_one(x2, sc.z, p.clamp_lo, p.clamp_hi, p.c_zp) << 16) |
+                   ((unsigned)qg_requant_one(x3, sc.w, p.clamp_lo, p.clamp_hi, p.c_zp) << 24);
+        }
+        *reinterpret_cast<uint4*>(p.out + (size_t)px * p.Cout + ch0 + c_l) =
+            make_uint4(out[0], out[1], out[2], out[3]);
+      }
+    }
+  }
+}
+
+// 16 bytes per lane from global memory into LDS at lds_base + lane*16 (lds_base wave-uniform)
+__device__ __forceinline__ void dma16(const void* gptr, unsigned char* lds_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
+                                   (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
+}
+
+// "Same" convolution (stride 1, 2*pad == R-1 == S-1): the input pixel of tap (kh, kw) of output pixel q
+// is pixel q + (kh-pad)*W + (kw-pad) of the same linear NHWC pixel sequence.  A workgroup owns 128
+// consecutive output pixels of one group of NCB*32 channels; it requests its whole input patch (the 128
+// pixels plus pad*W+pad on either side) and its weights with global_load_lds in one burst -- one memory
+// latency per workgroup -- and every tap then comes from LDS.  Pixel p's 16-byte channel chunks are
+// stored xor (p & 7) so that the 32 consecutive pixels a half-wave reads hit different banks.
+template <int R, int S, int NCB, bool HAS_BZP>
+__global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel(const qg_conv_args p, int halo,
+                                                                                 int nchunks_pad) {
+  constexpr int RS = R * S;
+  constexpr int NCH = NCB * 32;
+  constexpr int CP = NCH / 16;       // 16-byte chunks per pixel
+  constexpr int SW = (CP - 1) & 7;   // swizzle mask
+  constexpr int PAD_H = (R - 1) / 2, PAD_W = (S - 1) / 2;
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned char* w_s = smem;                                        // [cb][tap] fragments
+  int* cj_s = reinterpret_cast<int*>(smem + NCB * RS * QG_FRAG_BYTES);
+  int* nbz_s = cj_s + NCH;
+  float* sc_s = reinterpret_cast<float*>(nbz_s + NCH);
+  unsigned char* patch = smem + NCB * RS * QG_FRAG_BYTES + NCH * 12;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int ch0 = blockIdx.y * NCH;
+  const int q0 = blockIdx.x * 128;  // first output pixel of the workgroup
+  const int npix = p.Nb * p.H * p.W;
+  const int lin0 = q0 - halo;       // linear index of patch pixel 0 (may be negative; clamped per chunk)
+
+  // ---- one burst of requests: weights, then the input patch
+  {
+    const int8_t* wsrc = p.Wfrag + (size_t)blockIdx.y * NCB * RS * QG_FRAG_BYTES + lane * 16;
+    for (int f = wave; f < NCB * RS; f += 4) dma16(wsrc + (size_t)f * QG_FRAG_BYTES, w_s + f * QG_FRAG_BYTES);
+    for (int c0 = wave * 64; c0 < nchunks_pad; c0 += 256) {
+      const int c = c0 + lane;
+      const int pp = c / CP, phys = c % CP;
+      const int lin = min(max(lin0 + pp, 0), npix - 1);
+      dma16(p.in + (size_t)lin * p.C + ch0 + ((phys ^ (pp & SW)) << 4), patch + c0 * 16);
+    }
+    for (int c = tid; c < NCH; c += 256) {
+      const int oc = ch0 + c;
+      cj_s[c] = (p.bias ? p.bias[oc] : 0) - (p.a_zp - 128) * p.col_off[oc];
+      nbz_s[c] = -p.bzp[oc];
+      sc_s[c] = p.scales[(size_t)oc * p.scale_stride];
+    }
+  }
+  __syncthreads();  // includes the wait for every outstanding request of this wave
+
+  const int pl = lane & 31, g = lane >> 5;
+  const int px = q0 + wave * 32 + pl;
+  const int pxc = min(px, npix - 1);
+  const int wo = pxc % p.W;
+  const int ho = (pxc / p.W) % p.H;
+  const unsigned azp_word = (unsigned)p.a_zp * 0x01010101u;
+  const int pp_c = wave * 32 + pl + halo;  // patch index of this lane's centre pixel
+
+  v16i acc[NCB];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[cb][r] = 0;
+  unsigned rs[NCB][4];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) rs[cb][j] = 0;
+
+#pragma unroll
+  for (int kh = 0; kh < R; ++kh) {
+#pragma unroll
+    for (int kw = 0; kw < S; ++kw) {
+      const int hi = ho + kh - PAD_H, wi = wo + kw - PAD_W;
+      const bool ok = hi >= 0 && hi < p.H && wi >= 0 && wi < p.W;
+      const int pp = pp_c + (kh - PAD_H) * p.W + (kw - PAD_W);
+      const unsigned keep = ok ? 0xFFFFFFFFu : 0u;
+      // in-image: x ^ 0x80 (uint8 -> int8); out of image: theta_A - 128 in every byte
+      const unsigned flip = ok ? 0x80808080u : (azp_word ^ 0x80808080u);
+      const unsigned char* src = patch + pp * NCH;
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) {
+        v4i x = *reinterpret_cast<const v4i*>(src + (((cb * 2 + g) ^ (pp & SW)) << 4));
+        if (HAS_BZP) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const unsigned y = ((unsigned)x[j] & keep) | (azp_word & ~keep);  // uint8 value of the tap
+            rs[cb][j] = __builtin_amdgcn_sad_u8(y, 0u, rs[cb][j]);
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) x[j] = (int)(((unsigned)x[j] & keep) ^ flip);
+        const v4i wf = *reinterpret_cast<const v4i*>(w_s + (cb * RS + kh * S + kw) * QG_FRAG_BYTES + lane * 16);
+        acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, x, acc[cb], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- output pipeline: lane (pixel pl, half g) holds channels 32 cb + 16 g .. + 15 of its pixel
+  if (px < npix) {
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+      const int c_l = cb * 32 + 16 * g;
+      unsigned out[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const v4i cj = *reinterpret_cast<const v4i*>(&cj_s[c_l + 4 * q]);
+        const v4i nbz = *reinterpret_cast<const v4i*>(&nbz_s[c_l + 4 * q]);
+        const float4 sc = *reinterpret_cast<const float4*>(&sc_s[c_l + 4 * q]);
+        const int rsum = HAS_BZP ? (int)rs[cb][q] - 128 * RS * 4 : 0;
+        const int x0 = acc[cb][4 * q + 0] + cj.x + (HAS_BZP ? __mul24(nbz.x, rsum) : 0);
+        const int x1 = acc[cb][4 * q + 1] + cj.y + (HAS_BZP ? __mul24(nbz.y, rsum) : 0);
+        const int x2 = acc[cb][4 * q + 2] + cj.z + (HAS_BZP ? __mul24(nbz.z, rsum) : 0);
+        const int x3 = acc[cb][4 * q + 3] + cj.w + (HAS_BZP ? __mul24(nbz.w, rsum) : 0);
+        out[q] = (unsigned)qg_requant_one(x0, sc.x, p.clamp_lo, p.clamp_hi, p.c_zp) |
+                 ((unsigned)qg_requant_one(x1, sc.y, p.clamp_lo, p.clamp_hi, p.c_zp) << 8) |
+                 ((unsigned)qg_requant_one(x2, sc.z, p.clamp_lo, p.clamp_hi, p.c_zp) << 16) |
+                 ((unsigned)qg_requant_one(x3, sc.w, p.clamp_lo, p.clamp_hi, p.c_zp) << 24);
+      }
+      *reinterpret_cast<uint4*>(p.out + (size_t)px * p.Cout + ch0 + c_l) =
+          make_uint4(out[0], out[1], out[2], out[3]);
+    }
+  }
+}
 
 template <int R, int S>
 __global__ __launch_bounds__(256) void qg_conv_group_kernel(const qg_conv_args p, int ppb) {
@@ -79,7 +335,64 @@ __global__ __launch_bounds__(256) void qg_conv_group_kernel(const qg_conv_args p
 
 }  // namespace
 
+template <int R, int S, int NCB>
+hipError_t launch_mfma(const qg_conv_args& a, hipStream_t s) {
+  constexpr int RS = R * S;
+  const int smem = NCB * RS * QG_FRAG_BYTES + NCB * 32 * 12;
+  const int nblk = (a.Nb * a.Ho * a.Wo + 31) / 32;
+  const dim3 grid((unsigned)min((nblk + 3) / 4, 2048), (unsigned)(a.C / (NCB * 32)));
+  if (a.has_bzp) {
+    hipFuncSetAttribute((const void*)qg_conv_group_mfma_kernel<R, S, NCB, true>,
+                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    hipLaunchKernelGGL((qg_conv_group_mfma_kernel<R, S, NCB, true>), grid, dim3(256), smem, s, a);
+  } else {
+    hipFuncSetAttribute((const void*)qg_conv_group_mfma_kernel<R, S, NCB, false>,
+                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    hipLaunchKernelGGL((qg_conv_group_mfma_kernel<R, S, NCB, false>), grid, dim3(256), smem, s, a);
+  }
+  return hipGetLastError();
+}
+
+template <int R, int S, int NCB>
+hipError_t launch_same(const qg_conv_args& a, int smem, int halo, int nchunks_pad, hipStream_t s) {
+  const int npix = a.Nb * a.H * a.W;
+  const dim3 grid((unsigned)((npix + 127) / 128), (unsigned)(a.C / (NCB * 32)));
+  if (a.has_bzp) {
+    hipFuncSetAttribute((const void*)qg_conv_same_mfma_kernel<R, S, NCB, true>,
+                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    hipLaunchKernelGGL((qg_conv_same_mfma_kernel<R, S, NCB, true>), grid, dim3(256), smem, s, a, halo, nchunks_pad);
+  } else {
+    hipFuncSetAttribute((const void*)qg_conv_same_mfma_kernel<R, S, NCB, false>,
+                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    hipLaunchKernelGGL((qg_conv_same_mfma_kernel<R, S, NCB, false>), grid, dim3(256), smem, s, a, halo, nchunks_pad);
+  }
+  return hipGetLastError();
+}
+
 hipError_t qg_launch_conv_group(const qg_conv_args& a, int RS, hipStream_t s) {
+  const bool mfma_ok = a.Wfrag != nullptr && a.C % 32 == 0 && a.Cout == a.C &&
+                       reinterpret_cast<uintptr_t>(a.in) % 16 == 0 && reinterpret_cast<uintptr_t>(a.out) % 16 == 0;
+  // "same" convolution: whole input patch staged in LDS, if it fits
+  const int R = RS == 9 ? 3 : 1;
+  if (mfma_ok && a.stride == 1 && 2 * a.pad == R - 1 && a.Ho == a.H && a.Wo == a.W) {
+    const int ncb = (a.C % 128 == 0) ? 4 : 1;
+    const int halo = a.pad * a.W + a.pad;
+    const int cp = ncb * 2;
+    const int nchunks_pad = ((128 + 2 * halo) * cp + 255) / 256 * 256;
+    const int smem = ncb * RS * QG_FRAG_BYTES + ncb * 32 * 12 + nchunks_pad * 16;
+    if (smem <= 160 * 1024) {
+      if (ncb == 4) return RS == 9 ? launch_same<3, 3, 4>(a, smem, halo, nchunks_pad, s)
+                                   : launch_same<1, 1, 4>(a, smem, halo, nchunks_pad, s);
+      return RS == 9 ? launch_same<3, 3, 1>(a, smem, halo, nchunks_pad, s)
+                     : launch_same<1, 1, 1>(a, smem, halo, nchunks_pad, s);
+    }
+  }
+  // matrix-core kernel with taps fetched from global memory: needs whole 32-channel blocks and 16-byte aligned pixels
+  if (mfma_ok && a.C % 32 == 0 && a.Cout == a.C &&
+      reinterpret_cast<uintptr_t>(a.in) % 16 == 0 && reinterpret_cast<uintptr_t>(a.out) % 16 == 0) {
+    if (a.C % 128 == 0) return RS == 9 ? launch_mfma<3, 3, 4>(a, s) : launch_mfma<1, 1, 4>(a, s);
+    return RS == 9 ? launch_mfma<3, 3, 1>(a, s) : launch_mfma<1, 1, 1>(a, s);
+  }
   const int ppb = a.G >= 256 ? 1 : 256 / a.G;
   const int threads = ppb * a.G;
   const long long npix = (long long)a.Nb * a.Ho * a.Wo;

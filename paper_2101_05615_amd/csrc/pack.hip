@@ -71,6 +71,35 @@ __global__ void qg_pack_conv_w_kernel(const int8_t* __restrict__ W, int G, int R
   col_off[oc] = sum - RS * 4 * bzp[oc];
 }
 
+// Conv weights for the matrix-core kernel: for every 32-channel block cb and tap, one 1 KiB fragment in
+// v_mfma_i32_32x32x32_i8 operand order holding the block-diagonal 32 x 32 matrix W[oc][ic] (8 groups of
+// 4 x 4; everything off the diagonal blocks is zero).  Lane (i + 32 g) owns W[oc(i)][16 g .. 16 g + 15],
+// oc(i) being the column permutation that leaves each lane of the result with 16 consecutive channels.
+__global__ void qg_pack_conv_w_mfma_kernel(const int8_t* __restrict__ W, int RS, int nfrag,
+                                           int8_t* __restrict__ frags) {
+  const int gid = blockIdx.x * blockDim.x + threadIdx.x;  // one 16-byte chunk per thread
+  if (gid >= nfrag * 64) return;
+  const int frag = gid >> 6, lane = gid & 63;
+  const int cb = frag / RS, tap = frag % RS;
+  const int i = lane & 31, g = lane >> 5;
+  const int oc_l = qg_slot_to_col(i);
+  union {
+    int4 v;
+    int8_t b[16];
+  } u;
+#pragma unroll
+  for (int b = 0; b < 16; ++b) {
+    const int ic_l = 16 * g + b;
+    int8_t w = 0;
+    if ((ic_l >> 2) == (oc_l >> 2)) {
+      const int grp = cb * 8 + (oc_l >> 2);
+      w = W[(((size_t)grp * RS + tap) * 4 + (ic_l & 3)) * 4 + (oc_l & 3)];
+    }
+    u.b[b] = w;
+  }
+  *reinterpret_cast<int4*>(frags + (size_t)frag * QG_FRAG_BYTES + lane * 16) = u.v;
+}
+
 }  // namespace
 
 hipError_t qg_launch_pack_b(const int8_t* B, int K, int N, int ldb, int K_pad, int N_pad,
@@ -86,8 +115,13 @@ hipError_t qg_launch_pack_b(const int8_t* B, int K, int N, int ldb, int K_pad, i
 }
 
 hipError_t qg_launch_pack_conv_w(const int8_t* W, int G, int RS, int8_t* packed, int32_t* col_off,
-                                 const int32_t* bzp_dev, hipStream_t s) {
+                                 const int32_t* bzp_dev, int8_t* mfma_frags, hipStream_t s) {
   hipLaunchKernelGGL(qg_pack_conv_w_kernel, dim3((G * 4 + 63) / 64), dim3(64), 0, s, W, G, RS, packed,
                      col_off, bzp_dev);
+  if (mfma_frags != nullptr) {  // C = 4 G is a multiple of 32
+    const int nfrag = (G / 8) * RS;
+    hipLaunchKernelGGL(qg_pack_conv_w_mfma_kernel, dim3((nfrag * 64 + 255) / 256), dim3(256), 0, s, W, RS,
+                       nfrag, mfma_frags);
+  }
   return hipGetLastError();
 }

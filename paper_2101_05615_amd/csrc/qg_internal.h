@@ -59,6 +59,7 @@ struct qg_packed_b {
   const int32_t* bzp;     // device: per-column theta_B (inside the col_offsets buffer)
   // conv only
   int G, R, S, Cg, Og;
+  const int8_t* conv_frags;  // device: matrix-core layout of the conv weights, or null (C % 32 != 0)
 };
 
 // Arguments of the GEMM kernels (by value).
@@ -86,6 +87,7 @@ struct qg_gemm_args {
 struct qg_conv_args {
   const uint8_t* in;
   const int8_t* Wp;
+  const int8_t* Wfrag;  // matrix-core layout, or null
   const int32_t* col_off;
   const int32_t* bzp;
   const int32_t* bias;
@@ -117,7 +119,7 @@ __device__ __forceinline__ int qg_requant_one(int x, float sc, float lo, float h
 hipError_t qg_launch_pack_b(const int8_t* B, int K, int N, int ldb, int K_pad, int N_pad,
                             int8_t* packed, int32_t* col_off, const int32_t* bzp_dev, hipStream_t s);
 hipError_t qg_launch_pack_conv_w(const int8_t* W, int G, int RS, int8_t* packed, int32_t* col_off,
-                                 const int32_t* bzp_dev, hipStream_t s);
+                                 const int32_t* bzp_dev, int8_t* mfma_frags, hipStream_t s);
 hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, hipStream_t s);
 hipError_t qg_launch_gemm_skinny(const qg_gemm_args& a, int mode, hipStream_t s);
 hipError_t qg_launch_conv_group(const qg_conv_args& a, int RS, hipStream_t s);
