@@ -5,19 +5,24 @@
 // makes each wave load one contiguous KiB (16 B per lane).  LDS is used only to
 // combine the partial sums of the 16 waves that split K.
 //
-// One workgroup (1024 threads) owns one 16-column fragment column of B over all
-// of K; wave w takes a contiguous range of 64-deep k blocks and issues all of its
-// loads before the first MFMA so that the whole weight matrix is in flight at
-// once.  A (at most 64 rows) is read from L2 in MFMA operand order, shifted to
-// int8 (xor 0x80) and row-summed with v_dot4 on the way, as in the large kernel.
+// One workgroup owns one 16-column fragment column of B over all of K; wave w
+// takes a contiguous range of 64-deep k blocks and issues a whole batch of loads
+// before the first MFMA so that the whole weight matrix is in flight at once.
+// A (at most 64 rows) comes from L2, is row-summed on its raw bytes (v_sad_u8) and shifted
+// to int8 (xor 0x80) on the way, as in the large kernel.  For M <= 16 each wave stages its own
+// K-slice of A through a private 4 KiB of LDS with global_load_lds: the request reads whole
+// 256-byte row segments (MFMA operand order would touch 16 rows x 64 B per load), and the
+// fragment is then fetched from LDS in operand order.
 #include "qg_internal.h"
 
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-constexpr int NWAVES = 16;
-constexpr int NTHREADS = NWAVES * 64;
+// waves per workgroup and k blocks a wave requests at once (set per shape by the launcher)
+#ifndef QG_SKINNY_CFG
+#define QG_SKINNY_CFG 16, 4
+#endif
 
 __device__ __forceinline__ v4i load_a_chunk_slow(const uint8_t* p, int kvalid) {
   union {
@@ -29,26 +34,45 @@ __device__ __forceinline__ v4i load_a_chunk_slow(const uint8_t* p, int kvalid) {
   return u.v;
 }
 
-template <int MODE, int MB>
-__global__ __launch_bounds__(NTHREADS) void qg_gemm_skinny_kernel(const qg_gemm_args p) {
+template <int MODE, int MB, int NWAVES, int BATCH>
+__global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_gemm_args p) {
+  constexpr bool ASTAGE = (MB == 1 && BATCH == 4);  // A through LDS (see the file header)
+  constexpr int PART_BYTES = NWAVES * MB * 64 * (int)sizeof(v4i);
+  constexpr int RSP_BYTES = NWAVES * MB * 16 * (int)sizeof(int);
   extern __shared__ __align__(16) unsigned char smem[];
-  v4i* part = reinterpret_cast<v4i*>(smem);                              // [wave][mb][lane]
-  int* rsp = reinterpret_cast<int*>(smem + NWAVES * MB * 64 * sizeof(v4i));  // [wave][mb][16]
+  v4i* part = reinterpret_cast<v4i*>(smem);                 // [wave][mb][lane]
+  int* rsp = reinterpret_cast<int*>(smem + PART_BYTES);     // [wave][mb][16]
 
   const int nb16 = blockIdx.x;
   const int sb = nb16 >> 1, sfrag = nb16 & 1;
   // columns held by this fragment: sb*32 + 16*(u&1) + 8*sfrag + 4*(u>>1) + r, u<4, r<4
   if (sb * 32 + 8 * sfrag >= p.N) return;  // nothing but padding (uniform for the workgroup)
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ml = lane & 15, g = lane >> 4;
+
+  // the waves that run the output pipeline fetch its per-column constants now, not after the reduction
+  const int c0 = sb * 32 + 16 * (g & 1) + 8 * sfrag + 4 * (g >> 1);  // this lane's 4 output columns
+  int ep_co[4], ep_bz[4], ep_bias[4];
+  float ep_sc[4];
+  if (wave < MB) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int col = c0 + r;  // col_off / bzp are padded to N_pad, bias / scales are not
+      ep_co[r] = p.col_off[col];
+      ep_bz[r] = p.bzp[col];
+      ep_bias[r] = (MODE == QG_MODE_REQUANT && p.bias != nullptr && col < p.N) ? p.bias[col] : 0;
+      ep_sc[r] = (MODE == QG_MODE_REQUANT && col < p.N) ? p.scales[(size_t)col * p.scale_stride] : 1.0f;
+    }
+  }
 
   const int per = (p.kb64 + NWAVES - 1) / NWAVES;
   const int kb_begin = wave * per;
   const int kb_end = min(p.kb64, kb_begin + per);
 
   v4i acc[MB];
-  int rs[MB];
+  unsigned rs[MB];  // sums of raw uint8 bytes (K padding reads as 0x80)
   const uint8_t* a_row[MB];
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
@@ -56,18 +80,35 @@ __global__ __launch_bounds__(NTHREADS) void qg_gemm_skinny_kernel(const qg_gemm_
     rs[mb] = 0;
     a_row[mb] = p.A + (size_t)min(mb * 16 + ml, p.M - 1) * p.lda + g * 16;
   }
-  const int8_t* bcol = p.Bp + (size_t)nb16 * p.kb64 * QG_FRAG_BYTES + lane * 16;
+  const int8_t* bcol = p.Bp + (size_t)nb16 * QG_FRAG_BYTES + lane * 16;
+  const size_t b_step = (size_t)p.nb16 * QG_FRAG_BYTES;  // one 64-deep slab of the packed buffer
 
-  for (int kb = kb_begin; kb < kb_end; kb += 4) {
-    v4i bf[4];
+  for (int kb = kb_begin; kb < kb_end; kb += BATCH) {
+    v4i bf[BATCH];
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      if (kb + j < kb_end) bf[j] = *reinterpret_cast<const v4i*>(bcol + (size_t)(kb + j) * QG_FRAG_BYTES);
-    v4i af[MB][4];
+    for (int j = 0; j < BATCH; ++j)
+      if (kb + j < kb_end) bf[j] = *reinterpret_cast<const v4i*>(bcol + (size_t)(kb + j) * b_step);
+    v4i af[MB][BATCH];
+    if (ASTAGE && p.a_vec && kb + BATCH <= kb_end && (kb + BATCH) * QG_FRAG_K <= p.K) {
+      // 16 rows x 256 B of A: four requests of 4 rows x 256 B into this wave's LDS region, chunk c of
+      // row r stored at chunk c ^ r so that the operand-order reads below are bank-conflict free
+      unsigned char* region = smem + PART_BYTES + RSP_BYTES + wave * 4096;
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int r = jj * 4 + (lane >> 4);
+        const uint8_t* src = p.A + (size_t)min(r, p.M - 1) * p.lda + kb * QG_FRAG_K + (((lane & 15) ^ r) << 4);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)(region + jj * 1024), 16, 0, 0);
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int j = 0; j < BATCH; ++j)
+        af[0][j] = *reinterpret_cast<const v4i*>(region + ml * 256 + (((4 * j + g) ^ ml) << 4));
+    } else
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+      for (int j = 0; j < BATCH; ++j)
         if (kb + j < kb_end) {
           const int k = (kb + j) * QG_FRAG_K + g * 16;
           const int kvalid = p.K - k;
@@ -77,15 +118,15 @@ __global__ __launch_bounds__(NTHREADS) void qg_gemm_skinny_kernel(const qg_gemm_
             af[mb][j] = load_a_chunk_slow(a_row[mb] + (kb + j) * QG_FRAG_K, kvalid);
         }
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < BATCH; ++j)
       if (kb + j < kb_end) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
+          rs[mb] = __builtin_amdgcn_sad_u8(af[mb][j].x, 0u, rs[mb]);
+          rs[mb] = __builtin_amdgcn_sad_u8(af[mb][j].y, 0u, rs[mb]);
+          rs[mb] = __builtin_amdgcn_sad_u8(af[mb][j].z, 0u, rs[mb]);
+          rs[mb] = __builtin_amdgcn_sad_u8(af[mb][j].w, 0u, rs[mb]);
           const v4i a = af[mb][j] ^ (int)0x80808080;
-          rs[mb] = __builtin_amdgcn_sdot4(a.x, 0x01010101, rs[mb], false);
-          rs[mb] = __builtin_amdgcn_sdot4(a.y, 0x01010101, rs[mb], false);
-          rs[mb] = __builtin_amdgcn_sdot4(a.z, 0x01010101, rs[mb], false);
-          rs[mb] = __builtin_amdgcn_sdot4(a.w, 0x01010101, rs[mb], false);
           acc[mb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(bf[j], a, acc[mb], 0, 0, 0);
         }
       }
@@ -95,7 +136,7 @@ __global__ __launch_bounds__(NTHREADS) void qg_gemm_skinny_kernel(const qg_gemm_
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
     part[(wave * MB + mb) * 64 + lane] = acc[mb];
-    int v = rs[mb];
+    int v = (int)rs[mb];
     v += __shfl_xor(v, 16);
     v += __shfl_xor(v, 32);
     if (g == 0) rsp[(wave * MB + mb) * 16 + ml] = v;
@@ -104,7 +145,7 @@ __global__ __launch_bounds__(NTHREADS) void qg_gemm_skinny_kernel(const qg_gemm_
   if (wave >= MB) return;
   const int mb = wave;
   v4i sum = (v4i){0, 0, 0, 0};
-  int rsum = 0;
+  int rsum = -128 * (p.kb64 * QG_FRAG_K);  // every staged byte (padding included) is 128 above its int8 value
 #pragma unroll
   for (int w = 0; w < NWAVES; ++w) {
     sum += part[(w * MB + mb) * 64 + lane];
@@ -113,18 +154,13 @@ __global__ __launch_bounds__(NTHREADS) void qg_gemm_skinny_kernel(const qg_gemm_
 
   // ---- output pipeline; lane (ml, u = g) holds row mb*16+ml, 4 consecutive columns
   const int row = mb * 16 + ml;
-  const int c0 = sb * 32 + 16 * (g & 1) + 8 * sfrag + 4 * (g >> 1);
   if (row >= p.M || c0 >= p.N) return;
   if (MODE == QG_MODE_REQUANT) {
     unsigned out = 0;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int col = c0 + r;  // col_off / bzp are padded, bias / scales are not
-      const int co = p.col_off[col], bz = p.bzp[col];
-      const int b = (p.bias != nullptr && col < p.N) ? p.bias[col] : 0;
-      const float sc = (col < p.N) ? p.scales[(size_t)col * p.scale_stride] : 1.0f;
-      const int x = sum[r] + b - p.a_zp_m128 * co - bz * rsum;
-      out |= (unsigned)qg_requant_one(x, sc, p.clamp_lo, p.clamp_hi, p.c_zp) << (8 * r);
+      const int x = sum[r] + ep_bias[r] - p.a_zp_m128 * ep_co[r] - ep_bz[r] * rsum;
+      out |= (unsigned)qg_requant_one(x, ep_sc[r], p.clamp_lo, p.clamp_hi, p.c_zp) << (8 * r);
     }
     uint8_t* dst = p.C + (size_t)row * p.ldc + c0;
     if (p.c_vec && c0 + 4 <= p.N) {
@@ -138,29 +174,29 @@ __global__ __launch_bounds__(NTHREADS) void qg_gemm_skinny_kernel(const qg_gemm_
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int col = c0 + r;
-      if (col < p.N)
-        p.C32[(size_t)row * p.ldc + col] = sum[r] + 128 * (p.col_off[col] + p.K * p.bzp[col]);
+      if (col < p.N) p.C32[(size_t)row * p.ldc + col] = sum[r] + 128 * (ep_co[r] + p.K * ep_bz[r]);
     }
     if (p.rowsum_out != nullptr && nb16 == 0 && g == 0) p.rowsum_out[row] = rsum + 128 * p.K;
   }
 }
 
-template <int MODE, int MB>
+template <int MODE, int MB, int NWAVES, int BATCH>
 hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
-  const int smem = NWAVES * MB * 64 * (int)sizeof(v4i) + NWAVES * MB * 16 * (int)sizeof(int);
-  hipError_t e = hipFuncSetAttribute((const void*)qg_gemm_skinny_kernel<MODE, MB>,
+  const int smem = NWAVES * MB * 64 * (int)sizeof(v4i) + NWAVES * MB * 16 * (int)sizeof(int) +
+                   ((MB == 1 && BATCH == 4) ? NWAVES * 4096 : 0);
+  hipError_t e = hipFuncSetAttribute((const void*)qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, smem);
   if (e != hipSuccess) return e;
   const int nfrag = ((a.N + 31) / 32) * 2;
-  hipLaunchKernelGGL((qg_gemm_skinny_kernel<MODE, MB>), dim3(nfrag), dim3(NTHREADS), smem, s, a);
+  hipLaunchKernelGGL((qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH>), dim3(nfrag), dim3(NWAVES * 64), smem, s, a);
   return hipGetLastError();
 }
 
 template <int MODE>
 hipError_t launch_mb(const qg_gemm_args& a, hipStream_t s) {
-  if (a.M <= 16) return launch<MODE, 1>(a, s);
-  if (a.M <= 32) return launch<MODE, 2>(a, s);
-  return launch<MODE, 4>(a, s);
+  if (a.M <= 16) return launch<MODE, 1, QG_SKINNY_CFG>(a, s);
+  if (a.M <= 32) return launch<MODE, 2, 16, 4>(a, s);
+  return launch<MODE, 4, 16, 2>(a, s);
 }
 
 }  // namespace

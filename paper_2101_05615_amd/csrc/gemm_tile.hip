@@ -100,7 +100,7 @@ __global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_g
 
   // ---- staging.  A: one wave-load fills 1 KiB of LDS = 16 rows x 64 B; lane l lands at row l/4,
   // physical chunk l%4, so it fetches the logical chunk that the swizzle maps there.  B: the tile is
-  // BN/16 fragments of 1 KiB, each contiguous in the packed buffer.  Addresses are a wave-uniform
+  // BN/16 fragments of 1 KiB, one contiguous run of the packed buffer.  Addresses are a wave-uniform
   // base (advanced per tile on the scalar unit) plus a fixed 32-bit per-lane offset.
   unsigned a_voff[A_DMA], b_voff[B_DMA];
 #pragma unroll
@@ -112,13 +112,14 @@ __global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_g
   }
 #pragma unroll
   for (int q = 0; q < B_DMA; ++q)
-    b_voff[q] = (unsigned)(wave * B_DMA + q) * (unsigned)p.kb64 * QG_FRAG_BYTES + lane * 16;
-  const int8_t* b_tile0 = p.Bp + (size_t)(n0 / QG_FRAG_COLS) * p.kb64 * QG_FRAG_BYTES;
+    b_voff[q] = (unsigned)(wave * B_DMA + q) * QG_FRAG_BYTES + lane * 16;
+  const int8_t* b_tile0 = p.Bp + (size_t)(n0 / QG_FRAG_COLS) * QG_FRAG_BYTES;
+  const unsigned b_step = (unsigned)p.nb16 * QG_FRAG_BYTES;  // one 64-deep slab of the packed buffer
 
   auto request_tile = [&](int kt, int stage) {
     unsigned char* base = smem + stage * STAGE;
     const uint8_t* a_base = p.A + kt * BK;
-    const int8_t* b_base = b_tile0 + (size_t)kt * QG_FRAG_BYTES;
+    const int8_t* b_base = b_tile0 + (size_t)kt * b_step;
 #pragma unroll
     for (int q = 0; q < A_DMA; ++q) dma16(a_base + a_voff[q], base + (wave * A_DMA + q) * 1024);
 #pragma unroll
@@ -221,7 +222,7 @@ __global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_g
                    [rs01] "=v"(rs01), [rs23] "=v"(rs23)
                  : [av01] "v"(av01), [av23] "v"(av23), [bv01] "v"(bv01), [bv23] "v"(bv23), [ard] "v"(ard),
                    [brd] "v"(brd), [aptr] "s"(p.A), [bptr] "s"(b_tile0), [kt] "s"(KT), [ldsdma] "s"(lds_dma),
-                   [lds] "s"(lds_base)
+                   [lds] "s"(lds_base), [bstep] "s"(b_step)
                  : QG_TILE_LOOP_CLOBBERS);
     rs[0] = (unsigned)rs01;
     rs[1] = (unsigned)(rs01 >> 32);
@@ -241,7 +242,7 @@ __global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_g
         *reinterpret_cast<v4i*>(smem + (wave * A_DMA + q) * 1024 + lane * 16) =
             load_a_chunk_slow(src, p.K - (k0 + kc * 16));
       }
-      const int8_t* b_base = b_tile0 + (size_t)kt * QG_FRAG_BYTES;
+      const int8_t* b_base = b_tile0 + (size_t)kt * b_step;
 #pragma unroll
       for (int q = 0; q < B_DMA; ++q)
         *reinterpret_cast<v4i*>(smem + A_STAGE + (wave * B_DMA + q) * 1024 + lane * 16) =

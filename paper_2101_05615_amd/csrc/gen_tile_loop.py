@@ -16,10 +16,10 @@ Fixed register plan (all clobbered by the asm statement):
   v236/v237  per-lane LDS offsets of the A fragment for k-step 0 / 1, v238 of the B fragment
   v240/v241  LDS read addresses (stage base added)
   s84 xor mask, s[86:87] A request base, s[88:89] B request base, s90 loop counter, s91 LDS base of
-  this wave's request slots, s92 LDS base, s93 stage index, s96 request stage base, s97/s98 read
+  this wave's request slots, s92 LDS base, s99 bytes per 64-deep slab of packed B, s93 stage index, s96 request stage base, s97/s98 read
   stage bases (current / next), s94/s95 temporaries
 Operands: 16 accumulators c0..c15 ("+a", acc[mb][nb] = c{4*mb+nb}), packed 64-bit VGPR inputs
-av01 av23 bv01 bv23 ard brd, SGPR inputs aptr bptr kt ldsdma lds, 64-bit VGPR outputs rs01 rs23.
+av01 av23 bv01 bv23 ard brd, SGPR inputs aptr bptr kt ldsdma lds bstep, 64-bit VGPR outputs rs01 rs23.
 """
 import os
 
@@ -65,7 +65,7 @@ def dma(e, q):
 def advance_request_pointers(e):
     e("s_add_u32 s86, s86, 64")
     e("s_addc_u32 s87, s87, 0")
-    e("s_add_u32 s88, s88, 1024")
+    e("s_add_u32 s88, s88, s99")
     e("s_addc_u32 s89, s89, 0")
 
 
@@ -171,6 +171,7 @@ def generate():
     e("s_sub_u32 s90, %[kt], 4")
     e("s_mov_b32 s91, %[ldsdma]")
     e("s_mov_b32 s92, %[lds]")
+    e("s_mov_b32 s99, %[bstep]")
     for f in range(4):
         e(f"v_mov_b32 v{RS + f}, 0")
     # ---- request tiles 0..3 into stages 0..3

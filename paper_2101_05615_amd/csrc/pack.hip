@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void qg_pack_b_kernel(const int8_t* __restrict
   const int slot = qg_col_to_slot(c);
   const int nb16 = sb * 2 + (slot >> 4), nl = slot & 15;
   const int kb = kc16 >> 2, g = kc16 & 3;
-  const size_t dst = ((size_t)nb16 * (K_pad / QG_FRAG_K) + kb) * QG_FRAG_BYTES + (g * 16 + nl) * 16;
+  const size_t dst = ((size_t)kb * (N_pad / QG_FRAG_COLS) + nb16) * QG_FRAG_BYTES + (g * 16 + nl) * 16;
   *reinterpret_cast<int4*>(packed + dst) = u.v;
   if (n < N && sum != 0) atomicAdd(&colsum[n], sum);
 }

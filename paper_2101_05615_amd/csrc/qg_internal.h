@@ -21,7 +21,9 @@
 // half-fragments (g pair) of two fragments of one 32-column super-block are
 // what v_mfma_i32_32x32x32_i8 wants, so the same bytes serve both MFMA shapes.
 //
-// Fragments are ordered [nb16][kb64]: all of K for 16 columns is contiguous.
+// Fragments are ordered [kb64][nb16]: one 64-deep slab of K for all columns is contiguous, so
+// a k-tile of any width is one contiguous run and the workgroups of the small-batch kernel,
+// which walk down K side by side, stream adjacent KiBs (all HBM channels busy at once).
 //
 // Columns are permuted inside each 32-column super-block so that the 32x32
 // MFMA leaves every lane holding 16 CONSECUTIVE output columns (one 16-byte
@@ -75,6 +77,7 @@ struct qg_gemm_args {
   int32_t* rowsum_out;   // acc32 mode, may be null
   int M, N, K;
   int kb64;              // K_pad / 64
+  int nb16;              // N_pad / 16: fragments per 64-deep slab of the packed buffer
   int lda, ldc;
   int scale_stride;      // 0 per tensor, 1 per channel
   int a_zp_m128;         // theta_A - 128
