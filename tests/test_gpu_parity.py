@@ -52,6 +52,9 @@ ACC_SHAPES = [  # (M, N, K): both kernels (M <= 64 skinny, above: large tile), r
     (64, 64, 128), (5, 4, 36), (48, 512, 1024),
     (65, 64, 128), (255, 100, 100), (256, 256, 128), (257, 300, 129), (300, 4, 36), (512, 512, 512),
     (700, 520, 4097), (1024, 256, 2048),
+    # aligned shapes that take the pipelined paths: 4 / 5 / many 64-deep tiles, several batches per wave
+    (300, 512, 256), (512, 256, 320), (260, 256, 192), (16, 256, 8448), (5, 64, 4224), (16, 512, 12288),
+    (40, 128, 4096),
 ]
 
 
@@ -88,6 +91,7 @@ REQ_SHAPES = [
     (1, 1, 1), (1, 4, 36), (16, 64, 128), (16, 100, 100), (17, 100, 100), (31, 33, 65), (64, 257, 4097),
     (65, 64, 128), (100, 4, 36), (255, 100, 100), (256, 256, 256), (257, 255, 127), (300, 300, 300),
     (513, 264, 1000),
+    (300, 512, 256), (512, 256, 320), (260, 256, 192), (16, 256, 8448), (5, 64, 4224), (640, 384, 1024),
 ]
 
 
@@ -246,6 +250,11 @@ def _oracle_conv(c, oracle):
     dict(Nb=3, H=8, W=8, C=32, G=8, stride=2), dict(Nb=1, H=6, W=6, C=8, G=2, pad=0),
     dict(Nb=1, H=5, W=5, C=12, G=3, pad=2), dict(Nb=2, H=4, W=4, C=16, G=4, R=1, S=1, pad=0),
     dict(Nb=1, H=1, W=1, C=4, G=1),
+    # matrix-core kernels: one and several 32-channel blocks, two channel groups, 1x1, an image too wide for the
+    # LDS-staged patch (falls back to taps from global memory), a pixel count that is not a multiple of 32 or 128
+    dict(Nb=2, H=7, W=9, C=64, G=16), dict(Nb=1, H=5, W=5, C=256, G=64), dict(Nb=3, H=6, W=6, C=128, G=32, R=1, S=1, pad=0),
+    dict(Nb=1, H=3, W=600, C=128, G=32), dict(Nb=2, H=13, W=11, C=128, G=32), dict(Nb=1, H=8, W=8, C=32, G=8, pad=0),
+    dict(Nb=2, H=9, W=9, C=128, G=32, stride=2),
 ])
 @pytest.mark.parametrize("per_channel,with_bias,relu", [(True, True, False), (False, False, True)])
 def test_group_conv_bit_exact_small(env, cfg, per_channel, with_bias, relu):
@@ -254,6 +263,16 @@ def test_group_conv_bit_exact_small(env, cfg, per_channel, with_bias, relu):
     c = wl.random_conv(5, per_channel=per_channel, with_bias=with_bias, relu=relu, **cfg)
     got, Wp = _run_conv(c, q, torch, dev)
     assert_same(got, _oracle_conv(c, oracle), c.name)
+
+
+def test_group_conv_zero_weight_zero_point_variant(env):
+    # theta_B == 0 selects the kernel variants without row offsets
+    q, torch, dev, oracle = env
+    for cfg in (dict(Nb=2, H=8, W=8, C=128, G=32), dict(Nb=1, H=6, W=7, C=32, G=8), dict(Nb=1, H=5, W=5, C=8, G=2)):
+        c = wl.random_conv(11, **cfg)
+        c.b_zp = np.zeros(1, np.int32)
+        got, _ = _run_conv(c, q, torch, dev)
+        assert_same(got, _oracle_conv(c, oracle), c.name + "_bzp0")
 
 
 def test_config5_group_conv_full(env):
