@@ -52,12 +52,6 @@ __device__ __forceinline__ v4i load_a_chunk_slow(const uint8_t* p, int kvalid) {
   return u.v;
 }
 
-// 16 bytes per lane from global memory into LDS at lds_base + lane*16 (lds_base wave-uniform)
-__device__ __forceinline__ void dma16(const void* gptr, unsigned char* lds_base) {
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
-                                   (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
-}
-
 // NWM x NWN waves, each TM x TN blocks of 32 x 32.
 // FAST: A is 16-byte aligned with lda % 16 == 0, K % 64 == 0 and K >= 256, so every tile is requested with
 // global_load_lds and the loop is software-pipelined four tiles deep.  Otherwise a plain,
@@ -108,23 +102,15 @@ __global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_g
     const int r = (wave * A_DMA + q) * 16 + (lane >> 2);
     const int kc = (lane & 3) ^ ((r >> 1) & 3);
     const int rg = min(m0 + r, p.M - 1);  // rows past M re-read the last row; never stored
-    a_voff[q] = (unsigned)rg * (unsigned)p.lda + kc * 16;
+    // FAST: the asm loop uses instruction offset q*1024 (it moves the LDS slot AND the global address, so one
+    // M0 serves a group of requests) against a base of A - 3072; the per-lane offset absorbs the difference
+    a_voff[q] = (unsigned)rg * (unsigned)p.lda + kc * 16 + (FAST ? (3 - q) * 1024 : 0);
   }
 #pragma unroll
   for (int q = 0; q < B_DMA; ++q)
     b_voff[q] = (unsigned)(wave * B_DMA + q) * QG_FRAG_BYTES + lane * 16;
   const int8_t* b_tile0 = p.Bp + (size_t)(n0 / QG_FRAG_COLS) * QG_FRAG_BYTES;
   const unsigned b_step = (unsigned)p.nb16 * QG_FRAG_BYTES;  // one 64-deep slab of the packed buffer
-
-  auto request_tile = [&](int kt, int stage) {
-    unsigned char* base = smem + stage * STAGE;
-    const uint8_t* a_base = p.A + kt * BK;
-    const int8_t* b_base = b_tile0 + (size_t)kt * b_step;
-#pragma unroll
-    for (int q = 0; q < A_DMA; ++q) dma16(a_base + a_voff[q], base + (wave * A_DMA + q) * 1024);
-#pragma unroll
-    for (int q = 0; q < B_DMA; ++q) dma16(b_base + b_voff[q], base + A_STAGE + (wave * B_DMA + q) * 1024);
-  };
 
   // ---- fragment fetch (LDS -> registers): per-lane base offsets, everything else is an immediate
   int a_rd[2];  // k-step 0 / 1 of block mb = 0; block mb is 32 rows = 2 KiB further
@@ -173,26 +159,6 @@ __global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_g
       for (int nb = 0; nb < TN; ++nb)
         acc[mb][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf[nb], af[mb], acc[mb][nb], 0, 0, 0);
   };
-  // One k-step of 32: request the fragments of the next step, run this step's MFMAs, then row-sum and
-  // shift the fragments that arrived meanwhile.  With one wave per SIMD nothing else hides the LDS
-  // latency, so the instruction stream itself is interleaved: an LDS read behind each of the first
-  // MFMAs, the VALU work (and the tile requests, in the step that issues them) behind the rest.
-  auto interleave = [&](int n_vmem) {
-    constexpr int REST = TM * TN - (TM + TN);
-#pragma unroll
-    for (int i = 0; i < TM + TN; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
-    }
-#pragma unroll
-    for (int i = 0; i < REST; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if (i < n_vmem) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // tile request
-      __builtin_amdgcn_sched_group_barrier(0x002, (8 * TM + REST - 1) / REST, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-  };
-
   const int KT = (p.K + BK - 1) / BK;  // tiles that hold real data
   v4i a0[TM], b0[TN], a1[TM], b1[TN];
   if (FAST) {
@@ -221,7 +187,7 @@ __global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_g
                    [c12] "+a"(acc[3][0]), [c13] "+a"(acc[3][1]), [c14] "+a"(acc[3][2]), [c15] "+a"(acc[3][3]),
                    [rs01] "=v"(rs01), [rs23] "=v"(rs23)
                  : [av01] "v"(av01), [av23] "v"(av23), [bv01] "v"(bv01), [bv23] "v"(bv23), [ard] "v"(ard),
-                   [brd] "v"(brd), [aptr] "s"(p.A), [bptr] "s"(b_tile0), [kt] "s"(KT), [ldsdma] "s"(lds_dma),
+                   [brd] "v"(brd), [aptr] "s"(p.A - 3072), [bptr] "s"(b_tile0), [kt] "s"(KT), [ldsdma] "s"(lds_dma),
                    [lds] "s"(lds_base), [bstep] "s"(b_step)
                  : QG_TILE_LOOP_CLOBBERS);
     rs[0] = (unsigned)rs01;

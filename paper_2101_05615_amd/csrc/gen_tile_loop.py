@@ -52,14 +52,28 @@ def dma(e, q):
     """one tile request: q = 0..3 A, 4..7 B; m0 = request stage base + slot"""
     if "nodma" in ABL:
         return
+    if "m0each" in ABL:
+        if q < 4:
+            e(f"s_add_u32 m0, s96, {q * 1024}")
+            e("s_nop 0")
+            e(f"global_load_lds_dwordx4 v{AV + q}, s[86:87]")
+        else:
+            e(f"s_add_u32 m0, s96, {A_STAGE + (q - 4) * 1024}")
+            e("s_nop 0")
+            e(f"global_load_lds_dwordx4 v{BV + q - 4}, s[88:89]")
+        return
+    # The instruction offset is added to the global address AND to the LDS address, so one M0 value serves the
+    # four requests of a group; the per-lane A offsets come in pre-biased by -q*1024 (B is contiguous anyway).
+    if q == 0:
+        e("s_mov_b32 m0, s96")
+        e("s_nop 0")
+    if q == 4:
+        e(f"s_add_u32 m0, s96, {A_STAGE}")
+        e("s_nop 0")
     if q < 4:
-        e(f"s_add_u32 m0, s96, {q * 1024}")
-        e("s_nop 0")
-        e(f"global_load_lds_dwordx4 v{AV + q}, s[86:87]")
+        e(f"global_load_lds_dwordx4 v{AV + q}, s[86:87]" + (f" offset:{q * 1024}" if q else ""))
     else:
-        e(f"s_add_u32 m0, s96, {A_STAGE + (q - 4) * 1024}")
-        e("s_nop 0")
-        e(f"global_load_lds_dwordx4 v{BV + q - 4}, s[88:89]")
+        e(f"global_load_lds_dwordx4 v{BV}, s[88:89]" + (f" offset:{(q - 4) * 1024}" if q > 4 else ""))
 
 
 def advance_request_pointers(e):
