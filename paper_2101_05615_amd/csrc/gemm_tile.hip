@@ -254,6 +254,7 @@ __global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_g
   // column block are fetched once and reused for the wave's TM row blocks.
   if (MODE == QG_MODE_REQUANT) {
     const bool full_cols = p.c_vec && (n0 + BN <= p.N);  // uniform: every 16-byte store is in range
+    const float czp_f = (float)p.c_zp;
 #pragma unroll
     for (int nb = 0; nb < TN; ++nb) {
       const int col_l = (wave_n * TN + nb) * 32 + lg * 16;
@@ -278,7 +279,7 @@ __global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_g
           for (int t = 0; t < 4; ++t) {
             const int i = 4 * q + t;
             const int x = acc[mb][nb][i] + cj[i] + __mul24(nbz[i], rsum);
-            w |= (unsigned)qg_requant_one(x, sc[i], p.clamp_lo, p.clamp_hi, p.c_zp) << (8 * t);
+            w = qg_requant_pack(x, sc[i], p.clamp_lo, p.clamp_hi, czp_f, t, w);
           }
           out[q] = w;
         }

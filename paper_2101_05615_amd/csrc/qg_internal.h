@@ -116,6 +116,17 @@ __device__ __forceinline__ int qg_requant_one(int x, float sc, float lo, float h
   const float c = __builtin_amdgcn_fmed3f(r, lo, hi);  // lo <= hi, r is never NaN for finite scales
   return (int)c + czp;
 }
+// Same sequence, result inserted as byte `pos` of `word`.  After the clamp the value is an integer in
+// [-theta_C, 255 - theta_C]; adding theta_C in fp32 is exact and v_cvt_pk_u8_f32 converts that integer
+// exactly, so the byte equals qg_requant_one() bit for bit while the convert also does the packing.
+__device__ __forceinline__ unsigned qg_requant_pack(int x, float sc, float lo, float hi, float czp_f,
+                                                    unsigned pos, unsigned word) {
+  const float f = (float)x;
+  const float p = f * sc;
+  const float r = __builtin_rintf(p);
+  const float c = __builtin_amdgcn_fmed3f(r, lo, hi) + czp_f;
+  return __builtin_amdgcn_cvt_pk_u8_f32(c, pos, word);
+}
 #endif
 
 // launchers (each returns a hipError_t from hipGetLastError after the launch)
