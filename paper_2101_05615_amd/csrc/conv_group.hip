@@ -54,6 +54,7 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 4) void qg_conv_group_mfma_kerne
   const int npix = p.Nb * p.Ho * p.Wo;
   const int nblk = (npix + 31) / 32;
   const unsigned azp_word = (unsigned)p.a_zp * 0x01010101u;
+  const float czp_f = (float)p.c_zp;
 
   for (int blk = blockIdx.x * 4 + wave; blk < nblk; blk += gridDim.x * 4) {
     const int px = blk * 32 + pl;
@@ -105,12 +106,12 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 4) void qg_conv_group_mfma_kerne
         if (HAS_BZP) {
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            const unsigned y = ((unsigned)x[cb][j] & keep) | (azp_word & ~keep);  // uint8 value of the tap
+            const unsigned y = __builtin_amdgcn_bitop3_b32((unsigned)x[cb][j], keep, azp_word, 0xe2);  // keep ? x : theta_A bytes
             rs[cb][j] = __builtin_amdgcn_sad_u8(y, 0u, rs[cb][j]);
           }
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) x[cb][j] = (int)(((unsigned)x[cb][j] & keep) ^ flip);
+        for (int j = 0; j < 4; ++j) x[cb][j] = (int)__builtin_amdgcn_bitop3_b32((unsigned)x[cb][j], keep, flip, 0x6a);  // (x & keep) ^ flip
         const v4i wf = *reinterpret_cast<const v4i*>(smem + (cb * RS + tap) * QG_FRAG_BYTES + lane * 16);
         acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, x[cb], acc[cb], 0, 0, 0);
       }
@@ -133,10 +134,10 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 4) void qg_conv_group_mfma_kerne
           const int x1 = acc[cb][4 * q + 1] + cj.y + (HAS_BZP ? __mul24(nbz.y, rsum) : 0);
           const int x2 = acc[cb][4 * q + 2] + cj.z + (HAS_BZP ? __mul24(nbz.z, rsum) : 0);
           const int x3 = acc[cb][4 * q + 3] + cj.w + (HAS_BZP ? __mul24(nbz.w, rsum) : 0);
-          out[q] = (unsigned)qg_requant_one(x0, sc.x, p.clamp_lo, p.clamp_hi, p.c_zp) |
-                   ((unsigned)qg_requant_one(x1, sc.y, p.clamp_lo, p.clamp_hi, p.c_zp) << 8) |
-                   ((unsigned)qg_requant_one(x2, sc.z, p.clamp_lo, p.clamp_hi, p.c_zp) << 16) |
-                   ((unsigned)qg_requant_one(x3, sc.w, p.clamp_lo, p.clamp_hi, p.c_zp) << 24);
+          unsigned w = qg_requant_pack(x0, sc.x, p.clamp_lo, p.clamp_hi, czp_f, 0, 0);
+          w = qg_requant_pack(x1, sc.y, p.clamp_lo, p.clamp_hi, czp_f, 1, w);
+          w = qg_requant_pack(x2, sc.z, p.clamp_lo, p.clamp_hi, czp_f, 2, w);
+          out[q] = qg_requant_pack(x3, sc.w, p.clamp_lo, p.clamp_hi, czp_f, 3, w);
         }
         *reinterpret_cast<uint4*>(p.out + (size_t)px * p.Cout + ch0 + c_l) =
             make_uint4(out[0], out[1], out[2], out[3]);
@@ -204,6 +205,7 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
   const int wo = pxc % p.W;
   const int ho = (pxc / p.W) % p.H;
   const unsigned azp_word = (unsigned)p.a_zp * 0x01010101u;
+  const float czp_f = (float)p.c_zp;
   const int pp_c = wave * 32 + pl + halo;  // patch index of this lane's centre pixel
 
   v16i acc[NCB];
@@ -234,12 +236,12 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
         if (HAS_BZP) {
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            const unsigned y = ((unsigned)x[j] & keep) | (azp_word & ~keep);  // uint8 value of the tap
+            const unsigned y = __builtin_amdgcn_bitop3_b32((unsigned)x[j], keep, azp_word, 0xe2);  // keep ? x : theta_A bytes
             rs[cb][j] = __builtin_amdgcn_sad_u8(y, 0u, rs[cb][j]);
           }
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) x[j] = (int)(((unsigned)x[j] & keep) ^ flip);
+        for (int j = 0; j < 4; ++j) x[j] = (int)__builtin_amdgcn_bitop3_b32((unsigned)x[j], keep, flip, 0x6a);  // (x & keep) ^ flip
         const v4i wf = *reinterpret_cast<const v4i*>(w_s + (cb * RS + kh * S + kw) * QG_FRAG_BYTES + lane * 16);
         acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, x, acc[cb], 0, 0, 0);
       }
@@ -262,10 +264,10 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
         const int x1 = acc[cb][4 * q + 1] + cj.y + (HAS_BZP ? __mul24(nbz.y, rsum) : 0);
         const int x2 = acc[cb][4 * q + 2] + cj.z + (HAS_BZP ? __mul24(nbz.z, rsum) : 0);
         const int x3 = acc[cb][4 * q + 3] + cj.w + (HAS_BZP ? __mul24(nbz.w, rsum) : 0);
-        out[q] = (unsigned)qg_requant_one(x0, sc.x, p.clamp_lo, p.clamp_hi, p.c_zp) |
-                 ((unsigned)qg_requant_one(x1, sc.y, p.clamp_lo, p.clamp_hi, p.c_zp) << 8) |
-                 ((unsigned)qg_requant_one(x2, sc.z, p.clamp_lo, p.clamp_hi, p.c_zp) << 16) |
-                 ((unsigned)qg_requant_one(x3, sc.w, p.clamp_lo, p.clamp_hi, p.c_zp) << 24);
+        unsigned w = qg_requant_pack(x0, sc.x, p.clamp_lo, p.clamp_hi, czp_f, 0, 0);
+        w = qg_requant_pack(x1, sc.y, p.clamp_lo, p.clamp_hi, czp_f, 1, w);
+        w = qg_requant_pack(x2, sc.z, p.clamp_lo, p.clamp_hi, czp_f, 2, w);
+        out[q] = qg_requant_pack(x3, sc.w, p.clamp_lo, p.clamp_hi, czp_f, 3, w);
       }
       *reinterpret_cast<uint4*>(p.out + (size_t)px * p.Cout + ch0 + c_l) =
           make_uint4(out[0], out[1], out[2], out[3]);

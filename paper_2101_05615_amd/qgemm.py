@@ -153,6 +153,44 @@ def gemm_u8s8_requant(A, a_zp, Bp, bias, scales, c_zp, relu, out=None, workspace
     return out
 
 
+class PreparedGemm:
+    """All arguments of one qg_gemm_u8s8_requant call marshalled once; `launch()` is a single ctypes call on
+    the stream that was current when the object was made.  For loops that repeat the same call."""
+
+    def __init__(self, A, a_zp, Bp, bias, scales, c_zp, relu, out):
+        assert A.is_cuda and A.dtype == torch.uint8 and A.dim() == 2 and A.stride(1) == 1 and A.shape[1] == Bp.K
+        assert out.is_cuda and out.dtype == torch.uint8 and out.stride(1) == 1 and out.shape == (A.shape[0], Bp.N)
+        self._keep = (A, Bp, bias, scales, out)
+        self._p = _params(a_zp, bias, scales, c_zp, relu)
+        self._args = (A.data_ptr(), A.shape[0], A.stride(0), Bp.handle, ctypes.byref(self._p), out.data_ptr(),
+                      out.stride(0), None, _stream())
+        self.out = out
+
+    def launch(self):
+        rc = lib.qg_gemm_u8s8_requant(*self._args)
+        if rc != OK:
+            raise QGemmError(rc, "qg_gemm_u8s8_requant")
+
+
+class PreparedConv:
+    """Same for qg_conv_groupwise_u8s8_requant."""
+
+    def __init__(self, inp, Wp, a_zp, bias, scales, c_zp, relu, pad, stride, out):
+        assert inp.is_cuda and inp.dtype == torch.uint8 and inp.dim() == 4 and inp.is_contiguous()
+        assert out.is_cuda and out.dtype == torch.uint8 and out.is_contiguous()
+        Nb, H, W, C = inp.shape
+        self._keep = (inp, Wp, bias, scales, out)
+        self._p = _params(a_zp, bias, scales, c_zp, relu)
+        self._args = (inp.data_ptr(), Nb, H, W, C, pad, stride, Wp.handle, ctypes.byref(self._p), out.data_ptr(),
+                      _stream())
+        self.out = out
+
+    def launch(self):
+        rc = lib.qg_conv_groupwise_u8s8_requant(*self._args)
+        if rc != OK:
+            raise QGemmError(rc, "qg_conv_groupwise_u8s8_requant")
+
+
 def gemm_u8s8_acc32(A, Bp, want_rowsum=False):
     assert A.is_cuda and A.dtype == torch.uint8 and A.dim() == 2 and A.stride(1) == 1
     M = A.shape[0]
