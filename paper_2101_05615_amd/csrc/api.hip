@@ -135,6 +135,7 @@ static int gemm_common(const uint8_t* A_dev, int M, int lda, const qg_packed_b* 
   a->K = Bp->K;
   a->kb64 = Bp->K_pad / QG_FRAG_K;
   a->nb16 = Bp->N_pad / QG_FRAG_COLS;
+  a->has_bzp = Bp->has_bzp;
   a->lda = lda;
   // vector/DMA path: 16-byte aligned rows and 32-bit byte offsets into A
   a->a_vec = aligned(A_dev, 16) && (lda % 16 == 0) && ((uint64_t)(M - 1) * (uint64_t)lda + (uint64_t)Bp->K + 4096 < (1ull << 32));

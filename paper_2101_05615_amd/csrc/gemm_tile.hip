@@ -52,11 +52,25 @@ __device__ __forceinline__ v4i load_a_chunk_slow(const uint8_t* p, int kvalid) {
   return u.v;
 }
 
+// operand list shared by the two generated loop variants (gen_tile_loop.py)
+#define QG_TILE_LOOP_OPERANDS \
+                 : [c0] "+a"(acc[0][0]), [c1] "+a"(acc[0][1]), [c2] "+a"(acc[0][2]), [c3] "+a"(acc[0][3]), \
+                   [c4] "+a"(acc[1][0]), [c5] "+a"(acc[1][1]), [c6] "+a"(acc[1][2]), [c7] "+a"(acc[1][3]), \
+                   [c8] "+a"(acc[2][0]), [c9] "+a"(acc[2][1]), [c10] "+a"(acc[2][2]), [c11] "+a"(acc[2][3]), \
+                   [c12] "+a"(acc[3][0]), [c13] "+a"(acc[3][1]), [c14] "+a"(acc[3][2]), [c15] "+a"(acc[3][3]), \
+                   [rs01] "=v"(rs01), [rs23] "=v"(rs23) \
+                 : [av01] "v"(av01), [av23] "v"(av23), [bv01] "v"(bv01), [bv23] "v"(bv23), [ard] "v"(ard), \
+                   [brd] "v"(brd), [aptr] "s"(p.A - 3072), [bptr] "s"(b_tile0), [kt] "s"(KT), [ldsdma] "s"(lds_dma), \
+                   [lds] "s"(lds_base), [bstep] "s"(b_step) \
+                 : QG_TILE_LOOP_CLOBBERS
+
 // NWM x NWN waves, each TM x TN blocks of 32 x 32.
 // FAST: A is 16-byte aligned with lda % 16 == 0, K % 64 == 0 and K >= 256, so every tile is requested with
 // global_load_lds and the loop is software-pipelined four tiles deep.  Otherwise a plain,
 // single-stage loop stages A byte-wise with bounds checks (correct for any pointer, lda and K).
-template <int MODE, bool FAST, int NWM, int NWN, int TM, int TN>
+// ROWSUM: row offsets are needed (some theta_B != 0, or the test hook asks for them); without it the
+// loop skips the byte sums and the output pipeline skips the theta_B * rowsum term of Eq. (2).
+template <int MODE, bool FAST, bool ROWSUM, int NWM, int NWN, int TM, int TN>
 __global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_gemm_args p, int tiles_m,
                                                                       int tiles_n) {
   constexpr int NW = NWM * NWN, NT = NW * 64;
@@ -180,16 +194,10 @@ __global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_g
     const unsigned lds_base = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem);
     const unsigned lds_dma = lds_base + wave * (A_DMA * 1024);
     unsigned long long rs01, rs23;
-    asm volatile(QG_TILE_LOOP_ASM
-                 : [c0] "+a"(acc[0][0]), [c1] "+a"(acc[0][1]), [c2] "+a"(acc[0][2]), [c3] "+a"(acc[0][3]),
-                   [c4] "+a"(acc[1][0]), [c5] "+a"(acc[1][1]), [c6] "+a"(acc[1][2]), [c7] "+a"(acc[1][3]),
-                   [c8] "+a"(acc[2][0]), [c9] "+a"(acc[2][1]), [c10] "+a"(acc[2][2]), [c11] "+a"(acc[2][3]),
-                   [c12] "+a"(acc[3][0]), [c13] "+a"(acc[3][1]), [c14] "+a"(acc[3][2]), [c15] "+a"(acc[3][3]),
-                   [rs01] "=v"(rs01), [rs23] "=v"(rs23)
-                 : [av01] "v"(av01), [av23] "v"(av23), [bv01] "v"(bv01), [bv23] "v"(bv23), [ard] "v"(ard),
-                   [brd] "v"(brd), [aptr] "s"(p.A - 3072), [bptr] "s"(b_tile0), [kt] "s"(KT), [ldsdma] "s"(lds_dma),
-                   [lds] "s"(lds_base), [bstep] "s"(b_step)
-                 : QG_TILE_LOOP_CLOBBERS);
+    if (ROWSUM)
+      asm volatile(QG_TILE_LOOP_ASM QG_TILE_LOOP_OPERANDS);
+    else
+      asm volatile(QG_TILE_LOOP_ASM_NOROWSUM QG_TILE_LOOP_OPERANDS);
     rs[0] = (unsigned)rs01;
     rs[1] = (unsigned)(rs01 >> 32);
     rs[2] = (unsigned)rs23;
@@ -278,7 +286,7 @@ __global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_g
 #pragma unroll
           for (int t = 0; t < 4; ++t) {
             const int i = 4 * q + t;
-            const int x = acc[mb][nb][i] + cj[i] + __mul24(nbz[i], rsum);
+            const int x = acc[mb][nb][i] + cj[i] + (ROWSUM ? __mul24(nbz[i], rsum) : 0);
             w = qg_requant_pack(x, sc[i], p.clamp_lo, p.clamp_hi, czp_f, t, w);
           }
           out[q] = w;
@@ -315,13 +323,13 @@ __global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_g
   }
 }
 
-template <int MODE, bool FAST, int NWM, int NWN, int TM, int TN>
+template <int MODE, bool FAST, bool ROWSUM, int NWM, int NWN, int TM, int TN>
 hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
   constexpr int SMEM = (FAST ? NSTAGE : 1) * (BM + BN) * BK;
   const int tiles_m = (a.M + BM - 1) / BM;
   const int tiles_n = (a.N + BN - 1) / BN;
-  auto fn = qg_gemm_tile_kernel<MODE, FAST, NWM, NWN, TM, TN>;
+  auto fn = qg_gemm_tile_kernel<MODE, FAST, ROWSUM, NWM, NWN, TM, TN>;
   hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(fn, dim3((unsigned)(tiles_m * tiles_n)), dim3(NWM * NWN * 64), SMEM, s, a, tiles_m,
@@ -334,7 +342,12 @@ hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
 hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, hipStream_t s) {
   // a.a_vec: A base and lda are multiples of 16 and every byte offset into A fits 32 bits
   const bool fast = a.a_vec && (a.K % BK == 0) && (a.K >= NSTAGE * BK);
-  if (mode == QG_MODE_REQUANT)
-    return fast ? launch<QG_MODE_REQUANT, true, QG_TILE_CFG>(a, s) : launch<QG_MODE_REQUANT, false, QG_TILE_CFG>(a, s);
-  return fast ? launch<QG_MODE_ACC32, true, QG_TILE_CFG>(a, s) : launch<QG_MODE_ACC32, false, QG_TILE_CFG>(a, s);
+  if (mode == QG_MODE_REQUANT) {
+    if (a.has_bzp)
+      return fast ? launch<QG_MODE_REQUANT, true, true, QG_TILE_CFG>(a, s)
+                  : launch<QG_MODE_REQUANT, false, true, QG_TILE_CFG>(a, s);
+    return fast ? launch<QG_MODE_REQUANT, true, false, QG_TILE_CFG>(a, s)
+                : launch<QG_MODE_REQUANT, false, false, QG_TILE_CFG>(a, s);
+  }
+  return fast ? launch<QG_MODE_ACC32, true, true, QG_TILE_CFG>(a, s) : launch<QG_MODE_ACC32, false, true, QG_TILE_CFG>(a, s);
 }

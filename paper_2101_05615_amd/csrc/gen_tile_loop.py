@@ -102,6 +102,9 @@ def reads(e, slot, ld, ks):
             e(f"ds_read_b128 {vr(B[ld] + 4 * nb)}, v{VB} offset:{nb * 2048 + ks * 512}")
 
 
+ROWSUM = True  # False: variant for weights whose zero points are all 0 (no row offsets needed)
+
+
 def prep(e, slot, ld):
     """slots 8..15: fragment f = (slot-8)//2; even slot: byte sums, odd slot: xor"""
     f, odd = (slot - 8) // 2, (slot - 8) % 2
@@ -111,7 +114,8 @@ def prep(e, slot, ld):
     if not odd:
         e(f"s_waitcnt lgkmcnt({7 - f})")
         for c in range(4):
-            e(f"v_sad_u8 v{RS + f}, v{base + c}, 0, v{RS + f}")
+            if ROWSUM:
+                e(f"v_sad_u8 v{RS + f}, v{base + c}, 0, v{RS + f}")
     else:
         for c in range(4):
             e(f"v_xor_b32 v{base + c}, s84, v{base + c}")
@@ -170,7 +174,9 @@ def tile(e, wait_vm, request, last=False):
     e("s_waitcnt lgkmcnt(0)")
 
 
-def generate():
+def generate_loop(rowsum):
+    global ROWSUM
+    ROWSUM = rowsum
     e = Emit()
     # ---- unpack operands into the fixed registers
     e(f"v_mov_b64 v[{AV}:{AV + 1}], %[av01]")
@@ -207,7 +213,8 @@ def generate():
     for f in range(4):
         e(f"s_waitcnt lgkmcnt({7 - f})")
         for c in range(4):
-            e(f"v_sad_u8 v{RS + f}, v{A[0] + 4 * f + c}, 0, v{RS + f}")
+            if ROWSUM:
+                e(f"v_sad_u8 v{RS + f}, v{A[0] + 4 * f + c}, 0, v{RS + f}")
         for c in range(4):
             e(f"v_xor_b32 v{A[0] + 4 * f + c}, s84, v{A[0] + 4 * f + c}")
     e("s_waitcnt lgkmcnt(0)")
@@ -233,12 +240,17 @@ def generate():
     e("s_nop 15")
     e(f"v_mov_b64 %[rs01], v[{RS}:{RS + 1}]")
     e(f"v_mov_b64 %[rs23], v[{RS + 2}:{RS + 3}]")
+    return e.lines
+
+
+def generate():
     clob = [f'"v{i}"' for i in range(160, 256)] + [f'"s{i}"' for i in range(84, 100)] + \
            ['"scc"', '"memory"']
-    out = ("// GENERATED by gen_tile_loop.py -- do not edit.\n"
-           "#define QG_TILE_LOOP_ASM \\\n" +
-           "".join(f'  "{l}\\n" \\\n' for l in e.lines) + "  \"\"\n"
-           "#define QG_TILE_LOOP_CLOBBERS " + ", ".join(clob) + "\n")
+    out = "// GENERATED by gen_tile_loop.py -- do not edit.\n"
+    for name, rowsum in (("QG_TILE_LOOP_ASM", True), ("QG_TILE_LOOP_ASM_NOROWSUM", False)):
+        out += (f"#define {name} \\\n" +
+                "".join(f'  "{l}\\n" \\\n' for l in generate_loop(rowsum)) + "  \"\"\n")
+    out += "#define QG_TILE_LOOP_CLOBBERS " + ", ".join(clob) + "\n"
     return out
 
 

@@ -85,6 +85,7 @@ struct qg_gemm_args {
   float clamp_lo, clamp_hi;  // lo - theta_C, 255 - theta_C
   int a_vec;             // A base and lda are multiples of 16
   int c_vec;             // C base and ldc are multiples of 16 (4 for the skinny kernel)
+  int has_bzp;           // some theta_B != 0: the row-offset term of Eq. (2) is needed
 };
 
 struct qg_conv_args {
