@@ -67,8 +67,11 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
     }
   }
 
+  // K slices are dealt to the waves rotated by the workgroup index, so that at any instant the workgroups
+  // of an XCD read DIFFERENT lines of A (all of them read all of A; unrotated they would all hit the same
+  // L2 channel at the same time)
   const int per = (p.kb64 + NWAVES - 1) / NWAVES;
-  const int kb_begin = wave * per;
+  const int kb_begin = ((wave + nb16) % NWAVES) * per;
   const int kb_end = min(p.kb64, kb_begin + per);
 
   v4i acc[MB];
