@@ -157,15 +157,17 @@ __device__ __forceinline__ void dma16(const void* gptr, unsigned char* lds_base)
 // consecutive output pixels of one group of NCB*32 channels; it requests its whole input patch (the 128
 // pixels plus pad*W+pad on either side) and its weights with global_load_lds in one burst -- one memory
 // latency per workgroup -- and every tap then comes from LDS.  Pixel p's 16-byte channel chunks are
-// stored xor (p & 7) so that the 32 consecutive pixels a half-wave reads hit different banks.
+// stored swizzled so that the 32 consecutive pixels a half-wave reads hit different banks.
 template <int R, int S, int NCB, bool HAS_BZP>
 __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel(const qg_conv_args p, int halo,
                                                                                  int nchunks_pad) {
   constexpr int RS = R * S;
   constexpr int NCH = NCB * 32;
   constexpr int CP = NCH / 16;       // 16-byte chunks per pixel
-  constexpr int SW = (CP - 1) & 7;   // swizzle mask
   constexpr int PAD_H = (R - 1) / 2, PAD_W = (S - 1) / 2;
+  // chunk swizzle of patch pixel pp: 8 consecutive pixels of one chunk index must fall into 8 different
+  // 16-byte bank groups (pixel stride 128 B: xor pp; 64 B: xor pp/2; 32 B: consecutive already)
+  auto swz = [](int pp) { return CP == 8 ? (pp & 7) : (CP == 4 ? ((pp >> 1) & 3) : 0); };
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* w_s = smem;                                        // [cb][tap] fragments
   int* cj_s = reinterpret_cast<int*>(smem + NCB * RS * QG_FRAG_BYTES);
@@ -188,7 +190,7 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
       const int c = c0 + lane;
       const int pp = c / CP, phys = c % CP;
       const int lin = min(max(lin0 + pp, 0), npix - 1);
-      dma16(p.in + (size_t)lin * p.C + ch0 + ((phys ^ (pp & SW)) << 4), patch + c0 * 16);
+      dma16(p.in + (size_t)lin * p.C + ch0 + ((phys ^ swz(pp)) << 4), patch + c0 * 16);
     }
     for (int c = tid; c < NCH; c += 256) {
       const int oc = ch0 + c;
@@ -232,7 +234,7 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
       const unsigned char* src = patch + pp * NCH;
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb) {
-        v4i x = *reinterpret_cast<const v4i*>(src + (((cb * 2 + g) ^ (pp & SW)) << 4));
+        v4i x = *reinterpret_cast<const v4i*>(src + (((cb * 2 + g) ^ swz(pp)) << 4));
         if (HAS_BZP) {
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
@@ -377,14 +379,16 @@ hipError_t qg_launch_conv_group(const qg_conv_args& a, int RS, hipStream_t s) {
   // "same" convolution: whole input patch staged in LDS, if it fits
   const int R = RS == 9 ? 3 : 1;
   if (mfma_ok && a.stride == 1 && 2 * a.pad == R - 1 && a.Ho == a.H && a.Wo == a.W) {
-    const int ncb = (a.C % 128 == 0) ? 4 : 1;
+    // 64 channels per workgroup: about 35 KB of LDS at W = 56, so four workgroups share a CU and one's
+    // request burst overlaps the others' arithmetic (128 channels halve the weight traffic but leave two)
+    const int ncb = a.C % 64 == 0 ? 2 : 1;
     const int halo = a.pad * a.W + a.pad;
     const int cp = ncb * 2;
     const int nchunks_pad = ((128 + 2 * halo) * cp + 255) / 256 * 256;
     const int smem = ncb * RS * QG_FRAG_BYTES + ncb * 32 * 12 + nchunks_pad * 16;
     if (smem <= 160 * 1024) {
-      if (ncb == 4) return RS == 9 ? launch_same<3, 3, 4>(a, smem, halo, nchunks_pad, s)
-                                   : launch_same<1, 1, 4>(a, smem, halo, nchunks_pad, s);
+      if (ncb == 2) return RS == 9 ? launch_same<3, 3, 2>(a, smem, halo, nchunks_pad, s)
+                                   : launch_same<1, 1, 2>(a, smem, halo, nchunks_pad, s);
       return RS == 9 ? launch_same<3, 3, 1>(a, smem, halo, nchunks_pad, s)
                      : launch_same<1, 1, 1>(a, smem, halo, nchunks_pad, s);
     }
