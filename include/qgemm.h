@@ -120,6 +120,66 @@ int qg_gemm_u8s8_requant(const uint8_t* A_dev, int M, int lda, const qg_packed_b
 int qg_gemm_u8s8_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp, int32_t* C32_dev,
                        int ldc, int32_t* rowsum_dev, void* workspace_dev, void* stream);
 
+/* ---- shape-specific kernels (Appendix C) ----------------------------------- */
+
+/* The paper's observation: inference GEMMs are tall, skinny or small, so a few
+ * kernels specialised by shape beat one kernel tuned for large squares; the
+ * library asks "is there a kernel for this M" and maps every other size to the
+ * nearest one.  Here the family is a table of pre-instantiated configurations;
+ * every one of them computes every shape (bit-identical results), they differ
+ * only in speed:
+ *   SKINNY16/32/64  one workgroup per 16 columns of B and per block of 16/32/64
+ *                   rows, K split over the waves of the workgroup; B streams from
+ *                   HBM straight into operand registers (bandwidth-bound shapes)
+ *   TILE64          64 x 64 workgroup tile, three LDS stages
+ *   TILE128         128 x 128
+ *   TILE128X256     128 x 256
+ *   TILE256         256 x 256, four LDS stages, hand-scheduled loop (large shapes)
+ * QG_KERNEL_AUTO picks by (M, N, K): first the rules installed with
+ * qg_dispatch_set_rules (an offline autotune writes them), then a built-in
+ * rule of thumb derived from the same measurements. */
+#define QG_KERNEL_AUTO 0
+#define QG_KERNEL_SKINNY16 1
+#define QG_KERNEL_SKINNY32 2
+#define QG_KERNEL_SKINNY64 3
+#define QG_KERNEL_TILE64 4
+#define QG_KERNEL_TILE128 5
+#define QG_KERNEL_TILE128X256 6
+#define QG_KERNEL_TILE256 7
+#define QG_KERNEL_LAST 7
+
+/* Name of a kernel id ("skinny16", "tile128x256", ...; "auto" for 0), NULL if invalid. */
+const char* qg_kernel_name(int kernel);
+
+/* The id QG_KERNEL_AUTO resolves to for this shape (never QG_KERNEL_AUTO);
+ * QG_EINVAL (negative) if a size is not positive. */
+int qg_kernel_select(int M, int N, int K);
+
+/* One line of the dispatch table: shapes with m_lo <= M <= m_hi, n_lo <= N <= n_hi
+ * and k_lo <= K <= k_hi run `kernel` (QG_KERNEL_SKINNY16..QG_KERNEL_LAST). */
+typedef struct {
+  int32_t m_lo, m_hi, n_lo, n_hi, k_lo, k_hi;
+  int32_t kernel;
+} qg_dispatch_rule;
+#define QG_MAX_DISPATCH_RULES 256
+
+/* Replace the table by n rules (HOST array, copied); the first matching rule
+ * wins, shapes no rule matches use the built-in choice; n == 0 empties the
+ * table.  Process-wide; must not run concurrently with other qg_ calls.
+ * QG_EINVAL if n is out of range or a rule is malformed (then nothing changes). */
+int qg_dispatch_set_rules(const qg_dispatch_rule* rules_host, int n);
+
+/* qg_gemm_u8s8_requant / qg_gemm_u8s8_acc32 with the kernel chosen by the caller
+ * (the autotuner and the tests use these); QG_KERNEL_AUTO behaves like the plain
+ * calls.  QG_EINVAL for an unknown id or when M needs more than 65535 row blocks
+ * of a SKINNY kernel. */
+int qg_gemm_u8s8_requant_kernel(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp,
+                                const qg_requant_params* p, uint8_t* C_dev, int ldc,
+                                void* workspace_dev, void* stream, int kernel);
+int qg_gemm_u8s8_acc32_kernel(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp,
+                              int32_t* C32_dev, int ldc, int32_t* rowsum_dev, void* workspace_dev,
+                              void* stream, int kernel);
+
 /* ---- group-wise convolution with fused im2col ----------------------------- */
 
 /* The paper names convolution without describing it; the definition used is the

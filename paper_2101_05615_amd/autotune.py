@@ -1,0 +1,107 @@
+"""Offline autotune of the shape-specific kernel family (paper Appendix C).
+
+Times every kernel of the family on the given shapes (seeded synthetic operands, resident in HBM) and
+writes a dispatch table: one rule per shape naming the fastest kernel.  `load_table()` installs such a
+table with qg_dispatch_set_rules, after which QG_KERNEL_AUTO follows it; shapes that no rule covers keep
+the library's built-in choice.
+
+    python -m paper_2101_05615_amd.autotune --shapes 128x4096x4096,2048x2048x2048 --out table.json
+    python -m paper_2101_05615_amd.autotune --grid --out table.json
+
+Every kernel returns identical bytes for a given input, so the table affects speed only.
+"""
+import argparse
+import json
+import sys
+
+GRID_M = [65, 96, 128, 192, 256, 384, 512, 1024, 2048, 4096, 8192, 32768]
+GRID_N = [64, 256, 512, 1024, 2048, 4096, 8192]
+GRID_K = [256, 1024, 4096]
+MAX_OPS = 2.5e12  # skip grid points larger than the headline square
+
+
+def time_shape(q, torch, M, N, K, kernels, min_ms=3.0, seed=0):
+    """-> {kernel name: microseconds per launch}; operands drawn on the device from a seeded generator."""
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(seed)
+    A = torch.randint(0, 256, (M, K), dtype=torch.uint8, device=dev, generator=g)
+    B = torch.randint(-128, 128, (K, N), dtype=torch.int8, device=dev, generator=g)
+    b_zp = torch.randint(-8, 9, (N,), generator=torch.Generator().manual_seed(seed)).numpy()
+    scales = torch.full((N,), 2.0 ** -12, dtype=torch.float32, device=dev)
+    Bp = q.pack_b(B, b_zp)
+    C = torch.empty((M, N), dtype=torch.uint8, device=dev)
+    out = {}
+    for name in kernels:
+        call = q.PreparedGemm(A, 128, Bp, None, scales, 0, True, C, kernel=name)
+        for _ in range(3):
+            call.launch()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n, best = 4, None
+        while True:
+            e0.record()
+            for _ in range(n):
+                call.launch()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms / n if best is None else min(best, ms / n)
+            if ms >= min_ms or n >= 4096:
+                break
+            n *= 4
+        out[name] = best * 1e3
+    Bp.close()
+    return out
+
+
+def tune(q, torch, shapes, kernels=None, log=None):
+    names = q.kernel_names()
+    kernels = kernels or [names[k] for k in range(1, q.KERNEL_LAST + 1)]
+    rows = []
+    for (M, N, K) in shapes:
+        t = time_shape(q, torch, M, N, K, kernels)
+        best = min(t, key=t.get)
+        auto = names[q.kernel_select(M, N, K)]
+        rows.append({"M": M, "N": N, "K": K, "best": best, "auto": auto, "us": t})
+        if log:
+            line = " ".join(f"{k}={v:9.1f}" for k, v in t.items())
+            log(f"{M:6d} {N:6d} {K:6d}  best {best:12s} auto {auto:12s} loss {t[auto] / t[best]:5.2f}x  {line}")
+    return rows
+
+
+def table_from_rows(rows):
+    """Exact-shape rules naming the measured winner."""
+    return [[r["M"], r["M"], r["N"], r["N"], r["K"], r["K"], r["best"]] for r in rows]
+
+
+def load_table(q, path):
+    with open(path) as f:
+        doc = json.load(f)
+    q.dispatch_set_rules([tuple(r) for r in doc["rules"]])
+    return len(doc["rules"])
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
+    ap.add_argument("--shapes", default="", help="comma-separated MxNxK")
+    ap.add_argument("--grid", action="store_true", help="the built-in grid of inference-like shapes")
+    ap.add_argument("--out", default="", help="write the dispatch table (JSON) here")
+    a = ap.parse_args(argv)
+    import torch
+    from . import qgemm as q
+    shapes = [tuple(int(v) for v in s.split("x")) for s in a.shapes.split(",") if s]
+    if a.grid:
+        shapes += [(M, N, K) for M in GRID_M for N in GRID_N for K in GRID_K if 2.0 * M * N * K <= MAX_OPS]
+    if not shapes:
+        ap.error("no shapes given")
+    rows = tune(q, torch, shapes, log=lambda s: print(s, flush=True))
+    if a.out:
+        with open(a.out, "w") as f:
+            json.dump({"device": torch.cuda.get_device_name(0), "rules": table_from_rows(rows), "measured": rows}, f,
+                      indent=1)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

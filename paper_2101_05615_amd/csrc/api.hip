@@ -2,6 +2,8 @@
 // bookkeeping and kernel selection by shape.  No device allocation, no stream
 // creation, no synchronisation happens here (paper Appendix A: the library works
 // on caller-provided buffers and leaves parallelism to the caller).
+#include <math.h>
+
 #include <new>
 #include <vector>
 
@@ -46,9 +48,112 @@ int upload_bzp(const int32_t* b_zp_host, int n_b_zp, int N, int N_pad, int32_t* 
   return QG_OK;
 }
 
+// ---- kernel selection by shape (paper Appendix C) --------------------------------------------
+qg_dispatch_rule g_rules[QG_MAX_DISPATCH_RULES];
+int g_nrules = 0;
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Built-in choice: a small cost model of every kernel, fitted to timings of the whole family over a grid of
+// shapes on MI355X (256 CUs), evaluated for the shape at hand; the cheapest estimate wins.
+//
+// Tiled kernels.  A workgroup alone on the chip needs `lat` us per 64-deep k step (one barrier plus request
+// latency) and `fix` us of launch, prologue and output pipeline.  With the chip full, each of the
+// ceil(workgroups / 256) workgroups a CU has to run costs `thr` us per k step and `epi` us of output
+// pipeline: a big tile moves the fewest LDS bytes per multiply (small `thr` per unit of work) but pays for
+// it with few, long workgroups.  The estimate is the larger of the two regimes.
+// Streaming kernels.  One workgroup per 16 columns and per row block; alone it takes fix + K * lat_k us, with
+// the chip full each workgroup costs wg + K * wg_k nanoseconds.
+struct tile_cost {
+  int kernel, bm, bn;
+  double fix, lat, thr, epi;
+};
+struct stream_cost {
+  int kernel, rows;
+  double fix, lat_k, wg, wg_k;
+};
+const tile_cost k_tile_cost[] = {
+    {QG_KERNEL_TILE64, 64, 64, 2.7, 0.25, 0.123, 0.26},
+    {QG_KERNEL_TILE128, 128, 128, 3.5, 0.35, 0.334, 1.1},
+    {QG_KERNEL_TILE128X256, 128, 256, 5.1, 0.52, 0.566, 2.0},
+    {QG_KERNEL_TILE256, 256, 256, 7.5, 0.51, 0.99, 6.0},
+};
+const stream_cost k_stream_cost[] = {
+    {QG_KERNEL_SKINNY16, 16, 3.3, 1.2e-4, 5.4, 1.39e-3},
+    {QG_KERNEL_SKINNY32, 32, 3.5, 7.5e-4, 6.0, 3.8e-3},
+    {QG_KERNEL_SKINNY64, 64, 3.3, 1.75e-3, 7.2, 7.5e-3},
+};
+
+int builtin_select(int M, int N, int K) {
+  const double kt = (double)ceil_div(K, 64);
+  int best = QG_KERNEL_TILE64;
+  double best_us = 1e300;
+  for (const stream_cost& c : k_stream_cost) {
+    const long long blocks = ceil_div(M, c.rows);
+    if (blocks > 65535) continue;
+    const double wgs = (double)blocks * (double)(2 * ceil_div(N, 32));
+    const double us = fmax(c.fix + K * c.lat_k, 2.5 + wgs * (c.wg + K * c.wg_k) * 1e-3);
+    if (us < best_us) best_us = us, best = c.kernel;
+  }
+  for (const tile_cost& c : k_tile_cost) {
+    const double wgs = (double)ceil_div(M, c.bm) * (double)ceil_div(N, c.bn);
+    const double per_cu = ceil(wgs / 256.0);
+    const double us = fmax(c.fix + kt * c.lat, 2.5 + per_cu * (kt * c.thr + c.epi));
+    if (us < best_us) best_us = us, best = c.kernel;
+  }
+  return best;
+}
+
+int select_kernel(int M, int N, int K) {
+  for (int i = 0; i < g_nrules; ++i) {
+    const qg_dispatch_rule& r = g_rules[i];
+    if (M >= r.m_lo && M <= r.m_hi && N >= r.n_lo && N <= r.n_hi && K >= r.k_lo && K <= r.k_hi) return r.kernel;
+  }
+  return builtin_select(M, N, K);
+}
+
+hipError_t launch_gemm(const qg_gemm_args& a, int mode, int kernel, hipStream_t s) {
+  if (kernel <= QG_KERNEL_SKINNY64) return qg_launch_gemm_skinny(a, mode, kernel, s);
+  return qg_launch_gemm_tile(a, mode, kernel, s);
+}
+
+// kernel id valid for this M (the streaming kernels put row blocks on the 16-bit grid dimension)
+bool kernel_ok(int kernel, int M) {
+  if (kernel < QG_KERNEL_AUTO || kernel > QG_KERNEL_LAST) return false;
+  if (kernel >= QG_KERNEL_SKINNY16 && kernel <= QG_KERNEL_SKINNY64)
+    return ceil_div(M, 16 << (kernel - QG_KERNEL_SKINNY16)) <= 65535;
+  return true;
+}
+
 }  // namespace
 
 extern "C" {
+
+const char* qg_kernel_name(int kernel) {
+  static const char* const names[] = {"auto",   "skinny16", "skinny32",    "skinny64",
+                                      "tile64", "tile128",  "tile128x256", "tile256"};
+  return (kernel >= 0 && kernel <= QG_KERNEL_LAST) ? names[kernel] : nullptr;
+}
+
+int qg_kernel_select(int M, int N, int K) {
+  if (M <= 0 || N <= 0 || K <= 0) return QG_EINVAL;
+  int k = select_kernel(M, N, K);
+  if (!kernel_ok(k, M)) k = builtin_select(M, N, K);
+  return k;
+}
+
+int qg_dispatch_set_rules(const qg_dispatch_rule* rules_host, int n) {
+  if (n < 0 || n > QG_MAX_DISPATCH_RULES) return QG_EINVAL;
+  if (n > 0 && !rules_host) return QG_ENULL;
+  for (int i = 0; i < n; ++i) {
+    const qg_dispatch_rule& r = rules_host[i];
+    if (r.m_lo > r.m_hi || r.n_lo > r.n_hi || r.k_lo > r.k_hi) return QG_EINVAL;
+    if (r.kernel < QG_KERNEL_SKINNY16 || r.kernel > QG_KERNEL_LAST) return QG_EINVAL;
+  }
+  for (int i = 0; i < n; ++i) g_rules[i] = rules_host[i];
+  g_nrules = n;
+  return QG_OK;
+}
 
 const char* qg_status_string(int code) {
   switch (code) {
@@ -145,10 +250,18 @@ static int gemm_common(const uint8_t* A_dev, int M, int lda, const qg_packed_b* 
 int qg_gemm_u8s8_requant(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp,
                          const qg_requant_params* p, uint8_t* C_dev, int ldc, void* workspace_dev,
                          void* stream) {
+  return qg_gemm_u8s8_requant_kernel(A_dev, M, lda, Bp, p, C_dev, ldc, workspace_dev, stream, QG_KERNEL_AUTO);
+}
+
+int qg_gemm_u8s8_requant_kernel(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp,
+                                const qg_requant_params* p, uint8_t* C_dev, int ldc, void* workspace_dev,
+                                void* stream, int kernel) {
   (void)workspace_dev;
   qg_gemm_args a = {};
   int rc = gemm_common(A_dev, M, lda, Bp, &a);
   if (rc != QG_OK) return rc;
+  if (!kernel_ok(kernel, M)) return QG_EINVAL;
+  if (kernel == QG_KERNEL_AUTO) kernel = qg_kernel_select(M, Bp->N, Bp->K);
   if (!C_dev) return QG_ENULL;
   rc = check_requant(p, Bp->N);
   if (rc != QG_OK) return rc;
@@ -164,31 +277,32 @@ int qg_gemm_u8s8_requant(const uint8_t* A_dev, int M, int lda, const qg_packed_b
   a.C = C_dev;
   a.ldc = ldc;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e;
-  if (M <= QG_SKINNY_MAX_M) {
-    a.c_vec = aligned(C_dev, 4) && (ldc % 4 == 0);
-    e = qg_launch_gemm_skinny(a, QG_MODE_REQUANT, s);
-  } else {
-    a.c_vec = aligned(C_dev, 16) && (ldc % 16 == 0);
-    e = qg_launch_gemm_tile(a, QG_MODE_REQUANT, s);
-  }
+  // 4-byte stores in the streaming kernels, 16-byte stores in the tiled ones
+  a.c_vec = kernel <= QG_KERNEL_SKINNY64 ? (aligned(C_dev, 4) && (ldc % 4 == 0)) : (aligned(C_dev, 16) && (ldc % 16 == 0));
+  const hipError_t e = launch_gemm(a, QG_MODE_REQUANT, kernel, s);
   return e == hipSuccess ? QG_OK : QG_ELAUNCH;
 }
 
 int qg_gemm_u8s8_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp, int32_t* C32_dev,
                        int ldc, int32_t* rowsum_dev, void* workspace_dev, void* stream) {
+  return qg_gemm_u8s8_acc32_kernel(A_dev, M, lda, Bp, C32_dev, ldc, rowsum_dev, workspace_dev, stream,
+                                   QG_KERNEL_AUTO);
+}
+
+int qg_gemm_u8s8_acc32_kernel(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp, int32_t* C32_dev,
+                              int ldc, int32_t* rowsum_dev, void* workspace_dev, void* stream, int kernel) {
   (void)workspace_dev;
   qg_gemm_args a = {};
   int rc = gemm_common(A_dev, M, lda, Bp, &a);
   if (rc != QG_OK) return rc;
+  if (!kernel_ok(kernel, M)) return QG_EINVAL;
+  if (kernel == QG_KERNEL_AUTO) kernel = qg_kernel_select(M, Bp->N, Bp->K);
   if (!C32_dev) return QG_ENULL;
   if (ldc < Bp->N) return QG_EINVAL;
   a.C32 = C32_dev;
   a.rowsum_out = rowsum_dev;
   a.ldc = ldc;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e = (M <= QG_SKINNY_MAX_M) ? qg_launch_gemm_skinny(a, QG_MODE_ACC32, s)
-                                        : qg_launch_gemm_tile(a, QG_MODE_ACC32, s);
+  const hipError_t e = launch_gemm(a, QG_MODE_ACC32, kernel, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? QG_OK : QG_ELAUNCH;
 }
 

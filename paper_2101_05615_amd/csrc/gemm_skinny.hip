@@ -1,4 +1,4 @@
-// Small-batch quantized GEMM (M <= 64): the bandwidth-bound case the paper
+// Small-batch quantized GEMM (row blocks of 16, 32 or 64): the bandwidth-bound case the paper
 // stresses ("M is sometimes very small", Appendix C; int32 accumulation for the
 // bandwidth-bound shapes, Sec. 4).  Every byte of B is used exactly once, so B
 // fragments go STRAIGHT from HBM into MFMA operand registers: the packed layout
@@ -13,16 +13,15 @@
 // K-slice of A through a private 4 KiB of LDS with global_load_lds: the request reads whole
 // 256-byte row segments (MFMA operand order would touch 16 rows x 64 B per load), and the
 // fragment is then fetched from LDS in operand order.
+//
+// M larger than the row block is covered by the second grid dimension: every row block streams
+// B again (from L2 / the memory-side cache when the blocks run close together), which beats the
+// tiled kernel only while there are too few tiles to occupy the chip.
 #include "qg_internal.h"
 
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
-
-// waves per workgroup and k blocks a wave requests at once (set per shape by the launcher)
-#ifndef QG_SKINNY_CFG
-#define QG_SKINNY_CFG 16, 4
-#endif
 
 __device__ __forceinline__ v4i load_a_chunk_slow(const uint8_t* p, int kvalid) {
   union {
@@ -51,6 +50,7 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ml = lane & 15, g = lane >> 4;
+  const int m_base = blockIdx.y * (MB * 16);  // first row of this workgroup's row block
 
   // the waves that run the output pipeline fetch its per-column constants now, not after the reduction
   const int c0 = sb * 32 + 16 * (g & 1) + 8 * sfrag + 4 * (g >> 1);  // this lane's 4 output columns
@@ -81,7 +81,7 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
   for (int mb = 0; mb < MB; ++mb) {
     acc[mb] = (v4i){0, 0, 0, 0};
     rs[mb] = 0;
-    a_row[mb] = p.A + (size_t)min(mb * 16 + ml, p.M - 1) * p.lda + g * 16;
+    a_row[mb] = p.A + (size_t)min(m_base + mb * 16 + ml, p.M - 1) * p.lda + g * 16;
   }
   const int8_t* bcol = p.Bp + (size_t)nb16 * QG_FRAG_BYTES + lane * 16;
   const size_t b_step = (size_t)p.nb16 * QG_FRAG_BYTES;  // one 64-deep slab of the packed buffer
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
         const int r = jj * 4 + (lane >> 4);
-        const uint8_t* src = p.A + (size_t)min(r, p.M - 1) * p.lda + kb * QG_FRAG_K + (((lane & 15) ^ r) << 4);
+        const uint8_t* src = p.A + (size_t)min(m_base + r, p.M - 1) * p.lda + kb * QG_FRAG_K + (((lane & 15) ^ r) << 4);
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                          (__attribute__((address_space(3))) void*)(region + jj * 1024), 16, 0, 0);
       }
@@ -155,8 +155,8 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
     rsum += rsp[(w * MB + mb) * 16 + ml];
   }
 
-  // ---- output pipeline; lane (ml, u = g) holds row mb*16+ml, 4 consecutive columns
-  const int row = mb * 16 + ml;
+  // ---- output pipeline; lane (ml, u = g) holds row m_base+mb*16+ml, 4 consecutive columns
+  const int row = m_base + mb * 16 + ml;
   if (row >= p.M || c0 >= p.N) return;
   if (MODE == QG_MODE_REQUANT) {
     unsigned out = 0;
@@ -191,19 +191,26 @@ hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
                                      hipFuncAttributeMaxDynamicSharedMemorySize, smem);
   if (e != hipSuccess) return e;
   const int nfrag = ((a.N + 31) / 32) * 2;
-  hipLaunchKernelGGL((qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH>), dim3(nfrag), dim3(NWAVES * 64), smem, s, a);
+  const int mblocks = (a.M + MB * 16 - 1) / (MB * 16);
+  if (mblocks > 65535) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH>), dim3(nfrag, mblocks), dim3(NWAVES * 64), smem, s,
+                     a);
   return hipGetLastError();
 }
 
+// waves per workgroup and k blocks a wave requests at once, per row-block height
 template <int MODE>
-hipError_t launch_mb(const qg_gemm_args& a, hipStream_t s) {
-  if (a.M <= 16) return launch<MODE, 1, QG_SKINNY_CFG>(a, s);
-  if (a.M <= 32) return launch<MODE, 2, 16, 4>(a, s);
-  return launch<MODE, 4, 16, 2>(a, s);
+hipError_t launch_mb(const qg_gemm_args& a, int kernel, hipStream_t s) {
+  switch (kernel) {
+    case QG_KERNEL_SKINNY16: return launch<MODE, 1, 16, 4>(a, s);
+    case QG_KERNEL_SKINNY32: return launch<MODE, 2, 16, 4>(a, s);
+    case QG_KERNEL_SKINNY64: return launch<MODE, 4, 16, 2>(a, s);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 }  // namespace
 
-hipError_t qg_launch_gemm_skinny(const qg_gemm_args& a, int mode, hipStream_t s) {
-  return mode == QG_MODE_REQUANT ? launch_mb<QG_MODE_REQUANT>(a, s) : launch_mb<QG_MODE_ACC32>(a, s);
+hipError_t qg_launch_gemm_skinny(const qg_gemm_args& a, int mode, int kernel, hipStream_t s) {
+  return mode == QG_MODE_REQUANT ? launch_mb<QG_MODE_REQUANT>(a, kernel, s) : launch_mb<QG_MODE_ACC32>(a, kernel, s);
 }

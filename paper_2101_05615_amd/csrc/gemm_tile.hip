@@ -4,10 +4,10 @@
 //   - A is read once from HBM, straight into LDS (global_load_lds, no register
 //     staging); when a fragment is fetched from LDS for the matrix cores it is
 //     shifted from uint8 to int8 (xor 0x80 == subtract 128: the int8 MFMA is
-//     signed x signed) and its row offsets are accumulated with v_dot4 -- the row
+//     signed x signed) and its row offsets are accumulated with v_sad_u8 -- the row
 //     offsets are a by-product of the staged block, never a second pass over A
 //     (Appendix B, "PackingWithRowOffset");
-//   - int32 accumulation on v_mfma_i32_32x32x32_i8, LDS double-buffered;
+//   - int32 accumulation on v_mfma_i32_32x32x32_i8, LDS multi-buffered;
 //   - the output pipeline (zero-point corrections of Eq. (2), bias, fp32 scale,
 //     round-to-nearest-even, clamp/ReLU) runs on the accumulators in registers and
 //     stores uint8 directly: there is no int32 C in memory.
@@ -17,10 +17,15 @@
 //   x = acc_s - (theta_A - 128) * (colsum - K theta_B) - theta_B * rowsum_s + bias,
 // i.e. "replace theta_A by theta_A - 128" with the folded column offsets.
 //
-// Tile 256 x 256 x 64, four LDS stages.  The MFMA is issued transposed (first operand = B
-// fragment, second = A fragment) so that a lane ends up with 16 consecutive
-// columns of one row (one 16-byte store); the packed-B column permutation makes
-// those columns consecutive.
+// The MFMA is issued transposed (first operand = B fragment, second = A fragment) so that a
+// lane ends up with 16 consecutive columns of one row (one 16-byte store); the packed-B column
+// permutation makes those columns consecutive.
+//
+// One template, a family of tile shapes (Appendix C: a few shape-specific kernels, every
+// problem mapped to one of them): 256 x 256 with a hand-scheduled four-stage loop for the
+// large compute-bound shapes, and 128 x 256, 128 x 128 and 64 x 64 with a compiler-scheduled
+// three-stage loop, several workgroups per CU, for shapes that would leave most CUs idle
+// (or run a single, unoverlapped round) at 256 x 256.
 #include "qg_internal.h"
 #include "tile_loop_asm.inc"
 
@@ -30,12 +35,23 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 64;      // k extent of one LDS stage = one packed fragment deep
-constexpr int NSTAGE = 4;   // LDS stages: three tiles in flight behind the one being consumed
+constexpr int NSTAGE = 4;   // LDS stages of the hand-scheduled loop: three tiles in flight behind the one being consumed
+constexpr int PSTAGE = 3;   // LDS stages of the compiler-scheduled loop
 
-// waves in M, waves in N, 32-row blocks per wave, 32-column blocks per wave
-#ifndef QG_TILE_CFG
-#define QG_TILE_CFG 2, 2, 4, 4
-#endif
+// main-loop flavours
+constexpr int PATH_GENERAL = 0;  // any pointer, lda, K: one stage, byte-wise bounds-checked A
+constexpr int PATH_ASM = 1;      // 256 x 256, hand-scheduled, four stages
+constexpr int PATH_PIPE = 2;     // any tile shape, compiler-scheduled, three stages
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// 16 bytes per lane from global memory into LDS at lds_base + lane*16 (lds_base wave-uniform)
+__device__ __forceinline__ void dma16(const void* gptr, unsigned char* lds_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
+                                   (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
+}
 
 // swizzled byte offset of 16-byte chunk kc (0..3) of row r in an A stage (rows are 64 B; the xor
 // spreads the 8 rows a quarter-wave reads at once over all 32 LDS banks)
@@ -65,13 +81,21 @@ __device__ __forceinline__ v4i load_a_chunk_slow(const uint8_t* p, int kvalid) {
                  : QG_TILE_LOOP_CLOBBERS
 
 // NWM x NWN waves, each TM x TN blocks of 32 x 32.
-// FAST: A is 16-byte aligned with lda % 16 == 0, K % 64 == 0 and K >= 256, so every tile is requested with
-// global_load_lds and the loop is software-pipelined four tiles deep.  Otherwise a plain,
+// PATH_ASM / PATH_PIPE: A is 16-byte aligned with lda % 16 == 0 and K % 64 == 0 (PATH_ASM: K >= 256), so
+// every tile is requested with global_load_lds and the loop is software-pipelined.  PATH_GENERAL: a plain,
 // single-stage loop stages A byte-wise with bounds checks (correct for any pointer, lda and K).
 // ROWSUM: row offsets are needed (some theta_B != 0, or the test hook asks for them); without it the
 // loop skips the byte sums and the output pipeline skips the theta_B * rowsum term of Eq. (2).
-template <int MODE, bool FAST, bool ROWSUM, int NWM, int NWN, int TM, int TN>
-__global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_gemm_args p, int tiles_m,
+//
+// Workgroups per CU the register budget must allow: the hand-scheduled loop owns a SIMD per wave (256
+// accumulator registers); the compiler-scheduled shapes rely on neighbours to hide latency, as many as
+// their LDS stages allow (72 / 48 / 24 KB per workgroup).
+constexpr int min_wg_per_cu(int path, int blocks) {
+  return path != PATH_PIPE ? 1 : (blocks >= 8 ? 2 : (blocks >= 4 ? 3 : 4));
+}
+
+template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN>
+__global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void qg_gemm_tile_kernel(const qg_gemm_args p, int tiles_m,
                                                                       int tiles_n) {
   constexpr int NW = NWM * NWN, NT = NW * 64;
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
@@ -116,9 +140,9 @@ __global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_g
     const int r = (wave * A_DMA + q) * 16 + (lane >> 2);
     const int kc = (lane & 3) ^ ((r >> 1) & 3);
     const int rg = min(m0 + r, p.M - 1);  // rows past M re-read the last row; never stored
-    // FAST: the asm loop uses instruction offset q*1024 (it moves the LDS slot AND the global address, so one
+    // hand-scheduled loop: it uses instruction offset q*1024 (it moves the LDS slot AND the global address, so one
     // M0 serves a group of requests) against a base of A - 3072; the per-lane offset absorbs the difference
-    a_voff[q] = (unsigned)rg * (unsigned)p.lda + kc * 16 + (FAST ? (3 - q) * 1024 : 0);
+    a_voff[q] = (unsigned)rg * (unsigned)p.lda + kc * 16 + (PATH == PATH_ASM ? (3 - q) * 1024 : 0);
   }
 #pragma unroll
   for (int q = 0; q < B_DMA; ++q)
@@ -159,10 +183,12 @@ __global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_g
   auto prep = [&](v4i (&af)[TM]) {
 #pragma unroll
     for (int mb = 0; mb < TM; ++mb) {
-      rs[mb] = __builtin_amdgcn_sad_u8(af[mb].x, 0u, rs[mb]);
-      rs[mb] = __builtin_amdgcn_sad_u8(af[mb].y, 0u, rs[mb]);
-      rs[mb] = __builtin_amdgcn_sad_u8(af[mb].z, 0u, rs[mb]);
-      rs[mb] = __builtin_amdgcn_sad_u8(af[mb].w, 0u, rs[mb]);
+      if (ROWSUM) {
+        rs[mb] = __builtin_amdgcn_sad_u8(af[mb].x, 0u, rs[mb]);
+        rs[mb] = __builtin_amdgcn_sad_u8(af[mb].y, 0u, rs[mb]);
+        rs[mb] = __builtin_amdgcn_sad_u8(af[mb].z, 0u, rs[mb]);
+        rs[mb] = __builtin_amdgcn_sad_u8(af[mb].w, 0u, rs[mb]);
+      }
       af[mb] = af[mb] ^ (int)0x80808080;
     }
   };
@@ -175,7 +201,7 @@ __global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_g
   };
   const int KT = (p.K + BK - 1) / BK;  // tiles that hold real data
   v4i a0[TM], b0[TN], a1[TM], b1[TN];
-  if (FAST) {
+  if constexpr (PATH == PATH_ASM) {
     // Tile kt lives in stage kt % 4.  In iteration kt: the first k-step runs while the fragments of
     // the second are fetched; then every wave waits until ITS requests for tile kt+1 have landed
     // (two younger tiles may still be in flight) and until its own reads of tile kt are done, the
@@ -183,7 +209,7 @@ __global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_g
     // second k-step runs while the first fragments of tile kt+1 are fetched.  The loop is one
     // hand-scheduled asm statement (gen_tile_loop.py): behind every MFMA sit at most seven other
     // instructions, so LDS reads, row sums, shifts and tile requests issue in the MFMA's shadow.
-    static_assert(NWM == 2 && NWN == 2 && TM == 4 && TN == 4 && BK == 64 && NSTAGE == 4,
+    static_assert(PATH != PATH_ASM || (NWM == 2 && NWN == 2 && TM == 4 && TN == 4 && BK == 64 && NSTAGE == 4),
                   "the scheduled loop is written for this configuration");
     const unsigned long long av01 = a_voff[0] | ((unsigned long long)a_voff[1] << 32);
     const unsigned long long av23 = a_voff[2] | ((unsigned long long)a_voff[3] << 32);
@@ -202,6 +228,43 @@ __global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_g
     rs[1] = (unsigned)(rs01 >> 32);
     rs[2] = (unsigned)rs23;
     rs[3] = (unsigned)(rs23 >> 32);
+  } else if constexpr (PATH == PATH_PIPE) {
+    // Tile kt lives in stage kt % 3; two tiles are in flight behind the one being consumed.  At the top of
+    // iteration kt a wave waits until ITS requests for tile kt have landed (younger ones may still be in
+    // flight: requests complete in order), the workgroup meets at one barrier -- which also says that
+    // every wave is done with tile kt-1 -- and that tile's stage is handed to the request for tile kt+2.
+    // Instruction order inside the iteration is the compiler's; latency is hidden by the other
+    // workgroups on the CU.
+    auto request = [&](int kt, int stage) {
+      const uint8_t* ab = p.A + (size_t)kt * BK;
+      const int8_t* bb = b_tile0 + (size_t)kt * b_step;
+      unsigned char* st = smem + stage * STAGE;
+#pragma unroll
+      for (int q = 0; q < A_DMA; ++q) dma16(ab + a_voff[q], st + (wave * A_DMA + q) * 1024);
+#pragma unroll
+      for (int q = 0; q < B_DMA; ++q) dma16(bb + b_voff[q], st + A_STAGE + (wave * B_DMA + q) * 1024);
+    };
+    static_assert(PSTAGE == 3, "the waits below assume at most two tiles in flight");
+    request(0, 0);
+    if (KT > 1) request(1, 1);
+    int stage = 0;
+    for (int kt = 0; kt < KT; ++kt) {
+      if (kt + 1 < KT)
+        wait_vmcnt<N_DMA>();
+      else
+        wait_vmcnt<0>();
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      if (kt + 2 < KT) request(kt + 2, stage == 0 ? 2 : stage - 1);
+      fetch(stage, 0, a0, b0);
+      fetch(stage, 1, a1, b1);
+      prep(a0);
+      mma(a0, b0);
+      prep(a1);
+      mma(a1, b1);
+      stage = stage == 2 ? 0 : stage + 1;
+    }
   } else {
     // General path: one stage, no overlap.  A goes through registers byte by byte with bounds checks;
     // bytes past K are stored as 0x80 (int8 zero after the shift), rows past M repeat the last row.
@@ -323,13 +386,15 @@ __global__ __launch_bounds__(NWM * NWN * 64) void qg_gemm_tile_kernel(const qg_g
   }
 }
 
-template <int MODE, bool FAST, bool ROWSUM, int NWM, int NWN, int TM, int TN>
+template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN>
 hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
-  constexpr int SMEM = (FAST ? NSTAGE : 1) * (BM + BN) * BK;
+  constexpr int STAGES = PATH == PATH_ASM ? NSTAGE : (PATH == PATH_PIPE ? PSTAGE : 1);
+  // the output pipeline's per-column constants (12 B per column) reuse the stage memory
+  constexpr int SMEM = STAGES * (BM + BN) * BK > 12 * BN ? STAGES * (BM + BN) * BK : 12 * BN;
   const int tiles_m = (a.M + BM - 1) / BM;
   const int tiles_n = (a.N + BN - 1) / BN;
-  auto fn = qg_gemm_tile_kernel<MODE, FAST, ROWSUM, NWM, NWN, TM, TN>;
+  auto fn = qg_gemm_tile_kernel<MODE, PATH, ROWSUM, NWM, NWN, TM, TN>;
   hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(fn, dim3((unsigned)(tiles_m * tiles_n)), dim3(NWM * NWN * 64), SMEM, s, a, tiles_m,
@@ -337,17 +402,28 @@ hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// requant mode with / without the row-offset term; the int32 test hook always carries the row sums
+template <int PATH, int NWM, int NWN, int TM, int TN>
+hipError_t launch_cfg(const qg_gemm_args& a, int mode, hipStream_t s) {
+  if (mode == QG_MODE_REQUANT)
+    return a.has_bzp ? launch<QG_MODE_REQUANT, PATH, true, NWM, NWN, TM, TN>(a, s)
+                     : launch<QG_MODE_REQUANT, PATH, false, NWM, NWN, TM, TN>(a, s);
+  return launch<QG_MODE_ACC32, PATH, true, NWM, NWN, TM, TN>(a, s);
+}
+
 }  // namespace
 
-hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, hipStream_t s) {
+hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, int kernel, hipStream_t s) {
   // a.a_vec: A base and lda are multiples of 16 and every byte offset into A fits 32 bits
-  const bool fast = a.a_vec && (a.K % BK == 0) && (a.K >= NSTAGE * BK);
-  if (mode == QG_MODE_REQUANT) {
-    if (a.has_bzp)
-      return fast ? launch<QG_MODE_REQUANT, true, true, QG_TILE_CFG>(a, s)
-                  : launch<QG_MODE_REQUANT, false, true, QG_TILE_CFG>(a, s);
-    return fast ? launch<QG_MODE_REQUANT, true, false, QG_TILE_CFG>(a, s)
-                : launch<QG_MODE_REQUANT, false, false, QG_TILE_CFG>(a, s);
+  const bool pipe_ok = a.a_vec && (a.K % BK == 0);
+  if (!pipe_ok) return launch_cfg<PATH_GENERAL, 2, 2, 2, 2>(a, mode, s);
+  switch (kernel) {
+    case QG_KERNEL_TILE64: return launch_cfg<PATH_PIPE, 2, 2, 1, 1>(a, mode, s);
+    case QG_KERNEL_TILE128: return launch_cfg<PATH_PIPE, 2, 2, 2, 2>(a, mode, s);
+    case QG_KERNEL_TILE128X256: return launch_cfg<PATH_PIPE, 2, 2, 2, 4>(a, mode, s);
+    case QG_KERNEL_TILE256:
+      if (a.K >= NSTAGE * BK) return launch_cfg<PATH_ASM, 2, 2, 4, 4>(a, mode, s);
+      return launch_cfg<PATH_PIPE, 2, 2, 2, 4>(a, mode, s);
+    default: return hipErrorInvalidValue;
   }
-  return fast ? launch<QG_MODE_ACC32, true, true, QG_TILE_CFG>(a, s) : launch<QG_MODE_ACC32, false, true, QG_TILE_CFG>(a, s);
 }

@@ -135,10 +135,10 @@ hipError_t qg_launch_pack_b(const int8_t* B, int K, int N, int ldb, int K_pad, i
                             int8_t* packed, int32_t* col_off, const int32_t* bzp_dev, hipStream_t s);
 hipError_t qg_launch_pack_conv_w(const int8_t* W, int G, int RS, int8_t* packed, int32_t* col_off,
                                  const int32_t* bzp_dev, int8_t* mfma_frags, hipStream_t s);
-hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, hipStream_t s);
-hipError_t qg_launch_gemm_skinny(const qg_gemm_args& a, int mode, hipStream_t s);
+// `kernel` is one of the QG_KERNEL_* ids of qgemm.h (never QG_KERNEL_AUTO: selection happens in api.hip)
+hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, int kernel, hipStream_t s);
+hipError_t qg_launch_gemm_skinny(const qg_gemm_args& a, int mode, int kernel, hipStream_t s);
 hipError_t qg_launch_conv_group(const qg_conv_args& a, int RS, hipStream_t s);
 
 #define QG_MODE_REQUANT 0
 #define QG_MODE_ACC32 1
-#define QG_SKINNY_MAX_M 64

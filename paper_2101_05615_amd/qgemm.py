@@ -19,12 +19,21 @@ EXPORTS = [
     "qg_pack_b_sizes", "qg_pack_b", "qg_packed_b_destroy", "qg_packed_b_k", "qg_packed_b_n",
     "qg_gemm_workspace_bytes", "qg_gemm_u8s8_requant", "qg_gemm_u8s8_acc32",
     "qg_pack_conv_w_sizes", "qg_pack_conv_w", "qg_conv_groupwise_u8s8_requant", "qg_status_string",
+    "qg_kernel_name", "qg_kernel_select", "qg_dispatch_set_rules", "qg_gemm_u8s8_requant_kernel",
+    "qg_gemm_u8s8_acc32_kernel",
 ]
+
+KERNEL_AUTO, KERNEL_LAST = 0, 7
+MAX_DISPATCH_RULES = 256
 
 
 class RequantParams(ctypes.Structure):
     _fields_ = [("a_zp", ctypes.c_int32), ("bias", ctypes.c_void_p), ("scales", ctypes.c_void_p),
                 ("n_scales", ctypes.c_int32), ("c_zp", ctypes.c_int32), ("relu", ctypes.c_int32)]
+
+
+class DispatchRule(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("m_lo", "m_hi", "n_lo", "n_hi", "k_lo", "k_hi", "kernel")]
 
 
 def _load():
@@ -49,6 +58,12 @@ def _load():
                                                    vp, vp]
     lib.qg_status_string.argtypes = [i]
     lib.qg_status_string.restype = ctypes.c_char_p
+    lib.qg_kernel_name.argtypes = [i]
+    lib.qg_kernel_name.restype = ctypes.c_char_p
+    lib.qg_kernel_select.argtypes = [i, i, i]
+    lib.qg_dispatch_set_rules.argtypes = [ctypes.POINTER(DispatchRule), i]
+    lib.qg_gemm_u8s8_requant_kernel.argtypes = lib.qg_gemm_u8s8_requant.argtypes + [i]
+    lib.qg_gemm_u8s8_acc32_kernel.argtypes = lib.qg_gemm_u8s8_acc32.argtypes + [i]
     return lib
 
 
@@ -134,11 +149,40 @@ def _params(a_zp, bias, scales, c_zp, relu):
                          scales.numel(), int(c_zp), int(bool(relu)))
 
 
+def kernel_names():
+    """id -> name of every kernel of the shape-specific family (0 is "auto")."""
+    return {k: lib.qg_kernel_name(k).decode() for k in range(KERNEL_LAST + 1)}
+
+
+def kernel_id(kernel):
+    """Accepts an id or a name."""
+    if isinstance(kernel, str):
+        for k, n in kernel_names().items():
+            if n == kernel:
+                return k
+        raise ValueError(f"unknown kernel {kernel!r}")
+    return int(kernel)
+
+
+def kernel_select(M, N, K):
+    k = lib.qg_kernel_select(M, N, K)
+    if k < 0:
+        raise QGemmError(k, "qg_kernel_select")
+    return k
+
+
+def dispatch_set_rules(rules):
+    """rules: iterable of (m_lo, m_hi, n_lo, n_hi, k_lo, k_hi, kernel id or name); first match wins."""
+    rules = [tuple(r[:6]) + (kernel_id(r[6]),) for r in rules]
+    arr = (DispatchRule * max(len(rules), 1))(*[DispatchRule(*r) for r in rules])
+    _check(lib.qg_dispatch_set_rules(arr, len(rules)), "qg_dispatch_set_rules")
+
+
 def gemm_workspace_bytes(M, Bp):
     return lib.qg_gemm_workspace_bytes(M, Bp.handle)
 
 
-def gemm_u8s8_requant(A, a_zp, Bp, bias, scales, c_zp, relu, out=None, workspace=None):
+def gemm_u8s8_requant(A, a_zp, Bp, bias, scales, c_zp, relu, out=None, workspace=None, kernel=KERNEL_AUTO):
     """C_u8 = requant(A_u8 . B_s8): A uint8 cuda [M, K]; returns / fills uint8 [M, N]."""
     assert A.is_cuda and A.dtype == torch.uint8 and A.dim() == 2 and A.stride(1) == 1
     M = A.shape[0]
@@ -148,8 +192,8 @@ def gemm_u8s8_requant(A, a_zp, Bp, bias, scales, c_zp, relu, out=None, workspace
     assert out.is_cuda and out.dtype == torch.uint8 and out.stride(1) == 1 and out.shape == (M, Bp.N)
     p = _params(a_zp, bias, scales, c_zp, relu)
     ws = workspace.data_ptr() if workspace is not None else None
-    _check(lib.qg_gemm_u8s8_requant(A.data_ptr(), M, A.stride(0), Bp.handle, ctypes.byref(p), out.data_ptr(),
-                                    out.stride(0), ws, _stream()), "qg_gemm_u8s8_requant")
+    _check(lib.qg_gemm_u8s8_requant_kernel(A.data_ptr(), M, A.stride(0), Bp.handle, ctypes.byref(p), out.data_ptr(),
+                                           out.stride(0), ws, _stream(), kernel_id(kernel)), "qg_gemm_u8s8_requant")
     return out
 
 
@@ -157,17 +201,17 @@ class PreparedGemm:
     """All arguments of one qg_gemm_u8s8_requant call marshalled once; `launch()` is a single ctypes call on
     the stream that was current when the object was made.  For loops that repeat the same call."""
 
-    def __init__(self, A, a_zp, Bp, bias, scales, c_zp, relu, out):
+    def __init__(self, A, a_zp, Bp, bias, scales, c_zp, relu, out, kernel=KERNEL_AUTO):
         assert A.is_cuda and A.dtype == torch.uint8 and A.dim() == 2 and A.stride(1) == 1 and A.shape[1] == Bp.K
         assert out.is_cuda and out.dtype == torch.uint8 and out.stride(1) == 1 and out.shape == (A.shape[0], Bp.N)
         self._keep = (A, Bp, bias, scales, out)
         self._p = _params(a_zp, bias, scales, c_zp, relu)
         self._args = (A.data_ptr(), A.shape[0], A.stride(0), Bp.handle, ctypes.byref(self._p), out.data_ptr(),
-                      out.stride(0), None, _stream())
+                      out.stride(0), None, _stream(), kernel_id(kernel))
         self.out = out
 
     def launch(self):
-        rc = lib.qg_gemm_u8s8_requant(*self._args)
+        rc = lib.qg_gemm_u8s8_requant_kernel(*self._args)
         if rc != OK:
             raise QGemmError(rc, "qg_gemm_u8s8_requant")
 
@@ -191,14 +235,14 @@ class PreparedConv:
             raise QGemmError(rc, "qg_conv_groupwise_u8s8_requant")
 
 
-def gemm_u8s8_acc32(A, Bp, want_rowsum=False):
+def gemm_u8s8_acc32(A, Bp, want_rowsum=False, kernel=KERNEL_AUTO):
     assert A.is_cuda and A.dtype == torch.uint8 and A.dim() == 2 and A.stride(1) == 1
     M = A.shape[0]
     out = torch.empty((M, Bp.N), dtype=torch.int32, device=A.device)
     rs = torch.empty(M, dtype=torch.int32, device=A.device) if want_rowsum else None
-    _check(lib.qg_gemm_u8s8_acc32(A.data_ptr(), M, A.stride(0), Bp.handle, out.data_ptr(), out.stride(0),
-                                  rs.data_ptr() if rs is not None else None, None, _stream()),
-           "qg_gemm_u8s8_acc32")
+    _check(lib.qg_gemm_u8s8_acc32_kernel(A.data_ptr(), M, A.stride(0), Bp.handle, out.data_ptr(), out.stride(0),
+                                         rs.data_ptr() if rs is not None else None, None, _stream(),
+                                         kernel_id(kernel)), "qg_gemm_u8s8_acc32")
     return (out, rs) if want_rowsum else out
 
 

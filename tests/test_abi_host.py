@@ -109,3 +109,52 @@ def test_column_permutation_is_a_bijection_with_16_contiguous_columns_per_lane()
             i = 8 * q + 4 * h + t
             cols.append([c for c in range(32) if slot(c) == i][0])
         assert cols == list(range(16 * h, 16 * h + 16))
+
+
+def test_kernel_selection_is_host_logic(lib):
+    """The shape -> kernel map of the shape-specific family: ids, names, built-in choice, rule table."""
+    from paper_2101_05615_amd import qgemm as q
+    names = q.kernel_names()
+    assert names[0] == "auto" and len(set(names.values())) == q.KERNEL_LAST + 1
+    assert lib.qg_kernel_name(q.KERNEL_LAST + 1) is None
+    # small batches go to the streaming kernels, one row block when M fits the smallest
+    assert names[q.kernel_select(1, 4096, 4096)] == "skinny16"
+    assert names[q.kernel_select(16, 4096, 4096)] == "skinny16"
+    for M in (17, 32, 33, 48, 64):
+        assert names[q.kernel_select(M, 4096, 4096)].startswith("skinny")
+    # the large shapes go to the large tiles, thin grids to the small ones
+    assert names[q.kernel_select(8192, 8192, 8192)] == "tile256"
+    assert names[q.kernel_select(32768, 512, 1024)] in ("tile256", "tile128x256")
+    assert names[q.kernel_select(2048, 2048, 2048)] == "tile128"
+    assert names[q.kernel_select(128, 8192, 1024)] == "tile64"
+    # the choice is always a concrete kernel
+    for shape in [(65, 64, 64), (128, 4096, 4096), (2048, 2048, 2048), (32768, 512, 1024), (1 << 20, 16, 64)]:
+        assert 1 <= q.kernel_select(*shape) <= q.KERNEL_LAST
+    for bad in [(0, 1, 1), (1, 0, 1), (1, 1, 0), (-5, 4, 4)]:
+        assert lib.qg_kernel_select(*bad) == q.EINVAL
+
+
+def test_dispatch_rule_table(lib):
+    from paper_2101_05615_amd import qgemm as q
+    big = 1 << 30
+    before = q.kernel_select(500, 500, 512)
+    try:
+        q.dispatch_set_rules([(400, 600, 1, big, 1, big, "tile64"), (1, big, 1, big, 1, big, "tile128")])
+        assert q.kernel_names()[q.kernel_select(500, 500, 512)] == "tile64"     # first match wins
+        assert q.kernel_names()[q.kernel_select(700, 500, 512)] == "tile128"
+        # malformed tables change nothing
+        R = q.DispatchRule
+        for bad in [R(5, 4, 1, 2, 1, 2, 4), R(1, 2, 1, 2, 1, 2, 0), R(1, 2, 1, 2, 1, 2, 8), R(1, 2, 3, 2, 1, 2, 4)]:
+            arr = (R * 1)(bad)
+            assert lib.qg_dispatch_set_rules(arr, 1) == q.EINVAL
+        assert lib.qg_dispatch_set_rules(None, 1) == q.ENULL
+        assert lib.qg_dispatch_set_rules(None, -1) == q.EINVAL
+        assert lib.qg_dispatch_set_rules(None, q.MAX_DISPATCH_RULES + 1) == q.EINVAL
+        assert q.kernel_names()[q.kernel_select(500, 500, 512)] == "tile64"
+        # a streaming kernel that would need more row blocks than the grid allows falls back to the built-in choice
+        q.dispatch_set_rules([(1, big, 1, big, 1, big, "skinny16")])
+        assert q.kernel_names()[q.kernel_select(16 * 65535, 64, 64)] == "skinny16"
+        assert q.kernel_names()[q.kernel_select(16 * 65535 + 1, 64, 64)] != "skinny16"
+    finally:
+        q.dispatch_set_rules([])
+    assert q.kernel_select(500, 500, 512) == before

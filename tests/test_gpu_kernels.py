@@ -1,0 +1,124 @@
+"""GPU parity of the shape-specific kernel family (paper Appendix C): every kernel id must compute every
+shape, bit-identical to the CPU oracle; the dispatch table only chooses which one runs."""
+import numpy as np
+import pytest
+
+from paper_2101_05615_amd import workloads as wl
+from gpu_util import assert_same, dev_case, oracle_gemm, say
+
+pytestmark = pytest.mark.gpu
+
+KERNELS = ["skinny16", "skinny32", "skinny64", "tile64", "tile128", "tile128x256", "tile256"]
+
+# (M, N, K): 1, 2, 3, 4 and many 64-deep tiles on the pipelined paths (K % 64 == 0), ragged M and N that
+# span several tiles of every shape, and a ragged K that takes the general path
+SHAPES = [(257, 130, 64), (130, 257, 128), (70, 64, 192), (100, 300, 256), (300, 520, 1024), (515, 260, 448),
+          (130, 100, 100), (1, 1, 64)]
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2101_05615_amd import qgemm as q
+    import oracle
+    oracle.build()
+    return q, torch, torch.device("cuda:0"), oracle
+
+
+@pytest.fixture(scope="module")
+def cases(env):
+    """One seeded case per shape with its oracle results, shared by all kernels."""
+    _, _, _, oracle = env
+    out = {}
+    for (M, N, K) in SHAPES:
+        c = wl.unsaturated(wl.random_gemm(1000 + M + 3 * N + 7 * K, M, N, K, per_channel=True, with_bias=True,
+                                          wide_zp=True))
+        out[(M, N, K)] = (c, oracle_gemm(c, oracle), oracle.acc32(c.A, c.B), oracle.rowsum(c.A))
+    return out
+
+
+def test_kernel_names(env):
+    q = env[0]
+    names = q.kernel_names()
+    assert names[0] == "auto" and [names[i] for i in range(1, 8)] == KERNELS
+    assert q.lib.qg_kernel_name(8) is None and q.lib.qg_kernel_name(-1) is None
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_every_kernel_bit_exact_on_every_shape(env, cases, kernel, shape):
+    q, torch, dev, oracle = env
+    c, want, want_acc, want_rs = cases[shape]
+    say(f"kernel {kernel} shape {shape}")
+    A, B, bias, scales, C, c_store = dev_case(c, torch, dev)
+    Bp = q.pack_b(B, c.b_zp)
+    q.gemm_u8s8_requant(A, c.a_zp, Bp, bias, scales, c.c_zp, c.relu, out=C, kernel=kernel)
+    acc, rs = q.gemm_u8s8_acc32(A, Bp, want_rowsum=True, kernel=kernel)
+    torch.cuda.synchronize()
+    assert_same(C.cpu().numpy(), want, f"{kernel} requant")
+    assert_same(acc.cpu().numpy(), want_acc, f"{kernel} acc32")
+    assert_same(rs.cpu().numpy(), want_rs, f"{kernel} rowsum")
+    tail = c_store.cpu().numpy()[c.M * c.N:]
+    assert (tail == 0xEE).all(), "bytes past C were written"
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_every_kernel_without_row_offsets(env, kernel):
+    """theta_B == 0 everywhere: the variants that skip the row-offset term."""
+    q, torch, dev, oracle = env
+    c = wl.unsaturated(wl.random_gemm(5, 200, 264, 512, per_channel=True, with_bias=True))
+    c.b_zp[:] = 0
+    want = oracle_gemm(c, oracle)
+    A, B, bias, scales, C, _ = dev_case(c, torch, dev)
+    Bp = q.pack_b(B, c.b_zp)
+    q.gemm_u8s8_requant(A, c.a_zp, Bp, bias, scales, c.c_zp, c.relu, out=C, kernel=kernel)
+    torch.cuda.synchronize()
+    assert_same(C.cpu().numpy(), want, f"{kernel} requant, theta_B = 0")
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_every_kernel_unaligned(env, kernel):
+    q, torch, dev, oracle = env
+    c = wl.unsaturated(wl.random_gemm(6, 150, 140, 256, per_channel=False, with_bias=False, wide_zp=True))
+    want = oracle_gemm(c, oracle)
+    A, B, bias, scales, C, _ = dev_case(c, torch, dev, lda_pad=3, ldc_pad=5, a_off=1, c_off=3)
+    Bp = q.pack_b(B, c.b_zp)
+    q.gemm_u8s8_requant(A, c.a_zp, Bp, bias, scales, c.c_zp, c.relu, out=C, kernel=kernel)
+    torch.cuda.synchronize()
+    assert_same(C.cpu().numpy(), want, f"{kernel} unaligned")
+
+
+def test_dispatch_rules_choose_the_kernel_and_never_the_result(env, cases):
+    q, torch, dev, oracle = env
+    shape = (300, 520, 1024)
+    c, want, _, _ = cases[shape]
+    A, B, bias, scales, C, _ = dev_case(c, torch, dev)
+    Bp = q.pack_b(B, c.b_zp)
+    builtin = q.kernel_select(*shape)
+    try:
+        for name in KERNELS:
+            q.dispatch_set_rules([(257, 1000, 1, 1 << 30, 1, 1 << 30, name)])
+            assert q.kernel_names()[q.kernel_select(*shape)] == name
+            assert q.kernel_select(256, 520, 1024) == q.kernel_id(q.kernel_names()[q.kernel_select(256, 520, 1024)])
+            C.fill_(0xEE)
+            q.gemm_u8s8_requant(A, c.a_zp, Bp, bias, scales, c.c_zp, c.relu, out=C)  # auto
+            torch.cuda.synchronize()
+            assert_same(C.cpu().numpy(), want, f"auto -> {name}")
+    finally:
+        q.dispatch_set_rules([])
+    assert q.kernel_select(*shape) == builtin
+
+
+def test_unknown_kernel_id_is_rejected(env, cases):
+    import ctypes
+    q, torch, dev, oracle = env
+    c, _, _, _ = cases[(70, 64, 192)]
+    A, B, bias, scales, C, _ = dev_case(c, torch, dev)
+    Bp = q.pack_b(B, c.b_zp)
+    p = q.RequantParams(c.a_zp, None, scales.data_ptr(), scales.numel(), c.c_zp, 0)
+    for bad in (-1, 8, 100):
+        rc = q.lib.qg_gemm_u8s8_requant_kernel(A.data_ptr(), c.M, A.stride(0), Bp.handle, ctypes.byref(p),
+                                               C.data_ptr(), C.stride(0), None, None, bad)
+        assert rc == q.EINVAL
+    torch.cuda.synchronize()
