@@ -40,6 +40,13 @@ def _load():
         lib = ctypes.CDLL(_LIB)
         lib.orc_requant_one.restype = ctypes.c_uint8
         lib.orc_requant_one.argtypes = [ctypes.c_int32, ctypes.c_float, ctypes.c_int32, ctypes.c_int]
+        lib.orc_dequant_one.restype = ctypes.c_float
+        lib.orc_dequant_one.argtypes = [ctypes.c_int32, ctypes.c_float, ctypes.c_int]
+        lib.orc_quantize_one.restype = ctypes.c_uint8
+        lib.orc_quantize_one.argtypes = [ctypes.c_float, ctypes.c_float, ctypes.c_int32]
+        vp, i = ctypes.c_void_p, ctypes.c_int
+        lib.orc_quantize_f32.argtypes = [vp, i, i, i, ctypes.c_float, ctypes.c_int32, vp, i]
+        lib.orc_dequant_f32.argtypes = [vp, i, i, vp, i, i, vp]
         _lib = lib
     return _lib
 
@@ -136,6 +143,36 @@ def gemm_u8s8_requant(A, a_zp, B, b_zp, bias, scales, c_zp, relu, return_x=False
                                        int(bool(relu)), _p(C), N, _p(x))
     _check(rc, "gemm_u8s8_requant")
     return (C, x) if return_x else C
+
+
+def dequant_one(x, scale, relu):
+    return float(_load().orc_dequant_one(int(x), float(np.float32(scale)), int(bool(relu))))
+
+
+def quantize_one(a, inv_scale, zp):
+    return int(_load().orc_quantize_one(float(np.float32(a)), float(np.float32(inv_scale)), int(zp)))
+
+
+def quantize_f32(A, inv_scale, zp):
+    """uint8 quantization of an fp32 matrix (Eq. (1) solved for the quantized value)."""
+    A = np.ascontiguousarray(np.asarray(A, dtype=np.float32))
+    assert A.ndim == 2
+    M, K = A.shape
+    out = np.empty((M, K), np.uint8)
+    _check(_load().orc_quantize_f32(_p(A), M, K, K, float(np.float32(inv_scale)), int(zp), _p(out), K),
+           "quantize_f32")
+    return out
+
+
+def gemm_u8s8_dequant_f32(A, a_zp, B, b_zp, bias, scales, relu):
+    """fp32 output: the corrected accumulator x of Eq. (2) times scale[j] = alpha_A * alpha_B[j]."""
+    N = np.asarray(B).shape[1]
+    one = np.ones(1, np.float32)
+    _, x = gemm_u8s8_requant(A, a_zp, B, b_zp, bias, one, 0, False, return_x=True)
+    s = np.ascontiguousarray(np.atleast_1d(np.asarray(scales)).astype(np.float32))
+    out = np.empty(x.shape, np.float32)
+    _check(_load().orc_dequant_f32(_p(x), x.shape[0], N, _p(s), s.size, int(bool(relu)), _p(out)), "dequant_f32")
+    return out
 
 
 def conv_out_hw(H, W, R, S, pad, stride):

@@ -25,10 +25,22 @@
  * [0,255], bias added in the int32 domain before scaling, ReLU = lower clamp
  * at theta_C) are fixed here and must be mirrored bit for bit by the GPU.
  *
+ *   - the other ends of the pipeline (Appendix B: any packing routine for A,
+ *     any output processing): activations given in fp32 and quantized by
+ *     Eq. (1) solved for X^q, and the result left in fp32, i.e. the real-domain
+ *     product alpha_A alpha_B * x of Eq. (2) without the division by alpha_C.
+ *     Readings fixed here: the caller passes 1/alpha_A and alpha_A*alpha_B as
+ *     fp32 numbers and each is applied with ONE fp32 multiply; rounding is to
+ *     nearest even; quantized activations saturate to [0,255]; ReLU on the fp32
+ *     result is max(., 0).
+ *
  * Pins (tests/test_oracle_pins.py): brute force in Python integers, the
  * identity x - bias == sum_k (A - theta_A)(B - theta_B), fp64
  * dequantize->GEMM->quantize, closed forms for all-0 / all-255 inputs,
- * hand-worked rounding and clamp examples, torch conv2d for the convolution.
+ * hand-worked rounding and clamp examples, torch conv2d for the convolution;
+ * for the fp32 ends: hand-worked ties and saturation, exact round trips of
+ * Eq. (1) on power-of-two scales, the half-step error bound of rounding, and
+ * the fp64 real-domain product within two fp32 roundings.
  * No function here is "parity unpinned".
  *
  * Build: gcc -O2 -fopenmp -ffp-contract=off -fno-fast-math -shared -fPIC
@@ -127,6 +139,58 @@ uint8_t orc_requant_one(int32_t x, float scale, int32_t c_zp, int relu) {
   const int32_t lo = relu ? c_zp : 0;
   r = fminf(fmaxf(r, (float)(lo - c_zp)), (float)(255 - c_zp));
   return (uint8_t)((int32_t)r + c_zp);
+}
+
+/* fp32 output of one corrected accumulator: the real-domain value of Eq. (2),
+ * alpha_A*alpha_B*x, with the product alpha_A*alpha_B passed as one fp32
+ * number.  Fixed sequence: int32 -> fp32 (nearest even), ONE fp32 multiply,
+ * then max(., 0) if relu. */
+float orc_dequant_one(int32_t x, float scale, int relu) {
+  volatile float f = (float)x;
+  volatile float p = f * scale;
+  float r = p;
+  if (relu && r < 0.0f) r = 0.0f;
+  return r;
+}
+
+/* out[i][j] = orc_dequant_one(x[i][j], scales[j or 0], relu); x and out are
+ * M x N row-major with leading dimension N. */
+int orc_dequant_f32(const int32_t* x, int M, int N, const float* scales,
+                    int n_scales, int relu, float* out) {
+  if (!x || !scales || !out || M <= 0 || N <= 0) return ORC_EINVAL;
+  if (n_scales != 1 && n_scales != N) return ORC_EINVAL;
+  for (int i = 0; i < M; ++i)
+    for (int j = 0; j < N; ++j)
+      out[(size_t)i * N + j] = orc_dequant_one(
+          x[(size_t)i * N + j], scales[n_scales == 1 ? 0 : j], relu);
+  return ORC_OK;
+}
+
+/* Quantization of one fp32 activation, Eq. (1) solved for the quantized value:
+ * X^q = X / alpha + theta.  The caller passes inv_scale = 1/alpha as fp32.
+ * Fixed sequence (the mirror image of the requantization above):
+ *   p = a * inv_scale        ONE fp32 multiply
+ *   r = nearbyintf(p)        round to nearest even
+ *   clamp r to [-theta, 255 - theta]   (in float, before the conversion)
+ *   result = (int)r + theta
+ * a must not be NaN. */
+uint8_t orc_quantize_one(float a, float inv_scale, int32_t zp) {
+  volatile float p = a * inv_scale;
+  float r = nearbyintf(p);
+  r = fminf(fmaxf(r, (float)(0 - zp)), (float)(255 - zp));
+  return (uint8_t)((int32_t)r + zp);
+}
+
+/* Aq[i][k] = orc_quantize_one(A[i][k], inv_scale, zp) for an M x K matrix. */
+int orc_quantize_f32(const float* A, int M, int K, int lda, float inv_scale,
+                     int32_t zp, uint8_t* Aq, int ldq) {
+  if (!A || !Aq || M <= 0 || K <= 0 || lda < K || ldq < K) return ORC_EINVAL;
+  if (zp < 0 || zp > 255) return ORC_EINVAL;
+  for (int i = 0; i < M; ++i)
+    for (int k = 0; k < K; ++k)
+      Aq[(size_t)i * ldq + k] =
+          orc_quantize_one(A[(size_t)i * lda + k], inv_scale, zp);
+  return ORC_OK;
 }
 
 /* The whole path.  For every (i,j):

@@ -341,3 +341,107 @@ def test_workload_generators_are_seeded_and_shaped():
     c5 = wl.config5_group_conv(Nb=1)
     assert c5.inp.shape == (1, 56, 56, 128) and c5.wgt.shape == (32, 3, 3, 4, 4)
     assert np.all(c5.scales.reshape(32, 4) == c5.scales.reshape(32, 4)[:, :1])
+
+
+# ---------------------------------------------------------------- fp32 ends of the pipeline
+def _hand_cases_fp32():
+    path = os.path.join(os.path.dirname(__file__), "golden", "quantize_hand_cases.txt")
+    q, d = [], []
+    for line in open(path):
+        t = line.split()
+        if not t or t[0].startswith("#"):
+            continue
+        (q if t[0] == "q" else d).append(t[1:])
+    return q, d
+
+
+def test_quantize_hand_cases(oracle_mod):
+    q, _ = _hand_cases_fp32()
+    assert len(q) >= 25
+    for a, inv, zp, want in q:
+        got = oracle_mod.quantize_one(float(a), float(inv), int(zp))
+        assert got == int(want), (a, inv, zp, got, want)
+
+
+def test_dequant_hand_cases(oracle_mod):
+    _, d = _hand_cases_fp32()
+    assert len(d) >= 10
+    for x, sc, relu, want in d:
+        got = oracle_mod.dequant_one(int(x), float(sc), int(relu))
+        assert got == float(want) and not (got == 0.0 and np.signbit(np.float32(got)) and int(relu)), (x, sc, relu, got)
+
+
+def test_quantize_round_trips_every_code_of_eq1(oracle_mod):
+    """a = alpha (q - theta) quantizes back to q for every q, when alpha is a power of two (all exact)."""
+    for alpha, zp in [(2.0 ** -5, 0), (2.0 ** -3, 128), (2.0 ** 4, 255), (1.0, 17)]:
+        qs = np.arange(256)
+        a = (alpha * (qs - zp)).astype(np.float32)
+        got = oracle_mod.quantize_f32(a[None, :], 1.0 / alpha, zp)[0]
+        assert np.array_equal(got, qs)
+
+
+def test_quantize_is_nearest_code_within_half_a_step(oracle_mod):
+    """For in-range inputs, dequantizing the code gives a value within alpha/2 (+ fp32 slack) of the input;
+    out-of-range inputs saturate to 0 / 255."""
+    rng = np.random.default_rng(5)
+    for alpha, zp in [(0.05, 100), (0.0123, 3), (1.7, 128)]:
+        inv = np.float32(1.0 / alpha)
+        lo, hi = alpha * (0 - zp), alpha * (255 - zp)
+        a = rng.uniform(lo - 5 * alpha, hi + 5 * alpha, size=(7, 400)).astype(np.float32)
+        q = oracle_mod.quantize_f32(a, inv, zp).astype(np.int64)
+        real = a.astype(np.float64) * float(inv)       # position on the code axis, before rounding
+        inside = (real > -zp - 0.49) & (real < 255 - zp + 0.49)
+        err = np.abs((q - zp) - real)
+        assert inside.sum() > 2000 and np.all(err[inside] <= 0.5 + 1e-4)
+        assert np.all(q[real <= -zp - 0.51] == 0) and np.all(q[real >= 255 - zp + 0.51] == 255)
+        # against numpy's own nearest-even rounding of the fp32 product
+        prod = (a * inv).astype(np.float32)
+        want = np.clip(np.rint(prod.astype(np.float64)), -zp, 255 - zp).astype(np.int64) + zp
+        assert np.array_equal(q, want)
+
+
+def test_quantize_ties_go_to_even(oracle_mod):
+    a = (np.arange(0, 200) + 0.5).astype(np.float32)[None, :]
+    got = oracle_mod.quantize_f32(a, 1.0, 0)[0].astype(np.int64)
+    assert np.all(got % 2 == 0) and np.array_equal(got, 2 * np.round((np.arange(200) + 0.5) / 2).astype(np.int64))
+
+
+def test_dequant_output_is_the_real_domain_product(oracle_mod):
+    """fp32 output against Eq. (2)'s left-hand side in fp64: alpha_A alpha_B sum (A - theta_A)(B - theta_B) + bias;
+    the only differences are the int32 -> fp32 conversion and the one fp32 multiply (two roundings)."""
+    for seed, per_channel in [(1, True), (2, False)]:
+        c = wl.random_gemm(seed, 23, 37, 150, per_channel=per_channel, with_bias=True, wide_zp=True)
+        got = oracle_mod.gemm_u8s8_dequant_f32(c.A, c.a_zp, c.B, c.b_zp, c.bias, c.scales, False)
+        zb = np.broadcast_to(np.asarray(c.b_zp, np.int64), (c.N,))
+        x = (c.A.astype(np.int64) - c.a_zp) @ (c.B.astype(np.int64) - zb[None, :]) + c.bias.astype(np.int64)[None, :]
+        sc = np.broadcast_to(c.scales.astype(np.float64), (c.N,))
+        real = x.astype(np.float64) * sc[None, :]
+        assert got.dtype == np.float32 and got.shape == (c.M, c.N)
+        rel = np.abs(got.astype(np.float64) - real) <= 2.0 ** -22 * np.abs(real) + 1e-45
+        assert rel.all()
+        # exact when the scale is a power of two and |x| < 2^24
+        assert np.abs(x).max() < 2 ** 24
+        got2 = oracle_mod.gemm_u8s8_dequant_f32(c.A, c.a_zp, c.B, c.b_zp, c.bias, np.float32(2.0 ** -9), False)
+        assert np.array_equal(got2.astype(np.float64), x * 2.0 ** -9)
+        # ReLU = max(., 0) with no negative zero
+        got3 = oracle_mod.gemm_u8s8_dequant_f32(c.A, c.a_zp, c.B, c.b_zp, c.bias, np.float32(2.0 ** -9), True)
+        assert np.array_equal(got3.astype(np.float64), np.maximum(x, 0) * 2.0 ** -9)
+        assert not np.signbit(got3).any()
+
+
+def test_fp32_in_fp32_out_composite_approximates_the_real_gemm(oracle_mod):
+    """Quantize fp32 activations, multiply, leave the result in fp32: the result approximates the real product
+    A_real (alpha_B (B - theta_B)) within the activation quantization error bound K * alpha_A/2 * max|B_real|."""
+    rng = np.random.default_rng(9)
+    M, N, K = 9, 14, 64
+    alpha_a, zp_a, alpha_b = 0.02, 90, 0.01
+    a_real = rng.uniform(alpha_a * (0 - zp_a), alpha_a * (255 - zp_a), size=(M, K)).astype(np.float32)
+    B = rng.integers(-128, 128, size=(K, N)).astype(np.int8)
+    b_zp = np.array([3], np.int32)
+    Aq = oracle_mod.quantize_f32(a_real, np.float32(1.0 / alpha_a), zp_a)
+    out = oracle_mod.gemm_u8s8_dequant_f32(Aq, zp_a, B, b_zp, None, np.float32(alpha_a * alpha_b), False)
+    b_real = alpha_b * (B.astype(np.float64) - 3)
+    want = a_real.astype(np.float64) @ b_real
+    bound = K * (alpha_a / 2) * np.abs(b_real).max() * 1.01
+    assert np.abs(out - want).max() <= bound
+    assert np.abs(out - want).max() > 0  # and it is a quantized result, not a copy of the fp64 one
