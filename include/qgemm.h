@@ -18,8 +18,9 @@
  *
  * "dev" pointers are device (HBM) addresses valid on the current HIP device;
  * "host" pointers are ordinary host memory.  `stream` is a hipStream_t passed
- * as void* (NULL = the default stream).  Every call that launches work is
- * asynchronous: a 0 return means "enqueued on `stream`".
+ * as void* (NULL = the default stream).  Every run-time call is asynchronous:
+ * a 0 return means "enqueued on `stream`".  The two offline packing calls
+ * wait once for `stream` (they stage the host zero points through it).
  *
  * Errors: every function returns 0 on success or one of the negative QG_E*
  * codes; nothing is printed, nothing aborts.  On error no output is written.
@@ -179,6 +180,60 @@ int qg_gemm_u8s8_requant_kernel(const uint8_t* A_dev, int M, int lda, const qg_p
 int qg_gemm_u8s8_acc32_kernel(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp,
                               int32_t* C32_dev, int ldc, int32_t* rowsum_dev, void* workspace_dev,
                               void* stream, int kernel);
+
+/* ---- the other ends of the pipeline (Appendix B) --------------------------- */
+
+/* The paper builds a pipeline from any packing routine for A and any output
+ * processing around the same core kernels.  Two more ends are provided here:
+ * fp32 activations that are quantized by the library, and an fp32 result. */
+
+/* Output pipeline that leaves the result in fp32: the real-domain value of
+ * Eq. (2), alpha_A alpha_B[j] * x, with x the corrected accumulator of
+ * qg_requant_params (zero-point terms and bias included):
+ *   C[i,j] = (float)x * scale[j]        ONE IEEE fp32 multiply after the
+ *                                       int32 -> fp32 conversion (nearest even)
+ *   relu != 0:  C[i,j] = max(C[i,j], 0) */
+typedef struct {
+  int32_t a_zp;          /* theta_A, 0..255                                   */
+  const int32_t* bias;   /* dev, N entries in accumulator units, or NULL      */
+  const float* scales;   /* dev, n_scales entries: alpha_A * alpha_B[j]       */
+  int32_t n_scales;      /* 1 or N                                            */
+  int32_t relu;          /* 0 or 1                                            */
+} qg_dequant_params;
+
+/* As qg_gemm_u8s8_requant, with the fp32 output pipeline above.
+ *   C_dev  dev, float, row-major M x N, ldc >= N in ELEMENTS; must not alias A
+ * 16-byte aligned C_dev with ldc a multiple of 4 takes the vector store path.
+ * kernel: QG_KERNEL_AUTO or a kernel id. */
+int qg_gemm_u8s8_dequant_f32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp,
+                             const qg_dequant_params* p, float* C_dev, int ldc, void* workspace_dev,
+                             void* stream, int kernel);
+
+/* Quantization of fp32 activations, Eq. (1) solved for the quantized value:
+ *   Aq[i,k] = clamp(rne(A[i,k] * inv_scale), -theta_A, 255 - theta_A) + theta_A
+ * (inv_scale = 1 / alpha_A passed by the caller; ONE fp32 multiply; rne = round
+ * to nearest even; the clamp happens in float).  A must hold no NaN; +-inf
+ * saturate.  The fp32 matrix is read once; this is the bandwidth-bound
+ * "packing" pass of the pipeline, one launch.
+ *   A_dev   dev, float, row-major M x K, lda >= K (elements)
+ *   Aq_dev  dev, uint8, row-major M x K, ldq >= K; must not alias A
+ * No alignment required; 16-byte aligned A_dev with lda % 4 == 0 and 4-byte
+ * aligned Aq_dev with ldq % 4 == 0 take the vector path. */
+int qg_quantize_a_f32(const float* A_dev, int M, int K, int lda, float inv_scale, int a_zp,
+                      uint8_t* Aq_dev, int ldq, void* stream);
+
+/* fp32 activations in, either output: qg_quantize_a_f32 into the workspace
+ * followed by the GEMM on the quantized copy (two launches on `stream`);
+ * p->a_zp is the zero point of the quantization and of Eq. (2).
+ * workspace_dev: qg_gemm_f32_workspace_bytes(M, Bp) bytes, 16-byte aligned,
+ * QG_EWORKSPACE if NULL.  The quantized copy stays in the workspace. */
+size_t qg_gemm_f32_workspace_bytes(int M, const qg_packed_b* Bp);
+int qg_gemm_f32s8_requant(const float* A_dev, int M, int lda, float a_inv_scale, const qg_packed_b* Bp,
+                          const qg_requant_params* p, uint8_t* C_dev, int ldc, void* workspace_dev,
+                          void* stream, int kernel);
+int qg_gemm_f32s8_dequant_f32(const float* A_dev, int M, int lda, float a_inv_scale,
+                              const qg_packed_b* Bp, const qg_dequant_params* p, float* C_dev, int ldc,
+                              void* workspace_dev, void* stream, int kernel);
 
 /* ---- group-wise convolution with fused im2col ----------------------------- */
 

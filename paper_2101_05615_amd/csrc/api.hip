@@ -306,6 +306,100 @@ int qg_gemm_u8s8_acc32_kernel(const uint8_t* A_dev, int M, int lda, const qg_pac
   return e == hipSuccess ? QG_OK : QG_ELAUNCH;
 }
 
+static int check_dequant(const qg_dequant_params* p, int N) {
+  if (!p) return QG_ENULL;
+  if (!p->scales) return QG_ENULL;
+  if (p->a_zp < 0 || p->a_zp > 255) return QG_EINVAL;
+  if (p->n_scales != 1 && p->n_scales != N) return QG_EINVAL;
+  if (p->relu != 0 && p->relu != 1) return QG_EINVAL;
+  return QG_OK;
+}
+
+int qg_gemm_u8s8_dequant_f32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp,
+                             const qg_dequant_params* p, float* C_dev, int ldc, void* workspace_dev,
+                             void* stream, int kernel) {
+  (void)workspace_dev;
+  qg_gemm_args a = {};
+  int rc = gemm_common(A_dev, M, lda, Bp, &a);
+  if (rc != QG_OK) return rc;
+  if (!kernel_ok(kernel, M)) return QG_EINVAL;
+  if (kernel == QG_KERNEL_AUTO) kernel = qg_kernel_select(M, Bp->N, Bp->K);
+  if (!C_dev) return QG_ENULL;
+  rc = check_dequant(p, Bp->N);
+  if (rc != QG_OK) return rc;
+  if (ldc < Bp->N) return QG_EINVAL;
+  if (!aligned(C_dev, 4)) return QG_EALIGN;
+  a.bias = p->bias;
+  a.scales = p->scales;
+  a.scale_stride = p->n_scales == 1 ? 0 : 1;
+  a.a_zp_m128 = p->a_zp - 128;
+  a.relu_lo = p->relu ? 0.0f : -INFINITY;
+  a.Cf = C_dev;
+  a.ldc = ldc;
+  a.c_vec = aligned(C_dev, 16) && (ldc % 4 == 0);
+  const hipError_t e = launch_gemm(a, QG_MODE_DEQUANT, kernel, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? QG_OK : QG_ELAUNCH;
+}
+
+int qg_quantize_a_f32(const float* A_dev, int M, int K, int lda, float inv_scale, int a_zp, uint8_t* Aq_dev,
+                      int ldq, void* stream) {
+  if (!A_dev || !Aq_dev) return QG_ENULL;
+  if (M <= 0 || K <= 0 || lda < K || ldq < K) return QG_EINVAL;
+  if (a_zp < 0 || a_zp > 255 || !(inv_scale > 0.0f) || !isfinite(inv_scale)) return QG_EINVAL;
+  if (!aligned(A_dev, 4)) return QG_EALIGN;
+  const hipError_t e =
+      qg_launch_quantize_a(A_dev, M, K, lda, inv_scale, a_zp, Aq_dev, ldq, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? QG_OK : QG_ELAUNCH;
+}
+
+// row pitch of the quantized copy in the workspace: whole 16-byte chunks, so the copy takes the vector paths
+static int f32_ldq(const qg_packed_b* Bp) { return qg_round_up(Bp->K, 16); }
+
+size_t qg_gemm_f32_workspace_bytes(int M, const qg_packed_b* Bp) {
+  if (!Bp || M <= 0 || Bp->kind != QG_KIND_GEMM) return 0;
+  return (size_t)M * (size_t)f32_ldq(Bp);
+}
+
+static int quantize_into_workspace(const float* A_dev, int M, int lda, float a_inv_scale, const qg_packed_b* Bp,
+                                   int a_zp, void* workspace_dev, void* stream) {
+  if (!A_dev || !Bp) return QG_ENULL;
+  if (Bp->kind != QG_KIND_GEMM || Bp->version != QG_LAYOUT_VERSION) return QG_EINVAL;
+  if (!workspace_dev) return QG_EWORKSPACE;
+  if (!aligned(workspace_dev, 16)) return QG_EALIGN;
+  return qg_quantize_a_f32(A_dev, M, Bp->K, lda, a_inv_scale, a_zp, static_cast<uint8_t*>(workspace_dev),
+                           f32_ldq(Bp), stream);
+}
+
+int qg_gemm_f32s8_requant(const float* A_dev, int M, int lda, float a_inv_scale, const qg_packed_b* Bp,
+                          const qg_requant_params* p, uint8_t* C_dev, int ldc, void* workspace_dev,
+                          void* stream, int kernel) {
+  // every check of the second stage first, so that an error leaves nothing enqueued
+  if (!Bp || !p || !C_dev) return QG_ENULL;
+  if (Bp->kind != QG_KIND_GEMM || Bp->version != QG_LAYOUT_VERSION) return QG_EINVAL;
+  int rc = check_requant(p, Bp->N);
+  if (rc != QG_OK) return rc;
+  if (M <= 0 || ldc < Bp->N || !kernel_ok(kernel, M)) return QG_EINVAL;
+  rc = quantize_into_workspace(A_dev, M, lda, a_inv_scale, Bp, p->a_zp, workspace_dev, stream);
+  if (rc != QG_OK) return rc;
+  return qg_gemm_u8s8_requant_kernel(static_cast<const uint8_t*>(workspace_dev), M, f32_ldq(Bp), Bp, p, C_dev, ldc,
+                                     nullptr, stream, kernel);
+}
+
+int qg_gemm_f32s8_dequant_f32(const float* A_dev, int M, int lda, float a_inv_scale, const qg_packed_b* Bp,
+                              const qg_dequant_params* p, float* C_dev, int ldc, void* workspace_dev,
+                              void* stream, int kernel) {
+  if (!Bp || !p || !C_dev) return QG_ENULL;
+  if (Bp->kind != QG_KIND_GEMM || Bp->version != QG_LAYOUT_VERSION) return QG_EINVAL;
+  int rc = check_dequant(p, Bp->N);
+  if (rc != QG_OK) return rc;
+  if (M <= 0 || ldc < Bp->N || !kernel_ok(kernel, M)) return QG_EINVAL;
+  if (!aligned(C_dev, 4)) return QG_EALIGN;
+  rc = quantize_into_workspace(A_dev, M, lda, a_inv_scale, Bp, p->a_zp, workspace_dev, stream);
+  if (rc != QG_OK) return rc;
+  return qg_gemm_u8s8_dequant_f32(static_cast<const uint8_t*>(workspace_dev), M, f32_ldq(Bp), Bp, p, C_dev, ldc,
+                                  nullptr, stream, kernel);
+}
+
 int qg_pack_conv_w_sizes(int G, int R, int S, int Cg, int Og, size_t* packed_bytes,
                          size_t* col_offsets_bytes) {
   if (!packed_bytes || !col_offsets_bytes) return QG_ENULL;

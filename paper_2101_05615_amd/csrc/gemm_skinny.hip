@@ -62,8 +62,8 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
       const int col = c0 + r;  // col_off / bzp are padded to N_pad, bias / scales are not
       ep_co[r] = p.col_off[col];
       ep_bz[r] = p.bzp[col];
-      ep_bias[r] = (MODE == QG_MODE_REQUANT && p.bias != nullptr && col < p.N) ? p.bias[col] : 0;
-      ep_sc[r] = (MODE == QG_MODE_REQUANT && col < p.N) ? p.scales[(size_t)col * p.scale_stride] : 1.0f;
+      ep_bias[r] = (MODE != QG_MODE_ACC32 && p.bias != nullptr && col < p.N) ? p.bias[col] : 0;
+      ep_sc[r] = (MODE != QG_MODE_ACC32 && col < p.N) ? p.scales[(size_t)col * p.scale_stride] : 1.0f;
     }
   }
 
@@ -173,6 +173,21 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
       for (int r = 0; r < 4; ++r)
         if (c0 + r < p.N) dst[r] = (uint8_t)(out >> (8 * r));
     }
+  } else if (MODE == QG_MODE_DEQUANT) {
+    float out[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int x = sum[r] + ep_bias[r] - p.a_zp_m128 * ep_co[r] - ep_bz[r] * rsum;
+      out[r] = qg_dequant_one(x, ep_sc[r], p.relu_lo);
+    }
+    float* dst = p.Cf + (size_t)row * p.ldc + c0;
+    if (p.c_vec && c0 + 4 <= p.N) {
+      *reinterpret_cast<float4*>(dst) = make_float4(out[0], out[1], out[2], out[3]);
+    } else {
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        if (c0 + r < p.N) dst[r] = out[r];
+    }
   } else {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -212,5 +227,7 @@ hipError_t launch_mb(const qg_gemm_args& a, int kernel, hipStream_t s) {
 }  // namespace
 
 hipError_t qg_launch_gemm_skinny(const qg_gemm_args& a, int mode, int kernel, hipStream_t s) {
-  return mode == QG_MODE_REQUANT ? launch_mb<QG_MODE_REQUANT>(a, kernel, s) : launch_mb<QG_MODE_ACC32>(a, kernel, s);
+  if (mode == QG_MODE_REQUANT) return launch_mb<QG_MODE_REQUANT>(a, kernel, s);
+  if (mode == QG_MODE_DEQUANT) return launch_mb<QG_MODE_DEQUANT>(a, kernel, s);
+  return launch_mb<QG_MODE_ACC32>(a, kernel, s);
 }

@@ -10,7 +10,8 @@
 //   - int32 accumulation on v_mfma_i32_32x32x32_i8, LDS multi-buffered;
 //   - the output pipeline (zero-point corrections of Eq. (2), bias, fp32 scale,
 //     round-to-nearest-even, clamp/ReLU) runs on the accumulators in registers and
-//     stores uint8 directly: there is no int32 C in memory.
+//     stores uint8 directly: there is no int32 C in memory.  The same pipeline can
+//     instead leave the result in fp32 (Appendix B: any output processing).
 //
 // Shift algebra: with A_s = A_u - 128, rowsum_s = rowsum_u - 128 K and
 // acc_s = acc_u - 128 colsum, the corrected accumulator of Eq. (2) is
@@ -309,7 +310,7 @@ __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void 
   for (int t = tid; t < BN; t += NT) {
     const int col = n0 + t;  // col_off / bzp are padded to N_pad, bias / scales are not
     const int co = p.col_off[col], bz = p.bzp[col];
-    if (MODE == QG_MODE_REQUANT) {
+    if (MODE != QG_MODE_ACC32) {
       const int b = (p.bias != nullptr && col < p.N) ? p.bias[col] : 0;
       cj_s[t] = b - p.a_zp_m128 * co;
       sc_s[t] = (col < p.N) ? p.scales[(size_t)col * p.scale_stride] : 1.0f;
@@ -323,7 +324,7 @@ __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void 
   // ---- epilogue straight from the accumulators.  Lane (l32, lg) of block (mb, nb) holds row
   // 32*mb + l32 and the 16 consecutive columns 32*nb + 16*lg .. +15; the per-column constants of a
   // column block are fetched once and reused for the wave's TM row blocks.
-  if (MODE == QG_MODE_REQUANT) {
+  if (MODE != QG_MODE_ACC32) {
     const bool full_cols = p.c_vec && (n0 + BN <= p.N);  // uniform: every 16-byte store is in range
     const float czp_f = (float)p.c_zp;
 #pragma unroll
@@ -342,26 +343,48 @@ __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void 
       for (int mb = 0; mb < TM; ++mb) {
         const int row = m0 + (wave_m * TM + mb) * 32 + l32;
         const int rsum = rsum_s[mb];
-        unsigned out[4];
+        if (MODE == QG_MODE_REQUANT) {
+          unsigned out[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          unsigned w = 0;
+          for (int q = 0; q < 4; ++q) {
+            unsigned w = 0;
 #pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            const int i = 4 * q + t;
-            const int x = acc[mb][nb][i] + cj[i] + (ROWSUM ? __mul24(nbz[i], rsum) : 0);
-            w = qg_requant_pack(x, sc[i], p.clamp_lo, p.clamp_hi, czp_f, t, w);
+            for (int t = 0; t < 4; ++t) {
+              const int i = 4 * q + t;
+              const int x = acc[mb][nb][i] + cj[i] + (ROWSUM ? __mul24(nbz[i], rsum) : 0);
+              w = qg_requant_pack(x, sc[i], p.clamp_lo, p.clamp_hi, czp_f, t, w);
+            }
+            out[q] = w;
           }
-          out[q] = w;
-        }
-        if (row < p.M) {
-          uint8_t* dst = p.C + (size_t)row * p.ldc + col;
-          if (full_cols) {
-            *reinterpret_cast<uint4*>(dst) = make_uint4(out[0], out[1], out[2], out[3]);
-          } else {
+          if (row < p.M) {
+            uint8_t* dst = p.C + (size_t)row * p.ldc + col;
+            if (full_cols) {
+              *reinterpret_cast<uint4*>(dst) = make_uint4(out[0], out[1], out[2], out[3]);
+            } else {
 #pragma unroll
-            for (int i = 0; i < 16; ++i)
-              if (col + i < p.N) dst[i] = (uint8_t)(out[i >> 2] >> ((i & 3) * 8));
+              for (int i = 0; i < 16; ++i)
+                if (col + i < p.N) dst[i] = (uint8_t)(out[i >> 2] >> ((i & 3) * 8));
+            }
+          }
+        } else {
+          // fp32 output: 16 consecutive floats per lane, four 16-byte stores
+          float out[16];
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int x = acc[mb][nb][i] + cj[i] + (ROWSUM ? __mul24(nbz[i], rsum) : 0);
+            out[i] = qg_dequant_one(x, sc[i], p.relu_lo);
+          }
+          if (row < p.M) {
+            float* dst = p.Cf + (size_t)row * p.ldc + col;
+            if (full_cols) {
+#pragma unroll
+              for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<float4*>(dst + 4 * q) = make_float4(out[4 * q], out[4 * q + 1], out[4 * q + 2], out[4 * q + 3]);
+            } else {
+#pragma unroll
+              for (int i = 0; i < 16; ++i)
+                if (col + i < p.N) dst[i] = out[i];
+            }
           }
         }
       }
@@ -408,6 +431,9 @@ hipError_t launch_cfg(const qg_gemm_args& a, int mode, hipStream_t s) {
   if (mode == QG_MODE_REQUANT)
     return a.has_bzp ? launch<QG_MODE_REQUANT, PATH, true, NWM, NWN, TM, TN>(a, s)
                      : launch<QG_MODE_REQUANT, PATH, false, NWM, NWN, TM, TN>(a, s);
+  if (mode == QG_MODE_DEQUANT)
+    return a.has_bzp ? launch<QG_MODE_DEQUANT, PATH, true, NWM, NWN, TM, TN>(a, s)
+                     : launch<QG_MODE_DEQUANT, PATH, false, NWM, NWN, TM, TN>(a, s);
   return launch<QG_MODE_ACC32, PATH, true, NWM, NWN, TM, TN>(a, s);
 }
 

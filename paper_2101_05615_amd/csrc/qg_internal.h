@@ -74,6 +74,7 @@ struct qg_gemm_args {
   const float* scales;
   uint8_t* C;            // requant output
   int32_t* C32;          // acc32 output
+  float* Cf;             // fp32 output (dequant mode)
   int32_t* rowsum_out;   // acc32 mode, may be null
   int M, N, K;
   int kb64;              // K_pad / 64
@@ -83,8 +84,9 @@ struct qg_gemm_args {
   int a_zp_m128;         // theta_A - 128
   int c_zp;
   float clamp_lo, clamp_hi;  // lo - theta_C, 255 - theta_C
+  float relu_lo;         // dequant mode: 0 with ReLU, -inf without
   int a_vec;             // A base and lda are multiples of 16
-  int c_vec;             // C base and ldc are multiples of 16 (4 for the skinny kernel)
+  int c_vec;             // output base and row pitch are multiples of 16 bytes (uint8 output of the streaming kernels: 4)
   int has_bzp;           // some theta_B != 0: the row-offset term of Eq. (2) is needed
 };
 
@@ -128,6 +130,12 @@ __device__ __forceinline__ unsigned qg_requant_pack(int x, float sc, float lo, f
   const float c = __builtin_amdgcn_fmed3f(r, lo, hi) + czp_f;
   return __builtin_amdgcn_cvt_pk_u8_f32(c, pos, word);
 }
+// fp32 output of one corrected accumulator: int32 -> fp32 (nearest even), ONE fp32 multiply, optional
+// max(., 0) (lo = 0 with ReLU, -inf without; a select, so no NaN-canonicalising extra instruction).
+__device__ __forceinline__ float qg_dequant_one(int x, float sc, float lo) {
+  const float v = (float)x * sc;
+  return v < lo ? lo : v;
+}
 #endif
 
 // launchers (each returns a hipError_t from hipGetLastError after the launch)
@@ -138,7 +146,10 @@ hipError_t qg_launch_pack_conv_w(const int8_t* W, int G, int RS, int8_t* packed,
 // `kernel` is one of the QG_KERNEL_* ids of qgemm.h (never QG_KERNEL_AUTO: selection happens in api.hip)
 hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, int kernel, hipStream_t s);
 hipError_t qg_launch_gemm_skinny(const qg_gemm_args& a, int mode, int kernel, hipStream_t s);
+hipError_t qg_launch_quantize_a(const float* A, int M, int K, int lda, float inv_scale, int a_zp, uint8_t* Aq,
+                                int ldq, hipStream_t s);
 hipError_t qg_launch_conv_group(const qg_conv_args& a, int RS, hipStream_t s);
 
 #define QG_MODE_REQUANT 0
 #define QG_MODE_ACC32 1
+#define QG_MODE_DEQUANT 2

@@ -20,7 +20,8 @@ EXPORTS = [
     "qg_gemm_workspace_bytes", "qg_gemm_u8s8_requant", "qg_gemm_u8s8_acc32",
     "qg_pack_conv_w_sizes", "qg_pack_conv_w", "qg_conv_groupwise_u8s8_requant", "qg_status_string",
     "qg_kernel_name", "qg_kernel_select", "qg_dispatch_set_rules", "qg_gemm_u8s8_requant_kernel",
-    "qg_gemm_u8s8_acc32_kernel",
+    "qg_gemm_u8s8_acc32_kernel", "qg_gemm_u8s8_dequant_f32", "qg_quantize_a_f32", "qg_gemm_f32_workspace_bytes",
+    "qg_gemm_f32s8_requant", "qg_gemm_f32s8_dequant_f32",
 ]
 
 KERNEL_AUTO, KERNEL_LAST = 0, 7
@@ -30,6 +31,11 @@ MAX_DISPATCH_RULES = 256
 class RequantParams(ctypes.Structure):
     _fields_ = [("a_zp", ctypes.c_int32), ("bias", ctypes.c_void_p), ("scales", ctypes.c_void_p),
                 ("n_scales", ctypes.c_int32), ("c_zp", ctypes.c_int32), ("relu", ctypes.c_int32)]
+
+
+class DequantParams(ctypes.Structure):
+    _fields_ = [("a_zp", ctypes.c_int32), ("bias", ctypes.c_void_p), ("scales", ctypes.c_void_p),
+                ("n_scales", ctypes.c_int32), ("relu", ctypes.c_int32)]
 
 
 class DispatchRule(ctypes.Structure):
@@ -64,6 +70,13 @@ def _load():
     lib.qg_dispatch_set_rules.argtypes = [ctypes.POINTER(DispatchRule), i]
     lib.qg_gemm_u8s8_requant_kernel.argtypes = lib.qg_gemm_u8s8_requant.argtypes + [i]
     lib.qg_gemm_u8s8_acc32_kernel.argtypes = lib.qg_gemm_u8s8_acc32.argtypes + [i]
+    f = ctypes.c_float
+    lib.qg_gemm_u8s8_dequant_f32.argtypes = [vp, i, i, vp, ctypes.POINTER(DequantParams), vp, i, vp, vp, i]
+    lib.qg_quantize_a_f32.argtypes = [vp, i, i, i, f, i, vp, i, vp]
+    lib.qg_gemm_f32_workspace_bytes.argtypes = [i, vp]
+    lib.qg_gemm_f32_workspace_bytes.restype = sz
+    lib.qg_gemm_f32s8_requant.argtypes = [vp, i, i, f, vp, ctypes.POINTER(RequantParams), vp, i, vp, vp, i]
+    lib.qg_gemm_f32s8_dequant_f32.argtypes = [vp, i, i, f, vp, ctypes.POINTER(DequantParams), vp, i, vp, vp, i]
     return lib
 
 
@@ -244,6 +257,83 @@ def gemm_u8s8_acc32(A, Bp, want_rowsum=False, kernel=KERNEL_AUTO):
                                          rs.data_ptr() if rs is not None else None, None, _stream(),
                                          kernel_id(kernel)), "qg_gemm_u8s8_acc32")
     return (out, rs) if want_rowsum else out
+
+
+def _dq_params(a_zp, bias, scales, relu):
+    assert scales.is_cuda and scales.dtype == torch.float32 and scales.is_contiguous()
+    if bias is not None:
+        assert bias.is_cuda and bias.dtype == torch.int32 and bias.is_contiguous()
+    return DequantParams(int(a_zp), bias.data_ptr() if bias is not None else None, scales.data_ptr(),
+                         scales.numel(), int(bool(relu)))
+
+
+def _f32_out(out, M, N, dev):
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=dev)
+    assert out.is_cuda and out.dtype == torch.float32 and out.stride(1) == 1 and out.shape == (M, N)
+    return out
+
+
+def gemm_u8s8_dequant_f32(A, a_zp, Bp, bias, scales, relu, out=None, kernel=KERNEL_AUTO):
+    """fp32 C = (alpha_A alpha_B) * corrected accumulator: A uint8 cuda [M, K]; returns / fills float32 [M, N]."""
+    assert A.is_cuda and A.dtype == torch.uint8 and A.dim() == 2 and A.stride(1) == 1 and A.shape[1] == Bp.K
+    M = A.shape[0]
+    out = _f32_out(out, M, Bp.N, A.device)
+    p = _dq_params(a_zp, bias, scales, relu)
+    _check(lib.qg_gemm_u8s8_dequant_f32(A.data_ptr(), M, A.stride(0), Bp.handle, ctypes.byref(p), out.data_ptr(),
+                                        out.stride(0), None, _stream(), kernel_id(kernel)), "qg_gemm_u8s8_dequant_f32")
+    return out
+
+
+def quantize_a_f32(A, inv_scale, a_zp, out=None):
+    """uint8 copy of an fp32 activation matrix (cuda [M, K], unit column stride)."""
+    assert A.is_cuda and A.dtype == torch.float32 and A.dim() == 2 and A.stride(1) == 1
+    M, K = A.shape
+    if out is None:
+        out = torch.empty((M, K), dtype=torch.uint8, device=A.device)
+    assert out.is_cuda and out.dtype == torch.uint8 and out.stride(1) == 1 and out.shape == (M, K)
+    _check(lib.qg_quantize_a_f32(A.data_ptr(), M, K, A.stride(0), float(inv_scale), int(a_zp), out.data_ptr(),
+                                 out.stride(0), _stream()), "qg_quantize_a_f32")
+    return out
+
+
+def gemm_f32_workspace_bytes(M, Bp):
+    return lib.qg_gemm_f32_workspace_bytes(M, Bp.handle)
+
+
+def _f32_ws(A, Bp, workspace):
+    assert A.is_cuda and A.dtype == torch.float32 and A.dim() == 2 and A.stride(1) == 1 and A.shape[1] == Bp.K
+    if workspace is None:
+        workspace = torch.empty(gemm_f32_workspace_bytes(A.shape[0], Bp), dtype=torch.uint8, device=A.device)
+    return workspace
+
+
+def gemm_f32s8_requant(A, a_inv_scale, a_zp, Bp, bias, scales, c_zp, relu, out=None, workspace=None,
+                       kernel=KERNEL_AUTO):
+    """fp32 activations, quantized by the library, uint8 out."""
+    ws = _f32_ws(A, Bp, workspace)
+    M = A.shape[0]
+    if out is None:
+        out = torch.empty((M, Bp.N), dtype=torch.uint8, device=A.device)
+    assert out.is_cuda and out.dtype == torch.uint8 and out.stride(1) == 1 and out.shape == (M, Bp.N)
+    p = _params(a_zp, bias, scales, c_zp, relu)
+    _check(lib.qg_gemm_f32s8_requant(A.data_ptr(), M, A.stride(0), float(a_inv_scale), Bp.handle, ctypes.byref(p),
+                                     out.data_ptr(), out.stride(0), ws.data_ptr(), _stream(), kernel_id(kernel)),
+           "qg_gemm_f32s8_requant")
+    return out
+
+
+def gemm_f32s8_dequant_f32(A, a_inv_scale, a_zp, Bp, bias, scales, relu, out=None, workspace=None,
+                           kernel=KERNEL_AUTO):
+    """fp32 activations in, fp32 result out."""
+    ws = _f32_ws(A, Bp, workspace)
+    M = A.shape[0]
+    out = _f32_out(out, M, Bp.N, A.device)
+    p = _dq_params(a_zp, bias, scales, relu)
+    _check(lib.qg_gemm_f32s8_dequant_f32(A.data_ptr(), M, A.stride(0), float(a_inv_scale), Bp.handle,
+                                         ctypes.byref(p), out.data_ptr(), out.stride(0), ws.data_ptr(), _stream(),
+                                         kernel_id(kernel)), "qg_gemm_f32s8_dequant_f32")
+    return out
 
 
 def pack_conv_w(Wt, b_zp):

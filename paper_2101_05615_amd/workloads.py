@@ -177,3 +177,21 @@ def random_conv(seed, Nb, H, W, C, G, Cout=None, R=3, S=3, pad=1, stride=1, per_
     c_zp = int(rng.integers(0, 256))
     return ConvCase(f"randconv_{Nb}x{H}x{W}x{C}_g{G}_s{seed}", inp, a_zp, wgt, G, b_zp, bias, scales,
                     c_zp, relu, pad, stride)
+
+
+def random_fp32_activations(seed, M, K, alpha=0.05, zp=100, special=True):
+    """fp32 activations around the range an (alpha, zp) uint8 quantizer represents: most values inside the
+    range, some beyond either end, and -- with `special` -- exact half-way points, zeros, huge values and
+    infinities sprinkled in.  Returns (A float32 [M, K], inv_scale float32)."""
+    rng = np.random.default_rng(seed)
+    lo, hi = alpha * (0 - zp), alpha * (255 - zp)
+    span = hi - lo
+    A = rng.uniform(lo - 0.1 * span, hi + 0.1 * span, size=(M, K)).astype(np.float32)
+    if special and A.size >= 16:
+        flat = A.reshape(-1)
+        idx = rng.choice(flat.size, size=max(8, flat.size // 16), replace=False)
+        codes = rng.integers(0, 255, size=idx.size)
+        flat[idx] = (alpha * (codes - zp + 0.5)).astype(np.float32)   # near or exactly on a tie
+        extra = np.array([0.0, -0.0, 1e30, -1e30, np.inf, -np.inf, 1e-30, -1e-30], np.float32)
+        flat[idx[:8]] = extra
+    return A, np.float32(1.0 / alpha)
