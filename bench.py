@@ -104,7 +104,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--only", default="", help="comma list of c1..c5 to restrict the side configs")
+    ap.add_argument("--only", default="", help="comma list of c1..c5 and next to restrict the side sections")
     ap.add_argument("--pmc-target", default="", choices=["", "c2", "c3", "c4", "c5", "copy"],
                     help="run ONLY a few launches of one workload (or of a plain 256 MiB device copy, the "
                          "calibration kernel for FETCH_SIZE / WRITE_SIZE) and exit: for rocprofv3 --pmc runs")
@@ -249,6 +249,42 @@ def main():
                      "frac_hbm_peak_cold": round(nb / (cold_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                      "TOPS_cold": round(o / (cold_ms * 1e-3) / 1e12, 2)})
 
+    # ------------------------------------------------------------------ rows beyond the five configs
+    nxt = None
+    if only is None or "next" in only:
+        from paper_2101_05615_amd import autotune
+        nxt = {"kernel_family": [], "fp32_ends": {}}
+        # shape-specific kernel family: what the automatic choice picks, and what the best kernel would give
+        for shape in [(1, 4096, 4096), (64, 4096, 4096), (128, 4096, 4096), (256, 1024, 4096), (2048, 2048, 2048),
+                      (4096, 1024, 1024), (16384, 256, 512)]:
+            r = autotune.tune(q, torch, [shape])[0]
+            t = r["us"]
+            nxt["kernel_family"].append({"M": shape[0], "N": shape[1], "K": shape[2], "auto": r["auto"],
+                                         "auto_us": round(t[r["auto"]], 2), "best": r["best"],
+                                         "best_us": round(t[r["best"]], 2),
+                                         "TOPS": round(2.0 * shape[0] * shape[1] * shape[2] / t[r["auto"]] / 1e6, 1)})
+        # fp32 ends: the quantization pass (5 bytes per element) and the fp32 output pipeline at the headline size
+        Mq = Kq = 8192
+        g = torch.Generator(device=dev)
+        g.manual_seed(11)
+        Af = torch.rand((Mq, Kq), dtype=torch.float32, device=dev, generator=g) * 12.0 - 4.0
+        Aq = torch.empty((Mq, Kq), dtype=torch.uint8, device=dev)
+        _, qms = time_calls(torch, lambda i: q.quantize_a_f32(Af, 1.0 / 0.05, 80, out=Aq), 20, 3)
+        nxt["fp32_ends"]["quantize_a_8192x8192"] = {"us": round(qms * 1e3, 1), "bytes": 5 * Mq * Kq,
+                                                   "GBps": round(5 * Mq * Kq / (qms * 1e-3) / 1e9, 1),
+                                                   "frac_hbm_peak": round(5 * Mq * Kq / (qms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+        c3b = wl.config3_square()
+        A3, Bp3, bias3, scales3, _, _ = gemm_setup(c3b)
+        Cf = torch.empty((c3b.M, c3b.N), dtype=torch.float32, device=dev)
+        _, dms = time_calls(torch, lambda i: q.gemm_u8s8_dequant_f32(A3, c3b.a_zp, Bp3, bias3, scales3, True, out=Cf), 10, 3)
+        nxt["fp32_ends"]["u8_in_f32_out_8192^3"] = {"ms": round(dms, 4), "TOPS": round(ops / (dms * 1e-3) / 1e12, 1)}
+        ws = torch.empty(q.gemm_f32_workspace_bytes(Mq, Bp3), dtype=torch.uint8, device=dev)
+        C8 = torch.empty((c3b.M, c3b.N), dtype=torch.uint8, device=dev)
+        _, fms = time_calls(torch, lambda i: q.gemm_f32s8_requant(Af, 1.0 / 0.05, 80, Bp3, bias3, scales3, 0, True,
+                                                                  out=C8, workspace=ws), 10, 3)
+        nxt["fp32_ends"]["f32_in_u8_out_8192^3"] = {"ms": round(fms, 4), "TOPS": round(ops / (fms * 1e-3) / 1e12, 1)}
+        del Af, Aq, A3, Bp3, Cf, ws, C8
+
     out = {
         "metric": "int8 GEMM+requant TOPS at M=N=K=8192", "value": round(tops, 2), "unit": "TOPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 5),
@@ -260,6 +296,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "configs": side,
+        "next_rows": nxt,
     }
     print(json.dumps(out))
 
