@@ -47,6 +47,9 @@ def _load():
         vp, i = ctypes.c_void_p, ctypes.c_int
         lib.orc_quantize_f32.argtypes = [vp, i, i, i, ctypes.c_float, ctypes.c_int32, vp, i]
         lib.orc_dequant_f32.argtypes = [vp, i, i, vp, i, i, vp]
+        lib.orc_split_outliers.restype = ctypes.c_long
+        lib.orc_split_outliers.argtypes = [vp, i, i, i, i, i, vp, vp]
+        lib.orc_csc_from_dense.argtypes = [vp, i, i, vp, vp, vp, ctypes.c_long]
         _lib = lib
     return _lib
 
@@ -172,6 +175,42 @@ def gemm_u8s8_dequant_f32(A, a_zp, B, b_zp, bias, scales, relu):
     s = np.ascontiguousarray(np.atleast_1d(np.asarray(scales)).astype(np.float32))
     out = np.empty(x.shape, np.float32)
     _check(_load().orc_dequant_f32(_p(x), x.shape[0], N, _p(s), s.size, int(bool(relu)), _p(out)), "dequant_f32")
+    return out
+
+
+def split_outliers(B, lo=-8, hi=7):
+    """B = B_small + B_sparse (both dense int8 [K, N]); returns (B_small, B_sparse, number of outliers)."""
+    B = _s8(B)
+    K, N = B.shape
+    small, sparse = np.empty((K, N), np.int8), np.empty((K, N), np.int8)
+    nnz = _load().orc_split_outliers(_p(B), K, N, B.strides[0], int(lo), int(hi), _p(small), _p(sparse))
+    if nnz < 0:
+        raise OracleError(int(nnz), "split_outliers")
+    return small, sparse, int(nnz)
+
+
+def csc_from_dense(S):
+    """(col_ptr int32 [N+1], row_idx int32 [nnz], val int8 [nnz]) of a dense int8 [K, N] matrix."""
+    S = _s8(S)
+    K, N = S.shape
+    cap = int(np.count_nonzero(S))
+    col_ptr = np.empty(N + 1, np.int32)
+    row_idx, val = np.empty(max(cap, 1), np.int32), np.empty(max(cap, 1), np.int8)
+    _check(_load().orc_csc_from_dense(_p(S), K, N, _p(col_ptr), _p(row_idx), _p(val), cap), "csc_from_dense")
+    return col_ptr, row_idx[:cap], val[:cap]
+
+
+def acc32_split(A, B_small, csc):
+    """A B_small + A B_sparse with B_sparse in CSC form."""
+    A, B_small = _u8(A), _s8(B_small)
+    M, K = A.shape
+    N = B_small.shape[1]
+    col_ptr, row_idx, val = csc
+    row_idx = np.ascontiguousarray(row_idx if row_idx.size else np.zeros(1, np.int32))
+    val = np.ascontiguousarray(val if val.size else np.zeros(1, np.int8))
+    out = np.empty((M, N), np.int32)
+    _check(_load().orc_acc32_split(_p(A), M, K, A.strides[0], _p(np.ascontiguousarray(B_small)), N, _p(col_ptr),
+                                   _p(row_idx), _p(val), _p(out)), "acc32_split")
     return out
 
 

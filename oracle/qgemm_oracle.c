@@ -33,6 +33,11 @@
  *     fp32 numbers and each is applied with ONE fp32 multiply; rounding is to
  *     nearest even; quantized activations saturate to [0,255]; ReLU on the fp32
  *     result is max(., 0).
+ *   - outlier-aware split of the constant matrix (Sec. 2.2, "sample end-to-end
+ *     pipeline"): B = B' + B_sparse with only small-magnitude numbers in B',
+ *     the few big ones in B_sparse in compressed sparse column form, and
+ *     A B = A B' + A B_sparse.  "Small" is fixed here as lo <= b <= hi for a
+ *     caller-chosen range (the GPU library stores B' in 4 bits: -8..7).
  *
  * Pins (tests/test_oracle_pins.py): brute force in Python integers, the
  * identity x - bias == sum_k (A - theta_A)(B - theta_B), fp64
@@ -190,6 +195,69 @@ int orc_quantize_f32(const float* A, int M, int K, int lda, float inv_scale,
     for (int k = 0; k < K; ++k)
       Aq[(size_t)i * ldq + k] =
           orc_quantize_one(A[(size_t)i * lda + k], inv_scale, zp);
+  return ORC_OK;
+}
+
+/* Outlier split (Sec. 2.2): B' keeps the entries with lo <= b <= hi and is zero
+ * elsewhere; B_sparse = B - B' keeps the others.  Both are written densely
+ * (K x N, leading dimension N); returns the number of outliers, or a negative
+ * ORC_E* code. */
+long orc_split_outliers(const int8_t* B, int K, int N, int ldb, int lo, int hi,
+                        int8_t* B_small, int8_t* B_sparse) {
+  if (!B || !B_small || !B_sparse || K <= 0 || N <= 0 || ldb < N || lo > hi)
+    return ORC_EINVAL;
+  long nnz = 0;
+  for (int k = 0; k < K; ++k)
+    for (int j = 0; j < N; ++j) {
+      const int8_t b = B[(size_t)k * ldb + j];
+      const int small = (b >= lo && b <= hi);
+      B_small[(size_t)k * N + j] = small ? b : 0;
+      B_sparse[(size_t)k * N + j] = small ? 0 : b;
+      nnz += !small;
+    }
+  return nnz;
+}
+
+/* Compressed sparse column form of a dense K x N matrix (leading dimension N):
+ * col_ptr has N+1 entries; the nonzeros of column j are row_idx/val[col_ptr[j]
+ * .. col_ptr[j+1]) in increasing row order.  cap = capacity of row_idx/val. */
+int orc_csc_from_dense(const int8_t* S, int K, int N, int32_t* col_ptr,
+                       int32_t* row_idx, int8_t* val, long cap) {
+  if (!S || !col_ptr || K <= 0 || N <= 0) return ORC_EINVAL;
+  long n = 0;
+  for (int j = 0; j < N; ++j) {
+    col_ptr[j] = (int32_t)n;
+    for (int k = 0; k < K; ++k) {
+      const int8_t v = S[(size_t)k * N + j];
+      if (v != 0) {
+        if (n >= cap || !row_idx || !val) return ORC_EINVAL;
+        row_idx[n] = k;
+        val[n] = v;
+        ++n;
+      }
+    }
+  }
+  col_ptr[N] = (int32_t)n;
+  return ORC_OK;
+}
+
+/* Accumulator of the split product, term by term as the paper writes it:
+ *   C32 = A B_small  (dense, plain triple loop)  +  A B_sparse  (CSC, one
+ *   multiply-add per stored nonzero and row of A). */
+int orc_acc32_split(const uint8_t* A, int M, int K, int lda, const int8_t* B_small,
+                    int N, const int32_t* col_ptr, const int32_t* row_idx,
+                    const int8_t* val, int32_t* C32) {
+  if (!A || !B_small || !col_ptr || !C32 || M <= 0 || N <= 0 || K <= 0 || lda < K)
+    return ORC_EINVAL;
+  for (int i = 0; i < M; ++i)
+    for (int j = 0; j < N; ++j) {
+      int32_t acc = 0;
+      for (int k = 0; k < K; ++k)
+        acc += (int32_t)A[(size_t)i * lda + k] * (int32_t)B_small[(size_t)k * N + j];
+      for (int32_t e = col_ptr[j]; e < col_ptr[j + 1]; ++e)
+        acc += (int32_t)A[(size_t)i * lda + row_idx[e]] * (int32_t)val[e];
+      C32[(size_t)i * N + j] = acc;
+    }
   return ORC_OK;
 }
 

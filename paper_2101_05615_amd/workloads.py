@@ -195,3 +195,13 @@ def random_fp32_activations(seed, M, K, alpha=0.05, zp=100, special=True):
         extra = np.array([0.0, -0.0, 1e30, -1e30, np.inf, -np.inf, 1e-30, -1e-30], np.float32)
         flat[idx[:8]] = extra
     return A, np.float32(1.0 / alpha)
+
+
+def outlier_weights(seed, K, N, sigma=2.5, outlier_frac=0.01, outlier_sigma=40.0):
+    """int8 weights as outlier-aware quantization produces them: a narrow bulk (rounded normal, sigma a few
+    quantization steps) and a small fraction of large-magnitude entries."""
+    rng = np.random.default_rng(seed)
+    B = np.rint(rng.normal(0.0, sigma, size=(K, N)))
+    big = rng.random(size=(K, N)) < outlier_frac
+    B[big] = np.rint(rng.normal(0.0, outlier_sigma, size=int(big.sum())))
+    return np.clip(B, -128, 127).astype(np.int8)

@@ -445,3 +445,54 @@ def test_fp32_in_fp32_out_composite_approximates_the_real_gemm(oracle_mod):
     bound = K * (alpha_a / 2) * np.abs(b_real).max() * 1.01
     assert np.abs(out - want).max() <= bound
     assert np.abs(out - want).max() > 0  # and it is a quantized result, not a copy of the fp64 one
+
+
+# ---------------------------------------------------------------- outlier-aware split of B
+def test_outlier_split_is_an_exact_decomposition(oracle_mod):
+    B = wl.outlier_weights(3, 200, 37, outlier_frac=0.05)
+    small, sparse, nnz = oracle_mod.split_outliers(B, -8, 7)
+    assert np.array_equal(small.astype(np.int32) + sparse.astype(np.int32), B.astype(np.int32))
+    assert small.min() >= -8 and small.max() <= 7                      # only small numbers stay in B'
+    big = (B < -8) | (B > 7)
+    assert nnz == int(big.sum()) and nnz > 0
+    assert np.array_equal(sparse != 0, big) and np.all(small[big] == 0)  # every big number moved, nothing else
+    # boundary values stay in B'
+    edge = np.array([[-9, -8, 7, 8, 0, 127, -128]], np.int8)
+    s2, p2, n2 = oracle_mod.split_outliers(edge, -8, 7)
+    assert s2.tolist() == [[0, -8, 7, 0, 0, 0, 0]] and p2.tolist() == [[-9, 0, 0, 8, 0, 127, -128]] and n2 == 4
+
+
+def test_csc_is_well_formed_and_reconstructs_the_matrix(oracle_mod):
+    B = wl.outlier_weights(4, 150, 23, outlier_frac=0.08)
+    _, sparse, nnz = oracle_mod.split_outliers(B, -8, 7)
+    col_ptr, row_idx, val = oracle_mod.csc_from_dense(sparse)
+    assert col_ptr[0] == 0 and col_ptr[-1] == nnz == len(row_idx) == len(val)
+    assert np.all(np.diff(col_ptr) >= 0) and np.all(val != 0)
+    back = np.zeros_like(sparse)
+    for j in range(sparse.shape[1]):
+        rows = row_idx[col_ptr[j]:col_ptr[j + 1]]
+        assert np.all(np.diff(rows) > 0)                               # strictly increasing rows within a column
+        back[rows, j] = val[col_ptr[j]:col_ptr[j + 1]]
+    assert np.array_equal(back, sparse)
+    # scipy's CSC of the same matrix agrees
+    import scipy.sparse as sp
+    ref = sp.csc_matrix(sparse.astype(np.int32))
+    ref.sort_indices()
+    assert np.array_equal(ref.indptr, col_ptr) and np.array_equal(ref.indices, row_idx) and np.array_equal(ref.data, val)
+
+
+def test_split_product_equals_dense_product(oracle_mod):
+    """A B = A B' + A B_sparse (Sec. 2.2): the split accumulator equals the plain one and Python integers."""
+    rng = np.random.default_rng(8)
+    for (M, N, K, frac) in [(5, 9, 70, 0.1), (16, 33, 300, 0.02), (3, 4, 36, 0.0), (2, 3, 50, 1.0)]:
+        A = rng.integers(0, 256, size=(M, K)).astype(np.uint8)
+        B = wl.outlier_weights(M + N, K, N, outlier_frac=frac, outlier_sigma=60.0)
+        small, sparse, nnz = oracle_mod.split_outliers(B, -8, 7)
+        got = oracle_mod.acc32_split(A, small, oracle_mod.csc_from_dense(sparse))
+        assert np.array_equal(got, oracle_mod.acc32(A, B))
+        want = [[sum(int(A[i, k]) * int(B[k, j]) for k in range(K)) for j in range(N)] for i in range(M)]
+        assert got.tolist() == want
+        if frac == 0.0:
+            assert nnz == int(((B < -8) | (B > 7)).sum())
+    # a dropped sparse term would be caught: the two parts differ from the whole when outliers exist
+    assert not np.array_equal(oracle_mod.acc32(A, small), oracle_mod.acc32(A, B))
