@@ -43,6 +43,7 @@ extern "C" {
 #define QG_ELAUNCH (-5)    /* the HIP runtime refused a launch or copy                  */
 #define QG_ENOMEM (-6)     /* host allocation of the descriptor failed                  */
 #define QG_EUNSUPPORTED (-7) /* valid request outside what this build implements        */
+#define QG_ECAPACITY (-8)  /* more outliers than the caller's sparse buffer can hold       */
 
 /* Largest K accepted: with |A| <= 255 and |B - theta_B| <= 255 the int32
  * accumulator and every correction term stay below 2^31 (Eq. (2) never
@@ -234,6 +235,42 @@ int qg_gemm_f32s8_requant(const float* A_dev, int M, int lda, float a_inv_scale,
 int qg_gemm_f32s8_dequant_f32(const float* A_dev, int M, int lda, float a_inv_scale,
                               const qg_packed_b* Bp, const qg_dequant_params* p, float* C_dev, int ldc,
                               void* workspace_dev, void* stream, int kernel);
+
+/* ---- outlier-aware split of the weights (Sec. 2.2) ------------------------- */
+
+/* The paper's sample pipeline splits the constant matrix into B = B' + B_sparse:
+ * B' keeps the small-magnitude numbers, the few big ones go to B_sparse in a
+ * compressed sparse column format, both prepared once offline, and
+ * A B = A B' + A B_sparse with the sparse product fused into the output
+ * processing.  There the point is a cheaper accumulation for B'; on this GPU
+ * the point is bandwidth: B' (here: -8 <= b <= 7) is stored in 4 bits, which
+ * halves the bytes the small-batch kernels stream.  Results are bit-identical
+ * to the same call on a dense descriptor of B.
+ *
+ * A split descriptor runs on the streaming kernels only (QG_KERNEL_SKINNY*,
+ * any M through row blocks); naming a TILE kernel returns QG_EUNSUPPORTED.
+ *
+ * Protocol: qg_count_outliers -> allocate -> qg_pack_b_outlier.  Both calls
+ * wait for `stream`. */
+
+/* Number of entries of B outside -8..7.  scratch_dev: 8 bytes of device memory,
+ * 8-byte aligned. */
+int qg_count_outliers(const int8_t* B_dev, int K, int N, int ldb, void* scratch_dev, size_t* nnz_host,
+                      void* stream);
+
+/* Buffer sizes for a split descriptor holding up to max_nnz outliers. */
+int qg_pack_b_outlier_sizes(int K, int N, size_t max_nnz, size_t* packed_bytes,
+                            size_t* col_offsets_bytes, size_t* sparse_bytes);
+
+/* As qg_pack_b; packed_dev receives the 4-bit B', sparse_dev (256-byte aligned)
+ * the sparse part; col_offsets are those of the whole B.  QG_ECAPACITY when B
+ * holds more than max_nnz outliers (nothing usable is left in the buffers). */
+int qg_pack_b_outlier(const int8_t* B_dev, int K, int N, int ldb, const int32_t* b_zp_host,
+                      int n_b_zp, size_t max_nnz, void* packed_dev, int32_t* col_offsets_dev,
+                      void* sparse_dev, void* stream, qg_packed_b** out);
+
+/* Outliers held by a split descriptor (0 for a dense one or NULL). */
+size_t qg_packed_b_nnz(const qg_packed_b* p);
 
 /* ---- group-wise convolution with fused im2col ----------------------------- */
 

@@ -104,6 +104,20 @@ int builtin_select(int M, int N, int K) {
   return best;
 }
 
+// cheapest streaming kernel (outlier-split descriptors run on these only)
+int select_stream_kernel(int M, int N, int K) {
+  int best = QG_KERNEL_SKINNY64;
+  double best_us = 1e300;
+  for (const stream_cost& c : k_stream_cost) {
+    const long long blocks = ceil_div(M, c.rows);
+    if (blocks > 65535) continue;
+    const double wgs = (double)blocks * (double)(2 * ceil_div(N, 32));
+    const double us = fmax(c.fix + K * c.lat_k, 2.5 + wgs * (c.wg + K * c.wg_k) * 1e-3);
+    if (us < best_us) best_us = us, best = c.kernel;
+  }
+  return best;
+}
+
 int select_kernel(int M, int N, int K) {
   for (int i = 0; i < g_nrules; ++i) {
     const qg_dispatch_rule& r = g_rules[i];
@@ -117,12 +131,30 @@ hipError_t launch_gemm(const qg_gemm_args& a, int mode, int kernel, hipStream_t 
   return qg_launch_gemm_tile(a, mode, kernel, s);
 }
 
+// resolves QG_KERNEL_AUTO for a descriptor and checks an explicit choice against it: QG_OK, or
+// QG_EINVAL (unknown id / too many row blocks), QG_EUNSUPPORTED (tiled kernel on a split descriptor)
+int resolve_kernel(const qg_packed_b* Bp, int M, int* kernel);
+
 // kernel id valid for this M (the streaming kernels put row blocks on the 16-bit grid dimension)
 bool kernel_ok(int kernel, int M) {
   if (kernel < QG_KERNEL_AUTO || kernel > QG_KERNEL_LAST) return false;
   if (kernel >= QG_KERNEL_SKINNY16 && kernel <= QG_KERNEL_SKINNY64)
     return ceil_div(M, 16 << (kernel - QG_KERNEL_SKINNY16)) <= 65535;
   return true;
+}
+
+int resolve_kernel(const qg_packed_b* Bp, int M, int* kernel) {
+  if (!kernel_ok(*kernel, M)) return QG_EINVAL;
+  if (Bp->split) {
+    if (*kernel == QG_KERNEL_AUTO) *kernel = select_stream_kernel(M, Bp->N, Bp->K);
+    if (*kernel > QG_KERNEL_SKINNY64) return QG_EUNSUPPORTED;
+    return kernel_ok(*kernel, M) ? QG_OK : QG_EINVAL;
+  }
+  if (*kernel == QG_KERNEL_AUTO) {
+    *kernel = select_kernel(M, Bp->N, Bp->K);
+    if (!kernel_ok(*kernel, M)) *kernel = builtin_select(M, Bp->N, Bp->K);
+  }
+  return QG_OK;
 }
 
 }  // namespace
@@ -165,6 +197,7 @@ const char* qg_status_string(int code) {
     case QG_ELAUNCH: return "HIP runtime refused the launch or copy";
     case QG_ENOMEM: return "host allocation failed";
     case QG_EUNSUPPORTED: return "configuration not implemented in this build";
+    case QG_ECAPACITY: return "more outliers than the sparse buffer holds";
     default: return "unknown status";
   }
 }
@@ -201,6 +234,9 @@ int qg_pack_b(const int8_t* B_dev, int K, int N, int ldb, const int32_t* b_zp_ho
   h->bzp = col_offsets_dev + N_pad;
   h->G = h->R = h->S = h->Cg = h->Og = 0;
   h->conv_frags = nullptr;
+  h->split = 0;
+  h->frag_ptr = h->entries = nullptr;
+  h->nnz = 0;
 
   int rc = upload_bzp(b_zp_host, n_b_zp, N, N_pad, col_offsets_dev + N_pad, s, &h->has_bzp);
   if (rc != QG_OK) {
@@ -220,6 +256,97 @@ void qg_packed_b_destroy(qg_packed_b* p) { delete p; }
 
 int qg_packed_b_k(const qg_packed_b* p) { return p ? p->K : 0; }
 int qg_packed_b_n(const qg_packed_b* p) { return p ? p->N : 0; }
+
+int qg_count_outliers(const int8_t* B_dev, int K, int N, int ldb, void* scratch_dev, size_t* nnz_host, void* stream) {
+  if (!B_dev || !scratch_dev || !nnz_host) return QG_ENULL;
+  if (K <= 0 || N <= 0 || K > QG_MAX_K || ldb < N) return QG_EINVAL;
+  if (!aligned(scratch_dev, 8)) return QG_EALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned long long* cnt = static_cast<unsigned long long*>(scratch_dev);
+  if (qg_launch_count_outliers(B_dev, K, N, ldb, cnt, s) != hipSuccess) return QG_ELAUNCH;
+  unsigned long long host = 0;
+  if (hipMemcpyAsync(&host, cnt, sizeof(host), hipMemcpyDeviceToHost, s) != hipSuccess) return QG_ELAUNCH;
+  if (hipStreamSynchronize(s) != hipSuccess) return QG_ELAUNCH;
+  *nnz_host = (size_t)host;
+  return QG_OK;
+}
+
+// [frag_ptr: nfrag+1][cursor: nfrag] int32, rounded up to 256 B
+static size_t sparse_header_bytes(int N_pad) {
+  const size_t nfrag = (size_t)N_pad / QG_FRAG_COLS;
+  return (size_t)qg_round_up((int)((2 * nfrag + 1) * sizeof(int32_t)), 256);
+}
+
+int qg_pack_b_outlier_sizes(int K, int N, size_t max_nnz, size_t* packed_bytes, size_t* col_offsets_bytes,
+                            size_t* sparse_bytes) {
+  if (!packed_bytes || !col_offsets_bytes || !sparse_bytes) return QG_ENULL;
+  if (K <= 0 || N <= 0 || K > QG_MAX_K) return QG_EINVAL;
+  if (max_nnz > (size_t)0x7FFFFFFF) return QG_EINVAL;
+  const size_t K_pad = (size_t)qg_round_up(K, QG_KPAD), N_pad = (size_t)qg_round_up(N, QG_NPAD);
+  *packed_bytes = K_pad * N_pad / 2;
+  *col_offsets_bytes = 2 * N_pad * sizeof(int32_t);
+  *sparse_bytes = sparse_header_bytes((int)N_pad) + (max_nnz ? max_nnz : 1) * sizeof(int32_t);
+  return QG_OK;
+}
+
+int qg_pack_b_outlier(const int8_t* B_dev, int K, int N, int ldb, const int32_t* b_zp_host, int n_b_zp,
+                      size_t max_nnz, void* packed_dev, int32_t* col_offsets_dev, void* sparse_dev, void* stream,
+                      qg_packed_b** out) {
+  if (!B_dev || !b_zp_host || !packed_dev || !col_offsets_dev || !sparse_dev || !out) return QG_ENULL;
+  if (K <= 0 || N <= 0 || K > QG_MAX_K || ldb < N) return QG_EINVAL;
+  if (n_b_zp != 1 && n_b_zp != N) return QG_EINVAL;
+  if (max_nnz > (size_t)0x7FFFFFFF) return QG_EINVAL;
+  if (!aligned(packed_dev, 256) || !aligned(col_offsets_dev, 256) || !aligned(sparse_dev, 256)) return QG_EALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int K_pad = qg_round_up(K, QG_KPAD), N_pad = qg_round_up(N, QG_NPAD);
+  const int nfrag = N_pad / QG_FRAG_COLS;
+  int32_t* frag_ptr = static_cast<int32_t*>(sparse_dev);
+  int32_t* cursor = frag_ptr + nfrag + 1;
+  int32_t* entries = reinterpret_cast<int32_t*>(static_cast<unsigned char*>(sparse_dev) + sparse_header_bytes(N_pad));
+
+  qg_packed_b* h = new (std::nothrow) qg_packed_b();
+  if (!h) return QG_ENOMEM;
+  h->kind = QG_KIND_GEMM;
+  h->version = QG_LAYOUT_VERSION;
+  h->K = K;
+  h->N = N;
+  h->K_pad = K_pad;
+  h->N_pad = N_pad;
+  h->n_b_zp = n_b_zp;
+  h->packed = static_cast<const int8_t*>(packed_dev);
+  h->col_off = col_offsets_dev;
+  h->bzp = col_offsets_dev + N_pad;
+  h->G = h->R = h->S = h->Cg = h->Og = 0;
+  h->conv_frags = nullptr;
+  h->split = 1;
+  h->frag_ptr = frag_ptr;
+  h->entries = entries;
+  h->nnz = 0;
+
+  int rc = upload_bzp(b_zp_host, n_b_zp, N, N_pad, col_offsets_dev + N_pad, s, &h->has_bzp);
+  int32_t total = 0;
+  if (rc == QG_OK && qg_launch_pack_b_split_count(B_dev, K, N, ldb, K_pad, N_pad, static_cast<uint8_t*>(packed_dev),
+                                                  col_offsets_dev, col_offsets_dev + N_pad, frag_ptr, cursor,
+                                                  s) != hipSuccess)
+    rc = QG_ELAUNCH;
+  // the total decides whether the fill may run: it must not write past the caller's capacity
+  if (rc == QG_OK && (hipMemcpyAsync(&total, frag_ptr + nfrag, sizeof(total), hipMemcpyDeviceToHost, s) != hipSuccess ||
+                      hipStreamSynchronize(s) != hipSuccess))
+    rc = QG_ELAUNCH;
+  if (rc == QG_OK && (total < 0 || (size_t)total > max_nnz)) rc = QG_ECAPACITY;
+  if (rc == QG_OK && total > 0 &&
+      qg_launch_pack_b_split_fill(B_dev, K, N, ldb, N_pad, frag_ptr, cursor, entries, s) != hipSuccess)
+    rc = QG_ELAUNCH;
+  if (rc != QG_OK) {
+    delete h;
+    return rc;
+  }
+  h->nnz = total;
+  *out = h;
+  return QG_OK;
+}
+
+size_t qg_packed_b_nnz(const qg_packed_b* p) { return (p && p->split) ? (size_t)p->nnz : 0; }
 
 size_t qg_gemm_workspace_bytes(int M, const qg_packed_b* Bp) {
   (void)M;
@@ -241,6 +368,8 @@ static int gemm_common(const uint8_t* A_dev, int M, int lda, const qg_packed_b* 
   a->kb64 = Bp->K_pad / QG_FRAG_K;
   a->nb16 = Bp->N_pad / QG_FRAG_COLS;
   a->has_bzp = Bp->has_bzp;
+  a->sp_ptr = Bp->split ? Bp->frag_ptr : nullptr;
+  a->sp_entries = Bp->entries;
   a->lda = lda;
   // vector/DMA path: 16-byte aligned rows and 32-bit byte offsets into A
   a->a_vec = aligned(A_dev, 16) && (lda % 16 == 0) && ((uint64_t)(M - 1) * (uint64_t)lda + (uint64_t)Bp->K + 4096 < (1ull << 32));
@@ -260,8 +389,8 @@ int qg_gemm_u8s8_requant_kernel(const uint8_t* A_dev, int M, int lda, const qg_p
   qg_gemm_args a = {};
   int rc = gemm_common(A_dev, M, lda, Bp, &a);
   if (rc != QG_OK) return rc;
-  if (!kernel_ok(kernel, M)) return QG_EINVAL;
-  if (kernel == QG_KERNEL_AUTO) kernel = qg_kernel_select(M, Bp->N, Bp->K);
+  rc = resolve_kernel(Bp, M, &kernel);
+  if (rc != QG_OK) return rc;
   if (!C_dev) return QG_ENULL;
   rc = check_requant(p, Bp->N);
   if (rc != QG_OK) return rc;
@@ -295,8 +424,8 @@ int qg_gemm_u8s8_acc32_kernel(const uint8_t* A_dev, int M, int lda, const qg_pac
   qg_gemm_args a = {};
   int rc = gemm_common(A_dev, M, lda, Bp, &a);
   if (rc != QG_OK) return rc;
-  if (!kernel_ok(kernel, M)) return QG_EINVAL;
-  if (kernel == QG_KERNEL_AUTO) kernel = qg_kernel_select(M, Bp->N, Bp->K);
+  rc = resolve_kernel(Bp, M, &kernel);
+  if (rc != QG_OK) return rc;
   if (!C32_dev) return QG_ENULL;
   if (ldc < Bp->N) return QG_EINVAL;
   a.C32 = C32_dev;
@@ -322,8 +451,8 @@ int qg_gemm_u8s8_dequant_f32(const uint8_t* A_dev, int M, int lda, const qg_pack
   qg_gemm_args a = {};
   int rc = gemm_common(A_dev, M, lda, Bp, &a);
   if (rc != QG_OK) return rc;
-  if (!kernel_ok(kernel, M)) return QG_EINVAL;
-  if (kernel == QG_KERNEL_AUTO) kernel = qg_kernel_select(M, Bp->N, Bp->K);
+  rc = resolve_kernel(Bp, M, &kernel);
+  if (rc != QG_OK) return rc;
   if (!C_dev) return QG_ENULL;
   rc = check_dequant(p, Bp->N);
   if (rc != QG_OK) return rc;
@@ -378,7 +507,9 @@ int qg_gemm_f32s8_requant(const float* A_dev, int M, int lda, float a_inv_scale,
   if (Bp->kind != QG_KIND_GEMM || Bp->version != QG_LAYOUT_VERSION) return QG_EINVAL;
   int rc = check_requant(p, Bp->N);
   if (rc != QG_OK) return rc;
-  if (M <= 0 || ldc < Bp->N || !kernel_ok(kernel, M)) return QG_EINVAL;
+  if (M <= 0 || ldc < Bp->N) return QG_EINVAL;
+  rc = resolve_kernel(Bp, M, &kernel);
+  if (rc != QG_OK) return rc;
   rc = quantize_into_workspace(A_dev, M, lda, a_inv_scale, Bp, p->a_zp, workspace_dev, stream);
   if (rc != QG_OK) return rc;
   return qg_gemm_u8s8_requant_kernel(static_cast<const uint8_t*>(workspace_dev), M, f32_ldq(Bp), Bp, p, C_dev, ldc,
@@ -392,7 +523,9 @@ int qg_gemm_f32s8_dequant_f32(const float* A_dev, int M, int lda, float a_inv_sc
   if (Bp->kind != QG_KIND_GEMM || Bp->version != QG_LAYOUT_VERSION) return QG_EINVAL;
   int rc = check_dequant(p, Bp->N);
   if (rc != QG_OK) return rc;
-  if (M <= 0 || ldc < Bp->N || !kernel_ok(kernel, M)) return QG_EINVAL;
+  if (M <= 0 || ldc < Bp->N) return QG_EINVAL;
+  rc = resolve_kernel(Bp, M, &kernel);
+  if (rc != QG_OK) return rc;
   if (!aligned(C_dev, 4)) return QG_EALIGN;
   rc = quantize_into_workspace(A_dev, M, lda, a_inv_scale, Bp, p->a_zp, workspace_dev, stream);
   if (rc != QG_OK) return rc;
@@ -440,6 +573,9 @@ int qg_pack_conv_w(const int8_t* W_dev, int G, int R, int S, int Cg, int Og, con
   h->S = S;
   h->Cg = Cg;
   h->Og = Og;
+  h->split = 0;
+  h->frag_ptr = h->entries = nullptr;
+  h->nnz = 0;
   int8_t* frags = (G % 8 == 0) ? static_cast<int8_t*>(packed_dev) + qg_round_up(G * R * S * Cg * Og, 256) : nullptr;
   h->conv_frags = frags;
   rc = upload_bzp(b_zp_host, n_b_zp, Cout, Cout, col_offsets_dev + Cout, s, &h->has_bzp);

@@ -14,6 +14,12 @@
 // 256-byte row segments (MFMA operand order would touch 16 rows x 64 B per load), and the
 // fragment is then fetched from LDS in operand order.
 //
+// Outlier-split weights (Sec. 2.2, B = B' + B_sparse): B' streams in at 4 bits per weight -- half the bytes
+// of the shape this kernel exists for -- and is widened to int8 operand dwords with two bit operations
+// per eight weights; the sparse term A B_sparse is added while the partial sums of the workgroup are still
+// in LDS (the paper fuses it into the output processing while the block of C is cache-resident): the
+// workgroup's threads share the fragment's entries, one (row, entry) product each, into an LDS tile.
+//
 // M larger than the row block is covered by the second grid dimension: every row block streams
 // B again (from L2 / the memory-side cache when the blocks run close together), which beats the
 // tiled kernel only while there are too few tiles to occupy the chip.
@@ -33,14 +39,16 @@ __device__ __forceinline__ v4i load_a_chunk_slow(const uint8_t* p, int kvalid) {
   return u.v;
 }
 
-template <int MODE, int MB, int NWAVES, int BATCH>
+template <int MODE, int MB, int NWAVES, int BATCH, bool B4>
 __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_gemm_args p) {
   constexpr bool ASTAGE = (MB == 1 && BATCH == 4);  // A through LDS (see the file header)
   constexpr int PART_BYTES = NWAVES * MB * 64 * (int)sizeof(v4i);
   constexpr int RSP_BYTES = NWAVES * MB * 16 * (int)sizeof(int);
+  constexpr int ASTAGE_BYTES = ASTAGE ? NWAVES * 4096 : 0;
   extern __shared__ __align__(16) unsigned char smem[];
   v4i* part = reinterpret_cast<v4i*>(smem);                 // [wave][mb][lane]
   int* rsp = reinterpret_cast<int*>(smem + PART_BYTES);     // [wave][mb][16]
+  int* sp = reinterpret_cast<int*>(smem + PART_BYTES + RSP_BYTES + ASTAGE_BYTES);  // B4: [row][slot] sparse term
 
   const int nb16 = blockIdx.x;
   const int sb = nb16 >> 1, sfrag = nb16 & 1;
@@ -67,6 +75,11 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
     }
   }
 
+  if (B4) {
+    for (int t = tid; t < MB * 256; t += NWAVES * 64) sp[t] = 0;
+    __syncthreads();
+  }
+
   // K slices are dealt to the waves rotated by the workgroup index, so that at any instant the workgroups
   // of an XCD read DIFFERENT lines of A (all of them read all of A; unrotated they would all hit the same
   // L2 channel at the same time)
@@ -83,14 +96,23 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
     rs[mb] = 0;
     a_row[mb] = p.A + (size_t)min(m_base + mb * 16 + ml, p.M - 1) * p.lda + g * 16;
   }
-  const int8_t* bcol = p.Bp + (size_t)nb16 * QG_FRAG_BYTES + lane * 16;
-  const size_t b_step = (size_t)p.nb16 * QG_FRAG_BYTES;  // one 64-deep slab of the packed buffer
+  constexpr int FRAG = B4 ? QG_FRAG4_BYTES : QG_FRAG_BYTES;
+  const int8_t* bcol = p.Bp + (size_t)nb16 * FRAG + lane * (FRAG / 64);
+  const size_t b_step = (size_t)p.nb16 * FRAG;  // one 64-deep slab of the packed buffer
 
   for (int kb = kb_begin; kb < kb_end; kb += BATCH) {
     v4i bf[BATCH];
 #pragma unroll
     for (int j = 0; j < BATCH; ++j)
-      if (kb + j < kb_end) bf[j] = *reinterpret_cast<const v4i*>(bcol + (size_t)(kb + j) * b_step);
+      if (kb + j < kb_end) {
+        if (B4) {
+          const uint2 w = *reinterpret_cast<const uint2*>(bcol + (size_t)(kb + j) * b_step);
+          bf[j] = (v4i){(int)(w.x & 0x0F0F0F0Fu), (int)((w.x >> 4) & 0x0F0F0F0Fu), (int)(w.y & 0x0F0F0F0Fu),
+                        (int)((w.y >> 4) & 0x0F0F0F0Fu)};
+        } else {
+          bf[j] = *reinterpret_cast<const v4i*>(bcol + (size_t)(kb + j) * b_step);
+        }
+      }
     v4i af[MB][BATCH];
     if (ASTAGE && p.a_vec && kb + BATCH <= kb_end && (kb + BATCH) * QG_FRAG_K <= p.K) {
       // 16 rows x 256 B of A: four requests of 4 rows x 256 B into this wave's LDS region, chunk c of
@@ -135,6 +157,20 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
       }
   }
 
+  // ---- sparse term of the outlier split: entry e of this fragment column and row r of the block go to
+  // thread e * rows + r (A is small and L2-resident; the row offsets turn A_u into A_s = A_u - 128)
+  if (B4) {
+    constexpr int ROWS = MB * 16;
+    const int e0 = p.sp_ptr[nb16], ne = p.sp_ptr[nb16 + 1] - e0;
+    for (int idx = tid; idx < ne * ROWS; idx += NWAVES * 64) {
+      const int e = idx / ROWS, r = idx % ROWS;
+      const int ent = p.sp_entries[e0 + e];
+      const int k = ent & 0x7FFF, slot = (ent >> 16) & 15, v = ent >> 24;
+      const int a = p.A[(size_t)min(m_base + r, p.M - 1) * p.lda + k];
+      atomicAdd(&sp[r * 16 + slot], (a - 128) * v);
+    }
+  }
+
   // ---- combine the 16 K-slices through LDS
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
@@ -153,6 +189,11 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
   for (int w = 0; w < NWAVES; ++w) {
     sum += part[(w * MB + mb) * 64 + lane];
     rsum += rsp[(w * MB + mb) * 16 + ml];
+  }
+  if (B4) {
+    // A_s B = (A_s U - 8 rowsum(A_s)) + A_s B_sparse; lane (ml, g) register r is slot 4 g + r of the fragment
+#pragma unroll
+    for (int r = 0; r < 4; ++r) sum[r] += sp[(mb * 16 + ml) * 16 + 4 * g + r] - 8 * rsum;
   }
 
   // ---- output pipeline; lane (ml, u = g) holds row m_base+mb*16+ml, 4 consecutive columns
@@ -198,36 +239,42 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
   }
 }
 
-template <int MODE, int MB, int NWAVES, int BATCH>
+template <int MODE, int MB, int NWAVES, int BATCH, bool B4>
 hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   const int smem = NWAVES * MB * 64 * (int)sizeof(v4i) + NWAVES * MB * 16 * (int)sizeof(int) +
-                   ((MB == 1 && BATCH == 4) ? NWAVES * 4096 : 0);
-  hipError_t e = hipFuncSetAttribute((const void*)qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH>,
+                   ((MB == 1 && BATCH == 4) ? NWAVES * 4096 : 0) + (B4 ? MB * 256 * (int)sizeof(int) : 0);
+  hipError_t e = hipFuncSetAttribute((const void*)qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH, B4>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, smem);
   if (e != hipSuccess) return e;
   const int nfrag = ((a.N + 31) / 32) * 2;
   const int mblocks = (a.M + MB * 16 - 1) / (MB * 16);
   if (mblocks > 65535) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH>), dim3(nfrag, mblocks), dim3(NWAVES * 64), smem, s,
-                     a);
+  hipLaunchKernelGGL((qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH, B4>), dim3(nfrag, mblocks), dim3(NWAVES * 64), smem,
+                     s, a);
   return hipGetLastError();
 }
 
 // waves per workgroup and k blocks a wave requests at once, per row-block height
-template <int MODE>
+template <int MODE, bool B4>
 hipError_t launch_mb(const qg_gemm_args& a, int kernel, hipStream_t s) {
   switch (kernel) {
-    case QG_KERNEL_SKINNY16: return launch<MODE, 1, 16, 4>(a, s);
-    case QG_KERNEL_SKINNY32: return launch<MODE, 2, 16, 4>(a, s);
-    case QG_KERNEL_SKINNY64: return launch<MODE, 4, 16, 2>(a, s);
+    case QG_KERNEL_SKINNY16: return launch<MODE, 1, 16, 4, B4>(a, s);
+    case QG_KERNEL_SKINNY32: return launch<MODE, 2, 16, 4, B4>(a, s);
+    case QG_KERNEL_SKINNY64: return launch<MODE, 4, 16, 2, B4>(a, s);
     default: return hipErrorInvalidValue;
   }
+}
+
+template <bool B4>
+hipError_t launch_mode(const qg_gemm_args& a, int mode, int kernel, hipStream_t s) {
+  if (mode == QG_MODE_REQUANT) return launch_mb<QG_MODE_REQUANT, B4>(a, kernel, s);
+  if (mode == QG_MODE_DEQUANT) return launch_mb<QG_MODE_DEQUANT, B4>(a, kernel, s);
+  return launch_mb<QG_MODE_ACC32, B4>(a, kernel, s);
 }
 
 }  // namespace
 
 hipError_t qg_launch_gemm_skinny(const qg_gemm_args& a, int mode, int kernel, hipStream_t s) {
-  if (mode == QG_MODE_REQUANT) return launch_mb<QG_MODE_REQUANT>(a, kernel, s);
-  if (mode == QG_MODE_DEQUANT) return launch_mb<QG_MODE_DEQUANT>(a, kernel, s);
-  return launch_mb<QG_MODE_ACC32>(a, kernel, s);
+  // a.sp_ptr != null: Bp holds the 4-bit part of an outlier-split matrix
+  return a.sp_ptr != nullptr ? launch_mode<true>(a, mode, kernel, s) : launch_mode<false>(a, mode, kernel, s);
 }

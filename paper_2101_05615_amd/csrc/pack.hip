@@ -52,6 +52,105 @@ __global__ void qg_fold_offsets(int32_t* col_off, const int32_t* __restrict__ bz
   if (j < n) col_off[j] = col_off[j] - K * bzp[j];
 }
 
+// ---- outlier split (Sec. 2.2): B = B' + B_sparse, B' in 4 bits, B_sparse per fragment -------------------
+__device__ __forceinline__ bool is_outlier(int b) { return b < -8 || b > 7; }
+
+__global__ void qg_count_outliers_kernel(const int8_t* __restrict__ B, int K, int N, int ldb,
+                                         unsigned long long* __restrict__ count) {
+  const long long total = (long long)K * N;
+  const long long step = (long long)gridDim.x * blockDim.x;
+  unsigned n = 0;
+  for (long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += step) {
+    const int k = (int)(t / N), j = (int)(t - (long long)k * N);
+    n += is_outlier(B[(size_t)k * ldb + j]);
+  }
+  for (int o = 32; o > 0; o >>= 1) n += __shfl_xor((int)n, o);
+  if ((threadIdx.x & 63) == 0 && n) atomicAdd(count, (unsigned long long)n);
+}
+
+// As qg_pack_b_kernel, writing 8 bytes of nibbles (U = B' + 8) per thread; the column sums are those of
+// the WHOLE matrix B (the output pipeline corrects A B, not A B'), and the thread counts its outliers
+// into its fragment column.
+__global__ __launch_bounds__(256) void qg_pack_b_split_kernel(const int8_t* __restrict__ B, int K, int N, int ldb,
+                                                              int K_pad, int N_pad, uint8_t* __restrict__ packed4,
+                                                              int32_t* __restrict__ colsum,
+                                                              int32_t* __restrict__ frag_cnt) {
+  const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long total = (long long)N_pad * (K_pad / 16);
+  if (gid >= total) return;
+  const int n = (int)(gid % N_pad);
+  const int kc16 = (int)(gid / N_pad);
+  const int k0 = kc16 * 16;
+  int sum = 0, nout = 0;
+  unsigned w[2] = {0, 0};
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    int x = 0;
+    if (n < N && k0 + i < K) x = B[(size_t)(k0 + i) * ldb + n];
+    sum += x;
+    const bool big = is_outlier(x);
+    nout += big;
+    const unsigned u = (unsigned)((big ? 0 : x) + 8);  // 0..15
+    // value i of the chunk: dword i/8, byte i%4, high nibble for i%8 >= 4
+    w[i >> 3] |= u << (8 * (i & 3) + 4 * ((i >> 2) & 1));
+  }
+  const int sb = n >> 5, c = n & 31;
+  const int slot = qg_col_to_slot(c);
+  const int nb16 = sb * 2 + (slot >> 4), nl = slot & 15;
+  const int kb = kc16 >> 2, g = kc16 & 3;
+  const size_t dst = ((size_t)kb * (N_pad / QG_FRAG_COLS) + nb16) * QG_FRAG4_BYTES + (g * 16 + nl) * 8;
+  *reinterpret_cast<uint2*>(packed4 + dst) = make_uint2(w[0], w[1]);
+  if (n < N && sum != 0) atomicAdd(&colsum[n], sum);
+  if (nout) atomicAdd(&frag_cnt[nb16], nout);
+}
+
+// exclusive prefix sum of the per-fragment counts (in place: cnt[i] -> offset of fragment i, cnt[n] = total)
+// and zeroing of the fill cursors; one workgroup
+__global__ __launch_bounds__(1024) void qg_scan_frag_kernel(int32_t* __restrict__ cnt, int32_t* __restrict__ cursor,
+                                                            int n) {
+  __shared__ int part[1024];
+  const int t = threadIdx.x;
+  const int per = (n + 1023) / 1024;
+  const int lo = t * per, hi = min(n, lo + per);
+  int s = 0;
+  for (int i = lo; i < hi; ++i) s += cnt[i];
+  part[t] = s;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {
+    const int v = t >= o ? part[t - o] : 0;
+    __syncthreads();
+    part[t] += v;
+    __syncthreads();
+  }
+  int run = t ? part[t - 1] : 0;
+  for (int i = lo; i < hi; ++i) {
+    const int c = cnt[i];
+    cnt[i] = run;
+    cursor[i] = 0;
+    run += c;
+  }
+  if (t == 1023) cnt[n] = part[1023];
+}
+
+// every outlier takes the next free entry of its fragment column (order inside a fragment is arbitrary:
+// the sparse term is an integer sum)
+__global__ __launch_bounds__(256) void qg_fill_outliers_kernel(const int8_t* __restrict__ B, int K, int N, int ldb,
+                                                               const int32_t* __restrict__ frag_ptr,
+                                                               int32_t* __restrict__ cursor,
+                                                               int32_t* __restrict__ entries) {
+  const long long total = (long long)K * N;
+  const long long step = (long long)gridDim.x * blockDim.x;
+  for (long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += step) {
+    const int k = (int)(t / N), j = (int)(t - (long long)k * N);
+    const int x = B[(size_t)k * ldb + j];
+    if (!is_outlier(x)) continue;
+    const int slot = qg_col_to_slot(j & 31);
+    const int nb16 = (j >> 5) * 2 + (slot >> 4), nl = slot & 15;
+    const int pos = atomicAdd(&cursor[nb16], 1);
+    entries[frag_ptr[nb16] + pos] = (int32_t)((unsigned)k | ((unsigned)nl << 16) | ((unsigned)(x & 0xFF) << 24));
+  }
+}
+
 // Conv weights [G][RS][4 ci][4 co] -> [G][RS][4 co][4 ci]: one dword per (tap, co)
 // holding the group's 4 input channels, the operand shape of v_dot4_i32_i8.
 // One thread per output channel; it also forms that channel's folded offset.
@@ -111,6 +210,37 @@ hipError_t qg_launch_pack_b(const int8_t* B, int K, int N, int ldb, int K_pad, i
                      N, ldb, K_pad, N_pad, packed, col_off);
   hipLaunchKernelGGL(qg_fold_offsets, dim3((N_pad + 255) / 256), dim3(256), 0, s, col_off, bzp_dev,
                      N_pad, K);
+  return hipGetLastError();
+}
+
+hipError_t qg_launch_count_outliers(const int8_t* B, int K, int N, int ldb, unsigned long long* count_dev, hipStream_t s) {
+  hipLaunchKernelGGL(qg_fill_i32, dim3(1), dim3(64), 0, s, reinterpret_cast<int32_t*>(count_dev), 2, 0);
+  const long long total = (long long)K * N;
+  const unsigned blocks = (unsigned)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
+  hipLaunchKernelGGL(qg_count_outliers_kernel, dim3(blocks), dim3(256), 0, s, B, K, N, ldb, count_dev);
+  return hipGetLastError();
+}
+
+hipError_t qg_launch_pack_b_split_count(const int8_t* B, int K, int N, int ldb, int K_pad, int N_pad, uint8_t* packed4,
+                                        int32_t* col_off, const int32_t* bzp_dev, int32_t* frag_ptr, int32_t* cursor,
+                                        hipStream_t s) {
+  const int nfrag = N_pad / QG_FRAG_COLS;
+  hipLaunchKernelGGL(qg_fill_i32, dim3((N_pad + 255) / 256), dim3(256), 0, s, col_off, N_pad, 0);
+  hipLaunchKernelGGL(qg_fill_i32, dim3((nfrag + 1 + 255) / 256), dim3(256), 0, s, frag_ptr, nfrag + 1, 0);
+  const long long total = (long long)N_pad * (K_pad / 16);
+  hipLaunchKernelGGL(qg_pack_b_split_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, B, K, N, ldb,
+                     K_pad, N_pad, packed4, col_off, frag_ptr);
+  hipLaunchKernelGGL(qg_fold_offsets, dim3((N_pad + 255) / 256), dim3(256), 0, s, col_off, bzp_dev, N_pad, K);
+  hipLaunchKernelGGL(qg_scan_frag_kernel, dim3(1), dim3(1024), 0, s, frag_ptr, cursor, nfrag);
+  return hipGetLastError();
+}
+
+hipError_t qg_launch_pack_b_split_fill(const int8_t* B, int K, int N, int ldb, int N_pad, const int32_t* frag_ptr,
+                                       int32_t* cursor, int32_t* entries, hipStream_t s) {
+  (void)N_pad;
+  const long long total = (long long)K * N;
+  const unsigned blocks = (unsigned)((total + 255) / 256 < 8192 ? (total + 255) / 256 : 8192);
+  hipLaunchKernelGGL(qg_fill_outliers_kernel, dim3(blocks), dim3(256), 0, s, B, K, N, ldb, frag_ptr, cursor, entries);
   return hipGetLastError();
 }
 

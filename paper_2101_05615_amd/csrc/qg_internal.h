@@ -37,6 +37,20 @@
 #define QG_NPAD 256
 #define QG_LAYOUT_VERSION 1
 
+// ---------------------------------------------------------------------------
+// Outlier-split layout (paper Sec. 2.2: B = B' + B_sparse)
+//
+// B' (entries -8..7, zero where B holds a larger number) is stored as U = B' + 8 in 4 bits, same
+// fragment order as above at half the size: a fragment is 512 B, lane (nl + 16 g) owns 8 bytes = two
+// dwords; byte b of dword d holds U[k0 + 8d + b] in its low and U[k0 + 8d + 4 + b] in its high nibble
+// (k0 = kb*64 + g*16), so "x & 0x0F0F0F0F" and "(x >> 4) & 0x0F0F0F0F" are two consecutive operand
+// dwords.  The +8 is undone with the row offsets: A_s B' = A_s U - 8 rowsum(A_s).  Padding is U = 8.
+// B_sparse: per 16-column fragment nb16, entries [frag_ptr[nb16], frag_ptr[nb16+1]) of one int32 each:
+// bits 0..14 row k, bits 16..19 slot of the column inside the fragment, bits 24..31 the int8 value.
+// The sparse buffer is [frag_ptr: nfrag+1][cursor: nfrag] int32, rounded up to 256 B, then the entries.
+// ---------------------------------------------------------------------------
+#define QG_FRAG4_BYTES 512
+
 static inline __host__ __device__ int qg_round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 // column within a super-block -> slot (MFMA row index of the 32x32 shape)
@@ -62,6 +76,11 @@ struct qg_packed_b {
   // conv only
   int G, R, S, Cg, Og;
   const int8_t* conv_frags;  // device: matrix-core layout of the conv weights, or null (C % 32 != 0)
+  // outlier split only
+  int split;                 // packed holds 4-bit B', the sparse part is below
+  const int32_t* frag_ptr;   // device: nfrag + 1 offsets into entries
+  const int32_t* entries;    // device
+  long long nnz;             // number of outliers
 };
 
 // Arguments of the GEMM kernels (by value).
@@ -88,6 +107,8 @@ struct qg_gemm_args {
   int a_vec;             // A base and lda are multiples of 16
   int c_vec;             // output base and row pitch are multiples of 16 bytes (uint8 output of the streaming kernels: 4)
   int has_bzp;           // some theta_B != 0: the row-offset term of Eq. (2) is needed
+  const int32_t* sp_ptr;      // outlier split: per-fragment offsets, or null for a dense 8-bit B
+  const int32_t* sp_entries;  // outlier split: entries
 };
 
 struct qg_conv_args {
@@ -141,6 +162,12 @@ __device__ __forceinline__ float qg_dequant_one(int x, float sc, float lo) {
 // launchers (each returns a hipError_t from hipGetLastError after the launch)
 hipError_t qg_launch_pack_b(const int8_t* B, int K, int N, int ldb, int K_pad, int N_pad,
                             int8_t* packed, int32_t* col_off, const int32_t* bzp_dev, hipStream_t s);
+hipError_t qg_launch_count_outliers(const int8_t* B, int K, int N, int ldb, unsigned long long* count_dev, hipStream_t s);
+hipError_t qg_launch_pack_b_split_count(const int8_t* B, int K, int N, int ldb, int K_pad, int N_pad, uint8_t* packed4,
+                                        int32_t* col_off, const int32_t* bzp_dev, int32_t* frag_ptr, int32_t* cursor,
+                                        hipStream_t s);
+hipError_t qg_launch_pack_b_split_fill(const int8_t* B, int K, int N, int ldb, int N_pad, const int32_t* frag_ptr,
+                                       int32_t* cursor, int32_t* entries, hipStream_t s);
 hipError_t qg_launch_pack_conv_w(const int8_t* W, int G, int RS, int8_t* packed, int32_t* col_off,
                                  const int32_t* bzp_dev, int8_t* mfma_frags, hipStream_t s);
 // `kernel` is one of the QG_KERNEL_* ids of qgemm.h (never QG_KERNEL_AUTO: selection happens in api.hip)

@@ -12,7 +12,7 @@ import torch  # noqa: F401  (imported first so that libqgemm binds to the HIP ru
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libqgemm.so")
 
-OK, ENULL, EINVAL, EALIGN, EWORKSPACE, ELAUNCH, ENOMEM, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6, -7
+OK, ENULL, EINVAL, EALIGN, EWORKSPACE, ELAUNCH, ENOMEM, EUNSUPPORTED, ECAPACITY = 0, -1, -2, -3, -4, -5, -6, -7, -8
 MAX_K = 32768
 
 EXPORTS = [
@@ -22,6 +22,7 @@ EXPORTS = [
     "qg_kernel_name", "qg_kernel_select", "qg_dispatch_set_rules", "qg_gemm_u8s8_requant_kernel",
     "qg_gemm_u8s8_acc32_kernel", "qg_gemm_u8s8_dequant_f32", "qg_quantize_a_f32", "qg_gemm_f32_workspace_bytes",
     "qg_gemm_f32s8_requant", "qg_gemm_f32s8_dequant_f32",
+    "qg_count_outliers", "qg_pack_b_outlier_sizes", "qg_pack_b_outlier", "qg_packed_b_nnz",
 ]
 
 KERNEL_AUTO, KERNEL_LAST = 0, 7
@@ -77,6 +78,11 @@ def _load():
     lib.qg_gemm_f32_workspace_bytes.restype = sz
     lib.qg_gemm_f32s8_requant.argtypes = [vp, i, i, f, vp, ctypes.POINTER(RequantParams), vp, i, vp, vp, i]
     lib.qg_gemm_f32s8_dequant_f32.argtypes = [vp, i, i, f, vp, ctypes.POINTER(DequantParams), vp, i, vp, vp, i]
+    lib.qg_count_outliers.argtypes = [vp, i, i, i, vp, ctypes.POINTER(sz), vp]
+    lib.qg_pack_b_outlier_sizes.argtypes = [i, i, sz, ctypes.POINTER(sz), ctypes.POINTER(sz), ctypes.POINTER(sz)]
+    lib.qg_pack_b_outlier.argtypes = [vp, i, i, i, vp, i, sz, vp, vp, vp, vp, ctypes.POINTER(vp)]
+    lib.qg_packed_b_nnz.argtypes = [vp]
+    lib.qg_packed_b_nnz.restype = sz
     return lib
 
 
@@ -152,6 +158,39 @@ def pack_b(B, b_zp):
     _check(lib.qg_pack_b(B.data_ptr(), K, N, B.stride(0), zp, z.size, packed.data_ptr(), aux.data_ptr(),
                          _stream(), ctypes.byref(h)), "qg_pack_b")
     return PackedB(h, packed, aux, N)
+
+
+def count_outliers(B):
+    """Entries of B (int8 cuda [K, N]) outside -8..7."""
+    assert B.is_cuda and B.dtype == torch.int8 and B.dim() == 2 and B.stride(1) == 1
+    K, N = B.shape
+    scratch = torch.empty(1, dtype=torch.int64, device=B.device)
+    n = ctypes.c_size_t()
+    _check(lib.qg_count_outliers(B.data_ptr(), K, N, B.stride(0), scratch.data_ptr(), ctypes.byref(n), _stream()),
+           "qg_count_outliers")
+    return n.value
+
+
+def pack_b_outlier(B, b_zp, max_nnz=None):
+    """Outlier-split descriptor of B: 4-bit B' plus the sparse part (capacity max_nnz, default: exactly enough)."""
+    assert B.is_cuda and B.dtype == torch.int8 and B.dim() == 2 and B.stride(1) == 1
+    K, N = B.shape
+    if max_nnz is None:
+        max_nnz = count_outliers(B)
+    pb, cb, sb = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib.qg_pack_b_outlier_sizes(K, N, max_nnz, ctypes.byref(pb), ctypes.byref(cb), ctypes.byref(sb)),
+           "qg_pack_b_outlier_sizes")
+    packed = torch.empty(pb.value, dtype=torch.int8, device=B.device)
+    aux = torch.empty(cb.value // 4, dtype=torch.int32, device=B.device)
+    sparse = torch.empty(sb.value // 4, dtype=torch.int32, device=B.device)
+    z, zp = _host_i32(b_zp)
+    h = ctypes.c_void_p()
+    _check(lib.qg_pack_b_outlier(B.data_ptr(), K, N, B.stride(0), zp, z.size, max_nnz, packed.data_ptr(),
+                                 aux.data_ptr(), sparse.data_ptr(), _stream(), ctypes.byref(h)), "qg_pack_b_outlier")
+    pk = PackedB(h, packed, aux, N)
+    pk.sparse = sparse
+    pk.nnz = lib.qg_packed_b_nnz(h)
+    return pk
 
 
 def _params(a_zp, bias, scales, c_zp, relu):
