@@ -284,6 +284,30 @@ def main():
                                                                   out=C8, workspace=ws), 10, 3)
         nxt["fp32_ends"]["f32_in_u8_out_8192^3"] = {"ms": round(fms, 4), "TOPS": round(ops / (fms * 1e-3) / 1e12, 1)}
         del Af, Aq, A3, Bp3, Cf, ws, C8
+        # outlier-aware split: the same small-batch GEMM on a dense and on a split descriptor of the same weights
+        # (planted outlier fraction on top of the narrow bulk's own tail), rotating over enough copies that every
+        # launch streams its weights from HBM
+        nxt["outlier_split"] = []
+        for (Ms, Ns, Ks, frac) in [(16, 4096, 4096, 0.01), (16, 8192, 8192, 0.0), (16, 8192, 8192, 0.01)]:
+            Bs = up(wl.outlier_weights(31, Ks, Ns, outlier_frac=frac))
+            As = torch.randint(0, 256, (Ms, Ks), dtype=torch.uint8, device=dev)
+            scs = torch.full((1,), 2.0 ** -9, dtype=torch.float32, device=dev)
+            ncopy = max(4, int(1.2e9 // (Ks * Ns)))
+            rec = {"M": Ms, "N": Ns, "K": Ks, "planted_outlier_frac": frac}
+            for name, pack in (("dense", lambda: q.pack_b(Bs, [0])), ("split", lambda: q.pack_b_outlier(Bs, [0]))):
+                bps = [pack() for _ in range(ncopy)]
+                outs = [torch.empty((Ms, Ns), dtype=torch.uint8, device=dev) for _ in range(ncopy)]
+                calls = [q.PreparedGemm(As, 128, bps[i], None, scs, 128, False, outs[i]) for i in range(ncopy)]
+                _, warm = time_calls(torch, lambda i: calls[0].launch(), 100, 10)
+                _, cold = time_calls(torch, lambda i: calls[i % ncopy].launch(), 2 * ncopy, ncopy)
+                rec[name + "_warm_us"], rec[name + "_cold_us"] = round(warm * 1e3, 2), round(cold * 1e3, 2)
+                if name == "split":
+                    rec["outliers"] = bps[0].nnz
+                    rec["same_bytes_as_dense"] = bool(torch.equal(outs[0], ref_out))
+                else:
+                    ref_out = outs[0].clone()
+                del bps, outs, calls
+            nxt["outlier_split"].append(rec)
 
     out = {
         "metric": "int8 GEMM+requant TOPS at M=N=K=8192", "value": round(tops, 2), "unit": "TOPS",

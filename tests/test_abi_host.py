@@ -90,7 +90,7 @@ def test_null_and_range_checks_happen_before_any_device_work(lib):
 
 
 def test_status_strings(lib):
-    for code in range(0, -8, -1):
+    for code in range(0, -9, -1):
         s = lib.qg_status_string(code)
         assert s and (code == 0) == (s == b"ok")
     assert lib.qg_status_string(-99) == b"unknown status"
