@@ -296,6 +296,22 @@ int qg_conv_groupwise_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W,
                                    int stride, const qg_packed_b* Wp, const qg_requant_params* p,
                                    uint8_t* out_nhwc, void* stream);
 
+/* ---- dense convolution with fused im2col ---------------------------------- */
+
+/* Ordinary (one group) convolution as the same quantized GEMM: rows = output
+ * pixels, K = R*S*Cin ordered (kh, kw, c_in), N = Cout; definition as for the
+ * group-wise call (zero padding in the real domain).  The weights are packed
+ * with qg_pack_b from the row-major (R*S*Cin) x Cout matrix W[kh][kw][ci][co];
+ * the im2col matrix is never materialised: a 64-deep k tile is 64 channels of
+ * one filter tap and is requested straight from the image.
+ *   in_nhwc  dev uint8 [Nb][H][W][Cin], 16-byte aligned;  Cin % 64 == 0
+ *   out_nhwc dev uint8 [Nb][Ho][Wo][Cout], Ho = (H + 2*pad - R)/stride + 1
+ * QG_EUNSUPPORTED for other channel counts or an unaligned image; QG_EINVAL when
+ * R*S*Cin differs from the K of Wp. */
+int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int Cin, int R, int S,
+                               int pad, int stride, const qg_packed_b* Wp, const qg_requant_params* p,
+                               uint8_t* out_nhwc, void* stream);
+
 const char* qg_status_string(int code);
 
 #ifdef __cplusplus

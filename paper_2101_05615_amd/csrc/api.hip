@@ -533,6 +533,68 @@ int qg_gemm_f32s8_dequant_f32(const float* A_dev, int M, int lda, float a_inv_sc
                                   nullptr, stream, kernel);
 }
 
+int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int Cin, int R, int S, int pad,
+                               int stride, const qg_packed_b* Wp, const qg_requant_params* p, uint8_t* out_nhwc,
+                               void* stream) {
+  if (!in_nhwc || !Wp || !out_nhwc) return QG_ENULL;
+  if (Wp->kind != QG_KIND_GEMM || Wp->version != QG_LAYOUT_VERSION) return QG_EINVAL;
+  if (Nb <= 0 || H <= 0 || W <= 0 || Cin <= 0 || R <= 0 || S <= 0 || pad < 0 || stride <= 0) return QG_EINVAL;
+  if ((long long)R * S * Cin != Wp->K) return QG_EINVAL;
+  int rc = check_requant(p, Wp->N);
+  if (rc != QG_OK) return rc;
+  if (H + 2 * pad < R || W + 2 * pad < S) return QG_EINVAL;
+  const int Ho = (H + 2 * pad - R) / stride + 1, Wo = (W + 2 * pad - S) / stride + 1;
+  if (Wp->split || Cin % 64 != 0 || !aligned(in_nhwc, 16)) return QG_EUNSUPPORTED;
+  // 32-bit byte offsets into the image (tap offsets included) and 32-bit pixel counts
+  if ((uint64_t)Nb * H * W * Cin >= (1ull << 30) || (uint64_t)Nb * Ho * Wo >= (1ull << 31) / 4) return QG_EUNSUPPORTED;
+  qg_gemm_args a = {};
+  a.A = in_nhwc;
+  a.Bp = Wp->packed;
+  a.col_off = Wp->col_off;
+  a.bzp = Wp->bzp;
+  a.M = Nb * Ho * Wo;
+  a.N = Wp->N;
+  a.K = Wp->K;
+  a.kb64 = Wp->K_pad / QG_FRAG_K;
+  a.nb16 = Wp->N_pad / QG_FRAG_COLS;
+  a.has_bzp = Wp->has_bzp;
+  a.lda = 0;
+  a.a_vec = 1;
+  a.bias = p->bias;
+  a.scales = p->scales;
+  a.scale_stride = p->n_scales == 1 ? 0 : 1;
+  a.a_zp_m128 = p->a_zp - 128;
+  a.c_zp = p->c_zp;
+  const int lo = p->relu ? p->c_zp : 0;
+  a.clamp_lo = (float)(lo - p->c_zp);
+  a.clamp_hi = (float)(255 - p->c_zp);
+  a.C = out_nhwc;
+  a.ldc = Wp->N;
+  a.c_vec = aligned(out_nhwc, 16) && (Wp->N % 16 == 0);
+  a.cv_H = H;
+  a.cv_W = W;
+  a.cv_Cin = Cin;
+  a.cv_Ho = Ho;
+  a.cv_Wo = Wo;
+  a.cv_S = S;
+  a.cv_stride = stride;
+  a.cv_pad = pad;
+  a.cv_azp = p->a_zp;
+  a.cv_in_bytes = Nb * H * W * Cin;
+  // the tiled kernels with a compiler-scheduled loop, chosen like a GEMM of the same extents
+  int kernel = QG_KERNEL_TILE64;
+  double best_us = 1e300;
+  const double kt = (double)(a.K / 64);
+  for (const tile_cost& c : k_tile_cost) {
+    if (c.kernel == QG_KERNEL_TILE256) continue;
+    const double wgs = (double)ceil_div(a.M, c.bm) * (double)ceil_div(a.N, c.bn);
+    const double us = fmax(c.fix + kt * c.lat, 2.5 + ceil(wgs / 256.0) * (kt * c.thr + c.epi));
+    if (us < best_us) best_us = us, kernel = c.kernel;
+  }
+  const hipError_t e = qg_launch_conv_dense(a, kernel, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? QG_OK : QG_ELAUNCH;
+}
+
 int qg_pack_conv_w_sizes(int G, int R, int S, int Cg, int Og, size_t* packed_bytes,
                          size_t* col_offsets_bytes) {
   if (!packed_bytes || !col_offsets_bytes) return QG_ENULL;

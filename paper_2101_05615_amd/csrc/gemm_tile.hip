@@ -95,7 +95,12 @@ constexpr int min_wg_per_cu(int path, int blocks) {
   return path != PATH_PIPE ? 1 : (blocks >= 8 ? 2 : (blocks >= 4 ? 3 : 4));
 }
 
-template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN>
+// CONV (PATH_PIPE only): dense convolution with the im2col folded into the addressing.  Row m of "A" is
+// output pixel m of the NHWC result; the 64-deep k tile kt is 64 input channels of ONE filter tap
+// (Cin % 64 == 0), so staging a tile is the same request as in the GEMM with the row base moved by the
+// tap's pixel offset.  A tap outside the image must read as theta_A (zero in the real domain): the request
+// address is clamped into the buffer and the fragment is replaced by theta_A bytes when it is fetched.
+template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, bool CONV = false>
 __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void qg_gemm_tile_kernel(const qg_gemm_args p, int tiles_m,
                                                                       int tiles_n) {
   constexpr int NW = NWM * NWN, NT = NW * 64;
@@ -136,11 +141,19 @@ __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void 
   // BN/16 fragments of 1 KiB, one contiguous run of the packed buffer.  Addresses are a wave-uniform
   // base (advanced per tile on the scalar unit) plus a fixed 32-bit per-lane offset.
   unsigned a_voff[A_DMA], b_voff[B_DMA];
+  int a_pix[A_DMA];  // CONV: linear input pixel of tap (0, 0) of the row this lane requests (may be negative)
 #pragma unroll
   for (int q = 0; q < A_DMA; ++q) {
     const int r = (wave * A_DMA + q) * 16 + (lane >> 2);
     const int kc = (lane & 3) ^ ((r >> 1) & 3);
     const int rg = min(m0 + r, p.M - 1);  // rows past M re-read the last row; never stored
+    if (CONV) {
+      const int wo = rg % p.cv_Wo, t = rg / p.cv_Wo;
+      const int ho = t % p.cv_Ho, n = t / p.cv_Ho;
+      a_pix[q] = (n * p.cv_H + ho * p.cv_stride - p.cv_pad) * p.cv_W + wo * p.cv_stride - p.cv_pad;
+      a_voff[q] = kc * 16;
+      continue;
+    }
     // hand-scheduled loop: it uses instruction offset q*1024 (it moves the LDS slot AND the global address, so one
     // M0 serves a group of requests) against a base of A - 3072; the per-lane offset absorbs the difference
     a_voff[q] = (unsigned)rg * (unsigned)p.lda + kc * 16 + (PATH == PATH_ASM ? (3 - q) * 1024 : 0);
@@ -181,9 +194,36 @@ __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void 
   // Row-offset partial sums on the raw uint8 bytes (v_sad_u8 against 0 adds the four bytes of a
   // dword in one plain VALU op; v_dot4 would contend with the MFMAs for the dot-product pipeline),
   // then uint8 -> int8 in place (xor 0x80 == minus 128).
+  // CONV: position of tap (0, 0) of this lane's TM fragment rows, and the validity of the current tap
+  int cv_h[TM], cv_w[TM];
+  bool cv_ok[TM];
+  if (CONV) {
+#pragma unroll
+    for (int mb = 0; mb < TM; ++mb) {
+      const int m = min(m0 + (wave_m * TM + mb) * 32 + l32, p.M - 1);
+      const int wo = m % p.cv_Wo, ho = (m / p.cv_Wo) % p.cv_Ho;
+      cv_h[mb] = ho * p.cv_stride - p.cv_pad;
+      cv_w[mb] = wo * p.cv_stride - p.cv_pad;
+      cv_ok[mb] = true;
+    }
+  }
+  const unsigned azp_word = CONV ? (unsigned)p.cv_azp * 0x01010101u : 0u;
   auto prep = [&](v4i (&af)[TM]) {
 #pragma unroll
     for (int mb = 0; mb < TM; ++mb) {
+      if (CONV) {
+        const unsigned keep = cv_ok[mb] ? 0xFFFFFFFFu : 0u;
+        const unsigned flip = cv_ok[mb] ? 0x80808080u : (azp_word ^ 0x80808080u);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (ROWSUM) {
+            const unsigned y = __builtin_amdgcn_bitop3_b32((unsigned)af[mb][j], keep, azp_word, 0xe2);  // keep ? x : theta_A
+            rs[mb] = __builtin_amdgcn_sad_u8(y, 0u, rs[mb]);
+          }
+          af[mb][j] = (int)__builtin_amdgcn_bitop3_b32((unsigned)af[mb][j], keep, flip, 0x6a);  // (x & keep) ^ flip
+        }
+        continue;
+      }
       if (ROWSUM) {
         rs[mb] = __builtin_amdgcn_sad_u8(af[mb].x, 0u, rs[mb]);
         rs[mb] = __builtin_amdgcn_sad_u8(af[mb].y, 0u, rs[mb]);
@@ -236,10 +276,27 @@ __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void 
     // every wave is done with tile kt-1 -- and that tile's stage is handed to the request for tile kt+2.
     // Instruction order inside the iteration is the compiler's; latency is hidden by the other
     // workgroups on the CU.
+    // CONV: filter tap (kh, kw) and 64-channel slice cc of a k tile, advanced incrementally
+    const int cv_nc = CONV ? p.cv_Cin / BK : 1;
+    int rq_kh = 0, rq_kw = 0, rq_cc = 0;  // of the next tile to request
+    int cs_kh = 0, cs_kw = 0, cs_cc = 0;  // of the tile being consumed
     auto request = [&](int kt, int stage) {
       const uint8_t* ab = p.A + (size_t)kt * BK;
       const int8_t* bb = b_tile0 + (size_t)kt * b_step;
       unsigned char* st = smem + stage * STAGE;
+      if (CONV) {
+        const int tap_pix = rq_kh * p.cv_W + rq_kw;
+#pragma unroll
+        for (int q = 0; q < A_DMA; ++q) {
+          int off = (a_pix[q] + tap_pix) * p.cv_Cin + rq_cc * BK + (int)a_voff[q];
+          off = min(max(off, 0), p.cv_in_bytes - 16);  // taps outside the image: any valid address, masked later
+          dma16(p.A + off, st + (wave * A_DMA + q) * 1024);
+        }
+        if (++rq_cc == cv_nc) {
+          rq_cc = 0;
+          if (++rq_kw == p.cv_S) rq_kw = 0, ++rq_kh;
+        }
+      } else
 #pragma unroll
       for (int q = 0; q < A_DMA; ++q) dma16(ab + a_voff[q], st + (wave * A_DMA + q) * 1024);
 #pragma unroll
@@ -258,6 +315,15 @@ __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void 
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
       if (kt + 2 < KT) request(kt + 2, stage == 0 ? 2 : stage - 1);
+      if (CONV) {
+#pragma unroll
+        for (int mb = 0; mb < TM; ++mb)
+          cv_ok[mb] = (unsigned)(cv_h[mb] + cs_kh) < (unsigned)p.cv_H && (unsigned)(cv_w[mb] + cs_kw) < (unsigned)p.cv_W;
+        if (++cs_cc == cv_nc) {
+          cs_cc = 0;
+          if (++cs_kw == p.cv_S) cs_kw = 0, ++cs_kh;
+        }
+      }
       fetch(stage, 0, a0, b0);
       fetch(stage, 1, a1, b1);
       prep(a0);
@@ -437,7 +503,38 @@ hipError_t launch_cfg(const qg_gemm_args& a, int mode, hipStream_t s) {
   return launch<QG_MODE_ACC32, PATH, true, NWM, NWN, TM, TN>(a, s);
 }
 
+template <int NWM, int NWN, int TM, int TN>
+hipError_t launch_conv(const qg_gemm_args& a, hipStream_t s) {
+  constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
+  constexpr int SMEM = PSTAGE * (BM + BN) * BK;
+  const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+  const dim3 grid((unsigned)(tiles_m * tiles_n)), block(NWM * NWN * 64);
+  hipError_t e;
+  if (a.has_bzp) {
+    auto fn = qg_gemm_tile_kernel<QG_MODE_REQUANT, PATH_PIPE, true, NWM, NWN, TM, TN, true>;
+    e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(fn, grid, block, SMEM, s, a, tiles_m, tiles_n);
+  } else {
+    auto fn = qg_gemm_tile_kernel<QG_MODE_REQUANT, PATH_PIPE, false, NWM, NWN, TM, TN, true>;
+    e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(fn, grid, block, SMEM, s, a, tiles_m, tiles_n);
+  }
+  return hipGetLastError();
+}
+
 }  // namespace
+
+// Dense convolution: a.A is the NHWC image, a.M the number of output pixels, a.K = R*S*Cin with Cin % 64 == 0.
+hipError_t qg_launch_conv_dense(const qg_gemm_args& a, int kernel, hipStream_t s) {
+  switch (kernel) {
+    case QG_KERNEL_TILE64: return launch_conv<2, 2, 1, 1>(a, s);
+    case QG_KERNEL_TILE128: return launch_conv<2, 2, 2, 2>(a, s);
+    case QG_KERNEL_TILE128X256: return launch_conv<2, 2, 2, 4>(a, s);
+    default: return hipErrorInvalidValue;
+  }
+}
 
 hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, int kernel, hipStream_t s) {
   // a.a_vec: A base and lda are multiples of 16 and every byte offset into A fits 32 bits

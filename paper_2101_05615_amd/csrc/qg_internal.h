@@ -109,6 +109,10 @@ struct qg_gemm_args {
   int has_bzp;           // some theta_B != 0: the row-offset term of Eq. (2) is needed
   const int32_t* sp_ptr;      // outlier split: per-fragment offsets, or null for a dense 8-bit B
   const int32_t* sp_entries;  // outlier split: entries
+  // dense convolution through the tiled kernel (A = NHWC image, rows = output pixels, K = (kh, kw, ci)):
+  int cv_H, cv_W, cv_Cin, cv_Ho, cv_Wo, cv_S, cv_stride, cv_pad;
+  int cv_azp;                 // theta_A: what a tap outside the image reads as
+  int cv_in_bytes;            // size of the image buffer
 };
 
 struct qg_conv_args {
@@ -172,6 +176,7 @@ hipError_t qg_launch_pack_conv_w(const int8_t* W, int G, int RS, int8_t* packed,
                                  const int32_t* bzp_dev, int8_t* mfma_frags, hipStream_t s);
 // `kernel` is one of the QG_KERNEL_* ids of qgemm.h (never QG_KERNEL_AUTO: selection happens in api.hip)
 hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, int kernel, hipStream_t s);
+hipError_t qg_launch_conv_dense(const qg_gemm_args& a, int kernel, hipStream_t s);
 hipError_t qg_launch_gemm_skinny(const qg_gemm_args& a, int mode, int kernel, hipStream_t s);
 hipError_t qg_launch_quantize_a(const float* A, int M, int K, int lda, float inv_scale, int a_zp, uint8_t* Aq,
                                 int ldq, hipStream_t s);

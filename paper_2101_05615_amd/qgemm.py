@@ -23,6 +23,7 @@ EXPORTS = [
     "qg_gemm_u8s8_acc32_kernel", "qg_gemm_u8s8_dequant_f32", "qg_quantize_a_f32", "qg_gemm_f32_workspace_bytes",
     "qg_gemm_f32s8_requant", "qg_gemm_f32s8_dequant_f32",
     "qg_count_outliers", "qg_pack_b_outlier_sizes", "qg_pack_b_outlier", "qg_packed_b_nnz",
+    "qg_conv_dense_u8s8_requant",
 ]
 
 KERNEL_AUTO, KERNEL_LAST = 0, 7
@@ -82,6 +83,7 @@ def _load():
     lib.qg_pack_b_outlier_sizes.argtypes = [i, i, sz, ctypes.POINTER(sz), ctypes.POINTER(sz), ctypes.POINTER(sz)]
     lib.qg_pack_b_outlier.argtypes = [vp, i, i, i, vp, i, sz, vp, vp, vp, vp, ctypes.POINTER(vp)]
     lib.qg_packed_b_nnz.argtypes = [vp]
+    lib.qg_conv_dense_u8s8_requant.argtypes = [vp, i, i, i, i, i, i, i, i, vp, ctypes.POINTER(RequantParams), vp, vp]
     lib.qg_packed_b_nnz.restype = sz
     return lib
 
@@ -405,4 +407,28 @@ def conv_groupwise_u8s8_requant(inp, Wp, a_zp, bias, scales, c_zp, relu, pad=1, 
     _check(lib.qg_conv_groupwise_u8s8_requant(inp.data_ptr(), Nb, H, W, C, pad, stride, Wp.handle,
                                               ctypes.byref(p), out.data_ptr(), _stream()),
            "qg_conv_groupwise_u8s8_requant")
+    return out
+
+
+def pack_conv_dense_w(Wt, b_zp):
+    """Dense-convolution weights int8 cuda [R][S][Cin][Cout] -> GEMM descriptor of the (R*S*Cin) x Cout matrix."""
+    assert Wt.is_cuda and Wt.dtype == torch.int8 and Wt.dim() == 4 and Wt.is_contiguous()
+    R, S, Cin, Cout = Wt.shape
+    pk = pack_b(Wt.view(R * S * Cin, Cout), b_zp)
+    pk.R, pk.S = R, S
+    return pk
+
+
+def conv_dense_u8s8_requant(inp, Wp, a_zp, bias, scales, c_zp, relu, pad=1, stride=1, out=None):
+    """inp: uint8 cuda NHWC contiguous, Cin % 64 == 0; Wp from pack_conv_dense_w; returns uint8 NHWC."""
+    assert inp.is_cuda and inp.dtype == torch.uint8 and inp.dim() == 4 and inp.is_contiguous()
+    Nb, H, W, C = inp.shape
+    Ho = (H + 2 * pad - Wp.R) // stride + 1
+    Wo = (W + 2 * pad - Wp.S) // stride + 1
+    if out is None:
+        out = torch.empty((Nb, Ho, Wo, Wp.N), dtype=torch.uint8, device=inp.device)
+    assert out.is_contiguous() and out.shape == (Nb, Ho, Wo, Wp.N)
+    p = _params(a_zp, bias, scales, c_zp, relu)
+    _check(lib.qg_conv_dense_u8s8_requant(inp.data_ptr(), Nb, H, W, C, Wp.R, Wp.S, pad, stride, Wp.handle,
+                                          ctypes.byref(p), out.data_ptr(), _stream()), "qg_conv_dense_u8s8_requant")
     return out

@@ -1,0 +1,86 @@
+"""GPU parity of the dense (one group) convolution with fused im2col against the CPU oracle's direct
+7-loop convolution: identical bytes."""
+import ctypes
+
+import numpy as np
+import pytest
+
+from paper_2101_05615_amd import workloads as wl
+from gpu_util import assert_same, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2101_05615_amd import qgemm as q
+    import oracle
+    oracle.build()
+    return q, torch, torch.device("cuda:0"), oracle
+
+
+def run(c, q, torch, dev):
+    Wp = q.pack_conv_dense_w(torch.from_numpy(np.ascontiguousarray(c.wgt[0])).to(dev), c.b_zp)
+    bias = None if c.bias is None else torch.from_numpy(c.bias).to(dev)
+    out = q.conv_dense_u8s8_requant(torch.from_numpy(c.inp).to(dev), Wp, c.a_zp, bias, torch.from_numpy(c.scales).to(dev),
+                                    c.c_zp, c.relu, pad=c.pad, stride=c.stride)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def want(c, oracle):
+    return oracle.conv_groupwise_direct(c.inp, 1, c.wgt, c.a_zp, c.b_zp, c.bias, c.scales, c.c_zp, c.relu, c.pad, c.stride)
+
+
+@pytest.mark.parametrize("cfg", [
+    dict(Nb=2, H=7, W=9, C=64, Cout=64),                          # ragged pixel count, one channel slice per tap
+    dict(Nb=1, H=3, W=3, C=64, Cout=16),                          # every pixel but the centre sees padding
+    dict(Nb=1, H=12, W=10, C=128, Cout=40),                       # two channel slices per tap, ragged Cout
+    dict(Nb=3, H=9, W=9, C=64, Cout=96, stride=2),
+    dict(Nb=2, H=8, W=8, C=192, Cout=64, R=1, S=1, pad=0),        # 1 x 1: a plain GEMM over pixels
+    dict(Nb=1, H=10, W=11, C=64, Cout=64, R=5, S=5, pad=2),
+    dict(Nb=1, H=9, W=12, C=64, Cout=32, R=3, S=1, pad=1),        # non-square filter, padding wider than the filter needs
+    dict(Nb=2, H=14, W=14, C=256, Cout=300, pad=0),               # no padding, several column tiles
+    dict(Nb=1, H=6, W=6, C=64, Cout=64, pad=3),                   # padding beyond the filter's reach
+])
+@pytest.mark.parametrize("per_channel,with_bias,relu", [(True, True, False), (False, False, True)])
+def test_dense_conv_bit_exact(env, cfg, per_channel, with_bias, relu):
+    q, torch, dev, oracle = env
+    say(f"dense conv {cfg} per_channel={per_channel}")
+    c = wl.random_conv(11, G=1, per_channel=per_channel, with_bias=with_bias, relu=relu, **cfg)
+    assert_same(run(c, q, torch, dev), want(c, oracle), "dense conv")
+
+
+def test_dense_conv_zero_weight_zero_points(env):
+    q, torch, dev, oracle = env
+    c = wl.random_conv(12, Nb=2, H=9, W=7, C=64, G=1, Cout=48)
+    c.b_zp[:] = 0
+    assert_same(run(c, q, torch, dev), want(c, oracle), "dense conv, theta_B = 0")
+
+
+def test_dense_conv_resnet_block_shape(env):
+    """56 x 56 x 64 -> 64, 3 x 3, the first residual stage of a ResNet at batch 4: 12544 pixel rows, K = 576."""
+    q, torch, dev, oracle = env
+    c = wl.random_conv(13, Nb=4, H=56, W=56, C=64, G=1, Cout=64)
+    got, ref = run(c, q, torch, dev), want(c, oracle)
+    assert_same(got, ref, "dense conv 4x56x56x64")
+    assert np.mean((ref > 0) & (ref < 255)) > 0.5
+
+
+def test_dense_conv_errors(env):
+    q, torch, dev, oracle = env
+    c = wl.random_conv(14, Nb=1, H=5, W=5, C=64, G=1, Cout=64)
+    Wp = q.pack_conv_dense_w(torch.from_numpy(np.ascontiguousarray(c.wgt[0])).to(dev), c.b_zp)
+    inp = torch.from_numpy(c.inp).to(dev)
+    out = torch.empty((1, 5, 5, 64), dtype=torch.uint8, device=dev)
+    sc = torch.from_numpy(c.scales).to(dev)
+    p = q.RequantParams(c.a_zp, None, sc.data_ptr(), sc.numel(), c.c_zp, 0)
+    L = q.lib.qg_conv_dense_u8s8_requant
+    assert L(inp.data_ptr(), 1, 5, 5, 64, 3, 3, 1, 1, Wp.handle, ctypes.byref(p), None, None) == q.ENULL
+    assert L(inp.data_ptr(), 1, 5, 5, 64, 1, 1, 0, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None) == q.EINVAL  # K mismatch
+    assert L(inp.data_ptr(), 1, 5, 5, 32, 3, 6, 1, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None) == q.EUNSUPPORTED  # Cin % 64
+    assert L(inp.data_ptr() + 4, 1, 5, 5, 64, 3, 3, 1, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None) == q.EUNSUPPORTED
+    assert L(inp.data_ptr(), 1, 1, 1, 64, 3, 3, 0, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None) == q.EINVAL  # filter larger than image
+    torch.cuda.synchronize()

@@ -288,6 +288,8 @@ def _torch_conv_x(c):
     dict(Nb=2, H=6, W=6, C=8, G=2, stride=2),
     dict(Nb=1, H=5, W=5, C=4, G=1, R=1, S=1, pad=0),
     dict(Nb=1, H=6, W=5, C=8, G=2, pad=2),
+    dict(Nb=2, H=4, W=5, C=6, G=1, Cout=10, stride=2),   # dense convolution, Cout != C
+    dict(Nb=1, H=5, W=5, C=16, G=1, Cout=8, pad=0),
 ])
 def test_conv_direct_matches_torch_conv2d(oracle_mod, cfg):
     c = wl.random_conv(3, **cfg)
