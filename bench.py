@@ -309,6 +309,22 @@ def main():
                 del bps, outs, calls
             nxt["outlier_split"].append(rec)
 
+        # dense convolution with fused im2col: 3 x 3 layers of a ResNet-like network at batch 32
+        nxt["dense_conv"] = []
+        for (Hc, Cc) in [(56, 64), (28, 128), (14, 256)]:
+            cc = wl.random_conv(40 + Cc, Nb=32, H=Hc, W=Hc, C=Cc, G=1, Cout=Cc)
+            Wd = q.pack_conv_dense_w(up(np.ascontiguousarray(cc.wgt[0])), cc.b_zp)
+            xin, scd, bd = up(cc.inp), up(cc.scales), up(cc.bias)
+            yout = torch.empty((32, Hc, Hc, Cc), dtype=torch.uint8, device=dev)
+            _, cms = time_calls(torch, lambda i: q.conv_dense_u8s8_requant(xin, Wd, cc.a_zp, bd, scd, cc.c_zp, False,
+                                                                           out=yout), 50, 5)
+            oc = 2.0 * 32 * Hc * Hc * Cc * 9 * Cc
+            nbc = 2 * xin.numel() + 9 * Cc * Cc
+            nxt["dense_conv"].append({"shape": f"32x{Hc}x{Hc}x{Cc}->{Cc}, 3x3 s1 p1", "us": round(cms * 1e3, 2),
+                                      "TOPS": round(oc / (cms * 1e-3) / 1e12, 1),
+                                      "GBps": round(nbc / (cms * 1e-3) / 1e9, 1)})
+            del xin, yout, Wd
+
     out = {
         "metric": "int8 GEMM+requant TOPS at M=N=K=8192", "value": round(tops, 2), "unit": "TOPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 5),
