@@ -70,6 +70,24 @@ def tune(q, torch, shapes, kernels=None, log=None):
     return rows
 
 
+def summary(rows):
+    """A few lines: how often each kernel wins, and what the automatic choice loses against the measured best."""
+    import math
+    wins = {}
+    for r in rows:
+        wins[r["best"]] = wins.get(r["best"], 0) + 1
+    loss = [r["us"][r["auto"]] / r["us"][r["best"]] for r in rows]
+    worst = sorted(zip(loss, rows), key=lambda t: -t[0])[:5]
+    out = [f"shapes: {len(rows)}",
+           "fastest kernel, number of shapes: " + ", ".join(f"{k} {v}" for k, v in sorted(wins.items())),
+           f"automatic choice vs measured best: geometric mean {math.exp(sum(map(math.log, loss)) / len(loss)):.4f}x, "
+           f"within 5 % on {sum(l <= 1.05 for l in loss)} shapes, worst {max(loss):.2f}x"]
+    for l, r in worst:
+        out.append(f"  worst: {r['M']}x{r['N']}x{r['K']} auto {r['auto']} {r['us'][r['auto']]:.1f} us, "
+                   f"best {r['best']} {r['us'][r['best']]:.1f} us ({l:.2f}x)")
+    return "\n".join(out)
+
+
 def table_from_rows(rows):
     """Exact-shape rules naming the measured winner."""
     return [[r["M"], r["M"], r["N"], r["N"], r["K"], r["K"], r["best"]] for r in rows]
@@ -87,6 +105,7 @@ def main(argv=None):
     ap.add_argument("--shapes", default="", help="comma-separated MxNxK")
     ap.add_argument("--grid", action="store_true", help="the built-in grid of inference-like shapes")
     ap.add_argument("--out", default="", help="write the dispatch table (JSON) here")
+    ap.add_argument("--quiet", action="store_true", help="print only the summary")
     a = ap.parse_args(argv)
     import torch
     from . import qgemm as q
@@ -95,7 +114,8 @@ def main(argv=None):
         shapes += [(M, N, K) for M in GRID_M for N in GRID_N for K in GRID_K if 2.0 * M * N * K <= MAX_OPS]
     if not shapes:
         ap.error("no shapes given")
-    rows = tune(q, torch, shapes, log=lambda s: print(s, flush=True))
+    rows = tune(q, torch, shapes, log=None if a.quiet else (lambda s: print(s, flush=True)))
+    print(summary(rows), flush=True)
     if a.out:
         with open(a.out, "w") as f:
             json.dump({"device": torch.cuda.get_device_name(0), "rules": table_from_rows(rows), "measured": rows}, f,
