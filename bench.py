@@ -24,15 +24,27 @@ PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 MFMA, published
 PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, published
 
 
+SPIN_MS = 60.0  # untimed load before each side measurement, see time_calls
+
+
 def gemm_bytes(M, N, K, bias):
     # algorithmic bytes of one call: A and B read once, C written once, column offsets (+ bias)
     return M * K + K * N + M * N + 4 * N + (4 * N if bias else 0)
 
 
-def time_calls(torch, fn, steps, warmup):
-    """Wall-clock and device-event timing of `steps` back-to-back calls on torch's current stream."""
+def time_calls(torch, fn, steps, warmup, spin_ms=0.0):
+    """Wall-clock and device-event timing of `steps` back-to-back calls on torch's current stream, after
+    `warmup` untimed calls.  spin_ms > 0 keeps issuing untimed calls until that much wall time has passed: the
+    GPU raises its clocks only after some tens of milliseconds of load, which microsecond kernels do not
+    provide in a few dozen warm-up launches."""
     for _ in range(warmup):
         fn(0)
+    if spin_ms > 0.0:
+        t_end = time.perf_counter() + spin_ms * 1e-3
+        while time.perf_counter() < t_end:
+            for i in range(32):
+                fn(i)
+            torch.cuda.synchronize()
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
@@ -101,8 +113,9 @@ def pmc_target(which, torch, q, wl, dev):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=100,
+                    help="untimed launches before the timed ones (the clocks settle after ~75 launches of the headline kernel)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", default="", help="comma list of c1..c5 and next to restrict the side sections")
     ap.add_argument("--pmc-target", default="", choices=["", "c2", "c3", "c4", "c5", "copy"],
@@ -195,7 +208,7 @@ def main():
         nbytes = gemm_bytes(c2.M, c2.N, c2.K, False)
         # warm: same buffers every call (working set 17 MB stays in the 256 MB Infinity Cache)
         warm = q.PreparedGemm(A2, c2.a_zp, Bp2, None, scales2, c2.c_zp, c2.relu, C2)
-        _, warm_ms = time_calls(torch, lambda i: warm.launch(), 200, 20)
+        _, warm_ms = time_calls(torch, lambda i: warm.launch(), 500, 20, spin_ms=SPIN_MS)
         # cold: rotate over distinct packed weights, > 1 GB before any reuse
         nsets = 72
         B2 = up(c2.B)
@@ -204,7 +217,7 @@ def main():
             sets.append((q.pack_b(B2, c2.b_zp), A2.clone(), torch.empty_like(C2)))
         torch.cuda.synchronize()
         cold = [q.PreparedGemm(a, c2.a_zp, bp, None, scales2, c2.c_zp, c2.relu, cc) for bp, a, cc in sets]
-        _, cold_ms = time_calls(torch, lambda i: cold[i % nsets].launch(), 2 * nsets, nsets)
+        _, cold_ms = time_calls(torch, lambda i: cold[i % nsets].launch(), 4 * nsets, nsets, spin_ms=SPIN_MS)
         side.append({"workload": c2.name, "bound": "hbm", "bytes": nbytes,
                      "cold_us": round(cold_ms * 1e3, 2), "warm_us": round(warm_ms * 1e3, 2),
                      "cold_GBps": round(nbytes / (cold_ms * 1e-3) / 1e9, 1),
@@ -220,7 +233,7 @@ def main():
         c = make()
         Ax, Bpx, biasx, scalesx, Cx, packx_ms = gemm_setup(c)
         callx = q.PreparedGemm(Ax, c.a_zp, Bpx, biasx, scalesx, c.c_zp, c.relu, Cx)
-        _, ms = time_calls(torch, lambda i: callx.launch(), 50, 5)
+        _, ms = time_calls(torch, lambda i: callx.launch(), 200, 5, spin_ms=SPIN_MS)
         nb = gemm_bytes(c.M, c.N, c.K, c.bias is not None)
         o = 2.0 * c.M * c.N * c.K
         side.append({"workload": c.name, "us": round(ms * 1e3, 2), "TOPS": round(o / (ms * 1e-3) / 1e12, 2),
@@ -239,8 +252,8 @@ def main():
         ins = [inp.clone() for _ in range(nsets)]
         outs = [torch.empty_like(inp) for _ in range(nsets)]
         convs = [q.PreparedConv(ins[i], Wp, c5.a_zp, None, sc5, c5.c_zp, c5.relu, 1, 1, outs[i]) for i in range(nsets)]
-        _, warm_ms = time_calls(torch, lambda i: convs[0].launch(), 100, 10)
-        _, cold_ms = time_calls(torch, lambda i: convs[i % nsets].launch(), 2 * nsets, nsets)
+        _, warm_ms = time_calls(torch, lambda i: convs[0].launch(), 300, 10, spin_ms=SPIN_MS)
+        _, cold_ms = time_calls(torch, lambda i: convs[i % nsets].launch(), 4 * nsets, nsets, spin_ms=SPIN_MS)
         nb = 2 * inp.numel() + wgt.numel()
         o = 2.0 * inp.shape[0] * 56 * 56 * 128 * 36
         side.append({"workload": c5.name, "bound": "hbm", "bytes": nb, "cold_us": round(cold_ms * 1e3, 2),
@@ -269,19 +282,19 @@ def main():
         g.manual_seed(11)
         Af = torch.rand((Mq, Kq), dtype=torch.float32, device=dev, generator=g) * 12.0 - 4.0
         Aq = torch.empty((Mq, Kq), dtype=torch.uint8, device=dev)
-        _, qms = time_calls(torch, lambda i: q.quantize_a_f32(Af, 1.0 / 0.05, 80, out=Aq), 20, 3)
+        _, qms = time_calls(torch, lambda i: q.quantize_a_f32(Af, 1.0 / 0.05, 80, out=Aq), 50, 3, spin_ms=SPIN_MS)
         nxt["fp32_ends"]["quantize_a_8192x8192"] = {"us": round(qms * 1e3, 1), "bytes": 5 * Mq * Kq,
                                                    "GBps": round(5 * Mq * Kq / (qms * 1e-3) / 1e9, 1),
                                                    "frac_hbm_peak": round(5 * Mq * Kq / (qms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
         c3b = wl.config3_square()
         A3, Bp3, bias3, scales3, _, _ = gemm_setup(c3b)
         Cf = torch.empty((c3b.M, c3b.N), dtype=torch.float32, device=dev)
-        _, dms = time_calls(torch, lambda i: q.gemm_u8s8_dequant_f32(A3, c3b.a_zp, Bp3, bias3, scales3, True, out=Cf), 10, 3)
+        _, dms = time_calls(torch, lambda i: q.gemm_u8s8_dequant_f32(A3, c3b.a_zp, Bp3, bias3, scales3, True, out=Cf), 50, 20)
         nxt["fp32_ends"]["u8_in_f32_out_8192^3"] = {"ms": round(dms, 4), "TOPS": round(ops / (dms * 1e-3) / 1e12, 1)}
         ws = torch.empty(q.gemm_f32_workspace_bytes(Mq, Bp3), dtype=torch.uint8, device=dev)
         C8 = torch.empty((c3b.M, c3b.N), dtype=torch.uint8, device=dev)
         _, fms = time_calls(torch, lambda i: q.gemm_f32s8_requant(Af, 1.0 / 0.05, 80, Bp3, bias3, scales3, 0, True,
-                                                                  out=C8, workspace=ws), 10, 3)
+                                                                  out=C8, workspace=ws), 50, 20)
         nxt["fp32_ends"]["f32_in_u8_out_8192^3"] = {"ms": round(fms, 4), "TOPS": round(ops / (fms * 1e-3) / 1e12, 1)}
         del Af, Aq, A3, Bp3, Cf, ws, C8
         # outlier-aware split: the same small-batch GEMM on a dense and on a split descriptor of the same weights
@@ -298,8 +311,8 @@ def main():
                 bps = [pack() for _ in range(ncopy)]
                 outs = [torch.empty((Ms, Ns), dtype=torch.uint8, device=dev) for _ in range(ncopy)]
                 calls = [q.PreparedGemm(As, 128, bps[i], None, scs, 128, False, outs[i]) for i in range(ncopy)]
-                _, warm = time_calls(torch, lambda i: calls[0].launch(), 100, 10)
-                _, cold = time_calls(torch, lambda i: calls[i % ncopy].launch(), 2 * ncopy, ncopy)
+                _, warm = time_calls(torch, lambda i: calls[0].launch(), 300, 10, spin_ms=SPIN_MS)
+                _, cold = time_calls(torch, lambda i: calls[i % ncopy].launch(), 4 * ncopy, ncopy, spin_ms=SPIN_MS)
                 rec[name + "_warm_us"], rec[name + "_cold_us"] = round(warm * 1e3, 2), round(cold * 1e3, 2)
                 if name == "split":
                     rec["outliers"] = bps[0].nnz
@@ -317,7 +330,7 @@ def main():
             xin, scd, bd = up(cc.inp), up(cc.scales), up(cc.bias)
             yout = torch.empty((32, Hc, Hc, Cc), dtype=torch.uint8, device=dev)
             _, cms = time_calls(torch, lambda i: q.conv_dense_u8s8_requant(xin, Wd, cc.a_zp, bd, scd, cc.c_zp, False,
-                                                                           out=yout), 50, 5)
+                                                                           out=yout), 200, 5, spin_ms=SPIN_MS)
             oc = 2.0 * 32 * Hc * Hc * Cc * 9 * Cc
             nbc = 2 * xin.numel() + 9 * Cc * Cc
             nxt["dense_conv"].append({"shape": f"32x{Hc}x{Hc}x{Cc}->{Cc}, 3x3 s1 p1", "us": round(cms * 1e3, 2),

@@ -20,8 +20,10 @@ GRID_K = [256, 1024, 4096]
 MAX_OPS = 2.5e12  # skip grid points larger than the headline square
 
 
-def time_shape(q, torch, M, N, K, kernels, min_ms=3.0, seed=0):
-    """-> {kernel name: microseconds per launch}; operands drawn on the device from a seeded generator."""
+def time_shape(q, torch, M, N, K, kernels, min_ms=3.0, seed=0, spin_ms=15.0):
+    """-> {kernel name: microseconds per launch}; operands drawn on the device from a seeded generator.
+    Each kernel first runs untimed for spin_ms of wall time, so that it is timed at settled clocks."""
+    import time
     dev = torch.device("cuda:0")
     g = torch.Generator(device=dev)
     g.manual_seed(seed)
@@ -34,9 +36,13 @@ def time_shape(q, torch, M, N, K, kernels, min_ms=3.0, seed=0):
     out = {}
     for name in kernels:
         call = q.PreparedGemm(A, 128, Bp, None, scales, 0, True, C, kernel=name)
-        for _ in range(3):
-            call.launch()
-        torch.cuda.synchronize()
+        t_end = time.perf_counter() + spin_ms * 1e-3
+        while True:
+            for _ in range(8):
+                call.launch()
+            torch.cuda.synchronize()
+            if time.perf_counter() >= t_end:
+                break
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         n, best = 4, None
         while True:

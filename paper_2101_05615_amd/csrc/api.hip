@@ -73,15 +73,15 @@ struct stream_cost {
   double fix, lat_k, wg, wg_k;
 };
 const tile_cost k_tile_cost[] = {
-    {QG_KERNEL_TILE64, 64, 64, 2.7, 0.25, 0.123, 0.26},
-    {QG_KERNEL_TILE128, 128, 128, 3.5, 0.35, 0.334, 1.1},
-    {QG_KERNEL_TILE128X256, 128, 256, 5.1, 0.52, 0.566, 2.0},
-    {QG_KERNEL_TILE256, 256, 256, 7.5, 0.51, 0.99, 6.0},
+    {QG_KERNEL_TILE64, 64, 64, 2.75, 0.24, 0.122, 0.19},
+    {QG_KERNEL_TILE128, 128, 128, 3.9, 0.357, 0.295, 0.94},
+    {QG_KERNEL_TILE128X256, 128, 256, 5.5, 0.527, 0.514, 2.07},
+    {QG_KERNEL_TILE256, 256, 256, 8.7, 0.524, 0.838, 6.87},
 };
 const stream_cost k_stream_cost[] = {
-    {QG_KERNEL_SKINNY16, 16, 3.3, 1.2e-4, 5.4, 1.39e-3},
-    {QG_KERNEL_SKINNY32, 32, 3.5, 7.5e-4, 6.0, 3.8e-3},
-    {QG_KERNEL_SKINNY64, 64, 3.3, 1.75e-3, 7.2, 7.5e-3},
+    {QG_KERNEL_SKINNY16, 16, 3.5, 5.1e-5, 5.86, 1.10e-3},
+    {QG_KERNEL_SKINNY32, 32, 3.13, 8.5e-4, 5.8, 3.83e-3},
+    {QG_KERNEL_SKINNY64, 64, 3.21, 1.79e-3, 7.09, 7.32e-3},
 };
 
 int builtin_select(int M, int N, int K) {
