@@ -271,10 +271,10 @@ int qg_count_outliers(const int8_t* B_dev, int K, int N, int ldb, void* scratch_
   return QG_OK;
 }
 
-// [frag_ptr: nfrag+1][cursor: nfrag] int32, rounded up to 256 B
-static size_t sparse_header_bytes(int N_pad) {
-  const size_t nfrag = (size_t)N_pad / QG_FRAG_COLS;
-  return (size_t)qg_round_up((int)((2 * nfrag + 1) * sizeof(int32_t)), 256);
+// [frag_ptr: nbucket+1][cursor: nbucket] int32, rounded up to 256 B; one bucket per fragment of the packed matrix
+static size_t sparse_buckets(int K_pad, int N_pad) { return (size_t)(N_pad / QG_FRAG_COLS) * (size_t)(K_pad / QG_FRAG_K); }
+static size_t sparse_header_bytes(int K_pad, int N_pad) {
+  return ((2 * sparse_buckets(K_pad, N_pad) + 1) * sizeof(int32_t) + 255) / 256 * 256;
 }
 
 int qg_pack_b_outlier_sizes(int K, int N, size_t max_nnz, size_t* packed_bytes, size_t* col_offsets_bytes,
@@ -285,7 +285,7 @@ int qg_pack_b_outlier_sizes(int K, int N, size_t max_nnz, size_t* packed_bytes, 
   const size_t K_pad = (size_t)qg_round_up(K, QG_KPAD), N_pad = (size_t)qg_round_up(N, QG_NPAD);
   *packed_bytes = K_pad * N_pad / 2;
   *col_offsets_bytes = 2 * N_pad * sizeof(int32_t);
-  *sparse_bytes = sparse_header_bytes((int)N_pad) + (max_nnz ? max_nnz : 1) * sizeof(int32_t);
+  *sparse_bytes = sparse_header_bytes((int)K_pad, (int)N_pad) + (max_nnz ? max_nnz : 1) * sizeof(int32_t);
   return QG_OK;
 }
 
@@ -299,10 +299,11 @@ int qg_pack_b_outlier(const int8_t* B_dev, int K, int N, int ldb, const int32_t*
   if (!aligned(packed_dev, 256) || !aligned(col_offsets_dev, 256) || !aligned(sparse_dev, 256)) return QG_EALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int K_pad = qg_round_up(K, QG_KPAD), N_pad = qg_round_up(N, QG_NPAD);
-  const int nfrag = N_pad / QG_FRAG_COLS;
+  const size_t nbucket = sparse_buckets(K_pad, N_pad);
   int32_t* frag_ptr = static_cast<int32_t*>(sparse_dev);
-  int32_t* cursor = frag_ptr + nfrag + 1;
-  int32_t* entries = reinterpret_cast<int32_t*>(static_cast<unsigned char*>(sparse_dev) + sparse_header_bytes(N_pad));
+  int32_t* cursor = frag_ptr + nbucket + 1;
+  int32_t* entries =
+      reinterpret_cast<int32_t*>(static_cast<unsigned char*>(sparse_dev) + sparse_header_bytes(K_pad, N_pad));
 
   qg_packed_b* h = new (std::nothrow) qg_packed_b();
   if (!h) return QG_ENOMEM;
@@ -330,12 +331,12 @@ int qg_pack_b_outlier(const int8_t* B_dev, int K, int N, int ldb, const int32_t*
                                                   s) != hipSuccess)
     rc = QG_ELAUNCH;
   // the total decides whether the fill may run: it must not write past the caller's capacity
-  if (rc == QG_OK && (hipMemcpyAsync(&total, frag_ptr + nfrag, sizeof(total), hipMemcpyDeviceToHost, s) != hipSuccess ||
+  if (rc == QG_OK && (hipMemcpyAsync(&total, frag_ptr + nbucket, sizeof(total), hipMemcpyDeviceToHost, s) != hipSuccess ||
                       hipStreamSynchronize(s) != hipSuccess))
     rc = QG_ELAUNCH;
   if (rc == QG_OK && (total < 0 || (size_t)total > max_nnz)) rc = QG_ECAPACITY;
   if (rc == QG_OK && total > 0 &&
-      qg_launch_pack_b_split_fill(B_dev, K, N, ldb, N_pad, frag_ptr, cursor, entries, s) != hipSuccess)
+      qg_launch_pack_b_split_fill(B_dev, K, N, ldb, K_pad, frag_ptr, cursor, entries, s) != hipSuccess)
     rc = QG_ELAUNCH;
   if (rc != QG_OK) {
     delete h;
@@ -370,6 +371,7 @@ static int gemm_common(const uint8_t* A_dev, int M, int lda, const qg_packed_b* 
   a->has_bzp = Bp->has_bzp;
   a->sp_ptr = Bp->split ? Bp->frag_ptr : nullptr;
   a->sp_entries = Bp->entries;
+  a->sp_total = (int)Bp->nnz;
   a->lda = lda;
   // vector/DMA path: 16-byte aligned rows and 32-bit byte offsets into A
   a->a_vec = aligned(A_dev, 16) && (lda % 16 == 0) && ((uint64_t)(M - 1) * (uint64_t)lda + (uint64_t)Bp->K + 4096 < (1ull << 32));

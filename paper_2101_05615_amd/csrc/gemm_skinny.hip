@@ -16,9 +16,11 @@
 //
 // Outlier-split weights (Sec. 2.2, B = B' + B_sparse): B' streams in at 4 bits per weight -- half the bytes
 // of the shape this kernel exists for -- and is widened to int8 operand dwords with two bit operations
-// per eight weights; the sparse term A B_sparse is added while the partial sums of the workgroup are still
-// in LDS (the paper fuses it into the output processing while the block of C is cache-resident): the
-// workgroup's threads share the fragment's entries, one (row, entry) product each, into an LDS tile.
+// per eight weights; the sparse term A B_sparse is added while the block of C is still on chip (the paper
+// fuses it into the output processing while the block is cache-resident): a wave that has just consumed a
+// batch of k blocks adds the products of that batch's entries, one (row, entry) pair per lane, into an LDS
+// tile that joins the K-split reduction.  The A bytes come from the wave's staged LDS copy of the batch
+// when there is one (a gather from memory would cost one L1 line per lane).
 //
 // M larger than the row block is covered by the second grid dimension: every row block streams
 // B again (from L2 / the memory-side cache when the blocks run close together), which beats the
@@ -83,9 +85,18 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
   // K slices are dealt to the waves rotated by the workgroup index, so that at any instant the workgroups
   // of an XCD read DIFFERENT lines of A (all of them read all of A; unrotated they would all hit the same
   // L2 channel at the same time)
-  const int per = (p.kb64 + NWAVES - 1) / NWAVES;
+  // (4-bit weights come in pairs of k blocks, so their slices hold an even number of blocks)
+  const int per = B4 ? ((p.kb64 + 2 * NWAVES - 1) / (2 * NWAVES)) * 2 : (p.kb64 + NWAVES - 1) / NWAVES;
   const int kb_begin = ((wave + nb16) % NWAVES) * per;
   const int kb_end = min(p.kb64, kb_begin + per);
+
+  // outlier split: the entry offsets of all of this wave's batches, one per lane (batch b: lanes b and b+1), are
+  // requested before anything else so that no batch waits for an offset before it can ask for its entries
+  int sp_offs = 0;
+  if (B4 && kb_begin < kb_end) {
+    const int32_t* col = p.sp_ptr + (size_t)nb16 * p.kb64;
+    sp_offs = col[min(kb_begin + BATCH * lane, kb_end)];
+  }
 
   v4i acc[MB];
   unsigned rs[MB];  // sums of raw uint8 bytes (K padding reads as 0x80)
@@ -96,28 +107,54 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
     rs[mb] = 0;
     a_row[mb] = p.A + (size_t)min(m_base + mb * 16 + ml, p.M - 1) * p.lda + g * 16;
   }
-  constexpr int FRAG = B4 ? QG_FRAG4_BYTES : QG_FRAG_BYTES;
-  const int8_t* bcol = p.Bp + (size_t)nb16 * FRAG + lane * (FRAG / 64);
-  const size_t b_step = (size_t)p.nb16 * FRAG;  // one 64-deep slab of the packed buffer
+  // 8-bit: one 1 KiB fragment per k block, 16 bytes per lane.  4-bit: one 1 KiB unit per PAIR of k blocks, 16 bytes
+  // per lane (8 for each block), so that a request moves as many bytes as in the 8-bit layout.
+  const int8_t* bcol = p.Bp + (size_t)nb16 * QG_FRAG_BYTES + lane * 16;
+  const size_t b_step = (size_t)p.nb16 * QG_FRAG_BYTES;  // one slab (8-bit: 64 deep, 4-bit: 128 deep) of the packed buffer
 
-  for (int kb = kb_begin; kb < kb_end; kb += BATCH) {
-    v4i bf[BATCH];
+  // Weight requests of one batch: NLOAD loads of 16 bytes per lane, kept RAW (the 4-bit units are widened only
+  // when they are consumed, so that nothing waits for them before the activations have been requested too).
+  constexpr int NLOAD = B4 ? BATCH / 2 : BATCH;
+  static_assert(!B4 || BATCH % 2 == 0, "4-bit weights are fetched in pairs of k blocks");
+  // (every element is loaded unconditionally -- blocks past the end of the slice re-read its last block and are
+  // never used -- so that the loaded registers are plain values and no copy has to wait for them)
+  auto load_b = [&](int kb0, v4i (&raw)[NLOAD]) {
 #pragma unroll
-    for (int j = 0; j < BATCH; ++j)
-      if (kb + j < kb_end) {
-        if (B4) {
-          const uint2 w = *reinterpret_cast<const uint2*>(bcol + (size_t)(kb + j) * b_step);
-          bf[j] = (v4i){(int)(w.x & 0x0F0F0F0Fu), (int)((w.x >> 4) & 0x0F0F0F0Fu), (int)(w.y & 0x0F0F0F0Fu),
-                        (int)((w.y >> 4) & 0x0F0F0F0Fu)};
-        } else {
-          bf[j] = *reinterpret_cast<const v4i*>(bcol + (size_t)(kb + j) * b_step);
-        }
+    for (int i = 0; i < NLOAD; ++i) {
+      const int kbi = min(kb0 + (B4 ? 2 * i : i), kb_end - 1);  // B4: kb0 and kb_end are even
+      raw[i] = *reinterpret_cast<const v4i*>(bcol + (size_t)(B4 ? kbi >> 1 : kbi) * b_step);
+    }
+  };
+  auto operand = [&](const v4i (&raw)[NLOAD], int j) -> v4i {
+    if (!B4) return raw[j];
+    const v4i w = raw[j >> 1];
+    const unsigned lo = (unsigned)((j & 1) ? w.z : w.x), hi = (unsigned)((j & 1) ? w.w : w.y);
+    return (v4i){(int)(lo & 0x0F0F0F0Fu), (int)((lo >> 4) & 0x0F0F0F0Fu), (int)(hi & 0x0F0F0F0Fu),
+                 (int)((hi >> 4) & 0x0F0F0F0Fu)};
+  };
+
+  // One batch: its weights were requested one batch earlier (into `cur`); request its activations and the NEXT
+  // batch's weights (into `nxt`), then wait for the activations only.  Requests complete in order, so
+  // "at most NLOAD outstanding" means that everything older than the next batch's weights has arrived.
+  auto batch = [&](int kb, const v4i (&cur)[NLOAD], v4i (&nxt)[NLOAD], const bool has_next) {
+    constexpr int ROWS = MB * 16;
+    const bool staged = ASTAGE && p.a_vec && kb + BATCH <= kb_end && (kb + BATCH) * QG_FRAG_K <= p.K;
+    unsigned char* region = smem + PART_BYTES + RSP_BYTES + wave * 4096;
+    // outlier split: this batch's entries are one run; the first 64 are requested one per lane right behind the
+    // activations (always exactly one request, clamped into the buffer, so that the wait below can count it)
+    int sp_e0 = 0, sp_ne = 0, sp_first = 0;
+    auto sparse_request = [&]() {
+      if (B4) {
+        const int b = (kb - kb_begin) / BATCH;  // at most 64 batches per wave: K <= 32768 gives 32 blocks per wave
+        sp_e0 = __shfl(sp_offs, b);
+        sp_ne = __shfl(sp_offs, b + 1) - sp_e0;
+        sp_first = p.sp_entries[min(sp_e0 + lane, max(p.sp_total, 1) - 1)];
       }
+    };
     v4i af[MB][BATCH];
-    if (ASTAGE && p.a_vec && kb + BATCH <= kb_end && (kb + BATCH) * QG_FRAG_K <= p.K) {
+    if (staged) {
       // 16 rows x 256 B of A: four requests of 4 rows x 256 B into this wave's LDS region, chunk c of
       // row r stored at chunk c ^ r so that the operand-order reads below are bank-conflict free
-      unsigned char* region = smem + PART_BYTES + RSP_BYTES + wave * 4096;
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
         const int r = jj * 4 + (lane >> 4);
@@ -125,26 +162,38 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                          (__attribute__((address_space(3))) void*)(region + jj * 1024), 16, 0, 0);
       }
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      asm volatile("" ::: "memory");
+      sparse_request();
+      asm volatile("" ::: "memory");
+      if (has_next) {
+        load_b(kb + BATCH, nxt);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NLOAD) : "memory");
+      } else {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      }
 #pragma unroll
       for (int j = 0; j < BATCH; ++j)
         af[0][j] = *reinterpret_cast<const v4i*>(region + ml * 256 + (((4 * j + g) ^ ml) << 4));
-    } else
+    } else {
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
+      for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-      for (int j = 0; j < BATCH; ++j)
-        if (kb + j < kb_end) {
-          const int k = (kb + j) * QG_FRAG_K + g * 16;
-          const int kvalid = p.K - k;
-          if (p.a_vec && kvalid >= 16)
-            af[mb][j] = *reinterpret_cast<const v4i*>(a_row[mb] + (kb + j) * QG_FRAG_K);
-          else
-            af[mb][j] = load_a_chunk_slow(a_row[mb] + (kb + j) * QG_FRAG_K, kvalid);
-        }
+        for (int j = 0; j < BATCH; ++j)
+          if (kb + j < kb_end) {
+            const int k = (kb + j) * QG_FRAG_K + g * 16;
+            const int kvalid = p.K - k;
+            if (p.a_vec && kvalid >= 16)
+              af[mb][j] = *reinterpret_cast<const v4i*>(a_row[mb] + (kb + j) * QG_FRAG_K);
+            else
+              af[mb][j] = load_a_chunk_slow(a_row[mb] + (kb + j) * QG_FRAG_K, kvalid);
+          }
+      sparse_request();
+      if (has_next) load_b(kb + BATCH, nxt);
+    }
 #pragma unroll
     for (int j = 0; j < BATCH; ++j)
       if (kb + j < kb_end) {
+        const v4i bfj = operand(cur, j);
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
           rs[mb] = __builtin_amdgcn_sad_u8(af[mb][j].x, 0u, rs[mb]);
@@ -152,22 +201,52 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
           rs[mb] = __builtin_amdgcn_sad_u8(af[mb][j].z, 0u, rs[mb]);
           rs[mb] = __builtin_amdgcn_sad_u8(af[mb][j].w, 0u, rs[mb]);
           const v4i a = af[mb][j] ^ (int)0x80808080;
-          acc[mb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(bf[j], a, acc[mb], 0, 0, 0);
+          acc[mb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(bfj, a, acc[mb], 0, 0, 0);
         }
       }
-  }
+    if (B4) {
+      // sparse term of this batch: pair idx = (entry idx / ROWS, row idx % ROWS); A_s = A_u - 128.  Entries are
+      // held one per lane, 64 at a time, and handed to the lanes that need them with a shuffle.
+      for (int c0 = 0; c0 < sp_ne; c0 += 64) {
+        const int held = c0 == 0 ? sp_first : (c0 + lane < sp_ne ? p.sp_entries[sp_e0 + c0 + lane] : 0);
+        const int pairs = min(sp_ne - c0, 64) * ROWS;
+        for (int idx = lane; idx < ((pairs + 63) & ~63); idx += 64) {
+          const int ent = __shfl(held, idx / ROWS);  // every lane takes part in the shuffle
+          if (idx >= pairs) continue;
+          const int r = idx % ROWS;
+          const int k = ent & 0x7FFF, slot = (ent >> 16) & 15, v = ent >> 24;
+          int a;
+          if (staged) {
+            const int kk = k - kb * QG_FRAG_K;  // 0..255 inside the staged 16 x 256 block (chunk c of row r at c ^ r)
+            a = region[r * 256 + ((((kk >> 4) ^ r) & 15) << 4) + (kk & 15)];
+          } else {
+            a = p.A[(size_t)min(m_base + r, p.M - 1) * p.lda + k];
+          }
+          atomicAdd(&sp[r * 16 + slot], (a - 128) * v);
+        }
+      }
+    }
+  };
 
-  // ---- sparse term of the outlier split: entry e of this fragment column and row r of the block go to
-  // thread e * rows + r (A is small and L2-resident; the row offsets turn A_u into A_s = A_u - 128)
-  if (B4) {
-    constexpr int ROWS = MB * 16;
-    const int e0 = p.sp_ptr[nb16], ne = p.sp_ptr[nb16 + 1] - e0;
-    for (int idx = tid; idx < ne * ROWS; idx += NWAVES * 64) {
-      const int e = idx / ROWS, r = idx % ROWS;
-      const int ent = p.sp_entries[e0 + e];
-      const int k = ent & 0x7FFF, slot = (ent >> 16) & 15, v = ent >> 24;
-      const int a = p.A[(size_t)min(m_base + r, p.M - 1) * p.lda + k];
-      atomicAdd(&sp[r * 16 + slot], (a - 128) * v);
+  // two register sets alternate; `has_next` is a compile-time constant in each call so that the request of
+  // the next batch is straight-line code
+  if (kb_begin < kb_end) {
+    v4i braw0[NLOAD], braw1[NLOAD];
+    load_b(kb_begin, braw0);
+    int kb = kb_begin;
+    while (true) {
+      if (kb + BATCH >= kb_end) {
+        batch(kb, braw0, braw1, false);
+        break;
+      }
+      batch(kb, braw0, braw1, true);
+      kb += BATCH;
+      if (kb + BATCH >= kb_end) {
+        batch(kb, braw1, braw0, false);
+        break;
+      }
+      batch(kb, braw1, braw0, true);
+      kb += BATCH;
     }
   }
 

@@ -70,7 +70,7 @@ __global__ void qg_count_outliers_kernel(const int8_t* __restrict__ B, int K, in
 
 // As qg_pack_b_kernel, writing 8 bytes of nibbles (U = B' + 8) per thread; the column sums are those of
 // the WHOLE matrix B (the output pipeline corrects A B, not A B'), and the thread counts its outliers
-// into its fragment column.
+// into the bucket of its fragment (fragment column nb16, 64-deep k block kb: bucket nb16 * kb64 + kb).
 __global__ __launch_bounds__(256) void qg_pack_b_split_kernel(const int8_t* __restrict__ B, int K, int N, int ldb,
                                                               int K_pad, int N_pad, uint8_t* __restrict__ packed4,
                                                               int32_t* __restrict__ colsum,
@@ -98,13 +98,14 @@ __global__ __launch_bounds__(256) void qg_pack_b_split_kernel(const int8_t* __re
   const int slot = qg_col_to_slot(c);
   const int nb16 = sb * 2 + (slot >> 4), nl = slot & 15;
   const int kb = kc16 >> 2, g = kc16 & 3;
-  const size_t dst = ((size_t)kb * (N_pad / QG_FRAG_COLS) + nb16) * QG_FRAG4_BYTES + (g * 16 + nl) * 8;
+  // one 1 KiB unit per pair of k blocks: lane (g*16 + nl) owns 16 bytes, 8 for the even and 8 for the odd block
+  const size_t dst = ((size_t)(kb >> 1) * (N_pad / QG_FRAG_COLS) + nb16) * QG_FRAG_BYTES + (g * 16 + nl) * 16 + (kb & 1) * 8;
   *reinterpret_cast<uint2*>(packed4 + dst) = make_uint2(w[0], w[1]);
   if (n < N && sum != 0) atomicAdd(&colsum[n], sum);
-  if (nout) atomicAdd(&frag_cnt[nb16], nout);
+  if (nout) atomicAdd(&frag_cnt[(size_t)nb16 * (K_pad / QG_FRAG_K) + kb], nout);
 }
 
-// exclusive prefix sum of the per-fragment counts (in place: cnt[i] -> offset of fragment i, cnt[n] = total)
+// exclusive prefix sum of the per-bucket counts (in place: cnt[i] -> offset of bucket i, cnt[n] = total)
 // and zeroing of the fill cursors; one workgroup
 __global__ __launch_bounds__(1024) void qg_scan_frag_kernel(int32_t* __restrict__ cnt, int32_t* __restrict__ cursor,
                                                             int n) {
@@ -132,10 +133,10 @@ __global__ __launch_bounds__(1024) void qg_scan_frag_kernel(int32_t* __restrict_
   if (t == 1023) cnt[n] = part[1023];
 }
 
-// every outlier takes the next free entry of its fragment column (order inside a fragment is arbitrary:
-// the sparse term is an integer sum)
+// every outlier takes the next free entry of its bucket (order inside a bucket is arbitrary: the sparse term
+// is an integer sum)
 __global__ __launch_bounds__(256) void qg_fill_outliers_kernel(const int8_t* __restrict__ B, int K, int N, int ldb,
-                                                               const int32_t* __restrict__ frag_ptr,
+                                                               int kb64, const int32_t* __restrict__ frag_ptr,
                                                                int32_t* __restrict__ cursor,
                                                                int32_t* __restrict__ entries) {
   const long long total = (long long)K * N;
@@ -146,8 +147,9 @@ __global__ __launch_bounds__(256) void qg_fill_outliers_kernel(const int8_t* __r
     if (!is_outlier(x)) continue;
     const int slot = qg_col_to_slot(j & 31);
     const int nb16 = (j >> 5) * 2 + (slot >> 4), nl = slot & 15;
-    const int pos = atomicAdd(&cursor[nb16], 1);
-    entries[frag_ptr[nb16] + pos] = (int32_t)((unsigned)k | ((unsigned)nl << 16) | ((unsigned)(x & 0xFF) << 24));
+    const int bucket = nb16 * kb64 + k / QG_FRAG_K;
+    const int pos = atomicAdd(&cursor[bucket], 1);
+    entries[frag_ptr[bucket] + pos] = (int32_t)((unsigned)k | ((unsigned)nl << 16) | ((unsigned)(x & 0xFF) << 24));
   }
 }
 
@@ -224,23 +226,23 @@ hipError_t qg_launch_count_outliers(const int8_t* B, int K, int N, int ldb, unsi
 hipError_t qg_launch_pack_b_split_count(const int8_t* B, int K, int N, int ldb, int K_pad, int N_pad, uint8_t* packed4,
                                         int32_t* col_off, const int32_t* bzp_dev, int32_t* frag_ptr, int32_t* cursor,
                                         hipStream_t s) {
-  const int nfrag = N_pad / QG_FRAG_COLS;
+  const int nbucket = (N_pad / QG_FRAG_COLS) * (K_pad / QG_FRAG_K);
   hipLaunchKernelGGL(qg_fill_i32, dim3((N_pad + 255) / 256), dim3(256), 0, s, col_off, N_pad, 0);
-  hipLaunchKernelGGL(qg_fill_i32, dim3((nfrag + 1 + 255) / 256), dim3(256), 0, s, frag_ptr, nfrag + 1, 0);
+  hipLaunchKernelGGL(qg_fill_i32, dim3((nbucket + 1 + 255) / 256), dim3(256), 0, s, frag_ptr, nbucket + 1, 0);
   const long long total = (long long)N_pad * (K_pad / 16);
   hipLaunchKernelGGL(qg_pack_b_split_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, B, K, N, ldb,
                      K_pad, N_pad, packed4, col_off, frag_ptr);
   hipLaunchKernelGGL(qg_fold_offsets, dim3((N_pad + 255) / 256), dim3(256), 0, s, col_off, bzp_dev, N_pad, K);
-  hipLaunchKernelGGL(qg_scan_frag_kernel, dim3(1), dim3(1024), 0, s, frag_ptr, cursor, nfrag);
+  hipLaunchKernelGGL(qg_scan_frag_kernel, dim3(1), dim3(1024), 0, s, frag_ptr, cursor, nbucket);
   return hipGetLastError();
 }
 
-hipError_t qg_launch_pack_b_split_fill(const int8_t* B, int K, int N, int ldb, int N_pad, const int32_t* frag_ptr,
+hipError_t qg_launch_pack_b_split_fill(const int8_t* B, int K, int N, int ldb, int K_pad, const int32_t* frag_ptr,
                                        int32_t* cursor, int32_t* entries, hipStream_t s) {
-  (void)N_pad;
   const long long total = (long long)K * N;
   const unsigned blocks = (unsigned)((total + 255) / 256 < 8192 ? (total + 255) / 256 : 8192);
-  hipLaunchKernelGGL(qg_fill_outliers_kernel, dim3(blocks), dim3(256), 0, s, B, K, N, ldb, frag_ptr, cursor, entries);
+  hipLaunchKernelGGL(qg_fill_outliers_kernel, dim3(blocks), dim3(256), 0, s, B, K, N, ldb, K_pad / QG_FRAG_K, frag_ptr, cursor,
+                     entries);
   return hipGetLastError();
 }
 

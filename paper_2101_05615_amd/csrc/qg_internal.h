@@ -44,10 +44,16 @@
 // fragment order as above at half the size: a fragment is 512 B, lane (nl + 16 g) owns 8 bytes = two
 // dwords; byte b of dword d holds U[k0 + 8d + b] in its low and U[k0 + 8d + 4 + b] in its high nibble
 // (k0 = kb*64 + g*16), so "x & 0x0F0F0F0F" and "(x >> 4) & 0x0F0F0F0F" are two consecutive operand
-// dwords.  The +8 is undone with the row offsets: A_s B' = A_s U - 8 rowsum(A_s).  Padding is U = 8.
-// B_sparse: per 16-column fragment nb16, entries [frag_ptr[nb16], frag_ptr[nb16+1]) of one int32 each:
+// dwords.  Two fragments of consecutive k blocks (2p, 2p+1) are interleaved into one 1 KiB unit, lane by
+// lane (8 bytes of block 2p, then 8 of block 2p+1), so that one 16-byte-per-lane request fetches both:
+// unit (p, nb16) sits at (p * (N_pad/16) + nb16) * 1024.
+// The +8 is undone with the row offsets: A_s B' = A_s U - 8 rowsum(A_s).  Padding is U = 8.
+// B_sparse: one bucket per fragment (fragment column nb16, 64-deep k block kb), bucket index
+// nb16 * kb64 + kb, holding entries [frag_ptr[bucket], frag_ptr[bucket+1]) of one int32 each:
 // bits 0..14 row k, bits 16..19 slot of the column inside the fragment, bits 24..31 the int8 value.
-// The sparse buffer is [frag_ptr: nfrag+1][cursor: nfrag] int32, rounded up to 256 B, then the entries.
+// The buckets of one fragment column are consecutive, so any run of k blocks of a column is one run of
+// entries.  The sparse buffer is [frag_ptr: nbucket+1][cursor: nbucket] int32, rounded up to 256 B, then
+// the entries.
 // ---------------------------------------------------------------------------
 #define QG_FRAG4_BYTES 512
 
@@ -78,7 +84,7 @@ struct qg_packed_b {
   const int8_t* conv_frags;  // device: matrix-core layout of the conv weights, or null (C % 32 != 0)
   // outlier split only
   int split;                 // packed holds 4-bit B', the sparse part is below
-  const int32_t* frag_ptr;   // device: nfrag + 1 offsets into entries
+  const int32_t* frag_ptr;   // device: nbucket + 1 offsets into entries
   const int32_t* entries;    // device
   long long nnz;             // number of outliers
 };
@@ -107,8 +113,9 @@ struct qg_gemm_args {
   int a_vec;             // A base and lda are multiples of 16
   int c_vec;             // output base and row pitch are multiples of 16 bytes (uint8 output of the streaming kernels: 4)
   int has_bzp;           // some theta_B != 0: the row-offset term of Eq. (2) is needed
-  const int32_t* sp_ptr;      // outlier split: per-fragment offsets, or null for a dense 8-bit B
+  const int32_t* sp_ptr;      // outlier split: per-bucket offsets, or null for a dense 8-bit B
   const int32_t* sp_entries;  // outlier split: entries
+  int sp_total;               // outlier split: number of entries (the buffer holds at least one)
   // dense convolution through the tiled kernel (A = NHWC image, rows = output pixels, K = (kh, kw, ci)):
   int cv_H, cv_W, cv_Cin, cv_Ho, cv_Wo, cv_S, cv_stride, cv_pad;
   int cv_azp;                 // theta_A: what a tap outside the image reads as
@@ -170,7 +177,7 @@ hipError_t qg_launch_count_outliers(const int8_t* B, int K, int N, int ldb, unsi
 hipError_t qg_launch_pack_b_split_count(const int8_t* B, int K, int N, int ldb, int K_pad, int N_pad, uint8_t* packed4,
                                         int32_t* col_off, const int32_t* bzp_dev, int32_t* frag_ptr, int32_t* cursor,
                                         hipStream_t s);
-hipError_t qg_launch_pack_b_split_fill(const int8_t* B, int K, int N, int ldb, int N_pad, const int32_t* frag_ptr,
+hipError_t qg_launch_pack_b_split_fill(const int8_t* B, int K, int N, int ldb, int K_pad, const int32_t* frag_ptr,
                                        int32_t* cursor, int32_t* entries, hipStream_t s);
 hipError_t qg_launch_pack_conv_w(const int8_t* W, int G, int RS, int8_t* packed, int32_t* col_off,
                                  const int32_t* bzp_dev, int8_t* mfma_frags, hipStream_t s);
