@@ -177,14 +177,31 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int ch0 = blockIdx.y * NCH;
-  const int q0 = blockIdx.x * 128;  // first output pixel of the workgroup
+  // Workgroup -> (pixel tile, channel slice).  Workgroup ids go round-robin over the 8 XCDs.  The slices of one
+  // pixel tile touch the two halves of the same 128-byte input and output lines, so they are given ids 8 apart:
+  // same XCD, dispatched back to back, and its L2 fetches each input line once and merges the output halves.
+  // Each XCD walks its own contiguous eighth of the tile sequence, so neighbouring tiles, whose input patches
+  // overlap by the halo rows, also meet in one L2.
+  int tile, slice;
+  {
+    const int nslice = p.C / NCH, ntile = gridDim.x / nslice, id = blockIdx.x;
+    if ((ntile & 7) == 0) {
+      const int j = id >> 3;
+      slice = j % nslice;
+      tile = (id & 7) * (ntile >> 3) + j / nslice;
+    } else {
+      slice = id % nslice;
+      tile = id / nslice;
+    }
+  }
+  const int ch0 = slice * NCH;
+  const int q0 = tile * 128;  // first output pixel of the workgroup
   const int npix = p.Nb * p.H * p.W;
   const int lin0 = q0 - halo;       // linear index of patch pixel 0 (may be negative; clamped per chunk)
 
   // ---- one burst of requests: weights, then the input patch
   {
-    const int8_t* wsrc = p.Wfrag + (size_t)blockIdx.y * NCB * RS * QG_FRAG_BYTES + lane * 16;
+    const int8_t* wsrc = p.Wfrag + (size_t)slice * NCB * RS * QG_FRAG_BYTES + lane * 16;
     for (int f = wave; f < NCB * RS; f += 4) dma16(wsrc + (size_t)f * QG_FRAG_BYTES, w_s + f * QG_FRAG_BYTES);
     for (int c0 = wave * 64; c0 < nchunks_pad; c0 += 256) {
       const int c = c0 + lane;
@@ -360,7 +377,7 @@ hipError_t launch_mfma(const qg_conv_args& a, hipStream_t s) {
 template <int R, int S, int NCB>
 hipError_t launch_same(const qg_conv_args& a, int smem, int halo, int nchunks_pad, hipStream_t s) {
   const int npix = a.Nb * a.H * a.W;
-  const dim3 grid((unsigned)((npix + 127) / 128), (unsigned)(a.C / (NCB * 32)));
+  const dim3 grid((unsigned)(((npix + 127) / 128) * (a.C / (NCB * 32))));
   if (a.has_bzp) {
     hipFuncSetAttribute((const void*)qg_conv_same_mfma_kernel<R, S, NCB, true>,
                         hipFuncAttributeMaxDynamicSharedMemorySize, smem);
