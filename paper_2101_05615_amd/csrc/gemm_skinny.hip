@@ -7,10 +7,11 @@
 //
 // One workgroup owns one 16-column fragment column of B over all of K; wave w
 // takes a contiguous range of 64-deep k blocks and issues a whole batch of loads
-// before the first MFMA so that the whole weight matrix is in flight at once.
-// A (at most 64 rows) comes from L2, is row-summed on its raw bytes (v_sad_u8) and shifted
-// to int8 (xor 0x80) on the way, as in the large kernel.  For M <= 16 each wave stages its own
-// K-slice of A through a private 4 KiB of LDS with global_load_lds: the request reads whole
+// before the first MFMA so that the whole weight matrix is in flight at once; the next
+// batch's weights are requested before the wave waits for the current batch's activations.
+// A (the row block, at most 64 rows) comes from L2, is row-summed on its raw bytes (v_sad_u8) and
+// shifted to int8 (xor 0x80) on the way, as in the large kernel.  With 16-row blocks each wave stages
+// its own K-slice of A through a private 4 KiB of LDS with global_load_lds: the request reads whole
 // 256-byte row segments (MFMA operand order would touch 16 rows x 64 B per load), and the
 // fragment is then fetched from LDS in operand order.
 //

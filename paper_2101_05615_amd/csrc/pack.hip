@@ -55,14 +55,27 @@ __global__ void qg_fold_offsets(int32_t* col_off, const int32_t* __restrict__ bz
 // ---- outlier split (Sec. 2.2): B = B' + B_sparse, B' in 4 bits, B_sparse per fragment -------------------
 __device__ __forceinline__ bool is_outlier(int b) { return b < -8 || b > 7; }
 
-__global__ void qg_count_outliers_kernel(const int8_t* __restrict__ B, int K, int N, int ldb,
-                                         unsigned long long* __restrict__ count) {
-  const long long total = (long long)K * N;
+// one thread per 16 consecutive columns of a row (one 16-byte load when the row allows it), grid-stride
+__global__ __launch_bounds__(256) void qg_count_outliers_kernel(const int8_t* __restrict__ B, int K, int N, int ldb,
+                                                                int vec, unsigned long long* __restrict__ count) {
+  const int n16 = (N + 15) >> 4;
+  const long long total = (long long)K * n16;
   const long long step = (long long)gridDim.x * blockDim.x;
   unsigned n = 0;
   for (long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += step) {
-    const int k = (int)(t / N), j = (int)(t - (long long)k * N);
-    n += is_outlier(B[(size_t)k * ldb + j]);
+    const int k = (int)(t / n16), j0 = (int)(t - (long long)k * n16) * 16;
+    const int8_t* src = B + (size_t)k * ldb + j0;
+    if (vec && j0 + 16 <= N) {
+      union {
+        int4 v;
+        int8_t b[16];
+      } u;
+      u.v = *reinterpret_cast<const int4*>(src);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) n += is_outlier(u.b[i]);
+    } else {
+      for (int i = 0; i < 16 && j0 + i < N; ++i) n += is_outlier(src[i]);
+    }
   }
   for (int o = 32; o > 0; o >>= 1) n += __shfl_xor((int)n, o);
   if ((threadIdx.x & 63) == 0 && n) atomicAdd(count, (unsigned long long)n);
@@ -217,9 +230,10 @@ hipError_t qg_launch_pack_b(const int8_t* B, int K, int N, int ldb, int K_pad, i
 
 hipError_t qg_launch_count_outliers(const int8_t* B, int K, int N, int ldb, unsigned long long* count_dev, hipStream_t s) {
   hipLaunchKernelGGL(qg_fill_i32, dim3(1), dim3(64), 0, s, reinterpret_cast<int32_t*>(count_dev), 2, 0);
-  const long long total = (long long)K * N;
-  const unsigned blocks = (unsigned)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
-  hipLaunchKernelGGL(qg_count_outliers_kernel, dim3(blocks), dim3(256), 0, s, B, K, N, ldb, count_dev);
+  const long long total = (long long)K * ((N + 15) / 16);
+  const unsigned blocks = (unsigned)((total + 255) / 256 < 8192 ? (total + 255) / 256 : 8192);
+  const int vec = reinterpret_cast<uintptr_t>(B) % 16 == 0 && ldb % 16 == 0;
+  hipLaunchKernelGGL(qg_count_outliers_kernel, dim3(blocks), dim3(256), 0, s, B, K, N, ldb, vec, count_dev);
   return hipGetLastError();
 }
 
