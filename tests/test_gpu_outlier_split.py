@@ -85,6 +85,21 @@ def test_split_equals_dense_descriptor_on_config2_shape(env):
     assert_same(C.cpu().numpy(), oracle_gemm(c, oracle), "split, 16 x 4096 x 4096")
 
 
+def test_split_at_the_largest_k(env):
+    """K = 32768: 32 k blocks per wave, eight batches, entry offsets of nine batch boundaries per wave."""
+    q, torch, dev, oracle = env
+    c = split_case(33, 16, 40, q.MAX_K, 0.004, per_channel=True, with_bias=True)
+    A, B, bias, scales, C, _ = dev_case(c, torch, dev)
+    Bp = q.pack_b_outlier(B, c.b_zp)
+    for kernel in STREAM:
+        C.fill_(0xEE)
+        q.gemm_u8s8_requant(A, c.a_zp, Bp, bias, scales, c.c_zp, c.relu, out=C, kernel=kernel)
+        acc = q.gemm_u8s8_acc32(A, Bp, kernel=kernel)
+        torch.cuda.synchronize()
+        assert_same(acc.cpu().numpy(), oracle.acc32(c.A, c.B), f"{kernel} acc32 at K = 32768")
+        assert_same(C.cpu().numpy(), oracle_gemm(c, oracle), f"{kernel} requant at K = 32768")
+
+
 def test_split_with_fp32_activations(env):
     q, torch, dev, oracle = env
     M, N, K, zp = 16, 256, 1024, 90
