@@ -63,7 +63,7 @@ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // pipeline: a big tile moves the fewest LDS bytes per multiply (small `thr` per unit of work) but pays for
 // it with few, long workgroups.  The estimate is the larger of the two regimes.
 // Streaming kernels.  One workgroup per 16 columns and per row block; alone it takes fix + K * lat_k us, with
-// the chip full each workgroup costs wg + K * wg_k nanoseconds.
+// the chip full each workgroup costs wg + K * wg_k nanoseconds; a third bound covers tall, narrow shapes.
 struct tile_cost {
   int kernel, bm, bn;
   double fix, lat, thr, epi;
@@ -79,10 +79,19 @@ const tile_cost k_tile_cost[] = {
     {QG_KERNEL_TILE256, 256, 256, 8.7, 0.524, 0.838, 6.87},
 };
 const stream_cost k_stream_cost[] = {
-    {QG_KERNEL_SKINNY16, 16, 3.5, 5.1e-5, 5.86, 1.10e-3},
-    {QG_KERNEL_SKINNY32, 32, 3.13, 8.5e-4, 5.8, 3.83e-3},
-    {QG_KERNEL_SKINNY64, 64, 3.21, 1.79e-3, 7.09, 7.32e-3},
+    {QG_KERNEL_SKINNY16, 16, 3.58, 7.3e-5, 7.55, 0.74e-3},
+    {QG_KERNEL_SKINNY32, 32, 4.13, 1.99e-4, 10.33, 1.28e-3},
+    {QG_KERNEL_SKINNY64, 64, 4.96, 3.88e-4, 14.26, 2.23e-3},
 };
+// A streaming workgroup re-reads its rows of A for every 16 columns; with few columns to share them that
+// traffic comes from far memory, row piece by row piece, at about this many bytes per microsecond.
+const double k_stream_a_rate = 2.0e6;
+
+double stream_estimate(const stream_cost& c, int M, int N, int K) {
+  const double wgs = (double)ceil_div(M, c.rows) * (double)(2 * ceil_div(N, 32));
+  const double a_bound = 2.5 + (double)M * (double)K / k_stream_a_rate;
+  return fmax(fmax(c.fix + K * c.lat_k, 2.5 + wgs * (c.wg + K * c.wg_k) * 1e-3), a_bound);
+}
 
 int builtin_select(int M, int N, int K) {
   const double kt = (double)ceil_div(K, 64);
@@ -91,8 +100,7 @@ int builtin_select(int M, int N, int K) {
   for (const stream_cost& c : k_stream_cost) {
     const long long blocks = ceil_div(M, c.rows);
     if (blocks > 65535) continue;
-    const double wgs = (double)blocks * (double)(2 * ceil_div(N, 32));
-    const double us = fmax(c.fix + K * c.lat_k, 2.5 + wgs * (c.wg + K * c.wg_k) * 1e-3);
+    const double us = stream_estimate(c, M, N, K);
     if (us < best_us) best_us = us, best = c.kernel;
   }
   for (const tile_cost& c : k_tile_cost) {
@@ -111,8 +119,7 @@ int select_stream_kernel(int M, int N, int K) {
   for (const stream_cost& c : k_stream_cost) {
     const long long blocks = ceil_div(M, c.rows);
     if (blocks > 65535) continue;
-    const double wgs = (double)blocks * (double)(2 * ceil_div(N, 32));
-    const double us = fmax(c.fix + K * c.lat_k, 2.5 + wgs * (c.wg + K * c.wg_k) * 1e-3);
+    const double us = stream_estimate(c, M, N, K);
     if (us < best_us) best_us = us, best = c.kernel;
   }
   return best;

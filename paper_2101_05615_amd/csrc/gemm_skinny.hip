@@ -44,14 +44,19 @@ __device__ __forceinline__ v4i load_a_chunk_slow(const uint8_t* p, int kvalid) {
 
 template <int MODE, int MB, int NWAVES, int BATCH, bool B4>
 __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_gemm_args p) {
-  constexpr bool ASTAGE = (MB == 1 && BATCH == 4);  // A through LDS (see the file header)
+  // A through LDS (see the file header): per wave and batch, ROWS rows x ROWB bytes
+  constexpr int ROWS = MB * 16, ROWB = BATCH * QG_FRAG_K, NCHUNK = ROWB / 16;
+  constexpr int REGION = ROWS * ROWB, NREQ = REGION / 1024, RPR = 64 / NCHUNK;  // requests per batch, rows per request
+  static_assert(NCHUNK == 8 || NCHUNK == 16, "a request covers whole rows of 128 or 256 bytes");
   constexpr int PART_BYTES = NWAVES * MB * 64 * (int)sizeof(v4i);
   constexpr int RSP_BYTES = NWAVES * MB * 16 * (int)sizeof(int);
-  constexpr int ASTAGE_BYTES = ASTAGE ? NWAVES * 4096 : 0;
+  constexpr int STAGE_BYTES = NWAVES * REGION;
+  // the K-split partial sums reuse the staging regions once the main loop is over
+  constexpr int UNION_BYTES = STAGE_BYTES > PART_BYTES ? STAGE_BYTES : PART_BYTES;
   extern __shared__ __align__(16) unsigned char smem[];
   v4i* part = reinterpret_cast<v4i*>(smem);                 // [wave][mb][lane]
-  int* rsp = reinterpret_cast<int*>(smem + PART_BYTES);     // [wave][mb][16]
-  int* sp = reinterpret_cast<int*>(smem + PART_BYTES + RSP_BYTES + ASTAGE_BYTES);  // B4: [row][slot] sparse term
+  int* rsp = reinterpret_cast<int*>(smem + UNION_BYTES);    // [wave][mb][16]
+  int* sp = reinterpret_cast<int*>(smem + UNION_BYTES + RSP_BYTES);  // B4: [row][slot] sparse term
 
   const int nb16 = blockIdx.x;
   const int sb = nb16 >> 1, sfrag = nb16 & 1;
@@ -101,17 +106,25 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
 
   v4i acc[MB];
   unsigned rs[MB];  // sums of raw uint8 bytes (K padding reads as 0x80)
-  const uint8_t* a_row[MB];
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
     acc[mb] = (v4i){0, 0, 0, 0};
     rs[mb] = 0;
-    a_row[mb] = p.A + (size_t)min(m_base + mb * 16 + ml, p.M - 1) * p.lda + g * 16;
   }
   // 8-bit: one 1 KiB fragment per k block, 16 bytes per lane.  4-bit: one 1 KiB unit per PAIR of k blocks, 16 bytes
   // per lane (8 for each block), so that a request moves as many bytes as in the 8-bit layout.
   const int8_t* bcol = p.Bp + (size_t)nb16 * QG_FRAG_BYTES + lane * 16;
   const size_t b_step = (size_t)p.nb16 * QG_FRAG_BYTES;  // one slab (8-bit: 64 deep, 4-bit: 128 deep) of the packed buffer
+
+  // per-lane byte offsets of the NREQ activation requests of a batch (a.a_vec: they fit 32 bits); with them the
+  // request address is a wave-uniform base plus a register that is never the target of a load, so issuing
+  // the requests never has to wait for loads in flight
+  unsigned a_off[NREQ];
+#pragma unroll
+  for (int jj = 0; jj < NREQ; ++jj) {
+    const int r = jj * RPR + lane / NCHUNK;
+    a_off[jj] = (unsigned)min(m_base + r, p.M - 1) * (unsigned)p.lda + ((unsigned)((lane ^ r) & (NCHUNK - 1)) << 4);
+  }
 
   // Weight requests of one batch: NLOAD loads of 16 bytes per lane, kept RAW (the 4-bit units are widened only
   // when they are consumed, so that nothing waits for them before the activations have been requested too).
@@ -138,9 +151,8 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
   // batch's weights (into `nxt`), then wait for the activations only.  Requests complete in order, so
   // "at most NLOAD outstanding" means that everything older than the next batch's weights has arrived.
   auto batch = [&](int kb, const v4i (&cur)[NLOAD], v4i (&nxt)[NLOAD], const bool has_next) {
-    constexpr int ROWS = MB * 16;
-    const bool staged = ASTAGE && p.a_vec && kb + BATCH <= kb_end && (kb + BATCH) * QG_FRAG_K <= p.K;
-    unsigned char* region = smem + PART_BYTES + RSP_BYTES + wave * 4096;
+    const bool staged = p.a_vec && kb + BATCH <= kb_end && (kb + BATCH) * QG_FRAG_K <= p.K;
+    unsigned char* region = smem + wave * REGION;
     // outlier split: this batch's entries are one run; the first 64 are requested one per lane right behind the
     // activations (always exactly one request, clamped into the buffer, so that the wait below can count it)
     int sp_e0 = 0, sp_ne = 0, sp_first = 0;
@@ -154,15 +166,13 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
     };
     v4i af[MB][BATCH];
     if (staged) {
-      // 16 rows x 256 B of A: four requests of 4 rows x 256 B into this wave's LDS region, chunk c of
+      // ROWS rows x ROWB bytes of A: NREQ requests of RPR whole rows into this wave's LDS region, chunk c of
       // row r stored at chunk c ^ r so that the operand-order reads below are bank-conflict free
+      const uint8_t* a_base = p.A + (size_t)kb * QG_FRAG_K;  // wave-uniform
 #pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        const int r = jj * 4 + (lane >> 4);
-        const uint8_t* src = p.A + (size_t)min(m_base + r, p.M - 1) * p.lda + kb * QG_FRAG_K + (((lane & 15) ^ r) << 4);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+      for (int jj = 0; jj < NREQ; ++jj)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a_base + a_off[jj]),
                                          (__attribute__((address_space(3))) void*)(region + jj * 1024), 16, 0, 0);
-      }
       asm volatile("" ::: "memory");
       sparse_request();
       asm volatile("" ::: "memory");
@@ -172,25 +182,33 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
       } else {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       }
-#pragma unroll
-      for (int j = 0; j < BATCH; ++j)
-        af[0][j] = *reinterpret_cast<const v4i*>(region + ml * 256 + (((4 * j + g) ^ ml) << 4));
     } else {
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int j = 0; j < BATCH; ++j)
-          if (kb + j < kb_end) {
-            const int k = (kb + j) * QG_FRAG_K + g * 16;
-            const int kvalid = p.K - k;
-            if (p.a_vec && kvalid >= 16)
-              af[mb][j] = *reinterpret_cast<const v4i*>(a_row[mb] + (kb + j) * QG_FRAG_K);
-            else
-              af[mb][j] = load_a_chunk_slow(a_row[mb] + (kb + j) * QG_FRAG_K, kvalid);
-          }
+      // any pointer, lda and K, partial batches: the lanes copy the block into the region themselves, 16-byte
+      // chunk by chunk (bytes past K as 0x80, the int8 zero after the shift), in the same swizzled layout
+      const int nchunk = min(BATCH, kb_end - kb) * 4;  // 16-byte chunks per row that this batch will consume
+#pragma unroll 1
+      for (int i = lane; i < ROWS * nchunk; i += 64) {
+        const int r = i / nchunk, lc = i % nchunk;     // row, logical chunk
+        const int c = r * NCHUNK + ((lc ^ r) & (NCHUNK - 1));
+        const int k0 = kb * QG_FRAG_K + (lc << 4);
+        const uint8_t* src = p.A + (size_t)min(m_base + r, p.M - 1) * p.lda + k0;
+        v4i v;
+        if (p.a_vec && k0 + 16 <= p.K)
+          v = *reinterpret_cast<const v4i*>(src);
+        else
+          v = load_a_chunk_slow(src, p.K - k0);
+        *reinterpret_cast<v4i*>(region + c * 16) = v;
+      }
       sparse_request();
       if (has_next) load_b(kb + BATCH, nxt);
     }
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int j = 0; j < BATCH; ++j) {
+        const int r = mb * 16 + ml;
+        af[mb][j] = *reinterpret_cast<const v4i*>(region + r * ROWB + ((((4 * j + g) ^ r) & (NCHUNK - 1)) << 4));
+      }
 #pragma unroll
     for (int j = 0; j < BATCH; ++j)
       if (kb + j < kb_end) {
@@ -216,42 +234,27 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
           if (idx >= pairs) continue;
           const int r = idx % ROWS;
           const int k = ent & 0x7FFF, slot = (ent >> 16) & 15, v = ent >> 24;
-          int a;
-          if (staged) {
-            const int kk = k - kb * QG_FRAG_K;  // 0..255 inside the staged 16 x 256 block (chunk c of row r at c ^ r)
-            a = region[r * 256 + ((((kk >> 4) ^ r) & 15) << 4) + (kk & 15)];
-          } else {
-            a = p.A[(size_t)min(m_base + r, p.M - 1) * p.lda + k];
-          }
+          const int kk = k - kb * QG_FRAG_K;  // inside the staged ROWS x ROWB block (chunk c of row r at c ^ r)
+          const int a = region[r * ROWB + ((((kk >> 4) ^ r) & (NCHUNK - 1)) << 4) + (kk & 15)];
           atomicAdd(&sp[r * 16 + slot], (a - 128) * v);
         }
       }
     }
   };
 
-  // two register sets alternate; `has_next` is a compile-time constant in each call so that the request of
-  // the next batch is straight-line code
+  // two register sets alternate
   if (kb_begin < kb_end) {
     v4i braw0[NLOAD], braw1[NLOAD];
     load_b(kb_begin, braw0);
-    int kb = kb_begin;
-    while (true) {
-      if (kb + BATCH >= kb_end) {
-        batch(kb, braw0, braw1, false);
-        break;
-      }
-      batch(kb, braw0, braw1, true);
-      kb += BATCH;
-      if (kb + BATCH >= kb_end) {
-        batch(kb, braw1, braw0, false);
-        break;
-      }
-      batch(kb, braw1, braw0, true);
-      kb += BATCH;
+    for (int kb = kb_begin; kb < kb_end; kb += 2 * BATCH) {
+      batch(kb, braw0, braw1, kb + BATCH < kb_end);
+      if (kb + BATCH < kb_end) batch(kb + BATCH, braw1, braw0, kb + 2 * BATCH < kb_end);
     }
   }
 
-  // ---- combine the 16 K-slices through LDS
+  // ---- combine the 16 K-slices through LDS (the partial sums overwrite the staging regions: every wave must
+  // be done with its own first)
+  __syncthreads();
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
     part[(wave * MB + mb) * 64 + lane] = acc[mb];
@@ -321,8 +324,9 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
 
 template <int MODE, int MB, int NWAVES, int BATCH, bool B4>
 hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
-  const int smem = NWAVES * MB * 64 * (int)sizeof(v4i) + NWAVES * MB * 16 * (int)sizeof(int) +
-                   ((MB == 1 && BATCH == 4) ? NWAVES * 4096 : 0) + (B4 ? MB * 256 * (int)sizeof(int) : 0);
+  const int part = NWAVES * MB * 64 * (int)sizeof(v4i), stage = NWAVES * (MB * 16) * (BATCH * QG_FRAG_K);
+  const int smem = (stage > part ? stage : part) + NWAVES * MB * 16 * (int)sizeof(int) +
+                   (B4 ? MB * 256 * (int)sizeof(int) : 0);
   hipError_t e = hipFuncSetAttribute((const void*)qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH, B4>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, smem);
   if (e != hipSuccess) return e;
