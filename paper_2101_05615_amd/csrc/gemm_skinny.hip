@@ -10,10 +10,12 @@
 // before the first MFMA so that the whole weight matrix is in flight at once; the next
 // batch's weights are requested before the wave waits for the current batch's activations.
 // A (the row block, at most 64 rows) comes from L2, is row-summed on its raw bytes (v_sad_u8) and
-// shifted to int8 (xor 0x80) on the way, as in the large kernel.  With 16-row blocks each wave stages
-// its own K-slice of A through a private 4 KiB of LDS with global_load_lds: the request reads whole
-// 256-byte row segments (MFMA operand order would touch 16 rows x 64 B per load), and the
-// fragment is then fetched from LDS in operand order.
+// shifted to int8 (xor 0x80) on the way, as in the large kernel.  Each wave stages its own K-slice of
+// the row block, batch by batch, through a private 4 or 8 KiB of LDS with global_load_lds: a request
+// reads whole 128- or 256-byte row segments (MFMA operand order would touch 16 rows x 64 B per load,
+// half-used lines, which cost more than the weight stream itself at 64 rows), and the fragments are then
+// fetched from LDS in operand order.  Unaligned A, ragged K and partial batches take the same route
+// with the lanes copying the bytes themselves.
 //
 // Outlier-split weights (Sec. 2.2, B = B' + B_sparse): B' streams in at 4 bits per weight -- half the bytes
 // of the shape this kernel exists for -- and is widened to int8 operand dwords with two bit operations

@@ -55,7 +55,6 @@
 // entries.  The sparse buffer is [frag_ptr: nbucket+1][cursor: nbucket] int32, rounded up to 256 B, then
 // the entries.
 // ---------------------------------------------------------------------------
-#define QG_FRAG4_BYTES 512
 
 static inline __host__ __device__ int qg_round_up(int x, int m) { return (x + m - 1) / m * m; }
 
