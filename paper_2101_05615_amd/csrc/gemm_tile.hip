@@ -37,7 +37,16 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 64;      // k extent of one LDS stage = one packed fragment deep
 constexpr int NSTAGE = 4;   // LDS stages of the hand-scheduled loop: three tiles in flight behind the one being consumed
-constexpr int PSTAGE = 3;   // LDS stages of the compiler-scheduled loop
+// LDS stages of the compiler-scheduled loop, by 32 x 32 blocks per wave.  Three everywhere: measured with 3 to 8
+// stages, a thin grid's k step (0.28 us at 64 x 64) does not get shorter with more tiles in flight -- it is the
+// barrier / LDS read / MFMA chain of a lone workgroup -- while deeper buffers cost occupancy on full grids.
+#ifndef QG_PS_SMALL
+#define QG_PS_SMALL 3
+#endif
+#ifndef QG_PS_MID
+#define QG_PS_MID 3
+#endif
+constexpr int pipe_stages(int blocks) { return blocks >= 8 ? 3 : (blocks >= 4 ? QG_PS_MID : QG_PS_SMALL); }
 
 // main-loop flavours
 constexpr int PATH_GENERAL = 0;  // any pointer, lda, K: one stage, byte-wise bounds-checked A
@@ -47,6 +56,18 @@ constexpr int PATH_PIPE = 2;     // any tile shape, compiler-scheduled, three st
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// wait until at most min(younger, I) tiles of N_DMA requests each are still in flight
+template <int I, int N_DMA>
+__device__ __forceinline__ void wait_tiles(int younger) {
+  if constexpr (I == 0) {
+    wait_vmcnt<0>();
+  } else {
+    if (younger >= I)
+      wait_vmcnt<I * N_DMA>();
+    else
+      wait_tiles<I - 1, N_DMA>(younger);
+  }
 }
 // 16 bytes per lane from global memory into LDS at lds_base + lane*16 (lds_base wave-uniform)
 __device__ __forceinline__ void dma16(const void* gptr, unsigned char* lds_base) {
@@ -110,7 +131,8 @@ __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void 
   constexpr int B_DMA = B_STAGE / 1024 / NW;
   constexpr int N_DMA = A_DMA + B_DMA;
   static_assert(A_STAGE % (1024 * NW) == 0 && B_STAGE % (1024 * NW) == 0, "tile/wave mismatch");
-  static_assert(2 * N_DMA <= 63, "vmcnt is a 6-bit counter");
+  constexpr int NS = pipe_stages(TM * TN);  // PATH_PIPE
+  static_assert((PATH == PATH_PIPE ? NS - 2 : 2) * N_DMA <= 63, "vmcnt is a 6-bit counter");
   extern __shared__ __align__(16) unsigned char smem[];
 
   const int tid = threadIdx.x;
@@ -270,10 +292,10 @@ __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void 
     rs[2] = (unsigned)rs23;
     rs[3] = (unsigned)(rs23 >> 32);
   } else if constexpr (PATH == PATH_PIPE) {
-    // Tile kt lives in stage kt % 3; two tiles are in flight behind the one being consumed.  At the top of
+    // Tile kt lives in stage kt % NS; NS-2 tiles are in flight behind the one being consumed.  At the top of
     // iteration kt a wave waits until ITS requests for tile kt have landed (younger ones may still be in
     // flight: requests complete in order), the workgroup meets at one barrier -- which also says that
-    // every wave is done with tile kt-1 -- and that tile's stage is handed to the request for tile kt+2.
+    // every wave is done with tile kt-1 -- and that tile's stage is handed to the request for tile kt+NS-1.
     // Instruction order inside the iteration is the compiler's; latency is hidden by the other
     // workgroups on the CU.
     // CONV: filter tap (kh, kw) and 64-channel slice cc of a k tile, advanced incrementally
@@ -302,19 +324,16 @@ __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void 
 #pragma unroll
       for (int q = 0; q < B_DMA; ++q) dma16(bb + b_voff[q], st + A_STAGE + (wave * B_DMA + q) * 1024);
     };
-    static_assert(PSTAGE == 3, "the waits below assume at most two tiles in flight");
-    request(0, 0);
-    if (KT > 1) request(1, 1);
+#pragma unroll
+    for (int t = 0; t < NS - 1; ++t)
+      if (t < KT) request(t, t);
     int stage = 0;
     for (int kt = 0; kt < KT; ++kt) {
-      if (kt + 1 < KT)
-        wait_vmcnt<N_DMA>();
-      else
-        wait_vmcnt<0>();
+      wait_tiles<NS - 2, N_DMA>(KT - 1 - kt);  // tile kt has landed; up to NS-2 younger ones may be in flight
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
-      if (kt + 2 < KT) request(kt + 2, stage == 0 ? 2 : stage - 1);
+      if (kt + NS - 1 < KT) request(kt + NS - 1, stage == 0 ? NS - 1 : stage - 1);
       if (CONV) {
 #pragma unroll
         for (int mb = 0; mb < TM; ++mb)
@@ -330,7 +349,7 @@ __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void 
       mma(a0, b0);
       prep(a1);
       mma(a1, b1);
-      stage = stage == 2 ? 0 : stage + 1;
+      stage = stage == NS - 1 ? 0 : stage + 1;
     }
   } else {
     // General path: one stage, no overlap.  A goes through registers byte by byte with bounds checks;
@@ -478,7 +497,7 @@ __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void 
 template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN>
 hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
-  constexpr int STAGES = PATH == PATH_ASM ? NSTAGE : (PATH == PATH_PIPE ? PSTAGE : 1);
+  constexpr int STAGES = PATH == PATH_ASM ? NSTAGE : (PATH == PATH_PIPE ? pipe_stages(TM * TN) : 1);
   // the output pipeline's per-column constants (12 B per column) reuse the stage memory
   constexpr int SMEM = STAGES * (BM + BN) * BK > 12 * BN ? STAGES * (BM + BN) * BK : 12 * BN;
   const int tiles_m = (a.M + BM - 1) / BM;
@@ -506,7 +525,7 @@ hipError_t launch_cfg(const qg_gemm_args& a, int mode, hipStream_t s) {
 template <int NWM, int NWN, int TM, int TN>
 hipError_t launch_conv(const qg_gemm_args& a, hipStream_t s) {
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
-  constexpr int SMEM = PSTAGE * (BM + BN) * BK;
+  constexpr int SMEM = pipe_stages(TM * TN) * (BM + BN) * BK;
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
   const dim3 grid((unsigned)(tiles_m * tiles_n)), block(NWM * NWN * 64);
   hipError_t e;
