@@ -363,12 +363,10 @@ hipError_t launch_mfma(const qg_conv_args& a, hipStream_t s) {
   const int nblk = (a.Nb * a.Ho * a.Wo + 31) / 32;
   const dim3 grid((unsigned)min((nblk + 3) / 4, 2048), (unsigned)(a.C / (NCB * 32)));
   if (a.has_bzp) {
-    hipFuncSetAttribute((const void*)qg_conv_group_mfma_kernel<R, S, NCB, true>,
-                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (hipError_t e = qg_allow_smem<qg_conv_group_mfma_kernel<R, S, NCB, true>>(smem); e != hipSuccess) return e;
     hipLaunchKernelGGL((qg_conv_group_mfma_kernel<R, S, NCB, true>), grid, dim3(256), smem, s, a);
   } else {
-    hipFuncSetAttribute((const void*)qg_conv_group_mfma_kernel<R, S, NCB, false>,
-                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (hipError_t e = qg_allow_smem<qg_conv_group_mfma_kernel<R, S, NCB, false>>(smem); e != hipSuccess) return e;
     hipLaunchKernelGGL((qg_conv_group_mfma_kernel<R, S, NCB, false>), grid, dim3(256), smem, s, a);
   }
   return hipGetLastError();
@@ -379,12 +377,10 @@ hipError_t launch_same(const qg_conv_args& a, int smem, int halo, int nchunks_pa
   const int npix = a.Nb * a.H * a.W;
   const dim3 grid((unsigned)(((npix + 127) / 128) * (a.C / (NCB * 32))));
   if (a.has_bzp) {
-    hipFuncSetAttribute((const void*)qg_conv_same_mfma_kernel<R, S, NCB, true>,
-                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (hipError_t e = qg_allow_smem<qg_conv_same_mfma_kernel<R, S, NCB, true>>(smem); e != hipSuccess) return e;
     hipLaunchKernelGGL((qg_conv_same_mfma_kernel<R, S, NCB, true>), grid, dim3(256), smem, s, a, halo, nchunks_pad);
   } else {
-    hipFuncSetAttribute((const void*)qg_conv_same_mfma_kernel<R, S, NCB, false>,
-                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (hipError_t e = qg_allow_smem<qg_conv_same_mfma_kernel<R, S, NCB, false>>(smem); e != hipSuccess) return e;
     hipLaunchKernelGGL((qg_conv_same_mfma_kernel<R, S, NCB, false>), grid, dim3(256), smem, s, a, halo, nchunks_pad);
   }
   return hipGetLastError();

@@ -329,8 +329,7 @@ hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   const int part = NWAVES * MB * 64 * (int)sizeof(v4i), stage = NWAVES * (MB * 16) * (BATCH * QG_FRAG_K);
   const int smem = (stage > part ? stage : part) + NWAVES * MB * 16 * (int)sizeof(int) +
                    (B4 ? MB * 256 * (int)sizeof(int) : 0);
-  hipError_t e = hipFuncSetAttribute((const void*)qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH, B4>,
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+  hipError_t e = qg_allow_smem<qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH, B4>>(smem);
   if (e != hipSuccess) return e;
   const int nfrag = ((a.N + 31) / 32) * 2;
   const int mblocks = (a.M + MB * 16 - 1) / (MB * 16);

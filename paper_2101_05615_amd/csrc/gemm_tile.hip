@@ -502,8 +502,8 @@ hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   constexpr int SMEM = STAGES * (BM + BN) * BK > 12 * BN ? STAGES * (BM + BN) * BK : 12 * BN;
   const int tiles_m = (a.M + BM - 1) / BM;
   const int tiles_n = (a.N + BN - 1) / BN;
-  auto fn = qg_gemm_tile_kernel<MODE, PATH, ROWSUM, NWM, NWN, TM, TN>;
-  hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+  constexpr auto fn = qg_gemm_tile_kernel<MODE, PATH, ROWSUM, NWM, NWN, TM, TN>;
+  hipError_t e = qg_allow_smem<fn>(SMEM);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(fn, dim3((unsigned)(tiles_m * tiles_n)), dim3(NWM * NWN * 64), SMEM, s, a, tiles_m,
                      tiles_n);
@@ -530,13 +530,13 @@ hipError_t launch_conv(const qg_gemm_args& a, hipStream_t s) {
   const dim3 grid((unsigned)(tiles_m * tiles_n)), block(NWM * NWN * 64);
   hipError_t e;
   if (a.has_bzp) {
-    auto fn = qg_gemm_tile_kernel<QG_MODE_REQUANT, PATH_PIPE, true, NWM, NWN, TM, TN, true>;
-    e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+    constexpr auto fn = qg_gemm_tile_kernel<QG_MODE_REQUANT, PATH_PIPE, true, NWM, NWN, TM, TN, true>;
+    e = qg_allow_smem<fn>(SMEM);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(fn, grid, block, SMEM, s, a, tiles_m, tiles_n);
   } else {
-    auto fn = qg_gemm_tile_kernel<QG_MODE_REQUANT, PATH_PIPE, false, NWM, NWN, TM, TN, true>;
-    e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+    constexpr auto fn = qg_gemm_tile_kernel<QG_MODE_REQUANT, PATH_PIPE, false, NWM, NWN, TM, TN, true>;
+    e = qg_allow_smem<fn>(SMEM);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(fn, grid, block, SMEM, s, a, tiles_m, tiles_n);
   }

@@ -169,6 +169,23 @@ __device__ __forceinline__ float qg_dequant_one(int x, float sc, float lo) {
 }
 #endif
 
+#ifdef __HIPCC__
+// Raises kernel Fn's dynamic-LDS limit to `bytes` on the current device unless that was already done: the
+// runtime call costs about as much host time as the launch itself, which matters for microsecond kernels.
+// (Concurrent callers may both make the call; it is idempotent.)
+template <auto Fn>
+inline hipError_t qg_allow_smem(int bytes) {
+  static int allowed[64] = {0};  // per kernel, indexed by device
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev >= 0 && dev < 64 && allowed[dev] >= bytes) return hipSuccess;
+  e = hipFuncSetAttribute((const void*)Fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && dev >= 0 && dev < 64) allowed[dev] = bytes;
+  return e;
+}
+#endif
+
 // launchers (each returns a hipError_t from hipGetLastError after the launch)
 hipError_t qg_launch_pack_b(const int8_t* B, int K, int N, int ldb, int K_pad, int N_pad,
                             int8_t* packed, int32_t* col_off, const int32_t* bzp_dev, hipStream_t s);
