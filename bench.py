@@ -27,6 +27,11 @@ PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, published
 SPIN_MS = 60.0  # untimed load before each side measurement, see time_calls
 
 
+def unsaturated_frac(torch, out):
+    """Fraction of uint8 outputs strictly inside (0, 255): how much of the result exercises the rounding."""
+    return round(float(((out > 0) & (out < 255)).float().mean().item()), 4)
+
+
 def gemm_bytes(M, N, K, bias):
     # algorithmic bytes of one call: A and B read once, C written once, column offsets (+ bias)
     return M * K + K * N + M * N + 4 * N + (4 * N if bias else 0)
@@ -174,6 +179,7 @@ def main():
                 "avg_launch_ms": round(dev_ms, 5), "traffic": traffic_from_profiles("qg_gemm_tile_kernel_c3")}
     # spot check of the timed output against the sampled property used in the tests: ReLU floor
     assert int(C.min().item()) >= c3.c_zp
+    c3_unsat = unsaturated_frac(torch, C)
 
     # ------------------------------------------------------------------ cpu baseline (oracle, bounded sample)
     cpu = None
@@ -223,7 +229,7 @@ def main():
                      "cold_GBps": round(nbytes / (cold_ms * 1e-3) / 1e9, 1),
                      "warm_GBps": round(nbytes / (warm_ms * 1e-3) / 1e9, 1),
                      "frac_hbm_peak_cold": round(nbytes / (cold_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
-                     "pack_b_ms": round(pack2_ms, 3)})
+                     "pack_b_ms": round(pack2_ms, 3), "outputs_inside_0_255": unsaturated_frac(torch, C2)})
         del sets, cold, warm, A2, Bp2, C2, B2
 
     # ------------------------------------------------------------------ config 1 and 4
@@ -239,7 +245,8 @@ def main():
         side.append({"workload": c.name, "us": round(ms * 1e3, 2), "TOPS": round(o / (ms * 1e-3) / 1e12, 2),
                      "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
                      "frac_int8_peak": round(o / (ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 4),
-                     "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "pack_b_ms": round(packx_ms, 3)})
+                     "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "pack_b_ms": round(packx_ms, 3),
+                     "outputs_inside_0_255": unsaturated_frac(torch, Cx)})
         del Ax, Bpx, Cx
 
     # ------------------------------------------------------------------ config 5: group conv
@@ -260,7 +267,8 @@ def main():
                      "warm_us": round(warm_ms * 1e3, 2), "cold_GBps": round(nb / (cold_ms * 1e-3) / 1e9, 1),
                      "warm_GBps": round(nb / (warm_ms * 1e-3) / 1e9, 1),
                      "frac_hbm_peak_cold": round(nb / (cold_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
-                     "TOPS_cold": round(o / (cold_ms * 1e-3) / 1e12, 2)})
+                     "TOPS_cold": round(o / (cold_ms * 1e-3) / 1e12, 2),
+                     "outputs_inside_0_255": unsaturated_frac(torch, outs[0])})
 
     # ------------------------------------------------------------------ rows beyond the five configs
     nxt = None
@@ -344,7 +352,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": "config3: square GEMM M=N=K=8192, uint8 x int8 -> uint8, per-channel B_zp and "
                                "scales, int32 bias, ReLU (seed 2)", "M": c3.M, "N": c3.N, "K": c3.K,
-                   "step": "qg_gemm_u8s8_requant (pack_b offline, reported separately)"},
+                   "step": "qg_gemm_u8s8_requant (pack_b offline, reported separately)",
+                   "outputs_inside_0_255": c3_unsat},
         "pack_b_ms": round(pack_ms, 3),
         "roofline": roofline,
         "cpu_baseline": cpu,
