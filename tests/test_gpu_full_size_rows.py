@@ -1,0 +1,84 @@
+"""Full-size parity of the widening rows in the launch configurations bench.py times: fp32 output and fp32
+activations at 8192^3 (sampled complete rows, one in every 256-row tile), the outlier split at 16 x 8192 x 8192,
+the dense convolution layers at batch 32 (sampled images)."""
+import numpy as np
+import pytest
+
+from paper_2101_05615_amd import workloads as wl
+from gpu_util import assert_same, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2101_05615_amd import qgemm as q
+    import oracle
+    oracle.build()
+    return q, torch, torch.device("cuda:0"), oracle
+
+
+def _rows(M, tile, seed, extra):
+    rng = np.random.default_rng(seed)
+    rows = [t * tile + int(rng.integers(0, min(tile, M - t * tile))) for t in range((M + tile - 1) // tile)]
+    rows += [0, M - 1] + [int(v) for v in rng.integers(0, M, extra)]
+    return np.array(sorted(set(rows)))
+
+
+def test_fp32_ends_at_the_headline_size(env):
+    q, torch, dev, oracle = env
+    c = wl.unsaturated(wl.config3_square())
+    say("fp32 ends, 8192^3")
+    rows = _rows(c.M, 256, 7, 8)
+    A, B = torch.from_numpy(c.A).to(dev), torch.from_numpy(c.B).to(dev)
+    bias, scales = torch.from_numpy(c.bias).to(dev), torch.from_numpy(c.scales).to(dev)
+    Bp = q.pack_b(B, c.b_zp)
+    # uint8 in, fp32 out
+    out = q.gemm_u8s8_dequant_f32(A, c.a_zp, Bp, bias, scales, True)
+    torch.cuda.synchronize()
+    want = oracle.gemm_u8s8_dequant_f32(np.ascontiguousarray(c.A[rows]), c.a_zp, c.B, c.b_zp, c.bias, c.scales, True)
+    assert_same(out[torch.from_numpy(rows).to(dev)].cpu().numpy().view(np.uint32), want.view(np.uint32), "fp32 out rows")
+    del out
+    # fp32 in (quantized by the library), uint8 out
+    alpha, zp = 0.03, c.a_zp
+    Af, inv = wl.random_fp32_activations(11, c.M, c.K, alpha=alpha, zp=zp, special=False)
+    got = q.gemm_f32s8_requant(torch.from_numpy(Af).to(dev), inv, zp, Bp, bias, scales, c.c_zp, c.relu)
+    torch.cuda.synchronize()
+    Aq = oracle.quantize_f32(Af[rows], inv, zp)
+    want8 = oracle.gemm_u8s8_requant(Aq, zp, c.B, c.b_zp, c.bias, c.scales, c.c_zp, c.relu)
+    assert_same(got[torch.from_numpy(rows).to(dev)].cpu().numpy(), want8, "fp32 in rows")
+    assert np.mean((want8 > 0) & (want8 < 255)) > 0.3
+
+
+def test_outlier_split_at_the_benchmark_size(env):
+    q, torch, dev, oracle = env
+    say("outlier split, 16 x 8192 x 8192")
+    M, N, K = 16, 8192, 8192
+    c = wl.random_gemm(41, M, N, K, per_channel=False, with_bias=False)
+    c.B = wl.outlier_weights(31, K, N, outlier_frac=0.01)
+    c = wl.unsaturated(c)
+    A, B = torch.from_numpy(c.A).to(dev), torch.from_numpy(c.B).to(dev)
+    Bp = q.pack_b_outlier(B, c.b_zp)
+    got = q.gemm_u8s8_requant(A, c.a_zp, Bp, None, torch.from_numpy(c.scales).to(dev), c.c_zp, c.relu)
+    torch.cuda.synchronize()
+    want = oracle.gemm_u8s8_requant(c.A, c.a_zp, c.B, c.b_zp, None, c.scales, c.c_zp, c.relu)
+    assert_same(got.cpu().numpy(), want, "split 16 x 8192 x 8192")
+    _, _, nnz = oracle.split_outliers(c.B, -8, 7)
+    assert Bp.nnz == nnz
+
+
+@pytest.mark.parametrize("H,C", [(56, 64), (28, 128), (14, 256)])
+def test_dense_conv_layers_at_batch_32(env, H, C):
+    q, torch, dev, oracle = env
+    say(f"dense conv 32x{H}x{H}x{C}")
+    c = wl.random_conv(40 + C, Nb=32, H=H, W=H, C=C, G=1, Cout=C)
+    Wp = q.pack_conv_dense_w(torch.from_numpy(np.ascontiguousarray(c.wgt[0])).to(dev), c.b_zp)
+    got = q.conv_dense_u8s8_requant(torch.from_numpy(c.inp).to(dev), Wp, c.a_zp, torch.from_numpy(c.bias).to(dev),
+                                    torch.from_numpy(c.scales).to(dev), c.c_zp, c.relu).cpu().numpy()
+    # images are independent: the oracle recomputes the first, the last and one in the middle
+    for n in (0, 17, 31):
+        want = oracle.conv_groupwise_direct(c.inp[n:n + 1], 1, c.wgt, c.a_zp, c.b_zp, c.bias, c.scales, c.c_zp, c.relu,
+                                            c.pad, c.stride)
+        assert_same(got[n:n + 1], want, f"image {n}")
