@@ -90,6 +90,15 @@ int qg_pack_b_sizes(int K, int N, size_t* packed_bytes, size_t* col_offsets_byte
 int qg_pack_b(const int8_t* B_dev, int K, int N, int ldb, const int32_t* b_zp_host, int n_b_zp,
               void* packed_dev, int32_t* col_offsets_dev, void* stream, qg_packed_b** out);
 
+/* As qg_pack_b from the TRANSPOSED weight matrix, the layout deep-learning
+ * frameworks store (the paper's row-wise quantization speaks of the rows of
+ * that matrix = output channels = columns of B):
+ *   Bt_dev  dev, int8, row-major N x K, leading dimension ldbt >= K; Bt[n][k] = B[k][n]
+ * The descriptor is indistinguishable from qg_pack_b's. */
+int qg_pack_b_transposed(const int8_t* Bt_dev, int K, int N, int ldbt, const int32_t* b_zp_host,
+                         int n_b_zp, void* packed_dev, int32_t* col_offsets_dev, void* stream,
+                         qg_packed_b** out);
+
 /* Frees the host descriptor only.  NULL is allowed. */
 void qg_packed_b_destroy(qg_packed_b* p);
 

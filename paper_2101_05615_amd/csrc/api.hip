@@ -218,10 +218,23 @@ int qg_pack_b_sizes(int K, int N, size_t* packed_bytes, size_t* col_offsets_byte
   return QG_OK;
 }
 
+static int pack_b_any(const int8_t* B_dev, int K, int N, int ldb, int transposed, const int32_t* b_zp_host,
+                      int n_b_zp, void* packed_dev, int32_t* col_offsets_dev, void* stream, qg_packed_b** out);
+
 int qg_pack_b(const int8_t* B_dev, int K, int N, int ldb, const int32_t* b_zp_host, int n_b_zp,
               void* packed_dev, int32_t* col_offsets_dev, void* stream, qg_packed_b** out) {
+  return pack_b_any(B_dev, K, N, ldb, 0, b_zp_host, n_b_zp, packed_dev, col_offsets_dev, stream, out);
+}
+
+int qg_pack_b_transposed(const int8_t* Bt_dev, int K, int N, int ldbt, const int32_t* b_zp_host, int n_b_zp,
+                         void* packed_dev, int32_t* col_offsets_dev, void* stream, qg_packed_b** out) {
+  return pack_b_any(Bt_dev, K, N, ldbt, 1, b_zp_host, n_b_zp, packed_dev, col_offsets_dev, stream, out);
+}
+
+static int pack_b_any(const int8_t* B_dev, int K, int N, int ldb, int transposed, const int32_t* b_zp_host,
+                      int n_b_zp, void* packed_dev, int32_t* col_offsets_dev, void* stream, qg_packed_b** out) {
   if (!B_dev || !b_zp_host || !packed_dev || !col_offsets_dev || !out) return QG_ENULL;
-  if (K <= 0 || N <= 0 || K > QG_MAX_K || ldb < N) return QG_EINVAL;
+  if (K <= 0 || N <= 0 || K > QG_MAX_K || ldb < (transposed ? K : N)) return QG_EINVAL;
   if (n_b_zp != 1 && n_b_zp != N) return QG_EINVAL;
   if (!aligned(packed_dev, 256) || !aligned(col_offsets_dev, 256)) return QG_EALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -250,7 +263,7 @@ int qg_pack_b(const int8_t* B_dev, int K, int N, int ldb, const int32_t* b_zp_ho
     delete h;
     return rc;
   }
-  if (qg_launch_pack_b(B_dev, K, N, ldb, K_pad, N_pad, static_cast<int8_t*>(packed_dev), col_offsets_dev,
+  if (qg_launch_pack_b(B_dev, K, N, ldb, transposed, K_pad, N_pad, static_cast<int8_t*>(packed_dev), col_offsets_dev,
                        col_offsets_dev + N_pad, s) != hipSuccess) {
     delete h;
     return QG_ELAUNCH;

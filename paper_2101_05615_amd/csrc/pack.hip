@@ -14,6 +14,9 @@ __global__ void qg_fill_i32(int32_t* p, int n, int32_t v) {
 // One thread produces one 16-byte chunk of the packed buffer: 16 consecutive k of
 // one column.  Threads are ordered with the column fastest so that the 16 row
 // reads are coalesced across the wave.
+// TRANSPOSED: the source is B^T (N x K row-major, leading dimension ldb >= K, the layout deep-learning
+// frameworks keep weights in): the 16 k values of a chunk are then 16 consecutive bytes.
+template <bool TRANSPOSED>
 __global__ __launch_bounds__(256) void qg_pack_b_kernel(const int8_t* __restrict__ B, int K, int N,
                                                         int ldb, int K_pad, int N_pad,
                                                         int8_t* __restrict__ packed,
@@ -33,7 +36,7 @@ __global__ __launch_bounds__(256) void qg_pack_b_kernel(const int8_t* __restrict
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
     int8_t x = 0;
-    if (n < N && k0 + i < K) x = B[(size_t)(k0 + i) * ldb + n];
+    if (n < N && k0 + i < K) x = TRANSPOSED ? B[(size_t)n * ldb + k0 + i] : B[(size_t)(k0 + i) * ldb + n];
     u.b[i] = x;
     sum += x;
   }
@@ -216,13 +219,16 @@ __global__ void qg_pack_conv_w_mfma_kernel(const int8_t* __restrict__ W, int RS,
 
 }  // namespace
 
-hipError_t qg_launch_pack_b(const int8_t* B, int K, int N, int ldb, int K_pad, int N_pad,
+hipError_t qg_launch_pack_b(const int8_t* B, int K, int N, int ldb, int transposed, int K_pad, int N_pad,
                             int8_t* packed, int32_t* col_off, const int32_t* bzp_dev,
                             hipStream_t s) {
   hipLaunchKernelGGL(qg_fill_i32, dim3((N_pad + 255) / 256), dim3(256), 0, s, col_off, N_pad, 0);
   const long long total = (long long)N_pad * (K_pad / 16);
-  hipLaunchKernelGGL(qg_pack_b_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, B, K,
-                     N, ldb, K_pad, N_pad, packed, col_off);
+  const dim3 grid((unsigned)((total + 255) / 256));
+  if (transposed)
+    hipLaunchKernelGGL(qg_pack_b_kernel<true>, grid, dim3(256), 0, s, B, K, N, ldb, K_pad, N_pad, packed, col_off);
+  else
+    hipLaunchKernelGGL(qg_pack_b_kernel<false>, grid, dim3(256), 0, s, B, K, N, ldb, K_pad, N_pad, packed, col_off);
   hipLaunchKernelGGL(qg_fold_offsets, dim3((N_pad + 255) / 256), dim3(256), 0, s, col_off, bzp_dev,
                      N_pad, K);
   return hipGetLastError();

@@ -187,7 +187,7 @@ inline hipError_t qg_allow_smem(int bytes) {
 #endif
 
 // launchers (each returns a hipError_t from hipGetLastError after the launch)
-hipError_t qg_launch_pack_b(const int8_t* B, int K, int N, int ldb, int K_pad, int N_pad,
+hipError_t qg_launch_pack_b(const int8_t* B, int K, int N, int ldb, int transposed, int K_pad, int N_pad,
                             int8_t* packed, int32_t* col_off, const int32_t* bzp_dev, hipStream_t s);
 hipError_t qg_launch_count_outliers(const int8_t* B, int K, int N, int ldb, unsigned long long* count_dev, hipStream_t s);
 hipError_t qg_launch_pack_b_split_count(const int8_t* B, int K, int N, int ldb, int K_pad, int N_pad, uint8_t* packed4,

@@ -23,7 +23,7 @@ EXPORTS = [
     "qg_gemm_u8s8_acc32_kernel", "qg_gemm_u8s8_dequant_f32", "qg_quantize_a_f32", "qg_gemm_f32_workspace_bytes",
     "qg_gemm_f32s8_requant", "qg_gemm_f32s8_dequant_f32",
     "qg_count_outliers", "qg_pack_b_outlier_sizes", "qg_pack_b_outlier", "qg_packed_b_nnz",
-    "qg_conv_dense_u8s8_requant",
+    "qg_conv_dense_u8s8_requant", "qg_pack_b_transposed",
 ]
 
 KERNEL_AUTO, KERNEL_LAST = 0, 7
@@ -52,6 +52,7 @@ def _load():
     vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     lib.qg_pack_b_sizes.argtypes = [i, i, ctypes.POINTER(sz), ctypes.POINTER(sz)]
     lib.qg_pack_b.argtypes = [vp, i, i, i, vp, i, vp, vp, vp, ctypes.POINTER(vp)]
+    lib.qg_pack_b_transposed.argtypes = lib.qg_pack_b.argtypes
     lib.qg_packed_b_destroy.argtypes = [vp]
     lib.qg_packed_b_destroy.restype = None
     lib.qg_packed_b_k.argtypes = [vp]
@@ -193,6 +194,20 @@ def pack_b_outlier(B, b_zp, max_nnz=None):
     pk.sparse = sparse
     pk.nnz = lib.qg_packed_b_nnz(h)
     return pk
+
+
+def pack_b_transposed(Bt, b_zp):
+    """Bt: int8 cuda tensor [N, K] (the transposed weight matrix, unit stride along K); b_zp: 1 or N ints (host)."""
+    assert Bt.is_cuda and Bt.dtype == torch.int8 and Bt.dim() == 2 and Bt.stride(1) == 1
+    N, K = Bt.shape
+    pb, cb = pack_b_sizes(K, N)
+    packed = torch.empty(pb, dtype=torch.int8, device=Bt.device)
+    aux = torch.empty(cb // 4, dtype=torch.int32, device=Bt.device)
+    z, zp = _host_i32(b_zp)
+    h = ctypes.c_void_p()
+    _check(lib.qg_pack_b_transposed(Bt.data_ptr(), K, N, Bt.stride(0), zp, z.size, packed.data_ptr(), aux.data_ptr(),
+                                    _stream(), ctypes.byref(h)), "qg_pack_b_transposed")
+    return PackedB(h, packed, aux, N)
 
 
 def _params(a_zp, bias, scales, c_zp, relu):

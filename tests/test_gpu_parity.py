@@ -47,6 +47,25 @@ def test_pack_b_accepts_strided_b(env):
     assert_same(acc.cpu().numpy(), oracle.acc32(c.A, c.B), "acc32 strided B")
 
 
+@pytest.mark.parametrize("K,N", [(128, 64), (100, 100), (4097, 257), (1, 1), (512, 300)])
+def test_pack_from_the_transposed_weight_matrix(env, K, N):
+    """Packing B^T (N x K, the layout frameworks keep weights in) gives the same bytes as packing B."""
+    q, torch, dev, oracle = env
+    c = wl.random_gemm(K + N, 40, N, K, wide_zp=True)
+    B = torch.from_numpy(c.B).to(dev)
+    store = torch.zeros((N, K + 5), dtype=torch.int8, device=dev)   # padded rows: ldbt > K
+    store[:, :K] = B.t()
+    p1, p2 = q.pack_b(B, c.b_zp), q.pack_b_transposed(store[:, :K], c.b_zp)
+    torch.cuda.synchronize()
+    assert torch.equal(p1.packed, p2.packed), "packed bytes differ"
+    assert torch.equal(p1.aux, p2.aux), "col_offsets / theta_B differ"
+    assert_same(p2.col_offsets.cpu().numpy(), oracle.col_offsets(c.B, c.b_zp), "col_offsets")
+    A, _, bias, scales, C, _ = dev_case(c, torch, dev)
+    q.gemm_u8s8_requant(A, c.a_zp, p2, bias, scales, c.c_zp, c.relu, out=C)
+    torch.cuda.synchronize()
+    assert_same(C.cpu().numpy(), oracle_gemm(c, oracle), "GEMM on the transposed-packed weights")
+
+
 ACC_SHAPES = [  # (M, N, K): both kernels (M <= 64 skinny, above: large tile), ragged in every dimension
     (1, 1, 1), (1, 16, 64), (16, 16, 64), (16, 32, 128), (16, 100, 300), (17, 40, 36), (33, 257, 4097),
     (64, 64, 128), (5, 4, 36), (48, 512, 1024),
