@@ -142,7 +142,7 @@ int qg_gemm_u8s8_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* 
  *   SKINNY16/32/64  one workgroup per 16 columns of B and per block of 16/32/64
  *                   rows, K split over the waves of the workgroup; B streams from
  *                   HBM straight into operand registers (bandwidth-bound shapes)
- *   TILE64          64 x 64 workgroup tile, three LDS stages
+ *   TILE64          64 x 64 workgroup tile, three LDS stages, K split over two wave sets
  *   TILE128         128 x 128
  *   TILE128X256     128 x 256
  *   TILE256         256 x 256, four LDS stages, hand-scheduled loop (large shapes)

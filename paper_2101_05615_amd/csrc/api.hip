@@ -73,7 +73,7 @@ struct stream_cost {
   double fix, lat_k, wg, wg_k;
 };
 const tile_cost k_tile_cost[] = {
-    {QG_KERNEL_TILE64, 64, 64, 2.75, 0.24, 0.122, 0.19},
+    {QG_KERNEL_TILE64, 64, 64, 3.27, 0.141, 0.103, 0.64},
     {QG_KERNEL_TILE128, 128, 128, 3.9, 0.357, 0.295, 0.94},
     {QG_KERNEL_TILE128X256, 128, 256, 5.5, 0.527, 0.514, 2.07},
     {QG_KERNEL_TILE256, 256, 256, 8.7, 0.524, 0.838, 6.87},

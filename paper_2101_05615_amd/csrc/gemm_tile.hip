@@ -26,7 +26,8 @@
 // problem mapped to one of them): 256 x 256 with a hand-scheduled four-stage loop for the
 // large compute-bound shapes, and 128 x 256, 128 x 128 and 64 x 64 with a compiler-scheduled
 // three-stage loop, several workgroups per CU, for shapes that would leave most CUs idle
-// (or run a single, unoverlapped round) at 256 x 256.
+// (or run a single, unoverlapped round) at 256 x 256.  The 64 x 64 workgroup has two sets of four waves
+// that take alternate k tiles and add their accumulators at the end.
 #include "qg_internal.h"
 #include "tile_loop_asm.inc"
 
@@ -121,10 +122,16 @@ constexpr int min_wg_per_cu(int path, int blocks) {
 // (Cin % 64 == 0), so staging a tile is the same request as in the GEMM with the row base moved by the
 // tap's pixel offset.  A tap outside the image must read as theta_A (zero in the real domain): the request
 // address is clamped into the buffer and the fragment is replaced by theta_A bytes when it is fetched.
-template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, bool CONV = false>
-__global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void qg_gemm_tile_kernel(const qg_gemm_args p, int tiles_m,
-                                                                      int tiles_n) {
-  constexpr int NW = NWM * NWN, NT = NW * 64;
+// KS (PATH_PIPE only): wave groups that split K inside the workgroup.  With KS = 2 the workgroup has two sets of
+// NWM x NWN waves; set g consumes the k tiles g, g + 2, ... from its own LDS stages (a lone workgroup's k
+// step is a barrier / LDS read / MFMA chain, so two chains side by side halve the time of a thin grid), and the
+// two partial accumulators are added through LDS before the output pipeline, which set 0 runs.
+template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, bool CONV = false, int KS = 1>
+__global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) / KS) void qg_gemm_tile_kernel(const qg_gemm_args p,
+                                                                                                int tiles_m,
+                                                                                                int tiles_n) {
+  static_assert(KS == 1 || (KS == 2 && PATH == PATH_PIPE && !CONV), "K split: two wave sets on the pipelined path");
+  constexpr int NW = NWM * NWN, NT = NW * KS * 64;  // NW: waves of one set; NT: threads of the workgroup
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
   constexpr int A_STAGE = BM * BK, B_STAGE = BN * BK, STAGE = A_STAGE + B_STAGE;
   constexpr int A_DMA = A_STAGE / 1024 / NW;  // 1 KiB wave-loads per wave per tile
@@ -137,7 +144,9 @@ __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void 
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in an SGPR
+  const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in an SGPR
+  const int kg = wave_all / NW;      // wave set (0 unless KS == 2)
+  const int wave = wave_all % NW;    // position inside the set
   const int wave_m = wave % NWM, wave_n = wave / NWM;
   const int l32 = lane & 31, lg = lane >> 5;
 
@@ -193,7 +202,7 @@ __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void 
   // slot i = l32 -> fragment (i >> 4) of the super-block, nl = i & 15; k-half lg is 256 B further
   const int b_rd = A_STAGE + ((wave_n * TN) * 2 + (l32 >> 4)) * QG_FRAG_BYTES + (l32 & 15) * 16 + lg * 256;
   auto fetch = [&](int stage, int ks, v4i (&af)[TM], v4i (&bf)[TN]) {
-    const unsigned char* base = smem + stage * STAGE;
+    const unsigned char* base = smem + (stage * KS + kg) * STAGE;
 #pragma unroll
     for (int mb = 0; mb < TM; ++mb)
       af[mb] = *reinterpret_cast<const v4i*>(base + a_rd[ks] + mb * (32 * BK));
@@ -305,7 +314,7 @@ __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void 
     auto request = [&](int kt, int stage) {
       const uint8_t* ab = p.A + (size_t)kt * BK;
       const int8_t* bb = b_tile0 + (size_t)kt * b_step;
-      unsigned char* st = smem + stage * STAGE;
+      unsigned char* st = smem + (stage * KS + kg) * STAGE;
       if (CONV) {
         const int tap_pix = rq_kh * p.cv_W + rq_kw;
 #pragma unroll
@@ -324,16 +333,18 @@ __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void 
 #pragma unroll
       for (int q = 0; q < B_DMA; ++q) dma16(bb + b_voff[q], st + A_STAGE + (wave * B_DMA + q) * 1024);
     };
+    // this wave set's tiles are kg, kg + KS, ...: KTg of them, in KT2 common steps (sets share the barriers)
+    const int KTg = (KT - kg + KS - 1) / KS, KT2 = (KT + KS - 1) / KS;
 #pragma unroll
     for (int t = 0; t < NS - 1; ++t)
-      if (t < KT) request(t, t);
+      if (t < KTg) request(t * KS + kg, t);
     int stage = 0;
-    for (int kt = 0; kt < KT; ++kt) {
-      wait_tiles<NS - 2, N_DMA>(KT - 1 - kt);  // tile kt has landed; up to NS-2 younger ones may be in flight
+    for (int i = 0; i < KT2; ++i) {
+      wait_tiles<NS - 2, N_DMA>(KTg - 1 - i);  // this set's tile i has landed; up to NS-2 younger ones may be in flight
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
-      if (kt + NS - 1 < KT) request(kt + NS - 1, stage == 0 ? NS - 1 : stage - 1);
+      if (i + NS - 1 < KTg) request((i + NS - 1) * KS + kg, stage == 0 ? NS - 1 : stage - 1);
       if (CONV) {
 #pragma unroll
         for (int mb = 0; mb < TM; ++mb)
@@ -343,12 +354,14 @@ __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void 
           if (++cs_kw == p.cv_S) cs_kw = 0, ++cs_kh;
         }
       }
-      fetch(stage, 0, a0, b0);
-      fetch(stage, 1, a1, b1);
-      prep(a0);
-      mma(a0, b0);
-      prep(a1);
-      mma(a1, b1);
+      if (KS == 1 || i < KTg) {
+        fetch(stage, 0, a0, b0);
+        fetch(stage, 1, a1, b1);
+        prep(a0);
+        mma(a0, b0);
+        prep(a1);
+        mma(a1, b1);
+      }
       stage = stage == NS - 1 ? 0 : stage + 1;
     }
   } else {
@@ -380,6 +393,35 @@ __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void 
     }
   }
 
+  // ---- K split: the second wave set hands its accumulators and byte sums to the first through LDS
+  if constexpr (KS == 2) {
+    constexpr int PER_LANE = TM * TN * 16 + TM;
+    static_assert(4096 + PER_LANE * NW * 64 * 4 <= NS * KS * STAGE, "partials must fit the stage memory");
+    __syncthreads();  // every wave is done with the stages
+    int* red = reinterpret_cast<int*>(smem) + 1024;  // past the per-column constants staged below
+    if (kg == 1) {
+#pragma unroll
+      for (int mb = 0; mb < TM; ++mb) {
+#pragma unroll
+        for (int nb = 0; nb < TN; ++nb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) red[((mb * TN + nb) * 16 + r) * (NW * 64) + wave * 64 + lane] = acc[mb][nb][r];
+        red[(TM * TN * 16 + mb) * (NW * 64) + wave * 64 + lane] = (int)rs[mb];
+      }
+    }
+    __syncthreads();
+    if (kg == 0) {
+#pragma unroll
+      for (int mb = 0; mb < TM; ++mb) {
+#pragma unroll
+        for (int nb = 0; nb < TN; ++nb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[mb][nb][r] += red[((mb * TN + nb) * 16 + r) * (NW * 64) + wave * 64 + lane];
+        rs[mb] += (unsigned)red[(TM * TN * 16 + mb) * (NW * 64) + wave * 64 + lane];
+      }
+    }
+  }
+
   // ---- row offsets: lane (m, k-half) holds half of row m's byte sum; every one of the KT*64 bytes
   // summed (padding reads as 0x80) is 128 above its int8 value
   int rsum_s[TM];
@@ -405,6 +447,7 @@ __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void 
     bz_s[t] = -bz;  // negated: x = acc + cj + (-theta_B) * rowsum
   }
   __syncthreads();
+  if (KS == 2 && kg == 1) return;  // the first wave set holds the sums and runs the output pipeline
 
   // ---- epilogue straight from the accumulators.  Lane (l32, lg) of block (mb, nb) holds row
   // 32*mb + l32 and the 16 consecutive columns 32*nb + 16*lg .. +15; the per-column constants of a
@@ -494,32 +537,32 @@ __global__ __launch_bounds__(NWM * NWN * 64, min_wg_per_cu(PATH, TM * TN)) void 
   }
 }
 
-template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN>
+template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, int KS = 1>
 hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
-  constexpr int STAGES = PATH == PATH_ASM ? NSTAGE : (PATH == PATH_PIPE ? pipe_stages(TM * TN) : 1);
+  constexpr int STAGES = (PATH == PATH_ASM ? NSTAGE : (PATH == PATH_PIPE ? pipe_stages(TM * TN) : 1)) * KS;
   // the output pipeline's per-column constants (12 B per column) reuse the stage memory
   constexpr int SMEM = STAGES * (BM + BN) * BK > 12 * BN ? STAGES * (BM + BN) * BK : 12 * BN;
   const int tiles_m = (a.M + BM - 1) / BM;
   const int tiles_n = (a.N + BN - 1) / BN;
-  constexpr auto fn = qg_gemm_tile_kernel<MODE, PATH, ROWSUM, NWM, NWN, TM, TN>;
+  constexpr auto fn = qg_gemm_tile_kernel<MODE, PATH, ROWSUM, NWM, NWN, TM, TN, false, KS>;
   hipError_t e = qg_allow_smem<fn>(SMEM);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(fn, dim3((unsigned)(tiles_m * tiles_n)), dim3(NWM * NWN * 64), SMEM, s, a, tiles_m,
+  hipLaunchKernelGGL(fn, dim3((unsigned)(tiles_m * tiles_n)), dim3(NWM * NWN * KS * 64), SMEM, s, a, tiles_m,
                      tiles_n);
   return hipGetLastError();
 }
 
 // requant mode with / without the row-offset term; the int32 test hook always carries the row sums
-template <int PATH, int NWM, int NWN, int TM, int TN>
+template <int PATH, int NWM, int NWN, int TM, int TN, int KS = 1>
 hipError_t launch_cfg(const qg_gemm_args& a, int mode, hipStream_t s) {
   if (mode == QG_MODE_REQUANT)
-    return a.has_bzp ? launch<QG_MODE_REQUANT, PATH, true, NWM, NWN, TM, TN>(a, s)
-                     : launch<QG_MODE_REQUANT, PATH, false, NWM, NWN, TM, TN>(a, s);
+    return a.has_bzp ? launch<QG_MODE_REQUANT, PATH, true, NWM, NWN, TM, TN, KS>(a, s)
+                     : launch<QG_MODE_REQUANT, PATH, false, NWM, NWN, TM, TN, KS>(a, s);
   if (mode == QG_MODE_DEQUANT)
-    return a.has_bzp ? launch<QG_MODE_DEQUANT, PATH, true, NWM, NWN, TM, TN>(a, s)
-                     : launch<QG_MODE_DEQUANT, PATH, false, NWM, NWN, TM, TN>(a, s);
-  return launch<QG_MODE_ACC32, PATH, true, NWM, NWN, TM, TN>(a, s);
+    return a.has_bzp ? launch<QG_MODE_DEQUANT, PATH, true, NWM, NWN, TM, TN, KS>(a, s)
+                     : launch<QG_MODE_DEQUANT, PATH, false, NWM, NWN, TM, TN, KS>(a, s);
+  return launch<QG_MODE_ACC32, PATH, true, NWM, NWN, TM, TN, KS>(a, s);
 }
 
 template <int NWM, int NWN, int TM, int TN>
@@ -560,7 +603,7 @@ hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, int kernel, hipS
   const bool pipe_ok = a.a_vec && (a.K % BK == 0);
   if (!pipe_ok) return launch_cfg<PATH_GENERAL, 2, 2, 2, 2>(a, mode, s);
   switch (kernel) {
-    case QG_KERNEL_TILE64: return launch_cfg<PATH_PIPE, 2, 2, 1, 1>(a, mode, s);
+    case QG_KERNEL_TILE64: return launch_cfg<PATH_PIPE, 2, 2, 1, 1, 2>(a, mode, s);  // two wave sets split K
     case QG_KERNEL_TILE128: return launch_cfg<PATH_PIPE, 2, 2, 2, 2>(a, mode, s);
     case QG_KERNEL_TILE128X256: return launch_cfg<PATH_PIPE, 2, 2, 2, 4>(a, mode, s);
     case QG_KERNEL_TILE256:
