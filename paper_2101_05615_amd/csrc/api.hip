@@ -77,6 +77,7 @@ const tile_cost k_tile_cost[] = {
     {QG_KERNEL_TILE128, 128, 128, 3.9, 0.357, 0.295, 0.94},
     {QG_KERNEL_TILE128X256, 128, 256, 5.5, 0.527, 0.514, 2.07},
     {QG_KERNEL_TILE256, 256, 256, 8.7, 0.524, 0.838, 6.87},
+    {QG_KERNEL_TILE128K2, 128, 128, 4.4, 0.273, 0.34, 2.0},
 };
 const stream_cost k_stream_cost[] = {
     {QG_KERNEL_SKINNY16, 16, 3.58, 7.3e-5, 7.55, 0.74e-3},
@@ -170,7 +171,8 @@ extern "C" {
 
 const char* qg_kernel_name(int kernel) {
   static const char* const names[] = {"auto",   "skinny16", "skinny32",    "skinny64",
-                                      "tile64", "tile128",  "tile128x256", "tile256"};
+                                      "tile64", "tile128",  "tile128x256", "tile256",
+                                      "tile128k2"};
   return (kernel >= 0 && kernel <= QG_KERNEL_LAST) ? names[kernel] : nullptr;
 }
 
@@ -608,7 +610,7 @@ int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int
   double best_us = 1e300;
   const double kt = (double)(a.K / 64);
   for (const tile_cost& c : k_tile_cost) {
-    if (c.kernel == QG_KERNEL_TILE256) continue;
+    if (c.kernel == QG_KERNEL_TILE256 || c.kernel == QG_KERNEL_TILE128K2) continue;
     const double wgs = (double)ceil_div(a.M, c.bm) * (double)ceil_div(a.N, c.bn);
     const double us = fmax(c.fix + kt * c.lat, 2.5 + ceil(wgs / 256.0) * (kt * c.thr + c.epi));
     if (us < best_us) best_us = us, kernel = c.kernel;

@@ -606,6 +606,7 @@ hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, int kernel, hipS
     case QG_KERNEL_TILE64: return launch_cfg<PATH_PIPE, 2, 2, 1, 1, 2>(a, mode, s);  // two wave sets split K
     case QG_KERNEL_TILE128: return launch_cfg<PATH_PIPE, 2, 2, 2, 2>(a, mode, s);
     case QG_KERNEL_TILE128X256: return launch_cfg<PATH_PIPE, 2, 2, 2, 4>(a, mode, s);
+    case QG_KERNEL_TILE128K2: return launch_cfg<PATH_PIPE, 2, 2, 2, 2, 2>(a, mode, s);
     case QG_KERNEL_TILE256:
       if (a.K >= NSTAGE * BK) return launch_cfg<PATH_ASM, 2, 2, 4, 4>(a, mode, s);
       return launch_cfg<PATH_PIPE, 2, 2, 2, 4>(a, mode, s);

@@ -10,7 +10,7 @@ from gpu_util import assert_same, dev_case, say
 
 pytestmark = pytest.mark.gpu
 
-KERNELS = ["auto", "skinny16", "skinny32", "skinny64", "tile64", "tile128", "tile128x256", "tile256"]
+KERNELS = ["auto", "skinny16", "skinny32", "skinny64", "tile64", "tile128", "tile128x256", "tile256", "tile128k2"]
 
 
 @pytest.fixture(scope="module")
@@ -132,7 +132,7 @@ def test_fp32_ends_argument_errors(env):
     assert L.qg_gemm_f32s8_requant(Af.data_ptr(), 64, 128, 1.0, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, ws.data_ptr() + 1, None, 0) == q.EALIGN
     assert L.qg_gemm_f32s8_requant(Af.data_ptr(), 64, 127, 1.0, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, ws.data_ptr(), None, 0) == q.EINVAL
     assert L.qg_gemm_f32s8_requant(Af.data_ptr(), 64, 128, 0.0, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, ws.data_ptr(), None, 0) == q.EINVAL
-    assert L.qg_gemm_f32s8_requant(Af.data_ptr(), 64, 128, 1.0, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, ws.data_ptr(), None, 9) == q.EINVAL
+    assert L.qg_gemm_f32s8_requant(Af.data_ptr(), 64, 128, 1.0, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, ws.data_ptr(), None, q.KERNEL_LAST + 1) == q.EINVAL
     assert L.qg_gemm_f32s8_dequant_f32(Af.data_ptr(), 64, 128, 1.0, Bp.handle, ctypes.byref(d), Cf.data_ptr(), 63, ws.data_ptr(), None, 0) == q.EINVAL
     assert L.qg_gemm_f32s8_dequant_f32(Af.data_ptr(), 64, 128, 1.0, Bp.handle, ctypes.byref(d), None, 64, ws.data_ptr(), None, 0) == q.ENULL
     assert L.qg_gemm_u8s8_dequant_f32(A.data_ptr(), 64, 128, Bp.handle, ctypes.byref(d), Cf.data_ptr() + 2, 64, None, None, 0) == q.EALIGN

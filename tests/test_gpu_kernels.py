@@ -8,7 +8,7 @@ from gpu_util import assert_same, dev_case, oracle_gemm, say
 
 pytestmark = pytest.mark.gpu
 
-KERNELS = ["skinny16", "skinny32", "skinny64", "tile64", "tile128", "tile128x256", "tile256"]
+KERNELS = ["skinny16", "skinny32", "skinny64", "tile64", "tile128", "tile128x256", "tile256", "tile128k2"]
 
 # (M, N, K): 1, 2, 3, 4 and many 64-deep tiles on the pipelined paths (K % 64 == 0), ragged M and N that
 # span several tiles of every shape, and a ragged K that takes the general path
@@ -41,8 +41,8 @@ def cases(env):
 def test_kernel_names(env):
     q = env[0]
     names = q.kernel_names()
-    assert names[0] == "auto" and [names[i] for i in range(1, 8)] == KERNELS
-    assert q.lib.qg_kernel_name(8) is None and q.lib.qg_kernel_name(-1) is None
+    assert names[0] == "auto" and [names[i] for i in range(1, q.KERNEL_LAST + 1)] == KERNELS
+    assert q.lib.qg_kernel_name(q.KERNEL_LAST + 1) is None and q.lib.qg_kernel_name(-1) is None
 
 
 @pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
@@ -117,7 +117,7 @@ def test_unknown_kernel_id_is_rejected(env, cases):
     A, B, bias, scales, C, _ = dev_case(c, torch, dev)
     Bp = q.pack_b(B, c.b_zp)
     p = q.RequantParams(c.a_zp, None, scales.data_ptr(), scales.numel(), c.c_zp, 0)
-    for bad in (-1, 8, 100):
+    for bad in (-1, q.KERNEL_LAST + 1, 100):
         rc = q.lib.qg_gemm_u8s8_requant_kernel(A.data_ptr(), c.M, A.stride(0), Bp.handle, ctypes.byref(p),
                                                C.data_ptr(), C.stride(0), None, None, bad)
         assert rc == q.EINVAL
