@@ -128,8 +128,8 @@ def main():
                          "calibration kernel for FETCH_SIZE / WRITE_SIZE) and exit: for rocprofv3 --pmc runs")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the path shards over M or N with no collective; "
-              "see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (the path shards over M or N with no collective, "
+              "every GPU running this same kernel on its rows or columns); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -16,6 +16,7 @@
 //  * dot4 kernel (any C = 4 G): thread = (pixel, group), one tap of one group is one dword = one
 //    v_dot4_i32_i8 operand, the 36 x 4 weight block lives in 36 registers.
 #include "qg_internal.h"
+#include <type_traits>
 
 namespace {
 
@@ -119,6 +120,8 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 4) void qg_conv_group_mfma_kerne
 
     // ---- output pipeline: lane (pixel pl, half g) holds channels 32 cb + 16 g .. + 15 of its pixel
     if (px < npix) {
+      auto pipeline = [&](auto lo_tag) {
+      constexpr bool LO = decltype(lo_tag)::value;
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb) {
         const int c_l = cb * 32 + 16 * g;
@@ -134,14 +137,19 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 4) void qg_conv_group_mfma_kerne
           const int x1 = acc[cb][4 * q + 1] + cj.y + (HAS_BZP ? __mul24(nbz.y, rsum) : 0);
           const int x2 = acc[cb][4 * q + 2] + cj.z + (HAS_BZP ? __mul24(nbz.z, rsum) : 0);
           const int x3 = acc[cb][4 * q + 3] + cj.w + (HAS_BZP ? __mul24(nbz.w, rsum) : 0);
-          unsigned w = qg_requant_pack(x0, sc.x, p.clamp_lo, p.clamp_hi, czp_f, 0, 0);
-          w = qg_requant_pack(x1, sc.y, p.clamp_lo, p.clamp_hi, czp_f, 1, w);
-          w = qg_requant_pack(x2, sc.z, p.clamp_lo, p.clamp_hi, czp_f, 2, w);
-          out[q] = qg_requant_pack(x3, sc.w, p.clamp_lo, p.clamp_hi, czp_f, 3, w);
+          unsigned w = qg_requant_pack<LO>(x0, sc.x, p.clamp_lo, p.clamp_hi, czp_f, 0, 0);
+          w = qg_requant_pack<LO>(x1, sc.y, p.clamp_lo, p.clamp_hi, czp_f, 1, w);
+          w = qg_requant_pack<LO>(x2, sc.z, p.clamp_lo, p.clamp_hi, czp_f, 2, w);
+          out[q] = qg_requant_pack<LO>(x3, sc.w, p.clamp_lo, p.clamp_hi, czp_f, 3, w);
         }
         *reinterpret_cast<uint4*>(p.out + (size_t)px * p.Cout + ch0 + c_l) =
             make_uint4(out[0], out[1], out[2], out[3]);
       }
+      };
+      if (qg_requant_needs_lo(p.clamp_lo, czp_f))
+        pipeline(std::true_type{});
+      else
+        pipeline(std::false_type{});
     }
   }
 }
@@ -269,6 +277,8 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
 
   // ---- output pipeline: lane (pixel pl, half g) holds channels 32 cb + 16 g .. + 15 of its pixel
   if (px < npix) {
+    auto pipeline = [&](auto lo_tag) {
+    constexpr bool LO = decltype(lo_tag)::value;
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
       const int c_l = cb * 32 + 16 * g;
@@ -283,14 +293,19 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
         const int x1 = acc[cb][4 * q + 1] + cj.y + (HAS_BZP ? __mul24(nbz.y, rsum) : 0);
         const int x2 = acc[cb][4 * q + 2] + cj.z + (HAS_BZP ? __mul24(nbz.z, rsum) : 0);
         const int x3 = acc[cb][4 * q + 3] + cj.w + (HAS_BZP ? __mul24(nbz.w, rsum) : 0);
-        unsigned w = qg_requant_pack(x0, sc.x, p.clamp_lo, p.clamp_hi, czp_f, 0, 0);
-        w = qg_requant_pack(x1, sc.y, p.clamp_lo, p.clamp_hi, czp_f, 1, w);
-        w = qg_requant_pack(x2, sc.z, p.clamp_lo, p.clamp_hi, czp_f, 2, w);
-        out[q] = qg_requant_pack(x3, sc.w, p.clamp_lo, p.clamp_hi, czp_f, 3, w);
+        unsigned w = qg_requant_pack<LO>(x0, sc.x, p.clamp_lo, p.clamp_hi, czp_f, 0, 0);
+        w = qg_requant_pack<LO>(x1, sc.y, p.clamp_lo, p.clamp_hi, czp_f, 1, w);
+        w = qg_requant_pack<LO>(x2, sc.z, p.clamp_lo, p.clamp_hi, czp_f, 2, w);
+        out[q] = qg_requant_pack<LO>(x3, sc.w, p.clamp_lo, p.clamp_hi, czp_f, 3, w);
       }
       *reinterpret_cast<uint4*>(p.out + (size_t)px * p.Cout + ch0 + c_l) =
           make_uint4(out[0], out[1], out[2], out[3]);
     }
+    };
+    if (qg_requant_needs_lo(p.clamp_lo, czp_f))
+      pipeline(std::true_type{});
+    else
+      pipeline(std::false_type{});
   }
 }
 

@@ -29,6 +29,7 @@
 // (or run a single, unoverlapped round) at 256 x 256.  The 64 x 64 workgroup has two sets of four waves
 // that take alternate k tiles and add their accumulators at the end.
 #include "qg_internal.h"
+#include <type_traits>
 #include "tile_loop_asm.inc"
 
 namespace {
@@ -339,7 +340,9 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
     for (int t = 0; t < NS - 1; ++t)
       if (t < KTg) request(t * KS + kg, t);
     int stage = 0;
-    for (int i = 0; i < KT2; ++i) {
+    // one common step: `consume` says whether this wave set has a tile in it (always, except in the last step
+    // of the other set when the number of tiles is odd)
+    auto step = [&](int i, bool consume) {
       wait_tiles<NS - 2, N_DMA>(KTg - 1 - i);  // this set's tile i has landed; up to NS-2 younger ones may be in flight
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       __builtin_amdgcn_s_barrier();
@@ -354,7 +357,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
           if (++cs_kw == p.cv_S) cs_kw = 0, ++cs_kh;
         }
       }
-      if (KS == 1 || i < KTg) {
+      if (consume) {
         fetch(stage, 0, a0, b0);
         fetch(stage, 1, a1, b1);
         prep(a0);
@@ -363,7 +366,12 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
         mma(a1, b1);
       }
       stage = stage == NS - 1 ? 0 : stage + 1;
-    }
+    };
+    // the steps in which every set has a tile run unconditionally: a conditional MFMA inside the loop makes the
+    // compiler copy the accumulators every iteration
+    const int KTall = KT / KS;
+    for (int i = 0; i < KTall; ++i) step(i, true);
+    if (KS > 1 && KT2 > KTall) step(KTall, KTall < KTg);
   } else {
     // General path: one stage, no overlap.  A goes through registers byte by byte with bounds checks;
     // bytes past K are stored as 0x80 (int8 zero after the shift), rows past M repeat the last row.
@@ -455,6 +463,10 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
   if (MODE != QG_MODE_ACC32) {
     const bool full_cols = p.c_vec && (n0 + BN <= p.N);  // uniform: every 16-byte store is in range
     const float czp_f = (float)p.c_zp;
+    // LO: the output pipeline needs its explicit lower clamp (see qg_requant_pack); uniform over the launch.
+    // One-block waves keep the single, always-correct form: their pipeline is 16 values per lane, and a second
+    // copy of it costs registers that the occupancy of those kernels needs.
+    const bool need_lo = MODE == QG_MODE_REQUANT && (TM * TN == 1 || qg_requant_needs_lo(p.clamp_lo, czp_f));
 #pragma unroll
     for (int nb = 0; nb < TN; ++nb) {
       const int col_l = (wave_n * TN + nb) * 32 + lg * 16;
@@ -467,6 +479,8 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
         *reinterpret_cast<v4i*>(&nbz[4 * q]) = *reinterpret_cast<const v4i*>(&bz_s[col_l + 4 * q]);
         *reinterpret_cast<float4*>(&sc[4 * q]) = *reinterpret_cast<const float4*>(&sc_s[col_l + 4 * q]);
       }
+      auto rows = [&](auto lo_tag) {
+      constexpr bool LO = decltype(lo_tag)::value;
 #pragma unroll
       for (int mb = 0; mb < TM; ++mb) {
         const int row = m0 + (wave_m * TM + mb) * 32 + l32;
@@ -480,7 +494,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
             for (int t = 0; t < 4; ++t) {
               const int i = 4 * q + t;
               const int x = acc[mb][nb][i] + cj[i] + (ROWSUM ? __mul24(nbz[i], rsum) : 0);
-              w = qg_requant_pack(x, sc[i], p.clamp_lo, p.clamp_hi, czp_f, t, w);
+              w = qg_requant_pack<LO>(x, sc[i], p.clamp_lo, p.clamp_hi, czp_f, t, w);
             }
             out[q] = w;
           }
@@ -516,6 +530,11 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
           }
         }
       }
+      };
+      if (need_lo)
+        rows(std::true_type{});
+      else
+        rows(std::false_type{});
     }
   } else {
 #pragma unroll

@@ -150,17 +150,24 @@ __device__ __forceinline__ int qg_requant_one(int x, float sc, float lo, float h
   const float c = __builtin_amdgcn_fmed3f(r, lo, hi);  // lo <= hi, r is never NaN for finite scales
   return (int)c + czp;
 }
-// Same sequence, result inserted as byte `pos` of `word`.  After the clamp the value is an integer in
-// [-theta_C, 255 - theta_C]; adding theta_C in fp32 is exact and v_cvt_pk_u8_f32 converts that integer
-// exactly, so the byte equals qg_requant_one() bit for bit while the convert also does the packing.
+// Same result, inserted as byte `pos` of `word`, in fewer instructions.  v_cvt_pk_u8_f32 converts with
+// saturation to [0, 255] (and an integer-valued input exactly), so the clamp is done by the convert itself:
+// with r the rounded product, min(max(r, lo), hi) + theta_C == sat_u8(max(r + theta_C, lo + theta_C)).
+// r + theta_C is exact while |r| < 2^24 and stays far outside [0, 255], on the same side, beyond that.
+// Without ReLU the lower bound lo + theta_C is 0, which the saturation covers; with ReLU it is theta_C and
+// needs the explicit max unless theta_C == 0.  LO says whether that max is needed; `lo`, `hi` are the bounds of
+// qg_requant_one (lo - theta_C <= 0 <= 255 - theta_C), used only when LO.
+template <bool LO>
 __device__ __forceinline__ unsigned qg_requant_pack(int x, float sc, float lo, float hi, float czp_f,
                                                     unsigned pos, unsigned word) {
   const float f = (float)x;
   const float p = f * sc;
-  const float r = __builtin_rintf(p);
-  const float c = __builtin_amdgcn_fmed3f(r, lo, hi) + czp_f;
-  return __builtin_amdgcn_cvt_pk_u8_f32(c, pos, word);
+  float r = __builtin_rintf(p);
+  if (LO) r = __builtin_amdgcn_fmed3f(r, lo, hi);
+  return __builtin_amdgcn_cvt_pk_u8_f32(r + czp_f, pos, word);
 }
+// whether the explicit lower clamp is needed: ReLU (lo == 0 in the shifted domain) with a nonzero theta_C
+__device__ __forceinline__ bool qg_requant_needs_lo(float lo, float czp_f) { return lo == 0.0f && czp_f != 0.0f; }
 // fp32 output of one corrected accumulator: int32 -> fp32 (nearest even), ONE fp32 multiply, optional
 // max(., 0) (lo = 0 with ReLU, -inf without; a select, so no NaN-canonicalising extra instruction).
 __device__ __forceinline__ float qg_dequant_one(int x, float sc, float lo) {
