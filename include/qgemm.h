@@ -19,8 +19,13 @@
  * "dev" pointers are device (HBM) addresses valid on the current HIP device;
  * "host" pointers are ordinary host memory.  `stream` is a hipStream_t passed
  * as void* (NULL = the default stream).  Every run-time call is asynchronous:
- * a 0 return means "enqueued on `stream`".  The two offline packing calls
- * wait once for `stream` (they stage the host zero points through it).
+ * a 0 return means "enqueued on `stream`".  The run-time calls (the GEMMs, the
+ * convolutions, qg_quantize_a_f32) enqueue kernels and nothing else -- no copy,
+ * no memset, no allocation -- so they may be recorded into a HIP graph and
+ * replayed; call each once outside the capture first (the first launch of a
+ * kernel raises its LDS limit with a runtime call).  The offline packing and
+ * counting calls wait once for `stream` (they stage host values through it) and
+ * cannot be recorded.
  *
  * Errors: every function returns 0 on success or one of the negative QG_E*
  * codes; nothing is printed, nothing aborts.  On error no output is written.
