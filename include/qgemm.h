@@ -153,6 +153,8 @@ int qg_gemm_u8s8_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* 
  *   TILE256         256 x 256, four LDS stages, hand-scheduled loop (large shapes)
  *   TILE128K2       128 x 128 with K split over two wave sets like TILE64 (grids of
  *                   128 x 128 tiles that leave compute units idle and have a long K)
+ *   TILE64K4        64 x 64 with K split over four wave sets (1024 threads; a few
+ *                   tiles and a long K)
  * QG_KERNEL_AUTO picks by (M, N, K): first the rules installed with
  * qg_dispatch_set_rules (an offline autotune writes them), then a built-in
  * rule of thumb derived from the same measurements. */
@@ -165,7 +167,8 @@ int qg_gemm_u8s8_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* 
 #define QG_KERNEL_TILE128X256 6
 #define QG_KERNEL_TILE256 7
 #define QG_KERNEL_TILE128K2 8
-#define QG_KERNEL_LAST 8
+#define QG_KERNEL_TILE64K4 9
+#define QG_KERNEL_LAST 9
 
 /* Name of a kernel id ("skinny16", "tile128x256", ...; "auto" for 0), NULL if invalid. */
 const char* qg_kernel_name(int kernel);

@@ -61,7 +61,8 @@ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // latency) and `fix` us of launch, prologue and output pipeline.  With the chip full, each of the
 // ceil(workgroups / 256) workgroups a CU has to run costs `thr` us per k step and `epi` us of output
 // pipeline: a big tile moves the fewest LDS bytes per multiply (small `thr` per unit of work) but pays for
-// it with few, long workgroups.  The estimate is the larger of the two regimes.
+// it with few, long workgroups.  The estimate is the larger of the two regimes; a grid of at most one
+// workgroup per CU is in the first by definition.
 // Streaming kernels.  One workgroup per 16 columns and per row block; alone it takes fix + K * lat_k us, with
 // the chip full each workgroup costs wg + K * wg_k nanoseconds; a third bound covers tall, narrow shapes.
 struct tile_cost {
@@ -78,6 +79,7 @@ const tile_cost k_tile_cost[] = {
     {QG_KERNEL_TILE128X256, 128, 256, 5.5, 0.527, 0.514, 2.07},
     {QG_KERNEL_TILE256, 256, 256, 8.7, 0.524, 0.838, 6.87},
     {QG_KERNEL_TILE128K2, 128, 128, 4.4, 0.273, 0.34, 2.0},
+    {QG_KERNEL_TILE64K4, 64, 64, 4.15, 0.089, 0.103, 2.1},
 };
 const stream_cost k_stream_cost[] = {
     {QG_KERNEL_SKINNY16, 16, 3.58, 7.3e-5, 7.55, 0.74e-3},
@@ -87,15 +89,29 @@ const stream_cost k_stream_cost[] = {
 // A streaming workgroup re-reads its rows of A for every 16 columns; with few columns to share them that
 // traffic comes from far memory, row piece by row piece, at about this many bytes per microsecond.
 const double k_stream_a_rate = 2.0e6;
+const double k_stream_a_near = 1048576.0;     // bytes of A that the L2s keep
+const double k_stream_a_far_rate = 1.0e7;     // bytes per microsecond, all workgroups together
 
 double stream_estimate(const stream_cost& c, int M, int N, int K) {
   const double wgs = (double)ceil_div(M, c.rows) * (double)(2 * ceil_div(N, 32));
-  const double a_bound = 2.5 + (double)M * (double)K / k_stream_a_rate;
-  return fmax(fmax(c.fix + K * c.lat_k, 2.5 + wgs * (c.wg + K * c.wg_k) * 1e-3), a_bound);
+  double a_bound = 2.5 + (double)M * (double)K / k_stream_a_rate;
+  // an A too large to stay in the L2s is fetched from far memory once per 16 columns
+  if ((double)M * (double)K > k_stream_a_near)
+    a_bound = fmax(a_bound, 2.5 + (double)M * (double)K * (double)ceil_div(N, 16) / k_stream_a_far_rate);
+  const double alone = fmax(c.fix + K * c.lat_k, a_bound);
+  if (wgs <= 256.0) return alone;  // at most one workgroup per CU: each runs as if alone
+  return fmax(alone, 2.5 + wgs * (c.wg + K * c.wg_k) * 1e-3);
+}
+
+double tile_estimate(const tile_cost& c, int M, int N, int K) {
+  const double kt = (double)ceil_div(K, 64);
+  const double wgs = (double)ceil_div(M, c.bm) * (double)ceil_div(N, c.bn);
+  const double alone = c.fix + kt * c.lat;
+  if (wgs <= 256.0) return alone;
+  return fmax(alone, 2.5 + ceil(wgs / 256.0) * (kt * c.thr + c.epi));
 }
 
 int builtin_select(int M, int N, int K) {
-  const double kt = (double)ceil_div(K, 64);
   int best = QG_KERNEL_TILE64;
   double best_us = 1e300;
   for (const stream_cost& c : k_stream_cost) {
@@ -105,9 +121,7 @@ int builtin_select(int M, int N, int K) {
     if (us < best_us) best_us = us, best = c.kernel;
   }
   for (const tile_cost& c : k_tile_cost) {
-    const double wgs = (double)ceil_div(M, c.bm) * (double)ceil_div(N, c.bn);
-    const double per_cu = ceil(wgs / 256.0);
-    const double us = fmax(c.fix + kt * c.lat, 2.5 + per_cu * (kt * c.thr + c.epi));
+    const double us = tile_estimate(c, M, N, K);
     if (us < best_us) best_us = us, best = c.kernel;
   }
   return best;
@@ -172,7 +186,7 @@ extern "C" {
 const char* qg_kernel_name(int kernel) {
   static const char* const names[] = {"auto",   "skinny16", "skinny32",    "skinny64",
                                       "tile64", "tile128",  "tile128x256", "tile256",
-                                      "tile128k2"};
+                                      "tile128k2", "tile64k4"};
   return (kernel >= 0 && kernel <= QG_KERNEL_LAST) ? names[kernel] : nullptr;
 }
 
@@ -608,11 +622,9 @@ int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int
   // the tiled kernels with a compiler-scheduled loop, chosen like a GEMM of the same extents
   int kernel = QG_KERNEL_TILE64;
   double best_us = 1e300;
-  const double kt = (double)(a.K / 64);
   for (const tile_cost& c : k_tile_cost) {
-    if (c.kernel == QG_KERNEL_TILE256 || c.kernel == QG_KERNEL_TILE128K2) continue;
-    const double wgs = (double)ceil_div(a.M, c.bm) * (double)ceil_div(a.N, c.bn);
-    const double us = fmax(c.fix + kt * c.lat, 2.5 + ceil(wgs / 256.0) * (kt * c.thr + c.epi));
+    if (c.kernel == QG_KERNEL_TILE256 || c.kernel == QG_KERNEL_TILE128K2 || c.kernel == QG_KERNEL_TILE64K4) continue;
+    const double us = tile_estimate(c, a.M, a.N, a.K);
     if (us < best_us) best_us = us, kernel = c.kernel;
   }
   const hipError_t e = qg_launch_conv_dense(a, kernel, static_cast<hipStream_t>(stream));

@@ -131,7 +131,7 @@ template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, boo
 __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) / KS) void qg_gemm_tile_kernel(const qg_gemm_args p,
                                                                                                 int tiles_m,
                                                                                                 int tiles_n) {
-  static_assert(KS == 1 || (KS == 2 && PATH == PATH_PIPE && !CONV), "K split: two wave sets on the pipelined path");
+  static_assert(KS == 1 || ((KS == 2 || KS == 4) && PATH == PATH_PIPE && !CONV), "K split: wave sets on the pipelined path");
   constexpr int NW = NWM * NWN, NT = NW * KS * 64;  // NW: waves of one set; NT: threads of the workgroup
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
   constexpr int A_STAGE = BM * BK, B_STAGE = BN * BK, STAGE = A_STAGE + B_STAGE;
@@ -146,7 +146,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in an SGPR
-  const int kg = wave_all / NW;      // wave set (0 unless KS == 2)
+  const int kg = wave_all / NW;      // wave set (0 unless KS > 1)
   const int wave = wave_all % NW;    // position inside the set
   const int wave_m = wave % NWM, wave_n = wave / NWM;
   const int l32 = lane & 31, lg = lane >> 5;
@@ -401,31 +401,37 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
     }
   }
 
-  // ---- K split: the second wave set hands its accumulators and byte sums to the first through LDS
-  if constexpr (KS == 2) {
+  // ---- K split: the other wave sets hand their accumulators and byte sums to the first through LDS
+  if constexpr (KS > 1) {
     constexpr int PER_LANE = TM * TN * 16 + TM;
-    static_assert(4096 + PER_LANE * NW * 64 * 4 <= NS * KS * STAGE, "partials must fit the stage memory");
+    constexpr int SET = PER_LANE * NW * 64;  // ints per handing set
+    static_assert(4096 + (KS - 1) * SET * 4 <= NS * KS * STAGE, "partials must fit the stage memory");
     __syncthreads();  // every wave is done with the stages
     int* red = reinterpret_cast<int*>(smem) + 1024;  // past the per-column constants staged below
-    if (kg == 1) {
+    if (kg != 0) {
+      int* mine = red + (kg - 1) * SET;
 #pragma unroll
       for (int mb = 0; mb < TM; ++mb) {
 #pragma unroll
         for (int nb = 0; nb < TN; ++nb)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) red[((mb * TN + nb) * 16 + r) * (NW * 64) + wave * 64 + lane] = acc[mb][nb][r];
-        red[(TM * TN * 16 + mb) * (NW * 64) + wave * 64 + lane] = (int)rs[mb];
+          for (int r = 0; r < 16; ++r) mine[((mb * TN + nb) * 16 + r) * (NW * 64) + wave * 64 + lane] = acc[mb][nb][r];
+        mine[(TM * TN * 16 + mb) * (NW * 64) + wave * 64 + lane] = (int)rs[mb];
       }
     }
     __syncthreads();
     if (kg == 0) {
 #pragma unroll
-      for (int mb = 0; mb < TM; ++mb) {
+      for (int g = 0; g < KS - 1; ++g) {
+        const int* theirs = red + g * SET;
 #pragma unroll
-        for (int nb = 0; nb < TN; ++nb)
+        for (int mb = 0; mb < TM; ++mb) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) acc[mb][nb][r] += red[((mb * TN + nb) * 16 + r) * (NW * 64) + wave * 64 + lane];
-        rs[mb] += (unsigned)red[(TM * TN * 16 + mb) * (NW * 64) + wave * 64 + lane];
+          for (int nb = 0; nb < TN; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mb][nb][r] += theirs[((mb * TN + nb) * 16 + r) * (NW * 64) + wave * 64 + lane];
+          rs[mb] += (unsigned)theirs[(TM * TN * 16 + mb) * (NW * 64) + wave * 64 + lane];
+        }
       }
     }
   }
@@ -455,7 +461,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
     bz_s[t] = -bz;  // negated: x = acc + cj + (-theta_B) * rowsum
   }
   __syncthreads();
-  if (KS == 2 && kg == 1) return;  // the first wave set holds the sums and runs the output pipeline
+  if (KS > 1 && kg != 0) return;  // the first wave set holds the sums and runs the output pipeline
 
   // ---- epilogue straight from the accumulators.  Lane (l32, lg) of block (mb, nb) holds row
   // 32*mb + l32 and the 16 consecutive columns 32*nb + 16*lg .. +15; the per-column constants of a
@@ -626,6 +632,7 @@ hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, int kernel, hipS
     case QG_KERNEL_TILE128: return launch_cfg<PATH_PIPE, 2, 2, 2, 2>(a, mode, s);
     case QG_KERNEL_TILE128X256: return launch_cfg<PATH_PIPE, 2, 2, 2, 4>(a, mode, s);
     case QG_KERNEL_TILE128K2: return launch_cfg<PATH_PIPE, 2, 2, 2, 2, 2>(a, mode, s);
+    case QG_KERNEL_TILE64K4: return launch_cfg<PATH_PIPE, 2, 2, 1, 1, 4>(a, mode, s);
     case QG_KERNEL_TILE256:
       if (a.K >= NSTAGE * BK) return launch_cfg<PATH_ASM, 2, 2, 4, 4>(a, mode, s);
       return launch_cfg<PATH_PIPE, 2, 2, 2, 4>(a, mode, s);

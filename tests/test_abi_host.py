@@ -126,7 +126,7 @@ def test_kernel_selection_is_host_logic(lib):
     assert names[q.kernel_select(8192, 8192, 8192)] == "tile256"
     assert names[q.kernel_select(32768, 512, 1024)] in ("tile256", "tile128x256")
     assert names[q.kernel_select(2048, 2048, 2048)] in ("tile128", "tile128k2")
-    assert names[q.kernel_select(128, 8192, 1024)] == "tile64"
+    assert names[q.kernel_select(128, 8192, 1024)] in ("tile64", "tile64k4")
     # the choice is always a concrete kernel
     for shape in [(65, 64, 64), (128, 4096, 4096), (2048, 2048, 2048), (32768, 512, 1024), (1 << 20, 16, 64)]:
         assert 1 <= q.kernel_select(*shape) <= q.KERNEL_LAST
