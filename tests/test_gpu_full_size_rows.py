@@ -82,3 +82,37 @@ def test_dense_conv_layers_at_batch_32(env, H, C):
         want = oracle.conv_groupwise_direct(c.inp[n:n + 1], 1, c.wgt, c.a_zp, c.b_zp, c.bias, c.scales, c.c_zp, c.relu,
                                             c.pad, c.stride)
         assert_same(got[n:n + 1], want, f"image {n}")
+
+
+@pytest.mark.parametrize("shape,kernels", [
+    ((128, 4096, 4096), ["auto", "tile64", "tile64k4", "skinny64"]),
+    ((2048, 2048, 2048), ["auto", "tile128", "tile128k2"]),
+    ((4096, 1024, 1024), ["auto", "tile128k2", "tile128x256"]),
+    ((16384, 256, 512), ["auto", "tile64", "tile256"]),
+])
+def test_kernel_family_at_the_benchmark_shapes(env, shape, kernels):
+    """The shapes of bench.py's kernel-family rows, through the automatic choice and the kernels that compete for
+    them: sampled complete rows (one per 64-row block of a sample of blocks, first and last row) against the oracle,
+    and all kernels byte-identical to each other on the whole output."""
+    q, torch, dev, oracle = env
+    M, N, K = shape
+    say(f"kernel family {shape}")
+    c = wl.unsaturated(wl.random_gemm(900 + M % 97 + N % 89, M, N, K, per_channel=True, with_bias=True, relu=True))
+    rows = _rows(M, 64, 13, 4)
+    if rows.size > 48:
+        rows = np.unique(np.concatenate([rows[:: rows.size // 40], rows[-2:]]))
+    A, B = torch.from_numpy(c.A).to(dev), torch.from_numpy(c.B).to(dev)
+    bias, scales = torch.from_numpy(c.bias).to(dev), torch.from_numpy(c.scales).to(dev)
+    Bp = q.pack_b(B, c.b_zp)
+    want = oracle.gemm_u8s8_requant(np.ascontiguousarray(c.A[rows]), c.a_zp, c.B, c.b_zp, c.bias, c.scales, c.c_zp,
+                                    c.relu)
+    assert np.mean((want > 0) & (want < 255)) > 0.3
+    first = None
+    for kernel in kernels:
+        got = q.gemm_u8s8_requant(A, c.a_zp, Bp, bias, scales, c.c_zp, c.relu, kernel=kernel)
+        torch.cuda.synchronize()
+        assert_same(got[torch.from_numpy(rows).to(dev)].cpu().numpy(), want, f"{kernel} rows of {shape}")
+        if first is None:
+            first = got
+        else:
+            assert torch.equal(first, got), f"{kernel} differs from {kernels[0]} on {shape}"
