@@ -63,6 +63,29 @@ def time_calls(torch, fn, steps, warmup, spin_ms=0.0):
     return wall_ms, dev_ms
 
 
+def time_graph(torch, calls, reps, spin_ms):
+    """The same launches recorded once into a HIP graph and replayed: per-launch device time in ms.  Replay
+    removes the host's per-launch cost and most of the gap between dispatches, which is what a serving loop of
+    microsecond kernels would do.  `calls` are Prepared* objects; they are bound back to the current stream."""
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for c in calls:
+            c.rebind().launch()
+    for c in calls:
+        c.rebind()
+    t_end = time.perf_counter() + spin_ms * 1e-3
+    while time.perf_counter() < t_end:
+        g.replay()
+        torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(reps):
+        g.replay()
+    ev1.record()
+    torch.cuda.synchronize()
+    return ev0.elapsed_time(ev1) / (reps * len(calls))
+
+
 def traffic_from_profiles(kernel_key):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), if a summary is committed."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
@@ -224,8 +247,13 @@ def main():
         torch.cuda.synchronize()
         cold = [q.PreparedGemm(a, c2.a_zp, bp, None, scales2, c2.c_zp, c2.relu, cc) for bp, a, cc in sets]
         _, cold_ms = time_calls(torch, lambda i: cold[i % nsets].launch(), 4 * nsets, nsets, spin_ms=SPIN_MS)
+        gwarm_ms = time_graph(torch, [warm] * 200, 5, SPIN_MS)
+        gcold_ms = time_graph(torch, cold * 2, 5, SPIN_MS)
         side.append({"workload": c2.name, "bound": "hbm", "bytes": nbytes,
                      "cold_us": round(cold_ms * 1e3, 2), "warm_us": round(warm_ms * 1e3, 2),
+                     "graph_cold_us": round(gcold_ms * 1e3, 2), "graph_warm_us": round(gwarm_ms * 1e3, 2),
+                     "graph_cold_GBps": round(nbytes / (gcold_ms * 1e-3) / 1e9, 1),
+                     "graph_warm_GBps": round(nbytes / (gwarm_ms * 1e-3) / 1e9, 1),
                      "cold_GBps": round(nbytes / (cold_ms * 1e-3) / 1e9, 1),
                      "warm_GBps": round(nbytes / (warm_ms * 1e-3) / 1e9, 1),
                      "frac_hbm_peak_cold": round(nbytes / (cold_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
@@ -242,7 +270,9 @@ def main():
         _, ms = time_calls(torch, lambda i: callx.launch(), 200, 5, spin_ms=SPIN_MS)
         nb = gemm_bytes(c.M, c.N, c.K, c.bias is not None)
         o = 2.0 * c.M * c.N * c.K
-        side.append({"workload": c.name, "us": round(ms * 1e3, 2), "TOPS": round(o / (ms * 1e-3) / 1e12, 2),
+        gms = time_graph(torch, [callx] * 100, 5, SPIN_MS)
+        side.append({"workload": c.name, "us": round(ms * 1e3, 2), "graph_us": round(gms * 1e3, 2),
+                     "TOPS": round(o / (ms * 1e-3) / 1e12, 2),
                      "GBps": round(nb / (ms * 1e-3) / 1e9, 1),
                      "frac_int8_peak": round(o / (ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 4),
                      "frac_hbm_peak": round(nb / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "pack_b_ms": round(packx_ms, 3),
@@ -263,8 +293,11 @@ def main():
         _, cold_ms = time_calls(torch, lambda i: convs[i % nsets].launch(), 4 * nsets, nsets, spin_ms=SPIN_MS)
         nb = 2 * inp.numel() + wgt.numel()
         o = 2.0 * inp.shape[0] * 56 * 56 * 128 * 36
+        gwarm_ms = time_graph(torch, [convs[0]] * 100, 5, SPIN_MS)
+        gcold_ms = time_graph(torch, convs * 2, 5, SPIN_MS)
         side.append({"workload": c5.name, "bound": "hbm", "bytes": nb, "cold_us": round(cold_ms * 1e3, 2),
-                     "warm_us": round(warm_ms * 1e3, 2), "cold_GBps": round(nb / (cold_ms * 1e-3) / 1e9, 1),
+                     "warm_us": round(warm_ms * 1e3, 2), "graph_cold_us": round(gcold_ms * 1e3, 2),
+                     "graph_warm_us": round(gwarm_ms * 1e3, 2), "cold_GBps": round(nb / (cold_ms * 1e-3) / 1e9, 1),
                      "warm_GBps": round(nb / (warm_ms * 1e-3) / 1e9, 1),
                      "frac_hbm_peak_cold": round(nb / (cold_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                      "TOPS_cold": round(o / (cold_ms * 1e-3) / 1e12, 2),

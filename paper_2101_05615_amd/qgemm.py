@@ -284,6 +284,11 @@ class PreparedGemm:
         if rc != OK:
             raise QGemmError(rc, "qg_gemm_u8s8_requant")
 
+    def rebind(self):
+        """Later launches go to the stream that is current now (e.g. the capturing stream of a graph)."""
+        self._args = self._args[:8] + (_stream(),) + self._args[9:]
+        return self
+
 
 class PreparedConv:
     """Same for qg_conv_groupwise_u8s8_requant."""
@@ -302,6 +307,11 @@ class PreparedConv:
         rc = lib.qg_conv_groupwise_u8s8_requant(*self._args)
         if rc != OK:
             raise QGemmError(rc, "qg_conv_groupwise_u8s8_requant")
+
+    def rebind(self):
+        """Later launches go to the stream that is current now (e.g. the capturing stream of a graph)."""
+        self._args = self._args[:-1] + (_stream(),)
+        return self
 
 
 def gemm_u8s8_acc32(A, Bp, want_rowsum=False, kernel=KERNEL_AUTO):
