@@ -204,6 +204,57 @@ def main():
     assert int(C.min().item()) >= c3.c_zp
     c3_unsat = unsaturated_frac(torch, C)
 
+    # ------------------------------------------------------------------ what the machine sustains (probes)
+    # Right after the headline run, so with settled clocks: a register-only int8 MFMA loop on operands with the
+    # workload's bit statistics (A's bytes) and on constant operands, and a streaming read from the Infinity
+    # Cache (16 MiB, read repeatedly) and from HBM (1 GiB).
+    sustained = None
+    if only is None:
+        sink = torch.empty(256 * 256, dtype=torch.int32, device=dev)
+        ones = torch.full((32768,), 1, dtype=torch.uint8, device=dev)
+
+        def mfma_tops(operands):
+            iters = 100000  # 256 workgroups x 4 waves x 16 MFMAs x 32 cycles: about 30-50 ms
+            q.probe_mfma_i8(operands, sink, 256, 2000)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            q.probe_mfma_i8(operands, sink, 256, iters)   # settles the clocks for this operand mix
+            e0.record()
+            q.probe_mfma_i8(operands, sink, 256, iters)
+            e1.record()
+            torch.cuda.synchronize()
+            return 256.0 * 4 * iters * 16 * 65536 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+        def read_gbps(buf, reps):
+            # replayed as a graph: the host cannot issue microsecond launches fast enough through Python
+            for _ in range(3):
+                q.probe_read(buf, sink)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for _ in range(reps):
+                    q.probe_read(buf, sink)
+            g.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(3):
+                g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            return buf.numel() / (e0.elapsed_time(e1) * 1e-3 / (3 * reps)) / 1e9
+
+        rand_tops = mfma_tops(A)
+        const_tops = mfma_tops(ones)
+        small = torch.empty(16 << 20, dtype=torch.uint8, device=dev).random_(0, 256)
+        big = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 256)
+        sustained = {"int8_mfma_workload_operands_TOPS": round(rand_tops, 1),
+                     "int8_mfma_constant_operands_TOPS": round(const_tops, 1),
+                     "read_16MiB_GBps": round(read_gbps(small, 200), 1),
+                     "read_1GiB_GBps": round(read_gbps(big, 10), 1)}
+        roofline["frac_of_sustained"] = round(kern_tops / rand_tops, 4)
+        del small, big, sink, ones
+
     # ------------------------------------------------------------------ cpu baseline (oracle, bounded sample)
     cpu = None
     if not args.no_cpu_baseline:
@@ -389,6 +440,7 @@ def main():
                    "outputs_inside_0_255": c3_unsat},
         "pack_b_ms": round(pack_ms, 3),
         "roofline": roofline,
+        "sustained": sustained,
         "cpu_baseline": cpu,
         "configs": side,
         "next_rows": nxt,

@@ -332,6 +332,25 @@ int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int
                                int pad, int stride, const qg_packed_b* Wp, const qg_requant_params* p,
                                uint8_t* out_nhwc, void* stream);
 
+/* ---- measurement probes --------------------------------------------------- */
+
+/* What the machine sustains on the two resources the kernels are priced against
+ * (the performance discussion of the paper, Sec. 3, is in terms of the same two:
+ * compute peak and memory bandwidth).  Not part of the GEMM path; asynchronous.
+ *
+ * qg_probe_mfma_i8: a register-only loop of v_mfma_i32_32x32x32_i8 on a 4 x 4
+ * block register tile per wave; `workgroups` workgroups of 4 waves run `iters`
+ * rounds of 16 matrix instructions each, i.e. workgroups * 4 * iters * 16 * 65536
+ * operations.  The operands are the first 32 KiB at operands_dev (16-byte
+ * aligned, any content: the clock the chip holds depends on how many operand
+ * bits toggle, so pass bytes distributed like the data of interest).
+ * sink_dev receives workgroups * 256 int32 (contents meaningless).
+ *
+ * qg_probe_read: reads `bytes` (a multiple of 16) from src_dev (16-byte
+ * aligned) once with `workgroups` workgroups of 256 threads; sink_dev: one int32. */
+int qg_probe_mfma_i8(const void* operands_dev, int32_t* sink_dev, int workgroups, int iters, void* stream);
+int qg_probe_read(const void* src_dev, size_t bytes, int32_t* sink_dev, int workgroups, void* stream);
+
 const char* qg_status_string(int code);
 
 #ifdef __cplusplus

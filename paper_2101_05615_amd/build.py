@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqgemm.so")
-SOURCES = ["api.hip", "pack.hip", "quantize_a.hip", "gemm_tile.hip", "gemm_skinny.hip", "conv_group.hip"]
+SOURCES = ["api.hip", "pack.hip", "quantize_a.hip", "gemm_tile.hip", "gemm_skinny.hip", "conv_group.hip", "probe.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -87,6 +87,17 @@ def test_null_and_range_checks_happen_before_any_device_work(lib):
     assert lib.qg_conv_groupwise_u8s8_requant(fake, 1, 4, 4, 4, 1, 1, None, ctypes.byref(p), fake, None) == q.ENULL
     lib.qg_packed_b_destroy(None)
     assert lib.qg_packed_b_k(None) == 0 and lib.qg_gemm_workspace_bytes(16, None) == 0
+    # the measurement probes validate the same way
+    lib.qg_probe_mfma_i8.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    lib.qg_probe_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+    assert lib.qg_probe_mfma_i8(None, fake, 1, 1, None) == q.ENULL
+    assert lib.qg_probe_mfma_i8(fake, fake, 0, 1, None) == q.EINVAL
+    assert lib.qg_probe_mfma_i8(fake, fake, 1, 0, None) == q.EINVAL
+    assert lib.qg_probe_mfma_i8(ctypes.c_void_p(260), fake, 1, 1, None) == q.EALIGN
+    assert lib.qg_probe_read(fake, 16, None, 1, None) == q.ENULL
+    assert lib.qg_probe_read(fake, 24, fake, 1, None) == q.EINVAL
+    assert lib.qg_probe_read(fake, 0, fake, 1, None) == q.EINVAL
+    assert lib.qg_probe_read(ctypes.c_void_p(264), 16, fake, 1, None) == q.EALIGN
 
 
 def test_status_strings(lib):
