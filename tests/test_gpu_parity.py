@@ -339,3 +339,17 @@ def test_runtime_argument_errors(env):
     p = q.RequantParams(128, None, scales.data_ptr(), 1, 0, 0)
     assert q.lib.qg_gemm_u8s8_requant(A.data_ptr(), 64, 128, Wp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None) == q.EINVAL
     torch.cuda.synchronize()
+
+
+def test_measurement_probes_run(env):
+    """The probes are timing aids, not part of the path: they must launch, finish and leave their inputs alone."""
+    q, torch, dev, oracle = env
+    say("probes")
+    operands = torch.arange(32768, dtype=torch.int32, device=dev).to(torch.uint8)
+    before = operands.clone()
+    sink = torch.zeros(4 * 256, dtype=torch.int32, device=dev)
+    q.probe_mfma_i8(operands, sink, 4, 3)
+    src = torch.ones(1 << 20, dtype=torch.uint8, device=dev)
+    q.probe_read(src, sink, workgroups=64)
+    torch.cuda.synchronize()
+    assert torch.equal(operands, before) and int(src.sum().item()) == 1 << 20
