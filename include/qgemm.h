@@ -124,8 +124,10 @@ size_t qg_gemm_workspace_bytes(int M, const qg_packed_b* Bp);
  *   A_dev  dev, uint8, row-major M x K (K from Bp), lda >= K
  *   C_dev  dev, uint8, row-major M x N, ldc >= N; must not alias A
  * No alignment is required; 16-byte aligned A_dev/C_dev with lda, ldc multiples
- * of 16 take the vectorised load/store path.  Identical inputs give identical
- * bytes on every run. */
+ * of 16 take the vectorised load/store path.  A may exceed 4 GiB: the kernels
+ * address it with 32-bit offsets from a base, so the call then enqueues several
+ * launches over consecutive row ranges.  Identical inputs give identical bytes
+ * on every run. */
 int qg_gemm_u8s8_requant(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp,
                          const qg_requant_params* p, uint8_t* C_dev, int ldc, void* workspace_dev,
                          void* stream);

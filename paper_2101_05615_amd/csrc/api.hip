@@ -148,9 +148,35 @@ int select_kernel(int M, int N, int K) {
   return builtin_select(M, N, K);
 }
 
-hipError_t launch_gemm(const qg_gemm_args& a, int mode, int kernel, hipStream_t s) {
+hipError_t launch_rows(const qg_gemm_args& a, int mode, int kernel, hipStream_t s) {
   if (kernel <= QG_KERNEL_SKINNY64) return qg_launch_gemm_skinny(a, mode, kernel, s);
   return qg_launch_gemm_tile(a, mode, kernel, s);
+}
+
+// The vector / DMA paths address A with 32-bit byte offsets from its base.  An A beyond that reach is run as
+// several launches over consecutive row ranges (whole 256-row tiles, so the tiling is that of one launch),
+// each with its own base pointers; rows are independent, the result is the same.
+hipError_t launch_gemm(const qg_gemm_args& a, int mode, int kernel, hipStream_t s) {
+  const uint64_t reach = (1ull << 32) - (uint64_t)a.K - 4096;
+  if (!a.a_vec || (uint64_t)(a.M - 1) * (uint64_t)a.lda < reach) return launch_rows(a, mode, kernel, s);
+  const int rows = (int)((reach / (uint64_t)a.lda) / 256 * 256);
+  if (rows <= 0) {  // a single row block is already out of reach: byte-wise path
+    qg_gemm_args b = a;
+    b.a_vec = 0;
+    return launch_rows(b, mode, kernel, s);
+  }
+  for (int r0 = 0; r0 < a.M; r0 += rows) {
+    qg_gemm_args b = a;
+    b.M = a.M - r0 < rows ? a.M - r0 : rows;
+    b.A = a.A + (size_t)r0 * (size_t)a.lda;
+    if (a.C) b.C = a.C + (size_t)r0 * (size_t)a.ldc;
+    if (a.Cf) b.Cf = a.Cf + (size_t)r0 * (size_t)a.ldc;
+    if (a.C32) b.C32 = a.C32 + (size_t)r0 * (size_t)a.ldc;
+    if (a.rowsum_out) b.rowsum_out = a.rowsum_out + r0;
+    const hipError_t e = launch_rows(b, mode, kernel, s);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 // resolves QG_KERNEL_AUTO for a descriptor and checks an explicit choice against it: QG_OK, or
@@ -409,8 +435,8 @@ static int gemm_common(const uint8_t* A_dev, int M, int lda, const qg_packed_b* 
   a->sp_entries = Bp->entries;
   a->sp_total = (int)Bp->nnz;
   a->lda = lda;
-  // vector/DMA path: 16-byte aligned rows and 32-bit byte offsets into A
-  a->a_vec = aligned(A_dev, 16) && (lda % 16 == 0) && ((uint64_t)(M - 1) * (uint64_t)lda + (uint64_t)Bp->K + 4096 < (1ull << 32));
+  // vector/DMA path: 16-byte aligned rows (its 32-bit byte offsets into A are taken care of at launch)
+  a->a_vec = aligned(A_dev, 16) && (lda % 16 == 0);
   return QG_OK;
 }
 

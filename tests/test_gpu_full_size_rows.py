@@ -116,3 +116,46 @@ def test_kernel_family_at_the_benchmark_shapes(env, shape, kernels):
             first = got
         else:
             assert torch.equal(first, got), f"{kernel} differs from {kernels[0]} on {shape}"
+
+
+def test_activations_beyond_32_bit_offsets(env):
+    """An A of more than 4 GiB: the kernels address A with 32-bit offsets from a base, so the library runs it as
+    several launches over row ranges.  Rows around the seam, the first and the last row against the oracle, for
+    the automatic choice, a tiled and a streaming kernel."""
+    q, torch, dev, oracle = env
+    M, N, K = 1_050_000, 32, 4096
+    say(f"large A {M} x {K}")
+    rng = np.random.default_rng(2024)
+    B = rng.integers(-128, 128, size=(K, N), dtype=np.int8)
+    b_zp = rng.integers(-4, 5, size=N).astype(np.int32)
+    bias = rng.integers(-1000, 1001, size=N).astype(np.int32)
+    scales = (40.0 / (np.sqrt(K) * 74.0 * 74.0) * 2.0 ** rng.uniform(-1, 1, size=N)).astype(np.float32)
+    a_zp, c_zp = 131, 120
+    A = torch.empty((M, K), dtype=torch.uint8, device=dev)
+    seam = ((1 << 32) - K - 4096) // K // 256 * 256
+    rows = np.array(sorted({0, 1, 255, seam - 256, seam - 1, seam, seam + 1, seam + 255, M - 257, M - 2, M - 1}))
+    # seeded fill, block by block (host memory stays small); the sampled rows are kept for the oracle
+    kept = {}
+    blk = 65536
+    for r0 in range(0, M, blk):
+        n = min(blk, M - r0)
+        a = np.random.default_rng(5000 + r0 // blk).integers(0, 256, size=(n, K), dtype=np.uint8)
+        A[r0:r0 + n].copy_(torch.from_numpy(a).to(dev))
+        for r in rows[(rows >= r0) & (rows < r0 + n)]:
+            kept[int(r)] = a[r - r0].copy()
+    Arows = np.stack([kept[int(r)] for r in rows])
+    want = oracle.gemm_u8s8_requant(Arows, a_zp, B, b_zp, bias, scales, c_zp, False)
+    assert np.mean((want > 0) & (want < 255)) > 0.3
+    Bp = q.pack_b(torch.from_numpy(B).to(dev), b_zp)
+    d_bias, d_scales = torch.from_numpy(bias).to(dev), torch.from_numpy(scales).to(dev)
+    idx = torch.from_numpy(rows).to(dev)
+    first = None
+    for kernel in ("auto", "tile256", "skinny64"):
+        say(f"  kernel {kernel}")
+        got = q.gemm_u8s8_requant(A, a_zp, Bp, d_bias, d_scales, c_zp, False, kernel=kernel)
+        torch.cuda.synchronize()
+        assert_same(got[idx].cpu().numpy(), want, f"{kernel} rows of the large A")
+        if first is None:
+            first = got
+        else:
+            assert torch.equal(first, got), f"{kernel} differs from the automatic choice"
