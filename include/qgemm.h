@@ -123,8 +123,10 @@ size_t qg_gemm_workspace_bytes(int M, const qg_packed_b* Bp);
  * staged tile, accumulates in int32 and writes uint8 C from the accumulators.
  *   A_dev  dev, uint8, row-major M x K (K from Bp), lda >= K
  *   C_dev  dev, uint8, row-major M x N, ldc >= N; must not alias A
- * No alignment is required; 16-byte aligned A_dev/C_dev with lda, ldc multiples
- * of 16 take the vectorised load/store path.  A may exceed 4 GiB: the kernels
+ * No alignment is required and K need not be a multiple of anything: A is staged
+ * with 16-byte requests from any address, a last partial 64-deep slice of K with a
+ * byte mask; a 16-byte aligned C_dev with ldc a multiple of 16 takes the vector
+ * store path.  A may exceed 4 GiB: the kernels
  * address it with 32-bit offsets from a base, so the call then enqueues several
  * launches over consecutive row ranges.  Identical inputs give identical bytes
  * on every run. */

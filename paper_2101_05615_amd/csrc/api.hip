@@ -153,18 +153,14 @@ hipError_t launch_rows(const qg_gemm_args& a, int mode, int kernel, hipStream_t 
   return qg_launch_gemm_tile(a, mode, kernel, s);
 }
 
-// The vector / DMA paths address A with 32-bit byte offsets from its base.  An A beyond that reach is run as
-// several launches over consecutive row ranges (whole 256-row tiles, so the tiling is that of one launch),
+// The kernels address A with 32-bit byte offsets from its base.  An A beyond that reach is run as several
+// launches over consecutive row ranges (whole 256-row tiles where possible, so the tiling is that of one launch),
 // each with its own base pointers; rows are independent, the result is the same.
 hipError_t launch_gemm(const qg_gemm_args& a, int mode, int kernel, hipStream_t s) {
   const uint64_t reach = (1ull << 32) - (uint64_t)a.K - 4096;
-  if (!a.a_vec || (uint64_t)(a.M - 1) * (uint64_t)a.lda < reach) return launch_rows(a, mode, kernel, s);
-  const int rows = (int)((reach / (uint64_t)a.lda) / 256 * 256);
-  if (rows <= 0) {  // a single row block is already out of reach: byte-wise path
-    qg_gemm_args b = a;
-    b.a_vec = 0;
-    return launch_rows(b, mode, kernel, s);
-  }
+  if ((uint64_t)(a.M - 1) * (uint64_t)a.lda < reach) return launch_rows(a, mode, kernel, s);
+  int rows = (int)(reach / (uint64_t)a.lda);  // >= 1: lda is an int
+  if (rows >= 256) rows = rows / 256 * 256;
   for (int r0 = 0; r0 < a.M; r0 += rows) {
     qg_gemm_args b = a;
     b.M = a.M - r0 < rows ? a.M - r0 : rows;
@@ -435,7 +431,6 @@ static int gemm_common(const uint8_t* A_dev, int M, int lda, const qg_packed_b* 
   a->sp_entries = Bp->entries;
   a->sp_total = (int)Bp->nnz;
   a->lda = lda;
-  // vector/DMA path: 16-byte aligned rows (its 32-bit byte offsets into A are taken care of at launch)
   a->a_vec = aligned(A_dev, 16) && (lda % 16 == 0);
   return QG_OK;
 }
@@ -623,7 +618,6 @@ int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int
   a.nb16 = Wp->N_pad / QG_FRAG_COLS;
   a.has_bzp = Wp->has_bzp;
   a.lda = 0;
-  a.a_vec = 1;
   a.bias = p->bias;
   a.scales = p->scales;
   a.scale_stride = p->n_scales == 1 ? 0 : 1;

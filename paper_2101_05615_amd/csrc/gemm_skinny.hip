@@ -29,23 +29,18 @@
 // B again (from L2 / the memory-side cache when the blocks run close together), which beats the
 // tiled kernel only while there are too few tiles to occupy the chip.
 #include "qg_internal.h"
+#include <type_traits>
 
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ v4i load_a_chunk_slow(const uint8_t* p, int kvalid) {
-  union {
-    v4i v;
-    uint8_t b[16];
-  } u;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) u.b[i] = (i < kvalid) ? p[i] : (uint8_t)0x80;
-  return u.v;
-}
-
-template <int MODE, int MB, int NWAVES, int BATCH, bool B4>
+// ANYALIGN: rows of A that are not 16-byte aligned.  The requests and vector loads take any address; the variant
+// exists so that the aligned one keeps its code (and its timing) to the instruction.
+template <int MODE, int MB, int NWAVES, int BATCH, bool B4, bool ANYALIGN>
 __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_gemm_args p) {
+  const bool a_vec = ANYALIGN || p.a_vec;  // whole 16-byte chunks may be moved as such
+  using chunk_t = typename std::conditional<ANYALIGN, qg_v4i_unaligned, v4i>::type;
   // A through LDS (see the file header): per wave and batch, ROWS rows x ROWB bytes
   constexpr int ROWS = MB * 16, ROWB = BATCH * QG_FRAG_K, NCHUNK = ROWB / 16;
   constexpr int REGION = ROWS * ROWB, NREQ = REGION / 1024, RPR = 64 / NCHUNK;  // requests per batch, rows per request
@@ -153,7 +148,7 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
   // batch's weights (into `nxt`), then wait for the activations only.  Requests complete in order, so
   // "at most NLOAD outstanding" means that everything older than the next batch's weights has arrived.
   auto batch = [&](int kb, const v4i (&cur)[NLOAD], v4i (&nxt)[NLOAD], const bool has_next) {
-    const bool staged = p.a_vec && kb + BATCH <= kb_end && (kb + BATCH) * QG_FRAG_K <= p.K;
+    const bool staged = a_vec && kb + BATCH <= kb_end && (kb + BATCH) * QG_FRAG_K <= p.K;
     unsigned char* region = smem + wave * REGION;
     // outlier split: this batch's entries are one run; the first 64 are requested one per lane right behind the
     // activations (always exactly one request, clamped into the buffer, so that the wait below can count it)
@@ -195,10 +190,10 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
         const int k0 = kb * QG_FRAG_K + (lc << 4);
         const uint8_t* src = p.A + (size_t)min(m_base + r, p.M - 1) * p.lda + k0;
         v4i v;
-        if (p.a_vec && k0 + 16 <= p.K)
-          v = *reinterpret_cast<const v4i*>(src);
+        if (a_vec && k0 + 16 <= p.K)
+          v = *reinterpret_cast<const chunk_t*>(src);
         else
-          v = load_a_chunk_slow(src, p.K - k0);
+          v = qg_load_a_chunk(src, p.K - k0, false);  // byte by byte, bytes past K as 0x80
         *reinterpret_cast<v4i*>(region + c * 16) = v;
       }
       sparse_request();
@@ -324,42 +319,43 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
   }
 }
 
-template <int MODE, int MB, int NWAVES, int BATCH, bool B4>
+template <int MODE, int MB, int NWAVES, int BATCH, bool B4, bool ANYALIGN>
 hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   const int part = NWAVES * MB * 64 * (int)sizeof(v4i), stage = NWAVES * (MB * 16) * (BATCH * QG_FRAG_K);
   const int smem = (stage > part ? stage : part) + NWAVES * MB * 16 * (int)sizeof(int) +
                    (B4 ? MB * 256 * (int)sizeof(int) : 0);
-  hipError_t e = qg_allow_smem<qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH, B4>>(smem);
+  hipError_t e = qg_allow_smem<qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH, B4, ANYALIGN>>(smem);
   if (e != hipSuccess) return e;
   const int nfrag = ((a.N + 31) / 32) * 2;
   const int mblocks = (a.M + MB * 16 - 1) / (MB * 16);
   if (mblocks > 65535) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH, B4>), dim3(nfrag, mblocks), dim3(NWAVES * 64), smem,
+  hipLaunchKernelGGL((qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH, B4, ANYALIGN>), dim3(nfrag, mblocks), dim3(NWAVES * 64), smem,
                      s, a);
   return hipGetLastError();
 }
 
 // waves per workgroup and k blocks a wave requests at once, per row-block height
-template <int MODE, bool B4>
+template <int MODE, bool B4, bool ANYALIGN>
 hipError_t launch_mb(const qg_gemm_args& a, int kernel, hipStream_t s) {
   switch (kernel) {
-    case QG_KERNEL_SKINNY16: return launch<MODE, 1, 16, 4, B4>(a, s);
-    case QG_KERNEL_SKINNY32: return launch<MODE, 2, 16, 4, B4>(a, s);
-    case QG_KERNEL_SKINNY64: return launch<MODE, 4, 16, 2, B4>(a, s);
+    case QG_KERNEL_SKINNY16: return launch<MODE, 1, 16, 4, B4, ANYALIGN>(a, s);
+    case QG_KERNEL_SKINNY32: return launch<MODE, 2, 16, 4, B4, ANYALIGN>(a, s);
+    case QG_KERNEL_SKINNY64: return launch<MODE, 4, 16, 2, B4, ANYALIGN>(a, s);
     default: return hipErrorInvalidValue;
   }
 }
 
-template <bool B4>
+template <bool B4, bool ANYALIGN>
 hipError_t launch_mode(const qg_gemm_args& a, int mode, int kernel, hipStream_t s) {
-  if (mode == QG_MODE_REQUANT) return launch_mb<QG_MODE_REQUANT, B4>(a, kernel, s);
-  if (mode == QG_MODE_DEQUANT) return launch_mb<QG_MODE_DEQUANT, B4>(a, kernel, s);
-  return launch_mb<QG_MODE_ACC32, B4>(a, kernel, s);
+  if (mode == QG_MODE_REQUANT) return launch_mb<QG_MODE_REQUANT, B4, ANYALIGN>(a, kernel, s);
+  if (mode == QG_MODE_DEQUANT) return launch_mb<QG_MODE_DEQUANT, B4, ANYALIGN>(a, kernel, s);
+  return launch_mb<QG_MODE_ACC32, B4, ANYALIGN>(a, kernel, s);
 }
 
 }  // namespace
 
 hipError_t qg_launch_gemm_skinny(const qg_gemm_args& a, int mode, int kernel, hipStream_t s) {
   // a.sp_ptr != null: Bp holds the 4-bit part of an outlier-split matrix
-  return a.sp_ptr != nullptr ? launch_mode<true>(a, mode, kernel, s) : launch_mode<false>(a, mode, kernel, s);
+  if (a.a_vec) return a.sp_ptr != nullptr ? launch_mode<true, false>(a, mode, kernel, s) : launch_mode<false, false>(a, mode, kernel, s);
+  return a.sp_ptr != nullptr ? launch_mode<true, true>(a, mode, kernel, s) : launch_mode<false, true>(a, mode, kernel, s);
 }

@@ -51,7 +51,6 @@ constexpr int NSTAGE = 4;   // LDS stages of the hand-scheduled loop: three tile
 constexpr int pipe_stages(int blocks) { return blocks >= 8 ? 3 : (blocks >= 4 ? QG_PS_MID : QG_PS_SMALL); }
 
 // main-loop flavours
-constexpr int PATH_GENERAL = 0;  // any pointer, lda, K: one stage, byte-wise bounds-checked A
 constexpr int PATH_ASM = 1;      // 256 x 256, hand-scheduled, four stages
 constexpr int PATH_PIPE = 2;     // any tile shape, compiler-scheduled, three stages
 
@@ -81,17 +80,6 @@ __device__ __forceinline__ void dma16(const void* gptr, unsigned char* lds_base)
 // spreads the 8 rows a quarter-wave reads at once over all 32 LDS banks)
 __device__ __forceinline__ int a_lds_off(int r, int kc) { return r * BK + ((kc ^ ((r >> 1) & 3)) << 4); }
 
-__device__ __forceinline__ v4i load_a_chunk_slow(const uint8_t* p, int kvalid) {
-  // byte-wise, bounds-checked; bytes past K read as 0x80 (int8 zero after the shift)
-  union {
-    v4i v;
-    uint8_t b[16];
-  } u;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) u.b[i] = (i < kvalid) ? p[i] : (uint8_t)0x80;
-  return u.v;
-}
-
 // operand list shared by the two generated loop variants (gen_tile_loop.py)
 #define QG_TILE_LOOP_OPERANDS \
                  : [c0] "+a"(acc[0][0]), [c1] "+a"(acc[0][1]), [c2] "+a"(acc[0][2]), [c3] "+a"(acc[0][3]), \
@@ -100,14 +88,14 @@ __device__ __forceinline__ v4i load_a_chunk_slow(const uint8_t* p, int kvalid) {
                    [c12] "+a"(acc[3][0]), [c13] "+a"(acc[3][1]), [c14] "+a"(acc[3][2]), [c15] "+a"(acc[3][3]), \
                    [rs01] "=v"(rs01), [rs23] "=v"(rs23) \
                  : [av01] "v"(av01), [av23] "v"(av23), [bv01] "v"(bv01), [bv23] "v"(bv23), [ard] "v"(ard), \
-                   [brd] "v"(brd), [aptr] "s"(p.A - 3072), [bptr] "s"(b_tile0), [kt] "s"(KT), [ldsdma] "s"(lds_dma), \
+                   [brd] "v"(brd), [aptr] "s"(p.A - 3072), [bptr] "s"(b_tile0), [kt] "s"(KTF), [ldsdma] "s"(lds_dma), \
                    [lds] "s"(lds_base), [bstep] "s"(b_step) \
                  : QG_TILE_LOOP_CLOBBERS
 
 // NWM x NWN waves, each TM x TN blocks of 32 x 32.
-// PATH_ASM / PATH_PIPE: A is 16-byte aligned with lda % 16 == 0 and K % 64 == 0 (PATH_ASM: K >= 256), so
-// every tile is requested with global_load_lds and the loop is software-pipelined.  PATH_GENERAL: a plain,
-// single-stage loop stages A byte-wise with bounds checks (correct for any pointer, lda and K).
+// Both loops take any pointer, lda and K (PATH_ASM: K >= 256): every whole 64-deep tile is requested with
+// global_load_lds -- the requests are 16 bytes per lane from any address -- and the loop is software-pipelined; a
+// ragged last tile (K % 64 != 0) is staged once through registers with a byte mask and bounds checks.
 // ROWSUM: row offsets are needed (some theta_B != 0, or the test hook asks for them); without it the
 // loop skips the byte sums and the output pipeline skips the theta_B * rowsum term of Eq. (2).
 //
@@ -273,6 +261,9 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
         acc[mb][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf[nb], af[mb], acc[mb][nb], 0, 0, 0);
   };
   const int KT = (p.K + BK - 1) / BK;  // tiles that hold real data
+  // the pipelined loops run the KTF whole tiles; a ragged last tile (K % 64 bytes of A) is staged through
+  // registers afterwards, once per workgroup
+  const int KTF = p.K / BK;
   v4i a0[TM], b0[TN], a1[TM], b1[TN];
   if constexpr (PATH == PATH_ASM) {
     // Tile kt lives in stage kt % 4.  In iteration kt: the first k-step runs while the fragments of
@@ -335,7 +326,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
       for (int q = 0; q < B_DMA; ++q) dma16(bb + b_voff[q], st + A_STAGE + (wave * B_DMA + q) * 1024);
     };
     // this wave set's tiles are kg, kg + KS, ...: KTg of them, in KT2 common steps (sets share the barriers)
-    const int KTg = (KT - kg + KS - 1) / KS, KT2 = (KT + KS - 1) / KS;
+    const int KTg = (KTF - kg + KS - 1) / KS, KT2 = (KTF + KS - 1) / KS;
 #pragma unroll
     for (int t = 0; t < NS - 1; ++t)
       if (t < KTg) request(t * KS + kg, t);
@@ -369,29 +360,37 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
     };
     // the steps in which every set has a tile run unconditionally: a conditional MFMA inside the loop makes the
     // compiler copy the accumulators every iteration
-    const int KTall = KT / KS;
+    const int KTall = KTF / KS;
     for (int i = 0; i < KTall; ++i) step(i, true);
     if (KS > 1 && KT2 > KTall) step(KTall, KTall < KTg);
-  } else {
-    // General path: one stage, no overlap.  A goes through registers byte by byte with bounds checks;
-    // bytes past K are stored as 0x80 (int8 zero after the shift), rows past M repeat the last row.
-    for (int kt = 0; kt < KT; ++kt) {
-      const int k0 = kt * BK;
-      __syncthreads();
-#pragma unroll 1
+  }
+
+  // ---- ragged last tile of the pipelined paths: bytes past K are staged as 0x80 (int8 zero after the shift)
+  if (KTF < KT) {
+    const int k0 = KTF * BK;
+    __syncthreads();  // every wave is done with the stages
+    if (kg == 0) {
+      const size_t a_end = (size_t)(p.M - 1) * (size_t)p.lda + (size_t)p.K;  // one past the last byte A is known to have
+#pragma unroll
       for (int q = 0; q < A_DMA; ++q) {
         const int r = (wave * A_DMA + q) * 16 + (lane >> 2);
         const int kc = (lane & 3) ^ ((r >> 1) & 3);
-        const uint8_t* src = p.A + (size_t)min(m0 + r, p.M - 1) * p.lda + kc * 16 + k0;
+        const size_t off = (size_t)min(m0 + r, p.M - 1) * (size_t)p.lda + (size_t)(kc * 16 + k0);
         *reinterpret_cast<v4i*>(smem + (wave * A_DMA + q) * 1024 + lane * 16) =
-            load_a_chunk_slow(src, p.K - (k0 + kc * 16));
+            qg_load_a_chunk(p.A + off, p.K - (k0 + kc * 16), off + 16 <= a_end);
       }
-      const int8_t* b_base = b_tile0 + (size_t)kt * b_step;
+      const int8_t* b_base = b_tile0 + (size_t)KTF * b_step;
 #pragma unroll
       for (int q = 0; q < B_DMA; ++q)
         *reinterpret_cast<v4i*>(smem + A_STAGE + (wave * B_DMA + q) * 1024 + lane * 16) =
             *reinterpret_cast<const v4i*>(b_base + b_voff[q]);
-      __syncthreads();
+    }
+    __syncthreads();
+    if (kg == 0) {
+      if (CONV) {
+#pragma unroll
+        for (int mb = 0; mb < TM; ++mb) cv_ok[mb] = true;  // (a convolution has no ragged tile: Cin % 64 == 0)
+      }
       fetch(0, 0, a0, b0);
       fetch(0, 1, a1, b1);
       prep(a0);
@@ -565,7 +564,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
 template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, int KS = 1>
 hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
-  constexpr int STAGES = (PATH == PATH_ASM ? NSTAGE : (PATH == PATH_PIPE ? pipe_stages(TM * TN) : 1)) * KS;
+  constexpr int STAGES = (PATH == PATH_ASM ? NSTAGE : pipe_stages(TM * TN)) * KS;
   // the output pipeline's per-column constants (12 B per column) reuse the stage memory
   constexpr int SMEM = STAGES * (BM + BN) * BK > 12 * BN ? STAGES * (BM + BN) * BK : 12 * BN;
   const int tiles_m = (a.M + BM - 1) / BM;
@@ -624,9 +623,7 @@ hipError_t qg_launch_conv_dense(const qg_gemm_args& a, int kernel, hipStream_t s
 }
 
 hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, int kernel, hipStream_t s) {
-  // a.a_vec: A base and lda are multiples of 16 and every byte offset into A fits 32 bits
-  const bool pipe_ok = a.a_vec && (a.K % BK == 0);
-  if (!pipe_ok) return launch_cfg<PATH_GENERAL, 2, 2, 2, 2>(a, mode, s);
+  // any pointer, lda and K; every byte offset into A fits 32 bits (the caller splits larger matrices by rows)
   switch (kernel) {
     case QG_KERNEL_TILE64: return launch_cfg<PATH_PIPE, 2, 2, 1, 1, 2>(a, mode, s);  // two wave sets split K
     case QG_KERNEL_TILE128: return launch_cfg<PATH_PIPE, 2, 2, 2, 2>(a, mode, s);

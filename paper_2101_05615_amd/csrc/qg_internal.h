@@ -109,7 +109,7 @@ struct qg_gemm_args {
   int c_zp;
   float clamp_lo, clamp_hi;  // lo - theta_C, 255 - theta_C
   float relu_lo;         // dequant mode: 0 with ReLU, -inf without
-  int a_vec;             // A base and lda are multiples of 16
+  int a_vec;             // A base and lda are multiples of 16 (the streaming kernels keep a variant for that case)
   int c_vec;             // output base and row pitch are multiples of 16 bytes (uint8 output of the streaming kernels: 4)
   int has_bzp;           // some theta_B != 0: the row-offset term of Eq. (2) is needed
   const int32_t* sp_ptr;      // outlier split: per-bucket offsets, or null for a dense 8-bit B
@@ -140,6 +140,33 @@ struct qg_conv_args {
 };
 
 #ifdef __HIPCC__
+typedef int qg_v4i __attribute__((ext_vector_type(4)));
+typedef qg_v4i qg_v4i_unaligned __attribute__((aligned(1)));  // a 16-byte load from any address (one instruction)
+
+// 16 bytes of a row of A of which the first `kvalid` belong to the matrix; the rest reads as 0x80 (the int8
+// zero after the uint8 -> int8 shift).  `safe`: all 16 bytes lie inside the caller's buffer, so one vector
+// load and a byte mask do; otherwise byte by byte with bounds checks.  Any address.
+__device__ __forceinline__ qg_v4i qg_load_a_chunk(const uint8_t* p, int kvalid, bool safe) {
+  if (kvalid <= 0) return (qg_v4i){(int)0x80808080, (int)0x80808080, (int)0x80808080, (int)0x80808080};
+  if (!safe) {
+    union {
+      qg_v4i v;
+      uint8_t b[16];
+    } u;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) u.b[i] = (i < kvalid) ? p[i] : (uint8_t)0x80;
+    return u.v;
+  }
+  qg_v4i v = *reinterpret_cast<const qg_v4i_unaligned*>(p);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int nb = min(max(kvalid - 4 * j, 0), 4);  // valid bytes of this dword
+    const unsigned keep = nb == 4 ? 0xFFFFFFFFu : ((1u << (8 * nb)) - 1u);
+    v[j] = (int)(((unsigned)v[j] & keep) | (0x80808080u & ~keep));
+  }
+  return v;
+}
+
 // Requantization of one corrected int32 accumulator, the fixed fp32 sequence of the output pipeline
 // (paper Sec. 2.1, requantization remark): int32 -> fp32 (round to nearest even), ONE fp32 multiply,
 // round to nearest even, clamp in float (so the conversion back can never be out of range), add theta_C.

@@ -24,7 +24,7 @@ def assert_same(got, want, what):
 def dev_case(case, torch, dev, lda_pad=0, ldc_pad=0, a_off=0, c_off=0):
     """Upload a GemmCase; optional leading-dimension padding and byte offsets exercise the unaligned paths."""
     M, K, N = case.M, case.K, case.N
-    a_store = torch.zeros(M * (K + lda_pad) + a_off + 64, dtype=torch.uint8, device=dev)
+    a_store = torch.full((M * (K + lda_pad) + a_off + 64,), 0x5A, dtype=torch.uint8, device=dev)  # padding is garbage
     A = a_store[a_off:a_off + M * (K + lda_pad)].view(M, K + lda_pad)[:, :K]
     A.copy_(torch.from_numpy(case.A).to(dev))
     c_store = torch.full((M * (N + ldc_pad) + c_off + 64,), 0xEE, dtype=torch.uint8, device=dev)

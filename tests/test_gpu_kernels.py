@@ -89,6 +89,27 @@ def test_every_kernel_unaligned(env, kernel):
     assert_same(C.cpu().numpy(), want, f"{kernel} unaligned")
 
 
+@pytest.mark.parametrize("M,N,K,lda_pad", [(257, 130, 100, 12), (150, 200, 1000, 8), (70, 64, 37, 11),
+                                           (300, 260, 464, 0), (130, 96, 336, 16), (40, 48, 4, 12)])
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_every_kernel_ragged_k_on_aligned_rows(env, kernel, M, N, K, lda_pad):
+    """16-byte aligned rows with K % 64 != 0 (whole 16-byte chunks past K, a chunk cut by K, K below one tile):
+    the pipelined kernels run the whole tiles as usual and stage the ragged last tile with a byte mask."""
+    q, torch, dev, oracle = env
+    assert (K + lda_pad) % 16 == 0
+    say(f"kernel {kernel} ragged K {M}x{N}x{K} lda {K + lda_pad}")
+    c = wl.unsaturated(wl.random_gemm(7000 + M + K, M, N, K, per_channel=True, with_bias=True, wide_zp=True))
+    want = oracle_gemm(c, oracle)
+    A, B, bias, scales, C, _ = dev_case(c, torch, dev, lda_pad=lda_pad)
+    Bp = q.pack_b(B, c.b_zp)
+    q.gemm_u8s8_requant(A, c.a_zp, Bp, bias, scales, c.c_zp, c.relu, out=C, kernel=kernel)
+    acc, rs = q.gemm_u8s8_acc32(A, Bp, want_rowsum=True, kernel=kernel)
+    torch.cuda.synchronize()
+    assert_same(C.cpu().numpy(), want, f"{kernel} requant")
+    assert_same(acc.cpu().numpy(), oracle.acc32(c.A, c.B), f"{kernel} acc32")
+    assert_same(rs.cpu().numpy(), oracle.rowsum(c.A), f"{kernel} rowsum")
+
+
 def test_dispatch_rules_choose_the_kernel_and_never_the_result(env, cases):
     q, torch, dev, oracle = env
     shape = (300, 520, 1024)
