@@ -125,8 +125,8 @@ size_t qg_gemm_workspace_bytes(int M, const qg_packed_b* Bp);
  *   C_dev  dev, uint8, row-major M x N, ldc >= N; must not alias A
  * No alignment is required and K need not be a multiple of anything: A is staged
  * with 16-byte requests from any address, a last partial 64-deep slice of K with a
- * byte mask; a 16-byte aligned C_dev with ldc a multiple of 16 takes the vector
- * store path.  A may exceed 4 GiB: the kernels
+ * byte mask; C is written with 16-byte stores to any address, byte by byte only
+ * where N cuts a lane's 16 columns.  A may exceed 4 GiB: the kernels
  * address it with 32-bit offsets from a base, so the call then enqueues several
  * launches over consecutive row ranges.  Identical inputs give identical bytes
  * on every run. */

@@ -507,7 +507,11 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
             uint8_t* dst = p.C + (size_t)row * p.ldc + col;
             if (full_cols) {
               *reinterpret_cast<uint4*>(dst) = make_uint4(out[0], out[1], out[2], out[3]);
+            } else if (col + 16 <= p.N) {
+              // any address: one 16-byte store all the same
+              *reinterpret_cast<qg_v4i_unaligned*>(dst) = (v4i){(int)out[0], (int)out[1], (int)out[2], (int)out[3]};
             } else {
+              // the lanes whose 16 columns N cuts
 #pragma unroll
               for (int i = 0; i < 16; ++i)
                 if (col + i < p.N) dst[i] = (uint8_t)(out[i >> 2] >> ((i & 3) * 8));
@@ -527,6 +531,12 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
 #pragma unroll
               for (int q = 0; q < 4; ++q)
                 *reinterpret_cast<float4*>(dst + 4 * q) = make_float4(out[4 * q], out[4 * q + 1], out[4 * q + 2], out[4 * q + 3]);
+            } else if (col + 16 <= p.N) {
+#pragma unroll
+              for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<qg_v4i_unaligned*>(dst + 4 * q) =
+                    (v4i){__float_as_int(out[4 * q]), __float_as_int(out[4 * q + 1]), __float_as_int(out[4 * q + 2]),
+                          __float_as_int(out[4 * q + 3])};
             } else {
 #pragma unroll
               for (int i = 0; i < 16; ++i)
