@@ -148,7 +148,9 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
   // batch's weights (into `nxt`), then wait for the activations only.  Requests complete in order, so
   // "at most NLOAD outstanding" means that everything older than the next batch's weights has arrived.
   auto batch = [&](int kb, const v4i (&cur)[NLOAD], v4i (&nxt)[NLOAD], const bool has_next) {
-    const bool staged = a_vec && kb + BATCH <= kb_end && (kb + BATCH) * QG_FRAG_K <= p.K;
+    // whole rows of BATCH k blocks are requested even when the slice ends earlier: the surplus lies inside the
+    // row (it is the next wave's slice) and is simply not consumed
+    const bool staged = a_vec && (kb + BATCH) * QG_FRAG_K <= p.K;
     unsigned char* region = smem + wave * REGION;
     // outlier split: this batch's entries are one run; the first 64 are requested one per lane right behind the
     // activations (always exactly one request, clamped into the buffer, so that the wait below can count it)
