@@ -200,6 +200,18 @@ def main():
     roofline = {"bound": "mfma", "kernel": "qg_gemm_tile_kernel", "achieved": round(kern_tops, 2),
                 "peak": PEAK_INT8_TOPS, "unit": "TOP/s", "frac": round(kern_tops / PEAK_INT8_TOPS, 4),
                 "avg_launch_ms": round(dev_ms, 5), "traffic": traffic_from_profiles("qg_gemm_tile_kernel_c3")}
+    # per-launch spread: the same call with an event between consecutive launches (after the timed region, so that
+    # the figure above has no events inside it)
+    n_sp = min(args.steps, 100)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_sp + 1)]
+    evs[0].record()
+    for i in range(n_sp):
+        call3.launch()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    per = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(n_sp))
+    roofline["launch_ms_median"] = round(per[len(per) // 2], 5)
+    roofline["launch_ms_min"] = round(per[0], 5)
     # spot check of the timed output against the sampled property used in the tests: ReLU floor
     assert int(C.min().item()) >= c3.c_zp
     c3_unsat = unsaturated_frac(torch, C)
