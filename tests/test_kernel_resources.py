@@ -1,0 +1,43 @@
+"""Build-time guard for the hot kernels: no private memory.  The GEMM kernels keep their accumulator tiles in
+registers; a change that makes the compiler index them dynamically moves them to scratch memory and costs
+tens of per cent without failing any parity test.  hipcc reports the per-kernel resources while cross-compiling
+(no GPU needed)."""
+import os
+import re
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+sys.path.insert(0, ROOT)
+
+
+def _resources(src):
+    from paper_2101_05615_amd import build
+    flags = [f for f in build.FLAGS if f not in ("-shared",)]
+    cmd = ["hipcc"] + flags + ["--cuda-device-only", "-c", "-Rpass-analysis=kernel-resource-usage",
+                               os.path.join(build.CSRC, src), "-o", os.devnull]
+    err = subprocess.run(cmd, check=True, capture_output=True, text=True).stderr
+    out, name = {}, None
+    for line in err.splitlines():
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+            out[name] = {}
+        for key in ("ScratchSize [bytes/lane]", "VGPRs Spill", "SGPRs Spill"):
+            m = re.search(re.escape(key) + r": (\d+)", line)
+            if m and name:
+                out[name][key] = int(m.group(1))
+    return out
+
+
+@pytest.mark.timeout(600)
+def test_gemm_kernels_use_no_scratch_memory_and_spill_nothing():
+    with ThreadPoolExecutor(2) as ex:
+        tile, skinny = ex.map(_resources, ["gemm_tile.hip", "gemm_skinny.hip"])
+    assert len(tile) >= 30 and len(skinny) >= 30, "the resource report was not parsed"
+    for name, r in {**tile, **skinny}.items():
+        assert r.get("ScratchSize [bytes/lane]") == 0, f"{name} uses scratch memory: {r}"
+        assert r.get("VGPRs Spill") == 0 and r.get("SGPRs Spill") == 0, f"{name} spills registers: {r}"
