@@ -169,3 +169,13 @@ def test_dispatch_rule_table(lib):
     finally:
         q.dispatch_set_rules([])
     assert q.kernel_select(500, 500, 512) == before
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build shows one GPU's share; bench.py says so and exits before touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
