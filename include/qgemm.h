@@ -152,11 +152,9 @@ int qg_gemm_u8s8_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* 
  *                   rows, K split over the waves of the workgroup; B streams from
  *                   HBM straight into operand registers (bandwidth-bound shapes)
  *   TILE64          64 x 64 workgroup tile, three LDS stages, K split over two wave sets
- *   TILE128         128 x 128
- *   TILE128X256     128 x 256
+ *   TILE128         128 x 128, four LDS stages, hand-scheduled loop (K >= 256; else like TILE128X256)
+ *   TILE128X256     128 x 256, three LDS stages, compiler-scheduled loop
  *   TILE256         256 x 256, four LDS stages, hand-scheduled loop (large shapes)
- *   TILE128K2       128 x 128 with K split over two wave sets like TILE64 (grids of
- *                   128 x 128 tiles that leave compute units idle and have a long K)
  *   TILE64K4        64 x 64 with K split over four wave sets (1024 threads; a few
  *                   tiles and a long K)
  * QG_KERNEL_AUTO picks by (M, N, K): first the rules installed with
@@ -170,9 +168,8 @@ int qg_gemm_u8s8_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* 
 #define QG_KERNEL_TILE128 5
 #define QG_KERNEL_TILE128X256 6
 #define QG_KERNEL_TILE256 7
-#define QG_KERNEL_TILE128K2 8
-#define QG_KERNEL_TILE64K4 9
-#define QG_KERNEL_LAST 9
+#define QG_KERNEL_TILE64K4 8
+#define QG_KERNEL_LAST 8
 
 /* Name of a kernel id ("skinny16", "tile128x256", ...; "auto" for 0), NULL if invalid. */
 const char* qg_kernel_name(int kernel);

@@ -75,10 +75,9 @@ struct stream_cost {
 };
 const tile_cost k_tile_cost[] = {
     {QG_KERNEL_TILE64, 64, 64, 3.27, 0.141, 0.103, 0.64},
-    {QG_KERNEL_TILE128, 128, 128, 3.9, 0.357, 0.295, 0.94},
+    {QG_KERNEL_TILE128, 128, 128, 4.27, 0.226, 0.2445, 1.48},
     {QG_KERNEL_TILE128X256, 128, 256, 5.5, 0.527, 0.514, 2.07},
     {QG_KERNEL_TILE256, 256, 256, 8.7, 0.524, 0.838, 6.87},
-    {QG_KERNEL_TILE128K2, 128, 128, 4.4, 0.273, 0.34, 2.0},
     {QG_KERNEL_TILE64K4, 64, 64, 4.15, 0.089, 0.103, 2.1},
 };
 const stream_cost k_stream_cost[] = {
@@ -208,7 +207,7 @@ extern "C" {
 const char* qg_kernel_name(int kernel) {
   static const char* const names[] = {"auto",   "skinny16", "skinny32",    "skinny64",
                                       "tile64", "tile128",  "tile128x256", "tile256",
-                                      "tile128k2", "tile64k4"};
+                                      "tile64k4"};
   return (kernel >= 0 && kernel <= QG_KERNEL_LAST) ? names[kernel] : nullptr;
 }
 
@@ -643,7 +642,7 @@ int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int
   int kernel = QG_KERNEL_TILE64;
   double best_us = 1e300;
   for (const tile_cost& c : k_tile_cost) {
-    if (c.kernel == QG_KERNEL_TILE256 || c.kernel == QG_KERNEL_TILE128K2 || c.kernel == QG_KERNEL_TILE64K4) continue;
+    if (c.kernel == QG_KERNEL_TILE256 || c.kernel == QG_KERNEL_TILE64K4) continue;
     const double us = tile_estimate(c, a.M, a.N, a.K);
     if (us < best_us) best_us = us, kernel = c.kernel;
   }

@@ -23,11 +23,11 @@
 // permutation makes those columns consecutive.
 //
 // One template, a family of tile shapes (Appendix C: a few shape-specific kernels, every
-// problem mapped to one of them): 256 x 256 with a hand-scheduled four-stage loop for the
-// large compute-bound shapes, and 128 x 256, 128 x 128 and 64 x 64 with a compiler-scheduled
-// three-stage loop, several workgroups per CU, for shapes that would leave most CUs idle
-// (or run a single, unoverlapped round) at 256 x 256.  The 64 x 64 workgroup has two sets of four waves
-// that take alternate k tiles and add their accumulators at the end.
+// problem mapped to one of them): 256 x 256 and 128 x 128 with a hand-scheduled four-stage loop (one
+// generator, two register tiles), and 128 x 256 and 64 x 64 with a compiler-scheduled three-stage loop,
+// several workgroups per CU, for shapes that would leave most CUs idle (or run a single, unoverlapped
+// round) at 256 x 256.  The 64 x 64 workgroup has two or four sets of four waves that take alternate
+// k tiles and add their accumulators at the end.
 #include "qg_internal.h"
 #include <type_traits>
 #include "tile_loop_asm.inc"
@@ -88,9 +88,17 @@ __device__ __forceinline__ int a_lds_off(int r, int kc) { return r * BK + ((kc ^
                    [c12] "+a"(acc[3][0]), [c13] "+a"(acc[3][1]), [c14] "+a"(acc[3][2]), [c15] "+a"(acc[3][3]), \
                    [rs01] "=v"(rs01), [rs23] "=v"(rs23) \
                  : [av01] "v"(av01), [av23] "v"(av23), [bv01] "v"(bv01), [bv23] "v"(bv23), [ard] "v"(ard), \
-                   [brd] "v"(brd), [aptr] "s"(p.A - 3072), [bptr] "s"(b_tile0), [kt] "s"(KTF), [ldsdma] "s"(lds_dma), \
+                   [brd] "v"(brd), [aptr] "s"(p.A - (A_DMA - 1) * 1024), [bptr] "s"(b_tile0), [kt] "s"(KTF), [ldsdma] "s"(lds_dma), \
                    [lds] "s"(lds_base), [bstep] "s"(b_step) \
                  : QG_TILE_LOOP_CLOBBERS
+
+#define QG_TILE_LOOP_OPERANDS_2X2 \
+                 : [c0] "+a"(acc[0][0]), [c1] "+a"(acc[0][1]), [c2] "+a"(acc[1][0]), [c3] "+a"(acc[1][1]), \
+                   [rs01] "=v"(rs01) \
+                 : [av01] "v"(av01), [bv01] "v"(bv01), [ard] "v"(ard), [brd] "v"(brd), \
+                   [aptr] "s"(p.A - (A_DMA - 1) * 1024), [bptr] "s"(b_tile0), [kt] "s"(KTF), [ldsdma] "s"(lds_dma), \
+                   [lds] "s"(lds_base), [bstep] "s"(b_step) \
+                 : QG_TILE_LOOP_CLOBBERS_2X2
 
 // NWM x NWN waves, each TM x TN blocks of 32 x 32.
 // Both loops take any pointer, lda and K (PATH_ASM: K >= 256): every whole 64-deep tile is requested with
@@ -103,7 +111,8 @@ __device__ __forceinline__ int a_lds_off(int r, int kc) { return r * BK + ((kc ^
 // accumulator registers); the compiler-scheduled shapes rely on neighbours to hide latency, as many as
 // their LDS stages allow (72 / 48 / 24 KB per workgroup).
 constexpr int min_wg_per_cu(int path, int blocks) {
-  return path != PATH_PIPE ? 1 : (blocks >= 8 ? 2 : (blocks >= 4 ? 3 : 4));
+  if (path != PATH_PIPE) return blocks >= 16 ? 1 : 2;  // hand-scheduled: 128 / 64 KiB of LDS stages
+  return blocks >= 8 ? 2 : (blocks >= 4 ? 3 : 4);
 }
 
 // CONV (PATH_PIPE only): dense convolution with the im2col folded into the addressing.  Row m of "A" is
@@ -175,8 +184,8 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
       continue;
     }
     // hand-scheduled loop: it uses instruction offset q*1024 (it moves the LDS slot AND the global address, so one
-    // M0 serves a group of requests) against a base of A - 3072; the per-lane offset absorbs the difference
-    a_voff[q] = (unsigned)rg * (unsigned)p.lda + kc * 16 + (PATH == PATH_ASM ? (3 - q) * 1024 : 0);
+    // M0 serves a group of requests) against a base of A - (A_DMA-1) KiB; the per-lane offset absorbs the difference
+    a_voff[q] = (unsigned)rg * (unsigned)p.lda + kc * 16 + (PATH == PATH_ASM ? (A_DMA - 1 - q) * 1024 : 0);
   }
 #pragma unroll
   for (int q = 0; q < B_DMA; ++q)
@@ -273,25 +282,33 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
     // second k-step runs while the first fragments of tile kt+1 are fetched.  The loop is one
     // hand-scheduled asm statement (gen_tile_loop.py): behind every MFMA sit at most seven other
     // instructions, so LDS reads, row sums, shifts and tile requests issue in the MFMA's shadow.
-    static_assert(PATH != PATH_ASM || (NWM == 2 && NWN == 2 && TM == 4 && TN == 4 && BK == 64 && NSTAGE == 4),
-                  "the scheduled loop is written for this configuration");
+    static_assert(PATH != PATH_ASM || (NWM == 2 && NWN == 2 && TM == TN && (TM == 4 || TM == 2) && BK == 64 && NSTAGE == 4),
+                  "the scheduled loop is generated for these configurations");
     const unsigned long long av01 = a_voff[0] | ((unsigned long long)a_voff[1] << 32);
-    const unsigned long long av23 = a_voff[2] | ((unsigned long long)a_voff[3] << 32);
     const unsigned long long bv01 = b_voff[0] | ((unsigned long long)b_voff[1] << 32);
-    const unsigned long long bv23 = b_voff[2] | ((unsigned long long)b_voff[3] << 32);
     const unsigned long long ard = (unsigned)a_rd[0] | ((unsigned long long)(unsigned)a_rd[1] << 32);
     const unsigned long long brd = (unsigned)b_rd;
     const unsigned lds_base = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)smem);
     const unsigned lds_dma = lds_base + wave * (A_DMA * 1024);
-    unsigned long long rs01, rs23;
-    if (ROWSUM)
-      asm volatile(QG_TILE_LOOP_ASM QG_TILE_LOOP_OPERANDS);
-    else
-      asm volatile(QG_TILE_LOOP_ASM_NOROWSUM QG_TILE_LOOP_OPERANDS);
+    unsigned long long rs01;
+    if constexpr (TM == 4) {
+      const unsigned long long av23 = a_voff[2] | ((unsigned long long)a_voff[3] << 32);
+      const unsigned long long bv23 = b_voff[2] | ((unsigned long long)b_voff[3] << 32);
+      unsigned long long rs23;
+      if (ROWSUM)
+        asm volatile(QG_TILE_LOOP_ASM QG_TILE_LOOP_OPERANDS);
+      else
+        asm volatile(QG_TILE_LOOP_ASM_NOROWSUM QG_TILE_LOOP_OPERANDS);
+      rs[2] = (unsigned)rs23;
+      rs[3] = (unsigned)(rs23 >> 32);
+    } else {
+      if (ROWSUM)
+        asm volatile(QG_TILE_LOOP_ASM_2X2 QG_TILE_LOOP_OPERANDS_2X2);
+      else
+        asm volatile(QG_TILE_LOOP_ASM_NOROWSUM_2X2 QG_TILE_LOOP_OPERANDS_2X2);
+    }
     rs[0] = (unsigned)rs01;
     rs[1] = (unsigned)(rs01 >> 32);
-    rs[2] = (unsigned)rs23;
-    rs[3] = (unsigned)(rs23 >> 32);
   } else if constexpr (PATH == PATH_PIPE) {
     // Tile kt lives in stage kt % NS; NS-2 tiles are in flight behind the one being consumed.  At the top of
     // iteration kt a wave waits until ITS requests for tile kt have landed (younger ones may still be in
@@ -636,9 +653,10 @@ hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, int kernel, hipS
   // any pointer, lda and K; every byte offset into A fits 32 bits (the caller splits larger matrices by rows)
   switch (kernel) {
     case QG_KERNEL_TILE64: return launch_cfg<PATH_PIPE, 2, 2, 1, 1, 2>(a, mode, s);  // two wave sets split K
-    case QG_KERNEL_TILE128: return launch_cfg<PATH_PIPE, 2, 2, 2, 2>(a, mode, s);
+    case QG_KERNEL_TILE128:
+      if (a.K >= NSTAGE * BK) return launch_cfg<PATH_ASM, 2, 2, 2, 2>(a, mode, s);
+      return launch_cfg<PATH_PIPE, 2, 2, 2, 2>(a, mode, s);
     case QG_KERNEL_TILE128X256: return launch_cfg<PATH_PIPE, 2, 2, 2, 4>(a, mode, s);
-    case QG_KERNEL_TILE128K2: return launch_cfg<PATH_PIPE, 2, 2, 2, 2, 2>(a, mode, s);
     case QG_KERNEL_TILE64K4: return launch_cfg<PATH_PIPE, 2, 2, 1, 1, 4>(a, mode, s);
     case QG_KERNEL_TILE256:
       if (a.K >= NSTAGE * BK) return launch_cfg<PATH_ASM, 2, 2, 4, 4>(a, mode, s);

@@ -20,17 +20,40 @@ Fixed register plan (all clobbered by the asm statement):
   stage bases (current / next), s94/s95 temporaries
 Operands: 16 accumulators c0..c15 ("+a", acc[mb][nb] = c{4*mb+nb}), packed 64-bit VGPR inputs
 av01 av23 bv01 bv23 ard brd, SGPR inputs aptr bptr kt ldsdma lds bstep, 64-bit VGPR outputs rs01 rs23.
+
+Two configurations are generated from the same schedule: TM x TN = 4 x 4 blocks per wave (256 x 256 workgroup
+tile, the plan above) and 2 x 2 (128 x 128 tile: 4 accumulators c0..c3, inputs av01 bv01 ard brd, output rs01,
+fixed registers from v96, 16 KiB stages).  With only four MFMAs per k-step the LDS reads sit behind the first
+two and the row sums and shifts of both A fragments behind the last two.
 """
 import os
 
 ABL = set(filter(None, os.environ.get("QG_GEN_ABL", "").split(",")))
 
-A = [160, 192]
-B = [176, 208]
-RS, AV, BV, ARD0, ARD1, BRD, VA, VB = 224, 228, 232, 236, 237, 238, 240, 241
-STAGE_BYTES = 32768      # A 256x64 + B 256x64
-A_STAGE = 16384
-N_DMA = 8                # tile requests per wave per tile
+def configure(tm, tn):
+    """sets the module-level plan for TM x TN blocks of 32 x 32 per wave (2 x 2 waves per workgroup)"""
+    global TM, TN, NM, A, B, RS, AV, BV, ARD0, ARD1, BRD, VA, VB, STAGE_BYTES, A_STAGE, A_DMA, N_DMA, NREAD, RSLOTS
+    global FIRST_VGPR, LAST_VGPR
+    assert tm == tn and tm in (2, 4), "the request addressing assumes as many A as B requests per wave"
+    TM, TN, NM = tm, tn, tm * tn
+    base = 160 if tm == 4 else 96
+    A = [base, base + 4 * (tm + tn)]
+    B = [base + 4 * tm, base + 4 * (tm + tn) + 4 * tm]
+    RS = base + 8 * (tm + tn)                       # TM row-sum accumulators
+    AV = RS + 4                                     # per-lane offsets of the A requests
+    BV = AV + 4                                     # ... of the B requests (only the first is used: B is contiguous)
+    ARD0, ARD1, BRD = BV + 4, BV + 5, BV + 6        # BRD is moved as a 64-bit pair
+    VA, VB = BV + 8, BV + 9
+    FIRST_VGPR, LAST_VGPR = base, 255 if tm == 4 else VB
+    A_STAGE = tm * 4096                             # 64 * TM rows of 64 bytes
+    STAGE_BYTES = (tm + tn) * 4096
+    A_DMA = tm                                      # 1 KiB requests per wave and tile: A, then as many for B
+    N_DMA = tm + tn
+    NREAD = tm + tn                                 # LDS reads per k-step
+    RSLOTS = (NREAD + 1) // 2                       # slots that carry them, two each
+
+
+configure(4, 4)
 
 
 def vr(base, n=4):
@@ -49,31 +72,31 @@ class Emit:
 
 
 def dma(e, q):
-    """one tile request: q = 0..3 A, 4..7 B; m0 = request stage base + slot"""
+    """one tile request: q = 0..A_DMA-1 A, then B; m0 = request stage base + slot"""
     if "nodma" in ABL:
         return
     if "m0each" in ABL:
-        if q < 4:
+        if q < A_DMA:
             e(f"s_add_u32 m0, s96, {q * 1024}")
             e("s_nop 0")
             e(f"global_load_lds_dwordx4 v{AV + q}, s[86:87]")
         else:
-            e(f"s_add_u32 m0, s96, {A_STAGE + (q - 4) * 1024}")
+            e(f"s_add_u32 m0, s96, {A_STAGE + (q - A_DMA) * 1024}")
             e("s_nop 0")
-            e(f"global_load_lds_dwordx4 v{BV + q - 4}, s[88:89]")
+            e(f"global_load_lds_dwordx4 v{BV + q - A_DMA}, s[88:89]")
         return
     # The instruction offset is added to the global address AND to the LDS address, so one M0 value serves the
     # four requests of a group; the per-lane A offsets come in pre-biased by -q*1024 (B is contiguous anyway).
     if q == 0:
         e("s_mov_b32 m0, s96")
         e("s_nop 0")
-    if q == 4:
+    if q == A_DMA:
         e(f"s_add_u32 m0, s96, {A_STAGE}")
         e("s_nop 0")
-    if q < 4:
+    if q < A_DMA:
         e(f"global_load_lds_dwordx4 v{AV + q}, s[86:87]" + (f" offset:{q * 1024}" if q else ""))
     else:
-        e(f"global_load_lds_dwordx4 v{BV}, s[88:89]" + (f" offset:{(q - 4) * 1024}" if q > 4 else ""))
+        e(f"global_load_lds_dwordx4 v{BV}, s[88:89]" + (f" offset:{(q - A_DMA) * 1024}" if q > A_DMA else ""))
 
 
 def advance_request_pointers(e):
@@ -84,57 +107,66 @@ def advance_request_pointers(e):
 
 
 def mfma(e, i, use):
-    mb, nb = i // 4, i % 4
+    mb, nb = i // TN, i % TN
     if "nomfma" in ABL:
         return
     e(f"v_mfma_i32_32x32x32_i8 %[c{i}], {vr(B[use] + 4 * nb)}, {vr(A[use] + 4 * mb)}, %[c{i}]")
 
 
 def reads(e, slot, ld, ks):
-    """the two LDS reads of slot 0..3: A fragments first (they are needed first), then B"""
+    """the two LDS reads of slot 0..RSLOTS-1: A fragments first (they are needed first), then B"""
     for j in (2 * slot, 2 * slot + 1):
-        if "nolds" in ABL:
+        if "nolds" in ABL or j >= NREAD:
             continue
-        if j < 4:
+        if j < TM:
             e(f"ds_read_b128 {vr(A[ld] + 4 * j)}, v{VA} offset:{j * 2048}")
         else:
-            nb = j - 4
+            nb = j - TM
             e(f"ds_read_b128 {vr(B[ld] + 4 * nb)}, v{VB} offset:{nb * 2048 + ks * 512}")
 
 
 ROWSUM = True  # False: variant for weights whose zero points are all 0 (no row offsets needed)
 
 
+def prep_slots():
+    """(first slot, slots per A fragment) of the row-sum / shift work of a k-step: the last 2*TM slots with the
+    byte sums and the xor of a fragment in separate slots, or -- when the reads leave fewer -- the last TM slots
+    with both in one"""
+    per = 2 if NM - RSLOTS >= 2 * TM else 1
+    return NM - per * TM, per
+
+
 def prep(e, slot, ld):
-    """slots 8..15: fragment f = (slot-8)//2; even slot: byte sums, odd slot: xor"""
-    f, odd = (slot - 8) // 2, (slot - 8) % 2
+    """fragment f = (slot - first) // per; two slots per fragment: byte sums, then xor; one slot: both"""
+    first, per = prep_slots()
+    f, part = (slot - first) // per, (slot - first) % per
     if "novalu" in ABL:
         return
     base = A[ld] + 4 * f
-    if not odd:
-        e(f"s_waitcnt lgkmcnt({7 - f})")
+    if part == 0:
+        e(f"s_waitcnt lgkmcnt({NREAD - 1 - f})")
         for c in range(4):
             if ROWSUM:
                 e(f"v_sad_u8 v{RS + f}, v{base + c}, 0, v{RS + f}")
-    else:
+    if part == per - 1:
         for c in range(4):
             e(f"v_xor_b32 v{base + c}, s84, v{base + c}")
 
 
 def step(e, use, ks_load, request, next_va, load=True):
-    """16 MFMAs on fragment set `use`; meanwhile fetch the next k-step's fragments into the other set
-    (k-step ks_load of the stage v240/v241 point at), row-sum and shift its A fragments, and optionally
-    issue the 8 tile requests.  next_va: which A offset (0/1) the NEXT step's reads use."""
+    """TM*TN MFMAs on fragment set `use`; meanwhile fetch the next k-step's fragments into the other set
+    (k-step ks_load of the stage VA/VB point at), row-sum and shift its A fragments, and optionally
+    issue the tile requests.  next_va: which A offset (0/1) the NEXT step's reads use."""
     ld = 1 - use
-    for slot in range(16):
+    for slot in range(NM):
         mfma(e, slot, use)
-        if load and slot < 4:
+        if load and slot < RSLOTS:
             reads(e, slot, ld, ks_load)
-        if request and slot < 8:
+        if request and slot < N_DMA:
             dma(e, slot)
-        if load and slot >= 8:
+        if load and slot >= prep_slots()[0]:
             prep(e, slot, ld)
-        if slot == 5 and next_va is not None:
+        if slot == RSLOTS + 1 and next_va is not None:
             # all reads of this step are issued: point v240/v241 at the next step's fragments
             e(f"v_add_u32 v{VA}, s98, v{ARD0 if next_va == 0 else ARD1}")
             if next_va == 0:
@@ -148,7 +180,7 @@ def rotate_stage(e):
     e("s_mov_b32 s97, s98")
     e("s_add_u32 s94, s93, 1")
     e("s_and_b32 s94, s94, 3")
-    e("s_lshl_b32 s94, s94, 15")
+    e(f"s_lshl_b32 s94, s94, {STAGE_BYTES.bit_length() - 1}")
     e("s_add_u32 s98, s92, s94")
 
 
@@ -164,7 +196,7 @@ def tile(e, wait_vm, request, last=False):
     if "nobar" not in ABL:
         e("s_barrier")
     if request:
-        e("s_lshl_b32 s94, s93, 15")
+        e(f"s_lshl_b32 s94, s93, {STAGE_BYTES.bit_length() - 1}")
         e("s_add_u32 s96, s91, s94")
     # k-step 1 of tile t: consume set 1, fetch (t+1, 0) into set 0 from the next stage
     step(e, use=1, ks_load=0, request=request, next_va=1)
@@ -180,9 +212,11 @@ def generate_loop(rowsum):
     e = Emit()
     # ---- unpack operands into the fixed registers
     e(f"v_mov_b64 v[{AV}:{AV + 1}], %[av01]")
-    e(f"v_mov_b64 v[{AV + 2}:{AV + 3}], %[av23]")
+    if TM == 4:
+        e(f"v_mov_b64 v[{AV + 2}:{AV + 3}], %[av23]")
     e(f"v_mov_b64 v[{BV}:{BV + 1}], %[bv01]")
-    e(f"v_mov_b64 v[{BV + 2}:{BV + 3}], %[bv23]")
+    if TM == 4:
+        e(f"v_mov_b64 v[{BV + 2}:{BV + 3}], %[bv23]")
     e(f"v_mov_b64 v[{ARD0}:{ARD1}], %[ard]")
     e(f"v_mov_b64 v[{BRD}:{BRD + 1}], %[brd]")
     e("s_mov_b32 s84, 0x80808080")
@@ -192,7 +226,7 @@ def generate_loop(rowsum):
     e("s_mov_b32 s91, %[ldsdma]")
     e("s_mov_b32 s92, %[lds]")
     e("s_mov_b32 s99, %[bstep]")
-    for f in range(4):
+    for f in range(TM):
         e(f"v_mov_b32 v{RS + f}, 0")
     # ---- request tiles 0..3 into stages 0..3
     for st in range(4):
@@ -208,10 +242,10 @@ def generate_loop(rowsum):
     # ---- fragments (0, 0) into set 0
     e(f"v_add_u32 v{VA}, s97, v{ARD0}")
     e(f"v_add_u32 v{VB}, s97, v{BRD}")
-    for slot in range(4):
+    for slot in range(RSLOTS):
         reads(e, slot, 0, 0)
-    for f in range(4):
-        e(f"s_waitcnt lgkmcnt({7 - f})")
+    for f in range(TM):
+        e(f"s_waitcnt lgkmcnt({NREAD - 1 - f})")
         for c in range(4):
             if ROWSUM:
                 e(f"v_sad_u8 v{RS + f}, v{A[0] + 4 * f + c}, 0, v{RS + f}")
@@ -239,18 +273,22 @@ def generate_loop(rowsum):
     e("s_nop 15")
     e("s_nop 15")
     e(f"v_mov_b64 %[rs01], v[{RS}:{RS + 1}]")
-    e(f"v_mov_b64 %[rs23], v[{RS + 2}:{RS + 3}]")
+    if TM == 4:
+        e(f"v_mov_b64 %[rs23], v[{RS + 2}:{RS + 3}]")
     return e.lines
 
 
 def generate():
-    clob = [f'"v{i}"' for i in range(160, 256)] + [f'"s{i}"' for i in range(84, 100)] + \
-           ['"scc"', '"memory"']
     out = "// GENERATED by gen_tile_loop.py -- do not edit.\n"
-    for name, rowsum in (("QG_TILE_LOOP_ASM", True), ("QG_TILE_LOOP_ASM_NOROWSUM", False)):
-        out += (f"#define {name} \\\n" +
-                "".join(f'  "{l}\\n" \\\n' for l in generate_loop(rowsum)) + "  \"\"\n")
-    out += "#define QG_TILE_LOOP_CLOBBERS " + ", ".join(clob) + "\n"
+    for tm, suffix in ((4, ""), (2, "_2X2")):
+        configure(tm, tm)
+        clob = [f'"v{i}"' for i in range(FIRST_VGPR, LAST_VGPR + 1)] + [f'"s{i}"' for i in range(84, 100)] + \
+               ['"scc"', '"memory"']
+        for name, rowsum in (("QG_TILE_LOOP_ASM", True), ("QG_TILE_LOOP_ASM_NOROWSUM", False)):
+            out += (f"#define {name}{suffix} \\\n" +
+                    "".join(f'  "{l}\\n" \\\n' for l in generate_loop(rowsum)) + "  \"\"\n")
+        out += f"#define QG_TILE_LOOP_CLOBBERS{suffix} " + ", ".join(clob) + "\n"
+    configure(4, 4)
     return out
 
 

@@ -86,8 +86,8 @@ def test_dense_conv_layers_at_batch_32(env, H, C):
 
 @pytest.mark.parametrize("shape,kernels", [
     ((128, 4096, 4096), ["auto", "tile64", "tile64k4", "skinny64"]),
-    ((2048, 2048, 2048), ["auto", "tile128", "tile128k2"]),
-    ((4096, 1024, 1024), ["auto", "tile128k2", "tile128x256"]),
+    ((2048, 2048, 2048), ["auto", "tile128", "tile128x256"]),
+    ((4096, 1024, 1024), ["auto", "tile128", "tile256"]),
     ((16384, 256, 512), ["auto", "tile64", "tile256"]),
 ])
 def test_kernel_family_at_the_benchmark_shapes(env, shape, kernels):
