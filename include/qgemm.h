@@ -153,7 +153,7 @@ int qg_gemm_u8s8_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* 
  *                   HBM straight into operand registers (bandwidth-bound shapes)
  *   TILE64          64 x 64 workgroup tile, three LDS stages, K split over two wave sets
  *   TILE128         128 x 128, four LDS stages, hand-scheduled loop (K >= 256; else like TILE128X256)
- *   TILE128X256     128 x 256, three LDS stages, compiler-scheduled loop
+ *   TILE128X256     128 x 256, three LDS stages, hand-scheduled loop, two workgroups per CU (K >= 192)
  *   TILE256         256 x 256, four LDS stages, hand-scheduled loop (large shapes)
  *   TILE64K4        64 x 64 with K split over four wave sets (1024 threads; a few
  *                   tiles and a long K)

@@ -75,9 +75,9 @@ struct stream_cost {
 };
 const tile_cost k_tile_cost[] = {
     {QG_KERNEL_TILE64, 64, 64, 3.27, 0.141, 0.103, 0.64},
-    {QG_KERNEL_TILE128, 128, 128, 4.27, 0.226, 0.2445, 1.48},
-    {QG_KERNEL_TILE128X256, 128, 256, 5.5, 0.527, 0.514, 2.07},
-    {QG_KERNEL_TILE256, 256, 256, 8.7, 0.524, 0.838, 6.87},
+    {QG_KERNEL_TILE128, 128, 128, 4.25, 0.226, 0.251, 1.38},
+    {QG_KERNEL_TILE128X256, 128, 256, 6.35, 0.344, 0.398, 2.85},
+    {QG_KERNEL_TILE256, 256, 256, 9.9, 0.632, 0.76, 8.21},
     {QG_KERNEL_TILE64K4, 64, 64, 4.15, 0.089, 0.103, 2.1},
 };
 const stream_cost k_stream_cost[] = {

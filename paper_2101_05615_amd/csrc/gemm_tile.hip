@@ -23,11 +23,12 @@
 // permutation makes those columns consecutive.
 //
 // One template, a family of tile shapes (Appendix C: a few shape-specific kernels, every
-// problem mapped to one of them): 256 x 256 and 128 x 128 with a hand-scheduled four-stage loop (one
-// generator, two register tiles), and 128 x 256 and 64 x 64 with a compiler-scheduled three-stage loop,
-// several workgroups per CU, for shapes that would leave most CUs idle (or run a single, unoverlapped
-// round) at 256 x 256.  The 64 x 64 workgroup has two or four sets of four waves that take alternate
-// k tiles and add their accumulators at the end.
+// problem mapped to one of them): 256 x 256, 128 x 256 and 128 x 128 with a hand-scheduled loop (one
+// generator, three register tiles; four LDS stages, three for 128 x 256 so that two workgroups share a CU),
+// and 64 x 64 with a compiler-scheduled three-stage loop, several workgroups per CU, for shapes that would
+// leave most CUs idle at the larger tiles; the compiler-scheduled loop also serves the dense convolution and
+// K below the pipeline depth of the hand-scheduled one.  The 64 x 64 workgroup has two or four sets of four
+// waves that take alternate k tiles and add their accumulators at the end.
 #include "qg_internal.h"
 #include <type_traits>
 #include "tile_loop_asm.inc"
@@ -39,6 +40,8 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 64;      // k extent of one LDS stage = one packed fragment deep
 constexpr int NSTAGE = 4;   // LDS stages of the hand-scheduled loop: three tiles in flight behind the one being consumed
+// (three stages, two tiles in flight, for the 128 x 256 tile, so that two workgroups fit the LDS of a CU)
+constexpr int asm_stages(int blocks) { return blocks == 8 ? 3 : NSTAGE; }
 // LDS stages of the compiler-scheduled loop, by 32 x 32 blocks per wave.  Three everywhere: measured with 3 to 8
 // stages, a thin grid's k step (0.28 us at 64 x 64) does not get shorter with more tiles in flight -- it is the
 // barrier / LDS read / MFMA chain of a lone workgroup -- while deeper buffers cost occupancy on full grids.
@@ -99,6 +102,15 @@ __device__ __forceinline__ int a_lds_off(int r, int kc) { return r * BK + ((kc ^
                    [aptr] "s"(p.A - (A_DMA - 1) * 1024), [bptr] "s"(b_tile0), [kt] "s"(KTF), [ldsdma] "s"(lds_dma), \
                    [lds] "s"(lds_base), [bstep] "s"(b_step) \
                  : QG_TILE_LOOP_CLOBBERS_2X2
+
+#define QG_TILE_LOOP_OPERANDS_2X4 \
+                 : [c0] "+a"(acc[0][0]), [c1] "+a"(acc[0][1]), [c2] "+a"(acc[0][2]), [c3] "+a"(acc[0][3]), \
+                   [c4] "+a"(acc[1][0]), [c5] "+a"(acc[1][1]), [c6] "+a"(acc[1][2]), [c7] "+a"(acc[1][3]), \
+                   [rs01] "=v"(rs01) \
+                 : [av01] "v"(av01), [bv01] "v"(bv01), [ard] "v"(ard), [brd] "v"(brd), \
+                   [aptr] "s"(p.A - (A_DMA - 1) * 1024), [bptr] "s"(b_tile0), [kt] "s"(KTF), [ldsdma] "s"(lds_dma), \
+                   [lds] "s"(lds_base), [bstep] "s"(b_step), [bofs] "s"(A_STAGE + wave * ((B_DMA - A_DMA) * 1024)) \
+                 : QG_TILE_LOOP_CLOBBERS_2X4
 
 // NWM x NWN waves, each TM x TN blocks of 32 x 32.
 // Both loops take any pointer, lda and K (PATH_ASM: K >= 256): every whole 64-deep tile is requested with
@@ -282,7 +294,8 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
     // second k-step runs while the first fragments of tile kt+1 are fetched.  The loop is one
     // hand-scheduled asm statement (gen_tile_loop.py): behind every MFMA sit at most seven other
     // instructions, so LDS reads, row sums, shifts and tile requests issue in the MFMA's shadow.
-    static_assert(PATH != PATH_ASM || (NWM == 2 && NWN == 2 && TM == TN && (TM == 4 || TM == 2) && BK == 64 && NSTAGE == 4),
+    static_assert(PATH != PATH_ASM || (NWM == 2 && NWN == 2 && BK == 64 && NSTAGE == 4 &&
+                                       ((TM == 4 && TN == 4) || (TM == 2 && TN == 2) || (TM == 2 && TN == 4))),
                   "the scheduled loop is generated for these configurations");
     const unsigned long long av01 = a_voff[0] | ((unsigned long long)a_voff[1] << 32);
     const unsigned long long bv01 = b_voff[0] | ((unsigned long long)b_voff[1] << 32);
@@ -301,11 +314,16 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
         asm volatile(QG_TILE_LOOP_ASM_NOROWSUM QG_TILE_LOOP_OPERANDS);
       rs[2] = (unsigned)rs23;
       rs[3] = (unsigned)(rs23 >> 32);
-    } else {
+    } else if constexpr (TN == 2) {
       if (ROWSUM)
         asm volatile(QG_TILE_LOOP_ASM_2X2 QG_TILE_LOOP_OPERANDS_2X2);
       else
         asm volatile(QG_TILE_LOOP_ASM_NOROWSUM_2X2 QG_TILE_LOOP_OPERANDS_2X2);
+    } else {
+      if (ROWSUM)
+        asm volatile(QG_TILE_LOOP_ASM_2X4 QG_TILE_LOOP_OPERANDS_2X4);
+      else
+        asm volatile(QG_TILE_LOOP_ASM_NOROWSUM_2X4 QG_TILE_LOOP_OPERANDS_2X4);
     }
     rs[0] = (unsigned)rs01;
     rs[1] = (unsigned)(rs01 >> 32);
@@ -591,7 +609,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
 template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, int KS = 1>
 hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
-  constexpr int STAGES = (PATH == PATH_ASM ? NSTAGE : pipe_stages(TM * TN)) * KS;
+  constexpr int STAGES = (PATH == PATH_ASM ? asm_stages(TM * TN) : pipe_stages(TM * TN)) * KS;
   // the output pipeline's per-column constants (12 B per column) reuse the stage memory
   constexpr int SMEM = STAGES * (BM + BN) * BK > 12 * BN ? STAGES * (BM + BN) * BK : 12 * BN;
   const int tiles_m = (a.M + BM - 1) / BM;
@@ -656,7 +674,9 @@ hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, int kernel, hipS
     case QG_KERNEL_TILE128:
       if (a.K >= NSTAGE * BK) return launch_cfg<PATH_ASM, 2, 2, 2, 2>(a, mode, s);
       return launch_cfg<PATH_PIPE, 2, 2, 2, 2>(a, mode, s);
-    case QG_KERNEL_TILE128X256: return launch_cfg<PATH_PIPE, 2, 2, 2, 4>(a, mode, s);
+    case QG_KERNEL_TILE128X256:
+      if (a.K >= asm_stages(8) * BK) return launch_cfg<PATH_ASM, 2, 2, 2, 4>(a, mode, s);
+      return launch_cfg<PATH_PIPE, 2, 2, 2, 4>(a, mode, s);
     case QG_KERNEL_TILE64K4: return launch_cfg<PATH_PIPE, 2, 2, 1, 1, 4>(a, mode, s);
     case QG_KERNEL_TILE256:
       if (a.K >= NSTAGE * BK) return launch_cfg<PATH_ASM, 2, 2, 4, 4>(a, mode, s);

@@ -24,19 +24,21 @@ av01 av23 bv01 bv23 ard brd, SGPR inputs aptr bptr kt ldsdma lds bstep, 64-bit V
 Two configurations are generated from the same schedule: TM x TN = 4 x 4 blocks per wave (256 x 256 workgroup
 tile, the plan above) and 2 x 2 (128 x 128 tile: 4 accumulators c0..c3, inputs av01 bv01 ard brd, output rs01,
 fixed registers from v96, 16 KiB stages).  With only four MFMAs per k-step the LDS reads sit behind the first
-two and the row sums and shifts of both A fragments behind the last two.
+two and the row sums and shifts of both A fragments behind the last two.  A third one, 2 x 4 blocks (128 x 256
+tile: 8 accumulators, three 24 KiB stages so that two workgroups share a CU, fixed registers from v56, one more
+SGPR input bofs = distance from a wave's A request slots to its B request slots), has eight MFMAs per k-step.
 """
 import os
 
 ABL = set(filter(None, os.environ.get("QG_GEN_ABL", "").split(",")))
 
-def configure(tm, tn):
+def configure(tm, tn, nstage=4):
     """sets the module-level plan for TM x TN blocks of 32 x 32 per wave (2 x 2 waves per workgroup)"""
     global TM, TN, NM, A, B, RS, AV, BV, ARD0, ARD1, BRD, VA, VB, STAGE_BYTES, A_STAGE, A_DMA, N_DMA, NREAD, RSLOTS
-    global FIRST_VGPR, LAST_VGPR
-    assert tm == tn and tm in (2, 4), "the request addressing assumes as many A as B requests per wave"
-    TM, TN, NM = tm, tn, tm * tn
-    base = 160 if tm == 4 else 96
+    global FIRST_VGPR, LAST_VGPR, NSTAGE
+    assert (tm, tn) in ((4, 4), (2, 2), (2, 4)) and nstage in (3, 4)
+    TM, TN, NM, NSTAGE = tm, tn, tm * tn, nstage
+    base = {16: 160, 4: 96, 8: 56}[tm * tn]
     A = [base, base + 4 * (tm + tn)]
     B = [base + 4 * tm, base + 4 * (tm + tn) + 4 * tm]
     RS = base + 8 * (tm + tn)                       # TM row-sum accumulators
@@ -47,7 +49,7 @@ def configure(tm, tn):
     FIRST_VGPR, LAST_VGPR = base, 255 if tm == 4 else VB
     A_STAGE = tm * 4096                             # 64 * TM rows of 64 bytes
     STAGE_BYTES = (tm + tn) * 4096
-    A_DMA = tm                                      # 1 KiB requests per wave and tile: A, then as many for B
+    A_DMA = tm                                      # 1 KiB requests per wave and tile: TM for A, then TN for B
     N_DMA = tm + tn
     NREAD = tm + tn                                 # LDS reads per k-step
     RSLOTS = (NREAD + 1) // 2                       # slots that carry them, two each
@@ -91,7 +93,9 @@ def dma(e, q):
         e("s_mov_b32 m0, s96")
         e("s_nop 0")
     if q == A_DMA:
-        e(f"s_add_u32 m0, s96, {A_STAGE}")
+        # B slots of this wave: A_STAGE further when a wave requests as many KiB of B as of A; otherwise the
+        # distance is wave dependent and comes in as an operand (s85)
+        e(f"s_add_u32 m0, s96, {A_STAGE}" if TM == TN else "s_add_u32 m0, s96, s85")
         e("s_nop 0")
     if q < A_DMA:
         e(f"global_load_lds_dwordx4 v{AV + q}, s[86:87]" + (f" offset:{q * 1024}" if q else ""))
@@ -173,14 +177,31 @@ def step(e, use, ks_load, request, next_va, load=True):
                 e(f"v_add_u32 v{VB}, s98, v{BRD}")
 
 
+def wrap_stage(e, reg):
+    """reg = reg mod NSTAGE for reg in 0..NSTAGE"""
+    if NSTAGE == 4:
+        e(f"s_and_b32 {reg}, {reg}, 3")
+    else:
+        e(f"s_cmp_eq_u32 {reg}, {NSTAGE}")
+        e(f"s_cselect_b32 {reg}, 0, {reg}")
+
+
+def stage_offset(e, dst, src):
+    """dst = src * STAGE_BYTES"""
+    if STAGE_BYTES & (STAGE_BYTES - 1) == 0:
+        e(f"s_lshl_b32 {dst}, {src}, {STAGE_BYTES.bit_length() - 1}")
+    else:
+        e(f"s_mul_i32 {dst}, {src}, {STAGE_BYTES}")
+
+
 def rotate_stage(e):
-    """end of a tile: stage index += 1 (mod 4); recompute the read bases"""
+    """end of a tile: stage index += 1 (mod NSTAGE); recompute the read bases"""
     e("s_add_u32 s93, s93, 1")
-    e("s_and_b32 s93, s93, 3")
+    wrap_stage(e, "s93")
     e("s_mov_b32 s97, s98")
     e("s_add_u32 s94, s93, 1")
-    e("s_and_b32 s94, s94, 3")
-    e(f"s_lshl_b32 s94, s94, {STAGE_BYTES.bit_length() - 1}")
+    wrap_stage(e, "s94")
+    stage_offset(e, "s94", "s94")
     e("s_add_u32 s98, s92, s94")
 
 
@@ -196,7 +217,7 @@ def tile(e, wait_vm, request, last=False):
     if "nobar" not in ABL:
         e("s_barrier")
     if request:
-        e(f"s_lshl_b32 s94, s93, {STAGE_BYTES.bit_length() - 1}")
+        stage_offset(e, "s94", "s93")
         e("s_add_u32 s96, s91, s94")
     # k-step 1 of tile t: consume set 1, fetch (t+1, 0) into set 0 from the next stage
     step(e, use=1, ks_load=0, request=request, next_va=1)
@@ -220,16 +241,18 @@ def generate_loop(rowsum):
     e(f"v_mov_b64 v[{ARD0}:{ARD1}], %[ard]")
     e(f"v_mov_b64 v[{BRD}:{BRD + 1}], %[brd]")
     e("s_mov_b32 s84, 0x80808080")
+    if TM != TN:
+        e("s_mov_b32 s85, %[bofs]")
     e("s_mov_b64 s[86:87], %[aptr]")
     e("s_mov_b64 s[88:89], %[bptr]")
-    e("s_sub_u32 s90, %[kt], 4")
+    e(f"s_sub_u32 s90, %[kt], {NSTAGE}")
     e("s_mov_b32 s91, %[ldsdma]")
     e("s_mov_b32 s92, %[lds]")
     e("s_mov_b32 s99, %[bstep]")
     for f in range(TM):
         e(f"v_mov_b32 v{RS + f}, 0")
-    # ---- request tiles 0..3 into stages 0..3
-    for st in range(4):
+    # ---- request tiles 0..NSTAGE-1 into stages 0..NSTAGE-1
+    for st in range(NSTAGE):
         e(f"s_add_u32 s96, s91, {st * STAGE_BYTES}")
         for q in range(N_DMA):
             dma(e, q)
@@ -237,7 +260,7 @@ def generate_loop(rowsum):
     e("s_mov_b32 s93, 0")
     e("s_mov_b32 s97, s92")
     e(f"s_add_u32 s98, s92, {STAGE_BYTES}")
-    e(f"s_waitcnt vmcnt({3 * N_DMA})")
+    e(f"s_waitcnt vmcnt({(NSTAGE - 1) * N_DMA})")
     e("s_barrier")
     # ---- fragments (0, 0) into set 0
     e(f"v_add_u32 v{VA}, s97, v{ARD0}")
@@ -254,19 +277,18 @@ def generate_loop(rowsum):
     e("s_waitcnt lgkmcnt(0)")
     e(f"v_add_u32 v{VA}, s97, v{ARD1}")
     e("s_nop 1")
-    # ---- steady state: KT-4 tiles, each requesting tile t+4
+    # ---- steady state: KT-NSTAGE tiles, each requesting tile t+NSTAGE
     e("s_cmp_eq_u32 s90, 0")
     e("s_cbranch_scc1 2f")
     e("1:")
-    tile(e, 2 * N_DMA, request=True)
+    tile(e, (NSTAGE - 2) * N_DMA, request=True)
     e("s_sub_u32 s90, s90, 1")
     e("s_cmp_lg_u32 s90, 0")
     e("s_cbranch_scc1 1b")
     e("2:")
-    # ---- drain: nothing left to request
-    tile(e, 2 * N_DMA, request=False)
-    tile(e, N_DMA, request=False)
-    tile(e, 0, request=False)
+    # ---- drain: nothing left to request; the tiles still in flight are fewer with every tile
+    for younger in range(NSTAGE - 2, -1, -1):
+        tile(e, younger * N_DMA, request=False)
     tile(e, 0, request=False, last=True)
     # ---- results: let the last MFMAs retire, hand the row sums back
     e("s_nop 15")
@@ -280,8 +302,8 @@ def generate_loop(rowsum):
 
 def generate():
     out = "// GENERATED by gen_tile_loop.py -- do not edit.\n"
-    for tm, suffix in ((4, ""), (2, "_2X2")):
-        configure(tm, tm)
+    for tm, tn, nstage, suffix in ((4, 4, 4, ""), (2, 2, 4, "_2X2"), (2, 4, 3, "_2X4")):
+        configure(tm, tn, nstage)
         clob = [f'"v{i}"' for i in range(FIRST_VGPR, LAST_VGPR + 1)] + [f'"s{i}"' for i in range(84, 100)] + \
                ['"scc"', '"memory"']
         for name, rowsum in (("QG_TILE_LOOP_ASM", True), ("QG_TILE_LOOP_ASM_NOROWSUM", False)):
