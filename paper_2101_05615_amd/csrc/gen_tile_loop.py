@@ -38,7 +38,7 @@ def configure(tm, tn, nstage=4):
     global FIRST_VGPR, LAST_VGPR, NSTAGE
     assert (tm, tn) in ((4, 4), (2, 2), (2, 4)) and nstage in (3, 4)
     TM, TN, NM, NSTAGE = tm, tn, tm * tn, nstage
-    base = {16: 160, 4: 96, 8: 56}[tm * tn]
+    base = {16: 160, 4: 76, 8: 56}[tm * tn]
     A = [base, base + 4 * (tm + tn)]
     B = [base + 4 * tm, base + 4 * (tm + tn) + 4 * tm]
     RS = base + 8 * (tm + tn)                       # TM row-sum accumulators

@@ -1,6 +1,7 @@
 """Build-time guard for the hot kernels: no private memory.  The GEMM kernels keep their accumulator tiles in
 registers; a change that makes the compiler index them dynamically moves them to scratch memory and costs
-tens of per cent without failing any parity test.  hipcc reports the per-kernel resources while cross-compiling
+tens of per cent without failing any parity test.  The hand-scheduled loops must also name only registers
+inside the budget their occupancy leaves (the compiler warns otherwise).  hipcc reports the per-kernel resources while cross-compiling
 (no GPU needed)."""
 import os
 import re
@@ -20,6 +21,8 @@ def _resources(src):
     cmd = ["hipcc"] + flags + ["--cuda-device-only", "-c", "-Rpass-analysis=kernel-resource-usage",
                                os.path.join(build.CSRC, src), "-o", os.devnull]
     err = subprocess.run(cmd, check=True, capture_output=True, text=True).stderr
+    # the hand-scheduled loops name fixed registers; all of them must lie inside the kernel's register budget
+    assert "reserved registers" not in err, [l for l in err.splitlines() if "reserved registers" in l][:2]
     out, name = {}, None
     for line in err.splitlines():
         m = re.search(r"Function Name: (\S+)", line)
