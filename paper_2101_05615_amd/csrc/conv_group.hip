@@ -211,11 +211,21 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
   {
     const int8_t* wsrc = p.Wfrag + (size_t)slice * NCB * RS * QG_FRAG_BYTES + lane * 16;
     for (int f = wave; f < NCB * RS; f += 4) dma16(wsrc + (size_t)f * QG_FRAG_BYTES, w_s + f * QG_FRAG_BYTES);
-    for (int c0 = wave * 64; c0 < nchunks_pad; c0 += 256) {
-      const int c = c0 + lane;
+    if (lin0 >= 0 && lin0 + nchunks_pad / CP <= npix) {
+      // the whole patch lies inside the buffer: one address per lane, then 256 chunks = 256 / CP pixels further
+      // per request (the swizzle has period 8 pixels or less, so it is the same for every request of a lane)
+      const int c = wave * 64 + lane;
       const int pp = c / CP, phys = c % CP;
-      const int lin = min(max(lin0 + pp, 0), npix - 1);
-      dma16(p.in + (size_t)lin * p.C + ch0 + ((phys ^ swz(pp)) << 4), patch + c0 * 16);
+      const uint8_t* src = p.in + (size_t)(lin0 + pp) * p.C + ch0 + ((phys ^ swz(pp)) << 4);
+      const int step = 256 / CP * p.C;
+      for (int c0 = wave * 64; c0 < nchunks_pad; c0 += 256, src += step) dma16(src, patch + c0 * 16);
+    } else {
+      for (int c0 = wave * 64; c0 < nchunks_pad; c0 += 256) {
+        const int c = c0 + lane;
+        const int pp = c / CP, phys = c % CP;
+        const int lin = min(max(lin0 + pp, 0), npix - 1);
+        dma16(p.in + (size_t)lin * p.C + ch0 + ((phys ^ swz(pp)) << 4), patch + c0 * 16);
+      }
     }
     for (int c = tid; c < NCH; c += 256) {
       const int oc = ch0 + c;
@@ -228,18 +238,36 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
 
   const int pl = lane & 31, g = lane >> 5;
   const int px = q0 + wave * 32 + pl;
-  const int pxc = min(px, npix - 1);
-  const int wo = pxc % p.W;
-  const int ho = (pxc / p.W) % p.H;
+  // image position of this lane's pixel: the wave's first pixel is divided on the scalar unit, the lane walks
+  // pl pixels on from there (a lane past the last pixel gets a position that is never used for a store)
+  const int pw0 = q0 + wave * 32;
+  int wo = pw0 % p.W + pl;
+  int ho = (pw0 / p.W) % p.H;
+  for (int i = 31 / p.W + 1; i > 0; --i) {
+    const bool wrap = wo >= p.W;
+    wo -= wrap ? p.W : 0;
+    ho += wrap ? 1 : 0;
+    ho = ho == p.H ? 0 : ho;
+  }
+  bool row_ok[R], col_ok[S];
+#pragma unroll
+  for (int kh = 0; kh < R; ++kh) row_ok[kh] = (unsigned)(ho + kh - PAD_H) < (unsigned)p.H;
+#pragma unroll
+  for (int kw = 0; kw < S; ++kw) col_ok[kw] = (unsigned)(wo + kw - PAD_W) < (unsigned)p.W;
   const unsigned azp_word = (unsigned)p.a_zp * 0x01010101u;
   const float czp_f = (float)p.c_zp;
   const int pp_c = wave * 32 + pl + halo;  // patch index of this lane's centre pixel
 
+  // the accumulators start at bias - (theta_A - 128) * column offset, so the output pipeline adds nothing
   v16i acc[NCB];
 #pragma unroll
   for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[cb][r] = 0;
+    for (int q = 0; q < 4; ++q) {
+      const v4i cj = *reinterpret_cast<const v4i*>(&cj_s[cb * 32 + 16 * g + 4 * q]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[cb][4 * q + r] = cj[r];
+    }
   unsigned rs[NCB][4];
 #pragma unroll
   for (int cb = 0; cb < NCB; ++cb)
@@ -250,8 +278,7 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
   for (int kh = 0; kh < R; ++kh) {
 #pragma unroll
     for (int kw = 0; kw < S; ++kw) {
-      const int hi = ho + kh - PAD_H, wi = wo + kw - PAD_W;
-      const bool ok = hi >= 0 && hi < p.H && wi >= 0 && wi < p.W;
+      const bool ok = row_ok[kh] && col_ok[kw];
       const int pp = pp_c + (kh - PAD_H) * p.W + (kw - PAD_W);
       const unsigned keep = ok ? 0xFFFFFFFFu : 0u;
       // in-image: x ^ 0x80 (uint8 -> int8); out of image: theta_A - 128 in every byte
@@ -285,14 +312,16 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
       unsigned out[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const v4i cj = *reinterpret_cast<const v4i*>(&cj_s[c_l + 4 * q]);
-        const v4i nbz = *reinterpret_cast<const v4i*>(&nbz_s[c_l + 4 * q]);
         const float4 sc = *reinterpret_cast<const float4*>(&sc_s[c_l + 4 * q]);
-        const int rsum = HAS_BZP ? (int)rs[cb][q] - 128 * RS * 4 : 0;
-        const int x0 = acc[cb][4 * q + 0] + cj.x + (HAS_BZP ? __mul24(nbz.x, rsum) : 0);
-        const int x1 = acc[cb][4 * q + 1] + cj.y + (HAS_BZP ? __mul24(nbz.y, rsum) : 0);
-        const int x2 = acc[cb][4 * q + 2] + cj.z + (HAS_BZP ? __mul24(nbz.z, rsum) : 0);
-        const int x3 = acc[cb][4 * q + 3] + cj.w + (HAS_BZP ? __mul24(nbz.w, rsum) : 0);
+        int x0 = acc[cb][4 * q + 0], x1 = acc[cb][4 * q + 1], x2 = acc[cb][4 * q + 2], x3 = acc[cb][4 * q + 3];
+        if (HAS_BZP) {
+          const v4i nbz = *reinterpret_cast<const v4i*>(&nbz_s[c_l + 4 * q]);
+          const int rsum = (int)rs[cb][q] - 128 * RS * 4;
+          x0 += __mul24(nbz.x, rsum);
+          x1 += __mul24(nbz.y, rsum);
+          x2 += __mul24(nbz.z, rsum);
+          x3 += __mul24(nbz.w, rsum);
+        }
         unsigned w = qg_requant_pack<LO>(x0, sc.x, p.clamp_lo, p.clamp_hi, czp_f, 0, 0);
         w = qg_requant_pack<LO>(x1, sc.y, p.clamp_lo, p.clamp_hi, czp_f, 1, w);
         w = qg_requant_pack<LO>(x2, sc.z, p.clamp_lo, p.clamp_hi, czp_f, 2, w);
