@@ -173,9 +173,11 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
   constexpr int NCH = NCB * 32;
   constexpr int CP = NCH / 16;       // 16-byte chunks per pixel
   constexpr int PAD_H = (R - 1) / 2, PAD_W = (S - 1) / 2;
-  // chunk swizzle of patch pixel pp: 8 consecutive pixels of one chunk index must fall into 8 different
-  // 16-byte bank groups (pixel stride 128 B: xor pp; 64 B: xor pp/2; 32 B: consecutive already)
-  auto swz = [](int pp) { return CP == 8 ? (pp & 7) : (CP == 4 ? ((pp >> 1) & 3) : 0); };
+  // chunk swizzle of patch pixel pp: the 16 consecutive pixels whose chunk of one index is read in one cycle
+  // (8 on parts with 128 B of banks) must fall into different 16-byte bank groups; period 16 pixels
+  auto swz = [](int pp) {
+    return CP == 8 ? ((pp & 7) ^ ((pp >> 3) & 1)) : (CP == 4 ? (((pp >> 1) & 3) ^ ((pp >> 3) & 1)) : ((pp >> 3) & 1));
+  };
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* w_s = smem;                                        // [cb][tap] fragments
   int* cj_s = reinterpret_cast<int*>(smem + NCB * RS * QG_FRAG_BYTES);
@@ -213,7 +215,7 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
     for (int f = wave; f < NCB * RS; f += 4) dma16(wsrc + (size_t)f * QG_FRAG_BYTES, w_s + f * QG_FRAG_BYTES);
     if (lin0 >= 0 && lin0 + nchunks_pad / CP <= npix) {
       // the whole patch lies inside the buffer: one address per lane, then 256 chunks = 256 / CP pixels further
-      // per request (the swizzle has period 8 pixels or less, so it is the same for every request of a lane)
+      // per request (the swizzle has period 16 pixels or less, so it is the same for every request of a lane)
       const int c = wave * 64 + lane;
       const int pp = c / CP, phys = c % CP;
       const uint8_t* src = p.in + (size_t)(lin0 + pp) * p.C + ch0 + ((phys ^ swz(pp)) << 4);

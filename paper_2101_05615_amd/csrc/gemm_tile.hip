@@ -79,9 +79,12 @@ __device__ __forceinline__ void dma16(const void* gptr, unsigned char* lds_base)
                                    (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
 }
 
-// swizzled byte offset of 16-byte chunk kc (0..3) of row r in an A stage (rows are 64 B; the xor
-// spreads the 8 rows a quarter-wave reads at once over all 32 LDS banks)
-__device__ __forceinline__ int a_lds_off(int r, int kc) { return r * BK + ((kc ^ ((r >> 1) & 3)) << 4); }
+// Chunk swizzle of row r of an A stage (rows are 64 B = four 16-byte chunks).  A 16-byte read of one chunk
+// index is served sixteen rows at a time out of 256 B of banks (eight rows and 128 B on older parts): the
+// four rows 4 apart that share a 64-byte bank window must then hold that chunk at four different places.
+__device__ __forceinline__ int a_swz(int r) { return ((r >> 1) & 3) ^ ((r >> 3) & 1); }
+// swizzled byte offset of 16-byte chunk kc (0..3) of row r in an A stage
+__device__ __forceinline__ int a_lds_off(int r, int kc) { return r * BK + ((kc ^ a_swz(r)) << 4); }
 
 // operand list shared by the two generated loop variants (gen_tile_loop.py)
 #define QG_TILE_LOOP_OPERANDS \
@@ -186,7 +189,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
 #pragma unroll
   for (int q = 0; q < A_DMA; ++q) {
     const int r = (wave * A_DMA + q) * 16 + (lane >> 2);
-    const int kc = (lane & 3) ^ ((r >> 1) & 3);
+    const int kc = (lane & 3) ^ a_swz(r);
     const int rg = min(m0 + r, p.M - 1);  // rows past M re-read the last row; never stored
     if (CONV) {
       const int wo = rg % p.cv_Wo, t = rg / p.cv_Wo;
@@ -409,7 +412,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
 #pragma unroll
       for (int q = 0; q < A_DMA; ++q) {
         const int r = (wave * A_DMA + q) * 16 + (lane >> 2);
-        const int kc = (lane & 3) ^ ((r >> 1) & 3);
+        const int kc = (lane & 3) ^ a_swz(r);
         const size_t off = (size_t)min(m0 + r, p.M - 1) * (size_t)p.lda + (size_t)(kc * 16 + k0);
         *reinterpret_cast<v4i*>(smem + (wave * A_DMA + q) * 1024 + lane * 16) =
             qg_load_a_chunk(p.A + off, p.K - (k0 + kc * 16), off + 16 <= a_end);
