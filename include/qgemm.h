@@ -157,6 +157,8 @@ int qg_gemm_u8s8_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* 
  *   TILE256         256 x 256, four LDS stages, hand-scheduled loop (large shapes)
  *   TILE64K4        64 x 64 with K split over four wave sets (1024 threads; a few
  *                   tiles and a long K)
+ *   TILE64K1        64 x 64 without a K split (256 threads, 24 KB of LDS: many small
+ *                   workgroups per CU; the automatic choice uses it for convolutions)
  * QG_KERNEL_AUTO picks by (M, N, K): first the rules installed with
  * qg_dispatch_set_rules (an offline autotune writes them), then a built-in
  * rule of thumb derived from the same measurements. */
@@ -169,7 +171,8 @@ int qg_gemm_u8s8_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* 
 #define QG_KERNEL_TILE128X256 6
 #define QG_KERNEL_TILE256 7
 #define QG_KERNEL_TILE64K4 8
-#define QG_KERNEL_LAST 8
+#define QG_KERNEL_TILE64K1 9
+#define QG_KERNEL_LAST 9
 
 /* Name of a kernel id ("skinny16", "tile128x256", ...; "auto" for 0), NULL if invalid. */
 const char* qg_kernel_name(int kernel);
@@ -327,11 +330,14 @@ int qg_conv_groupwise_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W,
  * one filter tap and is requested straight from the image.
  *   in_nhwc  dev uint8 [Nb][H][W][Cin], 16-byte aligned;  Cin % 64 == 0
  *   out_nhwc dev uint8 [Nb][Ho][Wo][Cout], Ho = (H + 2*pad - R)/stride + 1
- * QG_EUNSUPPORTED for other channel counts or an unaligned image; QG_EINVAL when
- * R*S*Cin differs from the K of Wp. */
+ *   kernel   QG_KERNEL_AUTO (chosen from the extents by a cost model fitted to 3 x 3 and
+ *            1 x 1 layers), or QG_KERNEL_TILE64 / TILE64K4 / TILE64K1 / TILE128 /
+ *            TILE128X256; every choice gives the same bytes
+ * QG_EUNSUPPORTED for other channel counts, an unaligned image or another kernel id;
+ * QG_EINVAL when R*S*Cin differs from the K of Wp or the id is unknown. */
 int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int Cin, int R, int S,
                                int pad, int stride, const qg_packed_b* Wp, const qg_requant_params* p,
-                               uint8_t* out_nhwc, void* stream);
+                               uint8_t* out_nhwc, void* stream, int kernel);
 
 /* ---- measurement probes --------------------------------------------------- */
 

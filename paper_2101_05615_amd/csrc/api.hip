@@ -80,6 +80,16 @@ const tile_cost k_tile_cost[] = {
     {QG_KERNEL_TILE256, 256, 256, 9.9, 0.632, 0.76, 8.21},
     {QG_KERNEL_TILE64K4, 64, 64, 4.15, 0.089, 0.103, 2.1},
 };
+// The dense convolution runs the compiler-scheduled tile loops with the im2col addressing folded in; the same
+// formula, constants fitted to 3 x 3 and 1 x 1 layers of 1 .. 32 images (graph-replay times).  The 64 x 64 tile
+// comes without a K split, and with two or four wave sets that share K.
+const tile_cost k_conv_cost[] = {
+    {QG_KERNEL_TILE64K1, 64, 64, 3.35, 0.304, 0.163, 0.6},
+    {QG_KERNEL_TILE64, 64, 64, 4.12, 0.193, 0.135, 1.46},
+    {QG_KERNEL_TILE64K4, 64, 64, 5.19, 0.152, 0.145, 3.72},
+    {QG_KERNEL_TILE128, 128, 128, 4.79, 0.465, 0.301, 1.71},
+    {QG_KERNEL_TILE128X256, 128, 256, 6.84, 0.611, 0.551, 2.99},
+};
 const stream_cost k_stream_cost[] = {
     {QG_KERNEL_SKINNY16, 16, 3.58, 7.3e-5, 7.55, 0.74e-3},
     {QG_KERNEL_SKINNY32, 32, 4.13, 1.99e-4, 10.33, 1.28e-3},
@@ -207,7 +217,7 @@ extern "C" {
 const char* qg_kernel_name(int kernel) {
   static const char* const names[] = {"auto",   "skinny16", "skinny32",    "skinny64",
                                       "tile64", "tile128",  "tile128x256", "tile256",
-                                      "tile64k4"};
+                                      "tile64k4", "tile64k1"};
   return (kernel >= 0 && kernel <= QG_KERNEL_LAST) ? names[kernel] : nullptr;
 }
 
@@ -593,9 +603,13 @@ int qg_gemm_f32s8_dequant_f32(const float* A_dev, int M, int lda, float a_inv_sc
 
 int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int Cin, int R, int S, int pad,
                                int stride, const qg_packed_b* Wp, const qg_requant_params* p, uint8_t* out_nhwc,
-                               void* stream) {
+                               void* stream, int kernel) {
   if (!in_nhwc || !Wp || !out_nhwc) return QG_ENULL;
   if (Wp->kind != QG_KIND_GEMM || Wp->version != QG_LAYOUT_VERSION) return QG_EINVAL;
+  if (kernel < QG_KERNEL_AUTO || kernel > QG_KERNEL_LAST) return QG_EINVAL;
+  if (kernel != QG_KERNEL_AUTO && kernel != QG_KERNEL_TILE64 && kernel != QG_KERNEL_TILE64K4 &&
+      kernel != QG_KERNEL_TILE64K1 && kernel != QG_KERNEL_TILE128 && kernel != QG_KERNEL_TILE128X256)
+    return QG_EUNSUPPORTED;
   if (Nb <= 0 || H <= 0 || W <= 0 || Cin <= 0 || R <= 0 || S <= 0 || pad < 0 || stride <= 0) return QG_EINVAL;
   if ((long long)R * S * Cin != Wp->K) return QG_EINVAL;
   int rc = check_requant(p, Wp->N);
@@ -638,13 +652,13 @@ int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int
   a.cv_pad = pad;
   a.cv_azp = p->a_zp;
   a.cv_in_bytes = Nb * H * W * Cin;
-  // the tiled kernels with a compiler-scheduled loop, chosen like a GEMM of the same extents
-  int kernel = QG_KERNEL_TILE64;
-  double best_us = 1e300;
-  for (const tile_cost& c : k_tile_cost) {
-    if (c.kernel == QG_KERNEL_TILE256 || c.kernel == QG_KERNEL_TILE64K4) continue;
-    const double us = tile_estimate(c, a.M, a.N, a.K);
-    if (us < best_us) best_us = us, kernel = c.kernel;
+  // the tiled kernels with a compiler-scheduled loop, chosen by the same cost formula as a GEMM's
+  if (kernel == QG_KERNEL_AUTO) {
+    double best_us = 1e300;
+    for (const tile_cost& c : k_conv_cost) {
+      const double us = tile_estimate(c, a.M, a.N, a.K);
+      if (us < best_us) best_us = us, kernel = c.kernel;
+    }
   }
   const hipError_t e = qg_launch_conv_dense(a, kernel, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? QG_OK : QG_ELAUNCH;

@@ -143,7 +143,7 @@ template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, boo
 __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) / KS) void qg_gemm_tile_kernel(const qg_gemm_args p,
                                                                                                 int tiles_m,
                                                                                                 int tiles_n) {
-  static_assert(KS == 1 || ((KS == 2 || KS == 4) && PATH == PATH_PIPE && !CONV), "K split: wave sets on the pipelined path");
+  static_assert(KS == 1 || ((KS == 2 || KS == 4) && PATH == PATH_PIPE), "K split: wave sets on the pipelined path");
   constexpr int NW = NWM * NWN, NT = NW * KS * 64;  // NW: waves of one set; NT: threads of the workgroup
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
   constexpr int A_STAGE = BM * BK, B_STAGE = BN * BK, STAGE = A_STAGE + B_STAGE;
@@ -185,7 +185,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
   // BN/16 fragments of 1 KiB, one contiguous run of the packed buffer.  Addresses are a wave-uniform
   // base (advanced per tile on the scalar unit) plus a fixed 32-bit per-lane offset.
   unsigned a_voff[A_DMA], b_voff[B_DMA];
-  int a_pix[A_DMA];  // CONV: linear input pixel of tap (0, 0) of the row this lane requests (may be negative)
+  int a_pix[A_DMA];  // CONV: byte offset of the chunk this lane requests, at tap (0, 0) (may be negative)
 #pragma unroll
   for (int q = 0; q < A_DMA; ++q) {
     const int r = (wave * A_DMA + q) * 16 + (lane >> 2);
@@ -194,7 +194,8 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
     if (CONV) {
       const int wo = rg % p.cv_Wo, t = rg / p.cv_Wo;
       const int ho = t % p.cv_Ho, n = t / p.cv_Ho;
-      a_pix[q] = (n * p.cv_H + ho * p.cv_stride - p.cv_pad) * p.cv_W + wo * p.cv_stride - p.cv_pad;
+      // byte offset of this lane's chunk at tap (0, 0), channel slice 0; a tap adds a workgroup-uniform offset
+      a_pix[q] = ((n * p.cv_H + ho * p.cv_stride - p.cv_pad) * p.cv_W + wo * p.cv_stride - p.cv_pad) * p.cv_Cin + kc * 16;
       a_voff[q] = kc * 16;
       continue;
     }
@@ -258,14 +259,16 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
       if (CONV) {
         const unsigned keep = cv_ok[mb] ? 0xFFFFFFFFu : 0u;
         const unsigned flip = cv_ok[mb] ? 0x80808080u : (azp_word ^ 0x80808080u);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          if (ROWSUM) {
-            const unsigned y = __builtin_amdgcn_bitop3_b32((unsigned)af[mb][j], keep, azp_word, 0xe2);  // keep ? x : theta_A
-            rs[mb] = __builtin_amdgcn_sad_u8(y, 0u, rs[mb]);
-          }
-          af[mb][j] = (int)__builtin_amdgcn_bitop3_b32((unsigned)af[mb][j], keep, flip, 0x6a);  // (x & keep) ^ flip
+        if (ROWSUM) {  // the 16 bytes as staged, or 16 times theta_A for a tap outside the image
+          unsigned sum = __builtin_amdgcn_sad_u8(af[mb].x, 0u, 0u);
+          sum = __builtin_amdgcn_sad_u8(af[mb].y, 0u, sum);
+          sum = __builtin_amdgcn_sad_u8(af[mb].z, 0u, sum);
+          sum = __builtin_amdgcn_sad_u8(af[mb].w, 0u, sum);
+          rs[mb] += cv_ok[mb] ? sum : 16u * (unsigned)p.cv_azp;
         }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          af[mb][j] = (int)__builtin_amdgcn_bitop3_b32((unsigned)af[mb][j], keep, flip, 0x6a);  // (x & keep) ^ flip
         continue;
       }
       if (ROWSUM) {
@@ -341,22 +344,31 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
     const int cv_nc = CONV ? p.cv_Cin / BK : 1;
     int rq_kh = 0, rq_kw = 0, rq_cc = 0;  // of the next tile to request
     int cs_kh = 0, cs_kw = 0, cs_cc = 0;  // of the tile being consumed
+    // n tiles on (wave-uniform, scalar unit): a wave set starts at tile kg and takes every KS-th
+    auto cv_advance = [&](int& kh, int& kw, int& cc, int n) {
+      for (int j = 0; j < n; ++j)
+        if (++cc == cv_nc) {
+          cc = 0;
+          if (++kw == p.cv_S) kw = 0, ++kh;
+        }
+    };
+    if (CONV && KS > 1) {
+      cv_advance(rq_kh, rq_kw, rq_cc, kg);
+      cv_advance(cs_kh, cs_kw, cs_cc, kg);
+    }
     auto request = [&](int kt, int stage) {
       const uint8_t* ab = p.A + (size_t)kt * BK;
       const int8_t* bb = b_tile0 + (size_t)kt * b_step;
       unsigned char* st = smem + (stage * KS + kg) * STAGE;
       if (CONV) {
-        const int tap_pix = rq_kh * p.cv_W + rq_kw;
+        const int tap_off = (rq_kh * p.cv_W + rq_kw) * p.cv_Cin + rq_cc * BK;
 #pragma unroll
         for (int q = 0; q < A_DMA; ++q) {
-          int off = (a_pix[q] + tap_pix) * p.cv_Cin + rq_cc * BK + (int)a_voff[q];
+          int off = a_pix[q] + tap_off;
           off = min(max(off, 0), p.cv_in_bytes - 16);  // taps outside the image: any valid address, masked later
           dma16(p.A + off, st + (wave * A_DMA + q) * 1024);
         }
-        if (++rq_cc == cv_nc) {
-          rq_cc = 0;
-          if (++rq_kw == p.cv_S) rq_kw = 0, ++rq_kh;
-        }
+        cv_advance(rq_kh, rq_kw, rq_cc, KS);
       } else
 #pragma unroll
       for (int q = 0; q < A_DMA; ++q) dma16(ab + a_voff[q], st + (wave * A_DMA + q) * 1024);
@@ -381,10 +393,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
 #pragma unroll
         for (int mb = 0; mb < TM; ++mb)
           cv_ok[mb] = (unsigned)(cv_h[mb] + cs_kh) < (unsigned)p.cv_H && (unsigned)(cv_w[mb] + cs_kw) < (unsigned)p.cv_W;
-        if (++cs_cc == cv_nc) {
-          cs_cc = 0;
-          if (++cs_kw == p.cv_S) cs_kw = 0, ++cs_kh;
-        }
+        cv_advance(cs_kh, cs_kw, cs_cc, KS);
       }
       if (consume) {
         fetch(stage, 0, a0, b0);
@@ -637,20 +646,20 @@ hipError_t launch_cfg(const qg_gemm_args& a, int mode, hipStream_t s) {
   return launch<QG_MODE_ACC32, PATH, true, NWM, NWN, TM, TN, KS>(a, s);
 }
 
-template <int NWM, int NWN, int TM, int TN>
+template <int NWM, int NWN, int TM, int TN, int KS = 1>
 hipError_t launch_conv(const qg_gemm_args& a, hipStream_t s) {
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
-  constexpr int SMEM = pipe_stages(TM * TN) * (BM + BN) * BK;
+  constexpr int SMEM = pipe_stages(TM * TN) * KS * (BM + BN) * BK;
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
-  const dim3 grid((unsigned)(tiles_m * tiles_n)), block(NWM * NWN * 64);
+  const dim3 grid((unsigned)(tiles_m * tiles_n)), block(NWM * NWN * KS * 64);
   hipError_t e;
   if (a.has_bzp) {
-    constexpr auto fn = qg_gemm_tile_kernel<QG_MODE_REQUANT, PATH_PIPE, true, NWM, NWN, TM, TN, true>;
+    constexpr auto fn = qg_gemm_tile_kernel<QG_MODE_REQUANT, PATH_PIPE, true, NWM, NWN, TM, TN, true, KS>;
     e = qg_allow_smem<fn>(SMEM);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(fn, grid, block, SMEM, s, a, tiles_m, tiles_n);
   } else {
-    constexpr auto fn = qg_gemm_tile_kernel<QG_MODE_REQUANT, PATH_PIPE, false, NWM, NWN, TM, TN, true>;
+    constexpr auto fn = qg_gemm_tile_kernel<QG_MODE_REQUANT, PATH_PIPE, false, NWM, NWN, TM, TN, true, KS>;
     e = qg_allow_smem<fn>(SMEM);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(fn, grid, block, SMEM, s, a, tiles_m, tiles_n);
@@ -663,7 +672,9 @@ hipError_t launch_conv(const qg_gemm_args& a, hipStream_t s) {
 // Dense convolution: a.A is the NHWC image, a.M the number of output pixels, a.K = R*S*Cin with Cin % 64 == 0.
 hipError_t qg_launch_conv_dense(const qg_gemm_args& a, int kernel, hipStream_t s) {
   switch (kernel) {
-    case QG_KERNEL_TILE64: return launch_conv<2, 2, 1, 1>(a, s);
+    case QG_KERNEL_TILE64K1: return launch_conv<2, 2, 1, 1>(a, s);
+    case QG_KERNEL_TILE64: return launch_conv<2, 2, 1, 1, 2>(a, s);
+    case QG_KERNEL_TILE64K4: return launch_conv<2, 2, 1, 1, 4>(a, s);
     case QG_KERNEL_TILE128: return launch_conv<2, 2, 2, 2>(a, s);
     case QG_KERNEL_TILE128X256: return launch_conv<2, 2, 2, 4>(a, s);
     default: return hipErrorInvalidValue;
@@ -681,6 +692,7 @@ hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, int kernel, hipS
       if (a.K >= asm_stages(8) * BK) return launch_cfg<PATH_ASM, 2, 2, 2, 4>(a, mode, s);
       return launch_cfg<PATH_PIPE, 2, 2, 2, 4>(a, mode, s);
     case QG_KERNEL_TILE64K4: return launch_cfg<PATH_PIPE, 2, 2, 1, 1, 4>(a, mode, s);
+    case QG_KERNEL_TILE64K1: return launch_cfg<PATH_PIPE, 2, 2, 1, 1>(a, mode, s);
     case QG_KERNEL_TILE256:
       if (a.K >= NSTAGE * BK) return launch_cfg<PATH_ASM, 2, 2, 4, 4>(a, mode, s);
       return launch_cfg<PATH_PIPE, 2, 2, 2, 4>(a, mode, s);

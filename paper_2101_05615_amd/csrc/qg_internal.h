@@ -233,6 +233,7 @@ hipError_t qg_launch_pack_conv_w(const int8_t* W, int G, int RS, int8_t* packed,
                                  const int32_t* bzp_dev, int8_t* mfma_frags, hipStream_t s);
 // `kernel` is one of the QG_KERNEL_* ids of qgemm.h (never QG_KERNEL_AUTO: selection happens in api.hip)
 hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, int kernel, hipStream_t s);
+// kernel: QG_KERNEL_TILE64 / TILE64K4 / TILE64K1 / TILE128 / TILE128X256
 hipError_t qg_launch_conv_dense(const qg_gemm_args& a, int kernel, hipStream_t s);
 hipError_t qg_launch_gemm_skinny(const qg_gemm_args& a, int mode, int kernel, hipStream_t s);
 hipError_t qg_launch_quantize_a(const float* A, int M, int K, int lda, float inv_scale, int a_zp, uint8_t* Aq,

@@ -26,7 +26,7 @@ EXPORTS = [
     "qg_conv_dense_u8s8_requant", "qg_pack_b_transposed", "qg_probe_mfma_i8", "qg_probe_read",
 ]
 
-KERNEL_AUTO, KERNEL_LAST = 0, 8
+KERNEL_AUTO, KERNEL_LAST = 0, 9
 MAX_DISPATCH_RULES = 256
 
 
@@ -84,7 +84,7 @@ def _load():
     lib.qg_pack_b_outlier_sizes.argtypes = [i, i, sz, ctypes.POINTER(sz), ctypes.POINTER(sz), ctypes.POINTER(sz)]
     lib.qg_pack_b_outlier.argtypes = [vp, i, i, i, vp, i, sz, vp, vp, vp, vp, ctypes.POINTER(vp)]
     lib.qg_packed_b_nnz.argtypes = [vp]
-    lib.qg_conv_dense_u8s8_requant.argtypes = [vp, i, i, i, i, i, i, i, i, vp, ctypes.POINTER(RequantParams), vp, vp]
+    lib.qg_conv_dense_u8s8_requant.argtypes = [vp, i, i, i, i, i, i, i, i, vp, ctypes.POINTER(RequantParams), vp, vp, i]
     lib.qg_packed_b_nnz.restype = sz
     lib.qg_probe_mfma_i8.argtypes = [vp, vp, i, i, vp]
     lib.qg_probe_read.argtypes = [vp, sz, vp, i, vp]
@@ -446,8 +446,9 @@ def pack_conv_dense_w(Wt, b_zp):
     return pk
 
 
-def conv_dense_u8s8_requant(inp, Wp, a_zp, bias, scales, c_zp, relu, pad=1, stride=1, out=None):
-    """inp: uint8 cuda NHWC contiguous, Cin % 64 == 0; Wp from pack_conv_dense_w; returns uint8 NHWC."""
+def conv_dense_u8s8_requant(inp, Wp, a_zp, bias, scales, c_zp, relu, pad=1, stride=1, out=None, kernel="auto"):
+    """inp: uint8 cuda NHWC contiguous, Cin % 64 == 0; Wp from pack_conv_dense_w; returns uint8 NHWC.
+    kernel: "auto" or one of the 64- and 128-row tiled kernels (name or id)."""
     assert inp.is_cuda and inp.dtype == torch.uint8 and inp.dim() == 4 and inp.is_contiguous()
     Nb, H, W, C = inp.shape
     Ho = (H + 2 * pad - Wp.R) // stride + 1
@@ -457,7 +458,8 @@ def conv_dense_u8s8_requant(inp, Wp, a_zp, bias, scales, c_zp, relu, pad=1, stri
     assert out.is_contiguous() and out.shape == (Nb, Ho, Wo, Wp.N)
     p = _params(a_zp, bias, scales, c_zp, relu)
     _check(lib.qg_conv_dense_u8s8_requant(inp.data_ptr(), Nb, H, W, C, Wp.R, Wp.S, pad, stride, Wp.handle,
-                                          ctypes.byref(p), out.data_ptr(), _stream()), "qg_conv_dense_u8s8_requant")
+                                          ctypes.byref(p), out.data_ptr(), _stream(), kernel_id(kernel)),
+           "qg_conv_dense_u8s8_requant")
     return out
 
 

@@ -21,11 +21,14 @@ def env():
     return q, torch, torch.device("cuda:0"), oracle
 
 
-def run(c, q, torch, dev):
+CONV_KERNELS = ["auto", "tile64k1", "tile64", "tile64k4", "tile128", "tile128x256"]
+
+
+def run(c, q, torch, dev, kernel="auto"):
     Wp = q.pack_conv_dense_w(torch.from_numpy(np.ascontiguousarray(c.wgt[0])).to(dev), c.b_zp)
     bias = None if c.bias is None else torch.from_numpy(c.bias).to(dev)
     out = q.conv_dense_u8s8_requant(torch.from_numpy(c.inp).to(dev), Wp, c.a_zp, bias, torch.from_numpy(c.scales).to(dev),
-                                    c.c_zp, c.relu, pad=c.pad, stride=c.stride)
+                                    c.c_zp, c.relu, pad=c.pad, stride=c.stride, kernel=kernel)
     torch.cuda.synchronize()
     return out.cpu().numpy()
 
@@ -50,7 +53,9 @@ def test_dense_conv_bit_exact(env, cfg, per_channel, with_bias, relu):
     q, torch, dev, oracle = env
     say(f"dense conv {cfg} per_channel={per_channel}")
     c = wl.random_conv(11, G=1, per_channel=per_channel, with_bias=with_bias, relu=relu, **cfg)
-    assert_same(run(c, q, torch, dev), want(c, oracle), "dense conv")
+    ref = want(c, oracle)
+    for kernel in CONV_KERNELS:
+        assert_same(run(c, q, torch, dev, kernel), ref, f"dense conv, kernel {kernel}")
 
 
 def test_dense_conv_zero_weight_zero_points(env):
@@ -64,9 +69,24 @@ def test_dense_conv_resnet_block_shape(env):
     """56 x 56 x 64 -> 64, 3 x 3, the first residual stage of a ResNet at batch 4: 12544 pixel rows, K = 576."""
     q, torch, dev, oracle = env
     c = wl.random_conv(13, Nb=4, H=56, W=56, C=64, G=1, Cout=64)
-    got, ref = run(c, q, torch, dev), want(c, oracle)
-    assert_same(got, ref, "dense conv 4x56x56x64")
+    ref = want(c, oracle)
+    for kernel in CONV_KERNELS:
+        assert_same(run(c, q, torch, dev, kernel), ref, f"dense conv 4x56x56x64, kernel {kernel}")
     assert np.mean((ref > 0) & (ref < 255)) > 0.5
+
+
+def test_dense_conv_few_pixels_long_k(env):
+    """7 x 7 x 512 -> 128, 3 x 3: 98 pixel rows and K = 4608, the shape the K-split wave sets are for (72 k tiles:
+    an even and an odd share per set, taps that change inside a set's stride)."""
+    q, torch, dev, oracle = env
+    c = wl.random_conv(15, Nb=2, H=7, W=7, C=512, G=1, Cout=128)
+    ref = want(c, oracle)
+    for kernel in CONV_KERNELS:
+        assert_same(run(c, q, torch, dev, kernel), ref, f"dense conv 2x7x7x512, kernel {kernel}")
+    c = wl.random_conv(16, Nb=1, H=5, W=6, C=192, G=1, Cout=64)   # 27 k tiles: odd, and not a multiple of four
+    ref = want(c, oracle)
+    for kernel in CONV_KERNELS:
+        assert_same(run(c, q, torch, dev, kernel), ref, f"dense conv 1x5x6x192, kernel {kernel}")
 
 
 def test_dense_conv_errors(env):
@@ -78,9 +98,12 @@ def test_dense_conv_errors(env):
     sc = torch.from_numpy(c.scales).to(dev)
     p = q.RequantParams(c.a_zp, None, sc.data_ptr(), sc.numel(), c.c_zp, 0)
     L = q.lib.qg_conv_dense_u8s8_requant
-    assert L(inp.data_ptr(), 1, 5, 5, 64, 3, 3, 1, 1, Wp.handle, ctypes.byref(p), None, None) == q.ENULL
-    assert L(inp.data_ptr(), 1, 5, 5, 64, 1, 1, 0, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None) == q.EINVAL  # K mismatch
-    assert L(inp.data_ptr(), 1, 5, 5, 32, 3, 6, 1, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None) == q.EUNSUPPORTED  # Cin % 64
-    assert L(inp.data_ptr() + 4, 1, 5, 5, 64, 3, 3, 1, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None) == q.EUNSUPPORTED
-    assert L(inp.data_ptr(), 1, 1, 1, 64, 3, 3, 0, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None) == q.EINVAL  # filter larger than image
+    assert L(inp.data_ptr(), 1, 5, 5, 64, 3, 3, 1, 1, Wp.handle, ctypes.byref(p), None, None, 0) == q.ENULL
+    assert L(inp.data_ptr(), 1, 5, 5, 64, 1, 1, 0, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, 0) == q.EINVAL  # K mismatch
+    assert L(inp.data_ptr(), 1, 5, 5, 32, 3, 6, 1, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, 0) == q.EUNSUPPORTED  # Cin % 64
+    assert L(inp.data_ptr() + 4, 1, 5, 5, 64, 3, 3, 1, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, 0) == q.EUNSUPPORTED
+    assert L(inp.data_ptr(), 1, 1, 1, 64, 3, 3, 0, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, 0) == q.EINVAL  # filter larger than image
+    ok = (inp.data_ptr(), 1, 5, 5, 64, 3, 3, 1, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None)
+    assert L(*ok, q.KERNEL_LAST + 1) == q.EINVAL and L(*ok, -1) == q.EINVAL
+    assert L(*ok, q.kernel_id("tile256")) == q.EUNSUPPORTED and L(*ok, q.kernel_id("skinny16")) == q.EUNSUPPORTED
     torch.cuda.synchronize()

@@ -105,8 +105,10 @@ def test_random_convolution_cases(env, seed):
             say(tag)
         if dense:
             Wp = q.pack_conv_dense_w(up(np.ascontiguousarray(c.wgt[0])), c.b_zp)
+            kern = ["auto", "tile64k1", "tile64", "tile64k4", "tile128", "tile128x256"][int(rng.integers(0, 6))]
+            tag += f" kernel={kern}"
             got = q.conv_dense_u8s8_requant(up(c.inp), Wp, c.a_zp, up(c.bias), up(c.scales), c.c_zp, c.relu, pad=pad,
-                                            stride=stride)
+                                            stride=stride, kernel=kern)
         else:
             Wp = q.pack_conv_w(up(c.wgt), c.b_zp)
             got = q.conv_groupwise_u8s8_requant(up(c.inp), Wp, c.a_zp, up(c.bias), up(c.scales), c.c_zp, c.relu, pad,
