@@ -157,8 +157,8 @@ int qg_gemm_u8s8_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* 
  *   TILE256         256 x 256, four LDS stages, hand-scheduled loop (large shapes)
  *   TILE64K4        64 x 64 with K split over four wave sets (1024 threads; a few
  *                   tiles and a long K)
- *   TILE64K1        64 x 64 without a K split (256 threads, 24 KB of LDS: many small
- *                   workgroups per CU; the automatic choice uses it for convolutions)
+ *   TILE64K1        64 x 64 without a K split (256 threads, 24 KB of LDS: six small
+ *                   workgroups per CU; many tiles and a short K)
  * QG_KERNEL_AUTO picks by (M, N, K): first the rules installed with
  * qg_dispatch_set_rules (an offline autotune writes them), then a built-in
  * rule of thumb derived from the same measurements. */

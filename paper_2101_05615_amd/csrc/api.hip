@@ -79,6 +79,7 @@ const tile_cost k_tile_cost[] = {
     {QG_KERNEL_TILE128X256, 128, 256, 6.35, 0.344, 0.398, 2.85},
     {QG_KERNEL_TILE256, 256, 256, 9.9, 0.632, 0.76, 8.21},
     {QG_KERNEL_TILE64K4, 64, 64, 4.15, 0.089, 0.103, 2.1},
+    {QG_KERNEL_TILE64K1, 64, 64, 2.9, 0.239, 0.129, 0.222},
 };
 // The dense convolution runs the compiler-scheduled tile loops with the im2col addressing folded in; the same
 // formula, constants fitted to 3 x 3 and 1 x 1 layers of 1 .. 32 images (graph-replay times).  The 64 x 64 tile
