@@ -29,6 +29,10 @@
  *
  * Errors: every function returns 0 on success or one of the negative QG_E*
  * codes; nothing is printed, nothing aborts.  On error no output is written.
+ * An empty batch (M == 0, or Nb == 0 for a convolution) is a valid request:
+ * its data pointers (A, C, image, workspace) are not referenced and may be NULL,
+ * the other arguments are checked as usual, nothing is enqueued and the return
+ * is QG_OK; negative counts are QG_EINVAL.
  */
 #ifndef QGEMM_H
 #define QGEMM_H

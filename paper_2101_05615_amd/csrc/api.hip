@@ -424,9 +424,9 @@ size_t qg_gemm_workspace_bytes(int M, const qg_packed_b* Bp) {
 }
 
 static int gemm_common(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp, qg_gemm_args* a) {
-  if (!A_dev || !Bp) return QG_ENULL;
+  if (!Bp || (!A_dev && M != 0)) return QG_ENULL;  // the data pointers of an empty batch are not referenced
   if (Bp->kind != QG_KIND_GEMM || Bp->version != QG_LAYOUT_VERSION) return QG_EINVAL;
-  if (M <= 0 || lda < Bp->K) return QG_EINVAL;
+  if (M < 0 || lda < Bp->K) return QG_EINVAL;
   a->A = A_dev;
   a->Bp = Bp->packed;
   a->col_off = Bp->col_off;
@@ -460,7 +460,7 @@ int qg_gemm_u8s8_requant_kernel(const uint8_t* A_dev, int M, int lda, const qg_p
   if (rc != QG_OK) return rc;
   rc = resolve_kernel(Bp, M, &kernel);
   if (rc != QG_OK) return rc;
-  if (!C_dev) return QG_ENULL;
+  if (!C_dev && M != 0) return QG_ENULL;
   rc = check_requant(p, Bp->N);
   if (rc != QG_OK) return rc;
   if (ldc < Bp->N) return QG_EINVAL;
@@ -477,6 +477,7 @@ int qg_gemm_u8s8_requant_kernel(const uint8_t* A_dev, int M, int lda, const qg_p
   hipStream_t s = static_cast<hipStream_t>(stream);
   // 4-byte stores in the streaming kernels, 16-byte stores in the tiled ones
   a.c_vec = kernel <= QG_KERNEL_SKINNY64 ? (aligned(C_dev, 4) && (ldc % 4 == 0)) : (aligned(C_dev, 16) && (ldc % 16 == 0));
+  if (M == 0) return QG_OK;  // an empty batch: checked like any other, nothing to enqueue
   const hipError_t e = launch_gemm(a, QG_MODE_REQUANT, kernel, s);
   return e == hipSuccess ? QG_OK : QG_ELAUNCH;
 }
@@ -495,11 +496,12 @@ int qg_gemm_u8s8_acc32_kernel(const uint8_t* A_dev, int M, int lda, const qg_pac
   if (rc != QG_OK) return rc;
   rc = resolve_kernel(Bp, M, &kernel);
   if (rc != QG_OK) return rc;
-  if (!C32_dev) return QG_ENULL;
+  if (!C32_dev && M != 0) return QG_ENULL;
   if (ldc < Bp->N) return QG_EINVAL;
   a.C32 = C32_dev;
   a.rowsum_out = rowsum_dev;
   a.ldc = ldc;
+  if (M == 0) return QG_OK;
   const hipError_t e = launch_gemm(a, QG_MODE_ACC32, kernel, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? QG_OK : QG_ELAUNCH;
 }
@@ -522,7 +524,7 @@ int qg_gemm_u8s8_dequant_f32(const uint8_t* A_dev, int M, int lda, const qg_pack
   if (rc != QG_OK) return rc;
   rc = resolve_kernel(Bp, M, &kernel);
   if (rc != QG_OK) return rc;
-  if (!C_dev) return QG_ENULL;
+  if (!C_dev && M != 0) return QG_ENULL;
   rc = check_dequant(p, Bp->N);
   if (rc != QG_OK) return rc;
   if (ldc < Bp->N) return QG_EINVAL;
@@ -535,16 +537,18 @@ int qg_gemm_u8s8_dequant_f32(const uint8_t* A_dev, int M, int lda, const qg_pack
   a.Cf = C_dev;
   a.ldc = ldc;
   a.c_vec = aligned(C_dev, 16) && (ldc % 4 == 0);
+  if (M == 0) return QG_OK;
   const hipError_t e = launch_gemm(a, QG_MODE_DEQUANT, kernel, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? QG_OK : QG_ELAUNCH;
 }
 
 int qg_quantize_a_f32(const float* A_dev, int M, int K, int lda, float inv_scale, int a_zp, uint8_t* Aq_dev,
                       int ldq, void* stream) {
-  if (!A_dev || !Aq_dev) return QG_ENULL;
-  if (M <= 0 || K <= 0 || lda < K || ldq < K) return QG_EINVAL;
+  if ((!A_dev || !Aq_dev) && M != 0) return QG_ENULL;
+  if (M < 0 || K <= 0 || lda < K || ldq < K) return QG_EINVAL;
   if (a_zp < 0 || a_zp > 255 || !(inv_scale > 0.0f) || !isfinite(inv_scale)) return QG_EINVAL;
   if (!aligned(A_dev, 4)) return QG_EALIGN;
+  if (M == 0) return QG_OK;
   const hipError_t e =
       qg_launch_quantize_a(A_dev, M, K, lda, inv_scale, a_zp, Aq_dev, ldq, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? QG_OK : QG_ELAUNCH;
@@ -560,8 +564,10 @@ size_t qg_gemm_f32_workspace_bytes(int M, const qg_packed_b* Bp) {
 
 static int quantize_into_workspace(const float* A_dev, int M, int lda, float a_inv_scale, const qg_packed_b* Bp,
                                    int a_zp, void* workspace_dev, void* stream) {
-  if (!A_dev || !Bp) return QG_ENULL;
+  if (!Bp || (!A_dev && M != 0)) return QG_ENULL;
   if (Bp->kind != QG_KIND_GEMM || Bp->version != QG_LAYOUT_VERSION) return QG_EINVAL;
+  if (M == 0)  // an empty batch needs no workspace; the remaining arguments are still checked
+    return (lda < Bp->K || a_zp < 0 || a_zp > 255 || !(a_inv_scale > 0.0f) || !isfinite(a_inv_scale)) ? QG_EINVAL : QG_OK;
   if (!workspace_dev) return QG_EWORKSPACE;
   if (!aligned(workspace_dev, 16)) return QG_EALIGN;
   return qg_quantize_a_f32(A_dev, M, Bp->K, lda, a_inv_scale, a_zp, static_cast<uint8_t*>(workspace_dev),
@@ -572,15 +578,15 @@ int qg_gemm_f32s8_requant(const float* A_dev, int M, int lda, float a_inv_scale,
                           const qg_requant_params* p, uint8_t* C_dev, int ldc, void* workspace_dev,
                           void* stream, int kernel) {
   // every check of the second stage first, so that an error leaves nothing enqueued
-  if (!Bp || !p || !C_dev) return QG_ENULL;
+  if (!Bp || !p || (!C_dev && M != 0)) return QG_ENULL;
   if (Bp->kind != QG_KIND_GEMM || Bp->version != QG_LAYOUT_VERSION) return QG_EINVAL;
   int rc = check_requant(p, Bp->N);
   if (rc != QG_OK) return rc;
-  if (M <= 0 || ldc < Bp->N) return QG_EINVAL;
+  if (M < 0 || ldc < Bp->N) return QG_EINVAL;
   rc = resolve_kernel(Bp, M, &kernel);
   if (rc != QG_OK) return rc;
   rc = quantize_into_workspace(A_dev, M, lda, a_inv_scale, Bp, p->a_zp, workspace_dev, stream);
-  if (rc != QG_OK) return rc;
+  if (rc != QG_OK || M == 0) return rc;
   return qg_gemm_u8s8_requant_kernel(static_cast<const uint8_t*>(workspace_dev), M, f32_ldq(Bp), Bp, p, C_dev, ldc,
                                      nullptr, stream, kernel);
 }
@@ -588,16 +594,16 @@ int qg_gemm_f32s8_requant(const float* A_dev, int M, int lda, float a_inv_scale,
 int qg_gemm_f32s8_dequant_f32(const float* A_dev, int M, int lda, float a_inv_scale, const qg_packed_b* Bp,
                               const qg_dequant_params* p, float* C_dev, int ldc, void* workspace_dev,
                               void* stream, int kernel) {
-  if (!Bp || !p || !C_dev) return QG_ENULL;
+  if (!Bp || !p || (!C_dev && M != 0)) return QG_ENULL;
   if (Bp->kind != QG_KIND_GEMM || Bp->version != QG_LAYOUT_VERSION) return QG_EINVAL;
   int rc = check_dequant(p, Bp->N);
   if (rc != QG_OK) return rc;
-  if (M <= 0 || ldc < Bp->N) return QG_EINVAL;
+  if (M < 0 || ldc < Bp->N) return QG_EINVAL;
   rc = resolve_kernel(Bp, M, &kernel);
   if (rc != QG_OK) return rc;
   if (!aligned(C_dev, 4)) return QG_EALIGN;
   rc = quantize_into_workspace(A_dev, M, lda, a_inv_scale, Bp, p->a_zp, workspace_dev, stream);
-  if (rc != QG_OK) return rc;
+  if (rc != QG_OK || M == 0) return rc;
   return qg_gemm_u8s8_dequant_f32(static_cast<const uint8_t*>(workspace_dev), M, f32_ldq(Bp), Bp, p, C_dev, ldc,
                                   nullptr, stream, kernel);
 }
@@ -605,13 +611,13 @@ int qg_gemm_f32s8_dequant_f32(const float* A_dev, int M, int lda, float a_inv_sc
 int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int Cin, int R, int S, int pad,
                                int stride, const qg_packed_b* Wp, const qg_requant_params* p, uint8_t* out_nhwc,
                                void* stream, int kernel) {
-  if (!in_nhwc || !Wp || !out_nhwc) return QG_ENULL;
+  if (!Wp || ((!in_nhwc || !out_nhwc) && Nb != 0)) return QG_ENULL;
   if (Wp->kind != QG_KIND_GEMM || Wp->version != QG_LAYOUT_VERSION) return QG_EINVAL;
   if (kernel < QG_KERNEL_AUTO || kernel > QG_KERNEL_LAST) return QG_EINVAL;
   if (kernel != QG_KERNEL_AUTO && kernel != QG_KERNEL_TILE64 && kernel != QG_KERNEL_TILE64K4 &&
       kernel != QG_KERNEL_TILE64K1 && kernel != QG_KERNEL_TILE128 && kernel != QG_KERNEL_TILE128X256)
     return QG_EUNSUPPORTED;
-  if (Nb <= 0 || H <= 0 || W <= 0 || Cin <= 0 || R <= 0 || S <= 0 || pad < 0 || stride <= 0) return QG_EINVAL;
+  if (Nb < 0 || H <= 0 || W <= 0 || Cin <= 0 || R <= 0 || S <= 0 || pad < 0 || stride <= 0) return QG_EINVAL;
   if ((long long)R * S * Cin != Wp->K) return QG_EINVAL;
   int rc = check_requant(p, Wp->N);
   if (rc != QG_OK) return rc;
@@ -661,6 +667,7 @@ int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int
       if (us < best_us) best_us = us, kernel = c.kernel;
     }
   }
+  if (Nb == 0) return QG_OK;  // an empty batch
   const hipError_t e = qg_launch_conv_dense(a, kernel, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? QG_OK : QG_ELAUNCH;
 }
@@ -727,9 +734,9 @@ int qg_pack_conv_w(const int8_t* W_dev, int G, int R, int S, int Cg, int Og, con
 int qg_conv_groupwise_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int C, int pad,
                                    int stride, const qg_packed_b* Wp, const qg_requant_params* p,
                                    uint8_t* out_nhwc, void* stream) {
-  if (!in_nhwc || !Wp || !out_nhwc) return QG_ENULL;
+  if (!Wp || ((!in_nhwc || !out_nhwc) && Nb != 0)) return QG_ENULL;
   if (Wp->kind != QG_KIND_CONV || Wp->version != QG_LAYOUT_VERSION) return QG_EINVAL;
-  if (Nb <= 0 || H <= 0 || W <= 0 || C <= 0 || pad < 0 || stride <= 0) return QG_EINVAL;
+  if (Nb < 0 || H <= 0 || W <= 0 || C <= 0 || pad < 0 || stride <= 0) return QG_EINVAL;
   if (C != Wp->G * Wp->Cg) return QG_EINVAL;
   int rc = check_requant(p, Wp->N);
   if (rc != QG_OK) return rc;
@@ -764,6 +771,7 @@ int qg_conv_groupwise_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W,
   a.clamp_lo = (float)(lo - p->c_zp);
   a.clamp_hi = (float)(255 - p->c_zp);
   a.has_bzp = Wp->has_bzp;
+  if (Nb == 0) return QG_OK;  // an empty batch
   hipError_t e = qg_launch_conv_group(a, Wp->R * Wp->S, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? QG_OK : QG_ELAUNCH;
 }

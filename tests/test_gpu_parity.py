@@ -326,7 +326,7 @@ def test_runtime_argument_errors(env):
     p = q.RequantParams(128, None, scales.data_ptr(), 1, 0, 0)
     assert q.lib.qg_gemm_u8s8_requant(A.data_ptr(), 64, 127, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None) == q.EINVAL
     assert q.lib.qg_gemm_u8s8_requant(A.data_ptr(), 64, 128, Bp.handle, ctypes.byref(p), C.data_ptr(), 63, None, None) == q.EINVAL
-    assert q.lib.qg_gemm_u8s8_requant(A.data_ptr(), 0, 128, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None) == q.EINVAL
+    assert q.lib.qg_gemm_u8s8_requant(A.data_ptr(), -1, 128, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None) == q.EINVAL
     assert q.lib.qg_gemm_u8s8_requant(A.data_ptr(), 64, 128, Bp.handle, ctypes.byref(p), None, 64, None, None) == q.ENULL
     p.scales = None
     assert q.lib.qg_gemm_u8s8_requant(A.data_ptr(), 64, 128, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None) == q.ENULL
@@ -339,6 +339,60 @@ def test_runtime_argument_errors(env):
     p = q.RequantParams(128, None, scales.data_ptr(), 1, 0, 0)
     assert q.lib.qg_gemm_u8s8_requant(A.data_ptr(), 64, 128, Wp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None) == q.EINVAL
     torch.cuda.synchronize()
+
+
+def test_empty_batch_is_a_checked_no_op(env):
+    """M == 0 (Nb == 0 for the convolutions): QG_OK, nothing written; the other arguments are still checked."""
+    import ctypes
+    q, torch, dev, oracle = env
+    c = wl.config1_tiny()
+    A, B, bias, scales, C, _ = dev_case(c, torch, dev)
+    Bp = q.pack_b(B, c.b_zp)
+    L = q.lib
+    C.fill_(0x5A)
+    C32 = torch.full((64, 64), 77, dtype=torch.int32, device=dev)
+    Cf = torch.full((64, 64), 7.0, dtype=torch.float32, device=dev)
+    Af = torch.zeros((64, 128), dtype=torch.float32, device=dev)
+    p = q.RequantParams(128, None, scales.data_ptr(), 1, 0, 0)
+    d = q.DequantParams(128, None, scales.data_ptr(), 1, 0)
+    assert L.qg_gemm_u8s8_requant(A.data_ptr(), 0, 128, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None) == q.OK
+    assert L.qg_gemm_u8s8_acc32(A.data_ptr(), 0, 128, Bp.handle, C32.data_ptr(), 64, None, None, None) == q.OK
+    assert L.qg_gemm_u8s8_dequant_f32(A.data_ptr(), 0, 128, Bp.handle, ctypes.byref(d), Cf.data_ptr(), 64, None, None, 0) == q.OK
+    assert L.qg_quantize_a_f32(Af.data_ptr(), 0, 128, 128, 1.0, 128, A.data_ptr(), 128, None) == q.OK
+    assert L.qg_gemm_f32s8_requant(Af.data_ptr(), 0, 128, 1.0, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None, 0) == q.OK
+    assert L.qg_gemm_f32s8_dequant_f32(Af.data_ptr(), 0, 128, 1.0, Bp.handle, ctypes.byref(d), Cf.data_ptr(), 64, None, None, 0) == q.OK
+    # the data pointers of an empty batch are not referenced (an empty tensor has none)
+    assert L.qg_gemm_u8s8_requant(None, 0, 128, Bp.handle, ctypes.byref(p), None, 64, None, None) == q.OK
+    assert L.qg_gemm_f32s8_requant(None, 0, 128, 1.0, Bp.handle, ctypes.byref(p), None, 64, None, None, 0) == q.OK
+    # still checked: a short leading dimension, a bad zero point, a missing descriptor or parameter block
+    assert L.qg_gemm_u8s8_requant(A.data_ptr(), 0, 127, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None) == q.EINVAL
+    assert L.qg_gemm_u8s8_requant(A.data_ptr(), 0, 128, None, ctypes.byref(p), C.data_ptr(), 64, None, None) == q.ENULL
+    assert L.qg_gemm_u8s8_requant(A.data_ptr(), 0, 128, Bp.handle, None, C.data_ptr(), 64, None, None) == q.ENULL
+    assert L.qg_gemm_f32s8_requant(Af.data_ptr(), 0, 127, 1.0, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None, 0) == q.EINVAL
+    bad = q.RequantParams(300, None, scales.data_ptr(), 1, 0, 0)
+    assert L.qg_gemm_u8s8_requant(A.data_ptr(), 0, 128, Bp.handle, ctypes.byref(bad), C.data_ptr(), 64, None, None) == q.EINVAL
+    # convolutions with no image
+    cg = wl.random_conv(3, Nb=1, H=5, W=5, C=64, G=16)
+    Wg = q.pack_conv_w(torch.from_numpy(cg.wgt).to(dev), cg.b_zp)
+    cd = wl.random_conv(4, Nb=1, H=5, W=5, C=64, G=1, Cout=64)
+    Wd = q.pack_conv_dense_w(torch.from_numpy(np.ascontiguousarray(cd.wgt[0])).to(dev), cd.b_zp)
+    x = torch.zeros((1, 5, 5, 64), dtype=torch.uint8, device=dev)
+    y = torch.full((1, 5, 5, 64), 0x5A, dtype=torch.uint8, device=dev)
+    sg = torch.from_numpy(cg.scales).to(dev)
+    pg = q.RequantParams(cg.a_zp, None, sg.data_ptr(), sg.numel(), cg.c_zp, 0)
+    assert L.qg_conv_groupwise_u8s8_requant(x.data_ptr(), 0, 5, 5, 64, 1, 1, Wg.handle, ctypes.byref(pg), y.data_ptr(), None) == q.OK
+    sd = torch.from_numpy(cd.scales).to(dev)
+    pd = q.RequantParams(cd.a_zp, None, sd.data_ptr(), sd.numel(), cd.c_zp, 0)
+    assert L.qg_conv_dense_u8s8_requant(x.data_ptr(), 0, 5, 5, 64, 3, 3, 1, 1, Wd.handle, ctypes.byref(pd), y.data_ptr(), None, 0) == q.OK
+    assert L.qg_conv_dense_u8s8_requant(x.data_ptr(), -1, 5, 5, 64, 3, 3, 1, 1, Wd.handle, ctypes.byref(pd), y.data_ptr(), None, 0) == q.EINVAL
+    # through the binding: empty tensors in, empty tensors out
+    e = q.gemm_u8s8_requant(torch.empty((0, 128), dtype=torch.uint8, device=dev), 128, Bp, None, scales, 0, False)
+    assert tuple(e.shape) == (0, 64)
+    ec = q.conv_dense_u8s8_requant(torch.empty((0, 5, 5, 64), dtype=torch.uint8, device=dev), Wd, cd.a_zp, None, sd,
+                                   cd.c_zp, False)
+    assert tuple(ec.shape) == (0, 5, 5, 64)
+    torch.cuda.synchronize()
+    assert bool((C == 0x5A).all()) and bool((C32 == 77).all()) and bool((Cf == 7.0).all()) and bool((y == 0x5A).all())
 
 
 def test_measurement_probes_run(env):
