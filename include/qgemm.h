@@ -163,6 +163,8 @@ int qg_gemm_u8s8_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* 
  *                   tiles and a long K)
  *   TILE64K1        64 x 64 without a K split (256 threads, 24 KB of LDS: six small
  *                   workgroups per CU; many tiles and a short K)
+ *   TILE64X32K8     64 x 32 with K split over eight sets of two waves (1024 threads;
+ *                   at most one workgroup per CU and a long K: M up to 128 with N = K = 4096)
  * QG_KERNEL_AUTO picks by (M, N, K): first the rules installed with
  * qg_dispatch_set_rules (an offline autotune writes them), then a built-in
  * rule of thumb derived from the same measurements. */
@@ -176,7 +178,8 @@ int qg_gemm_u8s8_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* 
 #define QG_KERNEL_TILE256 7
 #define QG_KERNEL_TILE64K4 8
 #define QG_KERNEL_TILE64K1 9
-#define QG_KERNEL_LAST 9
+#define QG_KERNEL_TILE64X32K8 10
+#define QG_KERNEL_LAST 10
 
 /* Name of a kernel id ("skinny16", "tile128x256", ...; "auto" for 0), NULL if invalid. */
 const char* qg_kernel_name(int kernel);

@@ -80,6 +80,7 @@ const tile_cost k_tile_cost[] = {
     {QG_KERNEL_TILE256, 256, 256, 9.9, 0.632, 0.76, 8.21},
     {QG_KERNEL_TILE64K4, 64, 64, 4.15, 0.089, 0.103, 2.1},
     {QG_KERNEL_TILE64K1, 64, 64, 2.9, 0.239, 0.129, 0.222},
+    {QG_KERNEL_TILE64X32K8, 64, 32, 4.08, 0.0584, 0.0656, 2.57},
 };
 // The dense convolution runs the compiler-scheduled tile loops with the im2col addressing folded in; the same
 // formula, constants fitted to 3 x 3 and 1 x 1 layers of 1 .. 32 images (graph-replay times).  The 64 x 64 tile
@@ -218,7 +219,7 @@ extern "C" {
 const char* qg_kernel_name(int kernel) {
   static const char* const names[] = {"auto",   "skinny16", "skinny32",    "skinny64",
                                       "tile64", "tile128",  "tile128x256", "tile256",
-                                      "tile64k4", "tile64k1"};
+                                      "tile64k4", "tile64k1", "tile64x32k8"};
   return (kernel >= 0 && kernel <= QG_KERNEL_LAST) ? names[kernel] : nullptr;
 }
 

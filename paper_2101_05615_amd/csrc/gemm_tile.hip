@@ -143,7 +143,7 @@ template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, boo
 __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) / KS) void qg_gemm_tile_kernel(const qg_gemm_args p,
                                                                                                 int tiles_m,
                                                                                                 int tiles_n) {
-  static_assert(KS == 1 || ((KS == 2 || KS == 4) && PATH == PATH_PIPE), "K split: wave sets on the pipelined path");
+  static_assert(KS == 1 || ((KS == 2 || KS == 4 || KS == 8) && PATH == PATH_PIPE), "K split: wave sets on the pipelined path");
   constexpr int NW = NWM * NWN, NT = NW * KS * 64;  // NW: waves of one set; NT: threads of the workgroup
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
   constexpr int A_STAGE = BM * BK, B_STAGE = BN * BK, STAGE = A_STAGE + B_STAGE;
@@ -693,6 +693,7 @@ hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, int kernel, hipS
       return launch_cfg<PATH_PIPE, 2, 2, 2, 4>(a, mode, s);
     case QG_KERNEL_TILE64K4: return launch_cfg<PATH_PIPE, 2, 2, 1, 1, 4>(a, mode, s);
     case QG_KERNEL_TILE64K1: return launch_cfg<PATH_PIPE, 2, 2, 1, 1>(a, mode, s);
+    case QG_KERNEL_TILE64X32K8: return launch_cfg<PATH_PIPE, 2, 1, 1, 1, 8>(a, mode, s);  // two waves per set
     case QG_KERNEL_TILE256:
       if (a.K >= NSTAGE * BK) return launch_cfg<PATH_ASM, 2, 2, 4, 4>(a, mode, s);
       return launch_cfg<PATH_PIPE, 2, 2, 2, 4>(a, mode, s);

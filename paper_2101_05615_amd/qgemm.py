@@ -26,7 +26,7 @@ EXPORTS = [
     "qg_conv_dense_u8s8_requant", "qg_pack_b_transposed", "qg_probe_mfma_i8", "qg_probe_read",
 ]
 
-KERNEL_AUTO, KERNEL_LAST = 0, 9
+KERNEL_AUTO, KERNEL_LAST = 0, 10
 MAX_DISPATCH_RULES = 256
 
 

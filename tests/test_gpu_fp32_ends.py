@@ -10,7 +10,7 @@ from gpu_util import assert_same, dev_case, say
 
 pytestmark = pytest.mark.gpu
 
-KERNELS = ["auto", "skinny16", "skinny32", "skinny64", "tile64", "tile128", "tile128x256", "tile256", "tile64k4", "tile64k1"]
+KERNELS = ["auto", "skinny16", "skinny32", "skinny64", "tile64", "tile128", "tile128x256", "tile256", "tile64k4", "tile64k1", "tile64x32k8"]
 
 
 @pytest.fixture(scope="module")

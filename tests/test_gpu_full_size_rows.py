@@ -85,7 +85,7 @@ def test_dense_conv_layers_at_batch_32(env, H, C):
 
 
 @pytest.mark.parametrize("shape,kernels", [
-    ((128, 4096, 4096), ["auto", "tile64", "tile64k4", "skinny64"]),
+    ((128, 4096, 4096), ["auto", "tile64", "tile64k4", "tile64x32k8", "skinny64"]),
     ((2048, 2048, 2048), ["auto", "tile128", "tile128x256"]),
     ((4096, 1024, 1024), ["auto", "tile128", "tile256"]),
     ((16384, 256, 512), ["auto", "tile64", "tile256"]),

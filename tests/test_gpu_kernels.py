@@ -8,7 +8,7 @@ from gpu_util import assert_same, dev_case, oracle_gemm, say
 
 pytestmark = pytest.mark.gpu
 
-KERNELS = ["skinny16", "skinny32", "skinny64", "tile64", "tile128", "tile128x256", "tile256", "tile64k4", "tile64k1"]
+KERNELS = ["skinny16", "skinny32", "skinny64", "tile64", "tile128", "tile128x256", "tile256", "tile64k4", "tile64k1", "tile64x32k8"]
 
 # (M, N, K): 1, 2, 3, 4 and many 64-deep tiles on the pipelined paths (K % 64 == 0), ragged M and N that
 # span several tiles of every shape, and a ragged K that takes the general path
