@@ -216,6 +216,7 @@ inline hipError_t qg_allow_smem(int bytes) {
   if (dev >= 0 && dev < 64 && allowed[dev] >= bytes) return hipSuccess;
   e = hipFuncSetAttribute((const void*)Fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
   if (e == hipSuccess && dev >= 0 && dev < 64) allowed[dev] = bytes;
+  if (e != hipSuccess) (void)hipGetLastError();  // reported through the return value; not left for the next call to find
   return e;
 }
 #endif
