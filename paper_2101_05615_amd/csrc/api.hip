@@ -627,6 +627,10 @@ int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int
   if (Wp->split || Cin % 64 != 0 || !aligned(in_nhwc, 16)) return QG_EUNSUPPORTED;
   // 32-bit byte offsets into the image (tap offsets included) and 32-bit pixel counts
   if ((uint64_t)Nb * H * W * Cin >= (1ull << 30) || (uint64_t)Nb * Ho * Wo >= (1ull << 31) / 4) return QG_EUNSUPPORTED;
+  // A 1 x 1 filter with unit stride and no padding is the plain GEMM over the pixel rows (lda = Cin): it takes
+  // the GEMM's own kernels and choice, hand-scheduled loops included; the bytes are the same either way.
+  if (R == 1 && S == 1 && pad == 0 && stride == 1)
+    return qg_gemm_u8s8_requant_kernel(in_nhwc, Nb * H * W, Cin, Wp, p, out_nhwc, Wp->N, nullptr, stream, kernel);
   qg_gemm_args a = {};
   a.A = in_nhwc;
   a.Bp = Wp->packed;
