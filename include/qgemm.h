@@ -117,9 +117,26 @@ int qg_packed_b_n(const qg_packed_b* p);
 
 /* ---- run time ------------------------------------------------------------ */
 
-/* Scratch bytes qg_gemm_* needs for this M (the role of the paper's C_buffer,
- * Appendix A).  May be 0, in which case workspace_dev may be NULL. */
+/* Scratch for the GEMM calls: the role of the paper's caller-preallocated C_buffer
+ * (Appendix A).  A shape with few columns and a long K is split over K ACROSS
+ * workgroups so that the whole chip streams the weights; the int32 partial
+ * tiles meet in this workspace and the slice that arrives last runs the output
+ * pipeline.  Integer sums: every split gives the same bytes as no split.
+ *
+ * qg_gemm_workspace_bytes: bytes qg_gemm_u8s8_requant / _acc32 / _dequant_f32
+ * (and their _kernel forms with QG_KERNEL_AUTO) want for this M; 0 when the
+ * built-in choice does not split, in which case workspace_dev may be NULL.
+ * Passing NULL is always allowed: the call then never splits.
+ *
+ * Protocol: allocate (16-byte aligned), call qg_gemm_workspace_init ONCE (it
+ * enqueues a kernel that zero-fills it; no copy, no memset, so it may be
+ * recorded into a graph), then pass it to any number of calls that run one
+ * after another on one stream: every call leaves the workspace as it found it.
+ * Calls that may overlap in time (different streams) need different
+ * workspaces.  A workspace of qg_gemm_workspace_bytes(M, Bp) also serves any
+ * smaller M with the same Bp. */
 size_t qg_gemm_workspace_bytes(int M, const qg_packed_b* Bp);
+int qg_gemm_workspace_init(void* workspace_dev, size_t bytes, void* stream);
 
 /* The fused hot path (Sec. 2.1 Eq. (2) + requantization; Sec. 2.2 fusion of
  * row-offset computation into the A staging pass and of the output pipeline
@@ -212,6 +229,25 @@ int qg_gemm_u8s8_requant_kernel(const uint8_t* A_dev, int M, int lda, const qg_p
 int qg_gemm_u8s8_acc32_kernel(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp,
                               int32_t* C32_dev, int ldc, int32_t* rowsum_dev, void* workspace_dev,
                               void* stream, int kernel);
+
+/* The K split chosen by the caller (the tests compare every factor with the
+ * oracle; the autotuner times them).  Streaming kernels only:
+ *   kernel  QG_KERNEL_AUTO or QG_KERNEL_SKINNY16/32/64; a TILE kernel with
+ *           ksplit > 1 is QG_EUNSUPPORTED
+ *   ksplit  0 = built-in choice, 1 = no split, up to 64 slices of K; the factor
+ *           actually used (qg_gemm_splitk_factor) never leaves a slice without a
+ *           64-deep block of K
+ *   workspace_dev / workspace_bytes  as above, at least
+ *           qg_gemm_splitk_workspace_bytes(M, Bp, kernel, ksplit) bytes:
+ *           QG_EWORKSPACE when NULL or too small while the factor used exceeds 1. */
+size_t qg_gemm_splitk_workspace_bytes(int M, const qg_packed_b* Bp, int kernel, int ksplit);
+int qg_gemm_splitk_factor(int M, const qg_packed_b* Bp, int kernel, int ksplit);
+int qg_gemm_u8s8_requant_splitk(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp,
+                                const qg_requant_params* p, uint8_t* C_dev, int ldc, void* workspace_dev,
+                                size_t workspace_bytes, void* stream, int kernel, int ksplit);
+int qg_gemm_u8s8_acc32_splitk(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp, int32_t* C32_dev,
+                              int ldc, int32_t* rowsum_dev, void* workspace_dev, size_t workspace_bytes,
+                              void* stream, int kernel, int ksplit);
 
 /* ---- the other ends of the pipeline (Appendix B) --------------------------- */
 

@@ -13,6 +13,9 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off",                      # the fp32 requantization sequence must not be fused
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # leading scalar kernel arguments arrive in scalar registers with the wave (the microsecond kernels declare
+    # what they need first that way); kernels whose first argument is a struct are unaffected
+    "-mllvm", "-amdgpu-kernarg-preload-count=16",
     "-Wno-unused-command-line-argument",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
@@ -22,14 +25,36 @@ def sources():
     return [os.path.join(CSRC, s) for s in SOURCES]
 
 
-def build_lib(verbose=False, extra=()):
-    cmd = ["hipcc"] + FLAGS + list(extra) + sources() + ["-o", LIB]
+def build_lib(verbose=False, extra=(), incremental=False):
+    """One object per source file (compiled in parallel), then one link.  incremental=True recompiles only the
+    sources that are newer than their object (or older than a header); the default compiles everything."""
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    compile_flags = [f for f in FLAGS if f != "-shared"]
+    headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".h", ".inc"))]
+    headers.append(os.path.join(ROOT, "include", "qgemm.h"))
+    newest_header = max(os.path.getmtime(h) for h in headers)
+    procs, objs = [], []
+    for src in sources():
+        obj = os.path.join(objdir, os.path.basename(src) + ".o")
+        objs.append(obj)
+        if incremental and not extra and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header):
+            continue
+        cmd = ["hipcc"] + compile_flags + list(extra) + ["-c", src, "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        procs.append((cmd, subprocess.Popen(cmd)))
+    for cmd, pr in procs:
+        if pr.wait() != 0:
+            raise subprocess.CalledProcessError(pr.returncode, cmd)
+    link = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB]
     if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+        print(" ".join(link), flush=True)
+    subprocess.run(link, check=True)
     return LIB
 
 
 if __name__ == "__main__":
-    build_lib(verbose=True, extra=sys.argv[1:])
+    inc = "--incremental" in sys.argv[1:]
+    build_lib(verbose=True, extra=[a for a in sys.argv[1:] if a != "--incremental"], incremental=inc)
     print("built", LIB)

@@ -212,6 +212,76 @@ int resolve_kernel(const qg_packed_b* Bp, int M, int* kernel) {
   return QG_OK;
 }
 
+// ---- K split across workgroups (streaming kernels; the caller's workspace is the paper's C_buffer, Appendix A)
+constexpr int kSlotInts = 64 * 4 + 16;   // one (K slice, row block of 16) slot: 64 lanes x 4 partial sums + 16 row sums
+constexpr int kMaxKsplit = 64;
+
+struct splitk_layout {
+  size_t cnt_ints, slot_ints;
+  size_t bytes() const { return (cnt_ints + slot_ints) * sizeof(int32_t); }
+};
+// counters first (one per row block of 16 and fragment column, rounded up to 256 bytes), then the slots
+splitk_layout splitk_ws(int kernel, int M, int N, int ksplit) {
+  const int rows = 16 << (kernel - QG_KERNEL_SKINNY16);
+  const size_t units = (size_t)ceil_div(M, rows) * (size_t)(2 * ceil_div(N, 32)) * (size_t)(rows / 16);
+  return {(units + 63) / 64 * 64, units * (size_t)ksplit * kSlotInts};
+}
+// slices that are all non-empty: at most one per 64-deep block of K (a pair of blocks for 4-bit weights)
+int clamp_ksplit(const qg_packed_b* Bp, int ksplit) {
+  const int blocks = Bp->K_pad / QG_FRAG_K / (Bp->split ? 2 : 1);
+  if (ksplit > blocks) ksplit = blocks;
+  const int per = ceil_div(blocks, ksplit);
+  return ceil_div(blocks, per);
+}
+// Built-in choice of the split: as many slices as it takes to give every CU a workgroup, while every wave of
+// a slice still has two 64-deep blocks of K to stream.
+int auto_ksplit(int kernel, int M, const qg_packed_b* Bp) {
+  if (kernel < QG_KERNEL_SKINNY16 || kernel > QG_KERNEL_SKINNY64) return 1;
+  const int rows = 16 << (kernel - QG_KERNEL_SKINNY16);
+  const long long wgs = (long long)ceil_div(M, rows) * (2 * ceil_div(Bp->N, 32));
+  if (wgs * 2 > 256) return 1;
+  int s = (int)(256 / wgs);
+  const int by_depth = Bp->K_pad / QG_FRAG_K / 32;  // 16 waves x 2 blocks
+  if (s > by_depth) s = by_depth;
+  if (s > 16) s = 16;
+  return s < 2 ? 1 : clamp_ksplit(Bp, s);
+}
+// ksplit_req: 0 = built-in choice (1 without a workspace), otherwise the caller's.  Fills the workspace fields of `a`.
+int resolve_ksplit(const qg_packed_b* Bp, int M, int kernel, int ksplit_req, void* workspace_dev, size_t workspace_bytes,
+                   bool bytes_known, qg_gemm_args* a) {
+  a->ksplit = 1;
+  a->ks_per = Bp->K_pad / QG_FRAG_K;
+  a->ws_cnt = a->ws_slots = nullptr;
+  if (ksplit_req < 0 || ksplit_req > kMaxKsplit) return QG_EINVAL;
+  if (M == 0) return QG_OK;
+  int s = ksplit_req;
+  if (kernel > QG_KERNEL_SKINNY64) {
+    if (s > 1) return QG_EUNSUPPORTED;  // the tiled kernels keep K inside the workgroup
+    return QG_OK;
+  }
+  if (s == 0) s = workspace_dev ? auto_ksplit(kernel, M, Bp) : 1;
+  s = clamp_ksplit(Bp, s);
+  if (s <= 1) return QG_OK;
+  if (!workspace_dev) return QG_EWORKSPACE;
+  if (!aligned(workspace_dev, 16)) return QG_EALIGN;
+  const splitk_layout w = splitk_ws(kernel, M, Bp->N, s);
+  if (bytes_known && workspace_bytes < w.bytes()) return QG_EWORKSPACE;
+  a->ksplit = s;
+  {
+    const int unit = Bp->split ? 2 : 1, blocks = Bp->K_pad / QG_FRAG_K / unit;
+    a->ks_per = ceil_div(blocks, s) * unit;
+  }
+  a->ws_cnt = static_cast<int32_t*>(workspace_dev);
+  a->ws_slots = a->ws_cnt + w.cnt_ints;
+  return QG_OK;
+}
+
+__global__ void qg_fill_zero_kernel(int32_t* p, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = 0;
+}
+
 }  // namespace
 
 extern "C" {
@@ -419,9 +489,38 @@ int qg_pack_b_outlier(const int8_t* B_dev, int K, int N, int ldb, const int32_t*
 size_t qg_packed_b_nnz(const qg_packed_b* p) { return (p && p->split) ? (size_t)p->nnz : 0; }
 
 size_t qg_gemm_workspace_bytes(int M, const qg_packed_b* Bp) {
-  (void)M;
-  (void)Bp;
-  return 0;  // K is split only inside a workgroup; partial sums live in LDS
+  if (!Bp || M <= 0 || Bp->kind != QG_KIND_GEMM) return 0;
+  int kernel = QG_KERNEL_AUTO;
+  if (resolve_kernel(Bp, M, &kernel) != QG_OK) return 0;
+  const int s = auto_ksplit(kernel, M, Bp);
+  return s > 1 ? splitk_ws(kernel, M, Bp->N, s).bytes() : 0;
+}
+
+size_t qg_gemm_splitk_workspace_bytes(int M, const qg_packed_b* Bp, int kernel, int ksplit) {
+  if (!Bp || M <= 0 || Bp->kind != QG_KIND_GEMM || ksplit < 0 || ksplit > kMaxKsplit) return 0;
+  if (resolve_kernel(Bp, M, &kernel) != QG_OK || kernel > QG_KERNEL_SKINNY64) return 0;
+  const int s = ksplit == 0 ? auto_ksplit(kernel, M, Bp) : clamp_ksplit(Bp, ksplit);
+  return s > 1 ? splitk_ws(kernel, M, Bp->N, s).bytes() : 0;
+}
+
+int qg_gemm_splitk_factor(int M, const qg_packed_b* Bp, int kernel, int ksplit) {
+  if (!Bp || Bp->kind != QG_KIND_GEMM) return QG_ENULL;
+  if (M <= 0 || ksplit < 0 || ksplit > kMaxKsplit) return QG_EINVAL;
+  const int rc = resolve_kernel(Bp, M, &kernel);
+  if (rc != QG_OK) return rc;
+  if (kernel > QG_KERNEL_SKINNY64) return 1;
+  return ksplit == 0 ? auto_ksplit(kernel, M, Bp) : clamp_ksplit(Bp, ksplit);
+}
+
+int qg_gemm_workspace_init(void* workspace_dev, size_t bytes, void* stream) {
+  if (bytes == 0) return QG_OK;
+  if (!workspace_dev) return QG_ENULL;
+  if (!aligned(workspace_dev, 16) || bytes % 4 != 0) return QG_EALIGN;
+  const size_t n = bytes / 4;
+  const unsigned blocks = (unsigned)((n + 255) / 256 < 2048 ? (n + 255) / 256 : 2048);
+  hipLaunchKernelGGL(qg_fill_zero_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<int32_t*>(workspace_dev), n);
+  return hipGetLastError() == hipSuccess ? QG_OK : QG_ELAUNCH;
 }
 
 static int gemm_common(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp, qg_gemm_args* a) {
@@ -443,19 +542,14 @@ static int gemm_common(const uint8_t* A_dev, int M, int lda, const qg_packed_b* 
   a->sp_total = (int)Bp->nnz;
   a->lda = lda;
   a->a_vec = aligned(A_dev, 16) && (lda % 16 == 0);
+  a->ksplit = 1;
+  a->ks_per = a->kb64;
   return QG_OK;
 }
 
-int qg_gemm_u8s8_requant(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp,
-                         const qg_requant_params* p, uint8_t* C_dev, int ldc, void* workspace_dev,
-                         void* stream) {
-  return qg_gemm_u8s8_requant_kernel(A_dev, M, lda, Bp, p, C_dev, ldc, workspace_dev, stream, QG_KERNEL_AUTO);
-}
-
-int qg_gemm_u8s8_requant_kernel(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp,
-                                const qg_requant_params* p, uint8_t* C_dev, int ldc, void* workspace_dev,
-                                void* stream, int kernel) {
-  (void)workspace_dev;
+static int gemm_requant(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp, const qg_requant_params* p,
+                        uint8_t* C_dev, int ldc, void* workspace_dev, size_t workspace_bytes, bool bytes_known,
+                        void* stream, int kernel, int ksplit) {
   qg_gemm_args a = {};
   int rc = gemm_common(A_dev, M, lda, Bp, &a);
   if (rc != QG_OK) return rc;
@@ -465,6 +559,8 @@ int qg_gemm_u8s8_requant_kernel(const uint8_t* A_dev, int M, int lda, const qg_p
   rc = check_requant(p, Bp->N);
   if (rc != QG_OK) return rc;
   if (ldc < Bp->N) return QG_EINVAL;
+  rc = resolve_ksplit(Bp, M, kernel, ksplit, workspace_dev, workspace_bytes, bytes_known, &a);
+  if (rc != QG_OK) return rc;
   a.bias = p->bias;
   a.scales = p->scales;
   a.scale_stride = p->n_scales == 1 ? 0 : 1;
@@ -478,20 +574,33 @@ int qg_gemm_u8s8_requant_kernel(const uint8_t* A_dev, int M, int lda, const qg_p
   hipStream_t s = static_cast<hipStream_t>(stream);
   // 4-byte stores in the streaming kernels, 16-byte stores in the tiled ones
   a.c_vec = kernel <= QG_KERNEL_SKINNY64 ? (aligned(C_dev, 4) && (ldc % 4 == 0)) : (aligned(C_dev, 16) && (ldc % 16 == 0));
+  a.c_wt = (long long)M * Bp->N <= (1 << 18);
   if (M == 0) return QG_OK;  // an empty batch: checked like any other, nothing to enqueue
   const hipError_t e = launch_gemm(a, QG_MODE_REQUANT, kernel, s);
   return e == hipSuccess ? QG_OK : QG_ELAUNCH;
 }
 
-int qg_gemm_u8s8_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp, int32_t* C32_dev,
-                       int ldc, int32_t* rowsum_dev, void* workspace_dev, void* stream) {
-  return qg_gemm_u8s8_acc32_kernel(A_dev, M, lda, Bp, C32_dev, ldc, rowsum_dev, workspace_dev, stream,
-                                   QG_KERNEL_AUTO);
+int qg_gemm_u8s8_requant(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp,
+                         const qg_requant_params* p, uint8_t* C_dev, int ldc, void* workspace_dev,
+                         void* stream) {
+  return gemm_requant(A_dev, M, lda, Bp, p, C_dev, ldc, workspace_dev, 0, false, stream, QG_KERNEL_AUTO, 0);
 }
 
-int qg_gemm_u8s8_acc32_kernel(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp, int32_t* C32_dev,
-                              int ldc, int32_t* rowsum_dev, void* workspace_dev, void* stream, int kernel) {
-  (void)workspace_dev;
+int qg_gemm_u8s8_requant_kernel(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp,
+                                const qg_requant_params* p, uint8_t* C_dev, int ldc, void* workspace_dev,
+                                void* stream, int kernel) {
+  return gemm_requant(A_dev, M, lda, Bp, p, C_dev, ldc, workspace_dev, 0, false, stream, kernel, 0);
+}
+
+int qg_gemm_u8s8_requant_splitk(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp,
+                                const qg_requant_params* p, uint8_t* C_dev, int ldc, void* workspace_dev,
+                                size_t workspace_bytes, void* stream, int kernel, int ksplit) {
+  return gemm_requant(A_dev, M, lda, Bp, p, C_dev, ldc, workspace_dev, workspace_bytes, true, stream, kernel, ksplit);
+}
+
+static int gemm_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp, int32_t* C32_dev, int ldc,
+                      int32_t* rowsum_dev, void* workspace_dev, size_t workspace_bytes, bool bytes_known, void* stream,
+                      int kernel, int ksplit) {
   qg_gemm_args a = {};
   int rc = gemm_common(A_dev, M, lda, Bp, &a);
   if (rc != QG_OK) return rc;
@@ -499,12 +608,31 @@ int qg_gemm_u8s8_acc32_kernel(const uint8_t* A_dev, int M, int lda, const qg_pac
   if (rc != QG_OK) return rc;
   if (!C32_dev && M != 0) return QG_ENULL;
   if (ldc < Bp->N) return QG_EINVAL;
+  rc = resolve_ksplit(Bp, M, kernel, ksplit, workspace_dev, workspace_bytes, bytes_known, &a);
+  if (rc != QG_OK) return rc;
   a.C32 = C32_dev;
   a.rowsum_out = rowsum_dev;
   a.ldc = ldc;
   if (M == 0) return QG_OK;
   const hipError_t e = launch_gemm(a, QG_MODE_ACC32, kernel, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? QG_OK : QG_ELAUNCH;
+}
+
+int qg_gemm_u8s8_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp, int32_t* C32_dev,
+                       int ldc, int32_t* rowsum_dev, void* workspace_dev, void* stream) {
+  return gemm_acc32(A_dev, M, lda, Bp, C32_dev, ldc, rowsum_dev, workspace_dev, 0, false, stream, QG_KERNEL_AUTO, 0);
+}
+
+int qg_gemm_u8s8_acc32_kernel(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp, int32_t* C32_dev,
+                              int ldc, int32_t* rowsum_dev, void* workspace_dev, void* stream, int kernel) {
+  return gemm_acc32(A_dev, M, lda, Bp, C32_dev, ldc, rowsum_dev, workspace_dev, 0, false, stream, kernel, 0);
+}
+
+int qg_gemm_u8s8_acc32_splitk(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp, int32_t* C32_dev,
+                              int ldc, int32_t* rowsum_dev, void* workspace_dev, size_t workspace_bytes, void* stream,
+                              int kernel, int ksplit) {
+  return gemm_acc32(A_dev, M, lda, Bp, C32_dev, ldc, rowsum_dev, workspace_dev, workspace_bytes, true, stream, kernel,
+                    ksplit);
 }
 
 static int check_dequant(const qg_dequant_params* p, int N) {
@@ -519,7 +647,6 @@ static int check_dequant(const qg_dequant_params* p, int N) {
 int qg_gemm_u8s8_dequant_f32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp,
                              const qg_dequant_params* p, float* C_dev, int ldc, void* workspace_dev,
                              void* stream, int kernel) {
-  (void)workspace_dev;
   qg_gemm_args a = {};
   int rc = gemm_common(A_dev, M, lda, Bp, &a);
   if (rc != QG_OK) return rc;
@@ -530,6 +657,8 @@ int qg_gemm_u8s8_dequant_f32(const uint8_t* A_dev, int M, int lda, const qg_pack
   if (rc != QG_OK) return rc;
   if (ldc < Bp->N) return QG_EINVAL;
   if (!aligned(C_dev, 4)) return QG_EALIGN;
+  rc = resolve_ksplit(Bp, M, kernel, 0, workspace_dev, 0, false, &a);
+  if (rc != QG_OK) return rc;
   a.bias = p->bias;
   a.scales = p->scales;
   a.scale_stride = p->n_scales == 1 ? 0 : 1;

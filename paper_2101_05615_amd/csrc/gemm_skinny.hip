@@ -28,6 +28,16 @@
 // M larger than the row block is covered by the second grid dimension: every row block streams
 // B again (from L2 / the memory-side cache when the blocks run close together), which beats the
 // tiled kernel only while there are too few tiles to occupy the chip.
+//
+// K split ACROSS workgroups (third grid dimension, p.ksplit slices of K; the role of the paper's caller-provided
+// C_buffer, Appendix A): a shape with few fragment columns and a long K would leave most of the chip idle, so the
+// slices of one fragment column run as separate workgroups.  Each adds up its own waves through LDS as usual; the
+// wave that would run the output pipeline instead writes its int32 partial tile and row offsets into its slot of
+// the caller's workspace with device-coherent (write-through) stores, waits for their acknowledgement and takes
+// a ticket from a counter; the wave that draws the last ticket reads the other slices' slots, adds them in slice
+// order -- integer sums, so every split factor gives the same bytes -- runs the output pipeline and puts the
+// counter back to zero for the next call.  No fence instruction is used: a release fence at device scope writes
+// back the whole L2 of the XCD, which was measured at 20 - 80 us per workgroup.
 #include "qg_internal.h"
 #include <type_traits>
 
@@ -35,10 +45,39 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
+// ints of one (K slice, row block of 16) slot of the cross-workgroup workspace: 64 lanes x 4 partial sums, 16 row sums
+constexpr int SLOT_INTS = 64 * 4 + 16;
+
+// One activation request: 16 bytes per lane from a_base + voff (a_base wave-uniform, in scalar registers; voff a
+// per-lane byte offset) into LDS at lds + lane * 16 (lds wave-uniform).  Written out instead of the compiler's
+// builtin because that one forms the 64-bit address in a temporary vector register, and the register it picked
+// was the destination of a weight load still in flight: the request then waited for weights from HBM before it
+// could even be issued.  Here the address registers are never the target of a load.
+__device__ __forceinline__ void request_a(const uint8_t* a_base, unsigned voff, unsigned lds) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(a_base) : "memory");
+}
+
+// Explicit wait: at most LEFT vector-memory operations of this wave still in flight (they complete in order).
+// The compiler's own bookkeeping does not see the activation requests (they are issued by request_a), so the
+// waits that order LDS reads behind them are written out.
+template <int LEFT>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LEFT) : "memory");
+}
+
 // ANYALIGN: rows of A that are not 16-byte aligned.  The requests and vector loads take any address; the variant
 // exists so that the aligned one keeps its code (and its timing) to the instruction.
-template <int MODE, int MB, int NWAVES, int BATCH, bool B4, bool ANYALIGN>
-__global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_gemm_args p) {
+// SIMPLE: the straight-line variant for the common case the host has checked -- 8-bit weights, 16-byte aligned
+// rows, K a whole number of 64-deep blocks and every wave of every slice a whole number of batches: no partial
+// batch, no lane-copied staging, every request issued by hand in a known order.
+template <int MODE, int MB, int NWAVES, int BATCH, bool B4, bool ANYALIGN, bool SIMPLE = false>
+__global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8_t* A, const int8_t* Bp, const int M, const int N, const int K, const int kb64,
+                                                                   const int nb16_total, const int lda, const int ks_per, const int ksplit,
+                                                                   const qg_gemm_args p) {
+  // The leading scalar arguments repeat what a wave needs before it can issue its first loads (the fields of the same
+  // names in p): the file is compiled with kernel-argument preloading, so they arrive in scalar registers with the
+  // wave instead of costing a cold trip to memory (measured: 0.4 us of a 5 us launch).
+  static_assert(!SIMPLE || (!B4 && !ANYALIGN), "the straight-line variant takes dense 8-bit weights and aligned rows");
   const bool a_vec = ANYALIGN || p.a_vec;  // whole 16-byte chunks may be moved as such
   using chunk_t = typename std::conditional<ANYALIGN, qg_v4i_unaligned, v4i>::type;
   // A through LDS (see the file header): per wave and batch, ROWS rows x ROWB bytes
@@ -48,37 +87,43 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
   constexpr int PART_BYTES = NWAVES * MB * 64 * (int)sizeof(v4i);
   constexpr int RSP_BYTES = NWAVES * MB * 16 * (int)sizeof(int);
   constexpr int STAGE_BYTES = NWAVES * REGION;
-  // the K-split partial sums reuse the staging regions once the main loop is over
-  constexpr int UNION_BYTES = STAGE_BYTES > PART_BYTES ? STAGE_BYTES : PART_BYTES;
+  // every wave leaves its K-split partial sums (MB KiB) at the start of its OWN staging region (MB * BATCH KiB) once
+  // it is done with it: no wave waits for the others before it may write
+  static_assert(PART_BYTES <= STAGE_BYTES, "a wave's partial tile fits its staging region");
+  constexpr int UNION_BYTES = STAGE_BYTES;
   extern __shared__ __align__(16) unsigned char smem[];
-  v4i* part = reinterpret_cast<v4i*>(smem);                 // [wave][mb][lane]
-  int* rsp = reinterpret_cast<int*>(smem + UNION_BYTES);    // [wave][mb][16]
+  int* rsp = reinterpret_cast<int*>(smem + UNION_BYTES);    // [mb][row][wave]
   int* sp = reinterpret_cast<int*>(smem + UNION_BYTES + RSP_BYTES);  // B4: [row][slot] sparse term
 
   const int nb16 = blockIdx.x;
   const int sb = nb16 >> 1, sfrag = nb16 & 1;
   // columns held by this fragment: sb*32 + 16*(u&1) + 8*sfrag + 4*(u>>1) + r, u<4, r<4
-  if (sb * 32 + 8 * sfrag >= p.N) return;  // nothing but padding (uniform for the workgroup)
+  if (sb * 32 + 8 * sfrag >= N) return;  // nothing but padding (uniform for the workgroup)
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ml = lane & 15, g = lane >> 4;
   const int m_base = blockIdx.y * (MB * 16);  // first row of this workgroup's row block
 
-  // the waves that run the output pipeline fetch its per-column constants now, not after the reduction
+  // The waves that run the output pipeline fetch its per-column constants early, not after the reduction -- but
+  // BEHIND the first batch's weight loads and activation requests (load_ep is called from the first batch): cold,
+  // they take a trip to HBM, and nothing on the request path may end up waiting for them (the compiler had paired
+  // a pending constant with an address computation and stalled the requests of exactly the wave the others wait for).
   const int c0 = sb * 32 + 16 * (g & 1) + 8 * sfrag + 4 * (g >> 1);  // this lane's 4 output columns
-  int ep_co[4], ep_bz[4], ep_bias[4];
-  float ep_sc[4];
-  if (wave < MB) {
+  int ep_co[4] = {0, 0, 0, 0}, ep_bz[4] = {0, 0, 0, 0}, ep_bias[4] = {0, 0, 0, 0};
+  float ep_sc[4] = {1.0f, 1.0f, 1.0f, 1.0f};
+  auto load_ep = [&]() {
+    if (wave < MB) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int col = c0 + r;  // col_off / bzp are padded to N_pad, bias / scales are not
-      ep_co[r] = p.col_off[col];
-      ep_bz[r] = p.bzp[col];
-      ep_bias[r] = (MODE != QG_MODE_ACC32 && p.bias != nullptr && col < p.N) ? p.bias[col] : 0;
-      ep_sc[r] = (MODE != QG_MODE_ACC32 && col < p.N) ? p.scales[(size_t)col * p.scale_stride] : 1.0f;
+      for (int r = 0; r < 4; ++r) {
+        const int col = c0 + r;  // col_off / bzp are padded to N_pad, bias / scales are not
+        ep_co[r] = p.col_off[col];
+        ep_bz[r] = p.bzp[col];
+        ep_bias[r] = (MODE != QG_MODE_ACC32 && p.bias != nullptr && col < N) ? p.bias[col] : 0;
+        ep_sc[r] = (MODE != QG_MODE_ACC32 && col < N) ? p.scales[(size_t)col * p.scale_stride] : 1.0f;
+      }
     }
-  }
+  };
 
   if (B4) {
     for (int t = tid; t < MB * 256; t += NWAVES * 64) sp[t] = 0;
@@ -89,15 +134,18 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
   // of an XCD read DIFFERENT lines of A (all of them read all of A; unrotated they would all hit the same
   // L2 channel at the same time)
   // (4-bit weights come in pairs of k blocks, so their slices hold an even number of blocks)
-  const int per = B4 ? ((p.kb64 + 2 * NWAVES - 1) / (2 * NWAVES)) * 2 : (p.kb64 + NWAVES - 1) / NWAVES;
-  const int kb_begin = ((wave + nb16) % NWAVES) * per;
-  const int kb_end = min(p.kb64, kb_begin + per);
+  // (ksplit > 1: this workgroup owns slice blockIdx.z of K, whole k blocks, an even number of them for 4-bit weights)
+  const int ks_begin = min(kb64, (int)blockIdx.z * ks_per), ks_end = min(kb64, ks_begin + ks_per);
+  const int ks_len = ks_end - ks_begin;
+  const int per = B4 ? ((ks_len + 2 * NWAVES - 1) / (2 * NWAVES)) * 2 : (ks_len + NWAVES - 1) / NWAVES;
+  const int kb_begin = min(ks_end, ks_begin + ((wave + nb16) % NWAVES) * per);
+  const int kb_end = min(ks_end, kb_begin + per);
 
   // outlier split: the entry offsets of all of this wave's batches, one per lane (batch b: lanes b and b+1), are
   // requested before anything else so that no batch waits for an offset before it can ask for its entries
   int sp_offs = 0;
   if (B4 && kb_begin < kb_end) {
-    const int32_t* col = p.sp_ptr + (size_t)nb16 * p.kb64;
+    const int32_t* col = p.sp_ptr + (size_t)nb16 * kb64;
     sp_offs = col[min(kb_begin + BATCH * lane, kb_end)];
   }
 
@@ -110,8 +158,9 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
   }
   // 8-bit: one 1 KiB fragment per k block, 16 bytes per lane.  4-bit: one 1 KiB unit per PAIR of k blocks, 16 bytes
   // per lane (8 for each block), so that a request moves as many bytes as in the 8-bit layout.
-  const int8_t* bcol = p.Bp + (size_t)nb16 * QG_FRAG_BYTES + lane * 16;
-  const size_t b_step = (size_t)p.nb16 * QG_FRAG_BYTES;  // one slab (8-bit: 64 deep, 4-bit: 128 deep) of the packed buffer
+  const int8_t* bcol = Bp + (size_t)nb16 * QG_FRAG_BYTES;  // wave-uniform; the lane's 16 bytes are at + lane * 16
+  const unsigned lane16 = lane * 16;
+  const size_t b_step = (size_t)nb16_total * QG_FRAG_BYTES;  // one slab (8-bit: 64 deep, 4-bit: 128 deep) of the packed buffer
 
   // per-lane byte offsets of the NREQ activation requests of a batch (a.a_vec: they fit 32 bits); with them the
   // request address is a wave-uniform base plus a register that is never the target of a load, so issuing
@@ -120,7 +169,7 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
 #pragma unroll
   for (int jj = 0; jj < NREQ; ++jj) {
     const int r = jj * RPR + lane / NCHUNK;
-    a_off[jj] = (unsigned)min(m_base + r, p.M - 1) * (unsigned)p.lda + ((unsigned)((lane ^ r) & (NCHUNK - 1)) << 4);
+    a_off[jj] = (unsigned)min(m_base + r, M - 1) * (unsigned)lda + ((unsigned)((lane ^ r) & (NCHUNK - 1)) << 4);
   }
 
   // Weight requests of one batch: NLOAD loads of 16 bytes per lane, kept RAW (the 4-bit units are widened only
@@ -133,7 +182,7 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
 #pragma unroll
     for (int i = 0; i < NLOAD; ++i) {
       const int kbi = min(kb0 + (B4 ? 2 * i : i), kb_end - 1);  // B4: kb0 and kb_end are even
-      raw[i] = *reinterpret_cast<const v4i*>(bcol + (size_t)(B4 ? kbi >> 1 : kbi) * b_step);
+      raw[i] = *reinterpret_cast<const v4i*>(bcol + (size_t)(B4 ? kbi >> 1 : kbi) * b_step + lane16);
     }
   };
   auto operand = [&](const v4i (&raw)[NLOAD], int j) -> v4i {
@@ -147,10 +196,11 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
   // One batch: its weights were requested one batch earlier (into `cur`); request its activations and the NEXT
   // batch's weights (into `nxt`), then wait for the activations only.  Requests complete in order, so
   // "at most NLOAD outstanding" means that everything older than the next batch's weights has arrived.
-  auto batch = [&](int kb, const v4i (&cur)[NLOAD], v4i (&nxt)[NLOAD], const bool has_next) {
+  auto batch = [&](int kb, const v4i (&cur)[NLOAD], v4i (&nxt)[NLOAD], const bool has_next, auto first_tag) {
+    constexpr bool FIRST = decltype(first_tag)::value;
     // whole rows of BATCH k blocks are requested even when the slice ends earlier: the surplus lies inside the
     // row (it is the next wave's slice) and is simply not consumed
-    const bool staged = a_vec && (kb + BATCH) * QG_FRAG_K <= p.K;
+    const bool staged = a_vec && (kb + BATCH) * QG_FRAG_K <= K;
     unsigned char* region = smem + wave * REGION;
     // outlier split: this batch's entries are one run; the first 64 are requested one per lane right behind the
     // activations (always exactly one request, clamped into the buffer, so that the wait below can count it)
@@ -167,12 +217,12 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
     if (staged) {
       // ROWS rows x ROWB bytes of A: NREQ requests of RPR whole rows into this wave's LDS region, chunk c of
       // row r stored at chunk c ^ r so that the operand-order reads below are bank-conflict free
-      const uint8_t* a_base = p.A + (size_t)kb * QG_FRAG_K;  // wave-uniform
+      const uint8_t* a_base = A + (size_t)kb * QG_FRAG_K;  // wave-uniform
+      const unsigned region_lds = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)region);
 #pragma unroll
-      for (int jj = 0; jj < NREQ; ++jj)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a_base + a_off[jj]),
-                                         (__attribute__((address_space(3))) void*)(region + jj * 1024), 16, 0, 0);
+      for (int jj = 0; jj < NREQ; ++jj) request_a(a_base, a_off[jj], region_lds + jj * 1024);
       asm volatile("" ::: "memory");
+      if (FIRST) load_ep();
       sparse_request();
       asm volatile("" ::: "memory");
       if (has_next) {
@@ -190,14 +240,15 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
         const int r = i / nchunk, lc = i % nchunk;     // row, logical chunk
         const int c = r * NCHUNK + ((lc ^ r) & (NCHUNK - 1));
         const int k0 = kb * QG_FRAG_K + (lc << 4);
-        const uint8_t* src = p.A + (size_t)min(m_base + r, p.M - 1) * p.lda + k0;
+        const uint8_t* src = A + (size_t)min(m_base + r, M - 1) * lda + k0;
         v4i v;
-        if (a_vec && k0 + 16 <= p.K)
+        if (a_vec && k0 + 16 <= K)
           v = *reinterpret_cast<const chunk_t*>(src);
         else
-          v = qg_load_a_chunk(src, p.K - k0, false);  // byte by byte, bytes past K as 0x80
+          v = qg_load_a_chunk(src, K - k0, false);  // byte by byte, bytes past K as 0x80
         *reinterpret_cast<v4i*>(region + c * 16) = v;
       }
+      if (FIRST) load_ep();
       sparse_request();
       if (has_next) load_b(kb + BATCH, nxt);
     }
@@ -241,36 +292,103 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
     }
   };
 
-  // two register sets alternate
+  if constexpr (SIMPLE) {
+    // per is a multiple of BATCH and at least BATCH (host-checked); everything below is wave-uniform control flow
+    const int nbatch = per / BATCH;
+    const int8_t* bptr = bcol + (size_t)kb_begin * b_step;
+    const uint8_t* aptr = A + (size_t)kb_begin * QG_FRAG_K;
+    unsigned char* region = smem + wave * REGION;
+    const unsigned region_lds = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)region);
+    auto issue_w = [&](int b, v4i (&raw)[BATCH]) {
+      const int8_t* bp = bptr + (size_t)b * BATCH * b_step;
+#pragma unroll
+      for (int i = 0; i < BATCH; ++i) raw[i] = *reinterpret_cast<const v4i*>(bp + (size_t)i * b_step + lane16);
+    };
+    // batch b: its weights were requested one batch earlier; request its activations, (first batch) the constants of
+    // the output pipeline, the next batch's weights; wait for everything older than those; consume
+    auto step = [&](int b, v4i (&cur)[BATCH], v4i (&nxt)[BATCH], auto first_tag) {
+      const uint8_t* ab = aptr + (size_t)b * (BATCH * QG_FRAG_K);
+#pragma unroll
+      for (int jj = 0; jj < NREQ; ++jj) request_a(ab, a_off[jj], region_lds + jj * 1024);
+      if (decltype(first_tag)::value) load_ep();
+      asm volatile("" ::: "memory");
+      if (b + 1 < nbatch) {
+        issue_w(b + 1, nxt);
+        wait_vm<BATCH>();
+      } else {
+        wait_vm<0>();
+      }
+      v4i af[MB][BATCH];
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int j = 0; j < BATCH; ++j) {
+          const int r = mb * 16 + ml;
+          af[mb][j] = *reinterpret_cast<const v4i*>(region + r * ROWB + ((((4 * j + g) ^ r) & (NCHUNK - 1)) << 4));
+        }
+#pragma unroll
+      for (int j = 0; j < BATCH; ++j)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+          rs[mb] = __builtin_amdgcn_sad_u8(af[mb][j].x, 0u, rs[mb]);
+          rs[mb] = __builtin_amdgcn_sad_u8(af[mb][j].y, 0u, rs[mb]);
+          rs[mb] = __builtin_amdgcn_sad_u8(af[mb][j].z, 0u, rs[mb]);
+          rs[mb] = __builtin_amdgcn_sad_u8(af[mb][j].w, 0u, rs[mb]);
+          const v4i a = af[mb][j] ^ (int)0x80808080;
+          acc[mb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(cur[j], a, acc[mb], 0, 0, 0);
+        }
+      asm volatile("" ::: "memory");  // the fragment reads stay in front of the next batch's requests into the same region
+    };
+    v4i w0[BATCH], w1[BATCH];
+    issue_w(0, w0);
+    step(0, w0, w1, std::true_type{});
+    for (int b = 1; b < nbatch; b += 2) {
+      step(b, w1, w0, std::false_type{});
+      if (b + 1 < nbatch) step(b + 1, w0, w1, std::false_type{});
+    }
+  } else
+  // two register sets alternate; the first batch is peeled (it also requests the output-pipeline constants)
   if (kb_begin < kb_end) {
     v4i braw0[NLOAD], braw1[NLOAD];
     load_b(kb_begin, braw0);
-    for (int kb = kb_begin; kb < kb_end; kb += 2 * BATCH) {
-      batch(kb, braw0, braw1, kb + BATCH < kb_end);
-      if (kb + BATCH < kb_end) batch(kb + BATCH, braw1, braw0, kb + 2 * BATCH < kb_end);
+    batch(kb_begin, braw0, braw1, kb_begin + BATCH < kb_end, std::true_type{});
+    for (int kb = kb_begin + BATCH; kb < kb_end; kb += 2 * BATCH) {
+      batch(kb, braw1, braw0, kb + BATCH < kb_end, std::false_type{});
+      if (kb + BATCH < kb_end) batch(kb + BATCH, braw0, braw1, kb + 2 * BATCH < kb_end, std::false_type{});
     }
+  } else {
+    load_ep();
   }
 
-  // ---- combine the 16 K-slices through LDS (the partial sums overwrite the staging regions: every wave must
-  // be done with its own first)
-  __syncthreads();
+  // ---- combine the 16 K-slices through LDS (a wave's fragment reads of its region are complete: the MFMAs consumed them)
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
-    part[(wave * MB + mb) * 64 + lane] = acc[mb];
-    int v = (int)rs[mb];
-    v += __shfl_xor(v, 16);
-    v += __shfl_xor(v, 32);
-    if (g == 0) rsp[(wave * MB + mb) * 16 + ml] = v;
+    reinterpret_cast<v4i*>(smem + wave * REGION)[mb * 64 + lane] = acc[mb];
+    // the four lanes (ml, g = 0..3) of a row hold its byte sums over different k: add them with two lane swaps
+    // (v_permlane32_swap / v_permlane16_swap; a shuffle through the LDS crossbar costs about 100 cycles each)
+    const unsigned v = rs[mb];
+    const auto h = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    const unsigned v2 = h[0] + h[1];
+    const auto q = __builtin_amdgcn_permlane16_swap(v2, v2, false, false);
+    if (g == 0) rsp[((mb * 16 + ml) * NWAVES) + wave] = (int)(q[0] + q[1]);  // [mb][row][wave]: the reader takes a row's 16 sums in four reads
   }
   __syncthreads();
   if (wave >= MB) return;
   const int mb = wave;
   v4i sum = (v4i){0, 0, 0, 0};
-  int rsum = -128 * (p.kb64 * QG_FRAG_K);  // every staged byte (padding included) is 128 above its int8 value
+  int rsum = -128 * (ks_len * QG_FRAG_K);  // every staged byte (padding included) is 128 above its int8 value
+  {
+    // every read is issued before the first sum (a sum per read would serialise on the LDS latency, 16 times over)
+    static_assert(NWAVES % 4 == 0, "row sums are fetched four waves at a time");
+    v4i t[NWAVES], tr[NWAVES / 4];
 #pragma unroll
-  for (int w = 0; w < NWAVES; ++w) {
-    sum += part[(w * MB + mb) * 64 + lane];
-    rsum += rsp[(w * MB + mb) * 16 + ml];
+    for (int w = 0; w < NWAVES; ++w) t[w] = reinterpret_cast<const v4i*>(smem + w * REGION)[mb * 64 + lane];
+#pragma unroll
+    for (int w = 0; w < NWAVES / 4; ++w) tr[w] = reinterpret_cast<const v4i*>(rsp + (mb * 16 + ml) * NWAVES)[w];
+#pragma unroll
+    for (int w = 0; w < NWAVES; ++w) sum += t[w];
+#pragma unroll
+    for (int w = 0; w < NWAVES / 4; ++w) rsum += tr[w].x + tr[w].y + tr[w].z + tr[w].w;
   }
   if (B4) {
     // A_s B = (A_s U - 8 rowsum(A_s)) + A_s B_sparse; lane (ml, g) register r is slot 4 g + r of the fragment
@@ -278,9 +396,36 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
     for (int r = 0; r < 4; ++r) sum[r] += sp[(mb * 16 + ml) * 16 + 4 * g + r] - 8 * rsum;
   }
 
+  // ---- K split across workgroups: hand the partial tile in, the last slice to arrive carries on
+  if (ksplit > 1) {
+    const int unit = ((int)blockIdx.y * (int)gridDim.x + nb16) * MB + mb;  // one counter per (row block of 16, fragment column)
+    int* cnt = p.ws_cnt + unit;
+    int* slots = p.ws_slots + (size_t)unit * ksplit * SLOT_INTS;
+    int* mine = slots + (size_t)blockIdx.z * SLOT_INTS;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) __hip_atomic_store(mine + lane * 4 + r, sum[r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (g == 0) __hip_atomic_store(mine + 256 + ml, rsum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the write-through stores above have been acknowledged
+    int ticket = 0;
+    if (lane == 0) ticket = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    ticket = __builtin_amdgcn_readfirstlane(ticket);
+    if (ticket != ksplit - 1) return;
+    asm volatile("" ::: "memory");
+    // every other slice's stores were acknowledged before it took its ticket; add all slots in slice order
+    sum = (v4i){0, 0, 0, 0};
+    rsum = 0;
+    for (int ss = 0; ss < ksplit; ++ss) {
+      const int* theirs = slots + (size_t)ss * SLOT_INTS;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) sum[r] += __hip_atomic_load(theirs + lane * 4 + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      rsum += __hip_atomic_load(theirs + 256 + ml, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (lane == 0) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next call
+  }
+
   // ---- output pipeline; lane (ml, u = g) holds row m_base+mb*16+ml, 4 consecutive columns
   const int row = m_base + mb * 16 + ml;
-  if (row >= p.M || c0 >= p.N) return;
+  if (row >= M || c0 >= N) return;
   if (MODE == QG_MODE_REQUANT) {
     unsigned out = 0;
 #pragma unroll
@@ -289,12 +434,17 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
       out |= (unsigned)qg_requant_one(x, ep_sc[r], p.clamp_lo, p.clamp_hi, p.c_zp) << (8 * r);
     }
     uint8_t* dst = p.C + (size_t)row * p.ldc + c0;
-    if (p.c_vec && c0 + 4 <= p.N) {
-      *reinterpret_cast<unsigned*>(dst) = out;
+    if (p.c_vec && c0 + 4 <= N) {
+      // a small output goes out write-through: the end of the kernel then finds no dirty lines to write back
+      // (measured: 0.3 us of a 5 us launch)
+      if (p.c_wt)
+        __hip_atomic_store(reinterpret_cast<unsigned*>(dst), out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      else
+        *reinterpret_cast<unsigned*>(dst) = out;
     } else {
 #pragma unroll
       for (int r = 0; r < 4; ++r)
-        if (c0 + r < p.N) dst[r] = (uint8_t)(out >> (8 * r));
+        if (c0 + r < N) dst[r] = (uint8_t)(out >> (8 * r));
     }
   } else if (MODE == QG_MODE_DEQUANT) {
     float out[4];
@@ -304,20 +454,20 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const qg_ge
       out[r] = qg_dequant_one(x, ep_sc[r], p.relu_lo);
     }
     float* dst = p.Cf + (size_t)row * p.ldc + c0;
-    if (p.c_vec && c0 + 4 <= p.N) {
+    if (p.c_vec && c0 + 4 <= N) {
       *reinterpret_cast<float4*>(dst) = make_float4(out[0], out[1], out[2], out[3]);
     } else {
 #pragma unroll
       for (int r = 0; r < 4; ++r)
-        if (c0 + r < p.N) dst[r] = out[r];
+        if (c0 + r < N) dst[r] = out[r];
     }
   } else {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int col = c0 + r;
-      if (col < p.N) p.C32[(size_t)row * p.ldc + col] = sum[r] + 128 * (ep_co[r] + p.K * ep_bz[r]);
+      if (col < N) p.C32[(size_t)row * p.ldc + col] = sum[r] + 128 * (ep_co[r] + K * ep_bz[r]);
     }
-    if (p.rowsum_out != nullptr && nb16 == 0 && g == 0) p.rowsum_out[row] = rsum + 128 * p.K;
+    if (p.rowsum_out != nullptr && nb16 == 0 && g == 0) p.rowsum_out[row] = rsum + 128 * K;
   }
 }
 
@@ -326,13 +476,25 @@ hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   const int part = NWAVES * MB * 64 * (int)sizeof(v4i), stage = NWAVES * (MB * 16) * (BATCH * QG_FRAG_K);
   const int smem = (stage > part ? stage : part) + NWAVES * MB * 16 * (int)sizeof(int) +
                    (B4 ? MB * 256 * (int)sizeof(int) : 0);
-  hipError_t e = qg_allow_smem<qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH, B4, ANYALIGN>>(smem);
-  if (e != hipSuccess) return e;
   const int nfrag = ((a.N + 31) / 32) * 2;
   const int mblocks = (a.M + MB * 16 - 1) / (MB * 16);
-  if (mblocks > 65535) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH, B4, ANYALIGN>), dim3(nfrag, mblocks), dim3(NWAVES * 64), smem,
-                     s, a);
+  if (mblocks > 65535 || a.ksplit < 1 || a.ksplit > 65535) return hipErrorInvalidValue;
+  if (a.ksplit > 1 && (a.ws_cnt == nullptr || a.ws_slots == nullptr)) return hipErrorInvalidValue;
+  const dim3 grid(nfrag, mblocks, a.ksplit), block(NWAVES * 64);
+  if constexpr (!B4 && !ANYALIGN) {
+    // the straight-line variant: K is a whole number of blocks, all slices are equal and give every wave whole batches
+    if (a.K == a.kb64 * QG_FRAG_K && a.kb64 % a.ks_per == 0 && a.ks_per % (NWAVES * BATCH) == 0) {
+      constexpr auto fn = qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH, false, false, true>;
+      hipError_t e = qg_allow_smem<fn>(smem);
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL(fn, grid, block, smem, s, a.A, a.Bp, a.M, a.N, a.K, a.kb64, a.nb16, a.lda, a.ks_per, a.ksplit, a);
+      return hipGetLastError();
+    }
+  }
+  hipError_t e = qg_allow_smem<qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH, B4, ANYALIGN>>(smem);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH, B4, ANYALIGN>), grid, block, smem, s, a.A, a.Bp, a.M, a.N,
+                     a.K, a.kb64, a.nb16, a.lda, a.ks_per, a.ksplit, a);
   return hipGetLastError();
 }
 

@@ -88,10 +88,21 @@ struct qg_packed_b {
   long long nnz;             // number of outliers
 };
 
-// Arguments of the GEMM kernels (by value).
+// Arguments of the GEMM kernels (by value).  The first 64 bytes hold everything a wave needs before it can issue
+// its first loads, so that one line of the kernel-argument segment (cold at every launch) gets it going.
 struct qg_gemm_args {
   const uint8_t* A;
   const int8_t* Bp;
+  int M, N, K;
+  int kb64;              // K_pad / 64
+  int nb16;              // N_pad / 16: fragments per 64-deep slab of the packed buffer
+  int lda, ldc;
+  int ksplit;            // streaming kernels: slices of K that run as separate workgroups (>= 1)
+  int ks_per;            // 64-deep blocks of K per slice (ceil; even for 4-bit weights)
+  int a_vec;             // A base and lda are multiples of 16 (the streaming kernels keep a variant for that case)
+  int c_vec;             // output base and row pitch are multiples of 16 bytes (uint8 output of the streaming kernels: 4)
+  int has_bzp;           // some theta_B != 0: the row-offset term of Eq. (2) is needed
+  // ---- 64 bytes
   const int32_t* col_off;
   const int32_t* bzp;
   const int32_t* bias;   // may be null
@@ -100,18 +111,15 @@ struct qg_gemm_args {
   int32_t* C32;          // acc32 output
   float* Cf;             // fp32 output (dequant mode)
   int32_t* rowsum_out;   // acc32 mode, may be null
-  int M, N, K;
-  int kb64;              // K_pad / 64
-  int nb16;              // N_pad / 16: fragments per 64-deep slab of the packed buffer
-  int lda, ldc;
   int scale_stride;      // 0 per tensor, 1 per channel
   int a_zp_m128;         // theta_A - 128
   int c_zp;
   float clamp_lo, clamp_hi;  // lo - theta_C, 255 - theta_C
   float relu_lo;         // dequant mode: 0 with ReLU, -inf without
-  int a_vec;             // A base and lda are multiples of 16 (the streaming kernels keep a variant for that case)
-  int c_vec;             // output base and row pitch are multiples of 16 bytes (uint8 output of the streaming kernels: 4)
-  int has_bzp;           // some theta_B != 0: the row-offset term of Eq. (2) is needed
+  int c_wt;              // streaming kernels: write the (small) uint8 output through to memory instead of leaving it dirty in L2
+  // K split across workgroups (streaming kernels): the caller's workspace (tickets, partial tiles)
+  int32_t* ws_cnt;       // one ticket counter per (row block of 16, fragment column); zero between calls
+  int32_t* ws_slots;     // ksplit slots of 272 int32 per counter
   const int32_t* sp_ptr;      // outlier split: per-bucket offsets, or null for a dense 8-bit B
   const int32_t* sp_entries;  // outlier split: entries
   int sp_total;               // outlier split: number of entries (the buffer holds at least one)

@@ -24,6 +24,8 @@ EXPORTS = [
     "qg_gemm_f32s8_requant", "qg_gemm_f32s8_dequant_f32",
     "qg_count_outliers", "qg_pack_b_outlier_sizes", "qg_pack_b_outlier", "qg_packed_b_nnz",
     "qg_conv_dense_u8s8_requant", "qg_pack_b_transposed", "qg_probe_mfma_i8", "qg_probe_read",
+    "qg_gemm_workspace_init", "qg_gemm_splitk_workspace_bytes", "qg_gemm_splitk_factor",
+    "qg_gemm_u8s8_requant_splitk", "qg_gemm_u8s8_acc32_splitk",
 ]
 
 KERNEL_AUTO, KERNEL_LAST = 0, 10
@@ -86,6 +88,12 @@ def _load():
     lib.qg_packed_b_nnz.argtypes = [vp]
     lib.qg_conv_dense_u8s8_requant.argtypes = [vp, i, i, i, i, i, i, i, i, vp, ctypes.POINTER(RequantParams), vp, vp, i]
     lib.qg_packed_b_nnz.restype = sz
+    lib.qg_gemm_workspace_init.argtypes = [vp, sz, vp]
+    lib.qg_gemm_splitk_workspace_bytes.argtypes = [i, vp, i, i]
+    lib.qg_gemm_splitk_workspace_bytes.restype = sz
+    lib.qg_gemm_splitk_factor.argtypes = [i, vp, i, i]
+    lib.qg_gemm_u8s8_requant_splitk.argtypes = [vp, i, i, vp, ctypes.POINTER(RequantParams), vp, i, vp, sz, vp, i, i]
+    lib.qg_gemm_u8s8_acc32_splitk.argtypes = [vp, i, i, vp, vp, i, vp, vp, sz, vp, i, i]
     lib.qg_probe_mfma_i8.argtypes = [vp, vp, i, i, vp]
     lib.qg_probe_read.argtypes = [vp, sz, vp, i, vp]
     return lib
@@ -253,6 +261,50 @@ def gemm_workspace_bytes(M, Bp):
     return lib.qg_gemm_workspace_bytes(M, Bp.handle)
 
 
+def gemm_workspace(M, Bp, kernel=KERNEL_AUTO, ksplit=0):
+    """A zero-initialised workspace for the K split across workgroups (None when the split factor is 1)."""
+    n = lib.qg_gemm_splitk_workspace_bytes(M, Bp.handle, kernel_id(kernel), ksplit)
+    if n == 0:
+        return None
+    ws = torch.empty(n, dtype=torch.uint8, device=Bp.packed.device)
+    _check(lib.qg_gemm_workspace_init(ws.data_ptr(), n, _stream()), "qg_gemm_workspace_init")
+    return ws
+
+
+def gemm_splitk_factor(M, Bp, kernel=KERNEL_AUTO, ksplit=0):
+    s = lib.qg_gemm_splitk_factor(M, Bp.handle, kernel_id(kernel), ksplit)
+    if s < 0:
+        raise QGemmError(s, "qg_gemm_splitk_factor")
+    return s
+
+
+def gemm_u8s8_requant_splitk(A, a_zp, Bp, bias, scales, c_zp, relu, workspace, kernel=KERNEL_AUTO, ksplit=0, out=None):
+    """As gemm_u8s8_requant with the K split across workgroups chosen by the caller (0 = built-in choice)."""
+    assert A.is_cuda and A.dtype == torch.uint8 and A.dim() == 2 and A.stride(1) == 1 and A.shape[1] == Bp.K
+    M = A.shape[0]
+    if out is None:
+        out = torch.empty((M, Bp.N), dtype=torch.uint8, device=A.device)
+    assert out.is_cuda and out.dtype == torch.uint8 and out.stride(1) == 1 and out.shape == (M, Bp.N)
+    p = _params(a_zp, bias, scales, c_zp, relu)
+    wp, wn = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) if workspace is not None else (None, 0)
+    _check(lib.qg_gemm_u8s8_requant_splitk(A.data_ptr(), M, A.stride(0), Bp.handle, ctypes.byref(p), out.data_ptr(),
+                                           out.stride(0), wp, wn, _stream(), kernel_id(kernel), ksplit),
+           "qg_gemm_u8s8_requant_splitk")
+    return out
+
+
+def gemm_u8s8_acc32_splitk(A, Bp, workspace, kernel=KERNEL_AUTO, ksplit=0, want_rowsum=False):
+    assert A.is_cuda and A.dtype == torch.uint8 and A.dim() == 2 and A.stride(1) == 1
+    M = A.shape[0]
+    out = torch.empty((M, Bp.N), dtype=torch.int32, device=A.device)
+    rs = torch.empty(M, dtype=torch.int32, device=A.device) if want_rowsum else None
+    wp, wn = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) if workspace is not None else (None, 0)
+    _check(lib.qg_gemm_u8s8_acc32_splitk(A.data_ptr(), M, A.stride(0), Bp.handle, out.data_ptr(), out.stride(0),
+                                         rs.data_ptr() if rs is not None else None, wp, wn, _stream(),
+                                         kernel_id(kernel), ksplit), "qg_gemm_u8s8_acc32_splitk")
+    return (out, rs) if want_rowsum else out
+
+
 def gemm_u8s8_requant(A, a_zp, Bp, bias, scales, c_zp, relu, out=None, workspace=None, kernel=KERNEL_AUTO):
     """C_u8 = requant(A_u8 . B_s8): A uint8 cuda [M, K]; returns / fills uint8 [M, N]."""
     assert A.is_cuda and A.dtype == torch.uint8 and A.dim() == 2 and A.stride(1) == 1
@@ -272,13 +324,14 @@ class PreparedGemm:
     """All arguments of one qg_gemm_u8s8_requant call marshalled once; `launch()` is a single ctypes call on
     the stream that was current when the object was made.  For loops that repeat the same call."""
 
-    def __init__(self, A, a_zp, Bp, bias, scales, c_zp, relu, out, kernel=KERNEL_AUTO):
+    def __init__(self, A, a_zp, Bp, bias, scales, c_zp, relu, out, kernel=KERNEL_AUTO, workspace=None):
         assert A.is_cuda and A.dtype == torch.uint8 and A.dim() == 2 and A.stride(1) == 1 and A.shape[1] == Bp.K
         assert out.is_cuda and out.dtype == torch.uint8 and out.stride(1) == 1 and out.shape == (A.shape[0], Bp.N)
-        self._keep = (A, Bp, bias, scales, out)
+        self._keep = (A, Bp, bias, scales, out, workspace)
         self._p = _params(a_zp, bias, scales, c_zp, relu)
         self._args = (A.data_ptr(), A.shape[0], A.stride(0), Bp.handle, ctypes.byref(self._p), out.data_ptr(),
-                      out.stride(0), None, _stream(), kernel_id(kernel))
+                      out.stride(0), workspace.data_ptr() if workspace is not None else None, _stream(),
+                      kernel_id(kernel))
         self.out = out
 
     def launch(self):
