@@ -249,6 +249,25 @@ int qg_gemm_u8s8_acc32_splitk(const uint8_t* A_dev, int M, int lda, const qg_pac
                               int ldc, int32_t* rowsum_dev, void* workspace_dev, size_t workspace_bytes,
                               void* stream, int kernel, int ksplit);
 
+/* For callers that cannot allocate device memory or hand a workspace through:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * allocation.  qg_gemm_u8s8_requant_splitk with the workspace replaced by a
+ * scratch array built into the library (QG_NOALLOC_SCRATCH_BYTES per GPU, held
+ * from the first use of the library on that GPU until the process ends).  The
+ * call allocates nothing and enqueues kernels only.
+ *   kernel, ksplit  as qg_gemm_u8s8_requant_splitk (QG_KERNEL_AUTO / 0 = built-in choices)
+ * QG_EWORKSPACE when the split in use needs more than QG_NOALLOC_SCRATCH_BYTES
+ * (qg_gemm_splitk_workspace_bytes tells; pass ksplit = 1 to run without any).
+ * All calls on one GPU share that GPU's array: calls that may overlap in time
+ * (different streams, different threads) race on it and must not be made; one
+ * after another on a stream they are safe, since every call leaves the array
+ * ready for the next (a call that was killed mid-flight does not: the process
+ * must then stop using this entry point on that GPU). */
+#define QG_NOALLOC_SCRATCH_BYTES (2u << 20)
+int qg_gemm_u8s8_requant_noalloc(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp,
+                                 const qg_requant_params* p, uint8_t* C_dev, int ldc, void* stream, int kernel,
+                                 int ksplit);
+
 /* ---- the other ends of the pipeline (Appendix B) --------------------------- */
 
 /* The paper builds a pipeline from any packing routine for A and any output

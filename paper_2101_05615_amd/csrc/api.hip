@@ -276,6 +276,30 @@ int resolve_ksplit(const qg_packed_b* Bp, int M, int kernel, int ksplit_req, voi
   return QG_OK;
 }
 
+// ---- built-in scratch for callers that cannot allocate (qg_gemm_u8s8_requant_noalloc) -------------------------
+// The K-split workspace as a file-scope device array: every GPU the library runs on holds its own copy, at its own
+// address, from the moment the code object is loaded until the process ends.  Zero-initialised at load, and every
+// call leaves the ticket counters at zero, so no clearing pass is needed between calls.  In host code the array's
+// name is only a handle: the device address comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) int32_t qg_noalloc_scratch[QG_NOALLOC_SCRATCH_BYTES / sizeof(int32_t)];
+void* g_scratch_ptr[64] = {nullptr};  // per device; concurrent first calls may both look it up (same answer)
+
+int noalloc_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return QG_ELAUNCH;
+  if (dev < 0 || dev >= 64) return QG_EUNSUPPORTED;
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(qg_noalloc_scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return QG_ELAUNCH;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return QG_OK;
+}
+
 __global__ void qg_fill_zero_kernel(int32_t* p, size_t n) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -596,6 +620,20 @@ int qg_gemm_u8s8_requant_splitk(const uint8_t* A_dev, int M, int lda, const qg_p
                                 const qg_requant_params* p, uint8_t* C_dev, int ldc, void* workspace_dev,
                                 size_t workspace_bytes, void* stream, int kernel, int ksplit) {
   return gemm_requant(A_dev, M, lda, Bp, p, C_dev, ldc, workspace_dev, workspace_bytes, true, stream, kernel, ksplit);
+}
+
+int qg_gemm_u8s8_requant_noalloc(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp,
+                                 const qg_requant_params* p, uint8_t* C_dev, int ldc, void* stream, int kernel,
+                                 int ksplit) {
+  if (!Bp) return QG_ENULL;
+  if (Bp->kind != QG_KIND_GEMM || Bp->version != QG_LAYOUT_VERSION || M < 0) return QG_EINVAL;
+  // the split this call would use with a workspace at hand, and what it needs of the built-in scratch
+  const size_t need = M > 0 ? qg_gemm_splitk_workspace_bytes(M, Bp, kernel, ksplit) : 0;
+  if (need > QG_NOALLOC_SCRATCH_BYTES) return QG_EWORKSPACE;
+  void* scratch = nullptr;
+  const int rc = noalloc_scratch(&scratch);
+  if (rc != QG_OK) return rc;
+  return gemm_requant(A_dev, M, lda, Bp, p, C_dev, ldc, scratch, QG_NOALLOC_SCRATCH_BYTES, true, stream, kernel, ksplit);
 }
 
 static int gemm_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* Bp, int32_t* C32_dev, int ldc,

@@ -25,7 +25,7 @@ EXPORTS = [
     "qg_count_outliers", "qg_pack_b_outlier_sizes", "qg_pack_b_outlier", "qg_packed_b_nnz",
     "qg_conv_dense_u8s8_requant", "qg_pack_b_transposed", "qg_probe_mfma_i8", "qg_probe_read",
     "qg_gemm_workspace_init", "qg_gemm_splitk_workspace_bytes", "qg_gemm_splitk_factor",
-    "qg_gemm_u8s8_requant_splitk", "qg_gemm_u8s8_acc32_splitk",
+    "qg_gemm_u8s8_requant_splitk", "qg_gemm_u8s8_acc32_splitk", "qg_gemm_u8s8_requant_noalloc",
 ]
 
 KERNEL_AUTO, KERNEL_LAST = 0, 10
@@ -94,6 +94,7 @@ def _load():
     lib.qg_gemm_splitk_factor.argtypes = [i, vp, i, i]
     lib.qg_gemm_u8s8_requant_splitk.argtypes = [vp, i, i, vp, ctypes.POINTER(RequantParams), vp, i, vp, sz, vp, i, i]
     lib.qg_gemm_u8s8_acc32_splitk.argtypes = [vp, i, i, vp, vp, i, vp, vp, sz, vp, i, i]
+    lib.qg_gemm_u8s8_requant_noalloc.argtypes = [vp, i, i, vp, ctypes.POINTER(RequantParams), vp, i, vp, i, i]
     lib.qg_probe_mfma_i8.argtypes = [vp, vp, i, i, vp]
     lib.qg_probe_read.argtypes = [vp, sz, vp, i, vp]
     return lib
@@ -290,6 +291,20 @@ def gemm_u8s8_requant_splitk(A, a_zp, Bp, bias, scales, c_zp, relu, workspace, k
     _check(lib.qg_gemm_u8s8_requant_splitk(A.data_ptr(), M, A.stride(0), Bp.handle, ctypes.byref(p), out.data_ptr(),
                                            out.stride(0), wp, wn, _stream(), kernel_id(kernel), ksplit),
            "qg_gemm_u8s8_requant_splitk")
+    return out
+
+
+NOALLOC_SCRATCH_BYTES = 2 << 20
+
+
+def gemm_u8s8_requant_noalloc(A, a_zp, Bp, bias, scales, c_zp, relu, out, kernel=KERNEL_AUTO, ksplit=0):
+    """qg_gemm_u8s8_requant_noalloc: the K-split workspace is the library's built-in scratch; `out` is the caller's."""
+    assert A.is_cuda and A.dtype == torch.uint8 and A.dim() == 2 and A.stride(1) == 1 and A.shape[1] == Bp.K
+    assert out.is_cuda and out.dtype == torch.uint8 and out.stride(1) == 1 and out.shape == (A.shape[0], Bp.N)
+    p = _params(a_zp, bias, scales, c_zp, relu)
+    _check(lib.qg_gemm_u8s8_requant_noalloc(A.data_ptr(), A.shape[0], A.stride(0), Bp.handle, ctypes.byref(p),
+                                            out.data_ptr(), out.stride(0), _stream(), kernel_id(kernel), ksplit),
+           "qg_gemm_u8s8_requant_noalloc")
     return out
 
 
