@@ -55,8 +55,12 @@ extern "C" {
 #define QG_ECAPACITY (-8)  /* more outliers than the caller's sparse buffer can hold       */
 
 /* Largest K accepted: with |A| <= 255 and |B - theta_B| <= 255 the int32
- * accumulator and every correction term stay below 2^31 (Eq. (2) never
- * discusses overflow; this bound makes it impossible). */
+ * accumulator and the zero-point terms of Eq. (2) together stay within
+ * 255 * 255 * K <= 2 130 739 200 < 2^31 (Eq. (2) never discusses overflow).
+ * The int32 bias is added on top in 32-bit arithmetic, so the caller must keep
+ *     |bias[j]| <= 2^31 - 1 - 255 * 255 * K
+ * (16 744 447 at K = 32768, about 2^31 for short K); beyond that the corrected
+ * accumulator may wrap and the result is unspecified. */
 #define QG_MAX_K 32768
 
 /* Opaque HOST-side descriptor of a packed weight matrix.  It owns no device
@@ -72,7 +76,8 @@ typedef struct qg_packed_b qg_packed_b;
  * product is ONE IEEE fp32 multiply.  scales must be finite and > 0. */
 typedef struct {
   int32_t a_zp;          /* theta_A, 0..255                                   */
-  const int32_t* bias;   /* dev, N entries in accumulator units, or NULL      */
+  const int32_t* bias;   /* dev, N entries in accumulator units, or NULL;
+                            |bias[j]| <= 2^31 - 1 - 255*255*K (see QG_MAX_K)  */
   const float* scales;   /* dev, n_scales entries                             */
   int32_t n_scales;      /* 1 (per tensor) or N (per output channel)          */
   int32_t c_zp;          /* theta_C, 0..255                                   */
@@ -402,25 +407,6 @@ int qg_conv_groupwise_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W,
 int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int Cin, int R, int S,
                                int pad, int stride, const qg_packed_b* Wp, const qg_requant_params* p,
                                uint8_t* out_nhwc, void* stream, int kernel);
-
-/* ---- measurement probes --------------------------------------------------- */
-
-/* What the machine sustains on the two resources the kernels are priced against
- * (the performance discussion of the paper, Sec. 3, is in terms of the same two:
- * compute peak and memory bandwidth).  Not part of the GEMM path; asynchronous.
- *
- * qg_probe_mfma_i8: a register-only loop of v_mfma_i32_32x32x32_i8 on a 4 x 4
- * block register tile per wave; `workgroups` workgroups of 4 waves run `iters`
- * rounds of 16 matrix instructions each, i.e. workgroups * 4 * iters * 16 * 65536
- * operations.  The operands are the first 32 KiB at operands_dev (16-byte
- * aligned, any content: the clock the chip holds depends on how many operand
- * bits toggle, so pass bytes distributed like the data of interest).
- * sink_dev receives workgroups * 256 int32 (contents meaningless).
- *
- * qg_probe_read: reads `bytes` (a multiple of 16) from src_dev (16-byte
- * aligned) once with `workgroups` workgroups of 256 threads; sink_dev: one int32. */
-int qg_probe_mfma_i8(const void* operands_dev, int32_t* sink_dev, int workgroups, int iters, void* stream);
-int qg_probe_read(const void* src_dev, size_t bytes, int32_t* sink_dev, int workgroups, void* stream);
 
 const char* qg_status_string(int code);
 

@@ -7,7 +7,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqgemm.so")
-SOURCES = ["api.hip", "pack.hip", "quantize_a.hip", "gemm_tile.hip", "gemm_skinny.hip", "conv_group.hip", "probe.hip"]
+SOURCES = ["api.hip", "pack.hip", "quantize_a.hip", "gemm_tile.hip", "gemm_skinny.hip", "conv_group.hip"]
+PROBES_SRC = os.path.join(ROOT, "bench_probes.hip")   # bench.py's measurement probes, a library of their own
+PROBES_LIB = os.path.join(ROOT, "libbench_probes.so")
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -54,7 +56,17 @@ def build_lib(verbose=False, extra=(), incremental=False):
     return LIB
 
 
+def build_probes(verbose=False):
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Xclang", "-target-feature",
+           "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument", PROBES_SRC, "-o", PROBES_LIB]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return PROBES_LIB
+
+
 if __name__ == "__main__":
     inc = "--incremental" in sys.argv[1:]
     build_lib(verbose=True, extra=[a for a in sys.argv[1:] if a != "--incremental"], incremental=inc)
+    build_probes(verbose=True)
     print("built", LIB)

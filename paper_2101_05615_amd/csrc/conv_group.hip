@@ -236,7 +236,8 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
       sc_s[c] = p.scales[(size_t)oc * p.scale_stride];
     }
   }
-  __syncthreads();  // includes the wait for every outstanding request of this wave
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // every request of this wave has landed in LDS ...
+  __syncthreads();                                   // ... before any wave reads the others' slots
 
   const int pl = lane & 31, g = lane >> 5;
   const int px = q0 + wave * 32 + pl;

@@ -45,13 +45,7 @@ constexpr int asm_stages(int blocks) { return blocks == 8 ? 3 : NSTAGE; }
 // LDS stages of the compiler-scheduled loop, by 32 x 32 blocks per wave.  Three everywhere: measured with 3 to 8
 // stages, a thin grid's k step (0.28 us at 64 x 64) does not get shorter with more tiles in flight -- it is the
 // barrier / LDS read / MFMA chain of a lone workgroup -- while deeper buffers cost occupancy on full grids.
-#ifndef QG_PS_SMALL
-#define QG_PS_SMALL 3
-#endif
-#ifndef QG_PS_MID
-#define QG_PS_MID 3
-#endif
-constexpr int pipe_stages(int blocks) { return blocks >= 8 ? 3 : (blocks >= 4 ? QG_PS_MID : QG_PS_SMALL); }
+constexpr int pipe_stages(int) { return 3; }
 
 // main-loop flavours
 constexpr int PATH_ASM = 1;      // 256 x 256, hand-scheduled, four stages

@@ -30,8 +30,6 @@ SGPR input bofs = distance from a wave's A request slots to its B request slots)
 """
 import os
 
-ABL = set(filter(None, os.environ.get("QG_GEN_ABL", "").split(",")))
-
 def configure(tm, tn, nstage=4):
     """sets the module-level plan for TM x TN blocks of 32 x 32 per wave (2 x 2 waves per workgroup)"""
     global TM, TN, NM, A, B, RS, AV, BV, ARD0, ARD1, BRD, VA, VB, STAGE_BYTES, A_STAGE, A_DMA, N_DMA, NREAD, RSLOTS
@@ -75,18 +73,6 @@ class Emit:
 
 def dma(e, q):
     """one tile request: q = 0..A_DMA-1 A, then B; m0 = request stage base + slot"""
-    if "nodma" in ABL:
-        return
-    if "m0each" in ABL:
-        if q < A_DMA:
-            e(f"s_add_u32 m0, s96, {q * 1024}")
-            e("s_nop 0")
-            e(f"global_load_lds_dwordx4 v{AV + q}, s[86:87]")
-        else:
-            e(f"s_add_u32 m0, s96, {A_STAGE + (q - A_DMA) * 1024}")
-            e("s_nop 0")
-            e(f"global_load_lds_dwordx4 v{BV + q - A_DMA}, s[88:89]")
-        return
     # The instruction offset is added to the global address AND to the LDS address, so one M0 value serves the
     # four requests of a group; the per-lane A offsets come in pre-biased by -q*1024 (B is contiguous anyway).
     if q == 0:
@@ -112,15 +98,13 @@ def advance_request_pointers(e):
 
 def mfma(e, i, use):
     mb, nb = i // TN, i % TN
-    if "nomfma" in ABL:
-        return
     e(f"v_mfma_i32_32x32x32_i8 %[c{i}], {vr(B[use] + 4 * nb)}, {vr(A[use] + 4 * mb)}, %[c{i}]")
 
 
 def reads(e, slot, ld, ks):
     """the two LDS reads of slot 0..RSLOTS-1: A fragments first (they are needed first), then B"""
     for j in (2 * slot, 2 * slot + 1):
-        if "nolds" in ABL or j >= NREAD:
+        if j >= NREAD:
             continue
         if j < TM:
             e(f"ds_read_b128 {vr(A[ld] + 4 * j)}, v{VA} offset:{j * 2048}")
@@ -144,8 +128,6 @@ def prep(e, slot, ld):
     """fragment f = (slot - first) // per; two slots per fragment: byte sums, then xor; one slot: both"""
     first, per = prep_slots()
     f, part = (slot - first) // per, (slot - first) % per
-    if "novalu" in ABL:
-        return
     base = A[ld] + 4 * f
     if part == 0:
         e(f"s_waitcnt lgkmcnt({NREAD - 1 - f})")
@@ -214,8 +196,7 @@ def tile(e, wait_vm, request, last=False):
         return
     # every wave: its requests for tile t+1 have landed, its reads of tile t are done
     e(f"s_waitcnt vmcnt({wait_vm}) lgkmcnt(0)")
-    if "nobar" not in ABL:
-        e("s_barrier")
+    e("s_barrier")
     if request:
         stage_offset(e, "s94", "s93")
         e("s_add_u32 s96, s91, s94")
@@ -316,6 +297,6 @@ def generate():
 
 if __name__ == "__main__":
     here = os.path.dirname(os.path.abspath(__file__))
-    with open(os.environ.get("QG_GEN_OUT", os.path.join(here, "tile_loop_asm.inc")), "w") as f:
+    with open(os.path.join(here, "tile_loop_asm.inc"), "w") as f:
         f.write(generate())
     print("wrote tile_loop_asm.inc")

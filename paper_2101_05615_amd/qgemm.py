@@ -23,7 +23,7 @@ EXPORTS = [
     "qg_gemm_u8s8_acc32_kernel", "qg_gemm_u8s8_dequant_f32", "qg_quantize_a_f32", "qg_gemm_f32_workspace_bytes",
     "qg_gemm_f32s8_requant", "qg_gemm_f32s8_dequant_f32",
     "qg_count_outliers", "qg_pack_b_outlier_sizes", "qg_pack_b_outlier", "qg_packed_b_nnz",
-    "qg_conv_dense_u8s8_requant", "qg_pack_b_transposed", "qg_probe_mfma_i8", "qg_probe_read",
+    "qg_conv_dense_u8s8_requant", "qg_pack_b_transposed",
     "qg_gemm_workspace_init", "qg_gemm_splitk_workspace_bytes", "qg_gemm_splitk_factor",
     "qg_gemm_u8s8_requant_splitk", "qg_gemm_u8s8_acc32_splitk", "qg_gemm_u8s8_requant_noalloc",
 ]
@@ -95,8 +95,6 @@ def _load():
     lib.qg_gemm_u8s8_requant_splitk.argtypes = [vp, i, i, vp, ctypes.POINTER(RequantParams), vp, i, vp, sz, vp, i, i]
     lib.qg_gemm_u8s8_acc32_splitk.argtypes = [vp, i, i, vp, vp, i, vp, vp, sz, vp, i, i]
     lib.qg_gemm_u8s8_requant_noalloc.argtypes = [vp, i, i, vp, ctypes.POINTER(RequantParams), vp, i, vp, i, i]
-    lib.qg_probe_mfma_i8.argtypes = [vp, vp, i, i, vp]
-    lib.qg_probe_read.argtypes = [vp, sz, vp, i, vp]
     return lib
 
 
@@ -529,18 +527,3 @@ def conv_dense_u8s8_requant(inp, Wp, a_zp, bias, scales, c_zp, relu, pad=1, stri
                                           ctypes.byref(p), out.data_ptr(), _stream(), kernel_id(kernel)),
            "qg_conv_dense_u8s8_requant")
     return out
-
-
-def probe_mfma_i8(operands, sink, workgroups, iters):
-    """Register-only int8 matrix-core loop on the first 32 KiB of `operands` (cuda, 16-byte aligned);
-    workgroups * 4 * iters * 16 * 65536 operations.  sink: int32 cuda, workgroups * 256 entries."""
-    assert operands.is_cuda and operands.numel() * operands.element_size() >= 32768
-    assert sink.is_cuda and sink.dtype == torch.int32 and sink.numel() >= workgroups * 256
-    _check(lib.qg_probe_mfma_i8(operands.data_ptr(), sink.data_ptr(), workgroups, iters, _stream()), "qg_probe_mfma_i8")
-
-
-def probe_read(src, sink, workgroups=4096):
-    """Streaming read of the whole cuda tensor `src` (a multiple of 16 bytes)."""
-    assert src.is_cuda and sink.is_cuda and sink.dtype == torch.int32
-    _check(lib.qg_probe_read(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(), workgroups, _stream()),
-           "qg_probe_read")

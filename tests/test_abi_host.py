@@ -87,17 +87,6 @@ def test_null_and_range_checks_happen_before_any_device_work(lib):
     assert lib.qg_conv_groupwise_u8s8_requant(fake, 1, 4, 4, 4, 1, 1, None, ctypes.byref(p), fake, None) == q.ENULL
     lib.qg_packed_b_destroy(None)
     assert lib.qg_packed_b_k(None) == 0 and lib.qg_gemm_workspace_bytes(16, None) == 0
-    # the measurement probes validate the same way
-    lib.qg_probe_mfma_i8.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
-    lib.qg_probe_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
-    assert lib.qg_probe_mfma_i8(None, fake, 1, 1, None) == q.ENULL
-    assert lib.qg_probe_mfma_i8(fake, fake, 0, 1, None) == q.EINVAL
-    assert lib.qg_probe_mfma_i8(fake, fake, 1, 0, None) == q.EINVAL
-    assert lib.qg_probe_mfma_i8(ctypes.c_void_p(260), fake, 1, 1, None) == q.EALIGN
-    assert lib.qg_probe_read(fake, 16, None, 1, None) == q.ENULL
-    assert lib.qg_probe_read(fake, 24, fake, 1, None) == q.EINVAL
-    assert lib.qg_probe_read(fake, 0, fake, 1, None) == q.EINVAL
-    assert lib.qg_probe_read(ctypes.c_void_p(264), 16, fake, 1, None) == q.EALIGN
 
 
 def test_status_strings(lib):
@@ -179,3 +168,15 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
                        timeout=120)
     assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_workload_biases_respect_the_documented_bound():
+    """qgemm.h: |bias[j]| <= 2^31 - 1 - 255 * 255 * K, outside of which the 32-bit corrected accumulator may wrap (the
+    oracle then reports an overflow).  The seeded generators must stay inside it."""
+    from paper_2101_05615_amd import workloads as wl
+    cases = [wl.config1_tiny(), wl.config2_small_batch_fc(with_bias=True), wl.random_gemm(1, 40, 50, 1000),
+             wl.random_gemm(2, 3, 16, 32768), wl.unsaturated(wl.random_gemm(3, 17, 33, 4097))]
+    for c in cases:
+        if c.bias is not None:
+            bound = 2 ** 31 - 1 - 255 * 255 * c.K
+            assert bound > 0 and int(abs(c.bias.astype("int64")).max()) <= bound, c.name

@@ -157,11 +157,12 @@ def test_extreme_zero_points(env, a_zp, b_zp, c_zp, M):
     assert_same(got, oracle_gemm(c, oracle), c.name)
 
 
-def test_hand_worked_rounding_cases_through_the_gpu(env):
-    # x is injected through the bias with an all-zero accumulator (A = theta_A everywhere); expected values
-    # are the hand-worked ones in tests/golden/requant_hand_cases.txt
+ALL_KERNELS = ["skinny16", "skinny32", "skinny64", "tile64", "tile128", "tile128x256", "tile256", "tile64k4", "tile64k1",
+               "tile64x32k8"]
+
+
+def _hand_rows():
     import os
-    q, torch, dev, oracle = env
     rows = []
     with open(os.path.join(os.path.dirname(__file__), "golden", "requant_hand_cases.txt")) as f:
         for line in f:
@@ -169,25 +170,72 @@ def test_hand_worked_rounding_cases_through_the_gpu(env):
             if line:
                 x, s, z, r, e = line.split()
                 rows.append((int(x), float(s), int(z), int(r), int(e)))
-    for M in (3, 70):  # both kernels
-        for x, s, z, r, e in rows:
-            A = np.full((M, 8), 7, np.uint8)
-            B = np.ones((8, 2), np.int8)
-            c = wl.GemmCase("hand", A, 7, B, np.zeros(1, np.int32), np.array([x, x], np.int32),
-                            np.array([s], np.float32), z, bool(r))
-            got, _, _ = run_gemm(c, q, torch, dev)
-            assert np.all(got == e), (M, x, s, z, r, e, got[0])
+    return rows
+
+
+@pytest.mark.parametrize("relu,c_zp", [(0, 0), (0, 10), (1, 0), (1, 10), (0, 255)])
+@pytest.mark.parametrize("kernel", ["auto"] + ALL_KERNELS)
+def test_hand_worked_rounding_cases_through_every_kernel(env, kernel, relu, c_zp):
+    """The hand-worked ties, saturation rows and +-2^31 accumulators of tests/golden/requant_hand_cases.txt through
+    every kernel's output pipeline -- both forms of it: the explicit clamp (ReLU with theta_C != 0) and the saturating
+    convert -- at K = 256, so that the hand-scheduled tiles run their own loop.  x is injected through the bias of a
+    column whose accumulator is zero (A = theta_A everywhere), one column per (x, scale) pair; theta_C and ReLU are per
+    call, so every pair is also run under the other combinations, where the expected byte is the oracle's per-element
+    function (itself pinned to the hand-worked values on the CPU)."""
+    q, torch, dev, oracle = env
+    rows = _hand_rows()
+    pairs = sorted({(x, s) for x, s, _, _, _ in rows})
+    M, K, N = 130, 256, len(pairs)
+    A = np.full((M, K), 7, np.uint8)
+    B = np.ones((K, N), np.int8)
+    bias = np.array([x for x, _ in pairs], np.int32)
+    scales = np.array([s for _, s in pairs], np.float32)
+    c = wl.GemmCase("hand", A, 7, B, np.zeros(1, np.int32), bias, scales, c_zp, bool(relu))
+    want = np.array([oracle.requant_one(x, s, c_zp, relu) for x, s in pairs], np.uint8)
+    n_golden = 0
+    for x, s, z, r, e in rows:  # the rows worked by hand for exactly this (theta_C, ReLU)
+        if z == c_zp and r == relu:
+            assert want[pairs.index((x, s))] == e
+            n_golden += 1
+    say(f"hand cases: kernel {kernel} relu {relu} c_zp {c_zp}: {N} columns, {n_golden} of them hand-worked for this combination")
+    Ad, Bd, biasd, scalesd, C, _ = dev_case(c, torch, dev)
+    Bp = q.pack_b(Bd, c.b_zp)
+    q.gemm_u8s8_requant(Ad, c.a_zp, Bp, biasd, scalesd, c.c_zp, c.relu, out=C, kernel=kernel)
+    torch.cuda.synchronize()
+    got = C.cpu().numpy()
+    assert_same(got, np.broadcast_to(want, (M, N)), f"{kernel} hand cases")
 
 
 # ---------------------------------------------------- the five stated configs
-def test_config1_tiny(env):
+@pytest.mark.parametrize("kernel", ["auto"] + ALL_KERNELS)
+def test_config1_tiny(env, kernel):
     q, torch, dev, oracle = env
     c = wl.config1_tiny()
-    got, _, _ = run_gemm(c, q, torch, dev)
-    assert_same(got, oracle_gemm(c, oracle), c.name)
-    u = wl.unsaturated(c)
-    got, _, _ = run_gemm(u, q, torch, dev)
-    assert_same(got, oracle_gemm(u, oracle), u.name)
+    for case in (c, wl.unsaturated(c)):
+        Ad, Bd, biasd, scalesd, C, _ = dev_case(case, torch, dev)
+        Bp = q.pack_b(Bd, case.b_zp)
+        q.gemm_u8s8_requant(Ad, case.a_zp, Bp, biasd, scalesd, case.c_zp, case.relu, out=C, kernel=kernel)
+        torch.cuda.synchronize()
+        assert_same(C.cpu().numpy(), oracle_gemm(case, oracle), f"{case.name} {kernel}")
+
+
+@pytest.mark.parametrize("relu,c_zp", [(0, 0), (1, 10)])
+@pytest.mark.parametrize("kernel", ALL_KERNELS)
+def test_tie_rich_scale_at_a_depth_the_hand_scheduled_loops_take(env, kernel, relu, c_zp):
+    """Config 1's scale 2^-10 makes the product exact and exact .5 ties frequent (about one output in a thousand);
+    here at K = 512 and over several tiles, so that the 128- and 256-row kernels run their hand-scheduled loops."""
+    q, torch, dev, oracle = env
+    c = wl.random_gemm(4242, 200, 330, 512, per_channel=False, with_bias=True, relu=bool(relu), a_zp=128, c_zp=c_zp)
+    c.scales = np.array([2.0 ** -10], np.float32)
+    c.b_zp = np.zeros(1, np.int32)
+    want, x = oracle.gemm_u8s8_requant(c.A, c.a_zp, c.B, c.b_zp, c.bias, c.scales, c.c_zp, c.relu, return_x=True)
+    ties = int(np.sum(np.abs(x) % 1024 == 512))
+    assert ties >= 20, ties
+    Ad, Bd, biasd, scalesd, C, _ = dev_case(c, torch, dev)
+    Bp = q.pack_b(Bd, c.b_zp)
+    q.gemm_u8s8_requant(Ad, c.a_zp, Bp, biasd, scalesd, c.c_zp, c.relu, out=C, kernel=kernel)
+    torch.cuda.synchronize()
+    assert_same(C.cpu().numpy(), want, f"{kernel} ties ({ties} exact halves)")
 
 
 @pytest.mark.parametrize("with_bias", [False, True])
@@ -228,14 +276,15 @@ def test_config3_square_full_size_sampled_rows(env):
     assert got1.min() >= c.c_zp
 
 
-def test_config4_recsys_mlp_full_size_sampled_rows(env):
+def test_config4_recsys_mlp_full_output(env):
+    """All 32768 x 512 outputs of config 4 (and of its unsaturated variant) against the oracle: every one of the 128
+    row tiles, through the variant without row offsets (theta_B = 0)."""
     q, torch, dev, oracle = env
     c = wl.config4_recsys_mlp()
     say(c.name)
-    rows = _sampled_rows(c.M, 256, np.random.default_rng(1), 64)
     for case in (c, wl.unsaturated(c)):
         got, _, _ = run_gemm(case, q, torch, dev)
-        assert_same(got[rows], oracle_gemm(case, oracle, rows), case.name + " sampled rows")
+        assert_same(got, oracle_gemm(case, oracle), case.name + " all rows")
 
 
 def test_determinism_and_independence_of_m_padding(env):
@@ -396,14 +445,24 @@ def test_empty_batch_is_a_checked_no_op(env):
 
 
 def test_measurement_probes_run(env):
-    """The probes are timing aids, not part of the path: they must launch, finish and leave their inputs alone."""
+    """bench.py's probes (a library of their own, not part of the path): they must launch, finish and leave their
+    inputs alone."""
+    import ctypes
+    import os
     q, torch, dev, oracle = env
     say("probes")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    bp = ctypes.CDLL(os.path.join(root, "libbench_probes.so"))
+    vp = ctypes.c_void_p
+    bp.bp_mfma_i8.argtypes = [vp, vp, ctypes.c_int, ctypes.c_int, vp]
+    bp.bp_read.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_int, vp]
     operands = torch.arange(32768, dtype=torch.int32, device=dev).to(torch.uint8)
     before = operands.clone()
     sink = torch.zeros(4 * 256, dtype=torch.int32, device=dev)
-    q.probe_mfma_i8(operands, sink, 4, 3)
+    st = torch.cuda.current_stream().cuda_stream
+    assert bp.bp_mfma_i8(operands.data_ptr(), sink.data_ptr(), 4, 3, st) == 0
     src = torch.ones(1 << 20, dtype=torch.uint8, device=dev)
-    q.probe_read(src, sink, workgroups=64)
+    assert bp.bp_read(src.data_ptr(), src.numel(), sink.data_ptr(), 64, st) == 0
+    assert bp.bp_read(src.data_ptr(), 24, sink.data_ptr(), 64, st) == -1 and bp.bp_mfma_i8(None, sink.data_ptr(), 4, 3, st) == -1
     torch.cuda.synchronize()
     assert torch.equal(operands, before) and int(src.sum().item()) == 1 << 20
