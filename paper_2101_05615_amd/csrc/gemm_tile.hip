@@ -88,7 +88,7 @@ __device__ __forceinline__ int a_lds_off(int r, int kc) { return r * BK + ((kc ^
                    [c12] "+a"(acc[3][0]), [c13] "+a"(acc[3][1]), [c14] "+a"(acc[3][2]), [c15] "+a"(acc[3][3]), \
                    [rs01] "=v"(rs01), [rs23] "=v"(rs23) \
                  : [av01] "v"(av01), [av23] "v"(av23), [bv01] "v"(bv01), [bv23] "v"(bv23), [ard] "v"(ard), \
-                   [brd] "v"(brd), [aptr] "s"(p.A - (A_DMA - 1) * 1024), [bptr] "s"(b_tile0), [kt] "s"(KTF), [ldsdma] "s"(lds_dma), \
+                   [brd] "v"(brd), [aptr] "s"(A - (A_DMA - 1) * 1024), [bptr] "s"(b_tile0), [kt] "s"(KTF), [ldsdma] "s"(lds_dma), \
                    [lds] "s"(lds_base), [bstep] "s"(b_step) \
                  : QG_TILE_LOOP_CLOBBERS
 
@@ -96,7 +96,7 @@ __device__ __forceinline__ int a_lds_off(int r, int kc) { return r * BK + ((kc ^
                  : [c0] "+a"(acc[0][0]), [c1] "+a"(acc[0][1]), [c2] "+a"(acc[1][0]), [c3] "+a"(acc[1][1]), \
                    [rs01] "=v"(rs01) \
                  : [av01] "v"(av01), [bv01] "v"(bv01), [ard] "v"(ard), [brd] "v"(brd), \
-                   [aptr] "s"(p.A - (A_DMA - 1) * 1024), [bptr] "s"(b_tile0), [kt] "s"(KTF), [ldsdma] "s"(lds_dma), \
+                   [aptr] "s"(A - (A_DMA - 1) * 1024), [bptr] "s"(b_tile0), [kt] "s"(KTF), [ldsdma] "s"(lds_dma), \
                    [lds] "s"(lds_base), [bstep] "s"(b_step) \
                  : QG_TILE_LOOP_CLOBBERS_2X2
 
@@ -105,7 +105,7 @@ __device__ __forceinline__ int a_lds_off(int r, int kc) { return r * BK + ((kc ^
                    [c4] "+a"(acc[1][0]), [c5] "+a"(acc[1][1]), [c6] "+a"(acc[1][2]), [c7] "+a"(acc[1][3]), \
                    [rs01] "=v"(rs01) \
                  : [av01] "v"(av01), [bv01] "v"(bv01), [ard] "v"(ard), [brd] "v"(brd), \
-                   [aptr] "s"(p.A - (A_DMA - 1) * 1024), [bptr] "s"(b_tile0), [kt] "s"(KTF), [ldsdma] "s"(lds_dma), \
+                   [aptr] "s"(A - (A_DMA - 1) * 1024), [bptr] "s"(b_tile0), [kt] "s"(KTF), [ldsdma] "s"(lds_dma), \
                    [lds] "s"(lds_base), [bstep] "s"(b_step), [bofs] "s"(A_STAGE + wave * ((B_DMA - A_DMA) * 1024)) \
                  : QG_TILE_LOOP_CLOBBERS_2X4
 
@@ -133,10 +133,19 @@ constexpr int min_wg_per_cu(int path, int blocks) {
 // NWM x NWN waves; set g consumes the k tiles g, g + 2, ... from its own LDS stages (a lone workgroup's k
 // step is a barrier / LDS read / MFMA chain, so two chains side by side halve the time of a thin grid), and the
 // two partial accumulators are added through LDS before the output pipeline, which set 0 runs.
-template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, bool CONV = false, int KS = 1>
-__global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) / KS) void qg_gemm_tile_kernel(const qg_gemm_args p,
-                                                                                                int tiles_m,
-                                                                                                int tiles_n) {
+// EPI: the form of the uint8 output pipeline, fixed per launch by the host (one copy of the pipeline per kernel: the
+// large tiles sit at the edge of the register budget): EPI_CLAMP the explicit clamp of the definition, EPI_SAT the
+// saturating convert doing the clamp (no ReLU, or theta_C == 0), EPI_SAT0 the same with theta_C == 0, where the
+// convert also does the rounding (v_cvt_pk_u8_f32 rounds to nearest even: checked on 4 M values, ties included).
+//
+// The leading scalar arguments repeat the fields of p that a wave needs before its first tile request: the file is
+// compiled with kernel-argument preloading, so they arrive in scalar registers with the wave instead of costing a
+// cold trip to memory.
+constexpr int EPI_CLAMP = 0, EPI_SAT = 1, EPI_SAT0 = 2;
+template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, bool CONV = false, int KS = 1, int EPI = EPI_CLAMP>
+__global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) / KS) void qg_gemm_tile_kernel(
+    const uint8_t* A, const int8_t* Bp, const int M, const int N, const int K, const int nb16_total, const int lda,
+    const int tiles_m, const int tiles_n, const qg_gemm_args p) {
   static_assert(KS == 1 || ((KS == 2 || KS == 4 || KS == 8) && PATH == PATH_PIPE), "K split: wave sets on the pipelined path");
   constexpr int NW = NWM * NWN, NT = NW * KS * 64;  // NW: waves of one set; NT: threads of the workgroup
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
@@ -184,7 +193,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
   for (int q = 0; q < A_DMA; ++q) {
     const int r = (wave * A_DMA + q) * 16 + (lane >> 2);
     const int kc = (lane & 3) ^ a_swz(r);
-    const int rg = min(m0 + r, p.M - 1);  // rows past M re-read the last row; never stored
+    const int rg = min(m0 + r, M - 1);  // rows past M re-read the last row; never stored
     if (CONV) {
       const int wo = rg % p.cv_Wo, t = rg / p.cv_Wo;
       const int ho = t % p.cv_Ho, n = t / p.cv_Ho;
@@ -195,13 +204,13 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
     }
     // hand-scheduled loop: it uses instruction offset q*1024 (it moves the LDS slot AND the global address, so one
     // M0 serves a group of requests) against a base of A - (A_DMA-1) KiB; the per-lane offset absorbs the difference
-    a_voff[q] = (unsigned)rg * (unsigned)p.lda + kc * 16 + (PATH == PATH_ASM ? (A_DMA - 1 - q) * 1024 : 0);
+    a_voff[q] = (unsigned)rg * (unsigned)lda + kc * 16 + (PATH == PATH_ASM ? (A_DMA - 1 - q) * 1024 : 0);
   }
 #pragma unroll
   for (int q = 0; q < B_DMA; ++q)
     b_voff[q] = (unsigned)(wave * B_DMA + q) * QG_FRAG_BYTES + lane * 16;
-  const int8_t* b_tile0 = p.Bp + (size_t)(n0 / QG_FRAG_COLS) * QG_FRAG_BYTES;
-  const unsigned b_step = (unsigned)p.nb16 * QG_FRAG_BYTES;  // one 64-deep slab of the packed buffer
+  const int8_t* b_tile0 = Bp + (size_t)(n0 / QG_FRAG_COLS) * QG_FRAG_BYTES;
+  const unsigned b_step = (unsigned)nb16_total * QG_FRAG_BYTES;  // one 64-deep slab of the packed buffer
 
   // ---- fragment fetch (LDS -> registers): per-lane base offsets, everything else is an immediate
   int a_rd[2];  // k-step 0 / 1 of block mb = 0; block mb is 32 rows = 2 KiB further
@@ -239,7 +248,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
   if (CONV) {
 #pragma unroll
     for (int mb = 0; mb < TM; ++mb) {
-      const int m = min(m0 + (wave_m * TM + mb) * 32 + l32, p.M - 1);
+      const int m = min(m0 + (wave_m * TM + mb) * 32 + l32, M - 1);
       const int wo = m % p.cv_Wo, ho = (m / p.cv_Wo) % p.cv_Ho;
       cv_h[mb] = ho * p.cv_stride - p.cv_pad;
       cv_w[mb] = wo * p.cv_stride - p.cv_pad;
@@ -281,10 +290,10 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
       for (int nb = 0; nb < TN; ++nb)
         acc[mb][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf[nb], af[mb], acc[mb][nb], 0, 0, 0);
   };
-  const int KT = (p.K + BK - 1) / BK;  // tiles that hold real data
+  const int KT = (K + BK - 1) / BK;  // tiles that hold real data
   // the pipelined loops run the KTF whole tiles; a ragged last tile (K % 64 bytes of A) is staged through
   // registers afterwards, once per workgroup
-  const int KTF = p.K / BK;
+  const int KTF = K / BK;
   v4i a0[TM], b0[TN], a1[TM], b1[TN];
   if constexpr (PATH == PATH_ASM) {
     // Tile kt lives in stage kt % 4.  In iteration kt: the first k-step runs while the fragments of
@@ -351,7 +360,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
       cv_advance(cs_kh, cs_kw, cs_cc, kg);
     }
     auto request = [&](int kt, int stage) {
-      const uint8_t* ab = p.A + (size_t)kt * BK;
+      const uint8_t* ab = A + (size_t)kt * BK;
       const int8_t* bb = b_tile0 + (size_t)kt * b_step;
       unsigned char* st = smem + (stage * KS + kg) * STAGE;
       if (CONV) {
@@ -360,7 +369,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
         for (int q = 0; q < A_DMA; ++q) {
           int off = a_pix[q] + tap_off;
           off = min(max(off, 0), p.cv_in_bytes - 16);  // taps outside the image: any valid address, masked later
-          dma16(p.A + off, st + (wave * A_DMA + q) * 1024);
+          dma16(A + off, st + (wave * A_DMA + q) * 1024);
         }
         cv_advance(rq_kh, rq_kw, rq_cc, KS);
       } else
@@ -411,14 +420,14 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
     const int k0 = KTF * BK;
     __syncthreads();  // every wave is done with the stages
     if (kg == 0) {
-      const size_t a_end = (size_t)(p.M - 1) * (size_t)p.lda + (size_t)p.K;  // one past the last byte A is known to have
+      const size_t a_end = (size_t)(M - 1) * (size_t)lda + (size_t)K;  // one past the last byte A is known to have
 #pragma unroll
       for (int q = 0; q < A_DMA; ++q) {
         const int r = (wave * A_DMA + q) * 16 + (lane >> 2);
         const int kc = (lane & 3) ^ a_swz(r);
-        const size_t off = (size_t)min(m0 + r, p.M - 1) * (size_t)p.lda + (size_t)(kc * 16 + k0);
+        const size_t off = (size_t)min(m0 + r, M - 1) * (size_t)lda + (size_t)(kc * 16 + k0);
         *reinterpret_cast<v4i*>(smem + (wave * A_DMA + q) * 1024 + lane * 16) =
-            qg_load_a_chunk(p.A + off, p.K - (k0 + kc * 16), off + 16 <= a_end);
+            qg_load_a_chunk(A + off, K - (k0 + kc * 16), off + 16 <= a_end);
       }
       const int8_t* b_base = b_tile0 + (size_t)KTF * b_step;
 #pragma unroll
@@ -492,11 +501,11 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
     const int col = n0 + t;  // col_off / bzp are padded to N_pad, bias / scales are not
     const int co = p.col_off[col], bz = p.bzp[col];
     if (MODE != QG_MODE_ACC32) {
-      const int b = (p.bias != nullptr && col < p.N) ? p.bias[col] : 0;
+      const int b = (p.bias != nullptr && col < N) ? p.bias[col] : 0;
       cj_s[t] = b - p.a_zp_m128 * co;
-      sc_s[t] = (col < p.N) ? p.scales[(size_t)col * p.scale_stride] : 1.0f;
+      sc_s[t] = (col < N) ? p.scales[(size_t)col * p.scale_stride] : 1.0f;
     } else {
-      cj_s[t] = 128 * (co + p.K * bz);  // acc_u = acc_s + 128 * colsum
+      cj_s[t] = 128 * (co + K * bz);  // acc_u = acc_s + 128 * colsum
     }
     bz_s[t] = -bz;  // negated: x = acc + cj + (-theta_B) * rowsum
   }
@@ -507,12 +516,8 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
   // 32*mb + l32 and the 16 consecutive columns 32*nb + 16*lg .. +15; the per-column constants of a
   // column block are fetched once and reused for the wave's TM row blocks.
   if (MODE != QG_MODE_ACC32) {
-    const bool full_cols = p.c_vec && (n0 + BN <= p.N);  // uniform: every 16-byte store is in range
+    const bool full_cols = p.c_vec && (n0 + BN <= N);  // uniform: every 16-byte store is in range
     const float czp_f = (float)p.c_zp;
-    // LO: the output pipeline needs its explicit lower clamp (see qg_requant_pack); uniform over the launch.
-    // One-block waves keep the single, always-correct form: their pipeline is 16 values per lane, and a second
-    // copy of it costs registers that the occupancy of those kernels needs.
-    const bool need_lo = MODE == QG_MODE_REQUANT && (TM * TN == 1 || qg_requant_needs_lo(p.clamp_lo, czp_f));
 #pragma unroll
     for (int nb = 0; nb < TN; ++nb) {
       const int col_l = (wave_n * TN + nb) * 32 + lg * 16;
@@ -525,8 +530,6 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
         *reinterpret_cast<v4i*>(&nbz[4 * q]) = *reinterpret_cast<const v4i*>(&bz_s[col_l + 4 * q]);
         *reinterpret_cast<float4*>(&sc[4 * q]) = *reinterpret_cast<const float4*>(&sc_s[col_l + 4 * q]);
       }
-      auto rows = [&](auto lo_tag) {
-      constexpr bool LO = decltype(lo_tag)::value;
 #pragma unroll
       for (int mb = 0; mb < TM; ++mb) {
         const int row = m0 + (wave_m * TM + mb) * 32 + l32;
@@ -540,22 +543,25 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
             for (int t = 0; t < 4; ++t) {
               const int i = 4 * q + t;
               const int x = acc[mb][nb][i] + cj[i] + (ROWSUM ? __mul24(nbz[i], rsum) : 0);
-              w = qg_requant_pack<LO>(x, sc[i], p.clamp_lo, p.clamp_hi, czp_f, t, w);
+              if constexpr (EPI == EPI_SAT0)
+                w = qg_requant_pack0(x, sc[i], t, w);
+              else
+                w = qg_requant_pack<EPI == EPI_CLAMP>(x, sc[i], p.clamp_lo, p.clamp_hi, czp_f, t, w);
             }
             out[q] = w;
           }
-          if (row < p.M) {
+          if (row < M) {
             uint8_t* dst = p.C + (size_t)row * p.ldc + col;
             if (full_cols) {
               *reinterpret_cast<uint4*>(dst) = make_uint4(out[0], out[1], out[2], out[3]);
-            } else if (col + 16 <= p.N) {
+            } else if (col + 16 <= N) {
               // any address: one 16-byte store all the same
               *reinterpret_cast<qg_v4i_unaligned*>(dst) = (v4i){(int)out[0], (int)out[1], (int)out[2], (int)out[3]};
             } else {
               // the lanes whose 16 columns N cuts
 #pragma unroll
               for (int i = 0; i < 16; ++i)
-                if (col + i < p.N) dst[i] = (uint8_t)(out[i >> 2] >> ((i & 3) * 8));
+                if (col + i < N) dst[i] = (uint8_t)(out[i >> 2] >> ((i & 3) * 8));
             }
           }
         } else {
@@ -566,13 +572,13 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
             const int x = acc[mb][nb][i] + cj[i] + (ROWSUM ? __mul24(nbz[i], rsum) : 0);
             out[i] = qg_dequant_one(x, sc[i], p.relu_lo);
           }
-          if (row < p.M) {
+          if (row < M) {
             float* dst = p.Cf + (size_t)row * p.ldc + col;
             if (full_cols) {
 #pragma unroll
               for (int q = 0; q < 4; ++q)
                 *reinterpret_cast<float4*>(dst + 4 * q) = make_float4(out[4 * q], out[4 * q + 1], out[4 * q + 2], out[4 * q + 3]);
-            } else if (col + 16 <= p.N) {
+            } else if (col + 16 <= N) {
 #pragma unroll
               for (int q = 0; q < 4; ++q)
                 *reinterpret_cast<qg_v4i_unaligned*>(dst + 4 * q) =
@@ -581,24 +587,19 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
             } else {
 #pragma unroll
               for (int i = 0; i < 16; ++i)
-                if (col + i < p.N) dst[i] = out[i];
+                if (col + i < N) dst[i] = out[i];
             }
           }
         }
       }
-      };
-      if (need_lo)
-        rows(std::true_type{});
-      else
-        rows(std::false_type{});
     }
   } else {
 #pragma unroll
     for (int mb = 0; mb < TM; ++mb) {
       const int row = m0 + (wave_m * TM + mb) * 32 + l32;
-      if (row >= p.M) continue;
+      if (row >= M) continue;
       if (p.rowsum_out != nullptr && tn == 0 && wave_n == 0 && lg == 0)
-        p.rowsum_out[row] = rsum_s[mb] + 128 * p.K;
+        p.rowsum_out[row] = rsum_s[mb] + 128 * K;
 #pragma unroll
       for (int nb = 0; nb < TN; ++nb) {
         const int col_l = (wave_n * TN + nb) * 32 + lg * 16;
@@ -606,13 +607,13 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
         int32_t* dst = p.C32 + (size_t)row * p.ldc + col;
 #pragma unroll
         for (int i = 0; i < 16; ++i)
-          if (col + i < p.N) dst[i] = acc[mb][nb][i] + cj_s[col_l + i];
+          if (col + i < N) dst[i] = acc[mb][nb][i] + cj_s[col_l + i];
       }
     }
   }
 }
 
-template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, int KS = 1>
+template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, int KS = 1, int EPI = EPI_CLAMP>
 hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
   constexpr int STAGES = (PATH == PATH_ASM ? asm_stages(TM * TN) : pipe_stages(TM * TN)) * KS;
@@ -620,45 +621,73 @@ hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   constexpr int SMEM = STAGES * (BM + BN) * BK > 12 * BN ? STAGES * (BM + BN) * BK : 12 * BN;
   const int tiles_m = (a.M + BM - 1) / BM;
   const int tiles_n = (a.N + BN - 1) / BN;
-  constexpr auto fn = qg_gemm_tile_kernel<MODE, PATH, ROWSUM, NWM, NWN, TM, TN, false, KS>;
+  constexpr auto fn = qg_gemm_tile_kernel<MODE, PATH, ROWSUM, NWM, NWN, TM, TN, false, KS, EPI>;
   hipError_t e = qg_allow_smem<fn>(SMEM);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(fn, dim3((unsigned)(tiles_m * tiles_n)), dim3(NWM * NWN * KS * 64), SMEM, s, a, tiles_m,
-                     tiles_n);
+  hipLaunchKernelGGL(fn, dim3((unsigned)(tiles_m * tiles_n)), dim3(NWM * NWN * KS * 64), SMEM, s, a.A, a.Bp, a.M, a.N, a.K,
+                     a.nb16, a.lda, tiles_m, tiles_n, a);
   return hipGetLastError();
+}
+
+// which form of the uint8 output pipeline this launch needs (see EPI above); one-block waves keep the single,
+// always-correct form: their pipeline is 16 values per lane
+template <int BLOCKS>
+int epi_form(const qg_gemm_args& a) {
+  if (BLOCKS == 1 || qg_requant_needs_lo_host(a.clamp_lo, a.c_zp)) return EPI_CLAMP;
+  return a.c_zp == 0 ? EPI_SAT0 : EPI_SAT;
+}
+template <int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, int KS>
+hipError_t launch_requant(const qg_gemm_args& a, hipStream_t s) {
+  if constexpr (TM * TN == 1) {
+    return launch<QG_MODE_REQUANT, PATH, ROWSUM, NWM, NWN, TM, TN, KS, EPI_CLAMP>(a, s);
+  } else {
+    switch (epi_form<TM * TN>(a)) {
+      case EPI_SAT0: return launch<QG_MODE_REQUANT, PATH, ROWSUM, NWM, NWN, TM, TN, KS, EPI_SAT0>(a, s);
+      case EPI_SAT: return launch<QG_MODE_REQUANT, PATH, ROWSUM, NWM, NWN, TM, TN, KS, EPI_SAT>(a, s);
+      default: return launch<QG_MODE_REQUANT, PATH, ROWSUM, NWM, NWN, TM, TN, KS, EPI_CLAMP>(a, s);
+    }
+  }
 }
 
 // requant mode with / without the row-offset term; the int32 test hook always carries the row sums
 template <int PATH, int NWM, int NWN, int TM, int TN, int KS = 1>
 hipError_t launch_cfg(const qg_gemm_args& a, int mode, hipStream_t s) {
   if (mode == QG_MODE_REQUANT)
-    return a.has_bzp ? launch<QG_MODE_REQUANT, PATH, true, NWM, NWN, TM, TN, KS>(a, s)
-                     : launch<QG_MODE_REQUANT, PATH, false, NWM, NWN, TM, TN, KS>(a, s);
+    return a.has_bzp ? launch_requant<PATH, true, NWM, NWN, TM, TN, KS>(a, s)
+                     : launch_requant<PATH, false, NWM, NWN, TM, TN, KS>(a, s);
   if (mode == QG_MODE_DEQUANT)
     return a.has_bzp ? launch<QG_MODE_DEQUANT, PATH, true, NWM, NWN, TM, TN, KS>(a, s)
                      : launch<QG_MODE_DEQUANT, PATH, false, NWM, NWN, TM, TN, KS>(a, s);
   return launch<QG_MODE_ACC32, PATH, true, NWM, NWN, TM, TN, KS>(a, s);
 }
 
-template <int NWM, int NWN, int TM, int TN, int KS = 1>
-hipError_t launch_conv(const qg_gemm_args& a, hipStream_t s) {
+template <bool ROWSUM, int NWM, int NWN, int TM, int TN, int KS, int EPI>
+hipError_t launch_conv_epi(const qg_gemm_args& a, hipStream_t s) {
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
   constexpr int SMEM = pipe_stages(TM * TN) * KS * (BM + BN) * BK;
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
   const dim3 grid((unsigned)(tiles_m * tiles_n)), block(NWM * NWN * KS * 64);
-  hipError_t e;
-  if (a.has_bzp) {
-    constexpr auto fn = qg_gemm_tile_kernel<QG_MODE_REQUANT, PATH_PIPE, true, NWM, NWN, TM, TN, true, KS>;
-    e = qg_allow_smem<fn>(SMEM);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(fn, grid, block, SMEM, s, a, tiles_m, tiles_n);
-  } else {
-    constexpr auto fn = qg_gemm_tile_kernel<QG_MODE_REQUANT, PATH_PIPE, false, NWM, NWN, TM, TN, true, KS>;
-    e = qg_allow_smem<fn>(SMEM);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(fn, grid, block, SMEM, s, a, tiles_m, tiles_n);
-  }
+  constexpr auto fn = qg_gemm_tile_kernel<QG_MODE_REQUANT, PATH_PIPE, ROWSUM, NWM, NWN, TM, TN, true, KS, EPI>;
+  hipError_t e = qg_allow_smem<fn>(SMEM);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(fn, grid, block, SMEM, s, a.A, a.Bp, a.M, a.N, a.K, a.nb16, a.lda, tiles_m, tiles_n, a);
   return hipGetLastError();
+}
+template <bool ROWSUM, int NWM, int NWN, int TM, int TN, int KS>
+hipError_t launch_conv_rs(const qg_gemm_args& a, hipStream_t s) {
+  if constexpr (TM * TN == 1) {
+    return launch_conv_epi<ROWSUM, NWM, NWN, TM, TN, KS, EPI_CLAMP>(a, s);
+  } else {
+    switch (epi_form<TM * TN>(a)) {
+      case EPI_SAT0: return launch_conv_epi<ROWSUM, NWM, NWN, TM, TN, KS, EPI_SAT0>(a, s);
+      case EPI_SAT: return launch_conv_epi<ROWSUM, NWM, NWN, TM, TN, KS, EPI_SAT>(a, s);
+      default: return launch_conv_epi<ROWSUM, NWM, NWN, TM, TN, KS, EPI_CLAMP>(a, s);
+    }
+  }
+}
+template <int NWM, int NWN, int TM, int TN, int KS = 1>
+hipError_t launch_conv(const qg_gemm_args& a, hipStream_t s) {
+  return a.has_bzp ? launch_conv_rs<true, NWM, NWN, TM, TN, KS>(a, s) : launch_conv_rs<false, NWM, NWN, TM, TN, KS>(a, s);
 }
 
 }  // namespace

@@ -203,6 +203,13 @@ __device__ __forceinline__ unsigned qg_requant_pack(int x, float sc, float lo, f
 }
 // whether the explicit lower clamp is needed: ReLU (lo == 0 in the shifted domain) with a nonzero theta_C
 __device__ __forceinline__ bool qg_requant_needs_lo(float lo, float czp_f) { return lo == 0.0f && czp_f != 0.0f; }
+// theta_C == 0 and no explicit lower clamp: the saturating convert also does the rounding (v_cvt_pk_u8_f32 rounds to
+// nearest even), so sat_u8(rne(x * s)) is the convert of the product itself
+__device__ __forceinline__ unsigned qg_requant_pack0(int x, float sc, unsigned pos, unsigned word) {
+  const float f = (float)x;
+  const float p = f * sc;
+  return __builtin_amdgcn_cvt_pk_u8_f32(p, pos, word);
+}
 // fp32 output of one corrected accumulator: int32 -> fp32 (nearest even), ONE fp32 multiply, optional
 // max(., 0) (lo = 0 with ReLU, -inf without; a select, so no NaN-canonicalising extra instruction).
 __device__ __forceinline__ float qg_dequant_one(int x, float sc, float lo) {
@@ -210,6 +217,9 @@ __device__ __forceinline__ float qg_dequant_one(int x, float sc, float lo) {
   return v < lo ? lo : v;
 }
 #endif
+
+// host side of qg_requant_needs_lo (clamp_lo == 0 means ReLU: lo - theta_C with lo = theta_C)
+static inline bool qg_requant_needs_lo_host(float clamp_lo, int c_zp) { return clamp_lo == 0.0f && c_zp != 0; }
 
 #ifdef __HIPCC__
 // Raises kernel Fn's dynamic-LDS limit to `bytes` on the current device unless that was already done: the
