@@ -233,18 +233,21 @@ int clamp_ksplit(const qg_packed_b* Bp, int ksplit) {
   const int per = ceil_div(blocks, ksplit);
   return ceil_div(blocks, per);
 }
-// Built-in choice of the split: as many slices as it takes to give every CU a workgroup, while every wave of
-// a slice still has two 64-deep blocks of K to stream.
+// Built-in choice of the split, from timings of 16 x {16..512} x {4096..32768} and 64 x {64, 256} x {8192, 16384}
+// (cold weights): handing a partial tile through the workspace costs 1.5 - 2 us, so a split pays only where it
+// removes several batches of weight loads from every wave's chain.  Give each wave of a slice four 64-deep blocks
+// (one batch of loads); take the split from 4 slices up (from 2 for 64-row blocks, whose waves do four times the
+// work per block), and never more slices than there are idle CUs to take them.
 int auto_ksplit(int kernel, int M, const qg_packed_b* Bp) {
   if (kernel < QG_KERNEL_SKINNY16 || kernel > QG_KERNEL_SKINNY64) return 1;
   const int rows = 16 << (kernel - QG_KERNEL_SKINNY16);
   const long long wgs = (long long)ceil_div(M, rows) * (2 * ceil_div(Bp->N, 32));
   if (wgs * 2 > 256) return 1;
-  int s = (int)(256 / wgs);
-  const int by_depth = Bp->K_pad / QG_FRAG_K / 32;  // 16 waves x 2 blocks
-  if (s > by_depth) s = by_depth;
+  int s = Bp->K_pad / QG_FRAG_K / (16 * 4);  // 16 waves x 4 blocks
+  if (s > 256 / wgs) s = (int)(256 / wgs);
   if (s > 16) s = 16;
-  return s < 2 ? 1 : clamp_ksplit(Bp, s);
+  if (s < (rows == 64 ? 2 : 4)) return 1;
+  return clamp_ksplit(Bp, s);
 }
 // ksplit_req: 0 = built-in choice (1 without a workspace), otherwise the caller's.  Fills the workspace fields of `a`.
 int resolve_ksplit(const qg_packed_b* Bp, int M, int kernel, int ksplit_req, void* workspace_dev, size_t workspace_bytes,

@@ -70,7 +70,11 @@ __device__ __forceinline__ void wait_vm() {
 // SIMPLE: the straight-line variant for the common case the host has checked -- 8-bit weights, 16-byte aligned
 // rows, K a whole number of 64-deep blocks and every wave of every slice a whole number of batches: no partial
 // batch, no lane-copied staging, every request issued by hand in a known order.
-template <int MODE, int MB, int NWAVES, int BATCH, bool B4, bool ANYALIGN, bool SIMPLE = false>
+// CPW (straight-line variant only): fragment columns per wave.  With two, a workgroup of four waves covers a whole
+// 32-column super-block: every activation fragment feeds two MFMAs, the workgroup stages half as many activation
+// bytes per weight byte, and few fat waves (16 weight loads in flight each) keep a large matrix streaming at the
+// rate of a plain read -- the shape for weights of tens of MiB, where the 16-wave form pays for its A traffic.
+template <int MODE, int MB, int NWAVES, int BATCH, bool B4, bool ANYALIGN, bool SIMPLE = false, int CPW = 1>
 __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8_t* A, const int8_t* Bp, const int M, const int N, const int K, const int kb64,
                                                                    const int nb16_total, const int lda, const int ks_per, const int ksplit,
                                                                    const qg_gemm_args p) {
@@ -78,16 +82,18 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
   // names in p): the file is compiled with kernel-argument preloading, so they arrive in scalar registers with the
   // wave instead of costing a cold trip to memory (measured: 0.4 us of a 5 us launch).
   static_assert(!SIMPLE || (!B4 && !ANYALIGN), "the straight-line variant takes dense 8-bit weights and aligned rows");
+  static_assert(CPW == 1 || SIMPLE, "several fragment columns per wave: straight-line variant only");
+  static_assert(MB * CPW <= NWAVES && CPW <= BATCH, "one wave per (row block, fragment column) runs the output pipeline");
   const bool a_vec = ANYALIGN || p.a_vec;  // whole 16-byte chunks may be moved as such
   using chunk_t = typename std::conditional<ANYALIGN, qg_v4i_unaligned, v4i>::type;
   // A through LDS (see the file header): per wave and batch, ROWS rows x ROWB bytes
   constexpr int ROWS = MB * 16, ROWB = BATCH * QG_FRAG_K, NCHUNK = ROWB / 16;
   constexpr int REGION = ROWS * ROWB, NREQ = REGION / 1024, RPR = 64 / NCHUNK;  // requests per batch, rows per request
-  static_assert(NCHUNK == 8 || NCHUNK == 16, "a request covers whole rows of 128 or 256 bytes");
-  constexpr int PART_BYTES = NWAVES * MB * 64 * (int)sizeof(v4i);
+  static_assert(NCHUNK == 8 || NCHUNK == 16 || NCHUNK == 32, "a request covers whole rows of 128, 256 or 512 bytes");
+  constexpr int PART_BYTES = NWAVES * MB * CPW * 64 * (int)sizeof(v4i);
   constexpr int RSP_BYTES = NWAVES * MB * 16 * (int)sizeof(int);
   constexpr int STAGE_BYTES = NWAVES * REGION;
-  // every wave leaves its K-split partial sums (MB KiB) at the start of its OWN staging region (MB * BATCH KiB) once
+  // every wave leaves its K-split partial sums (MB * CPW KiB) at the start of its OWN staging region (MB * BATCH KiB) once
   // it is done with it: no wave waits for the others before it may write
   static_assert(PART_BYTES <= STAGE_BYTES, "a wave's partial tile fits its staging region");
   constexpr int UNION_BYTES = STAGE_BYTES;
@@ -95,10 +101,9 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
   int* rsp = reinterpret_cast<int*>(smem + UNION_BYTES);    // [mb][row][wave]
   int* sp = reinterpret_cast<int*>(smem + UNION_BYTES + RSP_BYTES);  // B4: [row][slot] sparse term
 
-  const int nb16 = blockIdx.x;
-  const int sb = nb16 >> 1, sfrag = nb16 & 1;
-  // columns held by this fragment: sb*32 + 16*(u&1) + 8*sfrag + 4*(u>>1) + r, u<4, r<4
-  if (sb * 32 + 8 * sfrag >= N) return;  // nothing but padding (uniform for the workgroup)
+  const int nb16 = blockIdx.x * CPW;  // first fragment column of this workgroup
+  // columns held by fragment f: (f>>1)*32 + 16*(u&1) + 8*(f&1) + 4*(u>>1) + r, u<4, r<4
+  if ((nb16 >> 1) * 32 + 8 * (nb16 & 1) >= N) return;  // nothing but padding (uniform for the workgroup)
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -109,11 +114,13 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
   // BEHIND the first batch's weight loads and activation requests (load_ep is called from the first batch): cold,
   // they take a trip to HBM, and nothing on the request path may end up waiting for them (the compiler had paired
   // a pending constant with an address computation and stalled the requests of exactly the wave the others wait for).
-  const int c0 = sb * 32 + 16 * (g & 1) + 8 * sfrag + 4 * (g >> 1);  // this lane's 4 output columns
+  // wave w < MB * CPW runs the output pipeline of row block w / CPW, fragment column nb16 + w % CPW
+  const int red_mb = wave / CPW, red_c = wave % CPW;
+  const int c0 = ((nb16 + red_c) >> 1) * 32 + 16 * (g & 1) + 8 * ((nb16 + red_c) & 1) + 4 * (g >> 1);  // this lane's 4 output columns
   int ep_co[4] = {0, 0, 0, 0}, ep_bz[4] = {0, 0, 0, 0}, ep_bias[4] = {0, 0, 0, 0};
   float ep_sc[4] = {1.0f, 1.0f, 1.0f, 1.0f};
   auto load_ep = [&]() {
-    if (wave < MB) {
+    if (wave < MB * CPW) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int col = c0 + r;  // col_off / bzp are padded to N_pad, bias / scales are not
@@ -149,11 +156,12 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
     sp_offs = col[min(kb_begin + BATCH * lane, kb_end)];
   }
 
-  v4i acc[MB];
+  v4i acc[MB][CPW];
   unsigned rs[MB];  // sums of raw uint8 bytes (K padding reads as 0x80)
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
-    acc[mb] = (v4i){0, 0, 0, 0};
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) acc[mb][c] = (v4i){0, 0, 0, 0};
     rs[mb] = 0;
   }
   // 8-bit: one 1 KiB fragment per k block, 16 bytes per lane.  4-bit: one 1 KiB unit per PAIR of k blocks, 16 bytes
@@ -270,7 +278,7 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
           rs[mb] = __builtin_amdgcn_sad_u8(af[mb][j].z, 0u, rs[mb]);
           rs[mb] = __builtin_amdgcn_sad_u8(af[mb][j].w, 0u, rs[mb]);
           const v4i a = af[mb][j] ^ (int)0x80808080;
-          acc[mb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(bfj, a, acc[mb], 0, 0, 0);
+          acc[mb][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(bfj, a, acc[mb][0], 0, 0, 0);
         }
       }
     if (B4) {
@@ -299,14 +307,17 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
     const uint8_t* aptr = A + (size_t)kb_begin * QG_FRAG_K;
     unsigned char* region = smem + wave * REGION;
     const unsigned region_lds = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)region);
-    auto issue_w = [&](int b, v4i (&raw)[BATCH]) {
+    auto issue_w = [&](int b, v4i (&raw)[BATCH * CPW]) {
       const int8_t* bp = bptr + (size_t)b * BATCH * b_step;
 #pragma unroll
-      for (int i = 0; i < BATCH; ++i) raw[i] = *reinterpret_cast<const v4i*>(bp + (size_t)i * b_step + lane16);
+      for (int i = 0; i < BATCH; ++i)
+#pragma unroll
+        for (int c = 0; c < CPW; ++c)  // the CPW fragments of one k block are adjacent KiBs
+          raw[i * CPW + c] = *reinterpret_cast<const v4i*>(bp + (size_t)i * b_step + c * QG_FRAG_BYTES + lane16);
     };
     // batch b: its weights were requested one batch earlier; request its activations, (first batch) the constants of
     // the output pipeline, the next batch's weights; wait for everything older than those; consume
-    auto step = [&](int b, v4i (&cur)[BATCH], v4i (&nxt)[BATCH], auto first_tag) {
+    auto step = [&](int b, v4i (&cur)[BATCH * CPW], v4i (&nxt)[BATCH * CPW], auto first_tag) {
       const uint8_t* ab = aptr + (size_t)b * (BATCH * QG_FRAG_K);
 #pragma unroll
       for (int jj = 0; jj < NREQ; ++jj) request_a(ab, a_off[jj], region_lds + jj * 1024);
@@ -314,7 +325,7 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
       asm volatile("" ::: "memory");
       if (b + 1 < nbatch) {
         issue_w(b + 1, nxt);
-        wait_vm<BATCH>();
+        wait_vm<BATCH * CPW>();
       } else {
         wait_vm<0>();
       }
@@ -335,11 +346,13 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
           rs[mb] = __builtin_amdgcn_sad_u8(af[mb][j].z, 0u, rs[mb]);
           rs[mb] = __builtin_amdgcn_sad_u8(af[mb][j].w, 0u, rs[mb]);
           const v4i a = af[mb][j] ^ (int)0x80808080;
-          acc[mb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(cur[j], a, acc[mb], 0, 0, 0);
+#pragma unroll
+          for (int c = 0; c < CPW; ++c)
+            acc[mb][c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(cur[j * CPW + c], a, acc[mb][c], 0, 0, 0);
         }
       asm volatile("" ::: "memory");  // the fragment reads stay in front of the next batch's requests into the same region
     };
-    v4i w0[BATCH], w1[BATCH];
+    v4i w0[BATCH * CPW], w1[BATCH * CPW];
     issue_w(0, w0);
     step(0, w0, w1, std::true_type{});
     for (int b = 1; b < nbatch; b += 2) {
@@ -363,7 +376,8 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
   // ---- combine the 16 K-slices through LDS (a wave's fragment reads of its region are complete: the MFMAs consumed them)
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
-    reinterpret_cast<v4i*>(smem + wave * REGION)[mb * 64 + lane] = acc[mb];
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) reinterpret_cast<v4i*>(smem + wave * REGION)[(mb * CPW + c) * 64 + lane] = acc[mb][c];
     // the four lanes (ml, g = 0..3) of a row hold its byte sums over different k: add them with two lane swaps
     // (v_permlane32_swap / v_permlane16_swap; a shuffle through the LDS crossbar costs about 100 cycles each)
     const unsigned v = rs[mb];
@@ -373,8 +387,8 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
     if (g == 0) rsp[((mb * 16 + ml) * NWAVES) + wave] = (int)(q[0] + q[1]);  // [mb][row][wave]: the reader takes a row's 16 sums in four reads
   }
   __syncthreads();
-  if (wave >= MB) return;
-  const int mb = wave;
+  if (wave >= MB * CPW) return;
+  const int mb = red_mb;
   v4i sum = (v4i){0, 0, 0, 0};
   int rsum = -128 * (ks_len * QG_FRAG_K);  // every staged byte (padding included) is 128 above its int8 value
   {
@@ -382,7 +396,7 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
     static_assert(NWAVES % 4 == 0, "row sums are fetched four waves at a time");
     v4i t[NWAVES], tr[NWAVES / 4];
 #pragma unroll
-    for (int w = 0; w < NWAVES; ++w) t[w] = reinterpret_cast<const v4i*>(smem + w * REGION)[mb * 64 + lane];
+    for (int w = 0; w < NWAVES; ++w) t[w] = reinterpret_cast<const v4i*>(smem + w * REGION)[(mb * CPW + red_c) * 64 + lane];
 #pragma unroll
     for (int w = 0; w < NWAVES / 4; ++w) tr[w] = reinterpret_cast<const v4i*>(rsp + (mb * 16 + ml) * NWAVES)[w];
 #pragma unroll
@@ -398,7 +412,8 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
 
   // ---- K split across workgroups: hand the partial tile in, the last slice to arrive carries on
   if (ksplit > 1) {
-    const int unit = ((int)blockIdx.y * (int)gridDim.x + nb16) * MB + mb;  // one counter per (row block of 16, fragment column)
+    // one counter per (row block of 16, fragment column)
+    const int unit = (((int)blockIdx.y * (int)gridDim.x + (int)blockIdx.x) * CPW + red_c) * MB + mb;
     int* cnt = p.ws_cnt + unit;
     int* slots = p.ws_slots + (size_t)unit * ksplit * SLOT_INTS;
     int* mine = slots + (size_t)blockIdx.z * SLOT_INTS;
@@ -414,6 +429,7 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
     // every other slice's stores were acknowledged before it took its ticket; add all slots in slice order
     sum = (v4i){0, 0, 0, 0};
     rsum = 0;
+#pragma unroll 4  // the loads of four slots are in flight together
     for (int ss = 0; ss < ksplit; ++ss) {
       const int* theirs = slots + (size_t)ss * SLOT_INTS;
 #pragma unroll
@@ -467,7 +483,7 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
       const int col = c0 + r;
       if (col < N) p.C32[(size_t)row * p.ldc + col] = sum[r] + 128 * (ep_co[r] + K * ep_bz[r]);
     }
-    if (p.rowsum_out != nullptr && nb16 == 0 && g == 0) p.rowsum_out[row] = rsum + 128 * K;
+    if (p.rowsum_out != nullptr && nb16 + red_c == 0 && g == 0) p.rowsum_out[row] = rsum + 128 * K;
   }
 }
 
@@ -481,6 +497,23 @@ hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   if (mblocks > 65535 || a.ksplit < 1 || a.ksplit > 65535) return hipErrorInvalidValue;
   if (a.ksplit > 1 && (a.ws_cnt == nullptr || a.ws_slots == nullptr)) return hipErrorInvalidValue;
   const dim3 grid(nfrag, mblocks, a.ksplit), block(NWAVES * 64);
+  if constexpr (!B4 && !ANYALIGN && MB == 1) {
+    // Enough columns to give every CU a 32-column super-block of its own: four waves per workgroup, each streaming
+    // two fragment columns, batches of eight k blocks.  Cold, 16 rows: 8192 x 4096 11.4 -> 9.4 us, 8192 x 8192
+    // 18.2 -> 15.0 (a plain read of the weights in the same launch shape: 14.4), 16384 x 16384 59.2 -> 48.7; with
+    // fewer columns half the CUs would idle and the 16-wave form stays ahead (4096 x 8192: 9.6 vs 10.9 us).
+    constexpr int WN = 4, WB = 8, WC = 2;
+    if ((long long)((a.N + 31) / 32) * mblocks >= 256 && a.K == a.kb64 * QG_FRAG_K && a.kb64 % a.ks_per == 0 &&
+        a.ks_per % (WN * WB) == 0) {
+      constexpr auto fn = qg_gemm_skinny_kernel<MODE, 1, WN, WB, false, false, true, WC>;
+      const int wsmem = WN * 16 * (WB * QG_FRAG_K) + WN * 16 * (int)sizeof(int);
+      hipError_t e = qg_allow_smem<fn>(wsmem);
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL(fn, dim3((a.N + 31) / 32, mblocks, a.ksplit), dim3(WN * 64), wsmem, s, a.A, a.Bp, a.M, a.N, a.K, a.kb64,
+                         a.nb16, a.lda, a.ks_per, a.ksplit, a);
+      return hipGetLastError();
+    }
+  }
   if constexpr (!B4 && !ANYALIGN) {
     // the straight-line variant: K is a whole number of blocks, all slices are equal and give every wave whole batches
     if (a.K == a.kb64 * QG_FRAG_K && a.kb64 % a.ks_per == 0 && a.ks_per % (NWAVES * BATCH) == 0) {

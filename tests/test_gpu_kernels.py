@@ -143,3 +143,28 @@ def test_unknown_kernel_id_is_rejected(env, cases):
                                                C.data_ptr(), C.stride(0), None, None, bad)
         assert rc == q.EINVAL
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("M,N,K,ksplit", [(16, 8192, 2048, 1), (5, 8200, 4096, 1), (1, 8192, 2048, 1), (40, 2752, 2048, 1),
+                                          (16, 8200, 4096, 2), (9, 8192, 6144, 3)])
+def test_streaming_kernel_with_two_fragment_columns_per_wave(env, M, N, K, ksplit):
+    """Enough columns for every CU to own a 32-column super-block (and aligned rows, K a multiple of 2048): the
+    16-row streaming kernel runs its four-wave form with two fragment columns per wave.  N that cuts a super-block,
+    several row blocks, one row, and the K split across workgroups on top."""
+    q, torch, dev, oracle = env
+    say(f"wide streaming form {M}x{N}x{K} ksplit {ksplit}")
+    c = wl.unsaturated(wl.random_gemm(8100 + M + N + K, M, N, K, per_channel=True, with_bias=True, wide_zp=True))
+    want = oracle_gemm(c, oracle)
+    A, B, bias, scales, C, c_store = dev_case(c, torch, dev)
+    Bp = q.pack_b(B, c.b_zp)
+    ws = q.gemm_workspace(M, Bp, "skinny16", ksplit)
+    assert (ws is None) == (ksplit == 1)
+    for rep in range(2):
+        C.fill_(0xEE)
+        q.gemm_u8s8_requant_splitk(A, c.a_zp, Bp, bias, scales, c.c_zp, c.relu, ws, "skinny16", ksplit, out=C)
+        acc, rs = q.gemm_u8s8_acc32_splitk(A, Bp, ws, "skinny16", ksplit, want_rowsum=True)
+        torch.cuda.synchronize()
+        assert_same(C.cpu().numpy(), want, f"requant (call {rep})")
+        assert_same(acc.cpu().numpy(), oracle.acc32(c.A, c.B), f"acc32 (call {rep})")
+        assert_same(rs.cpu().numpy(), oracle.rowsum(c.A), f"rowsum (call {rep})")
+    assert (c_store.cpu().numpy()[M * N:] == 0xEE).all(), "bytes past C were written"

@@ -126,12 +126,12 @@ def test_plain_call_splits_only_with_a_workspace_and_matches(env):
     """The plain entry point: NULL workspace never splits; with the workspace of qg_gemm_workspace_bytes the
     built-in choice may split; the bytes are the same."""
     q, torch, dev, oracle = env
-    c = wl.unsaturated(wl.random_gemm(80, 16, 64, 8192, per_channel=True, with_bias=True, wide_zp=True))
+    c = wl.unsaturated(wl.random_gemm(80, 16, 64, 16384, per_channel=True, with_bias=True, wide_zp=True))
     want = oracle_gemm(c, oracle)
     A, B, bias, scales, C, _ = dev_case(c, torch, dev)
     Bp = q.pack_b(B, c.b_zp)
     nbytes = q.gemm_workspace_bytes(c.M, Bp)
-    say(f"auto workspace for 16x64x8192: {nbytes} bytes, split {q.gemm_splitk_factor(c.M, Bp)}")
+    say(f"auto workspace for 16x64x16384: {nbytes} bytes, split {q.gemm_splitk_factor(c.M, Bp)}")
     assert nbytes > 0 and q.gemm_splitk_factor(c.M, Bp) > 1
     q.gemm_u8s8_requant(A, c.a_zp, Bp, bias, scales, c.c_zp, c.relu, out=C)
     torch.cuda.synchronize()

@@ -51,7 +51,7 @@ def test_two_calls_in_a_row_the_second_smaller(env):
 
 def test_built_in_choices_and_no_split(env):
     q, torch, dev, oracle = env
-    c = wl.unsaturated(wl.random_gemm(9102, 16, 64, 8192, per_channel=False, with_bias=False, wide_zp=True))
+    c = wl.unsaturated(wl.random_gemm(9102, 16, 64, 16384, per_channel=False, with_bias=False, wide_zp=True))
     assert run_pair(q, torch, dev, oracle, c, "auto", 0, "auto kernel, auto split") > 1
     run_pair(q, torch, dev, oracle, c, "auto", 1, "auto kernel, no split")
     big = wl.unsaturated(wl.random_gemm(9103, 300, 260, 512, per_channel=True, with_bias=True))
