@@ -314,11 +314,23 @@ int qg_gemm_u8s8_dequant_f32(const uint8_t* A_dev, int M, int lda, const qg_pack
 int qg_quantize_a_f32(const float* A_dev, int M, int K, int lda, float inv_scale, int a_zp,
                       uint8_t* Aq_dev, int ldq, void* stream);
 
-/* fp32 activations in, either output: qg_quantize_a_f32 into the workspace
- * followed by the GEMM on the quantized copy (two launches on `stream`);
- * p->a_zp is the zero point of the quantization and of Eq. (2).
- * workspace_dev: qg_gemm_f32_workspace_bytes(M, Bp) bytes, 16-byte aligned,
- * QG_EWORKSPACE if NULL.  The quantized copy stays in the workspace. */
+/* fp32 activations in, either output; p->a_zp is the zero point of the quantization
+ * and of Eq. (2).  Two forms, the same bytes either way:
+ *  - with a workspace (qg_gemm_f32_workspace_bytes(M, Bp) bytes, 16-byte
+ *    aligned): qg_quantize_a_f32 into the workspace, then the GEMM on the
+ *    quantized copy, two launches on `stream`.  The quantized copy stays in
+ *    the workspace.  This is the fast form on every shape measured: a tile of A
+ *    is staged once per tile column of C, so converting while staging repeats
+ *    the conversion for every column block.
+ *  - workspace_dev == NULL and a streaming kernel (kernel, or what QG_KERNEL_AUTO
+ *    resolves to, is QG_KERNEL_SKINNY*; dense descriptor): ONE launch, nothing
+ *    written but C.  The kernel quantizes the block of A it stages, with the
+ *    sequence of qg_quantize_a_f32, and takes row offsets from the staged block
+ *    in the same pass (Appendix B: row offsets computed while packing A).
+ *    A_dev 4-byte aligned; 16-byte aligned rows (A_dev % 16 == 0, lda % 4 == 0)
+ *    take the vector loads.  For callers that cannot provide a workspace; it
+ *    costs about 2 us more than the two launches at 16 x 4096 x 4096.
+ *    workspace_dev == NULL with a tiled kernel is QG_EWORKSPACE. */
 size_t qg_gemm_f32_workspace_bytes(int M, const qg_packed_b* Bp);
 int qg_gemm_f32s8_requant(const float* A_dev, int M, int lda, float a_inv_scale, const qg_packed_b* Bp,
                           const qg_requant_params* p, uint8_t* C_dev, int ldc, void* workspace_dev,

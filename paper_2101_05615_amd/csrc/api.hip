@@ -730,7 +730,7 @@ static int f32_ldq(const qg_packed_b* Bp) { return qg_round_up(Bp->K, 16); }
 
 size_t qg_gemm_f32_workspace_bytes(int M, const qg_packed_b* Bp) {
   if (!Bp || M <= 0 || Bp->kind != QG_KIND_GEMM) return 0;
-  return (size_t)M * (size_t)f32_ldq(Bp);
+  return (size_t)M * (size_t)f32_ldq(Bp);  // what a tiled kernel needs; a streaming kernel needs none
 }
 
 static int quantize_into_workspace(const float* A_dev, int M, int lda, float a_inv_scale, const qg_packed_b* Bp,
@@ -745,6 +745,30 @@ static int quantize_into_workspace(const float* A_dev, int M, int lda, float a_i
                            f32_ldq(Bp), stream);
 }
 
+// fp32 activations on a streaming kernel for a caller without a workspace: ONE launch -- the kernel quantizes the block it stages
+// (Appendix B: any packing routine for A; row offsets come from the staged block in the same pass).  Fills the
+// common fields of `a`; returns QG_OK with *fused = false when the kernel in use is a tiled one.
+static int f32_fused_common(const float* A_dev, int M, int lda, float a_inv_scale, int a_zp, const qg_packed_b* Bp,
+                            int kernel, const void* workspace_dev, qg_gemm_args* a, bool* fused) {
+  *fused = false;
+  // With a workspace at hand the separate quantization pass is the faster form even here (every 16-column
+  // workgroup of a streaming kernel would convert all of A again: 16 x 4096 x 4096 7.8 us fused, 5.8 us in two
+  // launches), so the one-launch form serves the caller that has none.
+  if (kernel > QG_KERNEL_SKINNY64 || Bp->split || workspace_dev != nullptr) return QG_OK;
+  if (!A_dev && M != 0) return QG_ENULL;
+  if (lda < Bp->K || a_zp < 0 || a_zp > 255 || !(a_inv_scale > 0.0f) || !isfinite(a_inv_scale)) return QG_EINVAL;
+  if (!aligned(A_dev, 4)) return QG_EALIGN;
+  int rc = gemm_common(reinterpret_cast<const uint8_t*>(A_dev), M, lda, Bp, a);
+  if (rc != QG_OK) return rc;
+  a->a_vec = aligned(A_dev, 16) && (lda % 4 == 0);  // rows of floats that 16-byte loads may take
+  a->q_inv = a_inv_scale;
+  a->q_lo = (float)(0 - a_zp);
+  a->q_hi = (float)(255 - a_zp);
+  a->q_zp = (float)a_zp;
+  *fused = true;
+  return QG_OK;
+}
+
 int qg_gemm_f32s8_requant(const float* A_dev, int M, int lda, float a_inv_scale, const qg_packed_b* Bp,
                           const qg_requant_params* p, uint8_t* C_dev, int ldc, void* workspace_dev,
                           void* stream, int kernel) {
@@ -756,6 +780,29 @@ int qg_gemm_f32s8_requant(const float* A_dev, int M, int lda, float a_inv_scale,
   if (M < 0 || ldc < Bp->N) return QG_EINVAL;
   rc = resolve_kernel(Bp, M, &kernel);
   if (rc != QG_OK) return rc;
+  {
+    qg_gemm_args a = {};
+    bool fused = false;
+    rc = f32_fused_common(A_dev, M, lda, a_inv_scale, p->a_zp, Bp, kernel, workspace_dev, &a, &fused);
+    if (rc != QG_OK) return rc;
+    if (fused) {
+      a.bias = p->bias;
+      a.scales = p->scales;
+      a.scale_stride = p->n_scales == 1 ? 0 : 1;
+      a.a_zp_m128 = p->a_zp - 128;
+      a.c_zp = p->c_zp;
+      const int lo = p->relu ? p->c_zp : 0;
+      a.clamp_lo = (float)(lo - p->c_zp);
+      a.clamp_hi = (float)(255 - p->c_zp);
+      a.C = C_dev;
+      a.ldc = ldc;
+      a.c_vec = aligned(C_dev, 4) && (ldc % 4 == 0);
+      a.c_wt = (long long)M * Bp->N <= (1 << 18);
+      if (M == 0) return QG_OK;
+      const hipError_t e = qg_launch_gemm_skinny_f32(a, QG_MODE_REQUANT, kernel, static_cast<hipStream_t>(stream));
+      return e == hipSuccess ? QG_OK : QG_ELAUNCH;
+    }
+  }
   rc = quantize_into_workspace(A_dev, M, lda, a_inv_scale, Bp, p->a_zp, workspace_dev, stream);
   if (rc != QG_OK || M == 0) return rc;
   return qg_gemm_u8s8_requant_kernel(static_cast<const uint8_t*>(workspace_dev), M, f32_ldq(Bp), Bp, p, C_dev, ldc,
@@ -773,6 +820,25 @@ int qg_gemm_f32s8_dequant_f32(const float* A_dev, int M, int lda, float a_inv_sc
   rc = resolve_kernel(Bp, M, &kernel);
   if (rc != QG_OK) return rc;
   if (!aligned(C_dev, 4)) return QG_EALIGN;
+  {
+    qg_gemm_args a = {};
+    bool fused = false;
+    rc = f32_fused_common(A_dev, M, lda, a_inv_scale, p->a_zp, Bp, kernel, workspace_dev, &a, &fused);
+    if (rc != QG_OK) return rc;
+    if (fused) {
+      a.bias = p->bias;
+      a.scales = p->scales;
+      a.scale_stride = p->n_scales == 1 ? 0 : 1;
+      a.a_zp_m128 = p->a_zp - 128;
+      a.relu_lo = p->relu ? 0.0f : -INFINITY;
+      a.Cf = C_dev;
+      a.ldc = ldc;
+      a.c_vec = aligned(C_dev, 16) && (ldc % 4 == 0);
+      if (M == 0) return QG_OK;
+      const hipError_t e = qg_launch_gemm_skinny_f32(a, QG_MODE_DEQUANT, kernel, static_cast<hipStream_t>(stream));
+      return e == hipSuccess ? QG_OK : QG_ELAUNCH;
+    }
+  }
   rc = quantize_into_workspace(A_dev, M, lda, a_inv_scale, Bp, p->a_zp, workspace_dev, stream);
   if (rc != QG_OK || M == 0) return rc;
   return qg_gemm_u8s8_dequant_f32(static_cast<const uint8_t*>(workspace_dev), M, f32_ldq(Bp), Bp, p, C_dev, ldc,

@@ -74,7 +74,11 @@ __device__ __forceinline__ void wait_vm() {
 // 32-column super-block: every activation fragment feeds two MFMAs, the workgroup stages half as many activation
 // bytes per weight byte, and few fat waves (16 weight loads in flight each) keep a large matrix streaming at the
 // rate of a plain read -- the shape for weights of tens of MiB, where the 16-wave form pays for its A traffic.
-template <int MODE, int MB, int NWAVES, int BATCH, bool B4, bool ANYALIGN, bool SIMPLE = false, int CPW = 1>
+// AF32: the activations are fp32 and are quantized to uint8 while they are staged (Appendix B: any packing routine for
+// A; Eq. (1) solved for the quantized value, the fixed sequence of the stand-alone quantization pass): the lanes load
+// 16 floats per 16-byte chunk of the staged block, convert and write the chunk to LDS, where row offsets and
+// fragments are taken from it as from any uint8 block.  A then points to floats and lda counts floats.
+template <int MODE, int MB, int NWAVES, int BATCH, bool B4, bool ANYALIGN, bool SIMPLE = false, int CPW = 1, bool AF32 = false>
 __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8_t* A, const int8_t* Bp, const int M, const int N, const int K, const int kb64,
                                                                    const int nb16_total, const int lda, const int ks_per, const int ksplit,
                                                                    const qg_gemm_args p) {
@@ -83,6 +87,7 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
   // wave instead of costing a cold trip to memory (measured: 0.4 us of a 5 us launch).
   static_assert(!SIMPLE || (!B4 && !ANYALIGN), "the straight-line variant takes dense 8-bit weights and aligned rows");
   static_assert(CPW == 1 || SIMPLE, "several fragment columns per wave: straight-line variant only");
+  static_assert(!AF32 || (!SIMPLE && !B4 && ANYALIGN), "fp32 activations: the lane-copied staging of the general variant");
   static_assert(MB * CPW <= NWAVES && CPW <= BATCH, "one wave per (row block, fragment column) runs the output pipeline");
   const bool a_vec = ANYALIGN || p.a_vec;  // whole 16-byte chunks may be moved as such
   using chunk_t = typename std::conditional<ANYALIGN, qg_v4i_unaligned, v4i>::type;
@@ -208,7 +213,7 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
     constexpr bool FIRST = decltype(first_tag)::value;
     // whole rows of BATCH k blocks are requested even when the slice ends earlier: the surplus lies inside the
     // row (it is the next wave's slice) and is simply not consumed
-    const bool staged = a_vec && (kb + BATCH) * QG_FRAG_K <= K;
+    const bool staged = !AF32 && a_vec && (kb + BATCH) * QG_FRAG_K <= K;
     unsigned char* region = smem + wave * REGION;
     // outlier split: this batch's entries are one run; the first 64 are requested one per lane right behind the
     // activations (always exactly one request, clamped into the buffer, so that the wait below can count it)
@@ -243,6 +248,57 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
       // any pointer, lda and K, partial batches: the lanes copy the block into the region themselves, 16-byte
       // chunk by chunk (bytes past K as 0x80, the int8 zero after the shift), in the same swizzled layout
       const int nchunk = min(BATCH, kb_end - kb) * 4;  // 16-byte chunks per row that this batch will consume
+      if constexpr (AF32) {
+        const float* Af = reinterpret_cast<const float*>(A);
+        constexpr int CH = ROWS * NCHUNK / 64;  // chunks per lane of a full batch
+        if (p.a_vec && nchunk == NCHUNK && (kb + BATCH) * QG_FRAG_K <= K) {
+          // whole batch inside K, rows of floats 16-byte aligned: two chunks' loads at a time (8 x 16 bytes per lane in
+          // flight; more would not fit the 128 registers of a 16-wave workgroup), then convert
+          constexpr int GRP = (CH >= 2 && MB == 1) ? 2 : 1;
+#pragma unroll 1
+          for (int t0 = 0; t0 < CH; t0 += GRP) {
+            float4 v[GRP][4];
+#pragma unroll
+            for (int t = 0; t < GRP; ++t) {
+              const int i = lane + 64 * (t0 + t), r = i / NCHUNK, lc = i % NCHUNK;
+              const float4* src = reinterpret_cast<const float4*>(Af + (size_t)min(m_base + r, M - 1) * lda + kb * QG_FRAG_K + (lc << 4));
+#pragma unroll
+              for (int e = 0; e < 4; ++e) v[t][e] = src[e];
+            }
+#pragma unroll
+            for (int t = 0; t < GRP; ++t) {
+              const int i = lane + 64 * (t0 + t), r = i / NCHUNK, lc = i % NCHUNK;
+              v4i w;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                unsigned d = qg_quantize_pack(v[t][e].x, p.q_inv, p.q_lo, p.q_hi, p.q_zp, 0, 0);
+                d = qg_quantize_pack(v[t][e].y, p.q_inv, p.q_lo, p.q_hi, p.q_zp, 1, d);
+                d = qg_quantize_pack(v[t][e].z, p.q_inv, p.q_lo, p.q_hi, p.q_zp, 2, d);
+                w[e] = (int)qg_quantize_pack(v[t][e].w, p.q_inv, p.q_lo, p.q_hi, p.q_zp, 3, d);
+              }
+              *reinterpret_cast<v4i*>(region + (r * NCHUNK + ((lc ^ r) & (NCHUNK - 1))) * 16) = w;
+            }
+          }
+        } else {
+          // any pointer, lda and K, partial batches: element by element, positions past K as 0x80
+#pragma unroll 1
+          for (int i = lane; i < ROWS * nchunk; i += 64) {
+            const int r = i / nchunk, lc = i % nchunk;
+            const int k0 = kb * QG_FRAG_K + (lc << 4);
+            const float* src = Af + (size_t)min(m_base + r, M - 1) * lda + k0;
+            v4i w;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              unsigned d = 0x80808080u;
+#pragma unroll
+              for (int b = 0; b < 4; ++b)
+                if (k0 + 4 * e + b < K) d = qg_quantize_pack(src[4 * e + b], p.q_inv, p.q_lo, p.q_hi, p.q_zp, b, d);
+              w[e] = (int)d;
+            }
+            *reinterpret_cast<v4i*>(region + (r * NCHUNK + ((lc ^ r) & (NCHUNK - 1))) * 16) = w;
+          }
+        }
+      } else
 #pragma unroll 1
       for (int i = lane; i < ROWS * nchunk; i += 64) {
         const int r = i / nchunk, lc = i % nchunk;     // row, logical chunk
@@ -531,6 +587,24 @@ hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// fp32 activations: the general variant with the converting staging (any alignment; a.a_vec says whether the rows of
+// floats are 16-byte aligned)
+template <int MODE, int MB, int NWAVES, int BATCH>
+hipError_t launch_af32(const qg_gemm_args& a, hipStream_t s) {
+  const int part = NWAVES * MB * 64 * (int)sizeof(v4i), stage = NWAVES * (MB * 16) * (BATCH * QG_FRAG_K);
+  const int smem = (stage > part ? stage : part) + NWAVES * MB * 16 * (int)sizeof(int);
+  const int nfrag = ((a.N + 31) / 32) * 2;
+  const int mblocks = (a.M + MB * 16 - 1) / (MB * 16);
+  if (mblocks > 65535 || a.ksplit < 1 || a.ksplit > 65535) return hipErrorInvalidValue;
+  if (a.ksplit > 1 && (a.ws_cnt == nullptr || a.ws_slots == nullptr)) return hipErrorInvalidValue;
+  constexpr auto fn = qg_gemm_skinny_kernel<MODE, MB, NWAVES, BATCH, false, true, false, 1, true>;
+  hipError_t e = qg_allow_smem<fn>(smem);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(fn, dim3(nfrag, mblocks, a.ksplit), dim3(NWAVES * 64), smem, s, a.A, a.Bp, a.M, a.N, a.K, a.kb64, a.nb16,
+                     a.lda, a.ks_per, a.ksplit, a);
+  return hipGetLastError();
+}
+
 // waves per workgroup and k blocks a wave requests at once, per row-block height
 template <int MODE, bool B4, bool ANYALIGN>
 hipError_t launch_mb(const qg_gemm_args& a, int kernel, hipStream_t s) {
@@ -550,6 +624,25 @@ hipError_t launch_mode(const qg_gemm_args& a, int mode, int kernel, hipStream_t 
 }
 
 }  // namespace
+
+// a.A points to fp32 activations (a.lda in floats, a.q_*: the quantization); mode: QG_MODE_REQUANT or QG_MODE_DEQUANT
+hipError_t qg_launch_gemm_skinny_f32(const qg_gemm_args& a, int mode, int kernel, hipStream_t s) {
+  if (a.sp_ptr != nullptr || mode == QG_MODE_ACC32) return hipErrorInvalidValue;
+  if (mode == QG_MODE_REQUANT) {
+    switch (kernel) {
+      case QG_KERNEL_SKINNY16: return launch_af32<QG_MODE_REQUANT, 1, 16, 4>(a, s);
+      case QG_KERNEL_SKINNY32: return launch_af32<QG_MODE_REQUANT, 2, 16, 4>(a, s);
+      case QG_KERNEL_SKINNY64: return launch_af32<QG_MODE_REQUANT, 4, 16, 2>(a, s);
+      default: return hipErrorInvalidValue;
+    }
+  }
+  switch (kernel) {
+    case QG_KERNEL_SKINNY16: return launch_af32<QG_MODE_DEQUANT, 1, 16, 4>(a, s);
+    case QG_KERNEL_SKINNY32: return launch_af32<QG_MODE_DEQUANT, 2, 16, 4>(a, s);
+    case QG_KERNEL_SKINNY64: return launch_af32<QG_MODE_DEQUANT, 4, 16, 2>(a, s);
+    default: return hipErrorInvalidValue;
+  }
+}
 
 hipError_t qg_launch_gemm_skinny(const qg_gemm_args& a, int mode, int kernel, hipStream_t s) {
   // a.sp_ptr != null: Bp holds the 4-bit part of an outlier-split matrix

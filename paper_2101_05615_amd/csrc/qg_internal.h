@@ -120,6 +120,7 @@ struct qg_gemm_args {
   // K split across workgroups (streaming kernels): the caller's workspace (tickets, partial tiles)
   int32_t* ws_cnt;       // one ticket counter per (row block of 16, fragment column); zero between calls
   int32_t* ws_slots;     // ksplit slots of 272 int32 per counter
+  float q_inv, q_lo, q_hi, q_zp;  // fp32 activations quantized while staged: 1/alpha_A, -theta_A, 255 - theta_A, theta_A
   const int32_t* sp_ptr;      // outlier split: per-bucket offsets, or null for a dense 8-bit B
   const int32_t* sp_entries;  // outlier split: entries
   int sp_total;               // outlier split: number of entries (the buffer holds at least one)
@@ -210,6 +211,16 @@ __device__ __forceinline__ unsigned qg_requant_pack0(int x, float sc, unsigned p
   const float p = f * sc;
   return __builtin_amdgcn_cvt_pk_u8_f32(p, pos, word);
 }
+// Quantization of one fp32 activation, Eq. (1) solved for the quantized value: ONE fp32 multiply, round to nearest
+// even, clamp in float to [-theta, 255 - theta], add theta; v_cvt_pk_u8_f32 converts the (exact, in-range) integer
+// and inserts it as byte `pos` of `word`.
+__device__ __forceinline__ unsigned qg_quantize_pack(float a, float inv, float lo, float hi, float zp_f, unsigned pos,
+                                                     unsigned word) {
+  const float pr = a * inv;
+  const float r = __builtin_rintf(pr);
+  const float c = __builtin_amdgcn_fmed3f(r, lo, hi) + zp_f;
+  return __builtin_amdgcn_cvt_pk_u8_f32(c, pos, word);
+}
 // fp32 output of one corrected accumulator: int32 -> fp32 (nearest even), ONE fp32 multiply, optional
 // max(., 0) (lo = 0 with ReLU, -inf without; a select, so no NaN-canonicalising extra instruction).
 __device__ __forceinline__ float qg_dequant_one(int x, float sc, float lo) {
@@ -255,6 +266,7 @@ hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, int kernel, hipS
 // kernel: QG_KERNEL_TILE64 / TILE64K4 / TILE64K1 / TILE128 / TILE128X256
 hipError_t qg_launch_conv_dense(const qg_gemm_args& a, int kernel, hipStream_t s);
 hipError_t qg_launch_gemm_skinny(const qg_gemm_args& a, int mode, int kernel, hipStream_t s);
+hipError_t qg_launch_gemm_skinny_f32(const qg_gemm_args& a, int mode, int kernel, hipStream_t s);
 hipError_t qg_launch_quantize_a(const float* A, int M, int K, int lda, float inv_scale, int a_zp, uint8_t* Aq,
                                 int ldq, hipStream_t s);
 hipError_t qg_launch_conv_group(const qg_conv_args& a, int RS, hipStream_t s);

@@ -11,16 +11,6 @@
 
 namespace {
 
-// One corrected value: ONE fp32 multiply, round to nearest even, clamp in float to [-theta, 255 - theta],
-// add theta; v_cvt_pk_u8_f32 converts the (exact, in-range) integer and inserts it as byte `pos`.
-__device__ __forceinline__ unsigned quantize_pack(float a, float inv, float lo, float hi, float zp_f, unsigned pos,
-                                                  unsigned word) {
-  const float pr = a * inv;
-  const float r = __builtin_rintf(pr);
-  const float c = __builtin_amdgcn_fmed3f(r, lo, hi) + zp_f;
-  return __builtin_amdgcn_cvt_pk_u8_f32(c, pos, word);
-}
-
 // One thread per 4 consecutive elements of a row (16 bytes in, 4 bytes out), grid-stride.
 __global__ __launch_bounds__(256) void qg_quantize_a_kernel(const float* __restrict__ A, int M, int K, int lda,
                                                             float inv, float lo, float hi, float zp_f,
@@ -35,13 +25,13 @@ __global__ __launch_bounds__(256) void qg_quantize_a_kernel(const float* __restr
     uint8_t* dst = Aq + (size_t)row * ldq + k;
     if (vec && k + 4 <= K) {
       const float4 v = *reinterpret_cast<const float4*>(src);
-      unsigned w = quantize_pack(v.x, inv, lo, hi, zp_f, 0, 0);
-      w = quantize_pack(v.y, inv, lo, hi, zp_f, 1, w);
-      w = quantize_pack(v.z, inv, lo, hi, zp_f, 2, w);
-      w = quantize_pack(v.w, inv, lo, hi, zp_f, 3, w);
+      unsigned w = qg_quantize_pack(v.x, inv, lo, hi, zp_f, 0, 0);
+      w = qg_quantize_pack(v.y, inv, lo, hi, zp_f, 1, w);
+      w = qg_quantize_pack(v.z, inv, lo, hi, zp_f, 2, w);
+      w = qg_quantize_pack(v.w, inv, lo, hi, zp_f, 3, w);
       *reinterpret_cast<unsigned*>(dst) = w;
     } else {
-      for (int i = 0; i < 4 && k + i < K; ++i) dst[i] = (uint8_t)quantize_pack(src[i], inv, lo, hi, zp_f, 0, 0);
+      for (int i = 0; i < 4 && k + i < K; ++i) dst[i] = (uint8_t)qg_quantize_pack(src[i], inv, lo, hi, zp_f, 0, 0);
     }
   }
 }

@@ -435,6 +435,17 @@ def gemm_f32_workspace_bytes(M, Bp):
     return lib.qg_gemm_f32_workspace_bytes(M, Bp.handle)
 
 
+class _NoWorkspace:
+    """Stands for a NULL workspace pointer (the one-launch form on a streaming kernel needs none)."""
+
+    @staticmethod
+    def data_ptr():
+        return None
+
+
+NO_WORKSPACE = _NoWorkspace()
+
+
 def _f32_ws(A, Bp, workspace):
     assert A.is_cuda and A.dtype == torch.float32 and A.dim() == 2 and A.stride(1) == 1 and A.shape[1] == Bp.K
     if workspace is None:

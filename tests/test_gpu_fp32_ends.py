@@ -115,6 +115,35 @@ def test_fp32_activations_both_outputs(env, M, N, K):
     assert np.mean((want_u8 > 0) & (want_u8 < 255)) > 0.3
 
 
+@pytest.mark.parametrize("kernel", ["skinny16", "skinny32", "skinny64"])
+@pytest.mark.parametrize("M,N,K,lda_pad", [(16, 256, 1024, 0), (48, 100, 300, 0), (7, 40, 4097, 3), (130, 72, 2048, 4),
+                                           (1, 520, 512, 0), (64, 64, 100, 1)])
+def test_fp32_activations_quantized_while_staged(env, kernel, M, N, K, lda_pad):
+    """A streaming kernel takes fp32 activations in ONE launch and without a workspace: it quantizes the block it
+    stages.  Bytes must be those of oracle.quantize_f32 followed by the oracle GEMM: aligned and unaligned rows of
+    floats, ragged K, ties, saturating and infinite activations, both outputs."""
+    q, torch, dev, oracle = env
+    say(f"fused fp32 staging {kernel} M={M} N={N} K={K} lda={K + lda_pad}")
+    alpha, zp = 0.02, 90
+    Af, inv = wl.random_fp32_activations(5 * M + K, M, K, alpha=alpha, zp=zp)
+    c = wl.unsaturated(wl.random_gemm(M * 3 + N + K, M, N, K, per_channel=True, with_bias=True, a_zp=zp, wide_zp=True))
+    B = torch.from_numpy(c.B).to(dev)
+    bias = torch.from_numpy(c.bias).to(dev)
+    scales = torch.from_numpy(c.scales).to(dev)
+    Bp = q.pack_b(B, c.b_zp)
+    store = torch.full((M, K + lda_pad), float("nan"), dtype=torch.float32, device=dev)
+    Ad = store[:, :K]
+    Ad.copy_(torch.from_numpy(Af).to(dev))
+    Aq = oracle.quantize_f32(Af, inv, zp)
+    want_u8 = oracle.gemm_u8s8_requant(Aq, zp, c.B, c.b_zp, c.bias, c.scales, c.c_zp, c.relu)
+    want_f32 = oracle.gemm_u8s8_dequant_f32(Aq, zp, c.B, c.b_zp, c.bias, c.scales, True)
+    got_u8 = q.gemm_f32s8_requant(Ad, inv, zp, Bp, bias, scales, c.c_zp, c.relu, workspace=q.NO_WORKSPACE, kernel=kernel)
+    got_f32 = q.gemm_f32s8_dequant_f32(Ad, inv, zp, Bp, bias, scales, True, workspace=q.NO_WORKSPACE, kernel=kernel)
+    torch.cuda.synchronize()
+    assert_same(got_u8.cpu().numpy(), want_u8, "fp32 in, uint8 out, one launch")
+    assert_same(bits(got_f32.cpu().numpy()), bits(want_f32), "fp32 in, fp32 out, one launch")
+
+
 def test_fp32_ends_argument_errors(env):
     import ctypes
     q, torch, dev, oracle = env
@@ -128,8 +157,8 @@ def test_fp32_ends_argument_errors(env):
     p = q.RequantParams(128, None, scales.data_ptr(), 1, 0, 0)
     d = q.DequantParams(128, None, scales.data_ptr(), 1, 0)
     L = q.lib
-    assert L.qg_gemm_f32s8_requant(Af.data_ptr(), 64, 128, 1.0, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None, 0) == q.EWORKSPACE
-    assert L.qg_gemm_f32s8_requant(Af.data_ptr(), 64, 128, 1.0, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, ws.data_ptr() + 1, None, 0) == q.EALIGN
+    assert L.qg_gemm_f32s8_requant(Af.data_ptr(), 64, 128, 1.0, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None, 4) == q.EWORKSPACE
+    assert L.qg_gemm_f32s8_requant(Af.data_ptr(), 64, 128, 1.0, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, ws.data_ptr() + 1, None, 4) == q.EALIGN
     assert L.qg_gemm_f32s8_requant(Af.data_ptr(), 64, 127, 1.0, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, ws.data_ptr(), None, 0) == q.EINVAL
     assert L.qg_gemm_f32s8_requant(Af.data_ptr(), 64, 128, 0.0, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, ws.data_ptr(), None, 0) == q.EINVAL
     assert L.qg_gemm_f32s8_requant(Af.data_ptr(), 64, 128, 1.0, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, ws.data_ptr(), None, q.KERNEL_LAST + 1) == q.EINVAL
@@ -141,4 +170,10 @@ def test_fp32_ends_argument_errors(env):
     assert L.qg_quantize_a_f32(Af.data_ptr(), 64, 128, 128, 1.0, 256, ws.data_ptr(), 128, None) == q.EINVAL
     assert L.qg_quantize_a_f32(Af.data_ptr(), 64, 128, 128, float("inf"), 0, ws.data_ptr(), 128, None) == q.EINVAL
     assert L.qg_quantize_a_f32(None, 64, 128, 128, 1.0, 0, ws.data_ptr(), 128, None) == q.ENULL
+    # a streaming kernel needs no workspace, and checks the quantization parameters itself
+    assert L.qg_gemm_f32s8_requant(Af.data_ptr(), 64, 128, 1.0, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None, 1) == q.OK
+    assert L.qg_gemm_f32s8_requant(Af.data_ptr(), 64, 128, 0.0, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None, 1) == q.EINVAL
+    assert L.qg_gemm_f32s8_requant(Af.data_ptr() + 2, 64, 128, 1.0, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None, 1) == q.EALIGN
+    assert L.qg_gemm_f32s8_requant(None, 64, 128, 1.0, Bp.handle, ctypes.byref(p), C.data_ptr(), 64, None, None, 1) == q.ENULL
+    torch.cuda.synchronize()
     torch.cuda.synchronize()
