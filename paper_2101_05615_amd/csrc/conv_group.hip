@@ -167,8 +167,11 @@ __device__ __forceinline__ void dma16(const void* gptr, unsigned char* lds_base)
 // latency per workgroup -- and every tap then comes from LDS.  Pixel p's 16-byte channel chunks are
 // stored swizzled so that the 32 consecutive pixels a half-wave reads hit different banks.
 template <int R, int S, int NCB, bool HAS_BZP>
-__global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel(const qg_conv_args p, int halo,
-                                                                                 int nchunks_pad) {
+__global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel(
+    const uint8_t* in, const int8_t* Wfrag, const int Nb, const int H, const int W, const int C, const int halo,
+    const int nchunks_pad, const qg_conv_args p) {
+  // the leading scalar arguments repeat the fields of p that the request burst needs: the file is compiled with
+  // kernel-argument preloading, so they arrive in scalar registers with the wave
   constexpr int RS = R * S;
   constexpr int NCH = NCB * 32;
   constexpr int CP = NCH / 16;       // 16-byte chunks per pixel
@@ -194,7 +197,7 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
   // overlap by the halo rows, also meet in one L2.
   int tile, slice;
   {
-    const int nslice = p.C / NCH, ntile = gridDim.x / nslice, id = blockIdx.x;
+    const int nslice = C / NCH, ntile = gridDim.x / nslice, id = blockIdx.x;
     if ((ntile & 7) == 0) {
       const int j = id >> 3;
       slice = j % nslice;
@@ -206,27 +209,27 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
   }
   const int ch0 = slice * NCH;
   const int q0 = tile * 128;  // first output pixel of the workgroup
-  const int npix = p.Nb * p.H * p.W;
+  const int npix = Nb * H * W;
   const int lin0 = q0 - halo;       // linear index of patch pixel 0 (may be negative; clamped per chunk)
 
   // ---- one burst of requests: weights, then the input patch
   {
-    const int8_t* wsrc = p.Wfrag + (size_t)slice * NCB * RS * QG_FRAG_BYTES + lane * 16;
+    const int8_t* wsrc = Wfrag + (size_t)slice * NCB * RS * QG_FRAG_BYTES + lane * 16;
     for (int f = wave; f < NCB * RS; f += 4) dma16(wsrc + (size_t)f * QG_FRAG_BYTES, w_s + f * QG_FRAG_BYTES);
     if (lin0 >= 0 && lin0 + nchunks_pad / CP <= npix) {
       // the whole patch lies inside the buffer: one address per lane, then 256 chunks = 256 / CP pixels further
       // per request (the swizzle has period 16 pixels or less, so it is the same for every request of a lane)
       const int c = wave * 64 + lane;
       const int pp = c / CP, phys = c % CP;
-      const uint8_t* src = p.in + (size_t)(lin0 + pp) * p.C + ch0 + ((phys ^ swz(pp)) << 4);
-      const int step = 256 / CP * p.C;
+      const uint8_t* src = in + (size_t)(lin0 + pp) * C + ch0 + ((phys ^ swz(pp)) << 4);
+      const int step = 256 / CP * C;
       for (int c0 = wave * 64; c0 < nchunks_pad; c0 += 256, src += step) dma16(src, patch + c0 * 16);
     } else {
       for (int c0 = wave * 64; c0 < nchunks_pad; c0 += 256) {
         const int c = c0 + lane;
         const int pp = c / CP, phys = c % CP;
         const int lin = min(max(lin0 + pp, 0), npix - 1);
-        dma16(p.in + (size_t)lin * p.C + ch0 + ((phys ^ swz(pp)) << 4), patch + c0 * 16);
+        dma16(in + (size_t)lin * C + ch0 + ((phys ^ swz(pp)) << 4), patch + c0 * 16);
       }
     }
     for (int c = tid; c < NCH; c += 256) {
@@ -244,19 +247,19 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
   // image position of this lane's pixel: the wave's first pixel is divided on the scalar unit, the lane walks
   // pl pixels on from there (a lane past the last pixel gets a position that is never used for a store)
   const int pw0 = q0 + wave * 32;
-  int wo = pw0 % p.W + pl;
-  int ho = (pw0 / p.W) % p.H;
-  for (int i = 31 / p.W + 1; i > 0; --i) {
-    const bool wrap = wo >= p.W;
-    wo -= wrap ? p.W : 0;
+  int wo = pw0 % W + pl;
+  int ho = (pw0 / W) % H;
+  for (int i = 31 / W + 1; i > 0; --i) {
+    const bool wrap = wo >= W;
+    wo -= wrap ? W : 0;
     ho += wrap ? 1 : 0;
-    ho = ho == p.H ? 0 : ho;
+    ho = ho == H ? 0 : ho;
   }
   bool row_ok[R], col_ok[S];
 #pragma unroll
-  for (int kh = 0; kh < R; ++kh) row_ok[kh] = (unsigned)(ho + kh - PAD_H) < (unsigned)p.H;
+  for (int kh = 0; kh < R; ++kh) row_ok[kh] = (unsigned)(ho + kh - PAD_H) < (unsigned)H;
 #pragma unroll
-  for (int kw = 0; kw < S; ++kw) col_ok[kw] = (unsigned)(wo + kw - PAD_W) < (unsigned)p.W;
+  for (int kw = 0; kw < S; ++kw) col_ok[kw] = (unsigned)(wo + kw - PAD_W) < (unsigned)W;
   const unsigned azp_word = (unsigned)p.a_zp * 0x01010101u;
   const float czp_f = (float)p.c_zp;
   const int pp_c = wave * 32 + pl + halo;  // patch index of this lane's centre pixel
@@ -282,7 +285,7 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
 #pragma unroll
     for (int kw = 0; kw < S; ++kw) {
       const bool ok = row_ok[kh] && col_ok[kw];
-      const int pp = pp_c + (kh - PAD_H) * p.W + (kw - PAD_W);
+      const int pp = pp_c + (kh - PAD_H) * W + (kw - PAD_W);
       const unsigned keep = ok ? 0xFFFFFFFFu : 0u;
       // in-image: x ^ 0x80 (uint8 -> int8); out of image: theta_A - 128 in every byte
       const unsigned flip = ok ? 0x80808080u : (azp_word ^ 0x80808080u);
@@ -425,10 +428,12 @@ hipError_t launch_same(const qg_conv_args& a, int smem, int halo, int nchunks_pa
   const dim3 grid((unsigned)(((npix + 127) / 128) * (a.C / (NCB * 32))));
   if (a.has_bzp) {
     if (hipError_t e = qg_allow_smem<qg_conv_same_mfma_kernel<R, S, NCB, true>>(smem); e != hipSuccess) return e;
-    hipLaunchKernelGGL((qg_conv_same_mfma_kernel<R, S, NCB, true>), grid, dim3(256), smem, s, a, halo, nchunks_pad);
+    hipLaunchKernelGGL((qg_conv_same_mfma_kernel<R, S, NCB, true>), grid, dim3(256), smem, s, a.in, a.Wfrag, a.Nb, a.H, a.W, a.C, halo,
+                       nchunks_pad, a);
   } else {
     if (hipError_t e = qg_allow_smem<qg_conv_same_mfma_kernel<R, S, NCB, false>>(smem); e != hipSuccess) return e;
-    hipLaunchKernelGGL((qg_conv_same_mfma_kernel<R, S, NCB, false>), grid, dim3(256), smem, s, a, halo, nchunks_pad);
+    hipLaunchKernelGGL((qg_conv_same_mfma_kernel<R, S, NCB, false>), grid, dim3(256), smem, s, a.in, a.Wfrag, a.Nb, a.H, a.W, a.C, halo,
+                       nchunks_pad, a);
   }
   return hipGetLastError();
 }
