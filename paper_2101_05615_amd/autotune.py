@@ -18,6 +18,10 @@ GRID_M = [65, 96, 128, 192, 256, 384, 512, 1024, 2048, 4096, 8192, 32768]
 GRID_N = [64, 256, 512, 1024, 2048, 4096, 8192]
 GRID_K = [256, 1024, 4096]
 MAX_OPS = 2.5e12  # skip grid points larger than the headline square
+# the small-batch shapes the paper stresses (Appendix C: M = 1 .. 64, N sometimes very small)
+SMALL_M = [1, 2, 4, 8, 16, 32, 64]
+SMALL_N = [4, 16, 64, 256, 1024, 4096]
+SMALL_K = [256, 1024, 4096]
 
 
 def time_shape(q, torch, M, N, K, kernels, min_ms=3.0, seed=0, spin_ms=15.0):
@@ -59,6 +63,45 @@ def time_shape(q, torch, M, N, K, kernels, min_ms=3.0, seed=0, spin_ms=15.0):
         out[name] = best * 1e3
     Bp.close()
     return out
+
+
+def time_cold(q, torch, M, N, K, kernel="auto", seed=0, reps=3):
+    """Microseconds per launch of one kernel with COLD weights: the launch rotates over enough packed copies of B
+    (more than 1 GB together, at most 256) that the 256 MB memory-side cache cannot hold them, recorded as one graph
+    and replayed (no host cost per launch).  -> (us, copies)"""
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(seed)
+    A = torch.randint(0, 256, (M, K), dtype=torch.uint8, device=dev, generator=g)
+    B = torch.randint(-128, 128, (K, N), dtype=torch.int8, device=dev, generator=g)
+    scales = torch.full((N,), 2.0 ** -12, dtype=torch.float32, device=dev)
+    b_zp = torch.randint(-8, 9, (N,), generator=torch.Generator().manual_seed(seed)).numpy()
+    ncopy = int(max(2, min(256, 1.2e9 // (K * N))))
+    calls = []
+    for _ in range(ncopy):
+        Bp = q.pack_b(B, b_zp)
+        calls.append(q.PreparedGemm(A.clone(), 128, Bp, None, scales, 0, True,
+                                    torch.empty((M, N), dtype=torch.uint8, device=dev), kernel=kernel))
+    for c in calls:
+        c.launch()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for c in calls:
+            c.rebind().launch()
+    for _ in range(3):
+        graph.replay()
+    torch.cuda.synchronize()
+    best = None
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        t = e0.elapsed_time(e1) * 1e3 / ncopy
+        best = t if best is None else min(best, t)
+    return best, ncopy
 
 
 def tune(q, torch, shapes, kernels=None, log=None):
@@ -110,6 +153,9 @@ def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
     ap.add_argument("--shapes", default="", help="comma-separated MxNxK")
     ap.add_argument("--grid", action="store_true", help="the built-in grid of inference-like shapes")
+    ap.add_argument("--small-grid", action="store_true",
+                    help="the small-batch grid (M 1..64 x N 4..4096 x K 256..4096); also times the automatic choice "
+                         "with cold weights and reports its fraction of the 8 TB/s HBM peak")
     ap.add_argument("--out", default="", help="write the dispatch table (JSON) here")
     ap.add_argument("--quiet", action="store_true", help="print only the summary")
     a = ap.parse_args(argv)
@@ -118,9 +164,16 @@ def main(argv=None):
     shapes = [tuple(int(v) for v in s.split("x")) for s in a.shapes.split(",") if s]
     if a.grid:
         shapes += [(M, N, K) for M in GRID_M for N in GRID_N for K in GRID_K if 2.0 * M * N * K <= MAX_OPS]
+    if a.small_grid:
+        shapes += [(M, N, K) for M in SMALL_M for N in SMALL_N for K in SMALL_K]
     if not shapes:
         ap.error("no shapes given")
     rows = tune(q, torch, shapes, log=None if a.quiet else (lambda s: print(s, flush=True)))
+    if a.small_grid:
+        for r in rows:
+            us, ncopy = time_cold(q, torch, r["M"], r["N"], r["K"])
+            nbytes = r["M"] * r["K"] + r["K"] * r["N"] + r["M"] * r["N"] + 4 * r["N"]
+            r["cold_us"], r["cold_copies"], r["cold_frac_hbm_peak"] = us, ncopy, nbytes / (us * 1e-6) / 8e12
     print(summary(rows), flush=True)
     if a.out:
         with open(a.out, "w") as f:

@@ -74,13 +74,13 @@ struct stream_cost {
   double fix, lat_k, wg, wg_k;
 };
 const tile_cost k_tile_cost[] = {
-    {QG_KERNEL_TILE64, 64, 64, 3.27, 0.141, 0.103, 0.64},
-    {QG_KERNEL_TILE128, 128, 128, 4.25, 0.226, 0.251, 1.38},
-    {QG_KERNEL_TILE128X256, 128, 256, 6.35, 0.344, 0.398, 2.85},
-    {QG_KERNEL_TILE256, 256, 256, 9.9, 0.632, 0.76, 8.21},
-    {QG_KERNEL_TILE64K4, 64, 64, 4.15, 0.089, 0.103, 2.1},
-    {QG_KERNEL_TILE64K1, 64, 64, 2.9, 0.239, 0.129, 0.222},
-    {QG_KERNEL_TILE64X32K8, 64, 32, 4.08, 0.0584, 0.0656, 2.57},
+    {QG_KERNEL_TILE64, 64, 64, 3.169, 0.1296, 0.1046, 0.6015},
+    {QG_KERNEL_TILE128, 128, 128, 3.401, 0.242, 0.2725, 1.102},
+    {QG_KERNEL_TILE128X256, 128, 256, 5.288, 0.3543, 0.4409, 2.253},
+    {QG_KERNEL_TILE256, 256, 256, 7.789, 0.6867, 0.8478, 6.549},
+    {QG_KERNEL_TILE64K4, 64, 64, 3.617, 0.1035, 0.1077, 2.38},
+    {QG_KERNEL_TILE64K1, 64, 64, 2.714, 0.2482, 0.1361, 0.1909},
+    {QG_KERNEL_TILE64X32K8, 64, 32, 3.817, 0.05427, 0.0602, 2.585},
 };
 // The dense convolution runs the compiler-scheduled tile loops with the im2col addressing folded in; the same
 // formula, constants fitted to 3 x 3 and 1 x 1 layers of 1 .. 32 images (graph-replay times).  The 64 x 64 tile
@@ -93,19 +93,27 @@ const tile_cost k_conv_cost[] = {
     {QG_KERNEL_TILE128X256, 128, 256, 6.84, 0.611, 0.551, 2.99},
 };
 const stream_cost k_stream_cost[] = {
-    {QG_KERNEL_SKINNY16, 16, 3.58, 7.3e-5, 7.55, 0.74e-3},
-    {QG_KERNEL_SKINNY32, 32, 4.13, 1.99e-4, 10.33, 1.28e-3},
-    {QG_KERNEL_SKINNY64, 64, 4.96, 3.88e-4, 14.26, 2.23e-3},
+    {QG_KERNEL_SKINNY16, 16, 3.826, 3.664e-06, 5.429, 0.002625},
+    {QG_KERNEL_SKINNY32, 32, 3.918, 2.404e-05, 8.639, 0.0005841},
+    {QG_KERNEL_SKINNY64, 64, 3.821, 0.0004905, 9.136, 0.002971},
 };
+// The 16-row kernel's four-wave form (more than 128 super-blocks of 16 rows x 32 columns, K a multiple of 2048,
+// dense weights): the same formula per super-block.
+const stream_cost k_stream_wide_cost = {QG_KERNEL_SKINNY16, 16, 3.191, 0.0002712, 4.302e-05, 0.001958};
 // A streaming workgroup re-reads its rows of A for every 16 columns; with few columns to share them that
 // traffic comes from far memory, row piece by row piece, at about this many bytes per microsecond.
 const double k_stream_a_rate = 2.0e6;
 const double k_stream_a_near = 1048576.0;     // bytes of A that the L2s keep
 const double k_stream_a_far_rate = 1.0e7;     // bytes per microsecond, all workgroups together
 
-double stream_estimate(const stream_cost& c, int M, int N, int K) {
-  const double wgs = (double)ceil_div(M, c.rows) * (double)(2 * ceil_div(N, 32));
+double stream_estimate(const stream_cost& c, int M, int N, int K, bool dense) {
   double a_bound = 2.5 + (double)M * (double)K / k_stream_a_rate;
+  const double blocks32 = (double)ceil_div(M, c.rows) * (double)ceil_div(N, 32);
+  if (dense && c.kernel == QG_KERNEL_SKINNY16 && blocks32 > 128.0 && K % 2048 == 0) {
+    const stream_cost& w = k_stream_wide_cost;
+    return fmax(fmax(w.fix + K * w.lat_k, a_bound), 2.5 + blocks32 * (w.wg + K * w.wg_k) * 1e-3);
+  }
+  const double wgs = 2.0 * blocks32;
   // an A too large to stay in the L2s is fetched from far memory once per 16 columns
   if ((double)M * (double)K > k_stream_a_near)
     a_bound = fmax(a_bound, 2.5 + (double)M * (double)K * (double)ceil_div(N, 16) / k_stream_a_far_rate);
@@ -128,7 +136,7 @@ int builtin_select(int M, int N, int K) {
   for (const stream_cost& c : k_stream_cost) {
     const long long blocks = ceil_div(M, c.rows);
     if (blocks > 65535) continue;
-    const double us = stream_estimate(c, M, N, K);
+    const double us = stream_estimate(c, M, N, K, true);
     if (us < best_us) best_us = us, best = c.kernel;
   }
   for (const tile_cost& c : k_tile_cost) {
@@ -145,7 +153,7 @@ int select_stream_kernel(int M, int N, int K) {
   for (const stream_cost& c : k_stream_cost) {
     const long long blocks = ceil_div(M, c.rows);
     if (blocks > 65535) continue;
-    const double us = stream_estimate(c, M, N, K);
+    const double us = stream_estimate(c, M, N, K, false);
     if (us < best_us) best_us = us, best = c.kernel;
   }
   return best;

@@ -554,12 +554,14 @@ hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   if (a.ksplit > 1 && (a.ws_cnt == nullptr || a.ws_slots == nullptr)) return hipErrorInvalidValue;
   const dim3 grid(nfrag, mblocks, a.ksplit), block(NWAVES * 64);
   if constexpr (!B4 && !ANYALIGN && MB == 1) {
-    // Enough columns to give every CU a 32-column super-block of its own: four waves per workgroup, each streaming
-    // two fragment columns, batches of eight k blocks.  Cold, 16 rows: 8192 x 4096 11.4 -> 9.4 us, 8192 x 8192
-    // 18.2 -> 15.0 (a plain read of the weights in the same launch shape: 14.4), 16384 x 16384 59.2 -> 48.7; with
-    // fewer columns half the CUs would idle and the 16-wave form stays ahead (4096 x 8192: 9.6 vs 10.9 us).
+    // More 32-column super-blocks than half the CUs: four waves per workgroup, each streaming two fragment columns,
+    // batches of eight k blocks.  The 16-wave form would put two or more workgroups on a CU there, and a second
+    // one costs about as much as the first (80 x 1536 x 2048: 6.7 -> 3.4 us cold, 640 x 128 x 2048: 6.7 -> 3.7,
+    // 80 x 1024 x 4096: 6.9 -> 5.7).  Cold, 16 rows: 8192 x 4096 11.4 -> 9.4 us, 8192 x 8192 18.2 -> 15.0 (a plain
+    // read of the weights in the same launch shape: 14.4), 16384 x 16384 59.2 -> 48.7.  With 128 super-blocks or
+    // fewer half the CUs would idle and the 16-wave form stays ahead (4096 x 8192: 9.6 vs 10.9 us).
     constexpr int WN = 4, WB = 8, WC = 2;
-    if ((long long)((a.N + 31) / 32) * mblocks >= 256 && a.K == a.kb64 * QG_FRAG_K && a.kb64 % a.ks_per == 0 &&
+    if ((long long)((a.N + 31) / 32) * mblocks > 128 && a.K == a.kb64 * QG_FRAG_K && a.kb64 % a.ks_per == 0 &&
         a.ks_per % (WN * WB) == 0) {
       constexpr auto fn = qg_gemm_skinny_kernel<MODE, 1, WN, WB, false, false, true, WC>;
       const int wsmem = WN * 16 * (WB * QG_FRAG_K) + WN * 16 * (int)sizeof(int);

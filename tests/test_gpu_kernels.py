@@ -146,11 +146,13 @@ def test_unknown_kernel_id_is_rejected(env, cases):
 
 
 @pytest.mark.parametrize("M,N,K,ksplit", [(16, 8192, 2048, 1), (5, 8200, 4096, 1), (1, 8192, 2048, 1), (40, 2752, 2048, 1),
-                                          (16, 8200, 4096, 2), (9, 8192, 6144, 3)])
+                                          (16, 8200, 4096, 2), (9, 8192, 6144, 3), (16, 4128, 2048, 1),
+                                          (70, 1000, 2048, 1), (640, 100, 4096, 2)])
 def test_streaming_kernel_with_two_fragment_columns_per_wave(env, M, N, K, ksplit):
-    """Enough columns for every CU to own a 32-column super-block (and aligned rows, K a multiple of 2048): the
-    16-row streaming kernel runs its four-wave form with two fragment columns per wave.  N that cuts a super-block,
-    several row blocks, one row, and the K split across workgroups on top."""
+    """More than 128 super-blocks of 16 rows x 32 columns (and aligned rows, K a multiple of 2048): the 16-row
+    streaming kernel runs its four-wave form with two fragment columns per wave.  N that cuts a super-block, several
+    row blocks, one row, the smallest count that takes this form (129), many row blocks of few columns, and the K
+    split across workgroups on top."""
     q, torch, dev, oracle = env
     say(f"wide streaming form {M}x{N}x{K} ksplit {ksplit}")
     c = wl.unsaturated(wl.random_gemm(8100 + M + N + K, M, N, K, per_channel=True, with_bias=True, wide_zp=True))
