@@ -45,12 +45,14 @@ def time_calls(torch, fn, steps, warmup, spin_ms=0.0):
     provide in a few dozen warm-up launches."""
     for _ in range(warmup):
         fn(0)
+    time_calls.settle_launches = 0
     if spin_ms > 0.0:
         t_end = time.perf_counter() + spin_ms * 1e-3
         while time.perf_counter() < t_end:
             for i in range(16):
                 fn(i)
             torch.cuda.synchronize()
+            time_calls.settle_launches += 16
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
@@ -140,6 +142,22 @@ def pmc_target(which, torch, q, wl, dev):
         torch.cuda.synchronize()
         print(json.dumps({"pmc_target": which, "workload": c.name, "launches": n}))
         return
+    if which in ("c2cold", "c2warm"):
+        # one temperature per run, so that a kernel trace of the run holds one row for it: cold rotates over 72
+        # packed copies of the weights (1.2 GB before any reuse), warm launches on one set of buffers
+        c = wl.config2_small_batch_fc()
+        A, B = torch.from_numpy(c.A).to(dev), torch.from_numpy(c.B).to(dev)
+        sc = torch.from_numpy(c.scales).to(dev)
+        ncopy = 72 if which == "c2cold" else 1
+        calls = [q.PreparedGemm(A.clone(), c.a_zp, q.pack_b(B, c.b_zp), None, sc, c.c_zp, c.relu,
+                                torch.empty((c.M, c.N), dtype=torch.uint8, device=dev)) for _ in range(ncopy)]
+        torch.cuda.synchronize()
+        n = 4 * 72
+        for i in range(n):
+            calls[i % ncopy].launch()
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_target": which, "workload": c.name, "launches": n, "weight_copies": ncopy}))
+        return
     c = {"c2": wl.config2_small_batch_fc, "c3": wl.config3_square, "c4": wl.config4_recsys_mlp}[which]()
     A, B = torch.from_numpy(c.A).to(dev), torch.from_numpy(c.B).to(dev)
     Bp = q.pack_b(B, c.b_zp)
@@ -161,9 +179,11 @@ def main():
                     help="untimed launches before the timed ones (the clocks settle after ~75 launches of the headline kernel)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", default="", help="comma list of c1..c5 and next to restrict the side sections")
-    ap.add_argument("--pmc-target", default="", choices=["", "c2", "c3", "c4", "c5", "copy"],
+    ap.add_argument("--pmc-target", default="", choices=["", "c2", "c3", "c4", "c5", "copy", "c2cold", "c2warm"],
                     help="run ONLY a few launches of one workload (or of a plain 256 MiB device copy, the "
-                         "calibration kernel for FETCH_SIZE / WRITE_SIZE) and exit: for rocprofv3 --pmc runs")
+                         "calibration kernel for FETCH_SIZE / WRITE_SIZE) and exit: for rocprofv3 --pmc runs; "
+                         "c2cold / c2warm: 288 launches of config 2 on rotating / on resident weights, for "
+                         "rocprofv3 --kernel-trace runs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path shards over M or N with no collective, "
@@ -225,12 +245,13 @@ def main():
     # The GPU reaches its settled clock only after some tens of milliseconds of load: whatever --warmup says, the
     # headline is timed after SETTLE_MS of untimed launches of the same call (like every side measurement).
     wall_ms, dev_ms = time_calls(torch, step3, args.steps, args.warmup, spin_ms=SETTLE_MS)
+    settle_launches = time_calls.settle_launches
     ops = 2.0 * c3.M * c3.N * c3.K
     tops = ops / (wall_ms * 1e-3) / 1e12
     kern_tops = ops / (dev_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "qg_gemm_tile_kernel", "achieved": round(kern_tops, 2),
                 "peak": PEAK_INT8_TOPS, "unit": "TOP/s", "frac": round(kern_tops / PEAK_INT8_TOPS, 4),
-                "avg_launch_ms": round(dev_ms, 5), "settle_ms": SETTLE_MS,
+                "avg_launch_ms": round(dev_ms, 5), "settle_ms": SETTLE_MS, "settle_launches": settle_launches,
                 "traffic": traffic_from_profiles("qg_gemm_tile_kernel_c3"),
                 "traffic_source": "profiles/hbm_traffic.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of the build named "
                                   "there; a recorded figure, not measured by this run"}
