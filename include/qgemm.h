@@ -405,11 +405,12 @@ int qg_conv_groupwise_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W,
  * pixels, K = R*S*Cin ordered (kh, kw, c_in), N = Cout; definition as for the
  * group-wise call (zero padding in the real domain).  The weights are packed
  * with qg_pack_b from the row-major (R*S*Cin) x Cout matrix W[kh][kw][ci][co];
- * the im2col matrix is never materialised: a 64-deep k tile is 64 channels of
- * one filter tap and is requested straight from the image.  A 1 x 1 filter with
+ * the im2col matrix is never materialised: a 64-deep k tile is requested
+ * straight from the image, as 64 channels of one filter tap when Cin % 64 == 0
+ * and as four 16-channel pieces that may belong to different taps otherwise.  A 1 x 1 filter with
  * stride 1 and no padding IS the GEMM over the pixel rows and runs as
  * qg_gemm_u8s8_requant_kernel(in, Nb*H*W, Cin, ...) with the same kernel id.
- *   in_nhwc  dev uint8 [Nb][H][W][Cin], 16-byte aligned;  Cin % 64 == 0
+ *   in_nhwc  dev uint8 [Nb][H][W][Cin], 16-byte aligned;  Cin % 16 == 0
  *   out_nhwc dev uint8 [Nb][Ho][Wo][Cout], Ho = (H + 2*pad - R)/stride + 1
  *   kernel   QG_KERNEL_AUTO (chosen from the extents by a cost model fitted to 3 x 3 and
  *            1 x 1 layers), or QG_KERNEL_TILE64 / TILE64K4 / TILE64K1 / TILE128 /

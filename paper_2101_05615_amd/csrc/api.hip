@@ -868,7 +868,7 @@ int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int
   if (rc != QG_OK) return rc;
   if (H + 2 * pad < R || W + 2 * pad < S) return QG_EINVAL;
   const int Ho = (H + 2 * pad - R) / stride + 1, Wo = (W + 2 * pad - S) / stride + 1;
-  if (Wp->split || Cin % 64 != 0 || !aligned(in_nhwc, 16)) return QG_EUNSUPPORTED;
+  if (Wp->split || Cin % 16 != 0 || !aligned(in_nhwc, 16)) return QG_EUNSUPPORTED;
   // 32-bit byte offsets into the image (tap offsets included) and 32-bit pixel counts
   if ((uint64_t)Nb * H * W * Cin >= (1ull << 30) || (uint64_t)Nb * Ho * Wo >= (1ull << 31) / 4) return QG_EUNSUPPORTED;
   // A 1 x 1 filter with unit stride and no padding is the plain GEMM over the pixel rows (lda = Cin): it takes
@@ -903,6 +903,7 @@ int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int
   a.cv_Cin = Cin;
   a.cv_Ho = Ho;
   a.cv_Wo = Wo;
+  a.cv_R = R;
   a.cv_S = S;
   a.cv_stride = stride;
   a.cv_pad = pad;

@@ -129,6 +129,10 @@ constexpr int min_wg_per_cu(int path, int blocks) {
 // (Cin % 64 == 0), so staging a tile is the same request as in the GEMM with the row base moved by the
 // tap's pixel offset.  A tap outside the image must read as theta_A (zero in the real domain): the request
 // address is clamped into the buffer and the fragment is replaced by theta_A bytes when it is fetched.
+// CONV == 2: any Cin % 16 == 0.  A 64-deep tile is then four 16-channel chunks that may belong to different
+// taps (and, in the last tile, lie past K = R*S*Cin), so the tap of a chunk is per-lane state: (channel chunk,
+// kw, kh) of the chunk a lane requests and of the two chunks it holds as MFMA operands, advanced by four
+// chunks per tile.  A chunk past K reads as the int8 zero (its weights are the zero padding of the pack).
 // KS (PATH_PIPE only): wave groups that split K inside the workgroup.  With KS = 2 the workgroup has two sets of
 // NWM x NWN waves; set g consumes the k tiles g, g + 2, ... from its own LDS stages (a lone workgroup's k
 // step is a barrier / LDS read / MFMA chain, so two chains side by side halve the time of a thin grid), and the
@@ -142,11 +146,12 @@ constexpr int min_wg_per_cu(int path, int blocks) {
 // compiled with kernel-argument preloading, so they arrive in scalar registers with the wave instead of costing a
 // cold trip to memory.
 constexpr int EPI_CLAMP = 0, EPI_SAT = 1, EPI_SAT0 = 2;
-template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, bool CONV = false, int KS = 1, int EPI = EPI_CLAMP>
+template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, int CONV = 0, int KS = 1, int EPI = EPI_CLAMP>
 __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) / KS) void qg_gemm_tile_kernel(
     const uint8_t* A, const int8_t* Bp, const int M, const int N, const int K, const int nb16_total, const int lda,
     const int tiles_m, const int tiles_n, const qg_gemm_args p) {
   static_assert(KS == 1 || ((KS == 2 || KS == 4 || KS == 8) && PATH == PATH_PIPE), "K split: wave sets on the pipelined path");
+  constexpr bool CVG = CONV == 2;  // per-chunk taps
   constexpr int NW = NWM * NWN, NT = NW * KS * 64;  // NW: waves of one set; NT: threads of the workgroup
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
   constexpr int A_STAGE = BM * BK, B_STAGE = BN * BK, STAGE = A_STAGE + B_STAGE;
@@ -198,8 +203,9 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
       const int wo = rg % p.cv_Wo, t = rg / p.cv_Wo;
       const int ho = t % p.cv_Ho, n = t / p.cv_Ho;
       // byte offset of this lane's chunk at tap (0, 0), channel slice 0; a tap adds a workgroup-uniform offset
-      a_pix[q] = ((n * p.cv_H + ho * p.cv_stride - p.cv_pad) * p.cv_W + wo * p.cv_stride - p.cv_pad) * p.cv_Cin + kc * 16;
-      a_voff[q] = kc * 16;
+      a_pix[q] = ((n * p.cv_H + ho * p.cv_stride - p.cv_pad) * p.cv_W + wo * p.cv_stride - p.cv_pad) * p.cv_Cin +
+                 (CVG ? 0 : kc * 16);
+      a_voff[q] = kc * 16;  // CVG: the chunk of the tile this lane requests
       continue;
     }
     // hand-scheduled loop: it uses instruction offset q*1024 (it moves the LDS slot AND the global address, so one
@@ -243,8 +249,9 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
   // dword in one plain VALU op; v_dot4 would contend with the MFMAs for the dot-product pipeline),
   // then uint8 -> int8 in place (xor 0x80 == minus 128).
   // CONV: position of tap (0, 0) of this lane's TM fragment rows, and the validity of the current tap
+  // (cv_ok[ks][mb]: of the chunk held for k-step ks; one tap per tile unless CVG, so both k-steps agree then)
   int cv_h[TM], cv_w[TM];
-  bool cv_ok[TM];
+  bool cv_ok[2][TM];
   if (CONV) {
 #pragma unroll
     for (int mb = 0; mb < TM; ++mb) {
@@ -252,22 +259,26 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
       const int wo = m % p.cv_Wo, ho = (m / p.cv_Wo) % p.cv_Ho;
       cv_h[mb] = ho * p.cv_stride - p.cv_pad;
       cv_w[mb] = wo * p.cv_stride - p.cv_pad;
-      cv_ok[mb] = true;
+      cv_ok[0][mb] = cv_ok[1][mb] = true;
     }
   }
   const unsigned azp_word = CONV ? (unsigned)p.cv_azp * 0x01010101u : 0u;
-  auto prep = [&](v4i (&af)[TM]) {
+  // what a chunk that is not read from the image stands for: theta_A bytes (a tap outside the image), or, CVG
+  // only, 0x80 bytes (past K: zero after the shift, and 128 per byte in the raw sums like all K padding)
+  unsigned cv_sub[2] = {azp_word, azp_word};
+  auto prep = [&](v4i (&af)[TM], int ks) {
 #pragma unroll
     for (int mb = 0; mb < TM; ++mb) {
       if (CONV) {
-        const unsigned keep = cv_ok[mb] ? 0xFFFFFFFFu : 0u;
-        const unsigned flip = cv_ok[mb] ? 0x80808080u : (azp_word ^ 0x80808080u);
-        if (ROWSUM) {  // the 16 bytes as staged, or 16 times theta_A for a tap outside the image
+        const bool ok = cv_ok[ks][mb];
+        const unsigned keep = ok ? 0xFFFFFFFFu : 0u;
+        const unsigned flip = ok ? 0x80808080u : (cv_sub[ks] ^ 0x80808080u);
+        if (ROWSUM) {  // the 16 bytes as staged, or 16 times the byte that stands in for them
           unsigned sum = __builtin_amdgcn_sad_u8(af[mb].x, 0u, 0u);
           sum = __builtin_amdgcn_sad_u8(af[mb].y, 0u, sum);
           sum = __builtin_amdgcn_sad_u8(af[mb].z, 0u, sum);
           sum = __builtin_amdgcn_sad_u8(af[mb].w, 0u, sum);
-          rs[mb] += cv_ok[mb] ? sum : 16u * (unsigned)p.cv_azp;
+          rs[mb] += ok ? sum : 16u * (cv_sub[ks] & 255u);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -293,7 +304,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
   const int KT = (K + BK - 1) / BK;  // tiles that hold real data
   // the pipelined loops run the KTF whole tiles; a ragged last tile (K % 64 bytes of A) is staged through
   // registers afterwards, once per workgroup
-  const int KTF = K / BK;
+  const int KTF = CVG ? KT : K / BK;  // (CVG: chunks past K are replaced like taps outside the image)
   v4i a0[TM], b0[TN], a1[TM], b1[TN];
   if constexpr (PATH == PATH_ASM) {
     // Tile kt lives in stage kt % 4.  In iteration kt: the first k-step runs while the fragments of
@@ -347,6 +358,31 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
     const int cv_nc = CONV ? p.cv_Cin / BK : 1;
     int rq_kh = 0, rq_kw = 0, rq_cc = 0;  // of the next tile to request
     int cs_kh = 0, cs_kw = 0, cs_cc = 0;  // of the tile being consumed
+    // CVG: the same per lane, in 16-channel chunks: [q] of the chunk requested by request q, [ks] of the operand
+    // chunk of k-step ks.  A step of n tiles is 4 n chunks; at most cv_wraps taps are crossed by it.
+    const int cv_nc16 = CVG ? p.cv_Cin / 16 : 1;
+    const int cv_wraps = CVG ? (4 * KS + cv_nc16 - 1) / cv_nc16 : 0;
+    int rqv_c[A_DMA], rqv_kw[A_DMA], rqv_kh[A_DMA], csv_c[2], csv_kw[2], csv_kh[2];
+    auto cvg_init = [&](int chunk, int& c, int& kw, int& kh) {  // chunk: index along K in units of 16
+      const int tap = chunk / cv_nc16;
+      c = chunk - tap * cv_nc16;
+      kh = tap / p.cv_S;
+      kw = tap - kh * p.cv_S;
+    };
+    auto cvg_advance = [&](int& c, int& kw, int& kh) {
+      c += 4 * KS;
+      for (int j = 0; j < cv_wraps; ++j)
+        if (c >= cv_nc16) {
+          c -= cv_nc16;
+          if (++kw == p.cv_S) kw = 0, ++kh;
+        }
+    };
+    if (CVG) {
+#pragma unroll
+      for (int q = 0; q < A_DMA; ++q) cvg_init(kg * 4 + (int)(a_voff[q] >> 4), rqv_c[q], rqv_kw[q], rqv_kh[q]);
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) cvg_init(kg * 4 + ks * 2 + lg, csv_c[ks], csv_kw[ks], csv_kh[ks]);
+    }
     // n tiles on (wave-uniform, scalar unit): a wave set starts at tile kg and takes every KS-th
     auto cv_advance = [&](int& kh, int& kw, int& cc, int n) {
       for (int j = 0; j < n; ++j)
@@ -355,7 +391,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
           if (++kw == p.cv_S) kw = 0, ++kh;
         }
     };
-    if (CONV && KS > 1) {
+    if (CONV == 1 && KS > 1) {
       cv_advance(rq_kh, rq_kw, rq_cc, kg);
       cv_advance(cs_kh, cs_kw, cs_cc, kg);
     }
@@ -363,7 +399,15 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
       const uint8_t* ab = A + (size_t)kt * BK;
       const int8_t* bb = b_tile0 + (size_t)kt * b_step;
       unsigned char* st = smem + (stage * KS + kg) * STAGE;
-      if (CONV) {
+      if (CVG) {
+#pragma unroll
+        for (int q = 0; q < A_DMA; ++q) {
+          int off = a_pix[q] + (rqv_kh[q] * p.cv_W + rqv_kw[q]) * p.cv_Cin + rqv_c[q] * 16;
+          off = min(max(off, 0), p.cv_in_bytes - 16);  // outside the image or past K: any valid address, replaced later
+          dma16(A + off, st + (wave * A_DMA + q) * 1024);
+          cvg_advance(rqv_c[q], rqv_kw[q], rqv_kh[q]);
+        }
+      } else if (CONV) {
         const int tap_off = (rq_kh * p.cv_W + rq_kw) * p.cv_Cin + rq_cc * BK;
 #pragma unroll
         for (int q = 0; q < A_DMA; ++q) {
@@ -392,18 +436,30 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
       if (i + NS - 1 < KTg) request((i + NS - 1) * KS + kg, stage == 0 ? NS - 1 : stage - 1);
-      if (CONV) {
+      if (CVG) {
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+          const bool in_k = csv_kh[ks] < p.cv_R;
+          cv_sub[ks] = in_k ? azp_word : 0x80808080u;
+#pragma unroll
+          for (int mb = 0; mb < TM; ++mb)
+            cv_ok[ks][mb] = in_k && (unsigned)(cv_h[mb] + csv_kh[ks]) < (unsigned)p.cv_H &&
+                            (unsigned)(cv_w[mb] + csv_kw[ks]) < (unsigned)p.cv_W;
+          cvg_advance(csv_c[ks], csv_kw[ks], csv_kh[ks]);
+        }
+      } else if (CONV) {
 #pragma unroll
         for (int mb = 0; mb < TM; ++mb)
-          cv_ok[mb] = (unsigned)(cv_h[mb] + cs_kh) < (unsigned)p.cv_H && (unsigned)(cv_w[mb] + cs_kw) < (unsigned)p.cv_W;
+          cv_ok[0][mb] = cv_ok[1][mb] =
+              (unsigned)(cv_h[mb] + cs_kh) < (unsigned)p.cv_H && (unsigned)(cv_w[mb] + cs_kw) < (unsigned)p.cv_W;
         cv_advance(cs_kh, cs_kw, cs_cc, KS);
       }
       if (consume) {
         fetch(stage, 0, a0, b0);
         fetch(stage, 1, a1, b1);
-        prep(a0);
+        prep(a0, 0);
         mma(a0, b0);
-        prep(a1);
+        prep(a1, 1);
         mma(a1, b1);
       }
       stage = stage == NS - 1 ? 0 : stage + 1;
@@ -437,14 +493,11 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
     }
     __syncthreads();
     if (kg == 0) {
-      if (CONV) {
-#pragma unroll
-        for (int mb = 0; mb < TM; ++mb) cv_ok[mb] = true;  // (a convolution has no ragged tile: Cin % 64 == 0)
-      }
+      // (a convolution has no ragged tile: Cin % 64 == 0, or its last tile went through the loop above)
       fetch(0, 0, a0, b0);
       fetch(0, 1, a1, b1);
-      prep(a0);
-      prep(a1);
+      prep(a0, 0);
+      prep(a1, 1);
       mma(a0, b0);
       mma(a1, b1);
     }
@@ -661,13 +714,13 @@ hipError_t launch_cfg(const qg_gemm_args& a, int mode, hipStream_t s) {
   return launch<QG_MODE_ACC32, PATH, true, NWM, NWN, TM, TN, KS>(a, s);
 }
 
-template <bool ROWSUM, int NWM, int NWN, int TM, int TN, int KS, int EPI>
+template <bool ROWSUM, int NWM, int NWN, int TM, int TN, int KS, int EPI, int CONV = 1>
 hipError_t launch_conv_epi(const qg_gemm_args& a, hipStream_t s) {
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
   constexpr int SMEM = pipe_stages(TM * TN) * KS * (BM + BN) * BK;
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
   const dim3 grid((unsigned)(tiles_m * tiles_n)), block(NWM * NWN * KS * 64);
-  constexpr auto fn = qg_gemm_tile_kernel<QG_MODE_REQUANT, PATH_PIPE, ROWSUM, NWM, NWN, TM, TN, true, KS, EPI>;
+  constexpr auto fn = qg_gemm_tile_kernel<QG_MODE_REQUANT, PATH_PIPE, ROWSUM, NWM, NWN, TM, TN, CONV, KS, EPI>;
   hipError_t e = qg_allow_smem<fn>(SMEM);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(fn, grid, block, SMEM, s, a.A, a.Bp, a.M, a.N, a.K, a.nb16, a.lda, tiles_m, tiles_n, a);
@@ -675,6 +728,8 @@ hipError_t launch_conv_epi(const qg_gemm_args& a, hipStream_t s) {
 }
 template <bool ROWSUM, int NWM, int NWN, int TM, int TN, int KS>
 hipError_t launch_conv_rs(const qg_gemm_args& a, hipStream_t s) {
+  // channel counts that are not a multiple of 64: the per-chunk variant, with the one always-correct output form
+  if (a.cv_Cin % BK != 0) return launch_conv_epi<ROWSUM, NWM, NWN, TM, TN, KS, EPI_CLAMP, 2>(a, s);
   if constexpr (TM * TN == 1) {
     return launch_conv_epi<ROWSUM, NWM, NWN, TM, TN, KS, EPI_CLAMP>(a, s);
   } else {
@@ -692,7 +747,7 @@ hipError_t launch_conv(const qg_gemm_args& a, hipStream_t s) {
 
 }  // namespace
 
-// Dense convolution: a.A is the NHWC image, a.M the number of output pixels, a.K = R*S*Cin with Cin % 64 == 0.
+// Dense convolution: a.A is the NHWC image, a.M the number of output pixels, a.K = R*S*Cin with Cin % 16 == 0.
 hipError_t qg_launch_conv_dense(const qg_gemm_args& a, int kernel, hipStream_t s) {
   switch (kernel) {
     case QG_KERNEL_TILE64K1: return launch_conv<2, 2, 1, 1>(a, s);

@@ -125,7 +125,7 @@ struct qg_gemm_args {
   const int32_t* sp_entries;  // outlier split: entries
   int sp_total;               // outlier split: number of entries (the buffer holds at least one)
   // dense convolution through the tiled kernel (A = NHWC image, rows = output pixels, K = (kh, kw, ci)):
-  int cv_H, cv_W, cv_Cin, cv_Ho, cv_Wo, cv_S, cv_stride, cv_pad;
+  int cv_H, cv_W, cv_Cin, cv_Ho, cv_Wo, cv_R, cv_S, cv_stride, cv_pad;
   int cv_azp;                 // theta_A: what a tap outside the image reads as
   int cv_in_bytes;            // size of the image buffer
 };

@@ -47,6 +47,14 @@ def want(c, oracle):
     dict(Nb=1, H=9, W=12, C=64, Cout=32, R=3, S=1, pad=1),        # non-square filter, padding wider than the filter needs
     dict(Nb=2, H=14, W=14, C=256, Cout=300, pad=0),               # no padding, several column tiles
     dict(Nb=1, H=6, W=6, C=64, Cout=64, pad=3),                   # padding beyond the filter's reach
+    # channel counts that are not a multiple of 64: a 64-deep k tile spans taps, the last one may end past K
+    dict(Nb=2, H=7, W=9, C=96, Cout=64),                          # K = 864: 13 whole tiles and a half one
+    dict(Nb=1, H=5, W=6, C=16, Cout=48),                          # four taps per tile, K = 144
+    dict(Nb=2, H=9, W=8, C=48, Cout=72, stride=2),                # K = 432, three chunks per tap
+    dict(Nb=1, H=8, W=8, C=80, Cout=64, R=5, S=5, pad=2),         # K = 2000
+    dict(Nb=2, H=6, W=7, C=32, Cout=40, R=1, S=1, pad=0, stride=2),  # 1 x 1 with a stride: not a plain GEMM
+    dict(Nb=1, H=6, W=6, C=160, Cout=64, pad=3),                  # padding beyond the filter's reach, K = 1440
+    dict(Nb=2, H=8, W=8, C=96, Cout=64, R=1, S=1, pad=0),         # 1 x 1: the plain GEMM with a ragged K
 ])
 @pytest.mark.parametrize("per_channel,with_bias,relu", [(True, True, False), (False, False, True)])
 def test_dense_conv_bit_exact(env, cfg, per_channel, with_bias, relu):
@@ -100,10 +108,29 @@ def test_dense_conv_errors(env):
     L = q.lib.qg_conv_dense_u8s8_requant
     assert L(inp.data_ptr(), 1, 5, 5, 64, 3, 3, 1, 1, Wp.handle, ctypes.byref(p), None, None, 0) == q.ENULL
     assert L(inp.data_ptr(), 1, 5, 5, 64, 1, 1, 0, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, 0) == q.EINVAL  # K mismatch
-    assert L(inp.data_ptr(), 1, 5, 5, 32, 3, 6, 1, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, 0) == q.EUNSUPPORTED  # Cin % 64
+    assert L(inp.data_ptr(), 1, 5, 5, 8, 9, 8, 4, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, 0) == q.EUNSUPPORTED  # Cin % 16
     assert L(inp.data_ptr() + 4, 1, 5, 5, 64, 3, 3, 1, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, 0) == q.EUNSUPPORTED
     assert L(inp.data_ptr(), 1, 1, 1, 64, 3, 3, 0, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, 0) == q.EINVAL  # filter larger than image
     ok = (inp.data_ptr(), 1, 5, 5, 64, 3, 3, 1, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None)
     assert L(*ok, q.KERNEL_LAST + 1) == q.EINVAL and L(*ok, -1) == q.EINVAL
     assert L(*ok, q.kernel_id("tile256")) == q.EUNSUPPORTED and L(*ok, q.kernel_id("skinny16")) == q.EUNSUPPORTED
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_dense_conv_random_extents_any_multiple_of_16_channels(env, seed):
+    """Random small layers: channel counts over the multiples of 16, filters 1..5 in each direction, padding 0..3,
+    stride 1..2, every kernel id."""
+    q, torch, dev, oracle = env
+    rng = np.random.default_rng(9000 + seed)
+    R, S = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+    pad, stride = int(rng.integers(0, 4)), int(rng.integers(1, 3))
+    H = int(rng.integers(max(1, R - 2 * pad), 13))
+    W = int(rng.integers(max(1, S - 2 * pad), 13))
+    cfg = dict(Nb=int(rng.integers(1, 4)), H=H, W=W, C=16 * int(rng.integers(1, 14)), Cout=int(rng.integers(4, 100)),
+               R=R, S=S, pad=pad, stride=stride)
+    say(f"dense conv, random extents {cfg}")
+    c = wl.random_conv(9100 + seed, G=1, per_channel=bool(seed & 1), with_bias=bool(seed & 2), relu=bool(seed & 4), **cfg)
+    ref = want(c, oracle)
+    for kernel in CONV_KERNELS:
+        assert_same(run(c, q, torch, dev, kernel), ref, f"dense conv {cfg}, kernel {kernel}")
