@@ -127,12 +127,13 @@ constexpr int min_wg_per_cu(int path, int blocks) {
 // CONV (PATH_PIPE only): dense convolution with the im2col folded into the addressing.  Row m of "A" is
 // output pixel m of the NHWC result; the 64-deep k tile kt is 64 input channels of ONE filter tap
 // (Cin % 64 == 0), so staging a tile is the same request as in the GEMM with the row base moved by the
-// tap's pixel offset.  A tap outside the image must read as theta_A (zero in the real domain): the request
-// address is clamped into the buffer and the fragment is replaced by theta_A bytes when it is fetched.
+// tap's pixel offset.  A tap outside the image must read as theta_A (zero in the real domain): a lane whose
+// chunk lies outside the image requests its 16 bytes from a constant row of theta_A bytes instead
+// (qg_byte_rows), so what lands in the stage is the im2col row itself and row sums, shift and MFMAs are the GEMM's.
 // CONV == 2: any Cin % 16 == 0.  A 64-deep tile is then four 16-channel chunks that may belong to different
-// taps (and, in the last tile, lie past K = R*S*Cin), so the tap of a chunk is per-lane state: (channel chunk,
-// kw, kh) of the chunk a lane requests and of the two chunks it holds as MFMA operands, advanced by four
-// chunks per tile.  A chunk past K reads as the int8 zero (its weights are the zero padding of the pack).
+// taps (and, in the last tile, lie past K = R*S*Cin), so the tap of the chunk a lane requests is per-lane state
+// (channel chunk, kw, kh), advanced by four chunks per tile.  A chunk past K is requested from the row of 0x80
+// bytes, the K padding of every A stage (zero after the shift).
 // KS (PATH_PIPE only): wave groups that split K inside the workgroup.  With KS = 2 the workgroup has two sets of
 // NWM x NWN waves; set g consumes the k tiles g, g + 2, ... from its own LDS stages (a lone workgroup's k
 // step is a barrier / LDS read / MFMA chain, so two chains side by side halve the time of a thin grid), and the
@@ -146,6 +147,18 @@ constexpr int min_wg_per_cu(int path, int blocks) {
 // compiled with kernel-argument preloading, so they arrive in scalar registers with the wave instead of costing a
 // cold trip to memory.
 constexpr int EPI_CLAMP = 0, EPI_SAT = 1, EPI_SAT0 = 2;
+
+// Row v holds 16 bytes of value v: where a convolution's requests go for chunks that are not in the image.
+struct qg_byte_rows_t {
+  uint8_t b[256][16];
+};
+constexpr qg_byte_rows_t qg_make_byte_rows() {
+  qg_byte_rows_t r{};
+  for (int v = 0; v < 256; ++v)
+    for (int i = 0; i < 16; ++i) r.b[v][i] = (uint8_t)v;
+  return r;
+}
+__device__ const qg_byte_rows_t qg_byte_rows = qg_make_byte_rows();
 template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, int CONV = 0, int KS = 1, int EPI = EPI_CLAMP>
 __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) / KS) void qg_gemm_tile_kernel(
     const uint8_t* A, const int8_t* Bp, const int M, const int N, const int K, const int nb16_total, const int lda,
@@ -194,6 +207,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
   // base (advanced per tile on the scalar unit) plus a fixed 32-bit per-lane offset.
   unsigned a_voff[A_DMA], b_voff[B_DMA];
   int a_pix[A_DMA];  // CONV: byte offset of the chunk this lane requests, at tap (0, 0) (may be negative)
+  int a_h[A_DMA], a_w[A_DMA];  // CONV: image row and column of that tap
 #pragma unroll
   for (int q = 0; q < A_DMA; ++q) {
     const int r = (wave * A_DMA + q) * 16 + (lane >> 2);
@@ -206,6 +220,8 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
       a_pix[q] = ((n * p.cv_H + ho * p.cv_stride - p.cv_pad) * p.cv_W + wo * p.cv_stride - p.cv_pad) * p.cv_Cin +
                  (CVG ? 0 : kc * 16);
       a_voff[q] = kc * 16;  // CVG: the chunk of the tile this lane requests
+      a_h[q] = ho * p.cv_stride - p.cv_pad;
+      a_w[q] = wo * p.cv_stride - p.cv_pad;
       continue;
     }
     // hand-scheduled loop: it uses instruction offset q*1024 (it moves the LDS slot AND the global address, so one
@@ -248,43 +264,9 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
   // Row-offset partial sums on the raw uint8 bytes (v_sad_u8 against 0 adds the four bytes of a
   // dword in one plain VALU op; v_dot4 would contend with the MFMAs for the dot-product pipeline),
   // then uint8 -> int8 in place (xor 0x80 == minus 128).
-  // CONV: position of tap (0, 0) of this lane's TM fragment rows, and the validity of the current tap
-  // (cv_ok[ks][mb]: of the chunk held for k-step ks; one tap per tile unless CVG, so both k-steps agree then)
-  int cv_h[TM], cv_w[TM];
-  bool cv_ok[2][TM];
-  if (CONV) {
+  auto prep = [&](v4i (&af)[TM]) {
 #pragma unroll
     for (int mb = 0; mb < TM; ++mb) {
-      const int m = min(m0 + (wave_m * TM + mb) * 32 + l32, M - 1);
-      const int wo = m % p.cv_Wo, ho = (m / p.cv_Wo) % p.cv_Ho;
-      cv_h[mb] = ho * p.cv_stride - p.cv_pad;
-      cv_w[mb] = wo * p.cv_stride - p.cv_pad;
-      cv_ok[0][mb] = cv_ok[1][mb] = true;
-    }
-  }
-  const unsigned azp_word = CONV ? (unsigned)p.cv_azp * 0x01010101u : 0u;
-  // what a chunk that is not read from the image stands for: theta_A bytes (a tap outside the image), or, CVG
-  // only, 0x80 bytes (past K: zero after the shift, and 128 per byte in the raw sums like all K padding)
-  unsigned cv_sub[2] = {azp_word, azp_word};
-  auto prep = [&](v4i (&af)[TM], int ks) {
-#pragma unroll
-    for (int mb = 0; mb < TM; ++mb) {
-      if (CONV) {
-        const bool ok = cv_ok[ks][mb];
-        const unsigned keep = ok ? 0xFFFFFFFFu : 0u;
-        const unsigned flip = ok ? 0x80808080u : (cv_sub[ks] ^ 0x80808080u);
-        if (ROWSUM) {  // the 16 bytes as staged, or 16 times the byte that stands in for them
-          unsigned sum = __builtin_amdgcn_sad_u8(af[mb].x, 0u, 0u);
-          sum = __builtin_amdgcn_sad_u8(af[mb].y, 0u, sum);
-          sum = __builtin_amdgcn_sad_u8(af[mb].z, 0u, sum);
-          sum = __builtin_amdgcn_sad_u8(af[mb].w, 0u, sum);
-          rs[mb] += ok ? sum : 16u * (cv_sub[ks] & 255u);
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          af[mb][j] = (int)__builtin_amdgcn_bitop3_b32((unsigned)af[mb][j], keep, flip, 0x6a);  // (x & keep) ^ flip
-        continue;
-      }
       if (ROWSUM) {
         rs[mb] = __builtin_amdgcn_sad_u8(af[mb].x, 0u, rs[mb]);
         rs[mb] = __builtin_amdgcn_sad_u8(af[mb].y, 0u, rs[mb]);
@@ -357,12 +339,12 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
     // CONV: filter tap (kh, kw) and 64-channel slice cc of a k tile, advanced incrementally
     const int cv_nc = CONV ? p.cv_Cin / BK : 1;
     int rq_kh = 0, rq_kw = 0, rq_cc = 0;  // of the next tile to request
-    int cs_kh = 0, cs_kw = 0, cs_cc = 0;  // of the tile being consumed
-    // CVG: the same per lane, in 16-channel chunks: [q] of the chunk requested by request q, [ks] of the operand
-    // chunk of k-step ks.  A step of n tiles is 4 n chunks; at most cv_wraps taps are crossed by it.
+    // CVG: the same per lane, in 16-channel chunks, for the chunk of request q.  A step of n tiles is 4 n chunks;
+    // at most cv_wraps taps are crossed by it.
     const int cv_nc16 = CVG ? p.cv_Cin / 16 : 1;
     const int cv_wraps = CVG ? (4 * KS + cv_nc16 - 1) / cv_nc16 : 0;
-    int rqv_c[A_DMA], rqv_kw[A_DMA], rqv_kh[A_DMA], csv_c[2], csv_kw[2], csv_kh[2];
+    int rqv_c[A_DMA], rqv_kw[A_DMA], rqv_kh[A_DMA];
+    const uint8_t* const azp_row = qg_byte_rows.b[CONV ? p.cv_azp : 0];
     auto cvg_init = [&](int chunk, int& c, int& kw, int& kh) {  // chunk: index along K in units of 16
       const int tap = chunk / cv_nc16;
       c = chunk - tap * cv_nc16;
@@ -380,8 +362,6 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
     if (CVG) {
 #pragma unroll
       for (int q = 0; q < A_DMA; ++q) cvg_init(kg * 4 + (int)(a_voff[q] >> 4), rqv_c[q], rqv_kw[q], rqv_kh[q]);
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) cvg_init(kg * 4 + ks * 2 + lg, csv_c[ks], csv_kw[ks], csv_kh[ks]);
     }
     // n tiles on (wave-uniform, scalar unit): a wave set starts at tile kg and takes every KS-th
     auto cv_advance = [&](int& kh, int& kw, int& cc, int n) {
@@ -391,10 +371,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
           if (++kw == p.cv_S) kw = 0, ++kh;
         }
     };
-    if (CONV == 1 && KS > 1) {
-      cv_advance(rq_kh, rq_kw, rq_cc, kg);
-      cv_advance(cs_kh, cs_kw, cs_cc, kg);
-    }
+    if (CONV == 1 && KS > 1) cv_advance(rq_kh, rq_kw, rq_cc, kg);
     auto request = [&](int kt, int stage) {
       const uint8_t* ab = A + (size_t)kt * BK;
       const int8_t* bb = b_tile0 + (size_t)kt * b_step;
@@ -402,18 +379,19 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
       if (CVG) {
 #pragma unroll
         for (int q = 0; q < A_DMA; ++q) {
-          int off = a_pix[q] + (rqv_kh[q] * p.cv_W + rqv_kw[q]) * p.cv_Cin + rqv_c[q] * 16;
-          off = min(max(off, 0), p.cv_in_bytes - 16);  // outside the image or past K: any valid address, replaced later
-          dma16(A + off, st + (wave * A_DMA + q) * 1024);
+          const int off = a_pix[q] + (rqv_kh[q] * p.cv_W + rqv_kw[q]) * p.cv_Cin + rqv_c[q] * 16;
+          const bool in_k = rqv_kh[q] < p.cv_R;
+          const bool in_image = (unsigned)(a_h[q] + rqv_kh[q]) < (unsigned)p.cv_H && (unsigned)(a_w[q] + rqv_kw[q]) < (unsigned)p.cv_W;
+          const uint8_t* src = !in_k ? qg_byte_rows.b[128] : (in_image ? A + off : azp_row);
+          dma16(src, st + (wave * A_DMA + q) * 1024);
           cvg_advance(rqv_c[q], rqv_kw[q], rqv_kh[q]);
         }
       } else if (CONV) {
         const int tap_off = (rq_kh * p.cv_W + rq_kw) * p.cv_Cin + rq_cc * BK;
 #pragma unroll
         for (int q = 0; q < A_DMA; ++q) {
-          int off = a_pix[q] + tap_off;
-          off = min(max(off, 0), p.cv_in_bytes - 16);  // taps outside the image: any valid address, masked later
-          dma16(A + off, st + (wave * A_DMA + q) * 1024);
+          const bool in_image = (unsigned)(a_h[q] + rq_kh) < (unsigned)p.cv_H && (unsigned)(a_w[q] + rq_kw) < (unsigned)p.cv_W;
+          dma16(in_image ? A + (a_pix[q] + tap_off) : azp_row, st + (wave * A_DMA + q) * 1024);
         }
         cv_advance(rq_kh, rq_kw, rq_cc, KS);
       } else
@@ -436,30 +414,12 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
       if (i + NS - 1 < KTg) request((i + NS - 1) * KS + kg, stage == 0 ? NS - 1 : stage - 1);
-      if (CVG) {
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-          const bool in_k = csv_kh[ks] < p.cv_R;
-          cv_sub[ks] = in_k ? azp_word : 0x80808080u;
-#pragma unroll
-          for (int mb = 0; mb < TM; ++mb)
-            cv_ok[ks][mb] = in_k && (unsigned)(cv_h[mb] + csv_kh[ks]) < (unsigned)p.cv_H &&
-                            (unsigned)(cv_w[mb] + csv_kw[ks]) < (unsigned)p.cv_W;
-          cvg_advance(csv_c[ks], csv_kw[ks], csv_kh[ks]);
-        }
-      } else if (CONV) {
-#pragma unroll
-        for (int mb = 0; mb < TM; ++mb)
-          cv_ok[0][mb] = cv_ok[1][mb] =
-              (unsigned)(cv_h[mb] + cs_kh) < (unsigned)p.cv_H && (unsigned)(cv_w[mb] + cs_kw) < (unsigned)p.cv_W;
-        cv_advance(cs_kh, cs_kw, cs_cc, KS);
-      }
       if (consume) {
         fetch(stage, 0, a0, b0);
         fetch(stage, 1, a1, b1);
-        prep(a0, 0);
+        prep(a0);
         mma(a0, b0);
-        prep(a1, 1);
+        prep(a1);
         mma(a1, b1);
       }
       stage = stage == NS - 1 ? 0 : stage + 1;
@@ -496,8 +456,8 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
       // (a convolution has no ragged tile: Cin % 64 == 0, or its last tile went through the loop above)
       fetch(0, 0, a0, b0);
       fetch(0, 1, a1, b1);
-      prep(a0, 0);
-      prep(a1, 1);
+      prep(a0);
+      prep(a1);
       mma(a0, b0);
       mma(a1, b1);
     }
