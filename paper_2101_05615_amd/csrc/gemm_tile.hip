@@ -109,6 +109,25 @@ __device__ __forceinline__ int a_lds_off(int r, int kc) { return r * BK + ((kc ^
                    [lds] "s"(lds_base), [bstep] "s"(b_step), [bofs] "s"(A_STAGE + wave * ((B_DMA - A_DMA) * 1024)) \
                  : QG_TILE_LOOP_CLOBBERS_2X4
 
+// the convolution variants: image base, per-lane pixel offsets and tap-validity bits, the row of theta_A bytes
+#define QG_TILE_LOOP_OPERANDS_CONV_2X2 \
+                 : [c0] "+a"(acc[0][0]), [c1] "+a"(acc[0][1]), [c2] "+a"(acc[1][0]), [c3] "+a"(acc[1][1]), \
+                   [rs01] "=v"(rs01) \
+                 : [apix01] "v"(apix01), [amask01] "v"(amask01), [bv01] "v"(bv01), [ard] "v"(ard), [brd] "v"(brd), \
+                   [aptr] "s"(A), [tab] "s"(azp_row), [nc] "s"(cv_nc), [fs] "s"(cv_fs), [rowjump] "s"(cv_rowjump), \
+                   [bptr] "s"(b_tile0), [kt] "s"(KTF), [ldsdma] "s"(lds_dma), [lds] "s"(lds_base), [bstep] "s"(b_step) \
+                 : QG_TILE_LOOP_CLOBBERS_CONV_2X2
+
+#define QG_TILE_LOOP_OPERANDS_CONV_2X4 \
+                 : [c0] "+a"(acc[0][0]), [c1] "+a"(acc[0][1]), [c2] "+a"(acc[0][2]), [c3] "+a"(acc[0][3]), \
+                   [c4] "+a"(acc[1][0]), [c5] "+a"(acc[1][1]), [c6] "+a"(acc[1][2]), [c7] "+a"(acc[1][3]), \
+                   [rs01] "=v"(rs01) \
+                 : [apix01] "v"(apix01), [amask01] "v"(amask01), [bv01] "v"(bv01), [ard] "v"(ard), [brd] "v"(brd), \
+                   [aptr] "s"(A), [tab] "s"(azp_row), [nc] "s"(cv_nc), [fs] "s"(cv_fs), [rowjump] "s"(cv_rowjump), \
+                   [bptr] "s"(b_tile0), [kt] "s"(KTF), [ldsdma] "s"(lds_dma), [lds] "s"(lds_base), [bstep] "s"(b_step), \
+                   [bofs] "s"(A_STAGE + wave * ((B_DMA - A_DMA) * 1024)) \
+                 : QG_TILE_LOOP_CLOBBERS_CONV_2X4
+
 // NWM x NWN waves, each TM x TN blocks of 32 x 32.
 // Both loops take any pointer, lda and K (PATH_ASM: K >= 256): every whole 64-deep tile is requested with
 // global_load_lds -- the requests are 16 bytes per lane from any address -- and the loop is software-pipelined; a
@@ -124,7 +143,7 @@ constexpr int min_wg_per_cu(int path, int blocks) {
   return blocks >= 8 ? 2 : (blocks >= 4 ? 3 : 4);
 }
 
-// CONV (PATH_PIPE only): dense convolution with the im2col folded into the addressing.  Row m of "A" is
+// CONV: dense convolution with the im2col folded into the addressing.  Row m of "A" is
 // output pixel m of the NHWC result; the 64-deep k tile kt is 64 input channels of ONE filter tap
 // (Cin % 64 == 0), so staging a tile is the same request as in the GEMM with the row base moved by the
 // tap's pixel offset.  A tap outside the image must read as theta_A (zero in the real domain): a lane whose
@@ -148,8 +167,11 @@ constexpr int min_wg_per_cu(int path, int blocks) {
 // cold trip to memory.
 constexpr int EPI_CLAMP = 0, EPI_SAT = 1, EPI_SAT0 = 2;
 
-// Row v holds 16 bytes of value v: where a convolution's requests go for chunks that are not in the image.
-struct qg_byte_rows_t {
+// Row v holds 16 bytes of value v: where a convolution's requests go for chunks that are not in the image.  The
+// hand-scheduled loop addresses a row minus 1 KiB with a 32-bit subtraction (its second request carries an
+// instruction offset of 1 KiB): the rows sit 4 KiB into an 8 KiB-aligned object, so that cannot borrow.
+struct alignas(8192) qg_byte_rows_t {
+  uint8_t lead[4096];
   uint8_t b[256][16];
 };
 constexpr qg_byte_rows_t qg_make_byte_rows() {
@@ -316,6 +338,32 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
         asm volatile(QG_TILE_LOOP_ASM_NOROWSUM QG_TILE_LOOP_OPERANDS);
       rs[2] = (unsigned)rs23;
       rs[3] = (unsigned)(rs23 >> 32);
+    } else if constexpr (CONV != 0) {
+      // the convolution's requests: pixel offsets pre-biased like the table rows, one validity bit per filter tap
+      static_assert(CONV == 1 && TM == 2 && A_DMA == 2, "generated for 64 channels per tile and two requests per wave");
+      unsigned amask[A_DMA];
+#pragma unroll
+      for (int q = 0; q < A_DMA; ++q) {
+        amask[q] = 0;
+        for (int kh = 0, tap = 0; kh < p.cv_R; ++kh)
+          for (int kw = 0; kw < p.cv_S; ++kw, ++tap)
+            if ((unsigned)(a_h[q] + kh) < (unsigned)p.cv_H && (unsigned)(a_w[q] + kw) < (unsigned)p.cv_W) amask[q] |= 1u << tap;
+      }
+      const unsigned long long apix01 = (unsigned)a_pix[0] | ((unsigned long long)(unsigned)(a_pix[1] - 1024) << 32);
+      const unsigned long long amask01 = amask[0] | ((unsigned long long)amask[1] << 32);
+      const uint8_t* const azp_row = qg_byte_rows.b[p.cv_azp];
+      const int cv_nc = p.cv_Cin / BK, cv_fs = p.cv_S, cv_rowjump = (p.cv_W - p.cv_S) * p.cv_Cin;
+      if constexpr (TN == 2) {
+        if (ROWSUM)
+          asm volatile(QG_TILE_LOOP_ASM_CONV_2X2 QG_TILE_LOOP_OPERANDS_CONV_2X2);
+        else
+          asm volatile(QG_TILE_LOOP_ASM_CONV_NOROWSUM_2X2 QG_TILE_LOOP_OPERANDS_CONV_2X2);
+      } else {
+        if (ROWSUM)
+          asm volatile(QG_TILE_LOOP_ASM_CONV_2X4 QG_TILE_LOOP_OPERANDS_CONV_2X4);
+        else
+          asm volatile(QG_TILE_LOOP_ASM_CONV_NOROWSUM_2X4 QG_TILE_LOOP_OPERANDS_CONV_2X4);
+      }
     } else if constexpr (TN == 2) {
       if (ROWSUM)
         asm volatile(QG_TILE_LOOP_ASM_2X2 QG_TILE_LOOP_OPERANDS_2X2);
@@ -674,22 +722,34 @@ hipError_t launch_cfg(const qg_gemm_args& a, int mode, hipStream_t s) {
   return launch<QG_MODE_ACC32, PATH, true, NWM, NWN, TM, TN, KS>(a, s);
 }
 
-template <bool ROWSUM, int NWM, int NWN, int TM, int TN, int KS, int EPI, int CONV = 1>
-hipError_t launch_conv_epi(const qg_gemm_args& a, hipStream_t s) {
+template <bool ROWSUM, int NWM, int NWN, int TM, int TN, int KS, int EPI, int CONV = 1, int PATH = PATH_PIPE>
+hipError_t launch_conv_path(const qg_gemm_args& a, hipStream_t s) {
   constexpr int BM = NWM * TM * 32, BN = NWN * TN * 32;
-  constexpr int SMEM = pipe_stages(TM * TN) * KS * (BM + BN) * BK;
+  constexpr int SMEM = (PATH == PATH_ASM ? asm_stages(TM * TN) : pipe_stages(TM * TN)) * KS * (BM + BN) * BK;
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
   const dim3 grid((unsigned)(tiles_m * tiles_n)), block(NWM * NWN * KS * 64);
-  constexpr auto fn = qg_gemm_tile_kernel<QG_MODE_REQUANT, PATH_PIPE, ROWSUM, NWM, NWN, TM, TN, CONV, KS, EPI>;
+  constexpr auto fn = qg_gemm_tile_kernel<QG_MODE_REQUANT, PATH, ROWSUM, NWM, NWN, TM, TN, CONV, KS, EPI>;
   hipError_t e = qg_allow_smem<fn>(SMEM);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(fn, grid, block, SMEM, s, a.A, a.Bp, a.M, a.N, a.K, a.nb16, a.lda, tiles_m, tiles_n, a);
   return hipGetLastError();
 }
+// The 128-row tiles take the hand-scheduled loop when it applies: whole 64-channel slices, at most 32 filter taps
+// (one validity bit each), enough k tiles to fill its stages, and an image that -- with the 1 KiB the second
+// request of a wave is biased by -- lies inside one 4 GiB window (the loop forms the low address word alone).
+template <bool ROWSUM, int NWM, int NWN, int TM, int TN, int KS, int EPI>
+hipError_t launch_conv_epi(const qg_gemm_args& a, hipStream_t s) {
+  if constexpr (TM == 2 && KS == 1) {
+    const uintptr_t lo = (uintptr_t)a.A - 1024, hi = (uintptr_t)a.A + (uintptr_t)a.cv_in_bytes - 1;
+    if (a.cv_R * a.cv_S <= 32 && a.K / BK >= asm_stages(TM * TN) && (lo >> 32) == (hi >> 32))
+      return launch_conv_path<ROWSUM, NWM, NWN, TM, TN, KS, EPI, 1, PATH_ASM>(a, s);
+  }
+  return launch_conv_path<ROWSUM, NWM, NWN, TM, TN, KS, EPI, 1, PATH_PIPE>(a, s);
+}
 template <bool ROWSUM, int NWM, int NWN, int TM, int TN, int KS>
 hipError_t launch_conv_rs(const qg_gemm_args& a, hipStream_t s) {
   // channel counts that are not a multiple of 64: the per-chunk variant, with the one always-correct output form
-  if (a.cv_Cin % BK != 0) return launch_conv_epi<ROWSUM, NWM, NWN, TM, TN, KS, EPI_CLAMP, 2>(a, s);
+  if (a.cv_Cin % BK != 0) return launch_conv_path<ROWSUM, NWM, NWN, TM, TN, KS, EPI_CLAMP, 2>(a, s);
   if constexpr (TM * TN == 1) {
     return launch_conv_epi<ROWSUM, NWM, NWN, TM, TN, KS, EPI_CLAMP>(a, s);
   } else {

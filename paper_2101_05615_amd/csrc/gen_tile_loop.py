@@ -27,16 +27,32 @@ fixed registers from v96, 16 KiB stages).  With only four MFMAs per k-step the L
 two and the row sums and shifts of both A fragments behind the last two.  A third one, 2 x 4 blocks (128 x 256
 tile: 8 accumulators, three 24 KiB stages so that two workgroups share a CU, fixed registers from v56, one more
 SGPR input bofs = distance from a wave's A request slots to its B request slots), has eight MFMAs per k-step.
+
+CONV variants (2 x 2 and 2 x 4): the A side of a dense convolution with the im2col folded into the requests.
+Tile kt is 64 channels of one filter tap (Cin % 64 == 0, at most 32 taps); a lane's chunk comes from the image at
+(its pixel's byte offset at tap (0, 0)) + (tap offset, kept on the scalar unit), or, when that tap of its pixel
+lies outside the image, from a constant row of theta_A bytes -- so the tile that lands in the stage is the im2col
+tile itself and everything behind the request is the GEMM's loop.  Requests take a 64-bit per-lane address
+(v[lo:hi], off): lo = image_lo + offset or row_lo, hi = image_hi or row_hi (the host checks that the image does
+not straddle a 4 GiB line, the row table is aligned so that it cannot).  Per request: add, and, compare, two
+selects.  Extra fixed registers (after VB): CT..CT+3 address temporaries (two even-aligned pairs), APIX, APIX+1
+per-lane pixel offsets (request q pre-biased by -q KiB, like the table rows: the instruction offset q*1024 moves
+the global address too), AMASK, AMASK+1 per-lane tap-validity bits, TABLO, TABLO+1, TABHI, IMGHI wave-uniform
+address parts.  Extra SGPRs s72..s79: image_lo + tap offset, channel slice, slices per tap, kw, S, row jump
+((W - S) * Cin), tap bit, temporary.  Inputs apix01 amask01 (64-bit VGPR), aptr = image, tab = row of theta_A
+bytes (64-bit SGPR), nc, fs (S), rowjump (SGPR); av01 is not used.
 """
 import os
 
-def configure(tm, tn, nstage=4):
+def configure(tm, tn, nstage=4, conv=False):
     """sets the module-level plan for TM x TN blocks of 32 x 32 per wave (2 x 2 waves per workgroup)"""
     global TM, TN, NM, A, B, RS, AV, BV, ARD0, ARD1, BRD, VA, VB, STAGE_BYTES, A_STAGE, A_DMA, N_DMA, NREAD, RSLOTS
-    global FIRST_VGPR, LAST_VGPR, NSTAGE
+    global FIRST_VGPR, LAST_VGPR, NSTAGE, CT, APIX, AMASK, TABLO, TABHI, IMGHI
     assert (tm, tn) in ((4, 4), (2, 2), (2, 4)) and nstage in (3, 4)
     TM, TN, NM, NSTAGE = tm, tn, tm * tn, nstage
-    base = {16: 160, 4: 76, 8: 56}[tm * tn]
+    # (two waves per SIMD split the register file into 128 vector and 128 accumulator registers: v127 is the last
+    # one, so the convolution variants, with twelve more fixed registers, start lower)
+    base = {16: 160, 4: 66 if conv else 76, 8: 50 if conv else 56}[tm * tn]
     A = [base, base + 4 * (tm + tn)]
     B = [base + 4 * tm, base + 4 * (tm + tn) + 4 * tm]
     RS = base + 8 * (tm + tn)                       # TM row-sum accumulators
@@ -45,6 +61,8 @@ def configure(tm, tn, nstage=4):
     ARD0, ARD1, BRD = BV + 4, BV + 5, BV + 6        # BRD is moved as a 64-bit pair
     VA, VB = BV + 8, BV + 9
     FIRST_VGPR, LAST_VGPR = base, 255 if tm == 4 else VB
+    CT = VB + 1 + ((VB + 1) & 1)                    # CONV: even-aligned address pairs of the two A requests
+    APIX, AMASK, TABLO, TABHI, IMGHI = CT + 4, CT + 6, CT + 8, CT + 10, CT + 11
     A_STAGE = tm * 4096                             # 64 * TM rows of 64 bytes
     STAGE_BYTES = (tm + tn) * 4096
     A_DMA = tm                                      # 1 KiB requests per wave and tile: TM for A, then TN for B
@@ -83,15 +101,38 @@ def dma(e, q):
         # distance is wave dependent and comes in as an operand (s85)
         e(f"s_add_u32 m0, s96, {A_STAGE}" if TM == TN else "s_add_u32 m0, s96, s85")
         e("s_nop 0")
-    if q < A_DMA:
+    if q < A_DMA and CONV:
+        lo, hi = CT + 2 * q, CT + 2 * q + 1
+        e(f"v_add_u32 v{lo}, s72, v{APIX + q}")
+        e(f"v_and_b32 v{hi}, s78, v{AMASK + q}")
+        e(f"v_cmp_ne_u32 vcc, 0, v{hi}")
+        e(f"v_cndmask_b32 v{lo}, v{TABLO + q}, v{lo}, vcc")
+        e(f"v_cndmask_b32 v{hi}, v{TABHI}, v{IMGHI}, vcc")
+        e(f"global_load_lds_dwordx4 v[{lo}:{hi}], off" + (f" offset:{q * 1024}" if q else ""))
+    elif q < A_DMA:
         e(f"global_load_lds_dwordx4 v{AV + q}, s[86:87]" + (f" offset:{q * 1024}" if q else ""))
     else:
         e(f"global_load_lds_dwordx4 v{BV}, s[88:89]" + (f" offset:{(q - A_DMA) * 1024}" if q > A_DMA else ""))
 
 
 def advance_request_pointers(e):
-    e("s_add_u32 s86, s86, 64")
-    e("s_addc_u32 s87, s87, 0")
+    if CONV:
+        # next 64-channel slice; past the last slice of a tap the next tap of the filter row follows in memory,
+        # past the last tap of a filter row the next image row is (W - S) * Cin bytes further
+        e("s_add_u32 s72, s72, 64")
+        e("s_add_u32 s73, s73, 1")
+        e("s_cmp_eq_u32 s73, s74")
+        e("s_cselect_b32 s79, 1, 0")
+        e("s_cselect_b32 s73, 0, s73")
+        e("s_lshl_b32 s78, s78, s79")
+        e("s_add_u32 s75, s75, s79")
+        e("s_cmp_eq_u32 s75, s76")
+        e("s_cselect_b32 s75, 0, s75")
+        e("s_cselect_b32 s79, s77, 0")
+        e("s_add_u32 s72, s72, s79")
+    else:
+        e("s_add_u32 s86, s86, 64")
+        e("s_addc_u32 s87, s87, 0")
     e("s_add_u32 s88, s88, s99")
     e("s_addc_u32 s89, s89, 0")
 
@@ -114,6 +155,7 @@ def reads(e, slot, ld, ks):
 
 
 ROWSUM = True  # False: variant for weights whose zero points are all 0 (no row offsets needed)
+CONV = False   # True: the A requests of a dense convolution (see the module text)
 
 
 def prep_slots():
@@ -208,12 +250,30 @@ def tile(e, wait_vm, request, last=False):
     e("s_waitcnt lgkmcnt(0)")
 
 
-def generate_loop(rowsum):
-    global ROWSUM
-    ROWSUM = rowsum
+def generate_loop(rowsum, conv=False):
+    global ROWSUM, CONV
+    ROWSUM, CONV = rowsum, conv
+    assert not conv or TM == 2
     e = Emit()
     # ---- unpack operands into the fixed registers
-    e(f"v_mov_b64 v[{AV}:{AV + 1}], %[av01]")
+    if conv:
+        e(f"v_mov_b64 v[{APIX}:{APIX + 1}], %[apix01]")
+        e(f"v_mov_b64 v[{AMASK}:{AMASK + 1}], %[amask01]")
+        e("s_mov_b64 s[72:73], %[tab]")
+        e(f"v_mov_b32 v{TABLO}, s72")
+        e("s_sub_u32 s72, s72, 1024")
+        e(f"v_mov_b32 v{TABLO + 1}, s72")
+        e(f"v_mov_b32 v{TABHI}, s73")
+        e("s_mov_b64 s[72:73], %[aptr]")
+        e(f"v_mov_b32 v{IMGHI}, s73")
+        e("s_mov_b32 s73, 0")
+        e("s_mov_b32 s74, %[nc]")
+        e("s_mov_b32 s75, 0")
+        e("s_mov_b32 s76, %[fs]")
+        e("s_mov_b32 s77, %[rowjump]")
+        e("s_mov_b32 s78, 1")
+    else:
+        e(f"v_mov_b64 v[{AV}:{AV + 1}], %[av01]")
     if TM == 4:
         e(f"v_mov_b64 v[{AV + 2}:{AV + 3}], %[av23]")
     e(f"v_mov_b64 v[{BV}:{BV + 1}], %[bv01]")
@@ -224,7 +284,8 @@ def generate_loop(rowsum):
     e("s_mov_b32 s84, 0x80808080")
     if TM != TN:
         e("s_mov_b32 s85, %[bofs]")
-    e("s_mov_b64 s[86:87], %[aptr]")
+    if not conv:
+        e("s_mov_b64 s[86:87], %[aptr]")
     e("s_mov_b64 s[88:89], %[bptr]")
     e(f"s_sub_u32 s90, %[kt], {NSTAGE}")
     e("s_mov_b32 s91, %[ldsdma]")
@@ -291,6 +352,14 @@ def generate():
             out += (f"#define {name}{suffix} \\\n" +
                     "".join(f'  "{l}\\n" \\\n' for l in generate_loop(rowsum)) + "  \"\"\n")
         out += f"#define QG_TILE_LOOP_CLOBBERS{suffix} " + ", ".join(clob) + "\n"
+        if tm == 2:
+            configure(tm, tn, nstage, conv=True)
+            clob = [f'"v{i}"' for i in range(FIRST_VGPR, IMGHI + 1)] + [f'"s{i}"' for i in range(72, 80)] + \
+                   [f'"s{i}"' for i in range(84, 100)] + ['"vcc"', '"scc"', '"memory"']
+            for name, rowsum in (("QG_TILE_LOOP_ASM_CONV", True), ("QG_TILE_LOOP_ASM_CONV_NOROWSUM", False)):
+                out += (f"#define {name}{suffix} \\\n" +
+                        "".join(f'  "{l}\\n" \\\n' for l in generate_loop(rowsum, conv=True)) + "  \"\"\n")
+            out += f"#define QG_TILE_LOOP_CLOBBERS_CONV{suffix} " + ", ".join(clob) + "\n"
     configure(4, 4)
     return out
 

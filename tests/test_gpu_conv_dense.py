@@ -47,6 +47,8 @@ def want(c, oracle):
     dict(Nb=1, H=9, W=12, C=64, Cout=32, R=3, S=1, pad=1),        # non-square filter, padding wider than the filter needs
     dict(Nb=2, H=14, W=14, C=256, Cout=300, pad=0),               # no padding, several column tiles
     dict(Nb=1, H=6, W=6, C=64, Cout=64, pad=3),                   # padding beyond the filter's reach
+    dict(Nb=1, H=9, W=9, C=64, Cout=64, R=6, S=6, pad=2),         # 36 taps: more than the hand-scheduled loop's validity bits
+    dict(Nb=2, H=11, W=13, C=128, Cout=130, R=2, S=4, pad=1, stride=2),  # even filter extents, two slices per tap
     # channel counts that are not a multiple of 64: a 64-deep k tile spans taps, the last one may end past K
     dict(Nb=2, H=7, W=9, C=96, Cout=64),                          # K = 864: 13 whole tiles and a half one
     dict(Nb=1, H=5, W=6, C=16, Cout=48),                          # four taps per tile, K = 144
