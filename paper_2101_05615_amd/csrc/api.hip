@@ -147,11 +147,17 @@ int builtin_select(int M, int N, int K) {
   return best;
 }
 
-// cheapest streaming kernel (outlier-split descriptors run on these only)
+// cheapest streaming kernel (outlier-split descriptors run on these only, always in the 16-wave form: the constants
+// fitted when every shape ran that form, large column counts included)
+const stream_cost k_stream_cost_16wave[] = {
+    {QG_KERNEL_SKINNY16, 16, 3.58, 7.3e-5, 7.55, 0.74e-3},
+    {QG_KERNEL_SKINNY32, 32, 4.13, 1.99e-4, 10.33, 1.28e-3},
+    {QG_KERNEL_SKINNY64, 64, 4.96, 3.88e-4, 14.26, 2.23e-3},
+};
 int select_stream_kernel(int M, int N, int K) {
   int best = QG_KERNEL_SKINNY64;
   double best_us = 1e300;
-  for (const stream_cost& c : k_stream_cost) {
+  for (const stream_cost& c : k_stream_cost_16wave) {
     const long long blocks = ceil_div(M, c.rows);
     if (blocks > 65535) continue;
     const double us = stream_estimate(c, M, N, K, false);
