@@ -384,8 +384,14 @@ size_t qg_packed_b_nnz(const qg_packed_b* p);
  * (kh, kw, c_in), N = Cout/G.  The im2col matrix is never materialised.
  *   W_dev      dev, int8, [G][R][S][C/G][Cout/G]
  *   b_zp_host  HOST, 1 or Cout entries
- * This build implements C/G == 4 and Cout/G == 4 with R*S in {1, 9}; anything
- * else returns QG_EUNSUPPORTED. */
+ * Any G, R, S, C/G and Cout/G (R*S*C/G <= QG_MAX_K).  Groups of 4 -> 4 channels
+ * with a 1 x 1 or 3 x 3 filter have the kernels this library is tuned for (one
+ * dword per tap, or block-diagonal matrix-core tiles when C % 32 == 0); square
+ * groups of 8, 16 or 32 channels with those filters and C % 32 == 0 run the same
+ * matrix-core kernels on their own block-diagonal tiles; other groups of a
+ * multiple of 16 input channels (up to 64 groups, 16-byte aligned image) run one
+ * dense convolution per group on the group's channel slice; every other shape
+ * runs a plain one-thread-per-output kernel (correct for any extents, not tuned). */
 int qg_pack_conv_w_sizes(int G, int R, int S, int Cg, int Og, size_t* packed_bytes,
                          size_t* col_offsets_bytes);
 int qg_pack_conv_w(const int8_t* W_dev, int G, int R, int S, int Cg, int Og, const int32_t* b_zp_host,
@@ -393,7 +399,8 @@ int qg_pack_conv_w(const int8_t* W_dev, int G, int R, int S, int Cg, int Og, con
                    qg_packed_b** out);
 
 /* in_nhwc: dev uint8 [Nb][H][W][C]; out_nhwc: dev uint8 [Nb][Ho][Wo][Cout],
- * Ho = (H + 2*pad - R)/stride + 1 (same for Wo); both 4-byte aligned.
+ * Ho = (H + 2*pad - R)/stride + 1 (same for Wo); both 4-byte aligned for the
+ * 4 -> 4 groups (QG_EALIGN otherwise), any address for other group shapes.
  * p->n_scales is 1 or Cout, p->bias has Cout entries or is NULL. */
 int qg_conv_groupwise_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int C, int pad,
                                    int stride, const qg_packed_b* Wp, const qg_requant_params* p,

@@ -860,6 +860,62 @@ int qg_gemm_f32s8_dequant_f32(const float* A_dev, int M, int lda, float a_inv_sc
                                   nullptr, stream, kernel);
 }
 
+namespace {
+// One convolution as a GEMM with the im2col folded into the requests: Cin channels starting at `in` of pixels that
+// are `pix` bytes apart (a whole image, or the channel slice of one group), weights as a packed K x N matrix with
+// K = R*S*Cin; output channel j goes to out[pixel * ldc + j]; bias and scales (when per channel) start at entry ch0.
+int launch_conv_gemm(const uint8_t* in, int in_bytes, int Nb, int H, int W, int Cin, int pix, int R, int S, int pad, int stride,
+                     int Ho, int Wo, const int8_t* packed, const int32_t* col_off, const int32_t* bzp, int K, int K_pad, int N,
+                     int N_pad, int has_bzp, const qg_requant_params* p, int ch0, uint8_t* out, int ldc, int kernel,
+                     hipStream_t stream) {
+  qg_gemm_args a = {};
+  a.A = in;
+  a.Bp = packed;
+  a.col_off = col_off;
+  a.bzp = bzp;
+  a.M = Nb * Ho * Wo;
+  a.N = N;
+  a.K = K;
+  a.kb64 = K_pad / QG_FRAG_K;
+  a.nb16 = N_pad / QG_FRAG_COLS;
+  a.has_bzp = has_bzp;
+  a.lda = 0;
+  a.bias = p->bias ? p->bias + ch0 : nullptr;
+  a.scales = p->n_scales == 1 ? p->scales : p->scales + ch0;
+  a.scale_stride = p->n_scales == 1 ? 0 : 1;
+  a.a_zp_m128 = p->a_zp - 128;
+  a.c_zp = p->c_zp;
+  const int lo = p->relu ? p->c_zp : 0;
+  a.clamp_lo = (float)(lo - p->c_zp);
+  a.clamp_hi = (float)(255 - p->c_zp);
+  a.C = out;
+  a.ldc = ldc;
+  a.c_vec = aligned(out, 16) && (ldc % 16 == 0);
+  a.cv_H = H;
+  a.cv_W = W;
+  a.cv_Cin = Cin;
+  a.cv_pix = pix;
+  a.cv_Ho = Ho;
+  a.cv_Wo = Wo;
+  a.cv_R = R;
+  a.cv_S = S;
+  a.cv_stride = stride;
+  a.cv_pad = pad;
+  a.cv_azp = p->a_zp;
+  a.cv_in_bytes = in_bytes;
+  // the tiled kernels, chosen by the same cost formula as a GEMM's
+  if (kernel == QG_KERNEL_AUTO) {
+    double best_us = 1e300;
+    for (const tile_cost& c : k_conv_cost) {
+      const double us = tile_estimate(c, a.M, a.N, a.K);
+      if (us < best_us) best_us = us, kernel = c.kernel;
+    }
+  }
+  const hipError_t e = qg_launch_conv_dense(a, kernel, stream);
+  return e == hipSuccess ? QG_OK : QG_ELAUNCH;
+}
+}  // namespace
+
 int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int Cin, int R, int S, int pad,
                                int stride, const qg_packed_b* Wp, const qg_requant_params* p, uint8_t* out_nhwc,
                                void* stream, int kernel) {
@@ -882,61 +938,60 @@ int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int
   // the GEMM's own kernels and choice, hand-scheduled loops included; the bytes are the same either way.
   if (R == 1 && S == 1 && pad == 0 && stride == 1)
     return qg_gemm_u8s8_requant_kernel(in_nhwc, Nb * H * W, Cin, Wp, p, out_nhwc, Wp->N, nullptr, stream, kernel);
-  qg_gemm_args a = {};
-  a.A = in_nhwc;
-  a.Bp = Wp->packed;
-  a.col_off = Wp->col_off;
-  a.bzp = Wp->bzp;
-  a.M = Nb * Ho * Wo;
-  a.N = Wp->N;
-  a.K = Wp->K;
-  a.kb64 = Wp->K_pad / QG_FRAG_K;
-  a.nb16 = Wp->N_pad / QG_FRAG_COLS;
-  a.has_bzp = Wp->has_bzp;
-  a.lda = 0;
-  a.bias = p->bias;
-  a.scales = p->scales;
-  a.scale_stride = p->n_scales == 1 ? 0 : 1;
-  a.a_zp_m128 = p->a_zp - 128;
-  a.c_zp = p->c_zp;
-  const int lo = p->relu ? p->c_zp : 0;
-  a.clamp_lo = (float)(lo - p->c_zp);
-  a.clamp_hi = (float)(255 - p->c_zp);
-  a.C = out_nhwc;
-  a.ldc = Wp->N;
-  a.c_vec = aligned(out_nhwc, 16) && (Wp->N % 16 == 0);
-  a.cv_H = H;
-  a.cv_W = W;
-  a.cv_Cin = Cin;
-  a.cv_Ho = Ho;
-  a.cv_Wo = Wo;
-  a.cv_R = R;
-  a.cv_S = S;
-  a.cv_stride = stride;
-  a.cv_pad = pad;
-  a.cv_azp = p->a_zp;
-  a.cv_in_bytes = Nb * H * W * Cin;
-  // the tiled kernels with a compiler-scheduled loop, chosen by the same cost formula as a GEMM's
-  if (kernel == QG_KERNEL_AUTO) {
-    double best_us = 1e300;
-    for (const tile_cost& c : k_conv_cost) {
-      const double us = tile_estimate(c, a.M, a.N, a.K);
-      if (us < best_us) best_us = us, kernel = c.kernel;
-    }
-  }
   if (Nb == 0) return QG_OK;  // an empty batch
-  const hipError_t e = qg_launch_conv_dense(a, kernel, static_cast<hipStream_t>(stream));
-  return e == hipSuccess ? QG_OK : QG_ELAUNCH;
+  return launch_conv_gemm(in_nhwc, Nb * H * W * Cin, Nb, H, W, Cin, Cin, R, S, pad, stride, Ho, Wo, Wp->packed, Wp->col_off,
+                          Wp->bzp, Wp->K, Wp->K_pad, Wp->N, Wp->N_pad, Wp->has_bzp, p, 0, out_nhwc, Wp->N, kernel,
+                          static_cast<hipStream_t>(stream));
 }
+
+namespace {
+// the groups of 4 -> 4 channels with a 1 x 1 or 3 x 3 filter have a layout (and kernels) of their own
+bool conv_is_4to4(int G, int R, int S, int Cg, int Og) {
+  return Cg == 4 && Og == 4 && ((R == 1 && S == 1) || (R == 3 && S == 3)) && G <= 256;
+}
+// log2(Cg) when the block-diagonal matrix-core fragments exist for a general group shape (square groups of 8, 16 or 32
+// channels -- or of 4 in more than 256 groups --, 1 x 1 or 3 x 3, whole 32-channel blocks), else -1
+int conv_mfma_lcg(int G, int R, int S, int Cg, int Og) {
+  if (Cg != Og || !((R == 1 && S == 1) || (R == 3 && S == 3)) || (G * Cg) % 32 != 0) return -1;
+  return Cg == 4 ? 2 : Cg == 8 ? 3 : Cg == 16 ? 4 : Cg == 32 ? 5 : -1;
+}
+// groups of a multiple of 16 channels without block-diagonal tiles: each group is a dense convolution of its own
+// channel slice (one launch per group), with its weights packed as a GEMM matrix
+bool conv_is_wide(int G, int R, int S, int Cg, int Og) {
+  return !conv_is_4to4(G, R, S, Cg, Og) && conv_mfma_lcg(G, R, S, Cg, Og) < 0 && Cg % 16 == 0 && G <= 64;
+}
+}  // namespace
+
+static int conv_sizes_without_gemms(int G, int R, int S, int Cg, int Og, size_t* packed_bytes, size_t* col_offsets_bytes);
 
 int qg_pack_conv_w_sizes(int G, int R, int S, int Cg, int Og, size_t* packed_bytes,
                          size_t* col_offsets_bytes) {
   if (!packed_bytes || !col_offsets_bytes) return QG_ENULL;
   if (G <= 0 || R <= 0 || S <= 0 || Cg <= 0 || Og <= 0) return QG_EINVAL;
-  if (Cg != 4 || Og != 4 || !((R == 1 && S == 1) || (R == 3 && S == 3)) || G > 256) return QG_EUNSUPPORTED;
-  // dot4 layout, then (when C = 4 G is a multiple of 32) the matrix-core fragments
-  *packed_bytes = (size_t)qg_round_up(G * R * S * Cg * Og, 256) +
-                  ((G % 8 == 0) ? (size_t)(G / 8) * R * S * QG_FRAG_BYTES : 0);
+  if ((long long)R * S * Cg > QG_MAX_K || (long long)G * Cg >= (1 << 24) || (long long)G * Og >= (1 << 24)) return QG_EINVAL;
+  const int rc = conv_sizes_without_gemms(G, R, S, Cg, Og, packed_bytes, col_offsets_bytes);
+  if (rc != QG_OK) return rc;
+  if (conv_is_wide(G, R, S, Cg, Og)) {
+    const size_t kp = (size_t)qg_round_up(R * S * Cg, QG_KPAD), np = (size_t)qg_round_up(Og, QG_NPAD);
+    *packed_bytes += (size_t)G * kp * np;
+    *col_offsets_bytes += (size_t)G * 2 * np * sizeof(int32_t);
+  }
+  return QG_OK;
+}
+
+// the layouts every group shape has: the general (or 4 -> 4) weights, the block-diagonal tiles, the folded offsets
+static int conv_sizes_without_gemms(int G, int R, int S, int Cg, int Og, size_t* packed_bytes, size_t* col_offsets_bytes) {
+  if (conv_is_4to4(G, R, S, Cg, Og)) {
+    // dot4 layout, then (when C = 4 G is a multiple of 32) the matrix-core fragments
+    *packed_bytes = (size_t)qg_round_up(G * R * S * Cg * Og, 256) +
+                    ((G % 8 == 0) ? (size_t)(G / 8) * R * S * QG_FRAG_BYTES : 0);
+  } else {
+    // general layout [Cout][R*S][Cg rounded up to 4], then the matrix-core fragments where they exist
+    const size_t any = (size_t)G * Og * R * S * (size_t)qg_round_up(Cg, 4);
+    if (any >= (1ull << 31)) return QG_EUNSUPPORTED;
+    *packed_bytes = (any + 255) / 256 * 256 +
+                    (conv_mfma_lcg(G, R, S, Cg, Og) >= 0 ? (size_t)(G * Cg / 32) * R * S * QG_FRAG_BYTES : 0);
+  }
   *col_offsets_bytes = (size_t)qg_round_up(2 * G * Og * (int)sizeof(int32_t), 256);
   return QG_OK;
 }
@@ -972,17 +1027,52 @@ int qg_pack_conv_w(const int8_t* W_dev, int G, int R, int S, int Cg, int Og, con
   h->split = 0;
   h->frag_ptr = h->entries = nullptr;
   h->nnz = 0;
-  int8_t* frags = (G % 8 == 0) ? static_cast<int8_t*>(packed_dev) + qg_round_up(G * R * S * Cg * Og, 256) : nullptr;
+  const bool four = conv_is_4to4(G, R, S, Cg, Og);
+  const int lcg = four ? 2 : conv_mfma_lcg(G, R, S, Cg, Og);
+  int8_t* frags = nullptr;
+  if (four)
+    frags = (G % 8 == 0) ? static_cast<int8_t*>(packed_dev) + qg_round_up(G * R * S * Cg * Og, 256) : nullptr;
+  else if (lcg >= 0)
+    frags = static_cast<int8_t*>(packed_dev) + ((size_t)Cout * R * S * (size_t)qg_round_up(Cg, 4) + 255) / 256 * 256;
   h->conv_frags = frags;
+  h->conv_any = four ? nullptr : static_cast<const int8_t*>(packed_dev);
   rc = upload_bzp(b_zp_host, n_b_zp, Cout, Cout, col_offsets_dev + Cout, s, &h->has_bzp);
   if (rc != QG_OK) {
     delete h;
     return rc;
   }
-  if (qg_launch_pack_conv_w(W_dev, G, R * S, static_cast<int8_t*>(packed_dev), col_offsets_dev,
-                            col_offsets_dev + Cout, frags, s) != hipSuccess) {
+  const hipError_t e = four ? qg_launch_pack_conv_w(W_dev, G, R * S, static_cast<int8_t*>(packed_dev), col_offsets_dev,
+                                                    col_offsets_dev + Cout, frags, s)
+                            : qg_launch_pack_conv_w_any(W_dev, G, R * S, Cg, Og, static_cast<int8_t*>(packed_dev),
+                                                        col_offsets_dev, col_offsets_dev + Cout, frags, lcg, s);
+  if (e != hipSuccess) {
     delete h;
     return QG_ELAUNCH;
+  }
+  h->conv_gemm = nullptr;
+  h->conv_gemm_off = nullptr;
+  if (conv_is_wide(G, R, S, Cg, Og)) {
+    const int K = R * S * Cg, kp = qg_round_up(K, QG_KPAD), np = qg_round_up(Og, QG_NPAD);
+    size_t pb0, cb0;
+    conv_sizes_without_gemms(G, R, S, Cg, Og, &pb0, &cb0);
+    int8_t* gp = static_cast<int8_t*>(packed_dev) + pb0;
+    int32_t* go = col_offsets_dev + cb0 / sizeof(int32_t);
+    for (int g = 0; g < G; ++g) {
+      int unused;
+      rc = upload_bzp(n_b_zp == 1 ? b_zp_host : b_zp_host + (size_t)g * Og, n_b_zp == 1 ? 1 : Og, Og, np,
+                      go + (size_t)g * 2 * np + np, s, &unused);
+      if (rc == QG_OK && qg_launch_pack_b(W_dev + (size_t)g * K * Og, K, Og, Og, 0, kp, np, gp + (size_t)g * kp * np,
+                                          go + (size_t)g * 2 * np, go + (size_t)g * 2 * np + np, s) != hipSuccess)
+        rc = QG_ELAUNCH;
+      if (rc != QG_OK) {
+        delete h;
+        return rc;
+      }
+    }
+    h->conv_gemm = gp;
+    h->conv_gemm_off = go;
+    h->conv_gemm_kpad = kp;
+    h->conv_gemm_npad = np;
   }
   *out = h;
   return QG_OK;
@@ -1000,7 +1090,7 @@ int qg_conv_groupwise_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W,
   const int Ho = (H + 2 * pad - Wp->R) / stride + 1;
   const int Wo = (W + 2 * pad - Wp->S) / stride + 1;
   if (H + 2 * pad < Wp->R || W + 2 * pad < Wp->S || Ho <= 0 || Wo <= 0) return QG_EINVAL;
-  if (!aligned(in_nhwc, 4) || !aligned(out_nhwc, 4)) return QG_EALIGN;
+  if (Wp->conv_any == nullptr && (!aligned(in_nhwc, 4) || !aligned(out_nhwc, 4))) return QG_EALIGN;
   if ((uint64_t)Nb * H * W * C >= (1ull << 31) || (uint64_t)Nb * Ho * Wo * Wp->N >= (1ull << 31)) return QG_EUNSUPPORTED;
   qg_conv_args a = {};
   a.in = in_nhwc;
@@ -1019,6 +1109,12 @@ int qg_conv_groupwise_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W,
   a.Wo = Wo;
   a.Cout = Wp->N;
   a.G = Wp->G;
+  a.Wany = Wp->conv_any;
+  a.Cg = Wp->Cg;
+  a.Og = Wp->Og;
+  a.R = Wp->R;
+  a.S = Wp->S;
+  a.lcg = Wp->conv_any == nullptr ? 2 : (Wp->conv_frags != nullptr ? conv_mfma_lcg(Wp->G, Wp->R, Wp->S, Wp->Cg, Wp->Og) : 0);
   a.pad = pad;
   a.stride = stride;
   a.scale_stride = p->n_scales == 1 ? 0 : 1;
@@ -1029,6 +1125,20 @@ int qg_conv_groupwise_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W,
   a.clamp_hi = (float)(255 - p->c_zp);
   a.has_bzp = Wp->has_bzp;
   if (Nb == 0) return QG_OK;  // an empty batch
+  // wide groups: every group is a dense convolution of its own channel slice (16-byte chunks need aligned pixels)
+  if (Wp->conv_gemm != nullptr && C % 16 == 0 && aligned(in_nhwc, 16) && (uint64_t)Nb * H * W * C < (1ull << 30) &&
+      (uint64_t)Nb * Ho * Wo < (1ull << 31) / 4) {
+    const size_t kp = (size_t)Wp->conv_gemm_kpad, np = (size_t)Wp->conv_gemm_npad;
+    for (int g = 0; g < Wp->G; ++g) {
+      const int32_t* off = Wp->conv_gemm_off + (size_t)g * 2 * np;
+      rc = launch_conv_gemm(in_nhwc + (size_t)g * Wp->Cg, Nb * H * W * C - g * Wp->Cg, Nb, H, W, Wp->Cg, C, Wp->R, Wp->S, pad,
+                            stride, Ho, Wo, Wp->conv_gemm + (size_t)g * kp * np, off, off + np, Wp->K, (int)kp, Wp->Og, (int)np,
+                            Wp->has_bzp, p, g * Wp->Og, out_nhwc + (size_t)g * Wp->Og, Wp->N, QG_KERNEL_AUTO,
+                            static_cast<hipStream_t>(stream));
+      if (rc != QG_OK) return rc;
+    }
+    return QG_OK;
+  }
   hipError_t e = qg_launch_conv_group(a, Wp->R * Wp->S, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? QG_OK : QG_ELAUNCH;
 }

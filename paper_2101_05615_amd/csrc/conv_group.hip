@@ -23,6 +23,22 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
+// Byte sums of a lane's four dwords (16 input channels of one pixel) -> per dword, the sum over the whole group the
+// dword belongs to: groups of 4 channels are the dwords themselves, of 8 pairs of dwords, of 16 the lane's four, of 32
+// those of both lanes of the pixel (lanes 32 apart).  lcg = log2(channels per group), uniform.
+__device__ __forceinline__ void group_sums(unsigned (&rs)[4], int lcg) {
+  if (lcg <= 2) return;
+  const unsigned a = rs[0] + rs[1], b = rs[2] + rs[3];
+  if (lcg == 3) {
+    rs[0] = rs[1] = a;
+    rs[2] = rs[3] = b;
+    return;
+  }
+  unsigned t = a + b;
+  if (lcg == 5) t += (unsigned)__shfl_xor((int)t, 32);
+  rs[0] = rs[1] = rs[2] = rs[3] = t;
+}
+
 // NCB 32-channel blocks per wave pass; the workgroup (4 waves) shares their weights in LDS and each wave
 // walks over blocks of 32 consecutive output pixels.
 template <int R, int S, int NCB, bool HAS_BZP>
@@ -119,6 +135,10 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 4) void qg_conv_group_mfma_kerne
     }
 
     // ---- output pipeline: lane (pixel pl, half g) holds channels 32 cb + 16 g .. + 15 of its pixel
+    if (HAS_BZP) {
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) group_sums(rs[cb], p.lcg);
+    }
     if (px < npix) {
       auto pipeline = [&](auto lo_tag) {
       constexpr bool LO = decltype(lo_tag)::value;
@@ -131,8 +151,8 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 4) void qg_conv_group_mfma_kerne
           const v4i cj = *reinterpret_cast<const v4i*>(&cj_s[c_l + 4 * q]);
           const v4i nbz = *reinterpret_cast<const v4i*>(&nbz_s[c_l + 4 * q]);
           const float4 sc = *reinterpret_cast<const float4*>(&sc_s[c_l + 4 * q]);
-          // row offset of group q of this half, in the int8 domain: every one of the RS*4 bytes is 128 high
-          const int rsum = HAS_BZP ? (int)rs[cb][q] - 128 * RS * 4 : 0;
+          // row offset of the group of dword q of this half, in the int8 domain: every one of its RS*Cg bytes is 128 high
+          const int rsum = HAS_BZP ? (int)rs[cb][q] - ((128 * RS) << p.lcg) : 0;
           const int x0 = acc[cb][4 * q + 0] + cj.x + (HAS_BZP ? __mul24(nbz.x, rsum) : 0);
           const int x1 = acc[cb][4 * q + 1] + cj.y + (HAS_BZP ? __mul24(nbz.y, rsum) : 0);
           const int x2 = acc[cb][4 * q + 2] + cj.z + (HAS_BZP ? __mul24(nbz.z, rsum) : 0);
@@ -309,6 +329,10 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
   }
 
   // ---- output pipeline: lane (pixel pl, half g) holds channels 32 cb + 16 g .. + 15 of its pixel
+  if (HAS_BZP) {
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) group_sums(rs[cb], p.lcg);
+  }
   if (px < npix) {
     auto pipeline = [&](auto lo_tag) {
     constexpr bool LO = decltype(lo_tag)::value;
@@ -322,7 +346,7 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
         int x0 = acc[cb][4 * q + 0], x1 = acc[cb][4 * q + 1], x2 = acc[cb][4 * q + 2], x3 = acc[cb][4 * q + 3];
         if (HAS_BZP) {
           const v4i nbz = *reinterpret_cast<const v4i*>(&nbz_s[c_l + 4 * q]);
-          const int rsum = (int)rs[cb][q] - 128 * RS * 4;
+          const int rsum = (int)rs[cb][q] - ((128 * RS) << p.lcg);
           x0 += __mul24(nbz.x, rsum);
           x1 += __mul24(nbz.y, rsum);
           x2 += __mul24(nbz.z, rsum);
@@ -404,6 +428,52 @@ __global__ __launch_bounds__(256) void qg_conv_group_kernel(const qg_conv_args p
   }
 }
 
+// Any group shape (G groups of Cg input and Og output channels, any filter): thread = (pixel, output channel),
+// output channels fastest so that the bytes of a pixel are stored side by side; the K = R*S*Cg inputs of the
+// thread's group are read tap by tap, whole dwords against the [Cout][R*S][Cg4] weight layout (v_dot4_i32_i8)
+// when Cg and C are multiples of 4, byte by byte otherwise.  Nothing is tiled: this is the kernel for the
+// shapes no other one takes.
+template <bool DWORDS>
+__global__ __launch_bounds__(256) void qg_conv_group_any_kernel(const qg_conv_args p) {
+  const int RS = p.R * p.S, Cg4 = (p.Cg + 3) / 4 * 4;
+  const long long total = (long long)p.Nb * p.Ho * p.Wo * p.Cout;
+  const int azp_s = p.a_zp - 128;
+  const int pad_word = (p.a_zp * 0x01010101) ^ 0x80808080;  // theta_A - 128 in every byte
+  for (long long idx = (long long)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (long long)gridDim.x * 256) {
+    const int oc = (int)(idx % p.Cout);
+    const long long px = idx / p.Cout;
+    const int g = oc / p.Og;
+    const int wo = (int)(px % p.Wo);
+    const int ho = (int)((px / p.Wo) % p.Ho);
+    const int n = (int)(px / ((long long)p.Wo * p.Ho));
+    const int8_t* w = p.Wany + (size_t)oc * RS * Cg4;
+    int acc = 0, rsum = 0;  // both on A - 128
+    for (int kh = 0; kh < p.R; ++kh) {
+      const int hi = ho * p.stride + kh - p.pad;
+      for (int kw = 0; kw < p.S; ++kw, w += Cg4) {
+        const int wi = wo * p.stride + kw - p.pad;
+        const bool ok = hi >= 0 && hi < p.H && wi >= 0 && wi < p.W;
+        const uint8_t* src = p.in + (((size_t)n * p.H + (ok ? hi : 0)) * p.W + (ok ? wi : 0)) * p.C + (size_t)g * p.Cg;
+        if (DWORDS) {
+          for (int c = 0; c < p.Cg; c += 4) {
+            const int a = ok ? (*reinterpret_cast<const int*>(src + c) ^ (int)0x80808080) : pad_word;
+            acc = __builtin_amdgcn_sdot4(a, *reinterpret_cast<const int*>(w + c), acc, false);
+            rsum = __builtin_amdgcn_sdot4(a, 0x01010101, rsum, false);
+          }
+        } else {
+          for (int c = 0; c < p.Cg; ++c) {
+            const int a = ok ? (int)src[c] - 128 : azp_s;
+            acc += a * (int)w[c];
+            rsum += a;
+          }
+        }
+      }
+    }
+    const int x = acc + (p.bias ? p.bias[oc] : 0) - azp_s * p.col_off[oc] - p.bzp[oc] * rsum;
+    p.out[idx] = (uint8_t)qg_requant_one(x, p.scales[(size_t)oc * p.scale_stride], p.clamp_lo, p.clamp_hi, p.c_zp);
+  }
+}
+
 }  // namespace
 
 template <int R, int S, int NCB>
@@ -439,7 +509,8 @@ hipError_t launch_same(const qg_conv_args& a, int smem, int halo, int nchunks_pa
 }
 
 hipError_t qg_launch_conv_group(const qg_conv_args& a, int RS, hipStream_t s) {
-  const bool mfma_ok = a.Wfrag != nullptr && a.C % 32 == 0 && a.Cout == a.C &&
+  // the matrix-core kernels: block-diagonal 32 x 32 weight fragments exist (Cg == Og in {4, 8, 16, 32}, 1 x 1 or 3 x 3)
+  const bool mfma_ok = a.Wfrag != nullptr && ((a.R == 3 && a.S == 3) || (a.R == 1 && a.S == 1)) && a.C % 32 == 0 && a.Cout == a.C &&
                        reinterpret_cast<uintptr_t>(a.in) % 16 == 0 && reinterpret_cast<uintptr_t>(a.out) % 16 == 0;
   // "same" convolution: whole input patch staged in LDS, if it fits
   const int R = RS == 9 ? 3 : 1;
@@ -463,6 +534,17 @@ hipError_t qg_launch_conv_group(const qg_conv_args& a, int RS, hipStream_t s) {
       reinterpret_cast<uintptr_t>(a.in) % 16 == 0 && reinterpret_cast<uintptr_t>(a.out) % 16 == 0) {
     if (a.C % 128 == 0) return RS == 9 ? launch_mfma<3, 3, 4>(a, s) : launch_mfma<1, 1, 4>(a, s);
     return RS == 9 ? launch_mfma<3, 3, 1>(a, s) : launch_mfma<1, 1, 1>(a, s);
+  }
+  if (a.Wany != nullptr) {
+    // the general kernel: one thread per output byte
+    const long long total = (long long)a.Nb * a.Ho * a.Wo * a.Cout;
+    const unsigned blocks = (unsigned)((total + 255) / 256 < 256LL * 64 ? (total + 255) / 256 : 256LL * 64);
+    const bool dwords = a.Cg % 4 == 0 && a.C % 4 == 0 && reinterpret_cast<uintptr_t>(a.in) % 4 == 0;
+    if (dwords)
+      hipLaunchKernelGGL(qg_conv_group_any_kernel<true>, dim3(blocks), dim3(256), 0, s, a);
+    else
+      hipLaunchKernelGGL(qg_conv_group_any_kernel<false>, dim3(blocks), dim3(256), 0, s, a);
+    return hipGetLastError();
   }
   const int ppb = a.G >= 256 ? 1 : 256 / a.G;
   const int threads = ppb * a.G;

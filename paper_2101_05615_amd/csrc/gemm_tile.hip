@@ -114,7 +114,7 @@ __device__ __forceinline__ int a_lds_off(int r, int kc) { return r * BK + ((kc ^
                  : [c0] "+a"(acc[0][0]), [c1] "+a"(acc[0][1]), [c2] "+a"(acc[1][0]), [c3] "+a"(acc[1][1]), \
                    [rs01] "=v"(rs01) \
                  : [apix01] "v"(apix01), [amask01] "v"(amask01), [bv01] "v"(bv01), [ard] "v"(ard), [brd] "v"(brd), \
-                   [aptr] "s"(A), [tab] "s"(azp_row), [nc] "s"(cv_nc), [fs] "s"(cv_fs), [rowjump] "s"(cv_rowjump), \
+                   [aptr] "s"(A), [tab] "s"(azp_row), [nc] "s"(cv_nc), [fs] "s"(cv_fs), [rowjump] "s"(cv_rowjump), [tapjump] "s"(cv_tapjump), \
                    [bptr] "s"(b_tile0), [kt] "s"(KTF), [ldsdma] "s"(lds_dma), [lds] "s"(lds_base), [bstep] "s"(b_step) \
                  : QG_TILE_LOOP_CLOBBERS_CONV_2X2
 
@@ -123,7 +123,7 @@ __device__ __forceinline__ int a_lds_off(int r, int kc) { return r * BK + ((kc ^
                    [c4] "+a"(acc[1][0]), [c5] "+a"(acc[1][1]), [c6] "+a"(acc[1][2]), [c7] "+a"(acc[1][3]), \
                    [rs01] "=v"(rs01) \
                  : [apix01] "v"(apix01), [amask01] "v"(amask01), [bv01] "v"(bv01), [ard] "v"(ard), [brd] "v"(brd), \
-                   [aptr] "s"(A), [tab] "s"(azp_row), [nc] "s"(cv_nc), [fs] "s"(cv_fs), [rowjump] "s"(cv_rowjump), \
+                   [aptr] "s"(A), [tab] "s"(azp_row), [nc] "s"(cv_nc), [fs] "s"(cv_fs), [rowjump] "s"(cv_rowjump), [tapjump] "s"(cv_tapjump), \
                    [bptr] "s"(b_tile0), [kt] "s"(KTF), [ldsdma] "s"(lds_dma), [lds] "s"(lds_base), [bstep] "s"(b_step), \
                    [bofs] "s"(A_STAGE + wave * ((B_DMA - A_DMA) * 1024)) \
                  : QG_TILE_LOOP_CLOBBERS_CONV_2X4
@@ -239,7 +239,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
       const int wo = rg % p.cv_Wo, t = rg / p.cv_Wo;
       const int ho = t % p.cv_Ho, n = t / p.cv_Ho;
       // byte offset of this lane's chunk at tap (0, 0), channel slice 0; a tap adds a workgroup-uniform offset
-      a_pix[q] = ((n * p.cv_H + ho * p.cv_stride - p.cv_pad) * p.cv_W + wo * p.cv_stride - p.cv_pad) * p.cv_Cin +
+      a_pix[q] = ((n * p.cv_H + ho * p.cv_stride - p.cv_pad) * p.cv_W + wo * p.cv_stride - p.cv_pad) * p.cv_pix +
                  (CVG ? 0 : kc * 16);
       a_voff[q] = kc * 16;  // CVG: the chunk of the tile this lane requests
       a_h[q] = ho * p.cv_stride - p.cv_pad;
@@ -352,7 +352,8 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
       const unsigned long long apix01 = (unsigned)a_pix[0] | ((unsigned long long)(unsigned)(a_pix[1] - 1024) << 32);
       const unsigned long long amask01 = amask[0] | ((unsigned long long)amask[1] << 32);
       const uint8_t* const azp_row = qg_byte_rows.b[p.cv_azp];
-      const int cv_nc = p.cv_Cin / BK, cv_fs = p.cv_S, cv_rowjump = (p.cv_W - p.cv_S) * p.cv_Cin;
+      const int cv_nc = p.cv_Cin / BK, cv_fs = p.cv_S, cv_rowjump = (p.cv_W - p.cv_S) * p.cv_pix;
+      const int cv_tapjump = p.cv_pix - p.cv_Cin;
       if constexpr (TN == 2) {
         if (ROWSUM)
           asm volatile(QG_TILE_LOOP_ASM_CONV_2X2 QG_TILE_LOOP_OPERANDS_CONV_2X2);
@@ -427,7 +428,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
       if (CVG) {
 #pragma unroll
         for (int q = 0; q < A_DMA; ++q) {
-          const int off = a_pix[q] + (rqv_kh[q] * p.cv_W + rqv_kw[q]) * p.cv_Cin + rqv_c[q] * 16;
+          const int off = a_pix[q] + (rqv_kh[q] * p.cv_W + rqv_kw[q]) * p.cv_pix + rqv_c[q] * 16;
           const bool in_k = rqv_kh[q] < p.cv_R;
           const bool in_image = (unsigned)(a_h[q] + rqv_kh[q]) < (unsigned)p.cv_H && (unsigned)(a_w[q] + rqv_kw[q]) < (unsigned)p.cv_W;
           const uint8_t* src = !in_k ? qg_byte_rows.b[128] : (in_image ? A + off : azp_row);
@@ -435,7 +436,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
           cvg_advance(rqv_c[q], rqv_kw[q], rqv_kh[q]);
         }
       } else if (CONV) {
-        const int tap_off = (rq_kh * p.cv_W + rq_kw) * p.cv_Cin + rq_cc * BK;
+        const int tap_off = (rq_kh * p.cv_W + rq_kw) * p.cv_pix + rq_cc * BK;
 #pragma unroll
         for (int q = 0; q < A_DMA; ++q) {
           const bool in_image = (unsigned)(a_h[q] + rq_kh) < (unsigned)p.cv_H && (unsigned)(a_w[q] + rq_kw) < (unsigned)p.cv_W;

@@ -38,9 +38,9 @@ not straddle a 4 GiB line, the row table is aligned so that it cannot).  Per req
 selects.  Extra fixed registers (after VB): CT..CT+3 address temporaries (two even-aligned pairs), APIX, APIX+1
 per-lane pixel offsets (request q pre-biased by -q KiB, like the table rows: the instruction offset q*1024 moves
 the global address too), AMASK, AMASK+1 per-lane tap-validity bits, TABLO, TABLO+1, TABHI, IMGHI wave-uniform
-address parts.  Extra SGPRs s72..s79: image_lo + tap offset, channel slice, slices per tap, kw, S, row jump
-((W - S) * Cin), tap bit, temporary.  Inputs apix01 amask01 (64-bit VGPR), aptr = image, tab = row of theta_A
-bytes (64-bit SGPR), nc, fs (S), rowjump (SGPR); av01 is not used.
+address parts.  Extra SGPRs s72..s81: image_lo + tap offset, channel slice, slices per tap, kw, S, row jump
+((W - S) pixels), tap bit, temporary, tap jump (pixel bytes - Cin), temporary.  Inputs apix01 amask01 (64-bit
+VGPR), aptr = image, tab = row of theta_A bytes (64-bit SGPR), nc, fs (S), rowjump, tapjump (SGPR); av01 is not used.
 """
 import os
 
@@ -117,13 +117,16 @@ def dma(e, q):
 
 def advance_request_pointers(e):
     if CONV:
-        # next 64-channel slice; past the last slice of a tap the next tap of the filter row follows in memory,
-        # past the last tap of a filter row the next image row is (W - S) * Cin bytes further
+        # next 64-channel slice; past the last slice of a tap the next tap of the filter row is (pixel bytes - Cin)
+        # further (0 unless the channels are a slice of wider pixels), past the last tap of a filter row the next
+        # image row (W - S) pixels further
         e("s_add_u32 s72, s72, 64")
         e("s_add_u32 s73, s73, 1")
         e("s_cmp_eq_u32 s73, s74")
         e("s_cselect_b32 s79, 1, 0")
         e("s_cselect_b32 s73, 0, s73")
+        e("s_cselect_b32 s81, s80, 0")
+        e("s_add_u32 s72, s72, s81")
         e("s_lshl_b32 s78, s78, s79")
         e("s_add_u32 s75, s75, s79")
         e("s_cmp_eq_u32 s75, s76")
@@ -272,6 +275,7 @@ def generate_loop(rowsum, conv=False):
         e("s_mov_b32 s76, %[fs]")
         e("s_mov_b32 s77, %[rowjump]")
         e("s_mov_b32 s78, 1")
+        e("s_mov_b32 s80, %[tapjump]")
     else:
         e(f"v_mov_b64 v[{AV}:{AV + 1}], %[av01]")
     if TM == 4:
@@ -354,7 +358,7 @@ def generate():
         out += f"#define QG_TILE_LOOP_CLOBBERS{suffix} " + ", ".join(clob) + "\n"
         if tm == 2:
             configure(tm, tn, nstage, conv=True)
-            clob = [f'"v{i}"' for i in range(FIRST_VGPR, IMGHI + 1)] + [f'"s{i}"' for i in range(72, 80)] + \
+            clob = [f'"v{i}"' for i in range(FIRST_VGPR, IMGHI + 1)] + [f'"s{i}"' for i in range(72, 82)] + \
                    [f'"s{i}"' for i in range(84, 100)] + ['"vcc"', '"scc"', '"memory"']
             for name, rowsum in (("QG_TILE_LOOP_ASM_CONV", True), ("QG_TILE_LOOP_ASM_CONV_NOROWSUM", False)):
                 out += (f"#define {name}{suffix} \\\n" +

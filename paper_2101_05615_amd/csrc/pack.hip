@@ -189,10 +189,11 @@ __global__ void qg_pack_conv_w_kernel(const int8_t* __restrict__ W, int G, int R
 }
 
 // Conv weights for the matrix-core kernel: for every 32-channel block cb and tap, one 1 KiB fragment in
-// v_mfma_i32_32x32x32_i8 operand order holding the block-diagonal 32 x 32 matrix W[oc][ic] (8 groups of
-// 4 x 4; everything off the diagonal blocks is zero).  Lane (i + 32 g) owns W[oc(i)][16 g .. 16 g + 15],
-// oc(i) being the column permutation that leaves each lane of the result with 16 consecutive channels.
-__global__ void qg_pack_conv_w_mfma_kernel(const int8_t* __restrict__ W, int RS, int nfrag,
+// v_mfma_i32_32x32x32_i8 operand order holding the block-diagonal 32 x 32 matrix W[oc][ic] (32 / Cg groups of
+// Cg x Cg, Cg = 1 << lcg in {4, 8, 16, 32}; everything off the diagonal blocks is zero).  Lane (i + 32 g) owns
+// W[oc(i)][16 g .. 16 g + 15], oc(i) being the column permutation that leaves each lane of the result with 16
+// consecutive channels.
+__global__ void qg_pack_conv_w_mfma_kernel(const int8_t* __restrict__ W, int RS, int nfrag, int lcg,
                                            int8_t* __restrict__ frags) {
   const int gid = blockIdx.x * blockDim.x + threadIdx.x;  // one 16-byte chunk per thread
   if (gid >= nfrag * 64) return;
@@ -208,13 +209,39 @@ __global__ void qg_pack_conv_w_mfma_kernel(const int8_t* __restrict__ W, int RS,
   for (int b = 0; b < 16; ++b) {
     const int ic_l = 16 * g + b;
     int8_t w = 0;
-    if ((ic_l >> 2) == (oc_l >> 2)) {
-      const int grp = cb * 8 + (oc_l >> 2);
-      w = W[(((size_t)grp * RS + tap) * 4 + (ic_l & 3)) * 4 + (oc_l & 3)];
+    if ((ic_l >> lcg) == (oc_l >> lcg)) {
+      const int cg = 1 << lcg;
+      const int grp = cb * (32 >> lcg) + (oc_l >> lcg);
+      w = W[(((size_t)grp * RS + tap) * cg + (ic_l & (cg - 1))) * cg + (oc_l & (cg - 1))];
     }
     u.b[b] = w;
   }
   *reinterpret_cast<int4*>(frags + (size_t)frag * QG_FRAG_BYTES + lane * 16) = u.v;
+}
+
+// Conv weights [G][RS][Cg][Og] -> [Cout][RS][Cg4] (Cg4 = Cg rounded up to 4, zero filled): the input channels of
+// one (output channel, tap) are consecutive bytes, whole dwords, the operand shape of v_dot4_i32_i8.  One thread
+// per byte of the result.
+__global__ void qg_pack_conv_w_any_kernel(const int8_t* __restrict__ W, int G, int RS, int Cg, int Og, int Cg4,
+                                          int8_t* __restrict__ packed) {
+  const long long total = (long long)G * Og * RS * Cg4;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    const int ci = (int)(i % Cg4);
+    const int tap = (int)((i / Cg4) % RS);
+    const int oc = (int)(i / ((long long)Cg4 * RS));
+    const int g = oc / Og, co = oc - g * Og;
+    packed[i] = ci < Cg ? W[(((size_t)g * RS + tap) * Cg + ci) * Og + co] : (int8_t)0;
+  }
+}
+// Folded offsets of the general layout: col_off[oc] = sum of the output channel's weights - R*S*Cg * theta_B[oc]
+__global__ void qg_conv_any_offsets_kernel(const int8_t* __restrict__ packed, int Cout, int RS, int Cg, int Cg4,
+                                           int32_t* __restrict__ col_off, const int32_t* __restrict__ bzp) {
+  const int oc = blockIdx.x * blockDim.x + threadIdx.x;
+  if (oc >= Cout) return;
+  const int8_t* w = packed + (size_t)oc * RS * Cg4;
+  int sum = 0;
+  for (int i = 0; i < RS * Cg4; ++i) sum += w[i];
+  col_off[oc] = sum - RS * Cg * bzp[oc];
 }
 
 }  // namespace
@@ -273,7 +300,25 @@ hipError_t qg_launch_pack_conv_w(const int8_t* W, int G, int RS, int8_t* packed,
   if (mfma_frags != nullptr) {  // C = 4 G is a multiple of 32
     const int nfrag = (G / 8) * RS;
     hipLaunchKernelGGL(qg_pack_conv_w_mfma_kernel, dim3((nfrag * 64 + 255) / 256), dim3(256), 0, s, W, RS,
-                       nfrag, mfma_frags);
+                       nfrag, 2, mfma_frags);
+  }
+  return hipGetLastError();
+}
+
+// any group shape: the general layout, its folded offsets and, when lcg >= 0 (Cg == Og == 1 << lcg, C a multiple of
+// 32), the matrix-core fragments
+hipError_t qg_launch_pack_conv_w_any(const int8_t* W, int G, int RS, int Cg, int Og, int8_t* packed, int32_t* col_off,
+                                     const int32_t* bzp_dev, int8_t* mfma_frags, int lcg, hipStream_t s) {
+  const int Cg4 = (Cg + 3) / 4 * 4, Cout = G * Og;
+  const long long total = (long long)Cout * RS * Cg4;
+  const unsigned blocks = (unsigned)((total + 255) / 256 < 65535 ? (total + 255) / 256 : 65535);
+  hipLaunchKernelGGL(qg_pack_conv_w_any_kernel, dim3(blocks), dim3(256), 0, s, W, G, RS, Cg, Og, Cg4, packed);
+  hipLaunchKernelGGL(qg_conv_any_offsets_kernel, dim3((Cout + 63) / 64), dim3(64), 0, s, packed, Cout, RS, Cg, Cg4, col_off,
+                     bzp_dev);
+  if (mfma_frags != nullptr) {
+    const int nfrag = (G * Cg / 32) * RS;
+    hipLaunchKernelGGL(qg_pack_conv_w_mfma_kernel, dim3((nfrag * 64 + 255) / 256), dim3(256), 0, s, W, RS, nfrag, lcg,
+                       mfma_frags);
   }
   return hipGetLastError();
 }

@@ -80,7 +80,11 @@ struct qg_packed_b {
   const int32_t* bzp;     // device: per-column theta_B (inside the col_offsets buffer)
   // conv only
   int G, R, S, Cg, Og;
-  const int8_t* conv_frags;  // device: matrix-core layout of the conv weights, or null (C % 32 != 0)
+  const int8_t* conv_frags;  // device: matrix-core layout of the conv weights, or null (no such layout for these extents)
+  const int8_t* conv_any;    // device: [Cout][R*S][Cg rounded up to 4] layout of the general kernel, or null (4 -> 4 groups)
+  const int8_t* conv_gemm;   // device: one packed (R*S*Cg) x Og GEMM matrix per group (groups of a multiple of 16 channels), or null
+  const int32_t* conv_gemm_off;  // device: per group [N_pad col_offsets][N_pad theta_B]
+  int conv_gemm_kpad, conv_gemm_npad;
   // outlier split only
   int split;                 // packed holds 4-bit B', the sparse part is below
   const int32_t* frag_ptr;   // device: nbucket + 1 offsets into entries
@@ -126,6 +130,7 @@ struct qg_gemm_args {
   int sp_total;               // outlier split: number of entries (the buffer holds at least one)
   // dense convolution through the tiled kernel (A = NHWC image, rows = output pixels, K = (kh, kw, ci)):
   int cv_H, cv_W, cv_Cin, cv_Ho, cv_Wo, cv_R, cv_S, cv_stride, cv_pad;
+  int cv_pix;  // bytes per pixel of the image (>= cv_Cin: the channels may be a slice of wider pixels, a group)
   int cv_azp;                 // theta_A: what a tap outside the image reads as
   int cv_in_bytes;            // size of the image buffer
 };
@@ -134,12 +139,15 @@ struct qg_conv_args {
   const uint8_t* in;
   const int8_t* Wp;
   const int8_t* Wfrag;  // matrix-core layout, or null
+  const int8_t* Wany;   // general layout [Cout][R*S][Cg4], or null
   const int32_t* col_off;
   const int32_t* bzp;
   const int32_t* bias;
   const float* scales;
   uint8_t* out;
   int Nb, H, W, C, Ho, Wo, Cout, G;
+  int Cg, Og, R, S;   // channels per group in / out, filter extents
+  int lcg;            // log2(Cg) when the matrix-core layout is used (Cg == Og in {4, 8, 16, 32})
   int pad, stride;
   int scale_stride;
   int a_zp;       // theta_A
@@ -261,6 +269,8 @@ hipError_t qg_launch_pack_b_split_fill(const int8_t* B, int K, int N, int ldb, i
                                        int32_t* cursor, int32_t* entries, hipStream_t s);
 hipError_t qg_launch_pack_conv_w(const int8_t* W, int G, int RS, int8_t* packed, int32_t* col_off,
                                  const int32_t* bzp_dev, int8_t* mfma_frags, hipStream_t s);
+hipError_t qg_launch_pack_conv_w_any(const int8_t* W, int G, int RS, int Cg, int Og, int8_t* packed, int32_t* col_off,
+                                     const int32_t* bzp_dev, int8_t* mfma_frags, int lcg, hipStream_t s);
 // `kernel` is one of the QG_KERNEL_* ids of qgemm.h (never QG_KERNEL_AUTO: selection happens in api.hip)
 hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, int kernel, hipStream_t s);
 // kernel: QG_KERNEL_TILE64 / TILE64K4 / TILE64K1 / TILE128 / TILE128X256

@@ -66,8 +66,16 @@ def test_size_query_rejects_bad_arguments(lib):
     assert lib.qg_pack_b_sizes(4, 4, None, ctypes.byref(cb)) == q.ENULL
     assert lib.qg_pack_conv_w_sizes(32, 3, 3, 4, 4, ctypes.byref(pb), ctypes.byref(cb)) == q.OK
     assert pb.value >= 32 * 36 * 4
-    assert lib.qg_pack_conv_w_sizes(32, 3, 3, 8, 4, ctypes.byref(pb), ctypes.byref(cb)) == q.EUNSUPPORTED
-    assert lib.qg_pack_conv_w_sizes(32, 5, 5, 4, 4, ctypes.byref(pb), ctypes.byref(cb)) == q.EUNSUPPORTED
+    # any group shape: [Cout][R*S][Cg rounded up to 4] bytes, plus block-diagonal tiles where they exist
+    assert lib.qg_pack_conv_w_sizes(32, 3, 3, 8, 4, ctypes.byref(pb), ctypes.byref(cb)) == q.OK
+    assert pb.value == 32 * 4 * 9 * 8 and cb.value >= 2 * 128 * 4
+    assert lib.qg_pack_conv_w_sizes(32, 5, 5, 4, 4, ctypes.byref(pb), ctypes.byref(cb)) == q.OK
+    assert pb.value == 32 * 4 * 25 * 4
+    assert lib.qg_pack_conv_w_sizes(8, 3, 3, 8, 8, ctypes.byref(pb), ctypes.byref(cb)) == q.OK
+    assert pb.value == 64 * 9 * 8 + 2 * 9 * 1024            # 64 channels: two 32-channel blocks of nine tiles
+    assert lib.qg_pack_conv_w_sizes(3, 2, 5, 3, 7, ctypes.byref(pb), ctypes.byref(cb)) == q.OK
+    assert pb.value == (21 * 10 * 4 + 255) // 256 * 256
+    assert lib.qg_pack_conv_w_sizes(1, 64, 64, 16, 4, ctypes.byref(pb), ctypes.byref(cb)) == q.EINVAL   # K beyond the bound
     assert lib.qg_pack_conv_w_sizes(0, 3, 3, 4, 4, ctypes.byref(pb), ctypes.byref(cb)) == q.EINVAL
 
 
