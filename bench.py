@@ -89,6 +89,20 @@ def time_graph(torch, calls, reps, spin_ms):
     return ev0.elapsed_time(ev1) / (reps * len(calls))
 
 
+class _Call:
+    """A plain callable as a Prepared*-like object for time_graph (the binding's wrappers take the stream that is
+    current when they are called, so they can be captured as they are)."""
+
+    def __init__(self, fn):
+        self.fn = fn
+
+    def rebind(self):
+        return self
+
+    def launch(self):
+        self.fn()
+
+
 def load_probes():
     """bench.py's own measurement probes (bench_probes.hip, built by __graft_entry__.build())."""
     import ctypes
@@ -490,6 +504,49 @@ def main():
                 del bps, outs, calls
             nxt["outlier_split"].append(rec)
 
+        # K split across workgroups (few columns, long K) and the four-wave streaming form (many columns): the same
+        # call without and with the workspace / against the 16-wave row block it replaces; cold weights
+        nxt["small_batch_forms"] = []
+        for (Ms, Ns, Ks) in [(16, 64, 32768), (16, 16, 32768), (64, 64, 16384), (16, 8192, 8192), (80, 1536, 2048)]:
+            Bs = up(wl.random_gemm(50, 4, Ns, Ks).B)
+            As = torch.randint(0, 256, (Ms, Ks), dtype=torch.uint8, device=dev)
+            scs = torch.full((1,), 2.0 ** -9, dtype=torch.float32, device=dev)
+            ncopy = max(4, min(72, int(1.2e9 // (Ks * Ns))))
+            bps = [q.pack_b(Bs, [3]) for _ in range(ncopy)]
+            outs = [torch.empty((Ms, Ns), dtype=torch.uint8, device=dev) for _ in range(ncopy)]
+            ws = q.gemm_workspace(Ms, bps[0])
+            rec = {"M": Ms, "N": Ns, "K": Ks, "split_factor": q.gemm_splitk_factor(Ms, bps[0])}
+            plain = [q.PreparedGemm(As, 128, bps[i], None, scs, 128, False, outs[i]) for i in range(ncopy)]
+            _, t = time_calls(torch, lambda i: plain[i % ncopy].launch(), 4 * ncopy, ncopy, spin_ms=SPIN_MS)
+            rec["no_workspace_cold_us"] = round(t * 1e3, 2)
+            ref = outs[0].clone()
+            if ws is not None:
+                split = [q.PreparedGemm(As, 128, bps[i], None, scs, 128, False, outs[i], workspace=ws) for i in range(ncopy)]
+                _, t = time_calls(torch, lambda i: split[i % ncopy].launch(), 4 * ncopy, ncopy, spin_ms=SPIN_MS)
+                rec["with_workspace_cold_us"] = round(t * 1e3, 2)
+                rec["same_bytes"] = bool(torch.equal(outs[0], ref))
+                del split
+            rec["kernel"] = q.kernel_names()[q.kernel_select(Ms, Ns, Ks)]
+            rec["weights_GBps_best"] = round(Ks * Ns / (min(v for k, v in rec.items() if k.endswith("_cold_us")) * 1e-6) / 1e9, 1)
+            nxt["small_batch_forms"].append(rec)
+            del bps, outs, plain
+        # fp32 activations on a streaming kernel: quantize pass + GEMM (two launches, workspace) against the staging that
+        # converts (one launch, no workspace)
+        c2f = wl.config2_small_batch_fc()
+        Bp2f = q.pack_b(up(c2f.B), c2f.b_zp)
+        Af2 = torch.rand((c2f.M, c2f.K), dtype=torch.float32, device=dev) * 12.0 - 4.0
+        sc2f = up(c2f.scales)
+        C2f = torch.empty((c2f.M, c2f.N), dtype=torch.uint8, device=dev)
+        ws2f = torch.empty(q.gemm_f32_workspace_bytes(c2f.M, Bp2f), dtype=torch.uint8, device=dev)
+        two = time_graph(torch, [_Call(lambda: q.gemm_f32s8_requant(Af2, 1.0 / 0.05, 80, Bp2f, None, sc2f, c2f.c_zp, True, out=C2f,
+                                                                    workspace=ws2f, kernel="skinny16"))] * 50, 5, SPIN_MS)
+        ref2f = C2f.clone()
+        one = time_graph(torch, [_Call(lambda: q.gemm_f32s8_requant(Af2, 1.0 / 0.05, 80, Bp2f, None, sc2f, c2f.c_zp, True, out=C2f,
+                                                                    workspace=q.NO_WORKSPACE, kernel="skinny16"))] * 50, 5, SPIN_MS)
+        nxt["fp32_ends"]["f32_in_u8_out_16x4096x4096"] = {"two_launches_us": round(two * 1e3, 2), "fused_one_launch_us": round(one * 1e3, 2),
+                                                          "same_bytes": bool(torch.equal(C2f, ref2f)), "timing": "graph replay, warm"}
+        del Af2, C2f, ws2f, Bp2f
+
         # dense convolution with fused im2col: 3 x 3 layers of a ResNet-like network at batch 32
         nxt["dense_conv"] = []
         for (Hc, Cc) in [(56, 64), (28, 128), (14, 256)]:
@@ -505,6 +562,34 @@ def main():
                                       "TOPS": round(oc / (cms * 1e-3) / 1e12, 1),
                                       "GBps": round(nbc / (cms * 1e-3) / 1e9, 1)})
             del xin, yout, Wd
+        # the hand-scheduled convolution loop against the GEMM of the same extents, and a channel count that is not
+        # a multiple of 64 (graph replay: the kernels alone)
+        for (Nbc, Hc, Cc) in [(8, 56, 128), (8, 56, 96)]:
+            cc = wl.random_conv(60 + Cc, Nb=Nbc, H=Hc, W=Hc, C=Cc, G=1, Cout=Cc)
+            Wd = q.pack_conv_dense_w(up(np.ascontiguousarray(cc.wgt[0])), cc.b_zp)
+            xin, scd, bd = up(cc.inp), up(cc.scales), up(cc.bias)
+            yout = torch.empty((Nbc, Hc, Hc, Cc), dtype=torch.uint8, device=dev)
+            Mg, Kg = Nbc * Hc * Hc, 9 * Cc
+            Ag = torch.randint(0, 256, (Mg, Kg), dtype=torch.uint8, device=dev)
+            Cg_ = torch.empty((Mg, Cc), dtype=torch.uint8, device=dev)
+            cus = time_graph(torch, [q.PreparedConvDense(xin, Wd, cc.a_zp, bd, scd, cc.c_zp, False, 1, 1, yout)] * 50, 5, SPIN_MS) * 1e3
+            gus = time_graph(torch, [q.PreparedGemm(Ag, cc.a_zp, Wd, bd, scd, cc.c_zp, False, Cg_)] * 50, 5, SPIN_MS) * 1e3
+            nxt["dense_conv"].append({"shape": f"{Nbc}x{Hc}x{Hc}x{Cc}->{Cc}, 3x3 s1 p1", "us": round(cus, 2),
+                                      "gemm_same_extents_us": round(gus, 2), "M": Mg, "N": Cc, "K": Kg})
+            del xin, yout, Wd, Ag, Cg_
+        # group-wise convolution beyond 4 -> 4 channels per group
+        nxt["group_conv_shapes"] = []
+        for cfg in [dict(Nb=32, H=56, W=56, C=256, G=32), dict(Nb=32, H=28, W=28, C=512, G=32), dict(Nb=32, H=14, W=14, C=1024, G=32),
+                    dict(Nb=8, H=56, W=56, C=128, G=2)]:
+            cg = wl.random_conv(70, **cfg)
+            Wg = q.pack_conv_w(up(cg.wgt), cg.b_zp)
+            xin, scg, bg = up(cg.inp), up(cg.scales), up(cg.bias)
+            yout = torch.empty_like(xin)
+            gms = time_graph(torch, [q.PreparedConv(xin, Wg, cg.a_zp, bg, scg, cg.c_zp, False, 1, 1, yout)] * 20, 5, SPIN_MS)
+            nxt["group_conv_shapes"].append({"shape": f"{cfg['Nb']}x{cfg['H']}x{cfg['W']}x{cfg['C']}, {cfg['G']} groups of "
+                                                      f"{cfg['C'] // cfg['G']}->{cfg['C'] // cfg['G']}, 3x3 s1 p1",
+                                             "us": round(gms * 1e3, 2), "GBps": round(2 * xin.numel() / (gms * 1e-3) / 1e9, 1)})
+            del xin, yout, Wg
 
     out = {
         "metric": "int8 GEMM+requant TOPS at M=N=K=8192", "value": round(tops, 2), "unit": "TOPS",

@@ -382,6 +382,30 @@ class PreparedConv:
         return self
 
 
+class PreparedConvDense:
+    """Same for qg_conv_dense_u8s8_requant (Wp from pack_conv_dense_w)."""
+
+    def __init__(self, inp, Wp, a_zp, bias, scales, c_zp, relu, pad, stride, out, kernel=KERNEL_AUTO):
+        assert inp.is_cuda and inp.dtype == torch.uint8 and inp.dim() == 4 and inp.is_contiguous()
+        assert out.is_cuda and out.dtype == torch.uint8 and out.is_contiguous()
+        Nb, H, W, C = inp.shape
+        self._keep = (inp, Wp, bias, scales, out)
+        self._p = _params(a_zp, bias, scales, c_zp, relu)
+        self._args = (inp.data_ptr(), Nb, H, W, C, Wp.R, Wp.S, pad, stride, Wp.handle, ctypes.byref(self._p), out.data_ptr(),
+                      _stream(), kernel_id(kernel))
+        self.out = out
+
+    def launch(self):
+        rc = lib.qg_conv_dense_u8s8_requant(*self._args)
+        if rc != OK:
+            raise QGemmError(rc, "qg_conv_dense_u8s8_requant")
+
+    def rebind(self):
+        """Later launches go to the stream that is current now (e.g. the capturing stream of a graph)."""
+        self._args = self._args[:12] + (_stream(),) + self._args[13:]
+        return self
+
+
 def gemm_u8s8_acc32(A, Bp, want_rowsum=False, kernel=KERNEL_AUTO):
     assert A.is_cuda and A.dtype == torch.uint8 and A.dim() == 2 and A.stride(1) == 1
     M = A.shape[0]
