@@ -420,8 +420,8 @@ int qg_conv_groupwise_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W,
  *   in_nhwc  dev uint8 [Nb][H][W][Cin], 16-byte aligned;  Cin % 16 == 0
  *   out_nhwc dev uint8 [Nb][Ho][Wo][Cout], Ho = (H + 2*pad - R)/stride + 1
  *   kernel   QG_KERNEL_AUTO (chosen from the extents by a cost model fitted to 3 x 3 and
- *            5 x 5 layers), or QG_KERNEL_TILE64 / TILE64K4 / TILE64K1 / TILE128 /
- *            TILE128X256; every choice gives the same bytes.  The 128-row tiles run
+ *            5 x 5 layers), or QG_KERNEL_TILE64 / TILE64K4 / TILE64X32K8 / TILE64K1 /
+ *            TILE128 / TILE128X256; every choice gives the same bytes.  The 128-row tiles run
  *            their hand-scheduled loop when Cin % 64 == 0, R*S <= 32 and K >= 256.
  * QG_EUNSUPPORTED for other channel counts, an unaligned image or another kernel id;
  * QG_EINVAL when R*S*Cin differs from the K of Wp or the id is unknown. */

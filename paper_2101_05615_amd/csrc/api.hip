@@ -84,14 +84,15 @@ const tile_cost k_tile_cost[] = {
 };
 // The dense convolution runs the same tile loops with the im2col addressing folded into the requests; the same
 // formula, constants fitted to 56 layers (3 x 3 and 5 x 5, stride 1 and 2, 1 .. 32 images, Cin % 64 == 0; graph-replay
-// times): the choice is within 5 % of the measured best on 53 of them, worst 1.08x.  The 64 x 64 tile comes without a
-// K split, and with two or four wave sets that share K.
+// times): the choice is within 5 % of the measured best on 54 of them, worst 1.07x.  The 64 x 64 tile comes without a
+// K split and with two or four wave sets that share K, the 64 x 32 tile with eight.
 const tile_cost k_conv_cost[] = {
-    {QG_KERNEL_TILE64K1, 64, 64, 3.04, 0.316, 0.169, 0.178},
-    {QG_KERNEL_TILE64, 64, 64, 4.06, 0.162, 0.114, 1.24},
-    {QG_KERNEL_TILE64K4, 64, 64, 5.45, 0.115, 0.114, 3.7},
-    {QG_KERNEL_TILE128, 128, 128, 5.53, 0.284, 0.249, 1.93},
-    {QG_KERNEL_TILE128X256, 128, 256, 10.5, 0.267, 0.363, 3.82},
+    {QG_KERNEL_TILE64K1, 64, 64, 2.55, 0.412, 0.136, 0.432},
+    {QG_KERNEL_TILE64, 64, 64, 3.95, 0.167, 0.115, 1.24},
+    {QG_KERNEL_TILE64K4, 64, 64, 5.36, 0.118, 0.112, 3.74},
+    {QG_KERNEL_TILE64X32K8, 64, 32, 6.28, 0.0686, 0.0682, 4.43},
+    {QG_KERNEL_TILE128, 128, 128, 5.68, 0.279, 0.229, 2.36},
+    {QG_KERNEL_TILE128X256, 128, 256, 11.1, 0.261, 0.353, 4.01},
 };
 const stream_cost k_stream_cost[] = {
     {QG_KERNEL_SKINNY16, 16, 3.826, 3.664e-06, 5.429, 0.002625},
@@ -922,7 +923,7 @@ int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int
   if (!Wp || ((!in_nhwc || !out_nhwc) && Nb != 0)) return QG_ENULL;
   if (Wp->kind != QG_KIND_GEMM || Wp->version != QG_LAYOUT_VERSION) return QG_EINVAL;
   if (kernel < QG_KERNEL_AUTO || kernel > QG_KERNEL_LAST) return QG_EINVAL;
-  if (kernel != QG_KERNEL_AUTO && kernel != QG_KERNEL_TILE64 && kernel != QG_KERNEL_TILE64K4 &&
+  if (kernel != QG_KERNEL_AUTO && kernel != QG_KERNEL_TILE64 && kernel != QG_KERNEL_TILE64K4 && kernel != QG_KERNEL_TILE64X32K8 &&
       kernel != QG_KERNEL_TILE64K1 && kernel != QG_KERNEL_TILE128 && kernel != QG_KERNEL_TILE128X256)
     return QG_EUNSUPPORTED;
   if (Nb < 0 || H <= 0 || W <= 0 || Cin <= 0 || R <= 0 || S <= 0 || pad < 0 || stride <= 0) return QG_EINVAL;

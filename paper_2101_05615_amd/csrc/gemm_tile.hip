@@ -774,6 +774,7 @@ hipError_t qg_launch_conv_dense(const qg_gemm_args& a, int kernel, hipStream_t s
     case QG_KERNEL_TILE64K1: return launch_conv<2, 2, 1, 1>(a, s);
     case QG_KERNEL_TILE64: return launch_conv<2, 2, 1, 1, 2>(a, s);
     case QG_KERNEL_TILE64K4: return launch_conv<2, 2, 1, 1, 4>(a, s);
+    case QG_KERNEL_TILE64X32K8: return launch_conv<2, 1, 1, 1, 8>(a, s);
     case QG_KERNEL_TILE128: return launch_conv<2, 2, 2, 2>(a, s);
     case QG_KERNEL_TILE128X256: return launch_conv<2, 2, 2, 4>(a, s);
     default: return hipErrorInvalidValue;

@@ -21,7 +21,7 @@ def env():
     return q, torch, torch.device("cuda:0"), oracle
 
 
-CONV_KERNELS = ["auto", "tile64k1", "tile64", "tile64k4", "tile128", "tile128x256"]
+CONV_KERNELS = ["auto", "tile64k1", "tile64", "tile64k4", "tile64x32k8", "tile128", "tile128x256"]
 
 
 def run(c, q, torch, dev, kernel="auto"):
