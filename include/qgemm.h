@@ -422,8 +422,10 @@ int qg_conv_groupwise_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W,
  *   kernel   QG_KERNEL_AUTO (chosen from the extents by a cost model fitted to 3 x 3 and
  *            5 x 5 layers), or QG_KERNEL_TILE64 / TILE64K4 / TILE64X32K8 / TILE64K1 /
  *            TILE128 / TILE128X256; every choice gives the same bytes.  The 128-row tiles run
- *            their hand-scheduled loop when Cin % 64 == 0, R*S <= 32 and K >= 256.
- * QG_EUNSUPPORTED for other channel counts, an unaligned image or another kernel id;
+ *            their hand-scheduled loop when Cin % 64 == 0, R*S <= 32 and K >= 256.  With
+ *            Cin % 64 == 0 and R*S <= 32 the streaming kernels QG_KERNEL_SKINNY16 / 32 / 64
+ *            are taken too (few output pixels and a long K; QG_EUNSUPPORTED otherwise).
+ * QG_EUNSUPPORTED for other channel counts, an unaligned image or QG_KERNEL_TILE256;
  * QG_EINVAL when R*S*Cin differs from the K of Wp or the id is unknown. */
 int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int Cin, int R, int S,
                                int pad, int stride, const qg_packed_b* Wp, const qg_requant_params* p,

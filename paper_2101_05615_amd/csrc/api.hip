@@ -155,6 +155,9 @@ const stream_cost k_stream_cost_16wave[] = {
     {QG_KERNEL_SKINNY32, 32, 4.13, 1.99e-4, 10.33, 1.28e-3},
     {QG_KERNEL_SKINNY64, 64, 4.96, 3.88e-4, 14.26, 2.23e-3},
 };
+// what the convolution's per-lane tap addressing adds to the 16-row streaming kernel's GEMM time (measured)
+const double k_conv_stream_factor = 1.4;
+
 int select_stream_kernel(int M, int N, int K) {
   int best = QG_KERNEL_SKINNY64;
   double best_us = 1e300;
@@ -904,13 +907,31 @@ int launch_conv_gemm(const uint8_t* in, int in_bytes, int Nb, int H, int W, int 
   a.cv_pad = pad;
   a.cv_azp = p->a_zp;
   a.cv_in_bytes = in_bytes;
-  // the tiled kernels, chosen by the same cost formula as a GEMM's
+  // the tiled kernels, chosen by the same cost formula as a GEMM's; few pixels and a long K go to the 16-row streaming
+  // kernel where it applies (whole 64-channel slices, at most 32 taps), priced with the GEMM's formula for that kernel
+  // plus what the convolution's requests were measured to add
+  const bool stream_ok = Cin % QG_FRAG_K == 0 && R * S <= 32;
   if (kernel == QG_KERNEL_AUTO) {
     double best_us = 1e300;
     for (const tile_cost& c : k_conv_cost) {
       const double us = tile_estimate(c, a.M, a.N, a.K);
       if (us < best_us) best_us = us, kernel = c.kernel;
     }
+    if (stream_ok)
+      for (const stream_cost& c : k_stream_cost_16wave) {
+        const double us = k_conv_stream_factor * stream_estimate(c, a.M, a.N, a.K, false);
+        if (ceil_div(a.M, c.rows) <= 65535 && us < best_us) best_us = us, kernel = c.kernel;
+      }
+  }
+  if (kernel <= QG_KERNEL_SKINNY64) {
+    if (!stream_ok) return QG_EUNSUPPORTED;
+    a.ksplit = 1;
+    a.ks_per = a.kb64;
+    a.a_vec = 1;
+    a.c_vec = aligned(out, 4) && (ldc % 4 == 0);
+    a.c_wt = (long long)a.M * N <= (1 << 18);
+    const hipError_t e = qg_launch_conv_skinny(a, kernel, stream);
+    return e == hipSuccess ? QG_OK : QG_ELAUNCH;
   }
   const hipError_t e = qg_launch_conv_dense(a, kernel, stream);
   return e == hipSuccess ? QG_OK : QG_ELAUNCH;
@@ -923,9 +944,7 @@ int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int
   if (!Wp || ((!in_nhwc || !out_nhwc) && Nb != 0)) return QG_ENULL;
   if (Wp->kind != QG_KIND_GEMM || Wp->version != QG_LAYOUT_VERSION) return QG_EINVAL;
   if (kernel < QG_KERNEL_AUTO || kernel > QG_KERNEL_LAST) return QG_EINVAL;
-  if (kernel != QG_KERNEL_AUTO && kernel != QG_KERNEL_TILE64 && kernel != QG_KERNEL_TILE64K4 && kernel != QG_KERNEL_TILE64X32K8 &&
-      kernel != QG_KERNEL_TILE64K1 && kernel != QG_KERNEL_TILE128 && kernel != QG_KERNEL_TILE128X256)
-    return QG_EUNSUPPORTED;
+  if (kernel == QG_KERNEL_TILE256) return QG_EUNSUPPORTED;
   if (Nb < 0 || H <= 0 || W <= 0 || Cin <= 0 || R <= 0 || S <= 0 || pad < 0 || stride <= 0) return QG_EINVAL;
   if ((long long)R * S * Cin != Wp->K) return QG_EINVAL;
   int rc = check_requant(p, Wp->N);

@@ -57,6 +57,11 @@ __device__ __forceinline__ void request_a(const uint8_t* a_base, unsigned voff, 
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(a_base) : "memory");
 }
 
+// The same with a 64-bit per-lane address (the convolution's requests go to the image or to a table row).
+__device__ __forceinline__ void request_a64(const uint8_t* addr, unsigned lds) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds), "v"(addr) : "memory");
+}
+
 // Explicit wait: at most LEFT vector-memory operations of this wave still in flight (they complete in order).
 // The compiler's own bookkeeping does not see the activation requests (they are issued by request_a), so the
 // waits that order LDS reads behind them are written out.
@@ -78,7 +83,16 @@ __device__ __forceinline__ void wait_vm() {
 // A; Eq. (1) solved for the quantized value, the fixed sequence of the stand-alone quantization pass): the lanes load
 // 16 floats per 16-byte chunk of the staged block, convert and write the chunk to LDS, where row offsets and
 // fragments are taken from it as from any uint8 block.  A then points to floats and lda counts floats.
-template <int MODE, int MB, int NWAVES, int BATCH, bool B4, bool ANYALIGN, bool SIMPLE = false, int CPW = 1, bool AF32 = false>
+// ACONV: the rows are the output pixels of a dense convolution and A is its NHWC image (the paper names convolution in
+// Sec. 1; im2col folded into the requests as in the tiled kernels): the K = R*S*Cin bytes of a row are R*S runs of
+// Cin channels (Cin a multiple of 64, so every 64-deep k block lies inside one filter tap), and the 16-byte chunk a
+// lane requests comes from its pixel at that tap, or from a constant row of theta_A bytes when the tap lies outside
+// the image (a k block past K: of 0x80 bytes, the K padding).  A request here covers ONE k block for 16 rows (lane =
+// row, 16-byte piece of the block), so the tap of a request is wave-uniform and lives on the scalar unit, moved on
+// block by block; a lane carries its pixel's byte offset and one validity bit per tap (R*S <= 32) per row block.
+// The staged batch is therefore laid out [k block][row block][16 rows][64 bytes] instead of whole row segments.
+template <int MODE, int MB, int NWAVES, int BATCH, bool B4, bool ANYALIGN, bool SIMPLE = false, int CPW = 1, bool AF32 = false,
+          bool ACONV = false>
 __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8_t* A, const int8_t* Bp, const int M, const int N, const int K, const int kb64,
                                                                    const int nb16_total, const int lda, const int ks_per, const int ksplit,
                                                                    const qg_gemm_args p) {
@@ -88,6 +102,7 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
   static_assert(!SIMPLE || (!B4 && !ANYALIGN), "the straight-line variant takes dense 8-bit weights and aligned rows");
   static_assert(CPW == 1 || SIMPLE, "several fragment columns per wave: straight-line variant only");
   static_assert(!AF32 || (!SIMPLE && !B4 && ANYALIGN), "fp32 activations: the lane-copied staging of the general variant");
+  static_assert(!ACONV || (!SIMPLE && !B4 && !ANYALIGN && !AF32), "convolution: the requested staging of the general variant");
   static_assert(MB * CPW <= NWAVES && CPW <= BATCH, "one wave per (row block, fragment column) runs the output pipeline");
   const bool a_vec = ANYALIGN || p.a_vec;  // whole 16-byte chunks may be moved as such
   using chunk_t = typename std::conditional<ANYALIGN, qg_v4i_unaligned, v4i>::type;
@@ -179,6 +194,33 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
   // request address is a wave-uniform base plus a register that is never the target of a load, so issuing
   // the requests never has to wait for loads in flight
   unsigned a_off[NREQ];
+  // ACONV: of the piece a lane requests for row block mb: byte offset of its pixel at tap (0, 0), channel slice 0 (may
+  // be negative) and the taps of that pixel that lie inside the image; wave-uniform: the tap of the next k block
+  int cv_pix[MB];
+  unsigned cv_mask[MB];
+  int cv_cc = 0, cv_kw = 0, cv_kh = 0;
+  const int cv_nc = ACONV ? p.cv_Cin / QG_FRAG_K : 1;  // k blocks per tap
+  const uint8_t* const cv_azp_row = qg_byte_rows.b[ACONV ? p.cv_azp : 0];
+  if (ACONV) {
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      const int r = mb * 16 + (lane >> 2);
+      const int m = min(m_base + r, M - 1);
+      const int wo = m % p.cv_Wo, t = m / p.cv_Wo;
+      const int ho = t % p.cv_Ho, n = t / p.cv_Ho;
+      const int h0 = ho * p.cv_stride - p.cv_pad, w0 = wo * p.cv_stride - p.cv_pad;
+      // the lane's 16 bytes land at piece lane % 4 of its row's 64-byte block; that place holds logical piece (lane % 4) ^ (row / 4 % 4)
+      cv_pix[mb] = ((n * p.cv_H + h0) * p.cv_W + w0) * p.cv_pix + ((((lane & 3) ^ (lane >> 4)) & 3) << 4);
+      cv_mask[mb] = 0;
+      for (int kh = 0, tap = 0; kh < p.cv_R; ++kh)
+        for (int kw = 0; kw < p.cv_S; ++kw, ++tap)
+          if ((unsigned)(h0 + kh) < (unsigned)p.cv_H && (unsigned)(w0 + kw) < (unsigned)p.cv_W) cv_mask[mb] |= 1u << tap;
+    }
+    const int tap = kb_begin / cv_nc;
+    cv_cc = kb_begin - tap * cv_nc;
+    cv_kh = tap / p.cv_S;
+    cv_kw = tap - cv_kh * p.cv_S;
+  }
 #pragma unroll
   for (int jj = 0; jj < NREQ; ++jj) {
     const int r = jj * RPR + lane / NCHUNK;
@@ -213,7 +255,7 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
     constexpr bool FIRST = decltype(first_tag)::value;
     // whole rows of BATCH k blocks are requested even when the slice ends earlier: the surplus lies inside the
     // row (it is the next wave's slice) and is simply not consumed
-    const bool staged = !AF32 && a_vec && (kb + BATCH) * QG_FRAG_K <= K;
+    const bool staged = ACONV || (!AF32 && a_vec && (kb + BATCH) * QG_FRAG_K <= K);
     unsigned char* region = smem + wave * REGION;
     // outlier split: this batch's entries are one run; the first 64 are requested one per lane right behind the
     // activations (always exactly one request, clamped into the buffer, so that the wait below can count it)
@@ -232,6 +274,24 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
       // row r stored at chunk c ^ r so that the operand-order reads below are bank-conflict free
       const uint8_t* a_base = A + (size_t)kb * QG_FRAG_K;  // wave-uniform
       const unsigned region_lds = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)region);
+      if (ACONV) {
+#pragma unroll
+        for (int j = 0; j < BATCH; ++j) {
+          // (wave-uniform) a k block past K -- the zero padding of the packed weights -- is staged as 0x80 bytes like
+          // all K padding, a tap outside the image as theta_A bytes
+          const bool in_k = cv_kh < p.cv_R;
+          const unsigned tapbit = in_k ? 1u << (cv_kh * p.cv_S + cv_kw) : 0u;
+          const int toff = (cv_kh * p.cv_W + cv_kw) * p.cv_pix + cv_cc * QG_FRAG_K;
+          const uint8_t* const other = in_k ? cv_azp_row : qg_byte_rows.b[128];
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb)
+            request_a64((cv_mask[mb] & tapbit) != 0 ? A + (cv_pix[mb] + toff) : other, region_lds + (j * MB + mb) * 1024);
+          if (++cv_cc == cv_nc) {
+            cv_cc = 0;
+            if (++cv_kw == p.cv_S) cv_kw = 0, ++cv_kh;
+          }
+        }
+      } else
 #pragma unroll
       for (int jj = 0; jj < NREQ; ++jj) request_a(a_base, a_off[jj], region_lds + jj * 1024);
       asm volatile("" ::: "memory");
@@ -321,7 +381,10 @@ __global__ __launch_bounds__(NWAVES * 64) void qg_gemm_skinny_kernel(const uint8
 #pragma unroll
       for (int j = 0; j < BATCH; ++j) {
         const int r = mb * 16 + ml;
-        af[mb][j] = *reinterpret_cast<const v4i*>(region + r * ROWB + ((((4 * j + g) ^ r) & (NCHUNK - 1)) << 4));
+        if (ACONV)  // [k block][row block][row][piece ^ (row / 4 % 4)]
+          af[mb][j] = *reinterpret_cast<const v4i*>(region + (j * MB + mb) * 1024 + ml * QG_FRAG_K + (((g ^ (ml >> 2)) & 3) << 4));
+        else
+          af[mb][j] = *reinterpret_cast<const v4i*>(region + r * ROWB + ((((4 * j + g) ^ r) & (NCHUNK - 1)) << 4));
       }
 #pragma unroll
     for (int j = 0; j < BATCH; ++j)
@@ -607,6 +670,22 @@ hipError_t launch_af32(const qg_gemm_args& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// dense convolution (a.cv_* describe it, a.A is the image): the general variant with the convolution's requests
+template <int MB, int NWAVES, int BATCH>
+hipError_t launch_conv(const qg_gemm_args& a, hipStream_t s) {
+  const int part = NWAVES * MB * 64 * (int)sizeof(v4i), stage = NWAVES * (MB * 16) * (BATCH * QG_FRAG_K);
+  const int smem = (stage > part ? stage : part) + NWAVES * MB * 16 * (int)sizeof(int);
+  const int nfrag = ((a.N + 31) / 32) * 2;
+  const int mblocks = (a.M + MB * 16 - 1) / (MB * 16);
+  if (mblocks > 65535) return hipErrorInvalidValue;
+  constexpr auto fn = qg_gemm_skinny_kernel<QG_MODE_REQUANT, MB, NWAVES, BATCH, false, false, false, 1, false, true>;
+  hipError_t e = qg_allow_smem<fn>(smem);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(fn, dim3(nfrag, mblocks, 1), dim3(NWAVES * 64), smem, s, a.A, a.Bp, a.M, a.N, a.K, a.kb64, a.nb16, a.lda,
+                     a.kb64, 1, a);
+  return hipGetLastError();
+}
+
 // waves per workgroup and k blocks a wave requests at once, per row-block height
 template <int MODE, bool B4, bool ANYALIGN>
 hipError_t launch_mb(const qg_gemm_args& a, int kernel, hipStream_t s) {
@@ -626,6 +705,17 @@ hipError_t launch_mode(const qg_gemm_args& a, int mode, int kernel, hipStream_t 
 }
 
 }  // namespace
+
+// Dense convolution on the streaming kernels: few output pixels and a long K.  Cin % 64 == 0, R*S <= 32.
+hipError_t qg_launch_conv_skinny(const qg_gemm_args& a, int kernel, hipStream_t s) {
+  if (a.sp_ptr != nullptr || a.cv_Cin % QG_FRAG_K != 0 || a.cv_R * a.cv_S > 32 || a.ksplit != 1) return hipErrorInvalidValue;
+  switch (kernel) {
+    case QG_KERNEL_SKINNY16: return launch_conv<1, 16, 4>(a, s);
+    case QG_KERNEL_SKINNY32: return launch_conv<2, 16, 4>(a, s);
+    case QG_KERNEL_SKINNY64: return launch_conv<4, 16, 2>(a, s);
+    default: return hipErrorInvalidValue;
+  }
+}
 
 // a.A points to fp32 activations (a.lda in floats, a.q_*: the quantization); mode: QG_MODE_REQUANT or QG_MODE_DEQUANT
 hipError_t qg_launch_gemm_skinny_f32(const qg_gemm_args& a, int mode, int kernel, hipStream_t s) {

@@ -167,20 +167,6 @@ constexpr int min_wg_per_cu(int path, int blocks) {
 // cold trip to memory.
 constexpr int EPI_CLAMP = 0, EPI_SAT = 1, EPI_SAT0 = 2;
 
-// Row v holds 16 bytes of value v: where a convolution's requests go for chunks that are not in the image.  The
-// hand-scheduled loop addresses a row minus 1 KiB with a 32-bit subtraction (its second request carries an
-// instruction offset of 1 KiB): the rows sit 4 KiB into an 8 KiB-aligned object, so that cannot borrow.
-struct alignas(8192) qg_byte_rows_t {
-  uint8_t lead[4096];
-  uint8_t b[256][16];
-};
-constexpr qg_byte_rows_t qg_make_byte_rows() {
-  qg_byte_rows_t r{};
-  for (int v = 0; v < 256; ++v)
-    for (int i = 0; i < 16; ++i) r.b[v][i] = (uint8_t)v;
-  return r;
-}
-__device__ const qg_byte_rows_t qg_byte_rows = qg_make_byte_rows();
 template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, int CONV = 0, int KS = 1, int EPI = EPI_CLAMP>
 __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) / KS) void qg_gemm_tile_kernel(
     const uint8_t* A, const int8_t* Bp, const int M, const int N, const int K, const int nb16_total, const int lda,

@@ -157,6 +157,21 @@ struct qg_conv_args {
 };
 
 #ifdef __HIPCC__
+// Row v holds 16 bytes of value v: where a convolution's requests go for chunks that are not in the image.  The
+// hand-scheduled loop addresses a row minus 1 KiB with a 32-bit subtraction (its second request carries an
+// instruction offset of 1 KiB): the rows sit 4 KiB into an 8 KiB-aligned object, so that cannot borrow.
+struct alignas(8192) qg_byte_rows_t {
+  uint8_t lead[4096];
+  uint8_t b[256][16];
+};
+constexpr qg_byte_rows_t qg_make_byte_rows() {
+  qg_byte_rows_t r{};
+  for (int v = 0; v < 256; ++v)
+    for (int i = 0; i < 16; ++i) r.b[v][i] = (uint8_t)v;
+  return r;
+}
+static __device__ const qg_byte_rows_t qg_byte_rows = qg_make_byte_rows();  // one copy per source file that uses it
+
 typedef int qg_v4i __attribute__((ext_vector_type(4)));
 typedef qg_v4i qg_v4i_unaligned __attribute__((aligned(1)));  // a 16-byte load from any address (one instruction)
 
@@ -277,6 +292,7 @@ hipError_t qg_launch_gemm_tile(const qg_gemm_args& a, int mode, int kernel, hipS
 hipError_t qg_launch_conv_dense(const qg_gemm_args& a, int kernel, hipStream_t s);
 hipError_t qg_launch_gemm_skinny(const qg_gemm_args& a, int mode, int kernel, hipStream_t s);
 hipError_t qg_launch_gemm_skinny_f32(const qg_gemm_args& a, int mode, int kernel, hipStream_t s);
+hipError_t qg_launch_conv_skinny(const qg_gemm_args& a, int kernel, hipStream_t s);
 hipError_t qg_launch_quantize_a(const float* A, int M, int K, int lda, float inv_scale, int a_zp, uint8_t* Aq,
                                 int ldq, hipStream_t s);
 hipError_t qg_launch_conv_group(const qg_conv_args& a, int RS, hipStream_t s);

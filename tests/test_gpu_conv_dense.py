@@ -66,6 +66,9 @@ def test_dense_conv_bit_exact(env, cfg, per_channel, with_bias, relu):
     ref = want(c, oracle)
     for kernel in CONV_KERNELS:
         assert_same(run(c, q, torch, dev, kernel), ref, f"dense conv, kernel {kernel}")
+    if cfg["C"] % 64 == 0 and cfg.get("R", 3) * cfg.get("S", 3) <= 32:   # the streaming kernels' conditions
+        for kernel in ("skinny16", "skinny32", "skinny64"):
+            assert_same(run(c, q, torch, dev, kernel), ref, f"dense conv, kernel {kernel}")
 
 
 def test_dense_conv_zero_weight_zero_points(env):
@@ -115,7 +118,7 @@ def test_dense_conv_errors(env):
     assert L(inp.data_ptr(), 1, 1, 1, 64, 3, 3, 0, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, 0) == q.EINVAL  # filter larger than image
     ok = (inp.data_ptr(), 1, 5, 5, 64, 3, 3, 1, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None)
     assert L(*ok, q.KERNEL_LAST + 1) == q.EINVAL and L(*ok, -1) == q.EINVAL
-    assert L(*ok, q.kernel_id("tile256")) == q.EUNSUPPORTED and L(*ok, q.kernel_id("skinny16")) == q.EUNSUPPORTED
+    assert L(*ok, q.kernel_id("tile256")) == q.EUNSUPPORTED
     torch.cuda.synchronize()
 
 
