@@ -387,8 +387,9 @@ size_t qg_packed_b_nnz(const qg_packed_b* p);
  * Any G, R, S, C/G and Cout/G (R*S*C/G <= QG_MAX_K).  Groups of 4 -> 4 channels
  * with a 1 x 1 or 3 x 3 filter have the kernels this library is tuned for (one
  * dword per tap, or block-diagonal matrix-core tiles when C % 32 == 0); square
- * groups of 8, 16 or 32 channels with those filters and C % 32 == 0 run the same
- * matrix-core kernels on their own block-diagonal tiles; other groups of a
+ * groups of 1 (a depthwise convolution), 2, 8, 16 or 32 channels with those
+ * filters and C % 32 == 0 run the same matrix-core kernels on their own
+ * block-diagonal tiles; other groups of a
  * multiple of 16 input channels (up to 64 groups, 16-byte aligned image) run one
  * dense convolution per group on the group's channel slice; every other shape
  * runs a plain one-thread-per-output kernel (correct for any extents, not tuned). */

@@ -969,11 +969,12 @@ namespace {
 bool conv_is_4to4(int G, int R, int S, int Cg, int Og) {
   return Cg == 4 && Og == 4 && ((R == 1 && S == 1) || (R == 3 && S == 3)) && G <= 256;
 }
-// log2(Cg) when the block-diagonal matrix-core fragments exist for a general group shape (square groups of 8, 16 or 32
-// channels -- or of 4 in more than 256 groups --, 1 x 1 or 3 x 3, whole 32-channel blocks), else -1
+// log2(Cg) when the block-diagonal matrix-core fragments exist for a general group shape (square groups of 1 -- a
+// depthwise convolution --, 2, 8, 16 or 32 channels -- or of 4 in more than 256 groups --, 1 x 1 or 3 x 3, whole
+// 32-channel blocks), else -1
 int conv_mfma_lcg(int G, int R, int S, int Cg, int Og) {
   if (Cg != Og || !((R == 1 && S == 1) || (R == 3 && S == 3)) || (G * Cg) % 32 != 0) return -1;
-  return Cg == 4 ? 2 : Cg == 8 ? 3 : Cg == 16 ? 4 : Cg == 32 ? 5 : -1;
+  return Cg == 1 ? 0 : Cg == 2 ? 1 : Cg == 4 ? 2 : Cg == 8 ? 3 : Cg == 16 ? 4 : Cg == 32 ? 5 : -1;
 }
 // groups of a multiple of 16 channels without block-diagonal tiles: each group is a dense convolution of its own
 // channel slice (one launch per group), with its weights packed as a GEMM matrix

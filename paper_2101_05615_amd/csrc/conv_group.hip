@@ -39,10 +39,29 @@ __device__ __forceinline__ void group_sums(unsigned (&rs)[4], int lcg) {
   rs[0] = rs[1] = rs[2] = rs[3] = t;
 }
 
+// Groups of 1 or 2 channels (depthwise and its neighbour) have no dword of their own to sum bytes over: their row
+// offsets come from the matrix cores too, as the product with the block-diagonal matrix of ONES of the same group
+// structure (RS_MFMA): one more MFMA per tap, on operands that are already in registers, and the sums arrive per
+// output channel, in the int8 domain, padding included.  This lane's 16 bytes of that matrix (the same for every tap):
+__device__ __forceinline__ v4i ones_fragment(int lane, int lcg) {
+  const int oc_l = qg_slot_to_col(lane & 31), g = lane >> 5;
+  v4i f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    unsigned w = 0;
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+      if (((16 * g + 4 * j + b) >> lcg) == (oc_l >> lcg)) w |= 1u << (8 * b);
+    f[j] = (int)w;
+  }
+  return f;
+}
+
 // NCB 32-channel blocks per wave pass; the workgroup (4 waves) shares their weights in LDS and each wave
 // walks over blocks of 32 consecutive output pixels.
-template <int R, int S, int NCB, bool HAS_BZP>
+template <int R, int S, int NCB, bool HAS_BZP, bool RS_MFMA = false>
 __global__ __launch_bounds__(256, HAS_BZP ? 2 : 4) void qg_conv_group_mfma_kernel(const qg_conv_args p) {
+  static_assert(!RS_MFMA || HAS_BZP, "row sums are only needed with a nonzero theta_B");
   constexpr int RS = R * S;
   constexpr int NCH = NCB * 32;
   extern __shared__ __align__(16) unsigned char smem[];  // [cb][tap] 1 KiB fragments, then constants
@@ -72,6 +91,7 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 4) void qg_conv_group_mfma_kerne
   const int nblk = (npix + 31) / 32;
   const unsigned azp_word = (unsigned)p.a_zp * 0x01010101u;
   const float czp_f = (float)p.c_zp;
+  const v4i ones = RS_MFMA ? ones_fragment(lane, p.lcg) : (v4i){0, 0, 0, 0};
 
   for (int blk = blockIdx.x * 4 + wave; blk < nblk; blk += gridDim.x * 4) {
     const int px = blk * 32 + pl;
@@ -91,6 +111,13 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 4) void qg_conv_group_mfma_kerne
     for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
       for (int j = 0; j < 4; ++j) rs[cb][j] = 0;
+    v16i racc[RS_MFMA ? NCB : 1];  // RS_MFMA: row offsets per output channel (int8 domain)
+    if (RS_MFMA) {
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) racc[cb][r] = 0;
+    }
 
     // taps one at a time, the next tap's 16-byte loads in flight while this tap's MFMAs run; the
     // scheduling barriers stop the compiler from hoisting all R*S*NCB loads (and their registers) up front
@@ -120,7 +147,7 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 4) void qg_conv_group_mfma_kerne
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb) {
-        if (HAS_BZP) {
+        if (HAS_BZP && !RS_MFMA) {
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             const unsigned y = __builtin_amdgcn_bitop3_b32((unsigned)x[cb][j], keep, azp_word, 0xe2);  // keep ? x : theta_A bytes
@@ -131,11 +158,12 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 4) void qg_conv_group_mfma_kerne
         for (int j = 0; j < 4; ++j) x[cb][j] = (int)__builtin_amdgcn_bitop3_b32((unsigned)x[cb][j], keep, flip, 0x6a);  // (x & keep) ^ flip
         const v4i wf = *reinterpret_cast<const v4i*>(smem + (cb * RS + tap) * QG_FRAG_BYTES + lane * 16);
         acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, x[cb], acc[cb], 0, 0, 0);
+        if (RS_MFMA) racc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ones, x[cb], racc[cb], 0, 0, 0);
       }
     }
 
     // ---- output pipeline: lane (pixel pl, half g) holds channels 32 cb + 16 g .. + 15 of its pixel
-    if (HAS_BZP) {
+    if (HAS_BZP && !RS_MFMA) {
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb) group_sums(rs[cb], p.lcg);
     }
@@ -153,10 +181,12 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 4) void qg_conv_group_mfma_kerne
           const float4 sc = *reinterpret_cast<const float4*>(&sc_s[c_l + 4 * q]);
           // row offset of the group of dword q of this half, in the int8 domain: every one of its RS*Cg bytes is 128 high
           const int rsum = HAS_BZP ? (int)rs[cb][q] - ((128 * RS) << p.lcg) : 0;
-          const int x0 = acc[cb][4 * q + 0] + cj.x + (HAS_BZP ? __mul24(nbz.x, rsum) : 0);
-          const int x1 = acc[cb][4 * q + 1] + cj.y + (HAS_BZP ? __mul24(nbz.y, rsum) : 0);
-          const int x2 = acc[cb][4 * q + 2] + cj.z + (HAS_BZP ? __mul24(nbz.z, rsum) : 0);
-          const int x3 = acc[cb][4 * q + 3] + cj.w + (HAS_BZP ? __mul24(nbz.w, rsum) : 0);
+          const int r0 = RS_MFMA ? racc[RS_MFMA ? cb : 0][4 * q + 0] : rsum, r1 = RS_MFMA ? racc[RS_MFMA ? cb : 0][4 * q + 1] : rsum;
+          const int r2 = RS_MFMA ? racc[RS_MFMA ? cb : 0][4 * q + 2] : rsum, r3 = RS_MFMA ? racc[RS_MFMA ? cb : 0][4 * q + 3] : rsum;
+          const int x0 = acc[cb][4 * q + 0] + cj.x + (HAS_BZP ? __mul24(nbz.x, r0) : 0);
+          const int x1 = acc[cb][4 * q + 1] + cj.y + (HAS_BZP ? __mul24(nbz.y, r1) : 0);
+          const int x2 = acc[cb][4 * q + 2] + cj.z + (HAS_BZP ? __mul24(nbz.z, r2) : 0);
+          const int x3 = acc[cb][4 * q + 3] + cj.w + (HAS_BZP ? __mul24(nbz.w, r3) : 0);
           unsigned w = qg_requant_pack<LO>(x0, sc.x, p.clamp_lo, p.clamp_hi, czp_f, 0, 0);
           w = qg_requant_pack<LO>(x1, sc.y, p.clamp_lo, p.clamp_hi, czp_f, 1, w);
           w = qg_requant_pack<LO>(x2, sc.z, p.clamp_lo, p.clamp_hi, czp_f, 2, w);
@@ -186,10 +216,11 @@ __device__ __forceinline__ void dma16(const void* gptr, unsigned char* lds_base)
 // pixels plus pad*W+pad on either side) and its weights with global_load_lds in one burst -- one memory
 // latency per workgroup -- and every tap then comes from LDS.  Pixel p's 16-byte channel chunks are
 // stored swizzled so that the 32 consecutive pixels a half-wave reads hit different banks.
-template <int R, int S, int NCB, bool HAS_BZP>
+template <int R, int S, int NCB, bool HAS_BZP, bool RS_MFMA = false>
 __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel(
     const uint8_t* in, const int8_t* Wfrag, const int Nb, const int H, const int W, const int C, const int halo,
     const int nchunks_pad, const qg_conv_args p) {
+  static_assert(!RS_MFMA || HAS_BZP, "row sums are only needed with a nonzero theta_B");
   // the leading scalar arguments repeat the fields of p that the request burst needs: the file is compiled with
   // kernel-argument preloading, so they arrive in scalar registers with the wave
   constexpr int RS = R * S;
@@ -299,6 +330,14 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
   for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
     for (int j = 0; j < 4; ++j) rs[cb][j] = 0;
+  v16i racc[RS_MFMA ? NCB : 1];  // RS_MFMA: row offsets per output channel (int8 domain)
+  const v4i ones = RS_MFMA ? ones_fragment(lane, p.lcg) : (v4i){0, 0, 0, 0};
+  if (RS_MFMA) {
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) racc[cb][r] = 0;
+  }
 
 #pragma unroll
   for (int kh = 0; kh < R; ++kh) {
@@ -313,7 +352,7 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb) {
         v4i x = *reinterpret_cast<const v4i*>(src + (((cb * 2 + g) ^ swz(pp)) << 4));
-        if (HAS_BZP) {
+        if (HAS_BZP && !RS_MFMA) {
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             const unsigned y = __builtin_amdgcn_bitop3_b32((unsigned)x[j], keep, azp_word, 0xe2);  // keep ? x : theta_A bytes
@@ -324,12 +363,13 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
         for (int j = 0; j < 4; ++j) x[j] = (int)__builtin_amdgcn_bitop3_b32((unsigned)x[j], keep, flip, 0x6a);  // (x & keep) ^ flip
         const v4i wf = *reinterpret_cast<const v4i*>(w_s + (cb * RS + kh * S + kw) * QG_FRAG_BYTES + lane * 16);
         acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, x, acc[cb], 0, 0, 0);
+        if (RS_MFMA) racc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ones, x, racc[cb], 0, 0, 0);
       }
     }
   }
 
   // ---- output pipeline: lane (pixel pl, half g) holds channels 32 cb + 16 g .. + 15 of its pixel
-  if (HAS_BZP) {
+  if (HAS_BZP && !RS_MFMA) {
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) group_sums(rs[cb], p.lcg);
   }
@@ -347,10 +387,10 @@ __global__ __launch_bounds__(256, HAS_BZP ? 2 : 3) void qg_conv_same_mfma_kernel
         if (HAS_BZP) {
           const v4i nbz = *reinterpret_cast<const v4i*>(&nbz_s[c_l + 4 * q]);
           const int rsum = (int)rs[cb][q] - ((128 * RS) << p.lcg);
-          x0 += __mul24(nbz.x, rsum);
-          x1 += __mul24(nbz.y, rsum);
-          x2 += __mul24(nbz.z, rsum);
-          x3 += __mul24(nbz.w, rsum);
+          x0 += __mul24(nbz.x, RS_MFMA ? racc[RS_MFMA ? cb : 0][4 * q + 0] : rsum);
+          x1 += __mul24(nbz.y, RS_MFMA ? racc[RS_MFMA ? cb : 0][4 * q + 1] : rsum);
+          x2 += __mul24(nbz.z, RS_MFMA ? racc[RS_MFMA ? cb : 0][4 * q + 2] : rsum);
+          x3 += __mul24(nbz.w, RS_MFMA ? racc[RS_MFMA ? cb : 0][4 * q + 3] : rsum);
         }
         unsigned w = qg_requant_pack<LO>(x0, sc.x, p.clamp_lo, p.clamp_hi, czp_f, 0, 0);
         w = qg_requant_pack<LO>(x1, sc.y, p.clamp_lo, p.clamp_hi, czp_f, 1, w);
@@ -482,7 +522,10 @@ hipError_t launch_mfma(const qg_conv_args& a, hipStream_t s) {
   const int smem = NCB * RS * QG_FRAG_BYTES + NCB * 32 * 12;
   const int nblk = (a.Nb * a.Ho * a.Wo + 31) / 32;
   const dim3 grid((unsigned)min((nblk + 3) / 4, 2048), (unsigned)(a.C / (NCB * 32)));
-  if (a.has_bzp) {
+  if (a.has_bzp && a.lcg < 2) {  // groups of 1 or 2 channels: row offsets from the matrix cores
+    if (hipError_t e = qg_allow_smem<qg_conv_group_mfma_kernel<R, S, NCB, true, true>>(smem); e != hipSuccess) return e;
+    hipLaunchKernelGGL((qg_conv_group_mfma_kernel<R, S, NCB, true, true>), grid, dim3(256), smem, s, a);
+  } else if (a.has_bzp) {
     if (hipError_t e = qg_allow_smem<qg_conv_group_mfma_kernel<R, S, NCB, true>>(smem); e != hipSuccess) return e;
     hipLaunchKernelGGL((qg_conv_group_mfma_kernel<R, S, NCB, true>), grid, dim3(256), smem, s, a);
   } else {
@@ -496,7 +539,11 @@ template <int R, int S, int NCB>
 hipError_t launch_same(const qg_conv_args& a, int smem, int halo, int nchunks_pad, hipStream_t s) {
   const int npix = a.Nb * a.H * a.W;
   const dim3 grid((unsigned)(((npix + 127) / 128) * (a.C / (NCB * 32))));
-  if (a.has_bzp) {
+  if (a.has_bzp && a.lcg < 2) {  // groups of 1 or 2 channels: row offsets from the matrix cores
+    if (hipError_t e = qg_allow_smem<qg_conv_same_mfma_kernel<R, S, NCB, true, true>>(smem); e != hipSuccess) return e;
+    hipLaunchKernelGGL((qg_conv_same_mfma_kernel<R, S, NCB, true, true>), grid, dim3(256), smem, s, a.in, a.Wfrag, a.Nb, a.H, a.W, a.C,
+                       halo, nchunks_pad, a);
+  } else if (a.has_bzp) {
     if (hipError_t e = qg_allow_smem<qg_conv_same_mfma_kernel<R, S, NCB, true>>(smem); e != hipSuccess) return e;
     hipLaunchKernelGGL((qg_conv_same_mfma_kernel<R, S, NCB, true>), grid, dim3(256), smem, s, a.in, a.Wfrag, a.Nb, a.H, a.W, a.C, halo,
                        nchunks_pad, a);

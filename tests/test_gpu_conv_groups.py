@@ -1,7 +1,8 @@
 """GPU parity of the group-wise convolution for group shapes beyond 4 -> 4 channels (the paper names convolution
 in Sec. 1 without describing it; the definition is the real-domain one of Eq. (1), one GEMM per group) against the
 CPU oracle's direct 7-loop convolution: identical bytes.  Square groups of 8, 16 and 32 channels with a 1 x 1 or
-3 x 3 filter run the matrix-core kernels on block-diagonal tiles; every other shape runs the plain kernel."""
+3 x 3 filter -- and of 1 (depthwise) and 2 -- run the matrix-core kernels on block-diagonal tiles; groups of a multiple of
+16 channels run one dense convolution per group; every other shape runs the plain kernel."""
 import numpy as np
 import pytest
 
@@ -43,6 +44,10 @@ def want(c, oracle):
     dict(Nb=2, H=8, W=8, C=256, G=16, R=1, S=1, pad=0),            # 1 x 1, 16 -> 16
     dict(Nb=1, H=7, W=7, C=96, G=12, pad=0),                       # 8 -> 8 without padding, three blocks
     dict(Nb=1, H=5, W=5, C=2048, G=512),                           # 4 -> 4 in more groups than the dword kernel takes
+    dict(Nb=2, H=9, W=7, C=64, G=64),                              # depthwise (1 -> 1): row offsets from the matrix cores
+    dict(Nb=1, H=11, W=10, C=32, G=32, stride=2),                  # depthwise, taps from memory
+    dict(Nb=2, H=8, W=8, C=128, G=128, R=1, S=1, pad=0),           # depthwise 1 x 1: a per-channel scale
+    dict(Nb=1, H=7, W=9, C=64, G=32),                              # 2 -> 2
     # everything else: the plain kernel
     dict(Nb=2, H=7, W=9, C=32, G=4, Cout=16),                      # 8 -> 4
     dict(Nb=1, H=8, W=8, C=24, G=2, Cout=40, R=5, S=5, pad=2),     # 12 -> 20, 5 x 5
@@ -68,7 +73,7 @@ def test_group_conv_any_group_shape_bit_exact(env, cfg, per_channel, with_bias, 
 def test_group_conv_zero_weight_zero_points(env):
     """theta_B == 0 everywhere: the kernels without row offsets."""
     q, torch, dev, oracle = env
-    for cfg in (dict(Nb=2, H=9, W=7, C=64, G=8), dict(Nb=1, H=7, W=7, C=18, G=3, Cout=12)):
+    for cfg in (dict(Nb=2, H=9, W=7, C=64, G=8), dict(Nb=1, H=7, W=7, C=18, G=3, Cout=12), dict(Nb=2, H=9, W=7, C=64, G=64)):
         c = wl.random_conv(22, **cfg)
         c.b_zp[:] = 0
         assert_same(run(c, q, torch, dev), want(c, oracle), f"group conv {cfg}, theta_B = 0")
