@@ -84,6 +84,46 @@ def test_dense_conv_layers_at_batch_32(env, H, C):
         assert_same(got[n:n + 1], want, f"image {n}")
 
 
+@pytest.mark.parametrize("cfg,kernels", [
+    (dict(Nb=8, H=56, W=56, C=128, Cout=128), ["auto", "tile128", "tile128x256", "tile64k1"]),   # the hand-scheduled loops
+    (dict(Nb=8, H=56, W=56, C=96, Cout=96), ["auto", "tile128"]),                                # 16-channel chunks
+    (dict(Nb=2, H=7, W=7, C=512, Cout=128), ["auto", "skinny16", "skinny32", "tile64x32k8"]),    # few pixels, K = 4608
+    (dict(Nb=4, H=14, W=14, C=256, Cout=256, stride=2), ["auto", "skinny64", "tile64"]),
+])
+def test_dense_conv_layers_on_every_competing_kernel(env, cfg, kernels):
+    """Real layer sizes through the kernels that compete for them, the whole output against the oracle's direct convolution."""
+    q, torch, dev, oracle = env
+    say(f"dense conv {cfg}")
+    c = wl.random_conv(50 + cfg["C"], G=1, **cfg)
+    want = oracle.conv_groupwise_direct(c.inp, 1, c.wgt, c.a_zp, c.b_zp, c.bias, c.scales, c.c_zp, c.relu, c.pad, c.stride)
+    Wp = q.pack_conv_dense_w(torch.from_numpy(np.ascontiguousarray(c.wgt[0])).to(dev), c.b_zp)
+    x, b, sc = torch.from_numpy(c.inp).to(dev), torch.from_numpy(c.bias).to(dev), torch.from_numpy(c.scales).to(dev)
+    for kernel in kernels:
+        got = q.conv_dense_u8s8_requant(x, Wp, c.a_zp, b, sc, c.c_zp, c.relu, pad=c.pad, stride=c.stride, kernel=kernel)
+        torch.cuda.synchronize()
+        assert_same(got.cpu().numpy(), want, f"kernel {kernel}")
+
+
+@pytest.mark.parametrize("cfg", [
+    dict(Nb=32, H=56, W=56, C=128, G=128),             # depthwise
+    dict(Nb=32, H=28, W=28, C=512, G=32),              # 16 -> 16
+    dict(Nb=8, H=56, W=56, C=128, G=2),                # 64 -> 64: one dense convolution per group
+    dict(Nb=2, H=28, W=28, C=40, G=5, Cout=60),        # 8 -> 12: the plain kernel
+])
+def test_group_conv_shapes_at_layer_sizes(env, cfg):
+    q, torch, dev, oracle = env
+    say(f"group conv {cfg}")
+    c = wl.random_conv(60 + cfg["G"], **cfg)
+    Wp = q.pack_conv_w(torch.from_numpy(c.wgt).to(dev), c.b_zp)
+    got = q.conv_groupwise_u8s8_requant(torch.from_numpy(c.inp).to(dev), Wp, c.a_zp, torch.from_numpy(c.bias).to(dev),
+                                        torch.from_numpy(c.scales).to(dev), c.c_zp, c.relu).cpu().numpy()
+    # images are independent: the oracle recomputes the first, the last and one in the middle
+    for n in sorted({0, cfg["Nb"] // 2, cfg["Nb"] - 1}):
+        want = oracle.conv_groupwise_direct(c.inp[n:n + 1], c.G, c.wgt, c.a_zp, c.b_zp, c.bias, c.scales, c.c_zp, c.relu,
+                                            c.pad, c.stride)
+        assert_same(got[n:n + 1], want, f"image {n}")
+
+
 @pytest.mark.parametrize("shape,kernels", [
     ((128, 4096, 4096), ["auto", "tile64", "tile64k4", "tile64x32k8", "skinny64"]),
     ((2048, 2048, 2048), ["auto", "tile128", "tile128x256"]),
