@@ -418,7 +418,9 @@ int qg_conv_groupwise_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W,
  * and as four 16-channel pieces that may belong to different taps otherwise.  A 1 x 1 filter with
  * stride 1 and no padding IS the GEMM over the pixel rows and runs as
  * qg_gemm_u8s8_requant_kernel(in, Nb*H*W, Cin, ...) with the same kernel id.
- *   in_nhwc  dev uint8 [Nb][H][W][Cin], 16-byte aligned;  Cin % 16 == 0
+ *   in_nhwc  dev uint8 [Nb][H][W][Cin]; 16-byte aligned with Cin % 16 == 0 for the staged
+ *            kernels below -- any other image runs, under QG_KERNEL_AUTO only, on a plain
+ *            one-thread-per-output kernel (correct for any extents, not tuned)
  *   out_nhwc dev uint8 [Nb][Ho][Wo][Cout], Ho = (H + 2*pad - R)/stride + 1
  *   kernel   QG_KERNEL_AUTO (chosen from the extents by a cost model fitted to 3 x 3 and
  *            5 x 5 layers), or QG_KERNEL_TILE64 / TILE64K4 / TILE64X32K8 / TILE64K1 /
@@ -426,7 +428,7 @@ int qg_conv_groupwise_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W,
  *            their hand-scheduled loop when Cin % 64 == 0, R*S <= 32 and K >= 256.  With
  *            Cin % 64 == 0 and R*S <= 32 the streaming kernels QG_KERNEL_SKINNY16 / 32 / 64
  *            are taken too (few output pixels and a long K; QG_EUNSUPPORTED otherwise).
- * QG_EUNSUPPORTED for other channel counts, an unaligned image or QG_KERNEL_TILE256;
+ * QG_EUNSUPPORTED for QG_KERNEL_TILE256, or an explicit kernel id with such an image;
  * QG_EINVAL when R*S*Cin differs from the K of Wp or the id is unknown. */
 int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int Cin, int R, int S,
                                int pad, int stride, const qg_packed_b* Wp, const qg_requant_params* p,

@@ -951,7 +951,44 @@ int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int
   if (rc != QG_OK) return rc;
   if (H + 2 * pad < R || W + 2 * pad < S) return QG_EINVAL;
   const int Ho = (H + 2 * pad - R) / stride + 1, Wo = (W + 2 * pad - S) / stride + 1;
-  if (Wp->split || Cin % 16 != 0 || !aligned(in_nhwc, 16)) return QG_EUNSUPPORTED;
+  if (Wp->split) return QG_EUNSUPPORTED;
+  if (Cin % 16 != 0 || !aligned(in_nhwc, 16)) {
+    // no staged kernel takes these extents: the plain kernel, under the automatic choice only
+    if (kernel != QG_KERNEL_AUTO) return QG_EUNSUPPORTED;
+    if ((uint64_t)Nb * H * W * Cin >= (1ull << 31) || (uint64_t)Nb * Ho * Wo * Wp->N >= (1ull << 31)) return QG_EUNSUPPORTED;
+    qg_conv_args c = {};
+    c.in = in_nhwc;
+    c.Bp = Wp->packed;
+    c.nb16 = Wp->N_pad / QG_FRAG_COLS;
+    c.col_off = Wp->col_off;
+    c.bzp = Wp->bzp;
+    c.bias = p->bias;
+    c.scales = p->scales;
+    c.out = out_nhwc;
+    c.Nb = Nb;
+    c.H = H;
+    c.W = W;
+    c.C = Cin;
+    c.Ho = Ho;
+    c.Wo = Wo;
+    c.Cout = Wp->N;
+    c.G = 1;
+    c.Cg = Cin;
+    c.Og = Wp->N;
+    c.R = R;
+    c.S = S;
+    c.pad = pad;
+    c.stride = stride;
+    c.scale_stride = p->n_scales == 1 ? 0 : 1;
+    c.a_zp = p->a_zp;
+    c.c_zp = p->c_zp;
+    const int lo = p->relu ? p->c_zp : 0;
+    c.clamp_lo = (float)(lo - p->c_zp);
+    c.clamp_hi = (float)(255 - p->c_zp);
+    c.has_bzp = Wp->has_bzp;
+    if (Nb == 0) return QG_OK;
+    return qg_launch_conv_dense_plain(c, static_cast<hipStream_t>(stream)) == hipSuccess ? QG_OK : QG_ELAUNCH;
+  }
   // 32-bit byte offsets into the image (tap offsets included) and 32-bit pixel counts
   if ((uint64_t)Nb * H * W * Cin >= (1ull << 30) || (uint64_t)Nb * Ho * Wo >= (1ull << 31) / 4) return QG_EUNSUPPORTED;
   // A 1 x 1 filter with unit stride and no padding is the plain GEMM over the pixel rows (lda = Cin): it takes

@@ -514,7 +514,50 @@ __global__ __launch_bounds__(256) void qg_conv_group_any_kernel(const qg_conv_ar
   }
 }
 
+// Dense convolution for the extents no staged kernel takes (channel counts that are not a multiple of 16, an image
+// that is not 16-byte aligned): thread = (pixel, output channel), the weights read byte by byte out of the packed
+// (R*S*C) x Cout matrix of a GEMM descriptor (fragment [k / 64][slot / 16], 16 consecutive k of a column per lane
+// position).  Correct for any extents, not tuned.
+__global__ __launch_bounds__(256) void qg_conv_dense_plain_kernel(const qg_conv_args p) {
+  const long long total = (long long)p.Nb * p.Ho * p.Wo * p.Cout;
+  const int azp_s = p.a_zp - 128;
+  for (long long idx = (long long)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (long long)gridDim.x * 256) {
+    const int oc = (int)(idx % p.Cout);
+    const long long px = idx / p.Cout;
+    const int wo = (int)(px % p.Wo);
+    const int ho = (int)((px / p.Wo) % p.Ho);
+    const int n = (int)(px / ((long long)p.Wo * p.Ho));
+    const int slot = qg_col_to_slot(oc & 31);
+    const int8_t* bcol = p.Bp + (size_t)((oc >> 5) * 2 + (slot >> 4)) * QG_FRAG_BYTES + (slot & 15) * 16;
+    int acc = 0, rsum = 0;  // both on A - 128
+    int k = 0;
+    for (int kh = 0; kh < p.R; ++kh) {
+      const int hi = ho * p.stride + kh - p.pad;
+      for (int kw = 0; kw < p.S; ++kw) {
+        const int wi = wo * p.stride + kw - p.pad;
+        const bool ok = hi >= 0 && hi < p.H && wi >= 0 && wi < p.W;
+        const uint8_t* src = p.in + (((size_t)n * p.H + (ok ? hi : 0)) * p.W + (ok ? wi : 0)) * p.C;
+        for (int c = 0; c < p.C; ++c, ++k) {
+          const int a = ok ? (int)src[c] - 128 : azp_s;
+          const int w = bcol[(size_t)(k >> 6) * p.nb16 * QG_FRAG_BYTES + ((k >> 4) & 3) * 256 + (k & 15)];
+          acc += a * w;
+          rsum += a;
+        }
+      }
+    }
+    const int x = acc + (p.bias ? p.bias[oc] : 0) - azp_s * p.col_off[oc] - p.bzp[oc] * rsum;
+    p.out[idx] = (uint8_t)qg_requant_one(x, p.scales[(size_t)oc * p.scale_stride], p.clamp_lo, p.clamp_hi, p.c_zp);
+  }
+}
+
 }  // namespace
+
+hipError_t qg_launch_conv_dense_plain(const qg_conv_args& a, hipStream_t s) {
+  const long long total = (long long)a.Nb * a.Ho * a.Wo * a.Cout;
+  const unsigned blocks = (unsigned)((total + 255) / 256 < 256LL * 64 ? (total + 255) / 256 : 256LL * 64);
+  hipLaunchKernelGGL(qg_conv_dense_plain_kernel, dim3(blocks), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
 
 template <int R, int S, int NCB>
 hipError_t launch_mfma(const qg_conv_args& a, hipStream_t s) {

@@ -140,6 +140,8 @@ struct qg_conv_args {
   const int8_t* Wp;
   const int8_t* Wfrag;  // matrix-core layout, or null
   const int8_t* Wany;   // general layout [Cout][R*S][Cg4], or null
+  const int8_t* Bp;     // dense convolution on the plain kernel: the packed (R*S*C) x Cout matrix; nb16 = N_pad / 16
+  int nb16;
   const int32_t* col_off;
   const int32_t* bzp;
   const int32_t* bias;
@@ -296,6 +298,7 @@ hipError_t qg_launch_conv_skinny(const qg_gemm_args& a, int kernel, hipStream_t 
 hipError_t qg_launch_quantize_a(const float* A, int M, int K, int lda, float inv_scale, int a_zp, uint8_t* Aq,
                                 int ldq, hipStream_t s);
 hipError_t qg_launch_conv_group(const qg_conv_args& a, int RS, hipStream_t s);
+hipError_t qg_launch_conv_dense_plain(const qg_conv_args& a, hipStream_t s);
 
 #define QG_MODE_REQUANT 0
 #define QG_MODE_ACC32 1

@@ -113,8 +113,10 @@ def test_dense_conv_errors(env):
     L = q.lib.qg_conv_dense_u8s8_requant
     assert L(inp.data_ptr(), 1, 5, 5, 64, 3, 3, 1, 1, Wp.handle, ctypes.byref(p), None, None, 0) == q.ENULL
     assert L(inp.data_ptr(), 1, 5, 5, 64, 1, 1, 0, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, 0) == q.EINVAL  # K mismatch
-    assert L(inp.data_ptr(), 1, 5, 5, 8, 9, 8, 4, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, 0) == q.EUNSUPPORTED  # Cin % 16
-    assert L(inp.data_ptr() + 4, 1, 5, 5, 64, 3, 3, 1, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, 0) == q.EUNSUPPORTED
+    # extents no staged kernel takes: fine under the automatic choice (the plain kernel), refused with an explicit kernel id
+    t64 = q.kernel_id("tile64")
+    assert L(inp.data_ptr(), 1, 5, 5, 8, 9, 8, 4, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, t64) == q.EUNSUPPORTED  # Cin % 16
+    assert L(inp.data_ptr() + 4, 1, 5, 5, 64, 3, 3, 1, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, t64) == q.EUNSUPPORTED
     assert L(inp.data_ptr(), 1, 1, 1, 64, 3, 3, 0, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, 0) == q.EINVAL  # filter larger than image
     ok = (inp.data_ptr(), 1, 5, 5, 64, 3, 3, 1, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None)
     assert L(*ok, q.KERNEL_LAST + 1) == q.EINVAL and L(*ok, -1) == q.EINVAL
@@ -139,3 +141,34 @@ def test_dense_conv_random_extents_any_multiple_of_16_channels(env, seed):
     ref = want(c, oracle)
     for kernel in CONV_KERNELS:
         assert_same(run(c, q, torch, dev, kernel), ref, f"dense conv {cfg}, kernel {kernel}")
+
+
+@pytest.mark.parametrize("cfg", [
+    dict(Nb=2, H=9, W=11, C=3, Cout=32, stride=2),                 # a first layer: three channels
+    dict(Nb=1, H=8, W=8, C=24, Cout=24),
+    dict(Nb=2, H=7, W=6, C=70, Cout=33, R=2, S=5, pad=2),          # K = 700 crosses several 64-deep blocks of the packed matrix
+    dict(Nb=1, H=6, W=6, C=1, Cout=5, R=1, S=1, pad=0),
+])
+def test_dense_conv_any_channel_count_on_the_plain_kernel(env, cfg):
+    q, torch, dev, oracle = env
+    say(f"dense conv, plain kernel {cfg}")
+    c = wl.random_conv(15, G=1, **cfg)
+    assert_same(run(c, q, torch, dev, "auto"), want(c, oracle), f"dense conv {cfg}")
+
+
+def test_dense_conv_unaligned_image_on_the_plain_kernel(env):
+    q, torch, dev, oracle = env
+    c = wl.random_conv(16, Nb=1, H=7, W=7, C=64, G=1, Cout=48)
+    Wp = q.pack_conv_dense_w(torch.from_numpy(np.ascontiguousarray(c.wgt[0])).to(dev), c.b_zp)
+    store = torch.zeros(c.inp.size + 16, dtype=torch.uint8, device=dev)
+    store[4:4 + c.inp.size] = torch.from_numpy(c.inp.reshape(-1)).to(dev)
+    inp = store[4:4 + c.inp.size].view(c.inp.shape)
+    out = torch.empty((1, 7, 7, 48), dtype=torch.uint8, device=dev)
+    sc = torch.from_numpy(c.scales).to(dev)
+    bias = torch.from_numpy(c.bias).to(dev)
+    p = q.RequantParams(c.a_zp, bias.data_ptr(), sc.data_ptr(), sc.numel(), c.c_zp, int(c.relu))
+    rc = q.lib.qg_conv_dense_u8s8_requant(inp.data_ptr(), 1, 7, 7, 64, 3, 3, c.pad, c.stride, Wp.handle, ctypes.byref(p),
+                                          out.data_ptr(), None, 0)
+    assert rc == q.OK
+    torch.cuda.synchronize()
+    assert_same(out.cpu().numpy(), want(c, oracle), "image 4 bytes off a 16-byte boundary")
