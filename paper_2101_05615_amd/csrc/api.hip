@@ -953,7 +953,7 @@ int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int
   const int Ho = (H + 2 * pad - R) / stride + 1, Wo = (W + 2 * pad - S) / stride + 1;
   if (Wp->split) return QG_EUNSUPPORTED;
   if (Cin % 16 != 0 || !aligned(in_nhwc, 16)) {
-    // no staged kernel takes these extents: the plain kernel, under the automatic choice only
+    // no staged kernel takes these extents: the byte-gathering kernel, under the automatic choice only
     if (kernel != QG_KERNEL_AUTO) return QG_EUNSUPPORTED;
     if ((uint64_t)Nb * H * W * Cin >= (1ull << 31) || (uint64_t)Nb * Ho * Wo * Wp->N >= (1ull << 31)) return QG_EUNSUPPORTED;
     qg_conv_args c = {};

@@ -514,48 +514,134 @@ __global__ __launch_bounds__(256) void qg_conv_group_any_kernel(const qg_conv_ar
   }
 }
 
-// Dense convolution for the extents no staged kernel takes (channel counts that are not a multiple of 16, an image
-// that is not 16-byte aligned): thread = (pixel, output channel), the weights read byte by byte out of the packed
-// (R*S*C) x Cout matrix of a GEMM descriptor (fragment [k / 64][slot / 16], 16 consecutive k of a column per lane
-// position).  Correct for any extents, not tuned.
-__global__ __launch_bounds__(256) void qg_conv_dense_plain_kernel(const qg_conv_args p) {
-  const long long total = (long long)p.Nb * p.Ho * p.Wo * p.Cout;
-  const int azp_s = p.a_zp - 128;
-  for (long long idx = (long long)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (long long)gridDim.x * 256) {
-    const int oc = (int)(idx % p.Cout);
-    const long long px = idx / p.Cout;
-    const int wo = (int)(px % p.Wo);
-    const int ho = (int)((px / p.Wo) % p.Ho);
-    const int n = (int)(px / ((long long)p.Wo * p.Ho));
-    const int slot = qg_col_to_slot(oc & 31);
-    const int8_t* bcol = p.Bp + (size_t)((oc >> 5) * 2 + (slot >> 4)) * QG_FRAG_BYTES + (slot & 15) * 16;
-    int acc = 0, rsum = 0;  // both on A - 128
-    int k = 0;
-    for (int kh = 0; kh < p.R; ++kh) {
-      const int hi = ho * p.stride + kh - p.pad;
-      for (int kw = 0; kw < p.S; ++kw) {
-        const int wi = wo * p.stride + kw - p.pad;
-        const bool ok = hi >= 0 && hi < p.H && wi >= 0 && wi < p.W;
-        const uint8_t* src = p.in + (((size_t)n * p.H + (ok ? hi : 0)) * p.W + (ok ? wi : 0)) * p.C;
-        for (int c = 0; c < p.C; ++c, ++k) {
-          const int a = ok ? (int)src[c] - 128 : azp_s;
-          const int w = bcol[(size_t)(k >> 6) * p.nb16 * QG_FRAG_BYTES + ((k >> 4) & 3) * 256 + (k & 15)];
-          acc += a * w;
-          rsum += a;
+// Dense convolution for the extents no requested staging takes (channel counts that are not a multiple of 16 -- the
+// three channels of a first layer --, an image that is not 16-byte aligned): the im2col tile is GATHERED, byte by
+// byte, into LDS.  Workgroup = 64 output pixels x 64 output channels, four waves of one 32 x 32 block each; per
+// 64-deep k chunk every thread gathers 16 consecutive k of one pixel row (walking (channel, kw, kh) as it goes; a tap
+// outside the image reads as theta_A, k past K as 0x80, the K padding of every A stage) and copies 16 bytes of the
+// packed weights, then two MFMAs per wave.  One stage, two barriers per chunk: K is short where this kernel is used.
+// Weights: the packed (R*S*C) x Cout matrix of a GEMM descriptor.
+__device__ __forceinline__ int gather_swz(int r) { return ((r >> 1) & 3) ^ ((r >> 3) & 1); }
+
+template <bool HAS_BZP>
+__global__ __launch_bounds__(256) void qg_conv_dense_gather_kernel(const qg_conv_args p) {
+  __shared__ __align__(16) unsigned char a_s[64 * 64];
+  __shared__ __align__(16) unsigned char b_s[4 * QG_FRAG_BYTES];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave & 1, wave_n = wave >> 1;
+  const int l32 = lane & 31, lg = lane >> 5;
+  const int npix = p.Nb * p.Ho * p.Wo;
+  const int m0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
+  const int K = p.R * p.S * p.C, KT = (K + 63) / 64;
+
+  // the row this thread gathers for: pixel position of tap (0, 0)
+  const int gr = tid >> 2, gc = tid & 3;
+  const int gm = min(m0 + gr, npix - 1);
+  const int gwo = gm % p.Wo, gt = gm / p.Wo;
+  const int h0 = (gt % p.Ho) * p.stride - p.pad, w0 = gwo * p.stride - p.pad;
+  const uint8_t* const img = p.in + (size_t)(gt / p.Ho) * p.H * p.W * p.C;
+  // (channel, kw, kh) of this thread's first k
+  int ci, kw, kh;
+  {
+    const int k0 = gc * 16, tap = k0 / p.C;
+    ci = k0 - tap * p.C;
+    kh = tap / p.S;
+    kw = tap - kh * p.S;
+  }
+  const int8_t* const bsrc = p.Bp + (size_t)(n0 / QG_FRAG_COLS) * QG_FRAG_BYTES + tid * 16;  // 4 KiB per chunk: 256 threads x 16 B
+  const size_t b_step = (size_t)p.nb16 * QG_FRAG_BYTES;
+  // whole fragments past N_pad do not exist: clamp the copy to the last fragment of the slab (its columns are never stored)
+  const int frag_ok = min(4, p.nb16 - n0 / QG_FRAG_COLS);
+  const int8_t* const bsrc_c = (tid >> 6) < frag_ok ? bsrc : p.Bp + (size_t)(p.nb16 - 1) * QG_FRAG_BYTES + lane * 16;
+
+  v16i acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0;
+  unsigned rs = 0;
+
+  for (int kc = 0; kc < KT; ++kc) {
+    // ---- gather 16 bytes of the im2col row, copy 16 bytes of weights
+    union {
+      v4i v;
+      unsigned char b[16];
+    } u;
+    {
+      int k = kc * 64 + gc * 16;
+#pragma unroll
+      for (int i = 0; i < 16; ++i, ++k) {
+        unsigned char x = 0x80;
+        if (k < K) {
+          const int hi = h0 + kh, wi = w0 + kw;
+          x = ((unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W) ? img[((size_t)hi * p.W + wi) * p.C + ci] : (unsigned char)p.a_zp;
+          if (++ci == p.C) {
+            ci = 0;
+            if (++kw == p.S) kw = 0, ++kh;
+          }
+        }
+        u.b[i] = x;
+      }
+      // on to this thread's 16 k of the next chunk: 48 further
+      if (kc + 1 < KT) {
+        int adv = 48;
+        while (adv > 0) {
+          const int stepc = min(adv, p.C - ci);
+          ci += stepc;
+          adv -= stepc;
+          if (ci == p.C) {
+            ci = 0;
+            if (++kw == p.S) kw = 0, ++kh;
+          }
         }
       }
     }
-    const int x = acc + (p.bias ? p.bias[oc] : 0) - azp_s * p.col_off[oc] - p.bzp[oc] * rsum;
-    p.out[idx] = (uint8_t)qg_requant_one(x, p.scales[(size_t)oc * p.scale_stride], p.clamp_lo, p.clamp_hi, p.c_zp);
+    const v4i bw = *reinterpret_cast<const v4i*>(bsrc_c + (size_t)kc * b_step);
+    __syncthreads();  // the previous chunk's fragments have been read
+    *reinterpret_cast<v4i*>(a_s + gr * 64 + ((gc ^ gather_swz(gr)) << 4)) = u.v;
+    *reinterpret_cast<v4i*>(b_s + tid * 16) = bw;
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const int r = wave_m * 32 + l32;
+      v4i af = *reinterpret_cast<const v4i*>(a_s + r * 64 + (((ks * 2 + lg) ^ gather_swz(r)) << 4));
+      const v4i bf = *reinterpret_cast<const v4i*>(b_s + (wave_n * 2 + (l32 >> 4)) * QG_FRAG_BYTES + (l32 & 15) * 16 + lg * 256 + ks * 512);
+      if (HAS_BZP) {
+        rs = __builtin_amdgcn_sad_u8(af.x, 0u, rs);
+        rs = __builtin_amdgcn_sad_u8(af.y, 0u, rs);
+        rs = __builtin_amdgcn_sad_u8(af.z, 0u, rs);
+        rs = __builtin_amdgcn_sad_u8(af.w, 0u, rs);
+      }
+      af = af ^ (int)0x80808080;
+      acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf, af, acc, 0, 0, 0);
+    }
+  }
+
+  // ---- output pipeline: lane (row l32, half lg) holds 16 consecutive output channels of its pixel
+  const int rsum = HAS_BZP ? (int)(rs + (unsigned)__shfl_xor((int)rs, 32)) - 128 * (KT * 64) : 0;
+  const int row = m0 + wave_m * 32 + l32;
+  const int col0 = n0 + wave_n * 32 + lg * 16;
+  if (row < npix) {
+    const int azp_s = p.a_zp - 128;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int col = col0 + i;
+      if (col < p.Cout) {
+        const int x = acc[i] + (p.bias ? p.bias[col] : 0) - azp_s * p.col_off[col] - (HAS_BZP ? p.bzp[col] * rsum : 0);
+        p.out[(size_t)row * p.Cout + col] =
+            (uint8_t)qg_requant_one(x, p.scales[(size_t)col * p.scale_stride], p.clamp_lo, p.clamp_hi, p.c_zp);
+      }
+    }
   }
 }
 
 }  // namespace
 
 hipError_t qg_launch_conv_dense_plain(const qg_conv_args& a, hipStream_t s) {
-  const long long total = (long long)a.Nb * a.Ho * a.Wo * a.Cout;
-  const unsigned blocks = (unsigned)((total + 255) / 256 < 256LL * 64 ? (total + 255) / 256 : 256LL * 64);
-  hipLaunchKernelGGL(qg_conv_dense_plain_kernel, dim3(blocks), dim3(256), 0, s, a);
+  const int npix = a.Nb * a.Ho * a.Wo;
+  const dim3 grid((unsigned)((npix + 63) / 64), (unsigned)((a.Cout + 63) / 64));
+  if (a.has_bzp)
+    hipLaunchKernelGGL(qg_conv_dense_gather_kernel<true>, grid, dim3(256), 0, s, a);
+  else
+    hipLaunchKernelGGL(qg_conv_dense_gather_kernel<false>, grid, dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

@@ -140,7 +140,7 @@ struct qg_conv_args {
   const int8_t* Wp;
   const int8_t* Wfrag;  // matrix-core layout, or null
   const int8_t* Wany;   // general layout [Cout][R*S][Cg4], or null
-  const int8_t* Bp;     // dense convolution on the plain kernel: the packed (R*S*C) x Cout matrix; nb16 = N_pad / 16
+  const int8_t* Bp;     // dense convolution on the byte-gathering kernel: the packed (R*S*C) x Cout matrix; nb16 = N_pad / 16
   int nb16;
   const int32_t* col_off;
   const int32_t* bzp;

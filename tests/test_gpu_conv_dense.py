@@ -113,7 +113,7 @@ def test_dense_conv_errors(env):
     L = q.lib.qg_conv_dense_u8s8_requant
     assert L(inp.data_ptr(), 1, 5, 5, 64, 3, 3, 1, 1, Wp.handle, ctypes.byref(p), None, None, 0) == q.ENULL
     assert L(inp.data_ptr(), 1, 5, 5, 64, 1, 1, 0, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, 0) == q.EINVAL  # K mismatch
-    # extents no staged kernel takes: fine under the automatic choice (the plain kernel), refused with an explicit kernel id
+    # extents no staged kernel takes: fine under the automatic choice (the byte-gathering kernel), refused with an explicit kernel id
     t64 = q.kernel_id("tile64")
     assert L(inp.data_ptr(), 1, 5, 5, 8, 9, 8, 4, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, t64) == q.EUNSUPPORTED  # Cin % 16
     assert L(inp.data_ptr() + 4, 1, 5, 5, 64, 3, 3, 1, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, t64) == q.EUNSUPPORTED
@@ -148,15 +148,22 @@ def test_dense_conv_random_extents_any_multiple_of_16_channels(env, seed):
     dict(Nb=1, H=8, W=8, C=24, Cout=24),
     dict(Nb=2, H=7, W=6, C=70, Cout=33, R=2, S=5, pad=2),          # K = 700 crosses several 64-deep blocks of the packed matrix
     dict(Nb=1, H=6, W=6, C=1, Cout=5, R=1, S=1, pad=0),
+    dict(Nb=3, H=19, W=17, C=3, Cout=150, R=7, S=7, pad=3, stride=2),   # several pixel and channel blocks, both ragged
+    dict(Nb=2, H=13, W=13, C=5, Cout=70, R=3, S=3, pad=0, stride=3),    # taps that straddle the 16-byte pieces
+    dict(Nb=1, H=10, W=12, C=17, Cout=64, R=3, S=1, pad=1),             # 17 channels: every piece starts mid-pixel
+    dict(Nb=1, H=1, W=1, C=3, Cout=1, R=1, S=1, pad=0),                 # one output byte
 ])
-def test_dense_conv_any_channel_count_on_the_plain_kernel(env, cfg):
+@pytest.mark.parametrize("variant", range(3))
+def test_dense_conv_any_channel_count_on_the_gathering_kernel(env, cfg, variant):
     q, torch, dev, oracle = env
-    say(f"dense conv, plain kernel {cfg}")
-    c = wl.random_conv(15, G=1, **cfg)
+    say(f"dense conv, byte-gathering kernel {cfg}, variant {variant}")
+    c = wl.random_conv(15 + variant, G=1, per_channel=variant != 1, with_bias=variant != 2, relu=variant == 1, **cfg)
+    if variant == 2:   # all weight zero points zero: the variant without row offsets
+        c.b_zp[:] = 0
     assert_same(run(c, q, torch, dev, "auto"), want(c, oracle), f"dense conv {cfg}")
 
 
-def test_dense_conv_unaligned_image_on_the_plain_kernel(env):
+def test_dense_conv_unaligned_image_on_the_gathering_kernel(env):
     q, torch, dev, oracle = env
     c = wl.random_conv(16, Nb=1, H=7, W=7, C=64, G=1, Cout=48)
     Wp = q.pack_conv_dense_w(torch.from_numpy(np.ascontiguousarray(c.wgt[0])).to(dev), c.b_zp)

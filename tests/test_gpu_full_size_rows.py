@@ -89,6 +89,8 @@ def test_dense_conv_layers_at_batch_32(env, H, C):
     (dict(Nb=8, H=56, W=56, C=96, Cout=96), ["auto", "tile128"]),                                # 16-channel chunks
     (dict(Nb=2, H=7, W=7, C=512, Cout=128), ["auto", "skinny16", "skinny32", "tile64x32k8"]),    # few pixels, K = 4608
     (dict(Nb=4, H=14, W=14, C=256, Cout=256, stride=2), ["auto", "skinny64", "tile64"]),
+    (dict(Nb=2, H=224, W=224, C=3, Cout=32, stride=2), ["auto"]),                               # first layers: the byte-gathering kernel
+    (dict(Nb=1, H=224, W=224, C=3, Cout=64, R=7, S=7, pad=3, stride=2), ["auto"]),
 ])
 def test_dense_conv_layers_on_every_competing_kernel(env, cfg, kernels):
     """Real layer sizes through the kernels that compete for them, the whole output against the oracle's direct convolution."""
@@ -108,7 +110,7 @@ def test_dense_conv_layers_on_every_competing_kernel(env, cfg, kernels):
     dict(Nb=32, H=56, W=56, C=128, G=128),             # depthwise
     dict(Nb=32, H=28, W=28, C=512, G=32),              # 16 -> 16
     dict(Nb=8, H=56, W=56, C=128, G=2),                # 64 -> 64: one dense convolution per group
-    dict(Nb=2, H=28, W=28, C=40, G=5, Cout=60),        # 8 -> 12: the plain kernel
+    dict(Nb=2, H=28, W=28, C=40, G=5, Cout=60),        # 8 -> 12: the one-thread-per-output kernel
 ])
 def test_group_conv_shapes_at_layer_sizes(env, cfg):
     q, torch, dev, oracle = env
