@@ -202,8 +202,14 @@ int qg_gemm_u8s8_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* 
 #define QG_KERNEL_TILE64K1 9
 #define QG_KERNEL_TILE64X32K8 10
 #define QG_KERNEL_LAST 10
+/* Dense convolution only (qg_conv_dense_u8s8_requant): the kernels that keep the input patch of a pixel tile in LDS;
+ * workgroup = 128 pixels x 128 channels, 256 x 64, 256 x 128 (eight waves). */
+#define QG_KERNEL_PATCH128 11
+#define QG_KERNEL_PATCH256X64 12
+#define QG_KERNEL_PATCH256 13
+#define QG_KERNEL_CONV_LAST 13
 
-/* Name of a kernel id ("skinny16", "tile128x256", ...; "auto" for 0), NULL if invalid. */
+/* Name of a kernel id ("skinny16", "tile128x256", "patch128", ...; "auto" for 0), NULL if invalid. */
 const char* qg_kernel_name(int kernel);
 
 /* The id QG_KERNEL_AUTO resolves to for this shape (never QG_KERNEL_AUTO);

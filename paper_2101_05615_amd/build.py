@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqgemm.so")
-SOURCES = ["api.hip", "pack.hip", "quantize_a.hip", "gemm_tile.hip", "gemm_skinny.hip", "conv_group.hip"]
+SOURCES = ["api.hip", "pack.hip", "quantize_a.hip", "gemm_tile.hip", "gemm_skinny.hip", "conv_group.hip", "conv_patch.hip"]
 PROBES_SRC = os.path.join(ROOT, "bench_probes.hip")   # bench.py's measurement probes, a library of their own
 PROBES_LIB = os.path.join(ROOT, "libbench_probes.so")
 

@@ -335,8 +335,9 @@ extern "C" {
 const char* qg_kernel_name(int kernel) {
   static const char* const names[] = {"auto",   "skinny16", "skinny32",    "skinny64",
                                       "tile64", "tile128",  "tile128x256", "tile256",
-                                      "tile64k4", "tile64k1", "tile64x32k8"};
-  return (kernel >= 0 && kernel <= QG_KERNEL_LAST) ? names[kernel] : nullptr;
+                                      "tile64k4", "tile64k1", "tile64x32k8",
+                                      "patch128", "patch256x64", "patch256"};
+  return (kernel >= 0 && kernel <= QG_KERNEL_CONV_LAST) ? names[kernel] : nullptr;
 }
 
 int qg_kernel_select(int M, int N, int K) {
@@ -923,6 +924,11 @@ int launch_conv_gemm(const uint8_t* in, int in_bytes, int Nb, int H, int W, int 
         if (ceil_div(a.M, c.rows) <= 65535 && us < best_us) best_us = us, kernel = c.kernel;
       }
   }
+  if (kernel >= QG_KERNEL_PATCH128) {
+    const int form = kernel - QG_KERNEL_PATCH128;
+    if (!qg_conv_patch_applies(a, form)) return QG_EUNSUPPORTED;
+    return qg_launch_conv_patch(a, form, stream) == hipSuccess ? QG_OK : QG_ELAUNCH;
+  }
   if (kernel <= QG_KERNEL_SKINNY64) {
     if (!stream_ok) return QG_EUNSUPPORTED;
     a.ksplit = 1;
@@ -943,7 +949,7 @@ int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int
                                void* stream, int kernel) {
   if (!Wp || ((!in_nhwc || !out_nhwc) && Nb != 0)) return QG_ENULL;
   if (Wp->kind != QG_KIND_GEMM || Wp->version != QG_LAYOUT_VERSION) return QG_EINVAL;
-  if (kernel < QG_KERNEL_AUTO || kernel > QG_KERNEL_LAST) return QG_EINVAL;
+  if (kernel < QG_KERNEL_AUTO || kernel > QG_KERNEL_CONV_LAST) return QG_EINVAL;
   if (kernel == QG_KERNEL_TILE256) return QG_EUNSUPPORTED;
   if (Nb < 0 || H <= 0 || W <= 0 || Cin <= 0 || R <= 0 || S <= 0 || pad < 0 || stride <= 0) return QG_EINVAL;
   if ((long long)R * S * Cin != Wp->K) return QG_EINVAL;
@@ -993,8 +999,10 @@ int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int
   if ((uint64_t)Nb * H * W * Cin >= (1ull << 30) || (uint64_t)Nb * Ho * Wo >= (1ull << 31) / 4) return QG_EUNSUPPORTED;
   // A 1 x 1 filter with unit stride and no padding is the plain GEMM over the pixel rows (lda = Cin): it takes
   // the GEMM's own kernels and choice, hand-scheduled loops included; the bytes are the same either way.
-  if (R == 1 && S == 1 && pad == 0 && stride == 1)
+  if (R == 1 && S == 1 && pad == 0 && stride == 1) {
+    if (kernel > QG_KERNEL_LAST) return QG_EUNSUPPORTED;  // the patch kernels have nothing to keep for a single tap
     return qg_gemm_u8s8_requant_kernel(in_nhwc, Nb * H * W, Cin, Wp, p, out_nhwc, Wp->N, nullptr, stream, kernel);
+  }
   if (Nb == 0) return QG_OK;  // an empty batch
   return launch_conv_gemm(in_nhwc, Nb * H * W * Cin, Nb, H, W, Cin, Cin, R, S, pad, stride, Ho, Wo, Wp->packed, Wp->col_off,
                           Wp->bzp, Wp->K, Wp->K_pad, Wp->N, Wp->N_pad, Wp->has_bzp, p, 0, out_nhwc, Wp->N, kernel,

@@ -29,6 +29,7 @@ EXPORTS = [
 ]
 
 KERNEL_AUTO, KERNEL_LAST = 0, 10
+KERNEL_CONV_LAST = 13   # the ids above KERNEL_LAST are kernels of the dense convolution only
 MAX_DISPATCH_RULES = 256
 
 
@@ -235,8 +236,8 @@ def kernel_names():
 def kernel_id(kernel):
     """Accepts an id or a name."""
     if isinstance(kernel, str):
-        for k, n in kernel_names().items():
-            if n == kernel:
+        for k in range(KERNEL_CONV_LAST + 1):
+            if lib.qg_kernel_name(k).decode() == kernel:
                 return k
         raise ValueError(f"unknown kernel {kernel!r}")
     return int(kernel)
