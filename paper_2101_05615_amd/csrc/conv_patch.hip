@@ -32,7 +32,12 @@ constexpr int ring_slabs(int tn) { return tn <= 64 ? 8 : 6; }
 // slab(0) && slab(1) && ... && slab(N-1): the ring, unrolled
 template <class F, int... Is>
 __device__ __forceinline__ bool once_round_the_ring(F& slab, std::integer_sequence<int, Is...>) {
-  return (... && slab(std::integral_constant<int, Is>{}));
+  return (... && slab(std::integral_constant<int, Is>{}, std::false_type{}));
+}
+// slab(1) && ... && slab(N)
+template <class F, int... Is>
+__device__ __forceinline__ bool rest_of_the_ring(F& slab, std::integer_sequence<int, Is...>) {
+  return (... && slab(std::integral_constant<int, Is + 1>{}, std::false_type{}));
 }
 
 // The requests (global memory straight into LDS, 16 or 4 bytes per lane, at lds + lane * size; lds wave-uniform) are
@@ -77,8 +82,13 @@ __device__ __forceinline__ void wait_vmcnt() {
 // thread flips the bytes of whole patch pixels in place and leaves each pixel's channel sum in LDS; the row offset
 // of an output pixel is then the sum of R*S of those (or Cin * theta_A for a tap outside the image).
 template <int WM, int WN, int MB, int NBW, bool HAS_BZP, bool C64>
-__global__ __launch_bounds__(WM* WN * 64) void qg_conv_patch_kernel(const qg_gemm_args p, const int ps,
-                                                                     const int patch_chunks, const int halo) {
+__global__ __launch_bounds__(WM* WN * 64) void qg_conv_patch_kernel(
+    const uint8_t* const in, const int8_t* const Bp, const int npix, const int W, const int H, const int N, const int nb16,
+    const int cpix, const int geom, const qg_gemm_args p) {
+  // The leading scalar arguments repeat what the request burst needs (cpix = Cin | bytes per image pixel << 16,
+  // geom = R | S << 8 | pad << 16 | theta_A << 24): the file is compiled with kernel-argument preloading, so they
+  // arrive in scalar registers with the wave (the first 14 dwords do), and the cold trip to the argument buffer
+  // for the rest of p (first used after the burst) overlaps the patch's own.
   constexpr int NW = WM * WN, NT = NW * 64;
   constexpr int TP = WM * MB * 32, TN = WN * NBW * 32;
   constexpr int STAGE = TN * QG_FRAG_K;           // bytes of one 64-deep slab of TN columns
@@ -86,14 +96,20 @@ __global__ __launch_bounds__(WM* WN * 64) void qg_conv_patch_kernel(const qg_gem
   constexpr int FPS = TN / QG_FRAG_COLS;          // fragments per slab
   static_assert(FPS % NW == 0, "every wave requests the same number of fragments per slab");
   constexpr int RPW = FPS / NW;                   // requests per wave and slab
+  constexpr int PARTS = TN / 64;                  // requests per array of column constants
+  static_assert((4 * PARTS) % NW == 0, "every wave requests the same number of constant rows");
+  constexpr int CPW = 4 * PARTS / NW;             // constant requests per wave
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wave_m = wave % WM, wave_n = wave / WM;
   const int l32 = lane & 31, lg = lane >> 5;
-  const int npix = p.M, W = p.cv_W, H = p.cv_H, R = p.cv_R, S = p.cv_S;
-  const int nc = p.cv_Cin >> 4, psc = ps >> 4;
-  const int npp = TP + (R - 1) * W + (S - 1);  // patch pixels
+  const int R = geom & 255, S = (geom >> 8) & 255, pad = (geom >> 16) & 255, azp = (geom >> 24) & 255;
+  const int Cin = cpix & 0xFFFF, pix = (int)((unsigned)cpix >> 16), K = R * S * Cin;
+  const int nc = Cin >> 4, psc = nc | 1, ps = psc << 4;  // an odd number of 16-byte chunks per patch pixel
+  const int npp = TP + (R - 1) * W + (S - 1);            // patch pixels
+  const int patch_chunks = (npp * psc + NT - 1) / NT * NT;
+  const int halo = pad * W + pad;
 
   extern __shared__ __align__(16) unsigned char smem[];
   const int theta_bytes = (ps + 63) & ~63;
@@ -104,67 +120,58 @@ __global__ __launch_bounds__(WM* WN * 64) void qg_conv_patch_kernel(const qg_gem
   int* const nbz_s = cj_s + TN;                                     // lands as theta_B, becomes -theta_B
   float* const sc_s = reinterpret_cast<float*>(nbz_s + TN);
   int* const coff_s = reinterpret_cast<int*>(sc_s + TN);            // column offsets
-  int* const rsum_s = coff_s + TN;                                  // TP row offsets (int8 domain)
-  int* const psum_s = rsum_s + TP;                             // npp channel sums of the patch pixels
+  int* const psum_s = coff_s + TN;                                  // npp channel sums of the patch pixels
 
   // Workgroup -> (pixel tile, channel slice).  Workgroup ids go round-robin over the 8 XCDs: each XCD walks its own
   // contiguous eighth of the pixel tiles (neighbouring tiles share their halo rows in one L2), the channel slices
   // of a tile back to back on the same XCD.
   int tile, slice;
   {
-    const int nslice = (p.N + TN - 1) / TN, ntile = gridDim.x / nslice, id = blockIdx.x;
-    if ((ntile & 7) == 0) {
-      const int j = id >> 3;
-      slice = j % nslice;
-      tile = (id & 7) * (ntile >> 3) + j / nslice;
+    const int ntile = (npix + TP - 1) / TP, id = blockIdx.x;
+    if (N <= TN) {  // one slice: no division
+      slice = 0;
+      tile = (ntile & 7) == 0 ? (id & 7) * (ntile >> 3) + (id >> 3) : id;
     } else {
-      slice = id % nslice;
-      tile = id / nslice;
+      const int nslice = (N + TN - 1) / TN;
+      if ((ntile & 7) == 0) {
+        const int j = id >> 3;
+        slice = j % nslice;
+        tile = (id & 7) * (ntile >> 3) + j / nslice;
+      } else {
+        slice = id % nslice;
+        tile = id / nslice;
+      }
     }
   }
   const int m0 = tile * TP, n0 = slice * TN;
   const int lin0 = m0 - halo;  // linear index of patch pixel 0 (may be negative)
 
-  // ---- one burst of requests: the column constants of the output pipeline (four arrays of TN entries, 64 per
-  // request; like everything else they go straight to LDS, so that every wait below is a constant count), the patch,
-  // then the first NSTAGE - 1 weight slabs
+  // ---- one burst of requests: the patch, then the first NSTAGE - 1 weight slabs
   {
-    constexpr int PARTS = TN / 64;  // requests per array
-    static_assert((4 * PARTS) % NW == 0, "every wave requests the same number of constant rows");
-#pragma unroll
-    for (int i = 0; i < 4 * PARTS / NW; ++i) {
-      const int q = wave + i * NW, arr = q / PARTS, part = q % PARTS;
-      const int c = part * 64 + lane;
-      const int oc = min(n0 + c, p.N - 1);  // columns past N read a valid entry that is never used
-      const void* src = arr == 0 ? (const void*)((p.bias ? p.bias : p.col_off) + oc)
-                      : arr == 1 ? (const void*)(p.bzp + oc)
-                      : arr == 2 ? (const void*)(p.scales + (size_t)oc * p.scale_stride)
-                                 : (const void*)(p.col_off + oc);
-      request4(src, lds_addr(cj_s + arr * TN + part * 64));
-    }
-  }
-  {
-    int c = wave * 64 + lane;
-    int pp = c / psc, ch = c - pp * psc;
+    const int c = wave * 64 + lane;
+    int pp = (int)((float)c / (float)psc);  // c < 2^16 and psc < 2^8: the rounded quotient is off by one at most
+    int ch = c - pp * psc;
+    if (ch < 0) ch += psc, --pp;
+    if (ch >= psc) ch -= psc, ++pp;
     const int dpp = NT / psc, dch = NT - dpp * psc;
-    const uint8_t* const theta_row = qg_byte_rows.b[p.cv_azp & 255];
+    const uint8_t* const theta_row = qg_byte_rows.b[azp];
     const unsigned patch_lds = lds_addr(patch);
     for (int c0 = wave * 64; c0 < patch_chunks; c0 += NT) {
       const int lin = lin0 + pp;
       const bool ok = ch < nc && (unsigned)lin < (unsigned)npix;
-      const uint8_t* src = ok ? p.A + (size_t)lin * p.cv_pix + (ch << 4) : theta_row;
+      const uint8_t* src = ok ? in + (size_t)lin * pix + (ch << 4) : theta_row;
       request16(src, patch_lds + c0 * 16);
       pp += dpp;
       ch += dch;
       if (ch >= psc) ch -= psc, ++pp;
     }
   }
-  const int nkb = (p.K + QG_FRAG_K - 1) / QG_FRAG_K;  // 64-deep slabs that hold weights
-  const size_t b_step = (size_t)p.nb16 * QG_FRAG_BYTES;
+  const int nkb = (K + QG_FRAG_K - 1) / QG_FRAG_K;  // 64-deep slabs that hold weights
+  const size_t b_step = (size_t)nb16 * QG_FRAG_BYTES;
   // Requests the next slab (they are requested in order, each into the next slot of the ring).  A slab past the last
   // is requested again from the last one, into a slot nobody reads any more: every iteration issues the same number
   // of requests, so the wait counts below are constants.
-  const int8_t* req_src = p.Bp + ((size_t)(n0 / QG_FRAG_COLS) + wave * RPW) * QG_FRAG_BYTES;  // wave-uniform
+  const int8_t* req_src = Bp + ((size_t)(n0 / QG_FRAG_COLS) + wave * RPW) * QG_FRAG_BYTES;  // wave-uniform
   int req_kb = 0;
   const unsigned ring_w = lds_addr(ring) + wave * RPW * QG_FRAG_BYTES;
   auto request_slab = [&](int slot) {
@@ -173,35 +180,51 @@ __global__ __launch_bounds__(WM* WN * 64) void qg_conv_patch_kernel(const qg_gem
   };
 #pragma unroll
   for (int u = 0; u < NSTAGE - 1; ++u) request_slab(u);
-
   // the row of (flipped) theta_A bytes
   for (int c = tid; c < (ps >> 2); c += NT)
-    reinterpret_cast<unsigned*>(theta_s)[c] = ((unsigned)(p.cv_azp & 255) * 0x01010101u) ^ 0x80808080u;
+    reinterpret_cast<unsigned*>(theta_s)[c] = ((unsigned)azp * 0x01010101u) ^ 0x80808080u;
 
-  // ---- this lane's pixels: patch address of tap (0, 0), and which filter rows / columns lie inside the image
+  // ---- this lane's pixels: patch address of tap (0, 0), and which taps lie inside the image.  The wave's first
+  // pixel is divided once (wave-uniform), the lanes walk on from there.
   unsigned pixaddr[MB], tapok[MB];  // tapok: bit t = tap t (row major) lies inside the image
+  {
+    const int mw = min(m0 + wave_m * MB * 32, npix - 1);
+    const int wo0 = mw % W, ho0 = (mw / W) % H;
 #pragma unroll
-  for (int mb = 0; mb < MB; ++mb) {
-    const int lp = (wave_m * MB + mb) * 32 + l32;
-    const int m = min(m0 + lp, npix - 1);
-    const int wo = m % W, ho = (m / W) % H;
-    unsigned rows = 0, cols = 0;
-    for (int kh = 0; kh < R; ++kh) rows |= ((unsigned)(ho + kh - p.cv_pad) < (unsigned)H ? 1u : 0u) << kh;
-    for (int kw = 0; kw < S; ++kw) cols |= ((unsigned)(wo + kw - p.cv_pad) < (unsigned)W ? 1u : 0u) << kw;
-    unsigned mask = 0;
-    for (int kh = 0; kh < R; ++kh) mask |= ((rows >> kh) & 1u ? cols : 0u) << (kh * S);
-    tapok[mb] = mask;
-    pixaddr[mb] = (unsigned)(theta_bytes + lp * ps + lg * 16);
+    for (int mb = 0; mb < MB; ++mb) {
+      const int lp = (wave_m * MB + mb) * 32 + l32;
+      int wo = wo0 + mb * 32 + l32, ho = ho0;
+      while (wo >= W) {
+        wo -= W;
+        ho = ho + 1 == H ? 0 : ho + 1;
+      }
+      // filter rows kh with 0 <= ho + kh - pad < H: bits [max(pad - ho, 0), min(H + pad - ho, R)); columns alike
+      const unsigned rows = ((1u << min(H + pad - ho, R)) - 1u) & ~((1u << max(pad - ho, 0)) - 1u);
+      const unsigned cols = ((1u << min(W + pad - wo, S)) - 1u) & ~((1u << max(pad - wo, 0)) - 1u);
+      unsigned mask = 0;
+      for (int kh = 0; kh < R; ++kh) mask |= ((rows >> kh) & 1u ? cols : 0u) << (kh * S);
+      tapok[mb] = m0 + lp < npix ? mask : 0u;  // rows past the last pixel read the theta row
+      pixaddr[mb] = (unsigned)(theta_bytes + lp * ps + lg * 16);
+    }
   }
 
-  // ---- the patch has landed (the weight slabs may still be in flight): flip its bytes, sum its pixels
-  wait_vmcnt<(NSTAGE - 1) * RPW>();
-  __syncthreads();
-  static_assert(TN <= NT, "one column constant per thread");
-  if (tid < TN) {
-    cj_s[tid] = (p.bias ? cj_s[tid] : 0) - p.a_zp_m128 * coff_s[tid];
-    nbz_s[tid] = -nbz_s[tid];
+  // The column constants of the output pipeline (first use of the arguments that are not preloaded): four arrays of
+  // TN entries, 64 per request, straight to LDS like everything else, so every wait below is a constant count.
+  // They are needed after the main loop.
+#pragma unroll
+  for (int i = 0; i < CPW; ++i) {
+    const int q = wave + i * NW, arr = q / PARTS, part = q % PARTS;
+    const int oc = min(n0 + part * 64 + lane, N - 1);  // columns past N read a valid entry that is never used
+    const void* src = arr == 0 ? (const void*)((p.bias ? p.bias : p.col_off) + oc)
+                    : arr == 1 ? (const void*)(p.bzp + oc)
+                    : arr == 2 ? (const void*)(p.scales + (size_t)oc * p.scale_stride)
+                               : (const void*)(p.col_off + oc);
+    request4(src, lds_addr(cj_s + arr * TN + part * 64));
   }
+
+  // ---- the patch has landed (weights and constants may still be in flight): flip its bytes, sum its pixels
+  wait_vmcnt<(NSTAGE - 1) * RPW + CPW>();
+  __syncthreads();
   for (int pp = tid; pp < npp; pp += NT) {
     unsigned char* const px = patch + pp * ps;
     unsigned sum = 0;
@@ -218,34 +241,51 @@ __global__ __launch_bounds__(WM* WN * 64) void qg_conv_patch_kernel(const qg_gem
     }
     if (HAS_BZP) psum_s[pp] = (int)sum;
   }
-  __syncthreads();
+  // everything requested so far has landed; the column constants become what the output pipeline uses
+  wait_vmcnt<0>();
+  __syncthreads();  // flipped patch, pixel sums, everybody's constants
+  static_assert(TN <= NT, "one column constant per thread");
+  if (tid < TN) {
+    cj_s[tid] = (p.bias ? cj_s[tid] : 0) - p.a_zp_m128 * coff_s[tid];
+    nbz_s[tid] = -nbz_s[tid];
+  }
+  // row offsets of this lane's pixels, int8 domain: sum over the taps of (channel sum, or Cin * theta_A outside) - 128 K.
+  // A filter row's reads are issued together (up to five columns; a column the filter does not have reads the last
+  // one again and counts nothing), so the loop pays one LDS latency per filter row.
+  int rsum[MB];
   if (HAS_BZP) {
-    // row offsets in the int8 domain: sum over the taps of (channel sum, or Cin * theta_A outside) - 128 * K
-    for (int r = tid; r < TP; r += NT) {
-      const int m = min(m0 + r, npix - 1);
-      const int wo = m % W, ho = (m / W) % H;
-      int sum = -128 * p.K;
-      for (int kh = 0; kh < R; ++kh)
-        for (int kw = 0; kw < S; ++kw) {
-          const bool ok = (unsigned)(ho + kh - p.cv_pad) < (unsigned)H && (unsigned)(wo + kw - p.cv_pad) < (unsigned)W;
-          sum += ok ? psum_s[r + kh * W + kw] : p.cv_Cin * (p.cv_azp & 255);
+    const int outside = Cin * azp;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) rsum[mb] = -128 * K;
+    const int* const ps0 = psum_s + (wave_m * MB) * 32 + l32;
+    for (int kh = 0; kh < R; ++kh) {
+      int v[MB][5];
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int j = 0; j < 5; ++j) v[mb][j] = ps0[mb * 32 + kh * W + min(j, S - 1)];
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int j = 0; j < 5; ++j) {
+          const int here = (tapok[mb] >> (kh * S + min(j, S - 1))) & 1u ? v[mb][j] : outside;
+          rsum[mb] += j < S ? here : 0;
         }
-      rsum_s[r] = sum;
     }
   }
-
-  // the accumulators start at bias - (theta_A - 128) * column offset, so the output pipeline adds nothing
-  v16i acc[MB][NBW];
+  __syncthreads();  // cj_s, nbz_s
+  // The accumulators start at bias - (theta_A - 128) * column offset: it is the C operand of the first step's MFMAs
+  // (no instruction to initialise them, nothing to add in the output pipeline).
+  v16i cj0[NBW];
 #pragma unroll
   for (int nb = 0; nb < NBW; ++nb)
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const v4i cj = *reinterpret_cast<const v4i*>(&cj_s[(wave_n * NBW + nb) * 32 + 16 * lg + 4 * q]);
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc[mb][nb][4 * q + r] = cj[r];
+      for (int r = 0; r < 4; ++r) cj0[nb][4 * q + r] = cj[r];
     }
+  v16i acc[MB][NBW];
 
   // ---- main loop: one weight slab (two MFMA k steps of 32) per barrier.  The operand fragments of a step are read
   // from LDS one step ahead of their MFMAs, so slab kb + 1 must have landed when slab kb is consumed: one slab
@@ -265,7 +305,7 @@ __global__ __launch_bounds__(WM* WN * 64) void qg_conv_patch_kernel(const qg_gem
     }
   };
   constexpr int CSTEP = C64 ? 64 : 32;
-  const int ncc = p.cv_Cin / CSTEP;
+  const int ncc = Cin / CSTEP;
   const unsigned row_step = (unsigned)((W - S + 1) * ps);
   auto advance = [&]() {  // on to the next channel block, or the next tap
     if (++cc == ncc) {
@@ -289,22 +329,21 @@ __global__ __launch_bounds__(WM* WN * 64) void qg_conv_patch_kernel(const qg_gem
     for (int nb = 0; nb < NBW; ++nb)
       bf[nb] = *reinterpret_cast<const v4i*>(smem + b_lane + slot * STAGE + ks * 512 + nb * 2 * QG_FRAG_BYTES);
   };
-  auto mfmas = [&](const v4i(&af)[MB], const v4i(&bf)[NBW]) {
+  auto mfmas = [&](const v4i(&af)[MB], const v4i(&bf)[NBW], auto first_tag) {
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-      for (int nb = 0; nb < NBW; ++nb) acc[mb][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf[nb], af[mb], acc[mb][nb], 0, 0, 0);
+      for (int nb = 0; nb < NBW; ++nb)
+        acc[mb][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf[nb], af[mb], decltype(first_tag)::value ? cj0[nb] : acc[mb][nb], 0, 0, 0);
   };
   set_tap();
-  wait_vmcnt<(NSTAGE - 2) * RPW>();  // this wave's share of slab 0 has landed ...
-  __syncthreads();                   // ... and everybody's; row offsets and flipped patch are complete
   v4i a0[MB], b0[NBW], a1[MB], b1[NBW];
   read_a(a0, 0);
   read_b(b0, 0, 0);
   if (!C64) advance();
   int kb = 0;
   // one slab, in ring slot U; false after the last
-  auto slab = [&](auto u_tag) {
+  auto slab = [&](auto u_tag, auto first_tag) {
     constexpr int U = decltype(u_tag)::value, U1 = (U + 1) % NSTAGE, UR = (U + NSTAGE - 1) % NSTAGE;
     // slab kb + 1 has landed (this wave's share, then everybody's); every fragment of slab kb - 1 has been consumed
     wait_vmcnt<(NSTAGE - 3) * RPW>();
@@ -317,42 +356,50 @@ __global__ __launch_bounds__(WM* WN * 64) void qg_conv_patch_kernel(const qg_gem
     if (C64) {
       read_a(a1, 32);
       read_b(b1, U, 1);
-      mfmas(a0, b0);
+      mfmas(a0, b0, first_tag);
       advance();
       read_a(a0, 0);
       read_b(b0, U1, 0);
-      mfmas(a1, b1);
+      mfmas(a1, b1, std::false_type{});
     } else {
       read_a(a1, 0);
       read_b(b1, U, 1);
       advance();
-      mfmas(a0, b0);
+      mfmas(a0, b0, first_tag);
       read_a(a0, 0);
       read_b(b0, U1, 0);
       advance();
-      mfmas(a1, b1);
+      mfmas(a1, b1, std::false_type{});
     }
-    return ++kb < nkb;
+    ++kb;
+    return kb < nkb;
   };
-  while (once_round_the_ring(slab, std::make_integer_sequence<int, NSTAGE>{})) {
+  // the first slab starts the accumulators; then the rest of the first round of the ring, then whole rounds
+  if (slab(std::integral_constant<int, 0>{}, std::true_type{}) &&
+      rest_of_the_ring(slab, std::make_integer_sequence<int, NSTAGE - 1>{})) {
+    while (once_round_the_ring(slab, std::make_integer_sequence<int, NSTAGE>{})) {
+    }
   }
   wait_vmcnt<0>();  // the requests past the last slab: nothing may be in flight into LDS when the workgroup ends
 
   // ---- output pipeline: lane (pixel l32, half lg) holds 16 consecutive output channels of its pixel per block
   const float czp_f = (float)p.c_zp;
-  auto pipeline = [&](auto lo_tag) {
-    constexpr bool LO = decltype(lo_tag)::value;
+  // form 0: explicit lower clamp (ReLU with theta_C != 0); 1: the saturating convert clamps; 2: theta_C == 0, the
+  // saturating convert also rounds (qg_requant_pack0)
+  auto pipeline = [&](auto form_tag) {
+    constexpr int FORM = decltype(form_tag)::value;
+    constexpr bool LO = FORM == 0;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
       const int lp = (wave_m * MB + mb) * 32 + l32;
       const int row = m0 + lp;
+      const int rs = HAS_BZP ? rsum[mb] : 0;
       if (row >= npix) continue;
-      const int rsum = HAS_BZP ? rsum_s[lp] : 0;
 #pragma unroll
       for (int nb = 0; nb < NBW; ++nb) {
         const int c_l = (wave_n * NBW + nb) * 32 + 16 * lg;
         const int col = n0 + c_l;
-        if (col >= p.N) continue;
+        if (col >= N) continue;
         unsigned out[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -360,31 +407,41 @@ __global__ __launch_bounds__(WM* WN * 64) void qg_conv_patch_kernel(const qg_gem
           int x0 = acc[mb][nb][4 * q + 0], x1 = acc[mb][nb][4 * q + 1], x2 = acc[mb][nb][4 * q + 2], x3 = acc[mb][nb][4 * q + 3];
           if (HAS_BZP) {
             const v4i nbz = *reinterpret_cast<const v4i*>(&nbz_s[c_l + 4 * q]);
-            x0 += __mul24(nbz.x, rsum);  // |theta_B| <= 255, |row offset| <= 128 * K < 2^23
-            x1 += __mul24(nbz.y, rsum);
-            x2 += __mul24(nbz.z, rsum);
-            x3 += __mul24(nbz.w, rsum);
+            x0 += __mul24(nbz.x, rs);  // |theta_B| <= 255, |row offset| <= 128 * K < 2^23
+            x1 += __mul24(nbz.y, rs);
+            x2 += __mul24(nbz.z, rs);
+            x3 += __mul24(nbz.w, rs);
           }
-          unsigned w = qg_requant_pack<LO>(x0, sc.x, p.clamp_lo, p.clamp_hi, czp_f, 0, 0);
-          w = qg_requant_pack<LO>(x1, sc.y, p.clamp_lo, p.clamp_hi, czp_f, 1, w);
-          w = qg_requant_pack<LO>(x2, sc.z, p.clamp_lo, p.clamp_hi, czp_f, 2, w);
-          out[q] = qg_requant_pack<LO>(x3, sc.w, p.clamp_lo, p.clamp_hi, czp_f, 3, w);
+          unsigned w;
+          if (FORM == 2) {
+            w = qg_requant_pack0(x0, sc.x, 0, 0);
+            w = qg_requant_pack0(x1, sc.y, 1, w);
+            w = qg_requant_pack0(x2, sc.z, 2, w);
+            out[q] = qg_requant_pack0(x3, sc.w, 3, w);
+          } else {
+            w = qg_requant_pack<LO>(x0, sc.x, p.clamp_lo, p.clamp_hi, czp_f, 0, 0);
+            w = qg_requant_pack<LO>(x1, sc.y, p.clamp_lo, p.clamp_hi, czp_f, 1, w);
+            w = qg_requant_pack<LO>(x2, sc.z, p.clamp_lo, p.clamp_hi, czp_f, 2, w);
+            out[q] = qg_requant_pack<LO>(x3, sc.w, p.clamp_lo, p.clamp_hi, czp_f, 3, w);
+          }
         }
         uint8_t* dst = p.C + (size_t)row * p.ldc + col;
-        if (p.c_vec && col + 16 <= p.N) {
+        if (p.c_vec && col + 16 <= N) {
           *reinterpret_cast<uint4*>(dst) = make_uint4(out[0], out[1], out[2], out[3]);
         } else {
 #pragma unroll
           for (int i = 0; i < 16; ++i)
-            if (col + i < p.N) dst[i] = (uint8_t)(out[i >> 2] >> (8 * (i & 3)));
+            if (col + i < N) dst[i] = (uint8_t)(out[i >> 2] >> (8 * (i & 3)));
         }
       }
     }
   };
   if (qg_requant_needs_lo(p.clamp_lo, czp_f))
-    pipeline(std::true_type{});
+    pipeline(std::integral_constant<int, 0>{});
+  else if (p.c_zp != 0)
+    pipeline(std::integral_constant<int, 1>{});
   else
-    pipeline(std::false_type{});
+    pipeline(std::integral_constant<int, 2>{});
 }
 
 constexpr int k_lds_limit = 160 * 1024;
@@ -396,7 +453,7 @@ int patch_smem(const qg_gemm_args& a, int* ps_out, int* chunks_out) {
   const int nc = a.cv_Cin / 16, psc = nc | 1, ps = psc * 16;
   const long long pixels = (long long)TP + (long long)(a.cv_R - 1) * a.cv_W + (a.cv_S - 1);
   const long long chunks = (pixels * psc + NT - 1) / NT * NT;
-  const long long bytes = ((ps + 63) & ~63) + chunks * 16 + (long long)ring_slabs(TN) * TN * QG_FRAG_K + 16 * TN + 4 * (TP + pixels);
+  const long long bytes = ((ps + 63) & ~63) + chunks * 16 + (long long)ring_slabs(TN) * TN * QG_FRAG_K + 16 * TN + 4 * pixels;
   if (bytes > k_lds_limit) return 0;
   *ps_out = ps;
   *chunks_out = (int)chunks;
@@ -409,13 +466,14 @@ hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   int ps = 0, chunks = 0;
   const int smem = patch_smem<WM, WN, MB, NBW>(a, &ps, &chunks);
   if (smem == 0) return hipErrorInvalidValue;
-  const int halo = a.cv_pad * a.cv_W + a.cv_pad;
   const unsigned grid = (unsigned)((a.M + TP - 1) / TP) * (unsigned)((a.N + TN - 1) / TN);
   auto go = [&](auto bzp_tag, auto c64_tag) {
     constexpr bool BZP = decltype(bzp_tag)::value, C64 = decltype(c64_tag)::value;
     const hipError_t e = qg_allow_smem<qg_conv_patch_kernel<WM, WN, MB, NBW, BZP, C64>>(smem);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((qg_conv_patch_kernel<WM, WN, MB, NBW, BZP, C64>), dim3(grid), dim3(WM * WN * 64), smem, s, a, ps, chunks, halo);
+    const int geom = a.cv_R | a.cv_S << 8 | a.cv_pad << 16 | (a.cv_azp & 255) << 24;
+    hipLaunchKernelGGL((qg_conv_patch_kernel<WM, WN, MB, NBW, BZP, C64>), dim3(grid), dim3(WM * WN * 64), smem, s, a.A, a.Bp, a.M,
+                       a.cv_W, a.cv_H, a.N, a.nb16, a.cv_Cin | a.cv_pix << 16, geom, a);
     return hipGetLastError();
   };
   const bool c64 = a.cv_Cin % 64 == 0;
@@ -429,7 +487,7 @@ hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
 // channels, 1 = 256 x 64, 2 = 256 x 128 (eight waves).
 bool qg_conv_patch_applies(const qg_gemm_args& a, int form) {
   if (a.cv_stride != 1 || a.cv_R != a.cv_S || a.cv_R % 2 == 0 || 2 * a.cv_pad != a.cv_R - 1 || a.cv_R * a.cv_S > 28) return false;  // a bit per tap, and a few taps past the last
-  if (a.cv_Ho != a.cv_H || a.cv_Wo != a.cv_W || a.cv_Cin % 32 != 0 || a.cv_pix % 16 != 0) return false;
+  if (a.cv_Ho != a.cv_H || a.cv_Wo != a.cv_W || a.cv_Cin % 32 != 0 || a.cv_pix % 16 != 0 || a.cv_pix >= 65536) return false;
   if (((uintptr_t)a.A & 15) != 0 || a.K != a.cv_R * a.cv_S * a.cv_Cin) return false;
   int ps, chunks;
   switch (form) {
