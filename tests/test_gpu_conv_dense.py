@@ -1,6 +1,7 @@
 """GPU parity of the dense (one group) convolution with fused im2col against the CPU oracle's direct
 7-loop convolution: identical bytes."""
 import ctypes
+import dataclasses
 
 import numpy as np
 import pytest
@@ -119,9 +120,59 @@ def test_dense_conv_errors(env):
     assert L(inp.data_ptr() + 4, 1, 5, 5, 64, 3, 3, 1, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, t64) == q.EUNSUPPORTED
     assert L(inp.data_ptr(), 1, 1, 1, 64, 3, 3, 0, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None, 0) == q.EINVAL  # filter larger than image
     ok = (inp.data_ptr(), 1, 5, 5, 64, 3, 3, 1, 1, Wp.handle, ctypes.byref(p), out.data_ptr(), None)
-    assert L(*ok, q.KERNEL_LAST + 1) == q.EINVAL and L(*ok, -1) == q.EINVAL
+    assert L(*ok, q.KERNEL_CONV_LAST + 1) == q.EINVAL and L(*ok, -1) == q.EINVAL
     assert L(*ok, q.kernel_id("tile256")) == q.EUNSUPPORTED
     torch.cuda.synchronize()
+
+
+PATCH_KERNELS = ["patch128", "patch256x64", "patch256"]
+
+
+@pytest.mark.parametrize("cfg", [
+    dict(Nb=2, H=7, W=9, C=64, Cout=64),                          # ragged pixel count, borders on every side
+    dict(Nb=1, H=3, W=3, C=64, Cout=16),                          # every pixel but the centre sees padding
+    dict(Nb=1, H=12, W=10, C=128, Cout=40),                       # two slabs per tap, ragged Cout
+    dict(Nb=3, H=9, W=9, C=32, Cout=96),                          # 32 channels: a slab holds two taps, K = 288 ends mid-slab
+    dict(Nb=2, H=20, W=17, C=96, Cout=200),                       # 96 channels: taps change mid-slab; several tiles and slices
+    dict(Nb=1, H=9, W=8, C=64, Cout=64, R=5, S=5, pad=2),         # 5 x 5
+    dict(Nb=5, H=14, W=14, C=256, Cout=256),                      # images end inside tiles
+    dict(Nb=1, H=1, W=1, C=32, Cout=1),                           # one pixel, one channel: only the centre tap is inside
+    dict(Nb=1, H=40, W=70, C=160, Cout=130, R=5, S=5, pad=2),     # a wide image: the patch is several times the tile
+])
+@pytest.mark.parametrize("variant", range(4))
+def test_dense_conv_patch_kernels(env, cfg, variant):
+    """The kernels that keep a pixel tile's input patch in LDS, every form, against the oracle's direct convolution;
+    the variants cover the three output forms (saturating convert with and without theta_C, explicit lower clamp) and
+    weights without zero points (no row offsets)."""
+    q, torch, dev, oracle = env
+    say(f"dense conv, patch kernels {cfg}, variant {variant}")
+    c = wl.random_conv(15100 + variant, G=1, per_channel=variant != 1, with_bias=variant != 2, relu=variant in (1, 3), **cfg)
+    if variant == 2:
+        c.b_zp[:] = 0
+    c = dataclasses.replace(c, c_zp=[c.c_zp, 0, 0, 7][variant])
+    ref = want(c, oracle)
+    ran = 0
+    for kernel in PATCH_KERNELS:
+        try:
+            got = run(c, q, torch, dev, kernel)
+        except q.QGemmError as e:   # a form whose patch does not fit the LDS
+            assert e.code == q.EUNSUPPORTED, f"{kernel} {cfg}"
+            continue
+        assert_same(got, ref, f"dense conv {cfg}, kernel {kernel}")
+        ran += 1
+    assert ran >= 2
+
+
+def test_dense_conv_patch_kernels_refuse_other_geometries(env):
+    q, torch, dev, oracle = env
+    for cfg in [dict(Nb=1, H=8, W=8, C=64, Cout=32, stride=2), dict(Nb=1, H=8, W=8, C=64, Cout=32, pad=0),
+                dict(Nb=1, H=8, W=8, C=48, Cout=32), dict(Nb=1, H=8, W=8, C=64, Cout=32, R=3, S=5, pad=1),
+                dict(Nb=1, H=9, W=9, C=32, Cout=32, R=7, S=7, pad=3), dict(Nb=1, H=8, W=8, C=64, Cout=32, R=1, S=1, pad=0)]:
+        c = wl.random_conv(15200, G=1, **cfg)
+        for kernel in PATCH_KERNELS:
+            with pytest.raises(q.QGemmError) as err:
+                run(c, q, torch, dev, kernel)
+            assert err.value.code == q.EUNSUPPORTED, f"{kernel} {cfg}"
 
 
 @pytest.mark.parametrize("seed", range(12))

@@ -42,7 +42,7 @@ def test_kernel_names(env):
     q = env[0]
     names = q.kernel_names()
     assert names[0] == "auto" and [names[i] for i in range(1, q.KERNEL_LAST + 1)] == KERNELS
-    assert q.lib.qg_kernel_name(q.KERNEL_LAST + 1) is None and q.lib.qg_kernel_name(-1) is None
+    assert q.lib.qg_kernel_name(q.KERNEL_CONV_LAST + 1) is None and q.lib.qg_kernel_name(-1) is None
 
 
 @pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))

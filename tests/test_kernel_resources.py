@@ -38,9 +38,9 @@ def _resources(src):
 
 @pytest.mark.timeout(600)
 def test_gemm_kernels_use_no_scratch_memory_and_spill_nothing():
-    with ThreadPoolExecutor(2) as ex:
-        tile, skinny = ex.map(_resources, ["gemm_tile.hip", "gemm_skinny.hip"])
-    assert len(tile) >= 30 and len(skinny) >= 30, "the resource report was not parsed"
-    for name, r in {**tile, **skinny}.items():
+    with ThreadPoolExecutor(3) as ex:
+        tile, skinny, patch = ex.map(_resources, ["gemm_tile.hip", "gemm_skinny.hip", "conv_patch.hip"])
+    assert len(tile) >= 30 and len(skinny) >= 30 and len(patch) >= 12, "the resource report was not parsed"
+    for name, r in {**tile, **skinny, **patch}.items():
         assert r.get("ScratchSize [bytes/lane]") == 0, f"{name} uses scratch memory: {r}"
         assert r.get("VGPRs Spill") == 0 and r.get("SGPRs Spill") == 0, f"{name} spills registers: {r}"
