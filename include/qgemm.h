@@ -430,11 +430,15 @@ int qg_conv_groupwise_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W,
  *            the matrix cores (any extents; a 3-channel first layer is its case)
  *   out_nhwc dev uint8 [Nb][Ho][Wo][Cout], Ho = (H + 2*pad - R)/stride + 1
  *   kernel   QG_KERNEL_AUTO (chosen from the extents by a cost model fitted to 3 x 3 and
- *            5 x 5 layers), or QG_KERNEL_TILE64 / TILE64K4 / TILE64X32K8 / TILE64K1 /
+ *            5 x 5 layers, the patch kernels below included), or QG_KERNEL_TILE64 / TILE64K4 / TILE64X32K8 / TILE64K1 /
  *            TILE128 / TILE128X256; every choice gives the same bytes.  The 128-row tiles run
  *            their hand-scheduled loop when Cin % 64 == 0, R*S <= 32 and K >= 256.  With
  *            Cin % 64 == 0 and R*S <= 32 the streaming kernels QG_KERNEL_SKINNY16 / 32 / 64
  *            are taken too (few output pixels and a long K; QG_EUNSUPPORTED otherwise).
+ *            QG_KERNEL_PATCH128 / PATCH256X64 / PATCH256 keep the input patch of a tile of 128 or 256
+ *            consecutive output pixels in LDS and stream only the weights: "same" convolutions
+ *            (stride 1, R == S odd, 2*pad == R - 1, R*S <= 28) with Cin % 32 == 0, pixels less
+ *            than 64 KiB apart and a patch that fits the LDS; QG_EUNSUPPORTED otherwise.
  * QG_EUNSUPPORTED for QG_KERNEL_TILE256, or an explicit kernel id with such an image;
  * QG_EINVAL when R*S*Cin differs from the K of Wp or the id is unknown. */
 int qg_conv_dense_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W, int Cin, int R, int S,
