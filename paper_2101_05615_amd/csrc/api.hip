@@ -96,12 +96,13 @@ const tile_cost k_conv_cost[] = {
 };
 // "Same" convolutions (stride 1, output as large as the input) with Cin % 32 == 0 also have the kernels that keep the
 // input patch of a pixel tile in LDS; same formula, fitted to 80 layers (3 x 3 and 5 x 5, 1 .. 32 images, 32 .. 512
-// channels) together with the kernels above: the choice is within 5 % of the measured best on 71 of them, and the
-// best kernel is one of these on 29 (up to 1.38x faster than the best of the others).
+// channels) together with the kernels above: the choice is within 5 % of the measured best on 70 of them (worst
+// 1.12x), and the best kernel is one of these on 45 (up to 1.53x faster than the best of the others).
 const tile_cost k_conv_patch_cost[] = {
-    {QG_KERNEL_PATCH128, 128, 128, 5.98, 0.225, 0.22, 1.91},
-    {QG_KERNEL_PATCH256X64, 256, 64, 6.32, 0.247, 0.315, 1.61},
-    {QG_KERNEL_PATCH256, 256, 128, 5.88, 0.36, 0.457, 2.22},
+    {QG_KERNEL_PATCH64X128, 64, 128, 4.86, 0.137, 0.119, 1.4},
+    {QG_KERNEL_PATCH128X64, 128, 64, 4.83, 0.148, 0.135, 1.32},
+    {QG_KERNEL_PATCH256X64, 256, 64, 5.5, 0.196, 0.25, 1.84},
+    {QG_KERNEL_PATCH256, 256, 128, 5.78, 0.381, 0.642, 0.756},
 };
 const stream_cost k_stream_cost[] = {
     {QG_KERNEL_SKINNY16, 16, 3.826, 3.664e-06, 5.429, 0.002625},
@@ -345,7 +346,7 @@ const char* qg_kernel_name(int kernel) {
   static const char* const names[] = {"auto",   "skinny16", "skinny32",    "skinny64",
                                       "tile64", "tile128",  "tile128x256", "tile256",
                                       "tile64k4", "tile64k1", "tile64x32k8",
-                                      "patch128", "patch256x64", "patch256"};
+                                      "patch64x128", "patch128x64", "patch256x64", "patch256"};
   return (kernel >= 0 && kernel <= QG_KERNEL_CONV_LAST) ? names[kernel] : nullptr;
 }
 
@@ -928,7 +929,7 @@ int launch_conv_gemm(const uint8_t* in, int in_bytes, int Nb, int H, int W, int 
       if (us < best_us) best_us = us, kernel = c.kernel;
     }
     for (const tile_cost& c : k_conv_patch_cost) {
-      if (!qg_conv_patch_applies(a, c.kernel - QG_KERNEL_PATCH128)) continue;
+      if (!qg_conv_patch_applies(a, c.kernel - QG_KERNEL_PATCH64X128)) continue;
       const double us = tile_estimate(c, a.M, a.N, a.K);
       if (us < best_us) best_us = us, kernel = c.kernel;
     }
@@ -938,8 +939,8 @@ int launch_conv_gemm(const uint8_t* in, int in_bytes, int Nb, int H, int W, int 
         if (ceil_div(a.M, c.rows) <= 65535 && us < best_us) best_us = us, kernel = c.kernel;
       }
   }
-  if (kernel >= QG_KERNEL_PATCH128) {
-    const int form = kernel - QG_KERNEL_PATCH128;
+  if (kernel >= QG_KERNEL_PATCH64X128) {
+    const int form = kernel - QG_KERNEL_PATCH64X128;
     if (!qg_conv_patch_applies(a, form)) return QG_EUNSUPPORTED;
     return qg_launch_conv_patch(a, form, stream) == hipSuccess ? QG_OK : QG_ELAUNCH;
   }

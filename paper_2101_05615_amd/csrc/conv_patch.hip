@@ -94,11 +94,13 @@ __global__ __launch_bounds__(WM* WN * 64) void qg_conv_patch_kernel(
   constexpr int STAGE = TN * QG_FRAG_K;           // bytes of one 64-deep slab of TN columns
   constexpr int NSTAGE = ring_slabs(TN);
   constexpr int FPS = TN / QG_FRAG_COLS;          // fragments per slab
-  static_assert(FPS % NW == 0, "every wave requests the same number of fragments per slab");
-  constexpr int RPW = FPS / NW;                   // requests per wave and slab
+  // Requests per wave: the same number for every wave that requests at all, so the waits are constant counts; with
+  // more waves than requests the first waves issue one each and the others' waits are satisfied trivially.
+  static_assert(FPS % NW == 0 || NW % FPS == 0, "whole requests per wave");
+  constexpr int RPW = FPS >= NW ? FPS / NW : 1;   // requests per (requesting) wave and slab
   constexpr int PARTS = TN / 64;                  // requests per array of column constants
-  static_assert((4 * PARTS) % NW == 0, "every wave requests the same number of constant rows");
-  constexpr int CPW = 4 * PARTS / NW;             // constant requests per wave
+  static_assert((4 * PARTS) % NW == 0 || NW % (4 * PARTS) == 0, "whole requests per wave");
+  constexpr int CPW = 4 * PARTS >= NW ? 4 * PARTS / NW : 1;  // constant requests per (requesting) wave
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -175,7 +177,7 @@ __global__ __launch_bounds__(WM* WN * 64) void qg_conv_patch_kernel(
   int req_kb = 0;
   const unsigned ring_w = lds_addr(ring) + wave * RPW * QG_FRAG_BYTES;
   auto request_slab = [&](int slot) {
-    request_kib<RPW>(req_src, (unsigned)(lane * 16), ring_w + slot * STAGE);
+    if (FPS >= NW || wave < FPS) request_kib<RPW>(req_src, (unsigned)(lane * 16), ring_w + slot * STAGE);
     req_src += ++req_kb < nkb ? b_step : 0;
   };
 #pragma unroll
@@ -213,6 +215,7 @@ __global__ __launch_bounds__(WM* WN * 64) void qg_conv_patch_kernel(
   // They are needed after the main loop.
 #pragma unroll
   for (int i = 0; i < CPW; ++i) {
+    if (FPS < NW && wave >= FPS) break;
     const int q = wave + i * NW, arr = q / PARTS, part = q % PARTS;
     const int oc = min(n0 + part * 64 + lane, N - 1);  // columns past N read a valid entry that is never used
     const void* src = arr == 0 ? (const void*)((p.bias ? p.bias : p.col_off) + oc)
@@ -223,7 +226,11 @@ __global__ __launch_bounds__(WM* WN * 64) void qg_conv_patch_kernel(
   }
 
   // ---- the patch has landed (weights and constants may still be in flight): flip its bytes, sum its pixels
-  wait_vmcnt<(NSTAGE - 1) * RPW + CPW>();
+  static_assert(4 * PARTS == FPS, "the waves that request weights are the ones that request constants");
+  if (FPS >= NW || wave < FPS)
+    wait_vmcnt<(NSTAGE - 1) * RPW + CPW>();
+  else
+    wait_vmcnt<0>();  // a wave without weight and constant requests has only its patch requests in flight
   __syncthreads();
   for (int pp = tid; pp < npp; pp += NT) {
     unsigned char* const px = patch + pp * ps;
@@ -483,17 +490,19 @@ hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
 
 }  // namespace
 
-// Whether the patch kernel takes this convolution (geometry and LDS); `form` selects the tile: 0 = 128 pixels x 128
-// channels, 1 = 256 x 64, 2 = 256 x 128 (eight waves).
+// Whether the patch kernel takes this convolution (geometry and LDS); `form` selects the workgroup's tile and waves:
+// 0 = 64 pixels x 128 channels, 1 = 128 x 64, 2 = 256 x 64 (eight waves), 3 = 256 x 128 (eight waves, 2 x 2 blocks each).
 bool qg_conv_patch_applies(const qg_gemm_args& a, int form) {
-  if (a.cv_stride != 1 || a.cv_R != a.cv_S || a.cv_R % 2 == 0 || 2 * a.cv_pad != a.cv_R - 1 || a.cv_R * a.cv_S > 28) return false;  // a bit per tap, and a few taps past the last
+  // a bit per tap, and a few taps past the last
+  if (a.cv_stride != 1 || a.cv_R != a.cv_S || a.cv_R % 2 == 0 || 2 * a.cv_pad != a.cv_R - 1 || a.cv_R * a.cv_S > 28) return false;
   if (a.cv_Ho != a.cv_H || a.cv_Wo != a.cv_W || a.cv_Cin % 32 != 0 || a.cv_pix % 16 != 0 || a.cv_pix >= 65536) return false;
   if (((uintptr_t)a.A & 15) != 0 || a.K != a.cv_R * a.cv_S * a.cv_Cin) return false;
   int ps, chunks;
   switch (form) {
-    case 0: return patch_smem<2, 2, 2, 2>(a, &ps, &chunks) != 0;
-    case 1: return patch_smem<4, 1, 2, 2>(a, &ps, &chunks) != 0;
-    case 2: return patch_smem<4, 2, 2, 2>(a, &ps, &chunks) != 0;
+    case 0: return patch_smem<2, 2, 1, 2>(a, &ps, &chunks) != 0;
+    case 1: return patch_smem<4, 1, 1, 2>(a, &ps, &chunks) != 0;
+    case 2: return patch_smem<8, 1, 1, 2>(a, &ps, &chunks) != 0;
+    case 3: return patch_smem<4, 2, 2, 2>(a, &ps, &chunks) != 0;
   }
   return false;
 }
@@ -501,8 +510,9 @@ bool qg_conv_patch_applies(const qg_gemm_args& a, int form) {
 hipError_t qg_launch_conv_patch(const qg_gemm_args& a, int form, hipStream_t s) {
   if (!qg_conv_patch_applies(a, form)) return hipErrorInvalidValue;
   switch (form) {
-    case 0: return launch<2, 2, 2, 2>(a, s);
-    case 1: return launch<4, 1, 2, 2>(a, s);
+    case 0: return launch<2, 2, 1, 2>(a, s);
+    case 1: return launch<4, 1, 1, 2>(a, s);
+    case 2: return launch<8, 1, 1, 2>(a, s);
     default: return launch<4, 2, 2, 2>(a, s);
   }
 }

@@ -125,7 +125,7 @@ def test_dense_conv_errors(env):
     torch.cuda.synchronize()
 
 
-PATCH_KERNELS = ["patch128", "patch256x64", "patch256"]
+PATCH_KERNELS = ["patch64x128", "patch128x64", "patch256x64", "patch256"]
 
 
 @pytest.mark.parametrize("cfg", [
@@ -160,7 +160,7 @@ def test_dense_conv_patch_kernels(env, cfg, variant):
             continue
         assert_same(got, ref, f"dense conv {cfg}, kernel {kernel}")
         ran += 1
-    assert ran >= 2
+    assert ran >= 3
 
 
 def test_dense_conv_patch_kernels_refuse_other_geometries(env):
