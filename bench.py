@@ -156,6 +156,21 @@ def pmc_target(which, torch, q, wl, dev):
         torch.cuda.synchronize()
         print(json.dumps({"pmc_target": which, "workload": c.name, "launches": n}))
         return
+    if which == "dconv":
+        import numpy as np
+        # a 3 x 3 layer of a ResNet-like network at batch 32 (the first dense_conv row of the default run)
+        cc = wl.random_conv(104, Nb=32, H=56, W=56, C=64, G=1, Cout=64)
+        Wd = q.pack_conv_dense_w(torch.from_numpy(np.ascontiguousarray(cc.wgt[0])).to(dev), cc.b_zp)
+        xin, scd, bd = (torch.from_numpy(x).to(dev) for x in (cc.inp, cc.scales, cc.bias))
+        yout = torch.empty((32, 56, 56, 64), dtype=torch.uint8, device=dev)
+        torch.cuda.synchronize()
+        n = 20
+        for _ in range(n):
+            q.conv_dense_u8s8_requant(xin, Wd, cc.a_zp, bd, scd, cc.c_zp, False, out=yout)
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_target": which, "workload": "dense conv 32x56x56x64->64, 3x3 s1 p1", "launches": n,
+                          "bytes": int(xin.numel() + yout.numel() + 9 * 64 * 64), "ops": 2 * 32 * 56 * 56 * 64 * 9 * 64}))
+        return
     if which in ("c2cold", "c2warm"):
         # one temperature per run, so that a kernel trace of the run holds one row for it: cold rotates over 72
         # packed copies of the weights (1.2 GB before any reuse), warm launches on one set of buffers
@@ -193,11 +208,11 @@ def main():
                     help="untimed launches before the timed ones (the clocks settle after ~75 launches of the headline kernel)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", default="", help="comma list of c1..c5 and next to restrict the side sections")
-    ap.add_argument("--pmc-target", default="", choices=["", "c2", "c3", "c4", "c5", "copy", "c2cold", "c2warm"],
+    ap.add_argument("--pmc-target", default="", choices=["", "c2", "c3", "c4", "c5", "copy", "c2cold", "c2warm", "dconv"],
                     help="run ONLY a few launches of one workload (or of a plain 256 MiB device copy, the "
                          "calibration kernel for FETCH_SIZE / WRITE_SIZE) and exit: for rocprofv3 --pmc runs; "
                          "c2cold / c2warm: 288 launches of config 2 on rotating / on resident weights, for "
-                         "rocprofv3 --kernel-trace runs")
+                         "rocprofv3 --kernel-trace runs; dconv: 20 launches of a 3 x 3 dense convolution layer")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path shards over M or N with no collective, "
