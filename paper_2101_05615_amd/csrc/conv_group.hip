@@ -527,6 +527,8 @@ template <bool HAS_BZP>
 __global__ __launch_bounds__(256) void qg_conv_dense_gather_kernel(const qg_conv_args p) {
   __shared__ __align__(16) unsigned char a_s[64 * 64];
   __shared__ __align__(16) unsigned char b_s[4 * QG_FRAG_BYTES];
+  __shared__ int cj_s[64], nbz_s[64];
+  __shared__ float sc_s[64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_m = wave & 1, wave_n = wave >> 1;
   const int l32 = lane & 31, lg = lane >> 5;
@@ -558,6 +560,13 @@ __global__ __launch_bounds__(256) void qg_conv_dense_gather_kernel(const qg_conv
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0;
   unsigned rs = 0;
+  if (tid < 64) {  // column constants of the output pipeline (visible behind the barriers of the first chunk)
+    const int col = blockIdx.y * 64 + tid;
+    const bool in = col < p.Cout;
+    cj_s[tid] = in ? (p.bias ? p.bias[col] : 0) - (p.a_zp - 128) * p.col_off[col] : 0;
+    nbz_s[tid] = in && HAS_BZP ? -p.bzp[col] : 0;
+    sc_s[tid] = in ? p.scales[(size_t)col * p.scale_stride] : 0.0f;
+  }
 
   for (int kc = 0; kc < KT; ++kc) {
     // ---- gather 16 bytes of the im2col row, copy 16 bytes of weights
@@ -615,20 +624,31 @@ __global__ __launch_bounds__(256) void qg_conv_dense_gather_kernel(const qg_conv
     }
   }
 
-  // ---- output pipeline: lane (row l32, half lg) holds 16 consecutive output channels of its pixel
+  // ---- output pipeline: lane (row l32, half lg) holds 16 consecutive output channels of its pixel; the column
+  // constants were staged by the first 64 threads while the first chunk was gathered
   const int rsum = HAS_BZP ? (int)(rs + (unsigned)__shfl_xor((int)rs, 32)) - 128 * (KT * 64) : 0;
   const int row = m0 + wave_m * 32 + l32;
-  const int col0 = n0 + wave_n * 32 + lg * 16;
-  if (row < npix) {
-    const int azp_s = p.a_zp - 128;
+  const int c_l = wave_n * 32 + lg * 16, col0 = n0 + c_l;
+  if (row < npix && col0 < p.Cout) {
+    unsigned out[4];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int col = col0 + i;
-      if (col < p.Cout) {
-        const int x = acc[i] + (p.bias ? p.bias[col] : 0) - azp_s * p.col_off[col] - (HAS_BZP ? p.bzp[col] * rsum : 0);
-        p.out[(size_t)row * p.Cout + col] =
-            (uint8_t)qg_requant_one(x, p.scales[(size_t)col * p.scale_stride], p.clamp_lo, p.clamp_hi, p.c_zp);
+    for (int q = 0; q < 4; ++q) {
+      unsigned w = 0;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int i = 4 * q + r;
+        const int x = acc[i] + cj_s[c_l + i] + (HAS_BZP ? nbz_s[c_l + i] * rsum : 0);
+        w |= (unsigned)qg_requant_one(x, sc_s[c_l + i], p.clamp_lo, p.clamp_hi, p.c_zp) << (8 * r);
       }
+      out[q] = w;
+    }
+    uint8_t* dst = p.out + (size_t)row * p.Cout + col0;
+    if (col0 + 16 <= p.Cout && (((uintptr_t)p.out | (uintptr_t)p.Cout) & 15) == 0) {
+      *reinterpret_cast<uint4*>(dst) = make_uint4(out[0], out[1], out[2], out[3]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        if (col0 + i < p.Cout) dst[i] = (uint8_t)(out[i >> 2] >> (8 * (i & 3)));
     }
   }
 }
