@@ -163,6 +163,34 @@ def test_dense_conv_patch_kernels(env, cfg, variant):
     assert ran >= 3
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_dense_conv_patch_kernels_random_same_layers(env, seed):
+    """Random "same" layers (3 x 3 and 5 x 5, any multiple of 32 channels, images from one pixel to wider than a tile)
+    through every patch form and the automatic choice."""
+    q, torch, dev, oracle = env
+    rng = np.random.default_rng(15300 + seed)
+    R = int(rng.choice([3, 3, 5]))
+    cfg = dict(Nb=int(rng.integers(1, 4)), H=int(rng.integers(1, 24)), W=int(rng.integers(1, 90)), C=32 * int(rng.integers(1, 11)),
+               Cout=int(rng.integers(1, 300)), R=R, S=R, pad=R // 2)
+    say(f"dense conv, patch kernels, random layer {cfg}")
+    c = wl.random_conv(15300 + seed, G=1, per_channel=bool(seed & 1), with_bias=bool(seed & 2), relu=bool(seed & 4), **cfg)
+    if seed % 5 == 0:
+        c.b_zp[:] = 0
+    if seed % 3 == 0:
+        c = dataclasses.replace(c, c_zp=0)
+    ref = want(c, oracle)
+    ran = 0
+    for kernel in PATCH_KERNELS + ["auto"]:
+        try:
+            got = run(c, q, torch, dev, kernel)
+        except q.QGemmError as e:   # a form whose patch does not fit the LDS
+            assert e.code == q.EUNSUPPORTED and kernel != "auto", f"{kernel} {cfg}"
+            continue
+        assert_same(got, ref, f"dense conv {cfg}, kernel {kernel}")
+        ran += 1
+    assert ran >= 3
+
+
 def test_dense_conv_patch_kernels_refuse_other_geometries(env):
     q, torch, dev, oracle = env
     for cfg in [dict(Nb=1, H=8, W=8, C=64, Cout=32, stride=2), dict(Nb=1, H=8, W=8, C=64, Cout=32, pad=0),
