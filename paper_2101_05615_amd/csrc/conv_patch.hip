@@ -148,7 +148,7 @@ __global__ __launch_bounds__(WM* WN * 64) void qg_conv_patch_kernel(
   const int m0 = tile * TP, n0 = slice * TN;
   const int lin0 = m0 - halo;  // linear index of patch pixel 0 (may be negative)
 
-  // ---- one burst of requests: the patch, then the first NSTAGE - 1 weight slabs
+  // ---- the requests of the patch, one burst
   {
     const int c = wave * 64 + lane;
     int pp = (int)((float)c / (float)psc);  // c < 2^16 and psc < 2^8: the rounded quotient is off by one at most
@@ -180,8 +180,6 @@ __global__ __launch_bounds__(WM* WN * 64) void qg_conv_patch_kernel(
     if (FPS >= NW || wave < FPS) request_kib<RPW>(req_src, (unsigned)(lane * 16), ring_w + slot * STAGE);
     req_src += ++req_kb < nkb ? b_step : 0;
   };
-#pragma unroll
-  for (int u = 0; u < NSTAGE - 1; ++u) request_slab(u);
   // the row of (flipped) theta_A bytes
   for (int c = tid; c < (ps >> 2); c += NT)
     reinterpret_cast<unsigned*>(theta_s)[c] = ((unsigned)azp * 0x01010101u) ^ 0x80808080u;
@@ -210,6 +208,10 @@ __global__ __launch_bounds__(WM* WN * 64) void qg_conv_patch_kernel(
     }
   }
 
+  // The first NSTAGE - 1 weight slabs: behind the pixel set-up, which ran while the texture addresser worked through
+  // the patch requests (a wave cannot issue past a full request queue).
+#pragma unroll
+  for (int u = 0; u < NSTAGE - 1; ++u) request_slab(u);
   // The column constants of the output pipeline (first use of the arguments that are not preloaded): four arrays of
   // TN entries, 64 per request, straight to LDS like everything else, so every wait below is a constant count.
   // They are needed after the main loop.
