@@ -72,9 +72,9 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 
 // WM x WN waves of MB x NBW blocks of 32 x 32: the workgroup owns TP = WM*MB*32 pixels x TN = WN*NBW*32 channels.
-// ps: bytes per patch pixel in LDS; patch_chunks: 16-byte chunks requested for the patch (a multiple of the
-// workgroup size); halo = pad*W + pad: pixels in front of the tile's first.  C64: Cin is a multiple of 64, so every
-// 64-deep weight slab lies inside one filter tap.
+// C64: Cin is a multiple of 64, so every 64-deep weight slab lies inside one filter tap.  (Inside: ps = bytes per
+// patch pixel in LDS; patch_chunks = 16-byte chunks requested for the patch, a multiple of the workgroup size, the
+// same formula as the host's LDS sizing; halo = pad*W + pad = pixels in front of the tile's first.)
 //
 // A wave alone on its SIMD issues one instruction every four cycles or so, an MFMA of this shape occupies the pipe
 // for 32: whatever the main loop does per MFMA beyond its operand reads costs time.  So the uint8 -> int8 shift
