@@ -541,15 +541,9 @@ __global__ __launch_bounds__(256) void qg_conv_dense_gather_kernel(const qg_conv
   const int gm = min(m0 + gr, npix - 1);
   const int gwo = gm % p.Wo, gt = gm / p.Wo;
   const int h0 = (gt % p.Ho) * p.stride - p.pad, w0 = gwo * p.stride - p.pad;
-  const uint8_t* const img = p.in + (size_t)(gt / p.Ho) * p.H * p.W * p.C;
-  // (channel, kw, kh) of this thread's first k
-  int ci, kw, kh;
-  {
-    const int k0 = gc * 16, tap = k0 / p.C;
-    ci = k0 - tap * p.C;
-    kh = tap / p.S;
-    kw = tap - kh * p.S;
-  }
+  // byte offset of pixel (h0, w0) of this row's image, as if it existed (the image is smaller than 2 GiB)
+  const int pix0 = (((gt / p.Ho) * p.H + h0) * p.W + w0) * p.C;
+  const int row_step = (p.W - p.S) * p.C;  // from the end of one filter row to the start of the next
   const int8_t* const bsrc = p.Bp + (size_t)(n0 / QG_FRAG_COLS) * QG_FRAG_BYTES + tid * 16;  // 4 KiB per chunk: 256 threads x 16 B
   const size_t b_step = (size_t)p.nb16 * QG_FRAG_BYTES;
   // whole fragments past N_pad do not exist: clamp the copy to the last fragment of the slab (its columns are never stored)
@@ -570,38 +564,34 @@ __global__ __launch_bounds__(256) void qg_conv_dense_gather_kernel(const qg_conv
 
   for (int kc = 0; kc < KT; ++kc) {
     // ---- gather 16 bytes of the im2col row, copy 16 bytes of weights
-    union {
+    struct {
       v4i v;
-      unsigned char b[16];
     } u;
     {
-      int k = kc * 64 + gc * 16;
+      // (channel, kw, kh) and byte offset of this thread's first k of the chunk, then one byte per step.  Written
+      // without branches: every byte is loaded (from offset 0 when its tap lies outside the image) and selected, the
+      // walk advances by masks; a branch per byte costs more than the load it saves.
+      const int k0 = kc * 64 + gc * 16, tap = k0 / p.C;
+      int ci = k0 - tap * p.C, kh = tap / p.S, kw = tap - kh * p.S;
+      int off = pix0 + (kh * p.W + kw) * p.C + ci;
+      const int nvalid = K - k0;  // bytes of this chunk that belong to the matrix; the rest is the K padding, 0x80
+      unsigned w[4] = {0, 0, 0, 0};
 #pragma unroll
-      for (int i = 0; i < 16; ++i, ++k) {
-        unsigned char x = 0x80;
-        if (k < K) {
-          const int hi = h0 + kh, wi = w0 + kw;
-          x = ((unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W) ? img[((size_t)hi * p.W + wi) * p.C + ci] : (unsigned char)p.a_zp;
-          if (++ci == p.C) {
-            ci = 0;
-            if (++kw == p.S) kw = 0, ++kh;
-          }
-        }
-        u.b[i] = x;
+      for (int i = 0; i < 16; ++i) {
+        const unsigned ok = -(unsigned)((int)(i < nvalid) & (int)((unsigned)(h0 + kh) < (unsigned)p.H) & (int)((unsigned)(w0 + kw) < (unsigned)p.W));
+        const unsigned byte = p.in[off & ok];  // (masks, not ?: -- the compiler turns a selected load back into a branch)
+        const unsigned other = i < nvalid ? (unsigned)p.a_zp : 0x80u;
+        w[i >> 2] |= ((byte & ok) | (other & ~ok)) << (8 * (i & 3));
+        ++off;
+        const int wrapc = -(int)(++ci == p.C);           // all ones at the last channel of a pixel
+        ci &= ~wrapc;
+        kw -= wrapc;
+        const int wrapw = wrapc & -(int)(kw == p.S);     // ... of the last pixel of a filter row
+        kw &= ~wrapw;
+        kh -= wrapw;
+        off += wrapw & row_step;
       }
-      // on to this thread's 16 k of the next chunk: 48 further
-      if (kc + 1 < KT) {
-        int adv = 48;
-        while (adv > 0) {
-          const int stepc = min(adv, p.C - ci);
-          ci += stepc;
-          adv -= stepc;
-          if (ci == p.C) {
-            ci = 0;
-            if (++kw == p.S) kw = 0, ++kh;
-          }
-        }
-      }
+      u.v = (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
     }
     const v4i bw = *reinterpret_cast<const v4i*>(bsrc_c + (size_t)kc * b_step);
     __syncthreads();  // the previous chunk's fragments have been read
