@@ -8,7 +8,12 @@ the library's built-in choice.
     python -m paper_2101_05615_amd.autotune --shapes 128x4096x4096,2048x2048x2048 --out table.json
     python -m paper_2101_05615_amd.autotune --grid --out table.json
 
-Every kernel returns identical bytes for a given input, so the table affects speed only.
+    python -m paper_2101_05615_amd.autotune --conv-grid
+
+Every kernel returns identical bytes for a given input, so the table affects speed only.  --conv-grid times every
+kernel id of the dense convolution (tiled, streaming and patch-resident kernels) and the automatic choice on a
+built-in list of layers and reports what the choice loses against the measured best (the convolution has no rule
+table: its built-in cost constants were fitted to such a run).
 """
 import argparse
 import json
@@ -104,6 +109,92 @@ def time_cold(q, torch, M, N, K, kernel="auto", seed=0, reps=3):
     return best, ncopy
 
 
+# dense convolution layers (H = W, Cin, Cout, filter, stride), each at 1, 4, 8 and 32 images
+CONV_LAYERS = [(56, 64, 64, 3, 1), (56, 64, 128, 3, 1), (56, 128, 128, 3, 1), (56, 96, 96, 3, 1), (28, 128, 128, 3, 1),
+               (28, 256, 256, 3, 1), (28, 192, 192, 3, 1), (28, 64, 64, 5, 1), (14, 256, 256, 3, 1), (14, 512, 512, 3, 1),
+               (7, 512, 512, 3, 1), (112, 64, 64, 3, 1), (112, 32, 32, 3, 1), (56, 32, 64, 3, 1), (28, 128, 256, 3, 1),
+               (56, 256, 64, 3, 1), (224, 32, 32, 3, 1), (56, 128, 32, 3, 1), (14, 160, 320, 3, 1), (28, 128, 128, 5, 1),
+               (56, 64, 128, 3, 2), (28, 128, 256, 3, 2), (14, 256, 512, 3, 2)]
+CONV_BATCHES = [1, 4, 8, 32]
+
+
+def time_conv_layer(q, torch, Nb, H, Cin, Cout, R, stride, kernels, seed=0, spin_ms=10.0):
+    """-> {kernel name: microseconds per launch} for the kernels that take the layer; a recorded graph of 20 launches,
+    replayed after spin_ms of untimed replays (settled clocks)."""
+    import time
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(seed)
+    x = torch.randint(0, 256, (Nb, H, H, Cin), dtype=torch.uint8, device=dev, generator=g)
+    w = torch.randint(-127, 128, (R, R, Cin, Cout), dtype=torch.int8, device=dev, generator=g)
+    b_zp = torch.randint(-8, 9, (Cout,), generator=torch.Generator().manual_seed(seed)).tolist()
+    Wd = q.pack_conv_dense_w(w, b_zp)
+    sc = torch.full((Cout,), 1e-4, dtype=torch.float32, device=dev)
+    Ho = (H + 2 * (R // 2) - R) // stride + 1
+    y = torch.empty((Nb, Ho, Ho, Cout), dtype=torch.uint8, device=dev)
+    out = {}
+    for k in kernels:
+        call = lambda: q.conv_dense_u8s8_requant(x, Wd, 3, None, sc, 5, False, pad=R // 2, stride=stride, out=y, kernel=k)
+        try:
+            call()
+        except q.QGemmError:
+            continue   # the kernel does not take this layer
+        torch.cuda.synchronize()
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            for _ in range(20):
+                call()
+        t_end = time.perf_counter() + spin_ms * 1e-3
+        while time.perf_counter() < t_end:
+            gr.replay()
+            torch.cuda.synchronize()
+        best = float("inf")
+        for _ in range(4):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            gr.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1) * 1e3 / 20)
+        out[k] = best
+        del gr
+    return out
+
+
+def tune_conv(q, torch, log=None):
+    names = [q.lib.qg_kernel_name(k).decode() for k in range(1, q.KERNEL_CONV_LAST + 1)]
+    names = [n for n in names if n != "tile256"]
+    rows = []
+    for Nb in CONV_BATCHES:
+        for (H, Cin, Cout, R, stride) in CONV_LAYERS:
+            if Nb * H * H * max(Cin, Cout) > 64e6:
+                continue
+            t = time_conv_layer(q, torch, Nb, H, Cin, Cout, R, stride, names + ["auto"])
+            auto = t.pop("auto")
+            best = min(t, key=t.get)
+            rows.append({"Nb": Nb, "H": H, "Cin": Cin, "Cout": Cout, "R": R, "stride": stride, "best": best, "auto_us": auto, "us": t})
+            if log:
+                log(f"{Nb:3d} x {H:3d}^2 x {Cin:3d} -> {Cout:3d}, {R}x{R} s{stride}: best {best:12s} {t[best]:7.2f} us, auto {auto:7.2f} us "
+                    f"({auto / t[best]:4.2f}x), best without the patch kernels {min(v for k, v in t.items() if not k.startswith('patch')):7.2f} us")
+    return rows
+
+
+def conv_summary(rows):
+    import math
+    wins = {}
+    for r in rows:
+        wins[r["best"]] = wins.get(r["best"], 0) + 1
+    loss = [r["auto_us"] / r["us"][r["best"]] for r in rows]
+    gain = [min(v for k, v in r["us"].items() if not k.startswith("patch")) / r["us"][r["best"]] for r in rows]
+    gm = lambda v: math.exp(sum(map(math.log, v)) / len(v))
+    out = [f"layers: {len(rows)}",
+           "fastest kernel, number of layers: " + ", ".join(f"{k} {v}" for k, v in sorted(wins.items())),
+           f"automatic choice vs measured best: geometric mean {gm(loss):.4f}x, within 5 % on {sum(l <= 1.05 for l in loss)} layers, "
+           f"worst {max(loss):.2f}x",
+           f"best kernel vs best of the kernels without a resident patch: geometric mean {gm(gain):.3f}x faster, at most {max(gain):.2f}x"]
+    return "\n".join(out)
+
+
 def tune(q, torch, shapes, kernels=None, log=None):
     names = q.kernel_names()
     kernels = kernels or [names[k] for k in range(1, q.KERNEL_LAST + 1)]
@@ -156,6 +247,8 @@ def main(argv=None):
     ap.add_argument("--small-grid", action="store_true",
                     help="the small-batch grid (M 1..64 x N 4..4096 x K 256..4096); also times the automatic choice "
                          "with cold weights and reports its fraction of the 8 TB/s HBM peak")
+    ap.add_argument("--conv-grid", action="store_true",
+                    help="dense convolution: every kernel id and the automatic choice on the built-in list of layers")
     ap.add_argument("--out", default="", help="write the dispatch table (JSON) here")
     ap.add_argument("--quiet", action="store_true", help="print only the summary")
     a = ap.parse_args(argv)
@@ -166,6 +259,13 @@ def main(argv=None):
         shapes += [(M, N, K) for M in GRID_M for N in GRID_N for K in GRID_K if 2.0 * M * N * K <= MAX_OPS]
     if a.small_grid:
         shapes += [(M, N, K) for M in SMALL_M for N in SMALL_N for K in SMALL_K]
+    if a.conv_grid:
+        rows = tune_conv(q, torch, log=None if a.quiet else (lambda s: print(s, flush=True)))
+        print(conv_summary(rows), flush=True)
+        if a.out:
+            with open(a.out, "w") as f:
+                json.dump({"device": torch.cuda.get_device_name(0), "measured": rows}, f, indent=1)
+        return 0
     if not shapes:
         ap.error("no shapes given")
     rows = tune(q, torch, shapes, log=None if a.quiet else (lambda s: print(s, flush=True)))
