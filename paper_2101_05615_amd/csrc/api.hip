@@ -96,8 +96,9 @@ const tile_cost k_conv_cost[] = {
 };
 // "Same" convolutions (stride 1, output as large as the input) with Cin % 32 == 0 also have the kernels that keep the
 // input patch of a pixel tile in LDS; same formula, fitted to 80 layers (3 x 3 and 5 x 5, 1 .. 32 images, 32 .. 512
-// channels) together with the kernels above: the choice is within 5 % of the measured best on 70 of them (worst
-// 1.12x), and the best kernel is one of these on 45 (up to 1.53x faster than the best of the others).
+// channels).  Over the 92 layers of the autotuner's convolution grid the automatic choice among all of these
+// kernels is within 5 % of the measured best on 85 (geometric mean 1.008x, worst 1.17x), and the best kernel is one
+// of these on 44 (up to 1.46x faster than the best of the others).
 const tile_cost k_conv_patch_cost[] = {
     {QG_KERNEL_PATCH64X128, 64, 128, 4.86, 0.137, 0.119, 1.4},
     {QG_KERNEL_PATCH128X64, 128, 64, 4.83, 0.148, 0.135, 1.32},
@@ -165,8 +166,13 @@ const stream_cost k_stream_cost_16wave[] = {
     {QG_KERNEL_SKINNY32, 32, 4.13, 1.99e-4, 10.33, 1.28e-3},
     {QG_KERNEL_SKINNY64, 64, 4.96, 3.88e-4, 14.26, 2.23e-3},
 };
-// what the convolution's per-lane tap addressing adds to the 16-row streaming kernel's GEMM time (measured)
-const double k_conv_stream_factor = 1.4;
+// The same kernels with the convolution's per-lane tap addressing in their requests: the streaming formula with
+// constants of their own, fitted to 72 layers (Cin % 64 == 0; 3 x 3 and 5 x 5, stride 1 and 2, 1 .. 32 images).
+const stream_cost k_conv_stream_cost[] = {
+    {QG_KERNEL_SKINNY16, 16, 5.24, 2.1e-4, 12.0, 1.4e-3},
+    {QG_KERNEL_SKINNY32, 32, 5.74, 4.39e-4, 18.2, 1.85e-3},
+    {QG_KERNEL_SKINNY64, 64, 7.35, 6.52e-4, 24.4, 4.24e-3},
+};
 
 int select_stream_kernel(int M, int N, int K) {
   int best = QG_KERNEL_SKINNY64;
@@ -919,8 +925,8 @@ int launch_conv_gemm(const uint8_t* in, int in_bytes, int Nb, int H, int W, int 
   a.cv_azp = p->a_zp;
   a.cv_in_bytes = in_bytes;
   // the tiled kernels, chosen by the same cost formula as a GEMM's; few pixels and a long K go to the 16-row streaming
-  // kernel where it applies (whole 64-channel slices, at most 32 taps), priced with the GEMM's formula for that kernel
-  // plus what the convolution's requests were measured to add
+  // kernel where it applies (whole 64-channel slices, at most 32 taps), priced with the streaming formula and the
+  // constants measured for the convolution's requests
   const bool stream_ok = Cin % QG_FRAG_K == 0 && R * S <= 32;
   if (kernel == QG_KERNEL_AUTO) {
     double best_us = 1e300;
@@ -934,8 +940,8 @@ int launch_conv_gemm(const uint8_t* in, int in_bytes, int Nb, int H, int W, int 
       if (us < best_us) best_us = us, kernel = c.kernel;
     }
     if (stream_ok)
-      for (const stream_cost& c : k_stream_cost_16wave) {
-        const double us = k_conv_stream_factor * stream_estimate(c, a.M, a.N, a.K, false);
+      for (const stream_cost& c : k_conv_stream_cost) {
+        const double us = stream_estimate(c, a.M, a.N, a.K, false);
         if (ceil_div(a.M, c.rows) <= 65535 && us < best_us) best_us = us, kernel = c.kernel;
       }
   }
