@@ -480,9 +480,10 @@ hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
     constexpr bool BZP = decltype(bzp_tag)::value, C64 = decltype(c64_tag)::value;
     const hipError_t e = qg_allow_smem<qg_conv_patch_kernel<WM, WN, MB, NBW, BZP, C64>>(smem);
     if (e != hipSuccess) return e;
-    const int geom = a.cv_R | a.cv_S << 8 | a.cv_pad << 16 | (a.cv_azp & 255) << 24;
+    const int geom = (int)((unsigned)a.cv_R | (unsigned)a.cv_S << 8 | (unsigned)a.cv_pad << 16 | ((unsigned)a.cv_azp & 255u) << 24);
+    const int cpix = (int)((unsigned)a.cv_Cin | (unsigned)a.cv_pix << 16);
     hipLaunchKernelGGL((qg_conv_patch_kernel<WM, WN, MB, NBW, BZP, C64>), dim3(grid), dim3(WM * WN * 64), smem, s, a.A, a.Bp, a.M,
-                       a.cv_W, a.cv_H, a.N, a.nb16, a.cv_Cin | a.cv_pix << 16, geom, a);
+                       a.cv_W, a.cv_H, a.N, a.nb16, cpix, geom, a);
     return hipGetLastError();
   };
   const bool c64 = a.cv_Cin % 64 == 0;
