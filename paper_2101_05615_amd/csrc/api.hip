@@ -97,8 +97,8 @@ const tile_cost k_conv_cost[] = {
 // "Same" convolutions (stride 1, output as large as the input) with Cin % 32 == 0 also have the kernels that keep the
 // input patch of a pixel tile in LDS; same formula, fitted to 80 layers (3 x 3 and 5 x 5, 1 .. 32 images, 32 .. 512
 // channels).  Over the 92 layers of the autotuner's convolution grid the automatic choice among all of these
-// kernels is within 5 % of the measured best on 85 (geometric mean 1.008x, worst 1.17x), and the best kernel is one
-// of these on 44 (up to 1.46x faster than the best of the others).
+// kernels is within 5 % of the measured best on 84 (geometric mean 1.008x, worst 1.09x), and the best kernel is one
+// of these on 44 (up to 1.45x faster than the best of the others).
 const tile_cost k_conv_patch_cost[] = {
     {QG_KERNEL_PATCH64X128, 64, 128, 4.86, 0.137, 0.119, 1.4},
     {QG_KERNEL_PATCH128X64, 128, 64, 4.83, 0.148, 0.135, 1.32},
@@ -935,8 +935,16 @@ int launch_conv_gemm(const uint8_t* in, int in_bytes, int Nb, int H, int W, int 
       if (us < best_us) best_us = us, kernel = c.kernel;
     }
     for (const tile_cost& c : k_conv_patch_cost) {
-      if (!qg_conv_patch_applies(a, c.kernel - QG_KERNEL_PATCH64X128)) continue;
-      const double us = tile_estimate(c, a.M, a.N, a.K);
+      int threads = 0;
+      const int lds = qg_conv_patch_lds_bytes(a, c.kernel - QG_KERNEL_PATCH64X128, &threads);
+      if (lds == 0) continue;
+      double us = tile_estimate(c, a.M, a.N, a.K);
+      // A wide patch leaves room for few workgroups per CU (one, from 512 channels on): what does not run side by
+      // side runs one after the other, each pass at the pace of a workgroup alone.
+      const int per_cu = max(1, min(160 * 1024 / lds, 2048 / threads));
+      const double wgs = (double)ceil_div(a.M, c.bm) * (double)ceil_div(a.N, c.bn);
+      const double passes = ceil(wgs / (256.0 * per_cu));
+      us = fmax(us, 2.5 + passes * (c.fix + ceil_div(a.K, 64) * c.lat - 2.5));
       if (us < best_us) best_us = us, kernel = c.kernel;
     }
     if (stream_ok)

@@ -495,19 +495,26 @@ hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
 
 // Whether the patch kernel takes this convolution (geometry and LDS); `form` selects the workgroup's tile and waves:
 // 0 = 64 pixels x 128 channels, 1 = 128 x 64, 2 = 256 x 64 (eight waves), 3 = 256 x 128 (eight waves, 2 x 2 blocks each).
-bool qg_conv_patch_applies(const qg_gemm_args& a, int form) {
+// Also the LDS bytes and threads of one workgroup (what decides how many of them a CU runs side by side); 0 = the
+// kernel does not take the layer.
+int qg_conv_patch_lds_bytes(const qg_gemm_args& a, int form, int* threads) {
   // a bit per tap, and a few taps past the last
-  if (a.cv_stride != 1 || a.cv_R != a.cv_S || a.cv_R % 2 == 0 || 2 * a.cv_pad != a.cv_R - 1 || a.cv_R * a.cv_S > 28) return false;
-  if (a.cv_Ho != a.cv_H || a.cv_Wo != a.cv_W || a.cv_Cin % 32 != 0 || a.cv_pix % 16 != 0 || a.cv_pix >= 65536) return false;
-  if (((uintptr_t)a.A & 15) != 0 || a.K != a.cv_R * a.cv_S * a.cv_Cin) return false;
+  if (a.cv_stride != 1 || a.cv_R != a.cv_S || a.cv_R % 2 == 0 || 2 * a.cv_pad != a.cv_R - 1 || a.cv_R * a.cv_S > 28) return 0;
+  if (a.cv_Ho != a.cv_H || a.cv_Wo != a.cv_W || a.cv_Cin % 32 != 0 || a.cv_pix % 16 != 0 || a.cv_pix >= 65536) return 0;
+  if (((uintptr_t)a.A & 15) != 0 || a.K != a.cv_R * a.cv_S * a.cv_Cin) return 0;
   int ps, chunks;
   switch (form) {
-    case 0: return patch_smem<2, 2, 1, 2>(a, &ps, &chunks) != 0;
-    case 1: return patch_smem<4, 1, 1, 2>(a, &ps, &chunks) != 0;
-    case 2: return patch_smem<8, 1, 1, 2>(a, &ps, &chunks) != 0;
-    case 3: return patch_smem<4, 2, 2, 2>(a, &ps, &chunks) != 0;
+    case 0: *threads = 256; return patch_smem<2, 2, 1, 2>(a, &ps, &chunks);
+    case 1: *threads = 256; return patch_smem<4, 1, 1, 2>(a, &ps, &chunks);
+    case 2: *threads = 512; return patch_smem<8, 1, 1, 2>(a, &ps, &chunks);
+    case 3: *threads = 512; return patch_smem<4, 2, 2, 2>(a, &ps, &chunks);
   }
-  return false;
+  return 0;
+}
+
+bool qg_conv_patch_applies(const qg_gemm_args& a, int form) {
+  int threads;
+  return qg_conv_patch_lds_bytes(a, form, &threads) != 0;
 }
 
 hipError_t qg_launch_conv_patch(const qg_gemm_args& a, int form, hipStream_t s) {
