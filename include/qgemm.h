@@ -427,8 +427,9 @@ int qg_conv_groupwise_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W,
  * qg_gemm_u8s8_requant_kernel(in, Nb*H*W, Cin, ...) with the same kernel id.
  *   in_nhwc  dev uint8 [Nb][H][W][Cin]; 16-byte aligned with Cin % 16 == 0 for the staged
  *            kernels below -- any other image runs, under QG_KERNEL_AUTO only, on a kernel
- *            that gathers the im2col rows byte by byte into LDS and multiplies them on
- *            the matrix cores (any extents; a 3-channel first layer is its case)
+ *            that gathers the im2col rows into LDS byte by byte -- four bytes at a time when
+ *            Cin % 4 == 0 and the image is 4-byte aligned -- and multiplies them on the
+ *            matrix cores (any extents; a 3- or 4-channel first layer is its case)
  *   out_nhwc dev uint8 [Nb][Ho][Wo][Cout], Ho = (H + 2*pad - R)/stride + 1
  *   kernel   QG_KERNEL_AUTO (chosen from the extents by a cost model fitted to 3 x 3 and
  *            5 x 5 layers, the patch kernels below included), or QG_KERNEL_TILE64 / TILE64K4 / TILE64X32K8 / TILE64K1 /

@@ -523,7 +523,9 @@ __global__ __launch_bounds__(256) void qg_conv_group_any_kernel(const qg_conv_ar
 // Weights: the packed (R*S*C) x Cout matrix of a GEMM descriptor.
 __device__ __forceinline__ int gather_swz(int r) { return ((r >> 1) & 3) ^ ((r >> 3) & 1); }
 
-template <bool HAS_BZP>
+// GW = bytes per gathered piece: 4 when the channel count is a multiple of 4 and the image 4-byte aligned (a piece is
+// then four channels of one tap: a first layer with its RGB input padded to four channels), else 1.
+template <bool HAS_BZP, int GW>
 __global__ __launch_bounds__(256) void qg_conv_dense_gather_kernel(const qg_conv_args p) {
   __shared__ __align__(16) unsigned char a_s[64 * 64];
   __shared__ __align__(16) unsigned char b_s[4 * QG_FRAG_BYTES];
@@ -577,13 +579,21 @@ __global__ __launch_bounds__(256) void qg_conv_dense_gather_kernel(const qg_conv
       const int nvalid = K - k0;  // bytes of this chunk that belong to the matrix; the rest is the K padding, 0x80
       unsigned w[4] = {0, 0, 0, 0};
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
+      for (int i = 0; i < 16; i += GW) {
         const unsigned ok = -(unsigned)((int)(i < nvalid) & (int)((unsigned)(h0 + kh) < (unsigned)p.H) & (int)((unsigned)(w0 + kw) < (unsigned)p.W));
-        const unsigned byte = p.in[off & ok];  // (masks, not ?: -- the compiler turns a selected load back into a branch)
-        const unsigned other = i < nvalid ? (unsigned)p.a_zp : 0x80u;
-        w[i >> 2] |= ((byte & ok) | (other & ~ok)) << (8 * (i & 3));
-        ++off;
-        const int wrapc = -(int)(++ci == p.C);           // all ones at the last channel of a pixel
+        // (masks, not ?: -- the compiler turns a selected load back into a branch)
+        if (GW == 4) {  // K is a multiple of 4 as well: a piece lies inside the matrix or in its padding as a whole
+          const unsigned piece = *reinterpret_cast<const unsigned*>(p.in + (off & ok));
+          const unsigned other = i < nvalid ? (unsigned)p.a_zp * 0x01010101u : 0x80808080u;
+          w[i >> 2] = (piece & ok) | (other & ~ok);
+        } else {
+          const unsigned byte = p.in[off & ok];
+          const unsigned other = i < nvalid ? (unsigned)p.a_zp : 0x80u;
+          w[i >> 2] |= ((byte & ok) | (other & ~ok)) << (8 * (i & 3));
+        }
+        off += GW;
+        ci += GW;
+        const int wrapc = -(int)(ci == p.C);             // all ones behind the last channel of a pixel
         ci &= ~wrapc;
         kw -= wrapc;
         const int wrapw = wrapc & -(int)(kw == p.S);     // ... of the last pixel of a filter row
@@ -648,10 +658,18 @@ __global__ __launch_bounds__(256) void qg_conv_dense_gather_kernel(const qg_conv
 hipError_t qg_launch_conv_dense_plain(const qg_conv_args& a, hipStream_t s) {
   const int npix = a.Nb * a.Ho * a.Wo;
   const dim3 grid((unsigned)((npix + 63) / 64), (unsigned)((a.Cout + 63) / 64));
-  if (a.has_bzp)
-    hipLaunchKernelGGL(qg_conv_dense_gather_kernel<true>, grid, dim3(256), 0, s, a);
-  else
-    hipLaunchKernelGGL(qg_conv_dense_gather_kernel<false>, grid, dim3(256), 0, s, a);
+  const bool words = a.C % 4 == 0 && ((uintptr_t)a.in & 3) == 0;
+  if (a.has_bzp) {
+    if (words)
+      hipLaunchKernelGGL((qg_conv_dense_gather_kernel<true, 4>), grid, dim3(256), 0, s, a);
+    else
+      hipLaunchKernelGGL((qg_conv_dense_gather_kernel<true, 1>), grid, dim3(256), 0, s, a);
+  } else {
+    if (words)
+      hipLaunchKernelGGL((qg_conv_dense_gather_kernel<false, 4>), grid, dim3(256), 0, s, a);
+    else
+      hipLaunchKernelGGL((qg_conv_dense_gather_kernel<false, 1>), grid, dim3(256), 0, s, a);
+  }
   return hipGetLastError();
 }
 

@@ -231,6 +231,10 @@ def test_dense_conv_random_extents_any_multiple_of_16_channels(env, seed):
     dict(Nb=2, H=13, W=13, C=5, Cout=70, R=3, S=3, pad=0, stride=3),    # taps that straddle the 16-byte pieces
     dict(Nb=1, H=10, W=12, C=17, Cout=64, R=3, S=1, pad=1),             # 17 channels: every piece starts mid-pixel
     dict(Nb=1, H=1, W=1, C=3, Cout=1, R=1, S=1, pad=0),                 # one output byte
+    dict(Nb=2, H=19, W=15, C=4, Cout=64, R=7, S=7, pad=3, stride=2),    # RGB padded to four channels: gathered in 4-byte pieces
+    dict(Nb=1, H=9, W=10, C=12, Cout=40, R=3, S=3, pad=1),              # 12 channels: taps change inside a thread's 16 bytes
+    dict(Nb=2, H=6, W=7, C=20, Cout=33, R=5, S=3, pad=1, stride=2),     # K = 300: the last block ends mid-thread
+    dict(Nb=1, H=5, W=5, C=8, Cout=16, R=1, S=1, pad=0),                # 1 x 1 on 8 channels
 ])
 @pytest.mark.parametrize("variant", range(3))
 def test_dense_conv_any_channel_count_on_the_gathering_kernel(env, cfg, variant):
@@ -240,6 +244,24 @@ def test_dense_conv_any_channel_count_on_the_gathering_kernel(env, cfg, variant)
     if variant == 2:   # all weight zero points zero: the variant without row offsets
         c.b_zp[:] = 0
     assert_same(run(c, q, torch, dev, "auto"), want(c, oracle), f"dense conv {cfg}")
+
+
+def test_dense_conv_four_channel_image_off_a_4_byte_boundary(env):
+    """Cin = 4 with the image 2 bytes off a 4-byte boundary: the gathering kernel's byte form, not its 4-byte form."""
+    q, torch, dev, oracle = env
+    c = wl.random_conv(17, Nb=2, H=9, W=8, C=4, G=1, Cout=32, R=5, S=5, pad=2)
+    Wp = q.pack_conv_dense_w(torch.from_numpy(np.ascontiguousarray(c.wgt[0])).to(dev), c.b_zp)
+    store = torch.zeros(c.inp.size + 16, dtype=torch.uint8, device=dev)
+    store[2:2 + c.inp.size] = torch.from_numpy(c.inp.reshape(-1)).to(dev)
+    out = torch.empty((2, 9, 8, 32), dtype=torch.uint8, device=dev)
+    sc = torch.from_numpy(c.scales).to(dev)
+    bias = torch.from_numpy(c.bias).to(dev)
+    p = q.RequantParams(c.a_zp, bias.data_ptr(), sc.data_ptr(), sc.numel(), c.c_zp, int(c.relu))
+    rc = q.lib.qg_conv_dense_u8s8_requant(store.data_ptr() + 2, 2, 9, 8, 4, 5, 5, c.pad, c.stride, Wp.handle, ctypes.byref(p),
+                                          out.data_ptr(), None, 0)
+    assert rc == q.OK
+    torch.cuda.synchronize()
+    assert_same(out.cpu().numpy(), want(c, oracle), "four channels, image 2 bytes off a 4-byte boundary")
 
 
 def test_dense_conv_unaligned_image_on_the_gathering_kernel(env):
