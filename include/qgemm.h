@@ -203,12 +203,14 @@ int qg_gemm_u8s8_acc32(const uint8_t* A_dev, int M, int lda, const qg_packed_b* 
 #define QG_KERNEL_TILE64X32K8 10
 #define QG_KERNEL_LAST 10
 /* Dense convolution only (qg_conv_dense_u8s8_requant): the kernels that keep the input patch of a pixel tile in LDS;
- * workgroup = 64 pixels x 128 channels, 128 x 64, 256 x 64 (eight waves), 256 x 128 (eight waves). */
+ * workgroup = 64 pixels x 128 channels, 128 x 64, 256 x 64 (eight waves), 256 x 128 (eight waves), 512 x 128 (eight
+ * waves of 128 x 64: the form for many pixels and at least 96 output channels). */
 #define QG_KERNEL_PATCH64X128 11
 #define QG_KERNEL_PATCH128X64 12
 #define QG_KERNEL_PATCH256X64 13
 #define QG_KERNEL_PATCH256 14
-#define QG_KERNEL_CONV_LAST 14
+#define QG_KERNEL_PATCH512 15
+#define QG_KERNEL_CONV_LAST 15
 
 /* Name of a kernel id ("skinny16", "tile128x256", "patch128x64", ...; "auto" for 0), NULL if invalid. */
 const char* qg_kernel_name(int kernel);
@@ -437,8 +439,8 @@ int qg_conv_groupwise_u8s8_requant(const uint8_t* in_nhwc, int Nb, int H, int W,
  *            their hand-scheduled loop when Cin % 64 == 0, R*S <= 32 and K >= 256.  With
  *            Cin % 64 == 0 and R*S <= 32 the streaming kernels QG_KERNEL_SKINNY16 / 32 / 64
  *            are taken too (few output pixels and a long K; QG_EUNSUPPORTED otherwise).
- *            QG_KERNEL_PATCH64X128 / PATCH128X64 / PATCH256X64 / PATCH256 keep the input patch of a tile of 64 to 256
- *            consecutive output pixels in LDS and stream only the weights: "same" convolutions
+ *            QG_KERNEL_PATCH64X128 / PATCH128X64 / PATCH256X64 / PATCH256 / PATCH512 keep the input patch of a tile
+ *            of 64 to 512 consecutive output pixels in LDS and stream only the weights: "same" convolutions
  *            (stride 1, R == S odd, 2*pad == R - 1, R*S <= 28) with Cin % 32 == 0, pixels less
  *            than 64 KiB apart and a patch that fits the LDS; QG_EUNSUPPORTED otherwise.
  * QG_EUNSUPPORTED for QG_KERNEL_TILE256, or an explicit kernel id with such an image;

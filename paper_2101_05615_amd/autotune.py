@@ -114,7 +114,7 @@ CONV_LAYERS = [(56, 64, 64, 3, 1), (56, 64, 128, 3, 1), (56, 128, 128, 3, 1), (5
                (28, 256, 256, 3, 1), (28, 192, 192, 3, 1), (28, 64, 64, 5, 1), (14, 256, 256, 3, 1), (14, 512, 512, 3, 1),
                (7, 512, 512, 3, 1), (112, 64, 64, 3, 1), (112, 32, 32, 3, 1), (56, 32, 64, 3, 1), (28, 128, 256, 3, 1),
                (56, 256, 64, 3, 1), (224, 32, 32, 3, 1), (56, 128, 32, 3, 1), (14, 160, 320, 3, 1), (28, 128, 128, 5, 1),
-               (56, 64, 128, 3, 2), (28, 128, 256, 3, 2), (14, 256, 512, 3, 2)]
+               (56, 64, 128, 3, 2), (28, 128, 256, 3, 2), (14, 256, 512, 3, 2), (112, 128, 128, 3, 1), (56, 256, 256, 3, 1)]
 CONV_BATCHES = [1, 4, 8, 32]
 
 

@@ -96,14 +96,15 @@ const tile_cost k_conv_cost[] = {
 };
 // "Same" convolutions (stride 1, output as large as the input) with Cin % 32 == 0 also have the kernels that keep the
 // input patch of a pixel tile in LDS; same formula, fitted to 80 layers (3 x 3 and 5 x 5, 1 .. 32 images, 32 .. 512
-// channels).  Over the 92 layers of the autotuner's convolution grid the automatic choice among all of these
-// kernels is within 5 % of the measured best on 84 (geometric mean 1.008x, worst 1.09x), and the best kernel is one
-// of these on 44 (up to 1.45x faster than the best of the others).
+// channels; the 512 x 128 form to the layers of the autotuner's convolution grid).  Over the 100 layers of that grid
+// the automatic choice among all of these kernels is within 5 % of the measured best on 91 (geometric mean 1.011x,
+// worst 1.09x), and the best kernel is one of these on 50 (up to 1.54x faster than the best of the others).
 const tile_cost k_conv_patch_cost[] = {
     {QG_KERNEL_PATCH64X128, 64, 128, 4.86, 0.137, 0.119, 1.4},
     {QG_KERNEL_PATCH128X64, 128, 64, 4.83, 0.148, 0.135, 1.32},
     {QG_KERNEL_PATCH256X64, 256, 64, 5.5, 0.196, 0.25, 1.84},
     {QG_KERNEL_PATCH256, 256, 128, 5.78, 0.381, 0.642, 0.756},
+    {QG_KERNEL_PATCH512, 512, 128, 10.0, 0.603, 0.973, 3.72},
 };
 const stream_cost k_stream_cost[] = {
     {QG_KERNEL_SKINNY16, 16, 3.826, 3.664e-06, 5.429, 0.002625},
@@ -352,7 +353,7 @@ const char* qg_kernel_name(int kernel) {
   static const char* const names[] = {"auto",   "skinny16", "skinny32",    "skinny64",
                                       "tile64", "tile128",  "tile128x256", "tile256",
                                       "tile64k4", "tile64k1", "tile64x32k8",
-                                      "patch64x128", "patch128x64", "patch256x64", "patch256"};
+                                      "patch64x128", "patch128x64", "patch256x64", "patch256", "patch512"};
   return (kernel >= 0 && kernel <= QG_KERNEL_CONV_LAST) ? names[kernel] : nullptr;
 }
 

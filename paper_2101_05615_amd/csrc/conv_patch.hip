@@ -494,7 +494,8 @@ hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
 }  // namespace
 
 // Whether the patch kernel takes this convolution (geometry and LDS); `form` selects the workgroup's tile and waves:
-// 0 = 64 pixels x 128 channels, 1 = 128 x 64, 2 = 256 x 64 (eight waves), 3 = 256 x 128 (eight waves, 2 x 2 blocks each).
+// 0 = 64 pixels x 128 channels, 1 = 128 x 64, 2 = 256 x 64 (eight waves), 3 = 256 x 128 (eight waves, 2 x 2 blocks each),
+// 4 = 512 x 128 (eight waves, 4 x 2 blocks each).
 // Also the LDS bytes and threads of one workgroup (what decides how many of them a CU runs side by side); 0 = the
 // kernel does not take the layer.
 int qg_conv_patch_lds_bytes(const qg_gemm_args& a, int form, int* threads) {
@@ -508,6 +509,7 @@ int qg_conv_patch_lds_bytes(const qg_gemm_args& a, int form, int* threads) {
     case 1: *threads = 256; return patch_smem<4, 1, 1, 2>(a, &ps, &chunks);
     case 2: *threads = 512; return patch_smem<8, 1, 1, 2>(a, &ps, &chunks);
     case 3: *threads = 512; return patch_smem<4, 2, 2, 2>(a, &ps, &chunks);
+    case 4: *threads = 512; return patch_smem<4, 2, 4, 2>(a, &ps, &chunks);
   }
   return 0;
 }
@@ -523,6 +525,7 @@ hipError_t qg_launch_conv_patch(const qg_gemm_args& a, int form, hipStream_t s) 
     case 0: return launch<2, 2, 1, 2>(a, s);
     case 1: return launch<4, 1, 1, 2>(a, s);
     case 2: return launch<8, 1, 1, 2>(a, s);
-    default: return launch<4, 2, 2, 2>(a, s);
+    case 3: return launch<4, 2, 2, 2>(a, s);
+    default: return launch<4, 2, 4, 2>(a, s);
   }
 }

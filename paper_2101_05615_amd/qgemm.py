@@ -29,7 +29,7 @@ EXPORTS = [
 ]
 
 KERNEL_AUTO, KERNEL_LAST = 0, 10
-KERNEL_CONV_LAST = 14   # the ids above KERNEL_LAST are kernels of the dense convolution only
+KERNEL_CONV_LAST = 15   # the ids above KERNEL_LAST are kernels of the dense convolution only
 MAX_DISPATCH_RULES = 256
 
 
@@ -551,7 +551,7 @@ def pack_conv_dense_w(Wt, b_zp):
 def conv_dense_u8s8_requant(inp, Wp, a_zp, bias, scales, c_zp, relu, pad=1, stride=1, out=None, kernel="auto"):
     """inp: uint8 cuda NHWC contiguous (Cin % 16 == 0 for the staged kernels, anything under kernel="auto"); Wp from pack_conv_dense_w; returns uint8 NHWC.
     kernel: "auto", one of the 64- and 128-row tiled kernels or streaming kernels (name or id; not the 256 x 256 tile), or
-    "patch64x128" / "patch128x64" / "patch256x64" / "patch256" (stride-1 "same" layers with Cin % 32 == 0: the input patch stays in LDS)."""
+    "patch64x128" / "patch128x64" / "patch256x64" / "patch256" / "patch512" (stride-1 "same" layers with Cin % 32 == 0: the input patch stays in LDS)."""
     assert inp.is_cuda and inp.dtype == torch.uint8 and inp.dim() == 4 and inp.is_contiguous()
     Nb, H, W, C = inp.shape
     Ho = (H + 2 * pad - Wp.R) // stride + 1

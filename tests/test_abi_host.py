@@ -125,7 +125,7 @@ def test_kernel_selection_is_host_logic(lib):
     names = q.kernel_names()
     assert names[0] == "auto" and len(set(names.values())) == q.KERNEL_LAST + 1
     # the ids above the GEMM family's are kernels of the dense convolution only
-    assert [lib.qg_kernel_name(k) for k in range(q.KERNEL_LAST + 1, q.KERNEL_CONV_LAST + 1)] == [b"patch64x128", b"patch128x64", b"patch256x64", b"patch256"]
+    assert [lib.qg_kernel_name(k) for k in range(q.KERNEL_LAST + 1, q.KERNEL_CONV_LAST + 1)] == [b"patch64x128", b"patch128x64", b"patch256x64", b"patch256", b"patch512"]
     assert q.kernel_id("patch256x64") == q.KERNEL_LAST + 3
     assert lib.qg_kernel_name(q.KERNEL_CONV_LAST + 1) is None
     # small batches go to the streaming kernels, one row block when M fits the smallest

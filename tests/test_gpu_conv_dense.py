@@ -125,7 +125,7 @@ def test_dense_conv_errors(env):
     torch.cuda.synchronize()
 
 
-PATCH_KERNELS = ["patch64x128", "patch128x64", "patch256x64", "patch256"]
+PATCH_KERNELS = ["patch64x128", "patch128x64", "patch256x64", "patch256", "patch512"]
 
 
 @pytest.mark.parametrize("cfg", [

@@ -85,7 +85,7 @@ def test_dense_conv_layers_at_batch_32(env, H, C):
 
 
 @pytest.mark.parametrize("cfg,kernels", [
-    (dict(Nb=8, H=56, W=56, C=128, Cout=128), ["auto", "tile128", "tile128x256", "tile64k1", "patch64x128", "patch256"]),   # the hand-scheduled loops, the patch kernels
+    (dict(Nb=8, H=56, W=56, C=128, Cout=128), ["auto", "tile128", "tile128x256", "tile64k1", "patch64x128", "patch256", "patch512"]),   # the hand-scheduled loops, the patch kernels
     (dict(Nb=8, H=56, W=56, C=96, Cout=96), ["auto", "tile128", "patch128x64"]),                    # 16-channel chunks; taps that change mid-slab
     (dict(Nb=8, H=56, W=56, C=64, Cout=64), ["auto", "patch256x64", "tile64k1"]),
     (dict(Nb=2, H=7, W=7, C=512, Cout=128), ["auto", "skinny16", "skinny32", "tile64x32k8"]),    # few pixels, K = 4608
