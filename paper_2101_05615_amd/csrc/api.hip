@@ -97,8 +97,8 @@ const tile_cost k_conv_cost[] = {
 // "Same" convolutions (stride 1, output as large as the input) with Cin % 32 == 0 also have the kernels that keep the
 // input patch of a pixel tile in LDS; same formula, fitted to 80 layers (3 x 3 and 5 x 5, 1 .. 32 images, 32 .. 512
 // channels; the 512 x 128 form to the layers of the autotuner's convolution grid).  Over the 100 layers of that grid
-// the automatic choice among all of these kernels is within 5 % of the measured best on 91 (geometric mean 1.011x,
-// worst 1.09x), and the best kernel is one of these on 50 (up to 1.54x faster than the best of the others).
+// the automatic choice among all of these kernels is within 5 % of the measured best on 91 (geometric mean 1.009x,
+// worst 1.10x), and the best kernel is one of these on 49 (up to 1.74x faster than the best of the others).
 const tile_cost k_conv_patch_cost[] = {
     {QG_KERNEL_PATCH64X128, 64, 128, 4.86, 0.137, 0.119, 1.4},
     {QG_KERNEL_PATCH128X64, 128, 64, 4.83, 0.148, 0.135, 1.32},
@@ -936,13 +936,11 @@ int launch_conv_gemm(const uint8_t* in, int in_bytes, int Nb, int H, int W, int 
       if (us < best_us) best_us = us, kernel = c.kernel;
     }
     for (const tile_cost& c : k_conv_patch_cost) {
-      int threads = 0;
-      const int lds = qg_conv_patch_lds_bytes(a, c.kernel - QG_KERNEL_PATCH64X128, &threads);
-      if (lds == 0) continue;
+      const int per_cu = qg_conv_patch_per_cu(a, c.kernel - QG_KERNEL_PATCH64X128);
+      if (per_cu == 0) continue;
       double us = tile_estimate(c, a.M, a.N, a.K);
-      // A wide patch leaves room for few workgroups per CU (one, from 512 channels on): what does not run side by
-      // side runs one after the other, each pass at the pace of a workgroup alone.
-      const int per_cu = max(1, min(160 * 1024 / lds, 2048 / threads));
+      // A wide patch leaves room for few workgroups per CU: what does not run side by side runs one after the
+      // other, each pass at the pace of a workgroup alone.
       const double wgs = (double)ceil_div(a.M, c.bm) * (double)ceil_div(a.N, c.bn);
       const double passes = ceil(wgs / (256.0 * per_cu));
       us = fmax(us, 2.5 + passes * (c.fix + ceil_div(a.K, 64) * c.lat - 2.5));

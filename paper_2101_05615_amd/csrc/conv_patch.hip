@@ -26,8 +26,10 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 // ring of weight slabs: one consumed, the next landed, one being freed, the others in flight (an L2 hit takes about as
-// long as four slabs of MFMAs: the ring is as deep as 48 KiB of LDS allow)
-constexpr int ring_slabs(int tn) { return tn <= 64 ? 8 : 6; }
+// long as four slabs of MFMAs: the deep ring is as deep as 48 KiB of LDS allow).  The shallow ring is for the launches
+// in which it lets a CU hold one more workgroup and there are workgroups to fill the places: the other workgroups'
+// waves then cover the latency that the ring no longer does.
+constexpr int ring_slabs(int tn, bool deep) { return deep ? (tn <= 64 ? 8 : 6) : (tn <= 64 ? 4 : 3); }
 
 // slab(0) && slab(1) && ... && slab(N-1): the ring, unrolled
 template <class F, int... Is>
@@ -81,7 +83,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 // (xor 0x80) and the byte sums for the row offsets are NOT done per fragment: once the patch has landed, every
 // thread flips the bytes of whole patch pixels in place and leaves each pixel's channel sum in LDS; the row offset
 // of an output pixel is then the sum of R*S of those (or Cin * theta_A for a tap outside the image).
-template <int WM, int WN, int MB, int NBW, bool HAS_BZP, bool C64>
+template <int WM, int WN, int MB, int NBW, bool HAS_BZP, bool C64, bool DEEP>
 __global__ __launch_bounds__(WM* WN * 64) void qg_conv_patch_kernel(
     const uint8_t* const in, const int8_t* const Bp, const int npix, const int W, const int H, const int N, const int nb16,
     const int cpix, const int geom, const qg_gemm_args p) {
@@ -92,7 +94,7 @@ __global__ __launch_bounds__(WM* WN * 64) void qg_conv_patch_kernel(
   constexpr int NW = WM * WN, NT = NW * 64;
   constexpr int TP = WM * MB * 32, TN = WN * NBW * 32;
   constexpr int STAGE = TN * QG_FRAG_K;           // bytes of one 64-deep slab of TN columns
-  constexpr int NSTAGE = ring_slabs(TN);
+  constexpr int NSTAGE = ring_slabs(TN, DEEP);
   constexpr int FPS = TN / QG_FRAG_COLS;          // fragments per slab
   // Requests per wave: the same number for every wave that requests at all, so the waits are constant counts; with
   // more waves than requests the first waves issue one each and the others' waits are satisfied trivially.
@@ -455,36 +457,59 @@ __global__ __launch_bounds__(WM* WN * 64) void qg_conv_patch_kernel(
 
 constexpr int k_lds_limit = 160 * 1024;
 
-// LDS bytes of a launch, or 0 when the patch does not fit
+// LDS bytes of a workgroup with the deep or the shallow ring, or 0 when the patch does not fit
 template <int WM, int WN, int MB, int NBW>
-int patch_smem(const qg_gemm_args& a, int* ps_out, int* chunks_out) {
+int patch_smem(const qg_gemm_args& a, bool deep) {
   constexpr int NT = WM * WN * 64, TP = WM * MB * 32, TN = WN * NBW * 32;
   const int nc = a.cv_Cin / 16, psc = nc | 1, ps = psc * 16;
   const long long pixels = (long long)TP + (long long)(a.cv_R - 1) * a.cv_W + (a.cv_S - 1);
   const long long chunks = (pixels * psc + NT - 1) / NT * NT;
-  const long long bytes = ((ps + 63) & ~63) + chunks * 16 + (long long)ring_slabs(TN) * TN * QG_FRAG_K + 16 * TN + 4 * pixels;
-  if (bytes > k_lds_limit) return 0;
-  *ps_out = ps;
-  *chunks_out = (int)chunks;
-  return (int)bytes;
+  const long long bytes = ((ps + 63) & ~63) + chunks * 16 + (long long)ring_slabs(TN, deep) * TN * QG_FRAG_K + 16 * TN + 4 * pixels;
+  return bytes > k_lds_limit ? 0 : (int)bytes;
+}
+
+// What a launch of one tiling looks like: which ring, its LDS bytes (0 = the patch does not fit), the workgroups a CU
+// holds side by side.  The shallow ring where it raises that number and the grid has workgroups for the places (or
+// where only it fits).
+struct patch_plan {
+  bool deep;
+  int lds, per_cu;
+};
+template <int WM, int WN, int MB, int NBW>
+patch_plan plan(const qg_gemm_args& a) {
+  constexpr int NT = WM * WN * 64, TP = WM * MB * 32, TN = WN * NBW * 32;
+  const int lds_d = patch_smem<WM, WN, MB, NBW>(a, true), lds_s = patch_smem<WM, WN, MB, NBW>(a, false);
+  if (lds_s == 0) return {true, 0, 0};
+  // the registers of a SIMD hold 4 waves of the four-wave kernels (90 to 100 registers each, with the accumulators),
+  // 7 of the eight-wave one-block-row kernel (up to 72), 4 of the 2 x 2 kernel (up to 121), 2 of the 4 x 2 kernel
+  // (up to 218): the compiler's report, and tests/test_kernel_resources.py holds it to these
+  constexpr int waves_per_simd = MB * NBW >= 8 ? 2 : (MB * NBW == 2 && NT == 512 ? 7 : 4);
+  const int by_threads = waves_per_simd * 256 / NT;
+  const int cu_d = lds_d ? min(k_lds_limit / lds_d, by_threads) : 0, cu_s = min(k_lds_limit / lds_s, by_threads);
+  const long long wgs = (long long)((a.M + TP - 1) / TP) * ((a.N + TN - 1) / TN);
+  if (lds_d != 0 && (cu_s <= cu_d || wgs <= 256ll * cu_d)) return {true, lds_d, cu_d};
+  return {false, lds_s, cu_s};
 }
 
 template <int WM, int WN, int MB, int NBW>
 hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   constexpr int TP = WM * MB * 32, TN = WN * NBW * 32;
-  int ps = 0, chunks = 0;
-  const int smem = patch_smem<WM, WN, MB, NBW>(a, &ps, &chunks);
+  const patch_plan pl = plan<WM, WN, MB, NBW>(a);
+  const int smem = pl.lds;
   if (smem == 0) return hipErrorInvalidValue;
   const unsigned grid = (unsigned)((a.M + TP - 1) / TP) * (unsigned)((a.N + TN - 1) / TN);
-  auto go = [&](auto bzp_tag, auto c64_tag) {
-    constexpr bool BZP = decltype(bzp_tag)::value, C64 = decltype(c64_tag)::value;
-    const hipError_t e = qg_allow_smem<qg_conv_patch_kernel<WM, WN, MB, NBW, BZP, C64>>(smem);
+  auto go3 = [&](auto bzp_tag, auto c64_tag, auto deep_tag) {
+    constexpr bool BZP = decltype(bzp_tag)::value, C64 = decltype(c64_tag)::value, DEEP = decltype(deep_tag)::value;
+    const hipError_t e = qg_allow_smem<qg_conv_patch_kernel<WM, WN, MB, NBW, BZP, C64, DEEP>>(smem);
     if (e != hipSuccess) return e;
     const int geom = (int)((unsigned)a.cv_R | (unsigned)a.cv_S << 8 | (unsigned)a.cv_pad << 16 | ((unsigned)a.cv_azp & 255u) << 24);
     const int cpix = (int)((unsigned)a.cv_Cin | (unsigned)a.cv_pix << 16);
-    hipLaunchKernelGGL((qg_conv_patch_kernel<WM, WN, MB, NBW, BZP, C64>), dim3(grid), dim3(WM * WN * 64), smem, s, a.A, a.Bp, a.M,
-                       a.cv_W, a.cv_H, a.N, a.nb16, cpix, geom, a);
+    hipLaunchKernelGGL((qg_conv_patch_kernel<WM, WN, MB, NBW, BZP, C64, DEEP>), dim3(grid), dim3(WM * WN * 64), smem, s, a.A, a.Bp,
+                       a.M, a.cv_W, a.cv_H, a.N, a.nb16, cpix, geom, a);
     return hipGetLastError();
+  };
+  auto go = [&](auto bzp_tag, auto c64_tag) {
+    return pl.deep ? go3(bzp_tag, c64_tag, std::true_type{}) : go3(bzp_tag, c64_tag, std::false_type{});
   };
   const bool c64 = a.cv_Cin % 64 == 0;
   if (a.has_bzp) return c64 ? go(std::true_type{}, std::true_type{}) : go(std::true_type{}, std::false_type{});
@@ -496,28 +521,23 @@ hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
 // Whether the patch kernel takes this convolution (geometry and LDS); `form` selects the workgroup's tile and waves:
 // 0 = 64 pixels x 128 channels, 1 = 128 x 64, 2 = 256 x 64 (eight waves), 3 = 256 x 128 (eight waves, 2 x 2 blocks each),
 // 4 = 512 x 128 (eight waves, 4 x 2 blocks each).
-// Also the LDS bytes and threads of one workgroup (what decides how many of them a CU runs side by side); 0 = the
-// kernel does not take the layer.
-int qg_conv_patch_lds_bytes(const qg_gemm_args& a, int form, int* threads) {
+// Workgroups of the launch that a CU holds side by side; 0 = the kernel does not take the layer.
+int qg_conv_patch_per_cu(const qg_gemm_args& a, int form) {
   // a bit per tap, and a few taps past the last
   if (a.cv_stride != 1 || a.cv_R != a.cv_S || a.cv_R % 2 == 0 || 2 * a.cv_pad != a.cv_R - 1 || a.cv_R * a.cv_S > 28) return 0;
   if (a.cv_Ho != a.cv_H || a.cv_Wo != a.cv_W || a.cv_Cin % 32 != 0 || a.cv_pix % 16 != 0 || a.cv_pix >= 65536) return 0;
   if (((uintptr_t)a.A & 15) != 0 || a.K != a.cv_R * a.cv_S * a.cv_Cin) return 0;
-  int ps, chunks;
   switch (form) {
-    case 0: *threads = 256; return patch_smem<2, 2, 1, 2>(a, &ps, &chunks);
-    case 1: *threads = 256; return patch_smem<4, 1, 1, 2>(a, &ps, &chunks);
-    case 2: *threads = 512; return patch_smem<8, 1, 1, 2>(a, &ps, &chunks);
-    case 3: *threads = 512; return patch_smem<4, 2, 2, 2>(a, &ps, &chunks);
-    case 4: *threads = 512; return patch_smem<4, 2, 4, 2>(a, &ps, &chunks);
+    case 0: return plan<2, 2, 1, 2>(a).per_cu;
+    case 1: return plan<4, 1, 1, 2>(a).per_cu;
+    case 2: return plan<8, 1, 1, 2>(a).per_cu;
+    case 3: return plan<4, 2, 2, 2>(a).per_cu;
+    case 4: return plan<4, 2, 4, 2>(a).per_cu;
   }
   return 0;
 }
 
-bool qg_conv_patch_applies(const qg_gemm_args& a, int form) {
-  int threads;
-  return qg_conv_patch_lds_bytes(a, form, &threads) != 0;
-}
+bool qg_conv_patch_applies(const qg_gemm_args& a, int form) { return qg_conv_patch_per_cu(a, form) != 0; }
 
 hipError_t qg_launch_conv_patch(const qg_gemm_args& a, int form, hipStream_t s) {
   if (!qg_conv_patch_applies(a, form)) return hipErrorInvalidValue;

@@ -301,7 +301,7 @@ hipError_t qg_launch_conv_group(const qg_conv_args& a, int RS, hipStream_t s);
 hipError_t qg_launch_conv_dense_plain(const qg_conv_args& a, hipStream_t s);
 // the kernels with the input patch in LDS ("same" convolutions); form 0 = 64 pixels x 128 channels, 1 = 128 x 64, 2 = 256 x 64, 3 = 256 x 128, 4 = 512 x 128
 bool qg_conv_patch_applies(const qg_gemm_args& a, int form);
-int qg_conv_patch_lds_bytes(const qg_gemm_args& a, int form, int* threads);  // per workgroup; 0 = does not apply
+int qg_conv_patch_per_cu(const qg_gemm_args& a, int form);  // workgroups a CU holds side by side; 0 = does not apply
 hipError_t qg_launch_conv_patch(const qg_gemm_args& a, int form, hipStream_t s);
 
 #define QG_MODE_REQUANT 0

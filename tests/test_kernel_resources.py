@@ -29,7 +29,7 @@ def _resources(src):
         if m:
             name = m.group(1)
             out[name] = {}
-        for key in ("ScratchSize [bytes/lane]", "VGPRs Spill", "SGPRs Spill"):
+        for key in ("ScratchSize [bytes/lane]", "VGPRs Spill", "SGPRs Spill", "Occupancy [waves/SIMD]"):
             m = re.search(re.escape(key) + r": (\d+)", line)
             if m and name:
                 out[name][key] = int(m.group(1))
@@ -40,7 +40,13 @@ def _resources(src):
 def test_gemm_kernels_use_no_scratch_memory_and_spill_nothing():
     with ThreadPoolExecutor(3) as ex:
         tile, skinny, patch = ex.map(_resources, ["gemm_tile.hip", "gemm_skinny.hip", "conv_patch.hip"])
-    assert len(tile) >= 30 and len(skinny) >= 30 and len(patch) >= 12, "the resource report was not parsed"
+    assert len(tile) >= 30 and len(skinny) >= 30 and len(patch) >= 40, "the resource report was not parsed"
+    # the patch kernels' launcher counts on these waves per SIMD when it decides how many workgroups share a CU
+    for name, r in patch.items():
+        m = re.search(r"ILi(\d+)ELi(\d+)ELi(\d+)ELi(\d+)E", name)
+        wm, wn, mb, nbw = (int(x) for x in m.groups())
+        need = 2 if mb * nbw >= 8 else (7 if mb * nbw == 2 and wm * wn == 8 else 4)
+        assert r["Occupancy [waves/SIMD]"] >= need, f"{name}: {r}"
     for name, r in {**tile, **skinny, **patch}.items():
         assert r.get("ScratchSize [bytes/lane]") == 0, f"{name} uses scratch memory: {r}"
         assert r.get("VGPRs Spill") == 0 and r.get("SGPRs Spill") == 0, f"{name} spills registers: {r}"
