@@ -677,23 +677,19 @@ hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-// which form of the uint8 output pipeline this launch needs (see EPI above); one-block waves keep the single,
-// always-correct form: their pipeline is 16 values per lane
+// which form of the uint8 output pipeline this launch needs (see EPI above).  The one-block waves take the short
+// forms too: their pipeline is only 16 values per lane, but a short K with many rows is little else.
 template <int BLOCKS>
 int epi_form(const qg_gemm_args& a) {
-  if (BLOCKS == 1 || qg_requant_needs_lo_host(a.clamp_lo, a.c_zp)) return EPI_CLAMP;
+  if (qg_requant_needs_lo_host(a.clamp_lo, a.c_zp)) return EPI_CLAMP;
   return a.c_zp == 0 ? EPI_SAT0 : EPI_SAT;
 }
 template <int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, int KS>
 hipError_t launch_requant(const qg_gemm_args& a, hipStream_t s) {
-  if constexpr (TM * TN == 1) {
-    return launch<QG_MODE_REQUANT, PATH, ROWSUM, NWM, NWN, TM, TN, KS, EPI_CLAMP>(a, s);
-  } else {
-    switch (epi_form<TM * TN>(a)) {
-      case EPI_SAT0: return launch<QG_MODE_REQUANT, PATH, ROWSUM, NWM, NWN, TM, TN, KS, EPI_SAT0>(a, s);
-      case EPI_SAT: return launch<QG_MODE_REQUANT, PATH, ROWSUM, NWM, NWN, TM, TN, KS, EPI_SAT>(a, s);
-      default: return launch<QG_MODE_REQUANT, PATH, ROWSUM, NWM, NWN, TM, TN, KS, EPI_CLAMP>(a, s);
-    }
+  switch (epi_form<TM * TN>(a)) {
+    case EPI_SAT0: return launch<QG_MODE_REQUANT, PATH, ROWSUM, NWM, NWN, TM, TN, KS, EPI_SAT0>(a, s);
+    case EPI_SAT: return launch<QG_MODE_REQUANT, PATH, ROWSUM, NWM, NWN, TM, TN, KS, EPI_SAT>(a, s);
+    default: return launch<QG_MODE_REQUANT, PATH, ROWSUM, NWM, NWN, TM, TN, KS, EPI_CLAMP>(a, s);
   }
 }
 
@@ -737,14 +733,10 @@ template <bool ROWSUM, int NWM, int NWN, int TM, int TN, int KS>
 hipError_t launch_conv_rs(const qg_gemm_args& a, hipStream_t s) {
   // channel counts that are not a multiple of 64: the per-chunk variant, with the one always-correct output form
   if (a.cv_Cin % BK != 0) return launch_conv_path<ROWSUM, NWM, NWN, TM, TN, KS, EPI_CLAMP, 2>(a, s);
-  if constexpr (TM * TN == 1) {
-    return launch_conv_epi<ROWSUM, NWM, NWN, TM, TN, KS, EPI_CLAMP>(a, s);
-  } else {
-    switch (epi_form<TM * TN>(a)) {
-      case EPI_SAT0: return launch_conv_epi<ROWSUM, NWM, NWN, TM, TN, KS, EPI_SAT0>(a, s);
-      case EPI_SAT: return launch_conv_epi<ROWSUM, NWM, NWN, TM, TN, KS, EPI_SAT>(a, s);
-      default: return launch_conv_epi<ROWSUM, NWM, NWN, TM, TN, KS, EPI_CLAMP>(a, s);
-    }
+  switch (epi_form<TM * TN>(a)) {
+    case EPI_SAT0: return launch_conv_epi<ROWSUM, NWM, NWN, TM, TN, KS, EPI_SAT0>(a, s);
+    case EPI_SAT: return launch_conv_epi<ROWSUM, NWM, NWN, TM, TN, KS, EPI_SAT>(a, s);
+    default: return launch_conv_epi<ROWSUM, NWM, NWN, TM, TN, KS, EPI_CLAMP>(a, s);
   }
 }
 template <int NWM, int NWN, int TM, int TN, int KS = 1>
