@@ -68,6 +68,7 @@ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 struct tile_cost {
   int kernel, bm, bn;
   double fix, lat, thr, epi;
+  double out = 0.0;  // output bytes per microsecond that the kernel sustains when K is short; 0 = never the bound
 };
 struct stream_cost {
   int kernel, rows;
@@ -75,11 +76,11 @@ struct stream_cost {
 };
 const tile_cost k_tile_cost[] = {
     {QG_KERNEL_TILE64, 64, 64, 3.169, 0.1296, 0.1046, 0.6015},
-    {QG_KERNEL_TILE128, 128, 128, 3.401, 0.242, 0.2725, 1.102},
+    {QG_KERNEL_TILE128, 128, 128, 3.401, 0.242, 0.2725, 1.102, 2.88e6},
     {QG_KERNEL_TILE128X256, 128, 256, 5.288, 0.3543, 0.4409, 2.253},
     {QG_KERNEL_TILE256, 256, 256, 7.789, 0.6867, 0.8478, 6.549},
     {QG_KERNEL_TILE64K4, 64, 64, 3.617, 0.1035, 0.1077, 2.38},
-    {QG_KERNEL_TILE64K1, 64, 64, 2.714, 0.2482, 0.1361, 0.1909},
+    {QG_KERNEL_TILE64K1, 64, 64, 2.714, 0.2482, 0.1361, 0.1909, 2.35e6},
     {QG_KERNEL_TILE64X32K8, 64, 32, 3.817, 0.05427, 0.0602, 2.585},
 };
 // The dense convolution runs the same tile loops with the im2col addressing folded into the requests; the same
@@ -141,7 +142,12 @@ double tile_estimate(const tile_cost& c, int M, int N, int K) {
   const double wgs = (double)ceil_div(M, c.bm) * (double)ceil_div(N, c.bn);
   const double alone = c.fix + kt * c.lat;
   if (wgs <= 256.0) return alone;
-  return fmax(alone, 2.5 + ceil(wgs / 256.0) * (kt * c.thr + c.epi));
+  double us = fmax(alone, 2.5 + ceil(wgs / 256.0) * (kt * c.thr + c.epi));
+  // many rows and a K of one or two tiles (the 1 x 1 layers of a convolutional network as GEMMs): little but output,
+  // at a rate measured on 30 such shapes (without this bound the 64 x 64 tile was chosen for 100352 x 256 x 64,
+  // 1.15x behind the 128 x 128 tile)
+  if (c.out > 0.0) us = fmax(us, 2.5 + (double)M * (double)N / c.out);
+  return us;
 }
 
 int builtin_select(int M, int N, int K) {
