@@ -84,6 +84,31 @@ def test_dense_conv_layers_at_batch_32(env, H, C):
         assert_same(got[n:n + 1], want, f"image {n}")
 
 
+@pytest.mark.parametrize("H,C,Cout", [(56, 64, 64), (56, 64, 128), (14, 512, 512)])
+def test_patch_kernels_with_more_workgroups_than_places(env, H, C, Cout):
+    """Batch 32: grids of several hundred workgroups, where the patch kernels run the build with the shallow weight
+    ring (one more workgroup per CU); every form that takes the layer, three images against the oracle."""
+    q, torch, dev, oracle = env
+    say(f"dense conv 32x{H}x{H}x{C}->{Cout}, patch kernels")
+    c = wl.random_conv(45 + C, Nb=32, H=H, W=H, C=C, G=1, Cout=Cout)
+    Wp = q.pack_conv_dense_w(torch.from_numpy(np.ascontiguousarray(c.wgt[0])).to(dev), c.b_zp)
+    x, b, sc = torch.from_numpy(c.inp).to(dev), torch.from_numpy(c.bias).to(dev), torch.from_numpy(c.scales).to(dev)
+    want = {n: oracle.conv_groupwise_direct(c.inp[n:n + 1], 1, c.wgt, c.a_zp, c.b_zp, c.bias, c.scales, c.c_zp, c.relu,
+                                            c.pad, c.stride) for n in (0, 17, 31)}
+    ran = 0
+    for kernel in ["patch64x128", "patch128x64", "patch256x64", "patch256", "patch512"]:
+        try:
+            got = q.conv_dense_u8s8_requant(x, Wp, c.a_zp, b, sc, c.c_zp, c.relu, pad=c.pad, stride=c.stride, kernel=kernel)
+        except q.QGemmError:
+            continue   # the patch does not fit the LDS at this tile and channel count
+        torch.cuda.synchronize()
+        got = got.cpu().numpy()
+        for n, w in want.items():
+            assert_same(got[n:n + 1], w, f"kernel {kernel}, image {n}")
+        ran += 1
+    assert ran >= 2
+
+
 @pytest.mark.parametrize("cfg,kernels", [
     (dict(Nb=8, H=56, W=56, C=128, Cout=128), ["auto", "tile128", "tile128x256", "tile64k1", "patch64x128", "patch256", "patch512"]),   # the hand-scheduled loops, the patch kernels
     (dict(Nb=8, H=56, W=56, C=96, Cout=96), ["auto", "tile128", "patch128x64"]),                    # 16-channel chunks; taps that change mid-slab
