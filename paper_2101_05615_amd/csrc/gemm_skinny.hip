@@ -616,18 +616,23 @@ hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   if (mblocks > 65535 || a.ksplit < 1 || a.ksplit > 65535) return hipErrorInvalidValue;
   if (a.ksplit > 1 && (a.ws_cnt == nullptr || a.ws_slots == nullptr)) return hipErrorInvalidValue;
   const dim3 grid(nfrag, mblocks, a.ksplit), block(NWAVES * 64);
-  if constexpr (!B4 && !ANYALIGN && MB == 1) {
-    // More 32-column super-blocks than half the CUs: four waves per workgroup, each streaming two fragment columns,
-    // batches of eight k blocks.  The 16-wave form would put two or more workgroups on a CU there, and a second
+  if constexpr (!B4 && !ANYALIGN) {
+    // More 32-column super-blocks than half the CUs: few fat waves per workgroup, each streaming two fragment columns
+    // (four waves and batches of eight k blocks; eight waves and batches of four at 64 rows, whose staged batch is
+    // four times as large).  The 16-wave form would put two or more workgroups on a CU there, and a second
     // one costs about as much as the first (80 x 1536 x 2048: 6.7 -> 3.4 us cold, 640 x 128 x 2048: 6.7 -> 3.7,
     // 80 x 1024 x 4096: 6.9 -> 5.7).  Cold, 16 rows: 8192 x 4096 11.4 -> 9.4 us, 8192 x 8192 18.2 -> 15.0 (a plain
-    // read of the weights in the same launch shape: 14.4), 16384 x 16384 59.2 -> 48.7.  With 128 super-blocks or
-    // fewer half the CUs would idle and the 16-wave form stays ahead (4096 x 8192: 9.6 vs 10.9 us).
-    constexpr int WN = 4, WB = 8, WC = 2;
+    // read of the weights in the same launch shape: 14.4), 16384 x 16384 59.2 -> 48.7; 32 rows, 8192 x 8192:
+    // 21.0 -> 16.9; 64 rows: 8192 x 8192 26.3 -> 19.7, 2048 x 8192 10.8 -> 7.7, 128 x 8192 x 4096 27.7 -> 19.8 --
+    // every activation fragment feeds two MFMAs, so the workgroup stages half the activation bytes per weight byte,
+    // which at 64 rows is most of the traffic.  With 128 super-blocks or fewer half the CUs would idle and the
+    // 16-wave form stays ahead (16 x 4096 x 8192: 9.6 vs 10.9 us; 64 x 4096 x 4096: 8.1 vs 9.5).
+    constexpr int WN = MB == 4 ? 8 : 4, WB = MB == 4 ? 4 : 8, WC = 2;
     if ((long long)((a.N + 31) / 32) * mblocks > 128 && a.K == a.kb64 * QG_FRAG_K && a.kb64 % a.ks_per == 0 &&
         a.ks_per % (WN * WB) == 0) {
-      constexpr auto fn = qg_gemm_skinny_kernel<MODE, 1, WN, WB, false, false, true, WC>;
-      const int wsmem = WN * 16 * (WB * QG_FRAG_K) + WN * 16 * (int)sizeof(int);
+      constexpr auto fn = qg_gemm_skinny_kernel<MODE, MB, WN, WB, false, false, true, WC>;
+      const int wpart = WN * MB * WC * 64 * (int)sizeof(v4i), wstage = WN * (MB * 16) * (WB * QG_FRAG_K);
+      const int wsmem = (wstage > wpart ? wstage : wpart) + WN * MB * 16 * (int)sizeof(int);
       hipError_t e = qg_allow_smem<fn>(wsmem);
       if (e != hipSuccess) return e;
       hipLaunchKernelGGL(fn, dim3((a.N + 31) / 32, mblocks, a.ksplit), dim3(WN * 64), wsmem, s, a.A, a.Bp, a.M, a.N, a.K, a.kb64,
