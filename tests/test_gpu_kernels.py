@@ -170,3 +170,29 @@ def test_streaming_kernel_with_two_fragment_columns_per_wave(env, M, N, K, kspli
         assert_same(acc.cpu().numpy(), oracle.acc32(c.A, c.B), f"acc32 (call {rep})")
         assert_same(rs.cpu().numpy(), oracle.rowsum(c.A), f"rowsum (call {rep})")
     assert (c_store.cpu().numpy()[M * N:] == 0xEE).all(), "bytes past C were written"
+
+
+@pytest.mark.parametrize("kernel,M,N,K,ksplit", [("skinny32", 32, 8192, 2048, 1), ("skinny32", 19, 4140, 4096, 1), ("skinny32", 70, 2100, 2048, 1),
+                                                 ("skinny32", 32, 8200, 4096, 2), ("skinny64", 64, 8192, 2048, 1), ("skinny64", 33, 4128, 4096, 1),
+                                                 ("skinny64", 200, 1100, 2048, 1), ("skinny64", 64, 4200, 6144, 3), ("skinny64", 2200, 100, 4096, 2)])
+def test_taller_streaming_kernels_with_two_fragment_columns_per_wave(env, kernel, M, N, K, ksplit):
+    """The same form of the 32- and 64-row streaming kernels (four waves with batches of eight k blocks, eight waves
+    with batches of four): more than 128 super-blocks, N that cuts a super-block, ragged and several row blocks, the
+    smallest count that takes the form, and the K split across workgroups on top."""
+    q, torch, dev, oracle = env
+    say(f"wide streaming form {kernel} {M}x{N}x{K} ksplit {ksplit}")
+    c = wl.unsaturated(wl.random_gemm(8300 + M + N + K, M, N, K, per_channel=True, with_bias=True, wide_zp=True))
+    want = oracle_gemm(c, oracle)
+    A, B, bias, scales, C, c_store = dev_case(c, torch, dev)
+    Bp = q.pack_b(B, c.b_zp)
+    ws = q.gemm_workspace(M, Bp, kernel, ksplit)
+    assert (ws is None) == (ksplit == 1)
+    for rep in range(2):
+        C.fill_(0xEE)
+        q.gemm_u8s8_requant_splitk(A, c.a_zp, Bp, bias, scales, c.c_zp, c.relu, ws, kernel, ksplit, out=C)
+        acc, rs = q.gemm_u8s8_acc32_splitk(A, Bp, ws, kernel, ksplit, want_rowsum=True)
+        torch.cuda.synchronize()
+        assert_same(C.cpu().numpy(), want, f"requant (call {rep})")
+        assert_same(acc.cpu().numpy(), oracle.acc32(c.A, c.B), f"acc32 (call {rep})")
+        assert_same(rs.cpu().numpy(), oracle.rowsum(c.A), f"rowsum (call {rep})")
+    assert (c_store.cpu().numpy()[M * N:] == 0xEE).all(), "bytes past C were written"
