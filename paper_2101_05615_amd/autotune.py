@@ -8,9 +8,12 @@ the library's built-in choice.
     python -m paper_2101_05615_amd.autotune --shapes 128x4096x4096,2048x2048x2048 --out table.json
     python -m paper_2101_05615_amd.autotune --grid --out table.json
 
+    python -m paper_2101_05615_amd.autotune --cold --shapes 64x8192x8192 --out table.json
+
     python -m paper_2101_05615_amd.autotune --conv-grid
 
-Every kernel returns identical bytes for a given input, so the table affects speed only.  --conv-grid times every
+Every kernel returns identical bytes for a given input, so the table affects speed only.  Times are warm
+(back-to-back launches on one set of buffers, weights in the memory-side cache when they fit) unless --cold is given.  --conv-grid times every
 kernel id of the dense convolution (tiled, streaming and patch-resident kernels) and the automatic choice on a
 built-in list of layers and reports what the choice loses against the measured best (the convolution has no rule
 table: its built-in cost constants were fitted to such a run).
@@ -70,10 +73,10 @@ def time_shape(q, torch, M, N, K, kernels, min_ms=3.0, seed=0, spin_ms=15.0):
     return out
 
 
-def time_cold(q, torch, M, N, K, kernel="auto", seed=0, reps=3):
-    """Microseconds per launch of one kernel with COLD weights: the launch rotates over enough packed copies of B
+def time_cold_kernels(q, torch, M, N, K, kernels, seed=0, reps=3):
+    """Microseconds per launch with COLD weights, per kernel: the launches rotate over enough packed copies of B
     (more than 1 GB together, at most 256) that the 256 MB memory-side cache cannot hold them, recorded as one graph
-    and replayed (no host cost per launch).  -> (us, copies)"""
+    per kernel and replayed (no host cost per launch).  -> ({kernel name: us}, copies)"""
     dev = torch.device("cuda:0")
     g = torch.Generator(device=dev)
     g.manual_seed(seed)
@@ -82,31 +85,42 @@ def time_cold(q, torch, M, N, K, kernel="auto", seed=0, reps=3):
     scales = torch.full((N,), 2.0 ** -12, dtype=torch.float32, device=dev)
     b_zp = torch.randint(-8, 9, (N,), generator=torch.Generator().manual_seed(seed)).numpy()
     ncopy = int(max(2, min(256, 1.2e9 // (K * N))))
-    calls = []
-    for _ in range(ncopy):
-        Bp = q.pack_b(B, b_zp)
-        calls.append(q.PreparedGemm(A.clone(), 128, Bp, None, scales, 0, True,
-                                    torch.empty((M, N), dtype=torch.uint8, device=dev), kernel=kernel))
-    for c in calls:
-        c.launch()
-    torch.cuda.synchronize()
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph):
+    packed = [q.pack_b(B, b_zp) for _ in range(ncopy)]
+    acts = [A.clone() for _ in range(ncopy)]
+    outs = [torch.empty((M, N), dtype=torch.uint8, device=dev) for _ in range(ncopy)]
+    result = {}
+    for kernel in kernels:
+        calls = [q.PreparedGemm(acts[i], 128, packed[i], None, scales, 0, True, outs[i], kernel=kernel) for i in range(ncopy)]
         for c in calls:
-            c.rebind().launch()
-    for _ in range(3):
-        graph.replay()
-    torch.cuda.synchronize()
-    best = None
-    for _ in range(reps):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        graph.replay()
-        e1.record()
+            c.launch()
         torch.cuda.synchronize()
-        t = e0.elapsed_time(e1) * 1e3 / ncopy
-        best = t if best is None else min(best, t)
-    return best, ncopy
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for c in calls:
+                c.rebind().launch()
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            graph.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1) * 1e3 / ncopy
+            best = t if best is None else min(best, t)
+        result[kernel] = best
+        del graph, calls
+    for Bp in packed:
+        Bp.close()
+    return result, ncopy
+
+
+def time_cold(q, torch, M, N, K, kernel="auto", seed=0, reps=3):
+    """One kernel with cold weights -> (us, copies)."""
+    t, ncopy = time_cold_kernels(q, torch, M, N, K, [kernel], seed, reps)
+    return t[kernel], ncopy
 
 
 # dense convolution layers (H = W, Cin, Cout, filter, stride), each at 1, 4, 8 and 32 images
@@ -195,12 +209,12 @@ def conv_summary(rows):
     return "\n".join(out)
 
 
-def tune(q, torch, shapes, kernels=None, log=None):
+def tune(q, torch, shapes, kernels=None, log=None, cold=False):
     names = q.kernel_names()
     kernels = kernels or [names[k] for k in range(1, q.KERNEL_LAST + 1)]
     rows = []
     for (M, N, K) in shapes:
-        t = time_shape(q, torch, M, N, K, kernels)
+        t = time_cold_kernels(q, torch, M, N, K, kernels)[0] if cold else time_shape(q, torch, M, N, K, kernels)
         best = min(t, key=t.get)
         auto = names[q.kernel_select(M, N, K)]
         rows.append({"M": M, "N": N, "K": K, "best": best, "auto": auto, "us": t})
@@ -249,6 +263,9 @@ def main(argv=None):
                          "with cold weights and reports its fraction of the 8 TB/s HBM peak")
     ap.add_argument("--conv-grid", action="store_true",
                     help="dense convolution: every kernel id and the automatic choice on the built-in list of layers")
+    ap.add_argument("--cold", action="store_true",
+                    help="time every kernel with cold weights (launches rotate over more than 1 GB of packed copies): the "
+                         "table for a model whose weights do not stay in the memory-side cache between layers")
     ap.add_argument("--out", default="", help="write the dispatch table (JSON) here")
     ap.add_argument("--quiet", action="store_true", help="print only the summary")
     a = ap.parse_args(argv)
@@ -268,7 +285,7 @@ def main(argv=None):
         return 0
     if not shapes:
         ap.error("no shapes given")
-    rows = tune(q, torch, shapes, log=None if a.quiet else (lambda s: print(s, flush=True)))
+    rows = tune(q, torch, shapes, log=None if a.quiet else (lambda s: print(s, flush=True)), cold=a.cold)
     if a.small_grid:
         for r in rows:
             us, ncopy = time_cold(q, torch, r["M"], r["N"], r["K"])
