@@ -245,9 +245,12 @@ int qg_gemm_u8s8_acc32_kernel(const uint8_t* A_dev, int M, int lda, const qg_pac
                               void* stream, int kernel);
 
 /* The K split chosen by the caller (the tests compare every factor with the
- * oracle; the autotuner times them).  Streaming kernels only:
- *   kernel  QG_KERNEL_AUTO or QG_KERNEL_SKINNY16/32/64; a TILE kernel with
- *           ksplit > 1 is QG_EUNSUPPORTED
+ * oracle; the autotuner times them).  Appendix A: the caller's C_buffer.
+ *   kernel  QG_KERNEL_AUTO or QG_KERNEL_SKINNY16/32/64, or QG_KERNEL_TILE128 (the
+ *           caller's ksplit only: 0 does not split it; slices of at least four
+ *           64-deep tiles, K a multiple of 64, dense weights -- otherwise the
+ *           factor used is 1); another TILE kernel with ksplit > 1 is
+ *           QG_EUNSUPPORTED
  *   ksplit  0 = built-in choice, 1 = no split, up to 64 slices of K; the factor
  *           actually used (qg_gemm_splitk_factor) never leaves a slice without a
  *           64-deep block of K

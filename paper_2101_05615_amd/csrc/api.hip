@@ -264,6 +264,10 @@ struct splitk_layout {
 };
 // counters first (one per row block of 16 and fragment column, rounded up to 256 bytes), then the slots
 splitk_layout splitk_ws(int kernel, int M, int N, int ksplit) {
+  if (kernel == QG_KERNEL_TILE128) {  // one counter per 128 x 128 tile; a slot is 256 threads x (64 sums + 2 row offsets)
+    const size_t tiles = (size_t)ceil_div(M, 128) * (size_t)ceil_div(N, 128);
+    return {(tiles + 63) / 64 * 64, tiles * (size_t)ksplit * (66 * 256)};
+  }
   const int rows = 16 << (kernel - QG_KERNEL_SKINNY16);
   const size_t units = (size_t)ceil_div(M, rows) * (size_t)(2 * ceil_div(N, 32)) * (size_t)(rows / 16);
   return {(units + 63) / 64 * 64, units * (size_t)ksplit * kSlotInts};
@@ -280,6 +284,19 @@ int clamp_ksplit(const qg_packed_b* Bp, int ksplit) {
 // removes several batches of weight loads from every wave's chain.  Give each wave of a slice four 64-deep blocks
 // (one batch of loads); take the split from 4 slices up (from 2 for 64-row blocks, whose waves do four times the
 // work per block), and never more slices than there are idle CUs to take them.
+// The 128 x 128 tile: slices of whole 64-deep tiles, at least four each (the depth of the hand-scheduled loop's
+// pipeline), K a multiple of 64, dense weights.  -> the number of slices that `ksplit` gives, 1 if it cannot be split
+int clamp_ksplit_tile128(const qg_packed_b* Bp, int ksplit) {
+  if (Bp->split || Bp->K % QG_FRAG_K != 0) return 1;
+  const int blocks = Bp->K / QG_FRAG_K;
+  if (ksplit > blocks / 4) ksplit = blocks / 4;
+  while (ksplit > 1) {
+    const int per = ceil_div(blocks, ksplit), s = ceil_div(blocks, per);
+    if (blocks - (s - 1) * per >= 4) return s;
+    --ksplit;
+  }
+  return 1;
+}
 int auto_ksplit(int kernel, int M, const qg_packed_b* Bp) {
   if (kernel < QG_KERNEL_SKINNY16 || kernel > QG_KERNEL_SKINNY64) return 1;
   const int rows = 16 << (kernel - QG_KERNEL_SKINNY16);
@@ -300,8 +317,22 @@ int resolve_ksplit(const qg_packed_b* Bp, int M, int kernel, int ksplit_req, voi
   if (ksplit_req < 0 || ksplit_req > kMaxKsplit) return QG_EINVAL;
   if (M == 0) return QG_OK;
   int s = ksplit_req;
+  if (kernel == QG_KERNEL_TILE128 && s > 1) {
+    // the caller's split on the 128 x 128 tile (never the built-in choice)
+    s = clamp_ksplit_tile128(Bp, s);
+    if (s <= 1) return QG_OK;
+    if (!workspace_dev) return QG_EWORKSPACE;
+    if (!aligned(workspace_dev, 16)) return QG_EALIGN;
+    const splitk_layout w = splitk_ws(kernel, M, Bp->N, s);
+    if (bytes_known && workspace_bytes < w.bytes()) return QG_EWORKSPACE;
+    a->ksplit = s;
+    a->ks_per = ceil_div(Bp->K / QG_FRAG_K, s);
+    a->ws_cnt = static_cast<int32_t*>(workspace_dev);
+    a->ws_slots = a->ws_cnt + w.cnt_ints;
+    return QG_OK;
+  }
   if (kernel > QG_KERNEL_SKINNY64) {
-    if (s > 1) return QG_EUNSUPPORTED;  // the tiled kernels keep K inside the workgroup
+    if (s > 1) return QG_EUNSUPPORTED;  // the other tiled kernels keep K inside the workgroup
     return QG_OK;
   }
   if (s == 0) s = workspace_dev ? auto_ksplit(kernel, M, Bp) : 1;
@@ -568,7 +599,12 @@ size_t qg_gemm_workspace_bytes(int M, const qg_packed_b* Bp) {
 
 size_t qg_gemm_splitk_workspace_bytes(int M, const qg_packed_b* Bp, int kernel, int ksplit) {
   if (!Bp || M <= 0 || Bp->kind != QG_KIND_GEMM || ksplit < 0 || ksplit > kMaxKsplit) return 0;
-  if (resolve_kernel(Bp, M, &kernel) != QG_OK || kernel > QG_KERNEL_SKINNY64) return 0;
+  if (resolve_kernel(Bp, M, &kernel) != QG_OK) return 0;
+  if (kernel == QG_KERNEL_TILE128) {
+    const int s = ksplit > 1 ? clamp_ksplit_tile128(Bp, ksplit) : 1;
+    return s > 1 ? splitk_ws(kernel, M, Bp->N, s).bytes() : 0;
+  }
+  if (kernel > QG_KERNEL_SKINNY64) return 0;
   const int s = ksplit == 0 ? auto_ksplit(kernel, M, Bp) : clamp_ksplit(Bp, ksplit);
   return s > 1 ? splitk_ws(kernel, M, Bp->N, s).bytes() : 0;
 }
@@ -578,6 +614,7 @@ int qg_gemm_splitk_factor(int M, const qg_packed_b* Bp, int kernel, int ksplit) 
   if (M <= 0 || ksplit < 0 || ksplit > kMaxKsplit) return QG_EINVAL;
   const int rc = resolve_kernel(Bp, M, &kernel);
   if (rc != QG_OK) return rc;
+  if (kernel == QG_KERNEL_TILE128) return ksplit > 1 ? clamp_ksplit_tile128(Bp, ksplit) : 1;
   if (kernel > QG_KERNEL_SKINNY64) return 1;
   return ksplit == 0 ? auto_ksplit(kernel, M, Bp) : clamp_ksplit(Bp, ksplit);
 }

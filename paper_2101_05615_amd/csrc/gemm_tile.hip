@@ -167,10 +167,23 @@ constexpr int min_wg_per_cu(int path, int blocks) {
 // cold trip to memory.
 constexpr int EPI_CLAMP = 0, EPI_SAT = 1, EPI_SAT0 = 2;
 
-template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, int CONV = 0, int KS = 1, int EPI = EPI_CLAMP>
+// SPLIT (hand-scheduled 128 x 128 tile only): K split ACROSS workgroups, as in the streaming kernels (the role of the
+// paper's caller-provided C_buffer, Appendix A).  blockIdx.y is the slice: p.ks_per k tiles from tile blockIdx.y *
+// p.ks_per on.  A slice hands its int32 accumulators and row offsets to its slot of the caller's workspace with
+// device-coherent stores, waits for their acknowledgement and takes a ticket; the workgroup that draws the last
+// ticket adds the other slices' slots to its registers (integer sums: every split gives the same bytes), puts the
+// counter back to zero and runs the output pipeline.  For a few hundred rows and a long K, where the tiles of the
+// problem are fewer than the CUs and each would walk all of K alone.
+template <int MODE, int PATH, bool ROWSUM, int NWM, int NWN, int TM, int TN, int CONV = 0, int KS = 1, int EPI = EPI_CLAMP,
+          bool SPLIT = false>
 __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) / KS) void qg_gemm_tile_kernel(
-    const uint8_t* A, const int8_t* Bp, const int M, const int N, const int K, const int nb16_total, const int lda,
+    const uint8_t* A0, const int8_t* Bp, const int M, const int N, const int K0, const int nb16_total, const int lda,
     const int tiles_m, const int tiles_n, const qg_gemm_args p) {
+  static_assert(!SPLIT || (PATH == PATH_ASM && TM == 2 && TN == 2 && CONV == 0 && KS == 1), "the cross-workgroup K split is built for the 128 x 128 tile");
+  // this workgroup's part of K (all of it unless SPLIT; K0 stays the K of the whole product)
+  const int k_first = SPLIT ? (int)blockIdx.y * p.ks_per : 0;  // in 64-deep tiles
+  const uint8_t* const A = A0 + (SPLIT ? k_first * BK : 0);
+  const int K = SPLIT ? min(K0 - k_first * BK, p.ks_per * BK) : K0;
   static_assert(KS == 1 || ((KS == 2 || KS == 4 || KS == 8) && PATH == PATH_PIPE), "K split: wave sets on the pipelined path");
   constexpr bool CVG = CONV == 2;  // per-chunk taps
   constexpr int NW = NWM * NWN, NT = NW * KS * 64;  // NW: waves of one set; NT: threads of the workgroup
@@ -239,8 +252,8 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
 #pragma unroll
   for (int q = 0; q < B_DMA; ++q)
     b_voff[q] = (unsigned)(wave * B_DMA + q) * QG_FRAG_BYTES + lane * 16;
-  const int8_t* b_tile0 = Bp + (size_t)(n0 / QG_FRAG_COLS) * QG_FRAG_BYTES;
   const unsigned b_step = (unsigned)nb16_total * QG_FRAG_BYTES;  // one 64-deep slab of the packed buffer
+  const int8_t* b_tile0 = Bp + (size_t)(n0 / QG_FRAG_COLS) * QG_FRAG_BYTES + (SPLIT ? (size_t)k_first * b_step : 0);
 
   // ---- fragment fetch (LDS -> registers): per-lane base offsets, everything else is an immediate
   int a_rd[2];  // k-step 0 / 1 of block mb = 0; block mb is 32 rows = 2 KiB further
@@ -540,6 +553,45 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
   for (int mb = 0; mb < TM; ++mb)
     rsum_s[mb] = (int)(rs[mb] + (unsigned)__shfl_xor((int)rs[mb], 32)) - 128 * (KT * BK);
 
+  // ---- K split across workgroups: hand the partial tile in, the last slice to arrive carries on
+  if constexpr (SPLIT) {
+    constexpr int PER = TM * TN * 16 + TM;  // ints per thread and slot
+    const int unit = tm * tiles_n + tn, ks = p.ksplit;
+    int* const cnt = p.ws_cnt + unit;
+    int* const slots = p.ws_slots + (size_t)unit * ks * (PER * NT);
+    int* const mine = slots + (size_t)blockIdx.y * (PER * NT) + tid;
+#pragma unroll
+    for (int mb = 0; mb < TM; ++mb) {
+#pragma unroll
+      for (int nb = 0; nb < TN; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          __hip_atomic_store(mine + ((mb * TN + nb) * 16 + r) * NT, acc[mb][nb][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(mine + (TM * TN * 16 + mb) * NT, rsum_s[mb], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the write-through stores above have been acknowledged
+    __syncthreads();                                   // ... those of every wave (and every wave is done with the stages)
+    int* const ticket_s = reinterpret_cast<int*>(smem);
+    if (tid == 0) *ticket_s = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (*ticket_s != ks - 1) return;
+    // every other slice's stores were acknowledged before it took its ticket
+    for (int ss = 0; ss < ks; ++ss) {
+      if (ss == (int)blockIdx.y) continue;
+      const int* const theirs = slots + (size_t)ss * (PER * NT) + tid;
+#pragma unroll
+      for (int mb = 0; mb < TM; ++mb) {
+#pragma unroll
+        for (int nb = 0; nb < TN; ++nb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            acc[mb][nb][r] += __hip_atomic_load(theirs + ((mb * TN + nb) * 16 + r) * NT, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        rsum_s[mb] += __hip_atomic_load(theirs + (TM * TN * 16 + mb) * NT, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    if (tid == 0) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next call
+  }
+
   // ---- per-column constants of the output pipeline, staged once per workgroup
   __syncthreads();
   int* cj_s = reinterpret_cast<int*>(smem);
@@ -553,7 +605,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
       cj_s[t] = b - p.a_zp_m128 * co;
       sc_s[t] = (col < N) ? p.scales[(size_t)col * p.scale_stride] : 1.0f;
     } else {
-      cj_s[t] = 128 * (co + K * bz);  // acc_u = acc_s + 128 * colsum
+      cj_s[t] = 128 * (co + K0 * bz);  // acc_u = acc_s + 128 * colsum
     }
     bz_s[t] = -bz;  // negated: x = acc + cj + (-theta_B) * rowsum
   }
@@ -647,7 +699,7 @@ __global__ __launch_bounds__(NWM * NWN * KS * 64, min_wg_per_cu(PATH, TM * TN) /
       const int row = m0 + (wave_m * TM + mb) * 32 + l32;
       if (row >= M) continue;
       if (p.rowsum_out != nullptr && tn == 0 && wave_n == 0 && lg == 0)
-        p.rowsum_out[row] = rsum_s[mb] + 128 * K;
+        p.rowsum_out[row] = rsum_s[mb] + 128 * K0;
 #pragma unroll
       for (int nb = 0; nb < TN; ++nb) {
         const int col_l = (wave_n * TN + nb) * 32 + lg * 16;
@@ -669,6 +721,20 @@ hipError_t launch(const qg_gemm_args& a, hipStream_t s) {
   constexpr int SMEM = STAGES * (BM + BN) * BK > 12 * BN ? STAGES * (BM + BN) * BK : 12 * BN;
   const int tiles_m = (a.M + BM - 1) / BM;
   const int tiles_n = (a.N + BN - 1) / BN;
+  if constexpr (PATH == PATH_ASM && TM == 2 && TN == 2 && KS == 1) {
+    if (a.ksplit > 1) {  // K split across workgroups: the slices are the second grid dimension
+      if (a.ws_cnt == nullptr || a.ws_slots == nullptr || a.ksplit > 65535 || a.K % BK != 0 ||
+          a.K / BK - (a.ksplit - 1) * a.ks_per < NSTAGE || a.ks_per < NSTAGE)
+        return hipErrorInvalidValue;
+      constexpr auto fns = qg_gemm_tile_kernel<MODE, PATH, ROWSUM, NWM, NWN, TM, TN, 0, KS, EPI, true>;
+      hipError_t es = qg_allow_smem<fns>(SMEM);
+      if (es != hipSuccess) return es;
+      hipLaunchKernelGGL(fns, dim3((unsigned)(tiles_m * tiles_n), (unsigned)a.ksplit), dim3(NWM * NWN * KS * 64), SMEM, s, a.A, a.Bp,
+                         a.M, a.N, a.K, a.nb16, a.lda, tiles_m, tiles_n, a);
+      return hipGetLastError();
+    }
+  }
+  if (a.ksplit > 1) return hipErrorInvalidValue;
   constexpr auto fn = qg_gemm_tile_kernel<MODE, PATH, ROWSUM, NWM, NWN, TM, TN, false, KS, EPI>;
   hipError_t e = qg_allow_smem<fn>(SMEM);
   if (e != hipSuccess) return e;

@@ -279,7 +279,8 @@ def gemm_splitk_factor(M, Bp, kernel=KERNEL_AUTO, ksplit=0):
 
 
 def gemm_u8s8_requant_splitk(A, a_zp, Bp, bias, scales, c_zp, relu, workspace, kernel=KERNEL_AUTO, ksplit=0, out=None):
-    """As gemm_u8s8_requant with the K split across workgroups chosen by the caller (0 = built-in choice)."""
+    """As gemm_u8s8_requant with the K split across workgroups chosen by the caller (0 = built-in choice): a streaming
+    kernel, or "tile128" (the caller's factor only; slices of at least four 64-deep tiles)."""
     assert A.is_cuda and A.dtype == torch.uint8 and A.dim() == 2 and A.stride(1) == 1 and A.shape[1] == Bp.K
     M = A.shape[0]
     if out is None:

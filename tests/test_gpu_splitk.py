@@ -171,3 +171,59 @@ def test_split_argument_errors(env):
     assert q.lib.qg_gemm_splitk_workspace_bytes(c.M, Bp.handle, q.kernel_id("tile64"), 4) == 0
     # K = 1024 has 16 blocks of 64: a request for 64 slices is served with 16
     assert q.gemm_splitk_factor(c.M, Bp, "skinny16", 64) == 16
+
+
+@pytest.mark.parametrize("M,N,K,ksplit,served", [(128, 128, 512, 2, 2), (300, 200, 1024, 4, 4), (130, 520, 2048, 3, 3), (256, 256, 640, 2, 2),
+                                                 (64, 100, 8192, 8, 8), (200, 300, 768, 64, 3), (100, 64, 576, 2, 2)])
+def test_k_split_across_workgroups_on_the_128_tile(env, M, N, K, ksplit, served):
+    """The 128 x 128 tile with its K split over the second grid dimension (caller's choice only): slices of at least
+    four 64-deep tiles, a last slice that is shorter, ragged M and N, more slices asked for than K has; twice per
+    case (the counters go back to zero), uint8 result, raw accumulators and row sums against the oracle."""
+    q, torch, dev, oracle = env
+    say(f"tile128 K split {M}x{N}x{K} / {ksplit}")
+    c = wl.unsaturated(wl.random_gemm(8500 + M + N + K, M, N, K, per_channel=True, with_bias=True, wide_zp=True))
+    want = oracle_gemm(c, oracle)
+    A, B, bias, scales, C, c_store = dev_case(c, torch, dev)
+    Bp = q.pack_b(B, c.b_zp)
+    assert q.gemm_splitk_factor(M, Bp, "tile128", ksplit) == served
+    ws = q.gemm_workspace(M, Bp, "tile128", ksplit)
+    for rep in range(2):
+        C.fill_(0xEE)
+        q.gemm_u8s8_requant_splitk(A, c.a_zp, Bp, bias, scales, c.c_zp, c.relu, ws, "tile128", ksplit, out=C)
+        acc, rs = q.gemm_u8s8_acc32_splitk(A, Bp, ws, "tile128", ksplit, want_rowsum=True)
+        torch.cuda.synchronize()
+        assert_same(C.cpu().numpy(), want, f"requant (call {rep})")
+        assert_same(acc.cpu().numpy(), oracle.acc32(c.A, c.B), f"acc32 (call {rep})")
+        assert_same(rs.cpu().numpy(), oracle.rowsum(c.A), f"rowsum (call {rep})")
+    assert (c_store.cpu().numpy()[M * N:] == 0xEE).all(), "bytes past C were written"
+
+
+def test_128_tile_split_argument_errors(env):
+    q, torch, dev, oracle = env
+    c = wl.random_gemm(82, 130, 140, 1024)
+    A, B, bias, scales, C, _ = dev_case(c, torch, dev)
+    Bp = q.pack_b(B, c.b_zp)
+    p = q.RequantParams(c.a_zp, None, scales.data_ptr(), scales.numel(), c.c_zp, 0)
+    t128 = q.kernel_id("tile128")
+
+    def call(ws, nbytes, kernel, ksplit):
+        return q.lib.qg_gemm_u8s8_requant_splitk(A.data_ptr(), c.M, A.stride(0), Bp.handle, ctypes.byref(p), C.data_ptr(),
+                                                 C.stride(0), ws, nbytes, None, kernel, ksplit)
+
+    need = q.lib.qg_gemm_splitk_workspace_bytes(c.M, Bp.handle, t128, 4)
+    assert need == (64 + 4 * 4 * 66 * 256) * 4      # 4 tiles: 64 counters, 4 slots of 256 x 66 int32 each
+    ws = torch.zeros(need, dtype=torch.uint8, device=dev)
+    assert call(None, 0, t128, 4) == q.EWORKSPACE
+    assert call(ws.data_ptr(), need - 4, t128, 4) == q.EWORKSPACE
+    assert call(ws.data_ptr() + 4, need, t128, 4) == q.EALIGN
+    assert call(ws.data_ptr(), need, q.kernel_id("tile256"), 2) == q.EUNSUPPORTED
+    assert call(None, 0, t128, 0) == q.OK           # the built-in choice never splits this kernel
+    assert call(ws.data_ptr(), need, t128, 4) == q.OK
+    torch.cuda.synchronize()
+    # K = 1024 has 16 tiles: at most four slices of four
+    assert q.gemm_splitk_factor(c.M, Bp, "tile128", 64) == 4
+    # a K that is not a whole number of 64-deep tiles is not split
+    c2 = wl.random_gemm(83, 130, 140, 1000)
+    Bp2 = q.pack_b(torch.from_numpy(c2.B).to(dev), c2.b_zp)
+    assert q.gemm_splitk_factor(c2.M, Bp2, "tile128", 4) == 1
+    assert q.lib.qg_gemm_splitk_workspace_bytes(c2.M, Bp2.handle, t128, 4) == 0
