@@ -468,8 +468,8 @@ def main():
         from paper_2101_05615_amd import autotune
         nxt = {"kernel_family": [], "fp32_ends": {}}
         # shape-specific kernel family: what the automatic choice picks, and what the best kernel would give
-        for shape in [(1, 4096, 4096), (64, 4096, 4096), (128, 4096, 4096), (256, 1024, 4096), (2048, 2048, 2048),
-                      (4096, 1024, 1024), (16384, 256, 512)]:
+        for shape in [(1, 4096, 4096), (64, 4096, 4096), (64, 8192, 8192), (128, 4096, 4096), (256, 1024, 4096),
+                      (2048, 2048, 2048), (4096, 1024, 1024), (16384, 256, 512)]:
             r = autotune.tune(q, torch, [shape])[0]
             t = r["us"]
             nxt["kernel_family"].append({"M": shape[0], "N": shape[1], "K": shape[2], "auto": r["auto"],
